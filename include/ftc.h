@@ -1,0 +1,200 @@
+/*
+ * ftc.h -- C ABI of libftc: sparse neighbour aggregation for GCN / AGNN on AMD gfx950,
+ * after FTC-GNN (arXiv 2412.12218).
+ *
+ * Conventions shared by every entry point
+ * ---------------------------------------
+ *  - Every array pointer inside the structs and in the argument lists is a DEVICE
+ *    pointer owned by the caller; the structs themselves and all scalars live on the
+ *    host.  The library never allocates or frees device memory, never synchronises and
+ *    never prints: a call validates its arguments on the host and enqueues kernels on
+ *    `stream` (a hipStream_t passed as void*, NULL = the default stream).  Scratch
+ *    memory comes from a caller-provided workspace whose size is returned by the
+ *    matching *_workspace_bytes query (a pure host function).
+ *  - Return value: FTC_OK or a negative ftc_status; ftc_last_error() returns a
+ *    thread-local description of the last failure.
+ *  - The graph is a CSR adjacency with int32 indices (`nodePointer` / `edgeList` in the
+ *    paper, Section V.A).  Column indices within a row may be unsorted and may repeat;
+ *    repeated entries are separate edges whose contributions add.  Index validity
+ *    (monotone row_ptr, 0 <= col < n) is the caller's responsibility and can be checked
+ *    with ftc_validate_csr.
+ *  - Dense matrices are row-major with a leading dimension in ELEMENTS.  The vector
+ *    kernels need the base pointer 16-byte aligned and ld * sizeof(element) a multiple of
+ *    16 with D a multiple of 8 (16-bit types) or 4 (fp32); other shapes take a slower
+ *    generic kernel.  Outputs never alias inputs unless stated.
+ *  - n == 0 or nnz == 0 is legal.  A row without stored entries produces a zero output row
+ *    (SpMM / layers) and no softmax output.
+ */
+#ifndef FTC_H
+#define FTC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    FTC_OK = 0,
+    FTC_EINVAL = -1,       /* null pointer, negative size, inconsistent sizes          */
+    FTC_EUNSUPPORTED = -2, /* dtype / dimension / tile combination not implemented      */
+    FTC_EALIGN = -3,       /* pointer or leading dimension violates a stated alignment  */
+    FTC_EWORKSPACE = -4,   /* workspace missing or smaller than *_workspace_bytes says  */
+    FTC_EHIP = -5          /* the HIP runtime reported an error at launch               */
+} ftc_status;
+
+typedef enum { FTC_F32 = 0, FTC_F16 = 1, FTC_BF16 = 2 } ftc_dtype;
+
+/* Kernel family used by ftc_spmm / ftc_sddmm and the layers built on them. */
+typedef enum {
+    FTC_PATH_AUTO = 0, /* per row window: matrix-core tiles where the condensed window is
+                          dense enough, vector gather elsewhere                          */
+    FTC_PATH_VALU = 1, /* vector gather path for every window                           */
+    FTC_PATH_MFMA = 2  /* matrix-core condensed-tile path for every window (16-bit only) */
+} ftc_path;
+
+/* CSR adjacency: row_ptr[n+1], col_idx[nnz]; row_ptr[0] == 0, row_ptr[n] == nnz. */
+typedef struct {
+    int32_t n;
+    int32_t nnz;
+    const int32_t *row_ptr;
+    const int32_t *col_idx;
+} ftc_csr;
+
+/*
+ * Output of the sparse graph transformation (Section V.A).  Rows are cut into windows
+ * of blk_h consecutive rows (the last one may be short); S_w is the ascending list of
+ * distinct column ids used by window w.
+ *   edge_to_row[e]      global row of edge e                              [nnz]
+ *   edge_to_col[e]      position of col_idx[e] in S_w of the edge's window [nnz]
+ *   block_partition[w]  ceil(|S_w| / blk_w): TC blocks of window w        [n_windows]
+ *   win_col_ptr[w]      start of S_w inside win_cols                      [n_windows+1]
+ *   win_cols            S_0, S_1, ... back to back; capacity nnz entries  [nnz]
+ *   summary[0]          sum of |S_w|;  summary[1] = sum of block_partition
+ *                       (`block_counter`)                                 [2]
+ * All arrays are allocated by the caller before ftc_build_windows fills them.
+ */
+typedef struct {
+    int32_t blk_h;
+    int32_t blk_w;
+    int32_t n_windows; /* ceil(n / blk_h) */
+    int32_t *edge_to_row;
+    int32_t *edge_to_col;
+    int32_t *block_partition;
+    int32_t *win_col_ptr;
+    int32_t *win_cols;
+    int64_t *summary;
+} ftc_windows;
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int32_t ftc_version(void);
+
+/* Description of the last error on this host thread ("" if none). Never NULL. */
+const char *ftc_last_error(void);
+
+/*
+ * Checks on the device that row_ptr is non-decreasing with row_ptr[0] == 0 and
+ * row_ptr[n] == nnz, and that every column index lies in [0, n).  *flag (device int32)
+ * is set to 0 when the graph is valid, otherwise to a bit mask: 1 = row_ptr, 2 = col_idx.
+ */
+int32_t ftc_validate_csr(const ftc_csr *g, int32_t *flag, void *stream);
+
+/*
+ * Sparse graph transformation (Section V.A, `edgeToRow`, `edgeToColumn`,
+ * `blockPartition`, `block_counter`; TC_BLK_H = 16 and TC_BLK_W = 8 in the paper, both
+ * free here with 1 <= blk_h <= 64 and blk_w >= 1).  Fills every array of `out`;
+ * out->blk_h, blk_w and n_windows are inputs and must be consistent with g->n.  The
+ * result is uniquely determined (ascending order, strict de-duplication).
+ */
+size_t ftc_build_windows_workspace_bytes(int32_t n, int32_t nnz, int32_t blk_h, int32_t blk_w);
+int32_t ftc_build_windows(const ftc_csr *g, ftc_windows *out, void *ws, size_t ws_bytes,
+                          void *stream);
+
+/*
+ * Symmetric GCN normalisation for a pattern that already contains the self-loops
+ * (the paper names the GCN model in Section VI; the formula is the standard
+ * A^ = D~^-1/2 (A+I) D~^-1/2).  d~_i = number of stored entries of row i,
+ * dinv[i] = d~_i^-1/2 (0 for an empty row), vals[e] = dinv[row(e)] * dinv[col_idx[e]].
+ * Either output may be NULL.  w may be NULL; when given, its edge_to_row is used to
+ * find the row of an edge.
+ */
+int32_t ftc_gcn_norm(const ftc_csr *g, const ftc_windows *w, float *vals, float *dinv,
+                     void *stream);
+
+/*
+ * Sparse neighbour aggregation (Section V.A; SpMM C = A x B of Section I.A.2):
+ *   out[i, 0:D] = sum over stored entries e of row i of vals[e] * X[col_idx[e], 0:D]
+ * accumulated in fp32.  vals == NULL means all ones.  X has g->n rows of dtype x_dtype;
+ * out has g->n rows of dtype out_dtype.  relu != 0 applies max(0, .) before the store.
+ * w may be NULL (vector path on the CSR only).  `path` is an ftc_path.
+ */
+size_t ftc_spmm_workspace_bytes(int32_t n, int32_t nnz, int32_t D);
+int32_t ftc_spmm(const ftc_csr *g, const ftc_windows *w, const float *vals, const void *X,
+                 int32_t ldx, int32_t x_dtype, int32_t D, void *out, int32_t ldo,
+                 int32_t out_dtype, int32_t relu, int32_t path, void *ws, size_t ws_bytes,
+                 void *stream);
+
+/*
+ * Sparse edge feature computation (Section V.A; SDDMM D = A o (B x C) of Section I.A.2,
+ * A taken as the 0/1 pattern), result laid out like col_idx (`EdgeValList`):
+ *   edge_out[e] = alpha * row_scale[i] * col_scale[j] * sum_k X[i,k] * Y[j,k],
+ *   i = row of e, j = col_idx[e].
+ * X and Y have g->n rows, the same dtype and leading dimension, and may be the same
+ * matrix.  row_scale / col_scale may be NULL (1.0).
+ */
+size_t ftc_sddmm_workspace_bytes(int32_t n, int32_t nnz, int32_t D);
+int32_t ftc_sddmm(const ftc_csr *g, const ftc_windows *w, const void *X, const void *Y,
+                  int32_t ld, int32_t dtype, int32_t D, const float *row_scale,
+                  const float *col_scale, float alpha, float *edge_out, int32_t path,
+                  void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Inverse Euclidean row norms used by the AGNN cosine: rinv[i] = 1 / max(||H[i,:]||, 1e-12).
+ */
+int32_t ftc_row_rnorm(int32_t n, const void *H, int32_t ld, int32_t dtype, int32_t D,
+                      float *rinv, void *stream);
+
+/*
+ * Edge softmax over the stored entries of every row (the attention weights of AGNN,
+ * which the paper names in Section VI):
+ *   p[e] = exp(s[e] - m_i) / sum_{e' in row i} exp(s[e'] - m_i),  m_i = max over row i.
+ * p_out may alias e_in.  Rows without entries write nothing.
+ */
+int32_t ftc_edge_softmax(const ftc_csr *g, const float *e_in, float *p_out, void *stream);
+
+/*
+ * Dense update phase (Section I.A.2): Z = X * W, X n x d_in (dtype), W d_in x d_out
+ * row-major of the same dtype, fp32 accumulation, Z n x d_out of z_dtype.
+ * d_in <= 256 and d_out <= 64.  relu != 0 applies max(0, .).
+ */
+int32_t ftc_update_gemm(int32_t n, const void *X, int32_t ldx, int32_t dtype, int32_t d_in,
+                        const void *W, int32_t d_out, void *Z, int32_t ldz, int32_t z_dtype,
+                        int32_t relu, void *stream);
+
+/*
+ * GCN layer forward: out = act(A^ * (X * W)) with A^ given by (g, vals); update first,
+ * then aggregation (Eq. 1-2 of Section I).  W is d_in x d_out row-major, same dtype as X.
+ * The intermediate X * W is kept in fp32 inside the workspace.
+ */
+size_t ftc_gcn_layer_workspace_bytes(int32_t n, int32_t nnz, int32_t d_in, int32_t d_out);
+int32_t ftc_gcn_layer(const ftc_csr *g, const ftc_windows *w, const float *vals, const void *X,
+                      int32_t ldx, int32_t dtype, int32_t d_in, const void *W, int32_t d_out,
+                      int32_t relu, void *out, int32_t ldo, int32_t out_dtype, int32_t path,
+                      void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * AGNN propagation layer forward: s_ij = beta * cos(h_i, h_j) on the stored entries,
+ * P = edge softmax of s, out = P * H (H not normalised).  edge_p, when not NULL,
+ * receives P (nnz floats).
+ */
+size_t ftc_agnn_layer_workspace_bytes(int32_t n, int32_t nnz, int32_t D);
+int32_t ftc_agnn_layer(const ftc_csr *g, const ftc_windows *w, const void *H, int32_t ld,
+                       int32_t dtype, int32_t D, float beta, void *out, int32_t ldo,
+                       int32_t out_dtype, float *edge_p, int32_t path, void *ws,
+                       size_t ws_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FTC_H */

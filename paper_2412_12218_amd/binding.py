@@ -1,0 +1,240 @@
+"""ctypes binding of libftc.so: argument marshalling only.
+
+Every function here has the name of the C entry point it calls (include/ftc.h).  Tensors
+are torch CUDA tensors used purely as device buffers; outputs and workspaces are
+allocated with torch.empty and handed to the library as raw pointers.  All work is
+enqueued on torch's current stream.  There is no CPU or PyTorch fallback: if the shared
+library is missing, lib() raises.
+"""
+import ctypes as C
+import os
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libftc.so")
+
+FTC_F32, FTC_F16, FTC_BF16 = 0, 1, 2
+FTC_PATH_AUTO, FTC_PATH_VALU, FTC_PATH_MFMA = 0, 1, 2
+FTC_OK, FTC_EINVAL, FTC_EUNSUPPORTED, FTC_EALIGN, FTC_EWORKSPACE, FTC_EHIP = 0, -1, -2, -3, -4, -5
+
+_DTYPES = {torch.float32: FTC_F32, torch.float16: FTC_F16, torch.bfloat16: FTC_BF16}
+
+EXPORTS = ["ftc_version", "ftc_last_error", "ftc_validate_csr", "ftc_build_windows_workspace_bytes",
+           "ftc_build_windows", "ftc_gcn_norm", "ftc_spmm_workspace_bytes", "ftc_spmm",
+           "ftc_sddmm_workspace_bytes", "ftc_sddmm", "ftc_row_rnorm", "ftc_edge_softmax",
+           "ftc_update_gemm", "ftc_gcn_layer_workspace_bytes", "ftc_gcn_layer",
+           "ftc_agnn_layer_workspace_bytes", "ftc_agnn_layer"]
+
+
+class FtcError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"libftc error {code}: {msg}")
+        self.code = code
+
+
+class ftc_csr(C.Structure):
+    _fields_ = [("n", C.c_int32), ("nnz", C.c_int32), ("row_ptr", C.c_void_p), ("col_idx", C.c_void_p)]
+
+
+class ftc_windows(C.Structure):
+    _fields_ = [("blk_h", C.c_int32), ("blk_w", C.c_int32), ("n_windows", C.c_int32),
+                ("edge_to_row", C.c_void_p), ("edge_to_col", C.c_void_p),
+                ("block_partition", C.c_void_p), ("win_col_ptr", C.c_void_p),
+                ("win_cols", C.c_void_p), ("summary", C.c_void_p)]
+
+
+_lib = None
+
+
+def lib():
+    """Load libftc.so (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'`")
+        L = C.CDLL(LIB_PATH)
+        L.ftc_last_error.restype = C.c_char_p
+        for name in EXPORTS:
+            if name.endswith("_workspace_bytes"):
+                getattr(L, name).restype = C.c_size_t
+                getattr(L, name).argtypes = [C.c_int32] * 4 if name in (
+                    "ftc_build_windows_workspace_bytes", "ftc_gcn_layer_workspace_bytes") else [C.c_int32] * 3
+        _lib = L
+    return _lib
+
+
+def _check(code):
+    if code != FTC_OK:
+        raise FtcError(code, lib().ftc_last_error().decode())
+
+
+def _ptr(t):
+    return C.c_void_p(t.data_ptr()) if t is not None else C.c_void_p(0)
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dt(t):
+    return _DTYPES[t.dtype]
+
+
+class Graph:
+    """Device CSR adjacency (int32) plus its C descriptor."""
+
+    def __init__(self, row_ptr, col_idx):
+        assert row_ptr.dtype == torch.int32 and col_idx.dtype == torch.int32
+        assert row_ptr.is_cuda and col_idx.is_cuda and row_ptr.is_contiguous() and col_idx.is_contiguous()
+        self.row_ptr, self.col_idx = row_ptr, col_idx
+        self.n = row_ptr.numel() - 1
+        self.nnz = col_idx.numel()
+        self.c = ftc_csr(self.n, self.nnz, row_ptr.data_ptr(), col_idx.data_ptr() if self.nnz else 0)
+
+    @staticmethod
+    def from_numpy(row_ptr, col_idx, device="cuda"):
+        return Graph(torch.from_numpy(row_ptr).to(device=device, dtype=torch.int32),
+                     torch.from_numpy(col_idx).to(device=device, dtype=torch.int32))
+
+
+class Windows:
+    """Device arrays of the sparse graph transformation plus their C descriptor."""
+
+    def __init__(self, g, blk_h=16, blk_w=8):
+        dev = g.row_ptr.device
+        self.blk_h, self.blk_w = blk_h, blk_w
+        self.n_windows = (g.n + blk_h - 1) // blk_h
+        i32 = dict(dtype=torch.int32, device=dev)
+        self.edge_to_row = torch.empty(g.nnz, **i32)
+        self.edge_to_col = torch.empty(g.nnz, **i32)
+        self.block_partition = torch.empty(self.n_windows, **i32)
+        self.win_col_ptr = torch.empty(self.n_windows + 1, **i32)
+        self.win_cols = torch.empty(g.nnz, **i32)
+        self.summary = torch.empty(2, dtype=torch.int64, device=dev)
+        self.c = ftc_windows(blk_h, blk_w, self.n_windows, self.edge_to_row.data_ptr(),
+                             self.edge_to_col.data_ptr(), self.block_partition.data_ptr(),
+                             self.win_col_ptr.data_ptr(), self.win_cols.data_ptr(),
+                             self.summary.data_ptr())
+
+
+def _workspace(nbytes, device):
+    # torch's caching allocator returns 512-byte aligned blocks
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def _wref(w):
+    return C.byref(w.c) if w is not None else None
+
+
+def ftc_version():
+    return lib().ftc_version()
+
+
+def ftc_validate_csr(g):
+    flag = torch.empty(1, dtype=torch.int32, device=g.row_ptr.device)
+    _check(lib().ftc_validate_csr(C.byref(g.c), _ptr(flag), _stream()))
+    return flag
+
+
+def ftc_build_windows(g, blk_h=16, blk_w=8):
+    w = Windows(g, blk_h, blk_w)
+    nbytes = lib().ftc_build_windows_workspace_bytes(g.n, g.nnz, blk_h, blk_w)
+    ws = _workspace(nbytes, g.row_ptr.device)
+    _check(lib().ftc_build_windows(C.byref(g.c), C.byref(w.c), _ptr(ws), C.c_size_t(ws.numel()), _stream()))
+    return w
+
+
+def ftc_gcn_norm(g, w=None, want_vals=True, want_dinv=True):
+    dev = g.row_ptr.device
+    vals = torch.empty(g.nnz, dtype=torch.float32, device=dev) if want_vals else None
+    dinv = torch.empty(g.n, dtype=torch.float32, device=dev) if want_dinv else None
+    _check(lib().ftc_gcn_norm(C.byref(g.c), _wref(w), _ptr(vals), _ptr(dinv), _stream()))
+    return vals, dinv
+
+
+def ftc_spmm(g, w, vals, X, out=None, out_dtype=torch.float32, relu=False, path=FTC_PATH_AUTO, ws=None):
+    D = X.shape[1]
+    if out is None:
+        out = torch.empty((g.n, D), dtype=out_dtype, device=X.device)
+    if ws is None:
+        ws = _workspace(lib().ftc_spmm_workspace_bytes(g.n, g.nnz, D), X.device)
+    _check(lib().ftc_spmm(C.byref(g.c), _wref(w), _ptr(vals), _ptr(X), C.c_int32(X.stride(0)),
+                          C.c_int32(_dt(X)), C.c_int32(D), _ptr(out), C.c_int32(out.stride(0)),
+                          C.c_int32(_dt(out)), C.c_int32(1 if relu else 0), C.c_int32(path), _ptr(ws),
+                          C.c_size_t(ws.numel()), _stream()))
+    return out
+
+
+def ftc_sddmm(g, w, X, Y, row_scale=None, col_scale=None, alpha=1.0, out=None, path=FTC_PATH_AUTO, ws=None):
+    D = X.shape[1]
+    assert Y.shape[1] == D and X.stride(0) == Y.stride(0) and X.dtype == Y.dtype
+    if out is None:
+        out = torch.empty(g.nnz, dtype=torch.float32, device=X.device)
+    if ws is None:
+        ws = _workspace(lib().ftc_sddmm_workspace_bytes(g.n, g.nnz, D), X.device)
+    _check(lib().ftc_sddmm(C.byref(g.c), _wref(w), _ptr(X), _ptr(Y), C.c_int32(X.stride(0)),
+                           C.c_int32(_dt(X)), C.c_int32(D), _ptr(row_scale), _ptr(col_scale),
+                           C.c_float(alpha), _ptr(out), C.c_int32(path), _ptr(ws), C.c_size_t(ws.numel()),
+                           _stream()))
+    return out
+
+
+def ftc_row_rnorm(H, out=None):
+    if out is None:
+        out = torch.empty(H.shape[0], dtype=torch.float32, device=H.device)
+    _check(lib().ftc_row_rnorm(C.c_int32(H.shape[0]), _ptr(H), C.c_int32(H.stride(0)), C.c_int32(_dt(H)),
+                               C.c_int32(H.shape[1]), _ptr(out), _stream()))
+    return out
+
+
+def ftc_edge_softmax(g, e_in, out=None):
+    if out is None:
+        out = torch.empty_like(e_in)
+    _check(lib().ftc_edge_softmax(C.byref(g.c), _ptr(e_in), _ptr(out), _stream()))
+    return out
+
+
+def ftc_update_gemm(X, W, out=None, out_dtype=torch.float32, relu=False):
+    n, d_in = X.shape
+    d_out = W.shape[1]
+    assert W.shape[0] == d_in and W.is_contiguous() and W.dtype == X.dtype
+    if out is None:
+        out = torch.empty((n, d_out), dtype=out_dtype, device=X.device)
+    _check(lib().ftc_update_gemm(C.c_int32(n), _ptr(X), C.c_int32(X.stride(0)), C.c_int32(_dt(X)),
+                                 C.c_int32(d_in), _ptr(W), C.c_int32(d_out), _ptr(out),
+                                 C.c_int32(out.stride(0)), C.c_int32(_dt(out)), C.c_int32(1 if relu else 0),
+                                 _stream()))
+    return out
+
+
+def ftc_gcn_layer(g, w, vals, X, W, relu=False, out=None, out_dtype=torch.float32, path=FTC_PATH_AUTO,
+                  ws=None):
+    n, d_in = X.shape
+    d_out = W.shape[1]
+    assert W.shape[0] == d_in and W.is_contiguous() and W.dtype == X.dtype
+    if out is None:
+        out = torch.empty((n, d_out), dtype=out_dtype, device=X.device)
+    if ws is None:
+        ws = _workspace(lib().ftc_gcn_layer_workspace_bytes(g.n, g.nnz, d_in, d_out), X.device)
+    _check(lib().ftc_gcn_layer(C.byref(g.c), _wref(w), _ptr(vals), _ptr(X), C.c_int32(X.stride(0)),
+                               C.c_int32(_dt(X)), C.c_int32(d_in), _ptr(W), C.c_int32(d_out),
+                               C.c_int32(1 if relu else 0), _ptr(out), C.c_int32(out.stride(0)),
+                               C.c_int32(_dt(out)), C.c_int32(path), _ptr(ws), C.c_size_t(ws.numel()),
+                               _stream()))
+    return out
+
+
+def ftc_agnn_layer(g, w, H, beta=1.0, out=None, out_dtype=torch.float32, edge_p=None, path=FTC_PATH_AUTO,
+                   ws=None):
+    n, D = H.shape
+    if out is None:
+        out = torch.empty((n, D), dtype=out_dtype, device=H.device)
+    if ws is None:
+        ws = _workspace(lib().ftc_agnn_layer_workspace_bytes(g.n, g.nnz, D), H.device)
+    _check(lib().ftc_agnn_layer(C.byref(g.c), _wref(w), _ptr(H), C.c_int32(H.stride(0)), C.c_int32(_dt(H)),
+                                C.c_int32(D), C.c_float(beta), _ptr(out), C.c_int32(out.stride(0)),
+                                C.c_int32(_dt(out)), _ptr(edge_p), C.c_int32(path), _ptr(ws),
+                                C.c_size_t(ws.numel()), _stream()))
+    return out

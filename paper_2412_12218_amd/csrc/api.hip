@@ -1,0 +1,265 @@
+// C ABI of libftc: host-side argument validation and dispatch.  See include/ftc.h for the
+// contract of every entry point.
+#include <cstdarg>
+#include <cstdio>
+
+#include "ftc_common.hpp"
+
+namespace ftc {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+int32_t launch_status(const char *what)
+{
+    const hipError_t e = hipGetLastError();
+    if (e == hipSuccess) return FTC_OK;
+    set_error("%s: HIP error %d (%s)", what, static_cast<int>(e), hipGetErrorString(e));
+    return FTC_EHIP;
+}
+
+static int32_t fail(int32_t code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+static int32_t check_csr(const ftc_csr *g, const char *who)
+{
+    if (!g) return fail(FTC_EINVAL, "%s: graph is NULL", who);
+    if (g->n < 0 || g->nnz < 0) return fail(FTC_EINVAL, "%s: negative n or nnz", who);
+    if (!g->row_ptr) return fail(FTC_EINVAL, "%s: row_ptr is NULL", who);
+    if (g->nnz > 0 && !g->col_idx) return fail(FTC_EINVAL, "%s: col_idx is NULL", who);
+    if (g->n == 0 && g->nnz != 0) return fail(FTC_EINVAL, "%s: nnz > 0 with n == 0", who);
+    return FTC_OK;
+}
+
+static int32_t check_windows(const ftc_csr *g, const ftc_windows *w, const char *who, bool need_arrays)
+{
+    if (!w) return fail(FTC_EINVAL, "%s: window index is NULL", who);
+    if (w->blk_h < 1 || w->blk_h > 64 || w->blk_w < 1)
+        return fail(FTC_EUNSUPPORTED, "%s: need 1 <= blk_h <= 64 and blk_w >= 1", who);
+    if (w->n_windows != (g->n + w->blk_h - 1) / w->blk_h)
+        return fail(FTC_EINVAL, "%s: n_windows != ceil(n / blk_h)", who);
+    if (need_arrays) {
+        if (!w->win_col_ptr || !w->summary || (w->n_windows > 0 && !w->block_partition))
+            return fail(FTC_EINVAL, "%s: window arrays are NULL", who);
+        if (g->nnz > 0 && (!w->edge_to_row || !w->edge_to_col || !w->win_cols))
+            return fail(FTC_EINVAL, "%s: window edge arrays are NULL", who);
+    }
+    return FTC_OK;
+}
+
+static int32_t check_dense(const void *p, int ld, int dtype, int D, const char *who, const char *name)
+{
+    if (!p) return fail(FTC_EINVAL, "%s: %s is NULL", who, name);
+    if (!valid_dtype(dtype)) return fail(FTC_EUNSUPPORTED, "%s: unknown dtype for %s", who, name);
+    if (D < 1 || ld < D) return fail(FTC_EINVAL, "%s: need D >= 1 and ld >= D for %s", who, name);
+    if (reinterpret_cast<uintptr_t>(p) % elem_size(dtype) != 0)
+        return fail(FTC_EALIGN, "%s: %s is not aligned to its element size", who, name);
+    return FTC_OK;
+}
+
+}  // namespace ftc
+
+using namespace ftc;
+
+#define FTC_TRY(expr)                   \
+    do {                                \
+        const int32_t st__ = (expr);    \
+        if (st__ != FTC_OK) return st__; \
+    } while (0)
+
+extern "C" {
+
+int32_t ftc_version(void) { return 100; }
+
+const char *ftc_last_error(void) { return g_err; }
+
+int32_t ftc_validate_csr(const ftc_csr *g, int32_t *flag, void *stream)
+{
+    FTC_TRY(check_csr(g, "ftc_validate_csr"));
+    if (!flag) return fail(FTC_EINVAL, "ftc_validate_csr: flag is NULL");
+    return launch_validate(*g, flag, static_cast<hipStream_t>(stream));
+}
+
+size_t ftc_build_windows_workspace_bytes(int32_t n, int32_t nnz, int32_t blk_h, int32_t blk_w)
+{
+    if (n < 0 || nnz < 0 || blk_h < 1 || blk_w < 1) return 0;
+    return build_windows_ws(n, nnz, blk_h, blk_w);
+}
+
+int32_t ftc_build_windows(const ftc_csr *g, ftc_windows *out, void *ws, size_t ws_bytes, void *stream)
+{
+    FTC_TRY(check_csr(g, "ftc_build_windows"));
+    FTC_TRY(check_windows(g, out, "ftc_build_windows", true));
+    const size_t need = build_windows_ws(g->n, g->nnz, out->blk_h, out->blk_w);
+    if (!ws || ws_bytes < need)
+        return fail(FTC_EWORKSPACE, "ftc_build_windows: workspace of %zu bytes needed, %zu given", need,
+                    ws ? ws_bytes : static_cast<size_t>(0));
+    if (reinterpret_cast<uintptr_t>(ws) % 256 != 0)
+        return fail(FTC_EALIGN, "ftc_build_windows: workspace must be 256-byte aligned");
+    return launch_build_windows(*g, *out, ws, ws_bytes, static_cast<hipStream_t>(stream));
+}
+
+int32_t ftc_gcn_norm(const ftc_csr *g, const ftc_windows *w, float *vals, float *dinv, void *stream)
+{
+    FTC_TRY(check_csr(g, "ftc_gcn_norm"));
+    if (w) {
+        FTC_TRY(check_windows(g, w, "ftc_gcn_norm", false));
+        if (g->nnz > 0 && !w->edge_to_row) return fail(FTC_EINVAL, "ftc_gcn_norm: edge_to_row is NULL");
+    }
+    return launch_gcn_norm(*g, w, vals, dinv, static_cast<hipStream_t>(stream));
+}
+
+size_t ftc_spmm_workspace_bytes(int32_t n, int32_t nnz, int32_t D)
+{
+    (void)n; (void)nnz; (void)D;
+    return 0;
+}
+
+int32_t ftc_spmm(const ftc_csr *g, const ftc_windows *w, const float *vals, const void *X, int32_t ldx,
+                 int32_t x_dtype, int32_t D, void *out, int32_t ldo, int32_t out_dtype, int32_t relu,
+                 int32_t path, void *ws, size_t ws_bytes, void *stream)
+{
+    (void)ws; (void)ws_bytes;
+    FTC_TRY(check_csr(g, "ftc_spmm"));
+    if (g->n == 0) return FTC_OK;
+    FTC_TRY(check_dense(X, ldx, x_dtype, D, "ftc_spmm", "X"));
+    FTC_TRY(check_dense(out, ldo, out_dtype, D, "ftc_spmm", "out"));
+    if (out == X) return fail(FTC_EINVAL, "ftc_spmm: out aliases X");
+    if (w) FTC_TRY(check_windows(g, w, "ftc_spmm", true));
+    if (path != FTC_PATH_AUTO && path != FTC_PATH_VALU && path != FTC_PATH_MFMA)
+        return fail(FTC_EINVAL, "ftc_spmm: unknown path %d", path);
+    if (path == FTC_PATH_MFMA) return fail(FTC_EUNSUPPORTED, "ftc_spmm: matrix-core path not available");
+    return launch_spmm_rows(*g, vals, X, ldx, x_dtype, D, out, ldo, out_dtype, relu,
+                            static_cast<hipStream_t>(stream));
+}
+
+size_t ftc_sddmm_workspace_bytes(int32_t n, int32_t nnz, int32_t D)
+{
+    (void)n; (void)nnz; (void)D;
+    return 0;
+}
+
+int32_t ftc_sddmm(const ftc_csr *g, const ftc_windows *w, const void *X, const void *Y, int32_t ld,
+                  int32_t dtype, int32_t D, const float *row_scale, const float *col_scale, float alpha,
+                  float *edge_out, int32_t path, void *ws, size_t ws_bytes, void *stream)
+{
+    (void)ws; (void)ws_bytes;
+    FTC_TRY(check_csr(g, "ftc_sddmm"));
+    if (g->n == 0 || g->nnz == 0) return FTC_OK;
+    FTC_TRY(check_dense(X, ld, dtype, D, "ftc_sddmm", "X"));
+    FTC_TRY(check_dense(Y, ld, dtype, D, "ftc_sddmm", "Y"));
+    if (!edge_out) return fail(FTC_EINVAL, "ftc_sddmm: edge_out is NULL");
+    if (w) FTC_TRY(check_windows(g, w, "ftc_sddmm", true));
+    if (path != FTC_PATH_AUTO && path != FTC_PATH_VALU && path != FTC_PATH_MFMA)
+        return fail(FTC_EINVAL, "ftc_sddmm: unknown path %d", path);
+    if (path == FTC_PATH_MFMA) return fail(FTC_EUNSUPPORTED, "ftc_sddmm: matrix-core path not available");
+    return launch_sddmm_rows(*g, X, Y, ld, dtype, D, row_scale, col_scale, alpha, edge_out,
+                             static_cast<hipStream_t>(stream));
+}
+
+int32_t ftc_row_rnorm(int32_t n, const void *H, int32_t ld, int32_t dtype, int32_t D, float *rinv,
+                      void *stream)
+{
+    if (n < 0) return fail(FTC_EINVAL, "ftc_row_rnorm: negative n");
+    if (n == 0) return FTC_OK;
+    FTC_TRY(check_dense(H, ld, dtype, D, "ftc_row_rnorm", "H"));
+    if (!rinv) return fail(FTC_EINVAL, "ftc_row_rnorm: rinv is NULL");
+    return launch_row_rnorm(n, H, ld, dtype, D, rinv, static_cast<hipStream_t>(stream));
+}
+
+int32_t ftc_edge_softmax(const ftc_csr *g, const float *e_in, float *p_out, void *stream)
+{
+    FTC_TRY(check_csr(g, "ftc_edge_softmax"));
+    if (g->n == 0 || g->nnz == 0) return FTC_OK;
+    if (!e_in || !p_out) return fail(FTC_EINVAL, "ftc_edge_softmax: NULL edge array");
+    return launch_softmax(*g, e_in, p_out, static_cast<hipStream_t>(stream));
+}
+
+int32_t ftc_update_gemm(int32_t n, const void *X, int32_t ldx, int32_t dtype, int32_t d_in, const void *W,
+                        int32_t d_out, void *Z, int32_t ldz, int32_t z_dtype, int32_t relu, void *stream)
+{
+    if (n < 0) return fail(FTC_EINVAL, "ftc_update_gemm: negative n");
+    if (n == 0) return FTC_OK;
+    FTC_TRY(check_dense(X, ldx, dtype, d_in, "ftc_update_gemm", "X"));
+    FTC_TRY(check_dense(Z, ldz, z_dtype, d_out, "ftc_update_gemm", "Z"));
+    if (!W) return fail(FTC_EINVAL, "ftc_update_gemm: W is NULL");
+    if (d_in > 256 || d_out > 64) return fail(FTC_EUNSUPPORTED, "ftc_update_gemm: need d_in <= 256, d_out <= 64");
+    if (Z == X) return fail(FTC_EINVAL, "ftc_update_gemm: Z aliases X");
+    return launch_gemm(n, X, ldx, dtype, d_in, W, d_out, Z, ldz, z_dtype, relu, static_cast<hipStream_t>(stream));
+}
+
+size_t ftc_gcn_layer_workspace_bytes(int32_t n, int32_t nnz, int32_t d_in, int32_t d_out)
+{
+    (void)d_in;
+    if (n < 0 || nnz < 0 || d_out < 1) return 0;
+    const int ldz = (d_out + 3) / 4 * 4;
+    return align_up(static_cast<size_t>(n) * ldz * sizeof(float), 256) + ftc_spmm_workspace_bytes(n, nnz, d_out);
+}
+
+int32_t ftc_gcn_layer(const ftc_csr *g, const ftc_windows *w, const float *vals, const void *X, int32_t ldx,
+                      int32_t dtype, int32_t d_in, const void *W, int32_t d_out, int32_t relu, void *out,
+                      int32_t ldo, int32_t out_dtype, int32_t path, void *ws, size_t ws_bytes, void *stream)
+{
+    FTC_TRY(check_csr(g, "ftc_gcn_layer"));
+    if (g->n == 0) return FTC_OK;
+    const size_t need = ftc_gcn_layer_workspace_bytes(g->n, g->nnz, d_in, d_out);
+    if (!ws || ws_bytes < need)
+        return fail(FTC_EWORKSPACE, "ftc_gcn_layer: workspace of %zu bytes needed", need);
+    if (reinterpret_cast<uintptr_t>(ws) % 256 != 0)
+        return fail(FTC_EALIGN, "ftc_gcn_layer: workspace must be 256-byte aligned");
+    const int ldz = (d_out + 3) / 4 * 4;
+    float *Z = static_cast<float *>(ws);
+    const size_t zbytes = align_up(static_cast<size_t>(g->n) * ldz * sizeof(float), 256);
+    FTC_TRY(ftc_update_gemm(g->n, X, ldx, dtype, d_in, W, d_out, Z, ldz, FTC_F32, 0, stream));
+    return ftc_spmm(g, w, vals, Z, ldz, FTC_F32, d_out, out, ldo, out_dtype, relu, path,
+                    static_cast<char *>(ws) + zbytes, ws_bytes - zbytes, stream);
+}
+
+size_t ftc_agnn_layer_workspace_bytes(int32_t n, int32_t nnz, int32_t D)
+{
+    if (n < 0 || nnz < 0 || D < 1) return 0;
+    return align_up(static_cast<size_t>(n) * sizeof(float), 256) +
+           align_up(static_cast<size_t>(nnz) * sizeof(float), 256) +
+           align_up(ftc_sddmm_workspace_bytes(n, nnz, D), 256) + ftc_spmm_workspace_bytes(n, nnz, D);
+}
+
+int32_t ftc_agnn_layer(const ftc_csr *g, const ftc_windows *w, const void *H, int32_t ld, int32_t dtype,
+                       int32_t D, float beta, void *out, int32_t ldo, int32_t out_dtype, float *edge_p,
+                       int32_t path, void *ws, size_t ws_bytes, void *stream)
+{
+    FTC_TRY(check_csr(g, "ftc_agnn_layer"));
+    if (g->n == 0) return FTC_OK;
+    const size_t need = ftc_agnn_layer_workspace_bytes(g->n, g->nnz, D);
+    if (!ws || ws_bytes < need)
+        return fail(FTC_EWORKSPACE, "ftc_agnn_layer: workspace of %zu bytes needed", need);
+    if (reinterpret_cast<uintptr_t>(ws) % 256 != 0)
+        return fail(FTC_EALIGN, "ftc_agnn_layer: workspace must be 256-byte aligned");
+    char *p = static_cast<char *>(ws);
+    float *rinv = reinterpret_cast<float *>(p);
+    p += align_up(static_cast<size_t>(g->n) * sizeof(float), 256);
+    float *scores = edge_p ? edge_p : reinterpret_cast<float *>(p);
+    p += align_up(static_cast<size_t>(g->nnz) * sizeof(float), 256);
+    const size_t sd = align_up(ftc_sddmm_workspace_bytes(g->n, g->nnz, D), 256);
+    void *ws_sddmm = p;
+    p += sd;
+    const size_t rest = ws_bytes - static_cast<size_t>(p - static_cast<char *>(ws));
+    FTC_TRY(ftc_row_rnorm(g->n, H, ld, dtype, D, rinv, stream));
+    FTC_TRY(ftc_sddmm(g, w, H, H, ld, dtype, D, rinv, rinv, beta, scores, path, ws_sddmm, sd, stream));
+    FTC_TRY(ftc_edge_softmax(g, scores, scores, stream));
+    return ftc_spmm(g, w, scores, H, ld, dtype, D, out, ldo, out_dtype, 0, path, p, rest, stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,140 @@
+// Shared host/device helpers of libftc (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "ftc.h"
+
+namespace ftc {
+
+constexpr int WAVE = 64;
+
+// ---- host side -------------------------------------------------------------------------------
+void set_error(const char *fmt, ...);
+int32_t launch_status(const char *what);  // FTC_OK or FTC_EHIP after a kernel launch
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline int elem_size(int dtype) { return dtype == FTC_F32 ? 4 : 2; }
+inline bool valid_dtype(int d) { return d == FTC_F32 || d == FTC_F16 || d == FTC_BF16; }
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Entry points implemented in the individual .hip files (host launchers, no validation).
+int32_t launch_spmm_rows(const ftc_csr &g, const float *vals, const void *X, int ldx, int xdt, int D,
+                         void *out, int ldo, int odt, int relu, hipStream_t s);
+int32_t launch_sddmm_rows(const ftc_csr &g, const void *X, const void *Y, int ld, int dt, int D,
+                          const float *rs, const float *cs, float alpha, float *out, hipStream_t s);
+int32_t launch_softmax(const ftc_csr &g, const float *in, float *out, hipStream_t s);
+int32_t launch_row_rnorm(int n, const void *H, int ld, int dt, int D, float *rinv, hipStream_t s);
+int32_t launch_gemm(int n, const void *X, int ldx, int dt, int d_in, const void *W, int d_out, void *Z,
+                    int ldz, int zdt, int relu, hipStream_t s);
+int32_t launch_gcn_norm(const ftc_csr &g, const ftc_windows *w, float *vals, float *dinv, hipStream_t s);
+int32_t launch_validate(const ftc_csr &g, int32_t *flag, hipStream_t s);
+size_t build_windows_ws(int n, int nnz, int blk_h, int blk_w);
+int32_t launch_build_windows(const ftc_csr &g, ftc_windows &w, void *ws, size_t ws_bytes, hipStream_t s);
+
+// ---- device side -----------------------------------------------------------------------------
+#if defined(__HIPCC__)
+
+// Element types.  A "vector" is one 16-byte load: 4 fp32 or 8 16-bit values.
+struct F32 {
+    static constexpr int VEC = 4;
+    static constexpr int BYTES = 4;
+};
+struct F16 {
+    static constexpr int VEC = 8;
+    static constexpr int BYTES = 2;
+};
+struct BF16 {
+    static constexpr int VEC = 8;
+    static constexpr int BYTES = 2;
+};
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;  // NaN stays NaN
+    u += 0x7fffu + ((u >> 16) & 1u);                               // round to nearest even
+    return u >> 16;
+}
+__device__ __forceinline__ float f16_bits_to_f32(uint32_t b)
+{
+    return static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(b)));
+}
+__device__ __forceinline__ uint32_t f32_to_f16_bits(float f)
+{
+    return __builtin_bit_cast(uint16_t, static_cast<_Float16>(f));
+}
+
+// 16-byte vector load of T::VEC elements starting at element index `idx` (multiple of VEC).
+template <class T>
+__device__ __forceinline__ void load_vec(const void *base, int64_t idx, float (&f)[T::VEC]);
+
+template <>
+__device__ __forceinline__ void load_vec<F32>(const void *base, int64_t idx, float (&f)[4])
+{
+    float4 v = *reinterpret_cast<const float4 *>(static_cast<const float *>(base) + idx);
+    f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
+}
+template <>
+__device__ __forceinline__ void load_vec<F16>(const void *base, int64_t idx, float (&f)[8])
+{
+    uint4 v = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(base) + idx);
+    uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        f[2 * k] = f16_bits_to_f32(w[k] & 0xffffu);
+        f[2 * k + 1] = f16_bits_to_f32(w[k] >> 16);
+    }
+}
+template <>
+__device__ __forceinline__ void load_vec<BF16>(const void *base, int64_t idx, float (&f)[8])
+{
+    uint4 v = *reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(base) + idx);
+    uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        f[2 * k] = __uint_as_float(w[k] << 16);
+        f[2 * k + 1] = __uint_as_float(w[k] & 0xffff0000u);
+    }
+}
+
+// Scalar element load / store with a run-time dtype (generic paths and epilogues).
+__device__ __forceinline__ float load_elem(const void *base, int64_t idx, int dtype)
+{
+    if (dtype == FTC_F32) return static_cast<const float *>(base)[idx];
+    uint32_t b = static_cast<const uint16_t *>(base)[idx];
+    return dtype == FTC_F16 ? f16_bits_to_f32(b) : bf16_bits_to_f32(b);
+}
+__device__ __forceinline__ void store_elem(void *base, int64_t idx, int dtype, float v)
+{
+    if (dtype == FTC_F32) static_cast<float *>(base)[idx] = v;
+    else if (dtype == FTC_F16) static_cast<uint16_t *>(base)[idx] = static_cast<uint16_t>(f32_to_f16_bits(v));
+    else static_cast<uint16_t *>(base)[idx] = static_cast<uint16_t>(f32_to_bf16_bits(v));
+}
+
+// Store NV consecutive floats (NV = 4 or 8) at element index idx (multiple of NV; rows 16-byte
+// aligned by the caller's checks) in the run-time output dtype.
+template <int NV>
+__device__ __forceinline__ void store_vec(void *base, int64_t idx, int dtype, const float (&f)[NV])
+{
+    if (dtype == FTC_F32) {
+        float4 *p = reinterpret_cast<float4 *>(static_cast<float *>(base) + idx);
+#pragma unroll
+        for (int k = 0; k < NV / 4; ++k) p[k] = make_float4(f[4 * k], f[4 * k + 1], f[4 * k + 2], f[4 * k + 3]);
+    } else {
+        uint32_t w[NV / 2];
+#pragma unroll
+        for (int k = 0; k < NV / 2; ++k) {
+            uint32_t lo = dtype == FTC_F16 ? f32_to_f16_bits(f[2 * k]) : f32_to_bf16_bits(f[2 * k]);
+            uint32_t hi = dtype == FTC_F16 ? f32_to_f16_bits(f[2 * k + 1]) : f32_to_bf16_bits(f[2 * k + 1]);
+            w[k] = lo | (hi << 16);
+        }
+        uint16_t *q = static_cast<uint16_t *>(base) + idx;
+        if constexpr (NV == 8) *reinterpret_cast<uint4 *>(q) = make_uint4(w[0], w[1], w[2], w[3]);
+        else *reinterpret_cast<uint2 *>(q) = make_uint2(w[0], w[1]);
+    }
+}
+
+#endif  // __HIPCC__
+}  // namespace ftc

@@ -1,0 +1,104 @@
+"""Host-only checks of the C ABI: the library loads, exports every declared symbol, and
+rejects bad arguments on the host before anything is launched.  CPU only."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2412_12218_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "ftc.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ftc_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = B.lib()
+    names = declared_symbols()
+    assert len(names) >= 15
+    for name in names:
+        assert hasattr(L, name), name
+    assert sorted(B.EXPORTS) == names
+    assert L.ftc_version() >= 100
+
+
+def test_binding_has_same_names():
+    for name in declared_symbols():
+        if name in ("ftc_last_error",) or name.endswith("_workspace_bytes"):
+            continue
+        assert callable(getattr(B, name)), name
+
+
+def _null_call(fn, nargs):
+    return fn(*([None] * nargs))
+
+
+def test_null_graph_is_rejected_on_host():
+    L = B.lib()
+    z = C.c_size_t(0)
+    i = C.c_int32(0)
+    assert L.ftc_spmm(None, None, None, None, i, i, i, None, i, i, i, i, None, z, None) == B.FTC_EINVAL
+    assert b"graph is NULL" in L.ftc_last_error()
+    assert L.ftc_build_windows(None, None, None, z, None) == B.FTC_EINVAL
+    assert L.ftc_edge_softmax(None, None, None, None) == B.FTC_EINVAL
+    assert L.ftc_gcn_norm(None, None, None, None, None) == B.FTC_EINVAL
+
+
+def test_argument_validation_without_launch():
+    L = B.lib()
+    fake = C.c_void_p(0x1000)        # never dereferenced: validation fails first
+    g = B.ftc_csr(4, 10, 0x1000, 0x2000)
+    z = C.c_size_t(0)
+    I = C.c_int32
+    # negative sizes
+    bad = B.ftc_csr(-1, 0, 0x1000, 0)
+    assert L.ftc_spmm(C.byref(bad), None, None, fake, I(8), I(1), I(8), fake, I(8), I(0), I(0), I(0),
+                      None, z, None) == B.FTC_EINVAL
+    # unknown dtype
+    assert L.ftc_spmm(C.byref(g), None, None, fake, I(8), I(7), I(8), C.c_void_p(0x3000), I(8), I(0), I(0),
+                      I(0), None, z, None) == B.FTC_EUNSUPPORTED
+    # ld < D
+    assert L.ftc_spmm(C.byref(g), None, None, fake, I(4), I(1), I(8), C.c_void_p(0x3000), I(8), I(0), I(0),
+                      I(0), None, z, None) == B.FTC_EINVAL
+    # out aliases X
+    assert L.ftc_spmm(C.byref(g), None, None, fake, I(8), I(1), I(8), fake, I(8), I(1), I(0), I(0),
+                      None, z, None) == B.FTC_EINVAL
+    # unknown path
+    assert L.ftc_spmm(C.byref(g), None, None, fake, I(8), I(1), I(8), C.c_void_p(0x3000), I(8), I(0), I(0),
+                      I(9), None, z, None) == B.FTC_EINVAL
+    # window descriptor inconsistent with n
+    w = B.ftc_windows(16, 8, 5, 0x10, 0x20, 0x30, 0x40, 0x50, 0x60)
+    assert L.ftc_build_windows(C.byref(g), C.byref(w), fake, C.c_size_t(1 << 30), None) == B.FTC_EINVAL
+    w = B.ftc_windows(128, 8, 1, 0x10, 0x20, 0x30, 0x40, 0x50, 0x60)
+    assert L.ftc_build_windows(C.byref(g), C.byref(w), fake, C.c_size_t(1 << 30), None) == B.FTC_EUNSUPPORTED
+    # workspace too small / missing
+    w = B.ftc_windows(16, 8, 1, 0x10, 0x20, 0x30, 0x40, 0x50, 0x60)
+    assert L.ftc_build_windows(C.byref(g), C.byref(w), fake, C.c_size_t(8), None) == B.FTC_EWORKSPACE
+    assert L.ftc_gcn_layer(C.byref(g), None, None, fake, I(8), I(1), I(8), fake, I(8), I(0), fake, I(8), I(0),
+                           I(0), None, z, None) == B.FTC_EWORKSPACE
+    assert b"workspace" in L.ftc_last_error()
+    # gemm shape limits
+    assert L.ftc_update_gemm(I(4), fake, I(512), I(1), I(512), fake, I(8), C.c_void_p(0x3000), I(8), I(0), I(0),
+                             None) == B.FTC_EUNSUPPORTED
+
+
+def test_workspace_queries_are_pure_and_monotone():
+    L = B.lib()
+    a = L.ftc_build_windows_workspace_bytes(1000, 5000, 16, 8)
+    b = L.ftc_build_windows_workspace_bytes(2000, 10000, 16, 8)
+    assert 0 < a < b
+    assert L.ftc_build_windows_workspace_bytes(-1, 0, 16, 8) == 0
+    assert L.ftc_gcn_layer_workspace_bytes(1000, 5000, 128, 32) >= 1000 * 32 * 4
+    assert L.ftc_agnn_layer_workspace_bytes(1000, 5000, 32) >= 5000 * 4 + 1000 * 4
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", "/nonexistent/libftc.so")
+    with pytest.raises(FileNotFoundError):
+        B.lib()

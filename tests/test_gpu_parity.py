@@ -1,0 +1,312 @@
+"""GPU parity: every entry point of libftc, called through the C ABI, against the fp64 CPU
+oracle on the same seeded inputs.  Integer outputs bit-exact; float outputs within 2e-3
+(16-bit inputs) / 1e-5 (fp32 inputs) of the oracle, normalised by the sum of absolute terms."""
+import numpy as np
+import pytest
+import torch
+
+import synth
+from parity import TOL, check_windows, dev_graph, norm_err, quantise, rel_err
+from paper_2412_12218_amd import binding as B
+
+pytestmark = pytest.mark.gpu
+
+F32, F16, BF16 = torch.float32, torch.float16, torch.bfloat16
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+# ------------------------------------------------------------------ graphs used by several tests
+def hub_graph():
+    """n=700 (not a multiple of 16): one hub row with ~5000 entries incl. duplicates (a window too
+    large for LDS), empty rows, unsorted columns."""
+    rng = np.random.default_rng(42)
+    n = 700
+    rows = [rng.integers(0, n, size=rng.integers(0, 12)) for _ in range(n)]
+    rows[37] = rng.integers(0, n, size=5000)         # hub with many duplicates
+    rows[38] = np.array([], dtype=np.int64)
+    rows[699] = rng.integers(0, n, size=300)
+    for r in range(100, 140):
+        rows[r] = np.array([], dtype=np.int64)       # two fully empty windows
+    row_ptr = np.zeros(n + 1, dtype=np.int32)
+    row_ptr[1:] = np.cumsum([len(r) for r in rows])
+    col = np.concatenate(rows).astype(np.int32)
+    return synth.Graph(n, row_ptr, col, "hub")
+
+
+@pytest.fixture(scope="module")
+def graphs():
+    gs = {
+        "cfg1": synth.config_graph(1),
+        "cfg2s": synth.config_graph(2, 0.2),
+        "cfg3s": synth.config_graph(3, 0.1),
+        "cfg4s": synth.config_graph(4, 0.03),
+        "cfg5s": synth.config_graph(5, 1 / 32),
+        "hub": hub_graph(),
+    }
+    return gs
+
+
+GRAPH_NAMES = ["cfg1", "cfg2s", "cfg3s", "cfg4s", "cfg5s", "hub"]
+
+
+# ------------------------------------------------------------------ validation kernel
+def test_validate_csr(graphs):
+    g = graphs["cfg1"]
+    dg = dev_graph(g)
+    assert int(B.ftc_validate_csr(dg).item()) == 0
+    bad_col = g.col_idx.copy(); bad_col[5] = g.n
+    assert int(B.ftc_validate_csr(B.Graph.from_numpy(g.row_ptr, bad_col)).item()) == 2
+    bad_rp = g.row_ptr.copy(); bad_rp[3], bad_rp[4] = bad_rp[4] + 1, bad_rp[3]
+    assert int(B.ftc_validate_csr(B.Graph.from_numpy(bad_rp, g.col_idx)).item()) & 1
+
+
+# ------------------------------------------------------------------ window build (bit-exact)
+@pytest.mark.parametrize("name", GRAPH_NAMES)
+@pytest.mark.parametrize("blk", [(16, 8), (16, 16), (8, 4), (64, 8), (5, 3)])
+def test_build_windows(oracle, graphs, name, blk):
+    g = graphs[name]
+    if blk != (16, 8) and name in ("cfg2s", "cfg3s", "cfg4s"):
+        pytest.skip("other tile shapes are covered on the remaining graphs")
+    say(f"build_windows {name} n={g.n} nnz={g.nnz} blk={blk}")
+    ref = oracle.build_windows(g.row_ptr, g.col_idx, *blk)
+    dg = dev_graph(g)
+    win = B.ftc_build_windows(dg, *blk)
+    torch.cuda.synchronize()
+    check_windows(win, ref)
+    win2 = B.ftc_build_windows(dg, *blk)     # same answer again (no run-to-run variation)
+    check_windows(win2, ref)
+
+
+def test_build_windows_degenerate(oracle):
+    # no edges at all, and a single node
+    for n in (1, 33):
+        g = synth.Graph(n, np.zeros(n + 1, dtype=np.int32), np.zeros(0, dtype=np.int32))
+        ref = oracle.build_windows(g.row_ptr, g.col_idx)
+        win = B.ftc_build_windows(dev_graph(g))
+        check_windows(win, ref)
+    g = synth.Graph(1, np.array([0, 1], dtype=np.int32), np.array([0], dtype=np.int32))
+    check_windows(B.ftc_build_windows(dev_graph(g)), oracle.build_windows(g.row_ptr, g.col_idx))
+
+
+# ------------------------------------------------------------------ GCN normalisation
+@pytest.mark.parametrize("name", ["cfg1", "cfg5s", "hub"])
+@pytest.mark.parametrize("with_windows", [False, True])
+def test_gcn_norm(oracle, graphs, name, with_windows):
+    g = graphs[name]
+    say(f"gcn_norm {name} windows={with_windows}")
+    vals64, dinv64 = oracle.gcn_norm(g.row_ptr, g.col_idx)
+    dg = dev_graph(g)
+    win = B.ftc_build_windows(dg) if with_windows else None
+    vals, dinv = B.ftc_gcn_norm(dg, win)
+    if name == "hub":   # empty rows: dinv is 0 there and their columns give 0 values; compare the rest
+        deg = np.diff(g.row_ptr)
+        ok_e = deg[g.col_idx] > 0
+        assert rel_err(vals[torch.from_numpy(ok_e).cuda()], vals64[ok_e]) < 1e-6
+        assert rel_err(dinv[torch.from_numpy(deg > 0).cuda()], dinv64[deg > 0]) < 1e-6
+        assert torch.all(dinv[torch.from_numpy(deg == 0).cuda()] == 0)
+    else:
+        assert rel_err(vals, vals64) < 1e-6
+        assert rel_err(dinv, dinv64) < 1e-6
+
+
+# ------------------------------------------------------------------ SpMM
+def run_spmm(oracle, g, dtype, D, *, use_vals=True, with_windows=True, relu=False, out_dtype=F32,
+             pad=0, seed=0, path=B.FTC_PATH_AUTO):
+    rng = np.random.default_rng(seed)
+    X32 = rng.uniform(-1, 1, size=(g.n, D + pad)).astype(np.float32)
+    Xd, X64 = quantise(X32, dtype)
+    if pad:
+        Xd, X64 = Xd[:, :D], X64[:, :D]
+    vals32 = rng.uniform(0.1, 1.0, size=g.nnz).astype(np.float32) * rng.choice([-1.0, 1.0], g.nnz).astype(np.float32)
+    ref, ab = oracle.spmm(g.row_ptr, g.col_idx, vals32.astype(np.float64) if use_vals else None, X64)
+    if relu:
+        ref = np.maximum(ref, 0)
+    dg = dev_graph(g)
+    win = B.ftc_build_windows(dg) if with_windows else None
+    vd = torch.from_numpy(vals32).cuda() if use_vals else None
+    out = torch.full((g.n, D + pad), 777.0, dtype=out_dtype, device="cuda")[:, :D]
+    B.ftc_spmm(dg, win, vd, Xd, out=out, relu=relu, path=path)
+    out2 = torch.empty((g.n, D), dtype=out_dtype, device="cuda")
+    B.ftc_spmm(dg, win, vd, Xd, out=out2, relu=relu, path=path)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2), "two runs differ"
+    return norm_err(out, ref, ab, out_dtype)
+
+
+@pytest.mark.parametrize("name", GRAPH_NAMES)
+@pytest.mark.parametrize("dtype,D", [(F32, 16), (F16, 32), (BF16, 64), (F16, 128), (F16, 16), (F16, 8),
+                                     (F32, 4), (F32, 64), (BF16, 8)])
+@pytest.mark.parametrize("with_windows", [True, False])
+def test_spmm(oracle, graphs, name, dtype, D, with_windows):
+    g = graphs[name]
+    say(f"spmm {name} {dtype} D={D} windows={with_windows}")
+    err = run_spmm(oracle, g, dtype, D, with_windows=with_windows)
+    say(f"  err {err:.3e}")
+    assert err < TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype,D,pad", [(F16, 24, 0), (F16, 40, 8), (F32, 12, 4), (F16, 5, 0), (F32, 7, 2),
+                                         (BF16, 20, 3), (F16, 64, 64)])
+def test_spmm_odd_shapes(oracle, graphs, dtype, D, pad):
+    say(f"spmm odd {dtype} D={D} pad={pad}")
+    assert run_spmm(oracle, graphs["cfg1"], dtype, D, pad=pad) < TOL[dtype]
+    assert run_spmm(oracle, graphs["hub"], dtype, D, pad=pad) < TOL[dtype]
+
+
+@pytest.mark.parametrize("out_dtype", [F16, BF16])
+def test_spmm_epilogues(oracle, graphs, out_dtype):
+    say(f"spmm epilogue {out_dtype}")
+    g = graphs["cfg2s"]
+    assert run_spmm(oracle, g, F16, 32, relu=True, out_dtype=out_dtype) < 2e-3
+    assert run_spmm(oracle, g, F16, 32, use_vals=False) < 2e-3
+    assert run_spmm(oracle, g, F32, 16, relu=True) < 1e-5
+
+
+# ------------------------------------------------------------------ SDDMM
+def run_sddmm(oracle, g, dtype, D, *, scales=True, with_windows=True, same=False, seed=1, pad=0,
+              path=B.FTC_PATH_AUTO):
+    rng = np.random.default_rng(seed)
+    Xd, X64 = quantise(rng.standard_normal((g.n, D + pad)).astype(np.float32), dtype)
+    if same:
+        Yd, Y64 = Xd, X64
+    else:
+        Yd, Y64 = quantise(rng.standard_normal((g.n, D + pad)).astype(np.float32), dtype)
+    if pad:
+        Xd, X64, Yd, Y64 = Xd[:, :D], X64[:, :D], Yd[:, :D], Y64[:, :D]
+    rs = rng.uniform(0.5, 2.0, g.n).astype(np.float32) if scales else None
+    cs = rng.uniform(0.5, 2.0, g.n).astype(np.float32) if scales else None
+    alpha = 0.75
+    ref, ab = oracle.sddmm(g.row_ptr, g.col_idx, X64, Y64, None if rs is None else rs.astype(np.float64),
+                           None if cs is None else cs.astype(np.float64), alpha)
+    dg = dev_graph(g)
+    win = B.ftc_build_windows(dg) if with_windows else None
+    rsd = torch.from_numpy(rs).cuda() if scales else None
+    csd = torch.from_numpy(cs).cuda() if scales else None
+    out = B.ftc_sddmm(dg, win, Xd, Yd, rsd, csd, alpha, path=path)
+    out2 = B.ftc_sddmm(dg, win, Xd, Yd, rsd, csd, alpha, path=path)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2)
+    return norm_err(out, ref, ab)
+
+
+@pytest.mark.parametrize("name", GRAPH_NAMES)
+@pytest.mark.parametrize("dtype,D", [(F16, 32), (BF16, 64), (F32, 16), (F16, 128), (F16, 8), (F32, 32)])
+@pytest.mark.parametrize("with_windows", [True, False])
+def test_sddmm(oracle, graphs, name, dtype, D, with_windows):
+    g = graphs[name]
+    say(f"sddmm {name} {dtype} D={D} windows={with_windows}")
+    err = run_sddmm(oracle, g, dtype, D, with_windows=with_windows)
+    say(f"  err {err:.3e}")
+    assert err < TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype,D,pad", [(F16, 24, 0), (F16, 5, 0), (F32, 7, 1), (BF16, 40, 8), (F16, 32, 32)])
+def test_sddmm_odd_shapes(oracle, graphs, dtype, D, pad):
+    say(f"sddmm odd {dtype} D={D} pad={pad}")
+    assert run_sddmm(oracle, graphs["cfg1"], dtype, D, pad=pad) < TOL[dtype]
+    assert run_sddmm(oracle, graphs["hub"], dtype, D, pad=pad, scales=False, same=True) < TOL[dtype]
+
+
+# ------------------------------------------------------------------ row norms and edge softmax
+@pytest.mark.parametrize("dtype,D", [(F16, 32), (BF16, 64), (F32, 16), (F16, 5)])
+def test_row_rnorm(oracle, dtype, D):
+    rng = np.random.default_rng(3)
+    H32 = rng.standard_normal((1000, D)).astype(np.float32)
+    H32[17] = 0
+    Hd, H64 = quantise(H32, dtype)
+    ref = oracle.row_rnorm(H64)
+    got = B.ftc_row_rnorm(Hd)
+    assert rel_err(got, ref) < 1e-5 * (1 if dtype == F32 else 10)
+
+
+@pytest.mark.parametrize("name", GRAPH_NAMES)
+def test_edge_softmax(oracle, graphs, name):
+    g = graphs[name]
+    say(f"edge_softmax {name}")
+    rng = np.random.default_rng(5)
+    s32 = (rng.standard_normal(g.nnz) * 2).astype(np.float32)
+    ref = oracle.edge_softmax(g.row_ptr, s32.astype(np.float64))
+    dg = dev_graph(g)
+    sd = torch.from_numpy(s32).cuda()
+    p = B.ftc_edge_softmax(dg, sd)
+    assert rel_err(p, ref) < 1e-5
+    B.ftc_edge_softmax(dg, sd, out=sd)           # in place
+    assert torch.equal(p, sd)
+    rows = np.repeat(np.arange(g.n), np.diff(g.row_ptr))
+    sums = np.bincount(rows, weights=p.cpu().double().numpy(), minlength=g.n)
+    assert np.allclose(sums[np.diff(g.row_ptr) > 0], 1.0, atol=1e-5)
+
+
+def test_edge_softmax_long_rows(oracle):
+    """Rows of 1, 16, 17, 2048, 2049 and 70000 entries: every length class of the kernel."""
+    lens = [1, 16, 17, 0, 2048, 2049, 70000, 3, 100]
+    row_ptr = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    nnz = int(row_ptr[-1])
+    g = synth.Graph(len(lens), row_ptr, np.zeros(nnz, dtype=np.int32))
+    rng = np.random.default_rng(6)
+    s32 = (rng.standard_normal(nnz) * 3 + 50).astype(np.float32)
+    ref = oracle.edge_softmax(g.row_ptr, s32.astype(np.float64))
+    p = B.ftc_edge_softmax(dev_graph(g), torch.from_numpy(s32).cuda())
+    assert rel_err(p, ref) < 1e-5
+
+
+# ------------------------------------------------------------------ update GEMM and layers
+@pytest.mark.parametrize("dtype,d_in,d_out", [(F16, 128, 32), (F16, 128, 16), (F16, 16, 8), (BF16, 64, 64),
+                                              (F32, 16, 8), (F16, 32, 8), (F16, 20, 5), (F32, 256, 64)])
+@pytest.mark.parametrize("relu", [False, True])
+def test_update_gemm(oracle, dtype, d_in, d_out, relu):
+    say(f"gemm {dtype} {d_in}x{d_out} relu={relu}")
+    n = 3000 + 37
+    Xd, X64 = quantise(synth.uniform_features(n, d_in, seed=7), dtype)
+    Wd, W64 = quantise(synth.glorot_uniform(d_in, d_out, seed=8), dtype)
+    ref, ab = oracle.gemm(X64, W64)
+    if relu:
+        ref = np.maximum(ref, 0)
+    Z = B.ftc_update_gemm(Xd, Wd, relu=relu)
+    assert norm_err(Z, ref, ab) < TOL[dtype]
+    Zh = B.ftc_update_gemm(Xd, Wd, relu=relu, out_dtype=F16)
+    assert norm_err(Zh, ref, ab, F16) < TOL[dtype]
+
+
+@pytest.mark.parametrize("name,dtype,d_in,d_out", [("cfg1", F32, 16, 16), ("cfg2s", F16, 128, 32),
+                                                   ("cfg5s", F16, 128, 16), ("cfg5s", F16, 16, 8),
+                                                   ("hub", BF16, 64, 24)])
+@pytest.mark.parametrize("relu", [False, True])
+def test_gcn_layer(oracle, graphs, name, dtype, d_in, d_out, relu):
+    g = graphs[name]
+    say(f"gcn_layer {name} {dtype} {d_in}->{d_out} relu={relu}")
+    vals64, _ = oracle.gcn_norm(g.row_ptr, g.col_idx)
+    vals32 = np.nan_to_num(vals64, posinf=0.0).astype(np.float32)   # hub graph has empty rows
+    Xd, X64 = quantise(synth.uniform_features(g.n, d_in, seed=9), dtype)
+    Wd, W64 = quantise(synth.glorot_uniform(d_in, d_out, seed=10), dtype)
+    ref, ab = oracle.gcn_layer(g.row_ptr, g.col_idx, vals32.astype(np.float64), X64, W64, relu=relu)
+    dg = dev_graph(g)
+    win = B.ftc_build_windows(dg)
+    out = B.ftc_gcn_layer(dg, win, torch.from_numpy(vals32).cuda(), Xd, Wd, relu=relu)
+    err = norm_err(out, ref, ab)
+    say(f"  err {err:.3e}")
+    assert err < TOL[dtype]
+
+
+@pytest.mark.parametrize("name,dtype,D", [("cfg1", F32, 16), ("cfg3s", F16, 32), ("cfg5s", F16, 32),
+                                          ("cfg4s", BF16, 64)])
+@pytest.mark.parametrize("beta", [1.0, 2.5])
+def test_agnn_layer(oracle, graphs, name, dtype, D, beta):
+    g = graphs[name]
+    say(f"agnn_layer {name} {dtype} D={D} beta={beta}")
+    Hd, H64 = quantise(synth.normal_features(g.n, D, seed=11), dtype)
+    ref, ab, pref = oracle.agnn_layer(g.row_ptr, g.col_idx, H64, beta)
+    dg = dev_graph(g)
+    win = B.ftc_build_windows(dg)
+    p = torch.empty(g.nnz, dtype=F32, device="cuda")
+    out = B.ftc_agnn_layer(dg, win, Hd, beta=beta, edge_p=p)
+    err = norm_err(out, ref, ab)
+    perr = rel_err(p, pref)
+    say(f"  err {err:.3e} p err {perr:.3e}")
+    assert err < TOL[dtype]
+    assert perr < (1e-4 if dtype == F32 else 2e-3)
+    out2 = B.ftc_agnn_layer(dg, win, Hd, beta=beta)      # without the optional P output
+    assert torch.equal(out, out2)
