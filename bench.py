@@ -1,0 +1,214 @@
+#!/usr/bin/env python3
+"""Benchmark of the FTC-GNN hot path on one MI355X.
+
+One step = one pass of the whole hot path on the R-MAT configuration (N = 2^20, ~32.5 M stored
+entries, fp16 features N x 128): sparse graph transformation (window build), GCN normalisation,
+2-layer GCN forward (128 -> 16 -> 8) and 4-layer AGNN forward (128 -> 32, four propagation
+layers, -> 8).  All inputs are resident in HBM before the timed region.
+
+Prints one JSON line.  `value` is the hot path's algorithmic GB/s: the bytes the method has to
+move per step (window-deduplicated gathers, every index / value / output once; formulas in
+alg_bytes below) divided by the measured step time.  `roofline` is for the dominant kernel, timed
+with events on the launch stream inside the timed region.  `cpu_baseline` is the fp64 oracle
+running the same pass on a smaller R-MAT graph of the same recipe on the host cores.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def alg_bytes(n, nnz, sum_uniq, n_win):
+    """Algorithmic bytes of every call of one step, keyed by call name."""
+    e = 2  # fp16 activations
+    rp = 4 * (n + 1)
+    b = {}
+    b["build_windows"] = nnz * 4 + rp + nnz * 8 + sum_uniq * 4 + n_win * 8
+    b["gcn_norm"] = rp + nnz * 4 + nnz * 4 + n * 4
+
+    def gemm(di, do, o):
+        return n * di * e + di * do * e + n * do * o
+
+    def spmm(d, e_in, o):
+        return sum_uniq * d * e_in + nnz * 8 + n * d * o + rp
+
+    def sddmm(d):
+        return sum_uniq * d * e + n * d * e + nnz * 8 + rp
+
+    # GCN layer = update GEMM (fp32 Z) + aggregation over Z
+    b["gcn_l1_gemm"] = gemm(128, 16, 4)
+    b["gcn_l1_spmm"] = spmm(16, 4, 2)
+    b["gcn_l2_gemm"] = gemm(16, 8, 4)
+    b["gcn_l2_spmm"] = spmm(8, 4, 4)
+    b["agnn_in_gemm"] = gemm(128, 32, 2)
+    for l in range(4):
+        b[f"agnn_l{l}_rnorm"] = n * 32 * e + n * 4
+        b[f"agnn_l{l}_sddmm"] = sddmm(32)
+        b[f"agnn_l{l}_softmax"] = nnz * 8 + rp
+        b[f"agnn_l{l}_spmm"] = spmm(32, e, 2)
+    b["agnn_out_gemm"] = gemm(32, 8, 4)
+    return b
+
+
+def cpu_baseline(scale, seed, g=None):
+    """The oracle's whole hot path on an R-MAT graph of 2^scale nodes; returns the dict for the JSON."""
+    import numpy as np
+    import synth
+    from oracle import ftc_oracle as orc
+    if g is None:
+        g = synth.rmat(scale, 16, seed)
+    rng_x = synth.normal_features(g.n, 128, seed + 10).astype(np.float16).astype(np.float64)
+    W1 = synth.glorot_uniform(128, 16, seed + 11).astype(np.float64)
+    W2 = synth.glorot_uniform(16, 8, seed + 12).astype(np.float64)
+    Win = synth.glorot_uniform(128, 32, seed + 13).astype(np.float64)
+    Wout = synth.glorot_uniform(32, 8, seed + 14).astype(np.float64)
+    threads = orc.set_threads(0)
+    t0 = time.perf_counter()
+    win = orc.build_windows(g.row_ptr, g.col_idx)
+    vals, _ = orc.gcn_norm(g.row_ptr, g.col_idx)
+    h, _ = orc.gcn_layer(g.row_ptr, g.col_idx, vals, rng_x, W1, relu=True)
+    orc.gcn_layer(g.row_ptr, g.col_idx, vals, h, W2)
+    a, _ = orc.gemm(rng_x, Win)
+    a = np.maximum(a, 0)
+    for _ in range(4):
+        a, _, _ = orc.agnn_layer(g.row_ptr, g.col_idx, a, 1.0)
+    orc.gemm(a, Wout)
+    dt = time.perf_counter() - t0
+    orc.set_threads(1)
+    total = sum(alg_bytes(g.n, g.nnz, int(win["summary"][0]), win["n_windows"]).values())
+    return {"value": total / dt / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
+            "sample": f"whole hot path on R-MAT scale {scale} ({g.n} nodes, {g.nnz} stored entries), "
+                      f"same recipe as the workload, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--scale", type=int, default=20, help="R-MAT scale (20 = the benchmark workload)")
+    ap.add_argument("--cpu-scale", type=int, default=20, help="R-MAT scale of the oracle's sample; 0 = skip")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives or sharding are part of it); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import synth
+    from paper_2412_12218_amd import binding as B
+    from paper_2412_12218_amd.models import HotPath
+
+    B.lib()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    seed = synth.CONFIGS[5]["seed"]
+    t0 = time.perf_counter()
+    g = synth.rmat(args.scale, 16, seed)
+    X = torch.from_numpy(synth.normal_features(g.n, 128, seed + 10)).to(torch.float16).to(dev)
+    W1 = torch.from_numpy(synth.glorot_uniform(128, 16, seed + 11)).to(torch.float16).to(dev)
+    W2 = torch.from_numpy(synth.glorot_uniform(16, 8, seed + 12)).to(torch.float16).to(dev)
+    Win = torch.from_numpy(synth.glorot_uniform(128, 32, seed + 13)).to(torch.float16).to(dev)
+    Wout = torch.from_numpy(synth.glorot_uniform(32, 8, seed + 14)).to(torch.float16).to(dev)
+    betas = [1.0] * 4
+    dg = B.Graph.from_numpy(g.row_ptr, g.col_idx)
+    hp = HotPath(dg)
+    gen_s = time.perf_counter() - t0
+
+    for _ in range(args.warmup):
+        hp.step(X, W1, W2, Win, Wout, betas)
+    torch.cuda.synchronize()
+    sum_uniq = int(hp.win.summary[0].item())
+    bytes_by_call = alg_bytes(g.n, g.nnz, sum_uniq, hp.win.n_windows)
+    total_bytes = sum(bytes_by_call.values())
+
+    # Per-call events on the launch stream, recorded inside the timed region.
+    calls = []
+
+    def timed(name, fn):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        fn()
+        b.record()
+        calls.append((name, a, b))
+
+    L = B.lib()
+    C = B.C
+
+    def one_step():
+        timed("build_windows", lambda: B._check(L.ftc_build_windows(
+            C.byref(dg.c), C.byref(hp.win.c), B._ptr(hp.ws_win), C.c_size_t(hp.ws_win.numel()), B._stream())))
+        timed("gcn_norm", lambda: B._check(L.ftc_gcn_norm(
+            C.byref(dg.c), C.byref(hp.win.c), B._ptr(hp.vals), B._ptr(hp.dinv), B._stream())))
+        timed("gcn_layer1", lambda: B.ftc_gcn_layer(dg, hp.win, hp.vals, X, W1, relu=True, out=hp.gcn_h, ws=hp.ws))
+        timed("gcn_layer2", lambda: B.ftc_gcn_layer(dg, hp.win, hp.vals, hp.gcn_h, W2, out=hp.gcn_out, ws=hp.ws))
+        a, b = hp.agnn_h
+        timed("agnn_in_gemm", lambda: B.ftc_update_gemm(X, Win, out=a, relu=True))
+        n, nnz = dg.n, dg.nnz
+        # the AGNN layer is issued call by call so that SDDMM and SpMM get their own events
+        rinv = hp.ws[:n * 4].view(torch.float32)
+        off = (n * 4 + 255) // 256 * 256
+        scores = hp.ws[off:off + nnz * 4].view(torch.float32)
+        for l in range(4):
+            timed("rnorm", lambda: B.ftc_row_rnorm(a, out=rinv))
+            timed("sddmm", lambda: B.ftc_sddmm(dg, hp.win, a, a, rinv, rinv, betas[l], out=scores))
+            timed("softmax", lambda: B.ftc_edge_softmax(dg, scores, out=scores))
+            timed("spmm_d32", lambda: B.ftc_spmm(dg, hp.win, scores, a, out=b))
+            a, b = b, a
+        timed("agnn_out_gemm", lambda: B.ftc_update_gemm(a, Wout, out=hp.agnn_out))
+
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / args.steps * 1e3
+
+    per_call = {}
+    for name, a, b in calls:
+        per_call.setdefault(name, []).append(a.elapsed_time(b))
+    avg_ms = {k: float(np.mean(v)) for k, v in per_call.items()}
+    spmm_bytes = bytes_by_call["agnn_l0_spmm"]
+    sddmm_bytes = bytes_by_call["agnn_l0_sddmm"]
+    spmm_gbs = spmm_bytes / (avg_ms["spmm_d32"] * 1e-3) / 1e9
+    sddmm_gbs = sddmm_bytes / (avg_ms["sddmm"] * 1e-3) / 1e9
+    # dominant kernel: whichever of the two gather kernels takes longer per call
+    dom = "spmm_d32" if avg_ms["spmm_d32"] >= avg_ms["sddmm"] else "sddmm"
+    dom_gbs = spmm_gbs if dom == "spmm_d32" else sddmm_gbs
+
+    out = {
+        "metric": "hot-path algorithmic GB/s (window build + GCN norm + 2-layer GCN + 4-layer AGNN forward)",
+        "value": total_bytes / (ms_per_step * 1e-3) / 1e9,
+        "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "data": "synthetic",
+        "config": {"workload": f"cfg5 R-MAT scale {args.scale}: N={g.n}, nnz={g.nnz}, sum_uniq={sum_uniq}, "
+                               "fp16 features Nx128, GCN 128-16-8, AGNN 128-32x4-8, fp32 accumulate"},
+        "roofline": {"bound": "hbm", "kernel": dom, "achieved": dom_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": dom_gbs / HBM_PEAK_GBS, "traffic": None,
+                     "alg_bytes_per_launch": spmm_bytes if dom == "spmm_d32" else sddmm_bytes,
+                     "avg_ms": avg_ms[dom]},
+        "spmm_d32_GBs": spmm_gbs, "spmm_d32_frac": spmm_gbs / HBM_PEAK_GBS,
+        "sddmm_d32_GBs": sddmm_gbs, "sddmm_d32_frac": sddmm_gbs / HBM_PEAK_GBS,
+        "gcn_2layer_ms": avg_ms["gcn_layer1"] + avg_ms["gcn_layer2"],
+        "agnn_layer_ms": avg_ms["rnorm"] + avg_ms["sddmm"] + avg_ms["softmax"] + avg_ms["spmm_d32"],
+        "call_ms": avg_ms,
+        "alg_bytes_per_step": total_bytes,
+        "input_generation_s": gen_s,
+    }
+    if args.cpu_scale > 0:
+        out["cpu_baseline"] = cpu_baseline(args.cpu_scale, seed, g if args.cpu_scale == args.scale else None)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

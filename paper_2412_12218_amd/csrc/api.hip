@@ -124,15 +124,14 @@ int32_t ftc_gcn_norm(const ftc_csr *g, const ftc_windows *w, float *vals, float 
 
 size_t ftc_spmm_workspace_bytes(int32_t n, int32_t nnz, int32_t D)
 {
-    (void)n; (void)nnz; (void)D;
-    return 0;
+    if (n < 0 || nnz < 0 || D < 1) return 0;
+    return spmm_seg_ws(nnz, D);
 }
 
 int32_t ftc_spmm(const ftc_csr *g, const ftc_windows *w, const float *vals, const void *X, int32_t ldx,
                  int32_t x_dtype, int32_t D, void *out, int32_t ldo, int32_t out_dtype, int32_t relu,
                  int32_t path, void *ws, size_t ws_bytes, void *stream)
 {
-    (void)ws; (void)ws_bytes;
     FTC_TRY(check_csr(g, "ftc_spmm"));
     if (g->n == 0) return FTC_OK;
     FTC_TRY(check_dense(X, ldx, x_dtype, D, "ftc_spmm", "X"));
@@ -142,6 +141,20 @@ int32_t ftc_spmm(const ftc_csr *g, const ftc_windows *w, const float *vals, cons
     if (path != FTC_PATH_AUTO && path != FTC_PATH_VALU && path != FTC_PATH_MFMA)
         return fail(FTC_EINVAL, "ftc_spmm: unknown path %d", path);
     if (path == FTC_PATH_MFMA) return fail(FTC_EUNSUPPORTED, "ftc_spmm: matrix-core path not available");
+    int vec, lpr;
+    const bool rows16 = aligned16(X) && aligned16(out) &&
+                        (static_cast<int64_t>(ldx) * elem_size(x_dtype)) % 16 == 0 &&
+                        (static_cast<int64_t>(ldo) * elem_size(out_dtype)) % 16 == 0;
+    if (w && g->nnz > 0 && rows16 && seg_shape(x_dtype, D, &vec, &lpr)) {
+        const size_t need = spmm_seg_ws(g->nnz, D);
+        if (!ws || ws_bytes < need)
+            return fail(FTC_EWORKSPACE, "ftc_spmm: workspace of %zu bytes needed, %zu given", need,
+                        ws ? ws_bytes : static_cast<size_t>(0));
+        if (reinterpret_cast<uintptr_t>(ws) % 256 != 0)
+            return fail(FTC_EALIGN, "ftc_spmm: workspace must be 256-byte aligned");
+        return launch_spmm_seg(*g, *w, vals, X, ldx, x_dtype, D, out, ldo, out_dtype, relu, ws,
+                               static_cast<hipStream_t>(stream));
+    }
     return launch_spmm_rows(*g, vals, X, ldx, x_dtype, D, out, ldo, out_dtype, relu,
                             static_cast<hipStream_t>(stream));
 }
@@ -166,6 +179,11 @@ int32_t ftc_sddmm(const ftc_csr *g, const ftc_windows *w, const void *X, const v
     if (path != FTC_PATH_AUTO && path != FTC_PATH_VALU && path != FTC_PATH_MFMA)
         return fail(FTC_EINVAL, "ftc_sddmm: unknown path %d", path);
     if (path == FTC_PATH_MFMA) return fail(FTC_EUNSUPPORTED, "ftc_sddmm: matrix-core path not available");
+    int vec, lpr;
+    if (w && aligned16(X) && aligned16(Y) && (static_cast<int64_t>(ld) * elem_size(dtype)) % 16 == 0 &&
+        seg_shape(dtype, D, &vec, &lpr))
+        return launch_sddmm_edges(*g, *w, X, Y, ld, dtype, D, row_scale, col_scale, alpha, edge_out,
+                                  static_cast<hipStream_t>(stream));
     return launch_sddmm_rows(*g, X, Y, ld, dtype, D, row_scale, col_scale, alpha, edge_out,
                              static_cast<hipStream_t>(stream));
 }
@@ -201,11 +219,18 @@ int32_t ftc_update_gemm(int32_t n, const void *X, int32_t ldx, int32_t dtype, in
     return launch_gemm(n, X, ldx, dtype, d_in, W, d_out, Z, ldz, z_dtype, relu, static_cast<hipStream_t>(stream));
 }
 
+// The intermediate Z = X * W: fp16 when the inputs are fp16 (halves the gathered bytes; its rounding,
+// 2^-11 relative, stays far below the 16-bit tolerance), fp32 otherwise (a bf16 Z would round at
+// 2^-9, the size of the tolerance itself).  Rows padded to 16 bytes.
+static int z_dtype_for(int dtype) { return dtype == FTC_F16 ? FTC_F16 : FTC_F32; }
+static int z_ld(int d_out, int zdt) { return zdt == FTC_F32 ? (d_out + 3) / 4 * 4 : (d_out + 7) / 8 * 8; }
+
 size_t ftc_gcn_layer_workspace_bytes(int32_t n, int32_t nnz, int32_t d_in, int32_t d_out)
 {
     (void)d_in;
     if (n < 0 || nnz < 0 || d_out < 1) return 0;
-    const int ldz = (d_out + 3) / 4 * 4;
+    // sized for the fp32 intermediate, which covers the fp16 one
+    const int ldz = z_ld(d_out, FTC_F32);
     return align_up(static_cast<size_t>(n) * ldz * sizeof(float), 256) + ftc_spmm_workspace_bytes(n, nnz, d_out);
 }
 
@@ -220,11 +245,13 @@ int32_t ftc_gcn_layer(const ftc_csr *g, const ftc_windows *w, const float *vals,
         return fail(FTC_EWORKSPACE, "ftc_gcn_layer: workspace of %zu bytes needed", need);
     if (reinterpret_cast<uintptr_t>(ws) % 256 != 0)
         return fail(FTC_EALIGN, "ftc_gcn_layer: workspace must be 256-byte aligned");
-    const int ldz = (d_out + 3) / 4 * 4;
-    float *Z = static_cast<float *>(ws);
-    const size_t zbytes = align_up(static_cast<size_t>(g->n) * ldz * sizeof(float), 256);
-    FTC_TRY(ftc_update_gemm(g->n, X, ldx, dtype, d_in, W, d_out, Z, ldz, FTC_F32, 0, stream));
-    return ftc_spmm(g, w, vals, Z, ldz, FTC_F32, d_out, out, ldo, out_dtype, relu, path,
+    if (!valid_dtype(dtype)) return fail(FTC_EUNSUPPORTED, "ftc_gcn_layer: unknown dtype");
+    const int zdt = z_dtype_for(dtype);
+    const int ldz = z_ld(d_out, zdt);
+    void *Z = ws;
+    const size_t zbytes = align_up(static_cast<size_t>(g->n) * z_ld(d_out, FTC_F32) * sizeof(float), 256);
+    FTC_TRY(ftc_update_gemm(g->n, X, ldx, dtype, d_in, W, d_out, Z, ldz, zdt, 0, stream));
+    return ftc_spmm(g, w, vals, Z, ldz, zdt, d_out, out, ldo, out_dtype, relu, path,
                     static_cast<char *>(ws) + zbytes, ws_bytes - zbytes, stream);
 }
 

@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "ftc.h"
 
 namespace ftc {
@@ -29,6 +31,12 @@ int32_t launch_gemm(int n, const void *X, int ldx, int dt, int d_in, const void 
                     int ldz, int zdt, int relu, hipStream_t s);
 int32_t launch_gcn_norm(const ftc_csr &g, const ftc_windows *w, float *vals, float *dinv, hipStream_t s);
 int32_t launch_validate(const ftc_csr &g, int32_t *flag, hipStream_t s);
+bool seg_shape(int dtype, int D, int *vec, int *lpr);
+size_t spmm_seg_ws(int nnz, int D);
+int32_t launch_spmm_seg(const ftc_csr &g, const ftc_windows &w, const float *vals, const void *X, int ldx,
+                        int xdt, int D, void *out, int ldo, int odt, int relu, void *ws, hipStream_t s);
+int32_t launch_sddmm_edges(const ftc_csr &g, const ftc_windows &w, const void *X, const void *Y, int ld, int dt,
+                           int D, const float *rs, const float *cs, float alpha, float *out, hipStream_t s);
 size_t build_windows_ws(int n, int nnz, int blk_h, int blk_w);
 int32_t launch_build_windows(const ftc_csr &g, ftc_windows &w, void *ws, size_t ws_bytes, hipStream_t s);
 
@@ -113,26 +121,97 @@ __device__ __forceinline__ void store_elem(void *base, int64_t idx, int dtype, f
     else static_cast<uint16_t *>(base)[idx] = static_cast<uint16_t>(f32_to_bf16_bits(v));
 }
 
-// Store NV consecutive floats (NV = 4 or 8) at element index idx (multiple of NV; rows 16-byte
-// aligned by the caller's checks) in the run-time output dtype.
+// Narrow vector loads: NV elements (NV * sizeof(element) = 4, 8 or 16 bytes; 2 bytes for a
+// single 16-bit element) starting at element index idx, which must be a multiple of NV.
+// RawVec keeps the loaded words as they are; unpack() converts to fp32 at the point of use so
+// that several loads can be in flight without holding their fp32 expansions in registers.
+template <class T, int NV>
+struct RawVec {
+    static constexpr int WORDS = (NV * T::BYTES + 3) / 4;
+    uint32_t w[WORDS];
+};
+
+template <class T, int NV>
+__device__ __forceinline__ void zero_raw(RawVec<T, NV> &r)
+{
+#pragma unroll
+    for (int k = 0; k < RawVec<T, NV>::WORDS; ++k) r.w[k] = 0u;
+}
+
+template <class T, int NV>
+__device__ __forceinline__ void load_raw(const void *base, int64_t idx, RawVec<T, NV> &r)
+{
+    constexpr int BYTES = NV * T::BYTES;
+    const char *p = static_cast<const char *>(base) + idx * T::BYTES;
+    if constexpr (BYTES == 16) {
+        const uint4 v = *reinterpret_cast<const uint4 *>(p);
+        r.w[0] = v.x; r.w[1] = v.y; r.w[2] = v.z; r.w[3] = v.w;
+    } else if constexpr (BYTES == 8) {
+        const uint2 v = *reinterpret_cast<const uint2 *>(p);
+        r.w[0] = v.x; r.w[1] = v.y;
+    } else if constexpr (BYTES == 4) {
+        r.w[0] = *reinterpret_cast<const uint32_t *>(p);
+    } else {
+        static_assert(BYTES == 2, "vector loads are 2, 4, 8 or 16 bytes");
+        r.w[0] = *reinterpret_cast<const uint16_t *>(p);
+    }
+}
+
+template <class T, int NV>
+__device__ __forceinline__ void unpack(const RawVec<T, NV> &r, float (&f)[NV])
+{
+#pragma unroll
+    for (int k = 0; k < NV; ++k) {
+        if constexpr (T::BYTES == 4) {
+            f[k] = __uint_as_float(r.w[k]);
+        } else {
+            const uint32_t word = r.w[k / 2];
+            if constexpr (std::is_same<T, F16>::value) f[k] = f16_bits_to_f32((k & 1) ? (word >> 16) : (word & 0xffffu));
+            else f[k] = (k & 1) ? __uint_as_float(word & 0xffff0000u) : __uint_as_float(word << 16);
+        }
+    }
+}
+
+template <class T, int NV>
+__device__ __forceinline__ void load_n(const void *base, int64_t idx, float (&f)[NV])
+{
+    RawVec<T, NV> r;
+    load_raw<T, NV>(base, idx, r);
+    unpack<T, NV>(r, f);
+}
+
+// Store NV consecutive floats (NV = 1, 2, 4 or 8) at element index idx (multiple of NV; rows are
+// 16-byte aligned by the caller's checks) in the run-time output dtype.
 template <int NV>
 __device__ __forceinline__ void store_vec(void *base, int64_t idx, int dtype, const float (&f)[NV])
 {
     if (dtype == FTC_F32) {
-        float4 *p = reinterpret_cast<float4 *>(static_cast<float *>(base) + idx);
+        float *p = static_cast<float *>(base) + idx;
+        if constexpr (NV >= 4) {
 #pragma unroll
-        for (int k = 0; k < NV / 4; ++k) p[k] = make_float4(f[4 * k], f[4 * k + 1], f[4 * k + 2], f[4 * k + 3]);
-    } else {
-        uint32_t w[NV / 2];
-#pragma unroll
-        for (int k = 0; k < NV / 2; ++k) {
-            uint32_t lo = dtype == FTC_F16 ? f32_to_f16_bits(f[2 * k]) : f32_to_bf16_bits(f[2 * k]);
-            uint32_t hi = dtype == FTC_F16 ? f32_to_f16_bits(f[2 * k + 1]) : f32_to_bf16_bits(f[2 * k + 1]);
-            w[k] = lo | (hi << 16);
+            for (int k = 0; k < NV / 4; ++k)
+                reinterpret_cast<float4 *>(p)[k] = make_float4(f[4 * k], f[4 * k + 1], f[4 * k + 2], f[4 * k + 3]);
+        } else if constexpr (NV == 2) {
+            *reinterpret_cast<float2 *>(p) = make_float2(f[0], f[1]);
+        } else {
+            *p = f[0];
         }
+    } else {
         uint16_t *q = static_cast<uint16_t *>(base) + idx;
-        if constexpr (NV == 8) *reinterpret_cast<uint4 *>(q) = make_uint4(w[0], w[1], w[2], w[3]);
-        else *reinterpret_cast<uint2 *>(q) = make_uint2(w[0], w[1]);
+        if constexpr (NV == 1) {
+            *q = static_cast<uint16_t>(dtype == FTC_F16 ? f32_to_f16_bits(f[0]) : f32_to_bf16_bits(f[0]));
+        } else {
+            uint32_t w[NV / 2];
+#pragma unroll
+            for (int k = 0; k < NV / 2; ++k) {
+                const uint32_t lo = dtype == FTC_F16 ? f32_to_f16_bits(f[2 * k]) : f32_to_bf16_bits(f[2 * k]);
+                const uint32_t hi = dtype == FTC_F16 ? f32_to_f16_bits(f[2 * k + 1]) : f32_to_bf16_bits(f[2 * k + 1]);
+                w[k] = lo | (hi << 16);
+            }
+            if constexpr (NV == 8) *reinterpret_cast<uint4 *>(q) = make_uint4(w[0], w[1], w[2], w[3]);
+            else if constexpr (NV == 4) *reinterpret_cast<uint2 *>(q) = make_uint2(w[0], w[1]);
+            else *reinterpret_cast<uint32_t *>(q) = w[0];
+        }
     }
 }
 

@@ -1,0 +1,172 @@
+// Edge-parallel sparse edge feature computation (SDDMM, Section V.A) on the vector units.
+//
+// The output has one value per stored entry (`EdgeValList`), so equal numbers of EDGES per wave
+// balance the work however skewed the rows are; edge_to_row of the window index gives each
+// edge its row.  A wave stages the (column, row) pairs of SEG_R consecutive edges in LDS, groups
+// of LPR lanes walk contiguous runs of them, eight edges at a time: eight independent gathers of
+// Y rows in flight per lane, the X row is re-read only when the row changes.  Dot products are
+// reduced inside the group with DPP lane shuffles, parked in LDS, and written back scaled
+// (alpha * row_scale[i] * col_scale[j]) with fully coalesced stores.
+#include "ftc_common.hpp"
+
+namespace ftc {
+
+constexpr int SD_R = 512;  // edges per wave
+constexpr int SD_B = 8;    // edges per batch
+
+bool seg_shape(int dtype, int D, int *vec, int *lpr);  // spmm_seg.hip: same lane layout
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float v)
+{
+    const int moved = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false);
+    return v + __int_as_float(moved);
+}
+
+// Sum over the LPR consecutive lanes of a group; every lane of the group gets the total.
+template <int LPR>
+__device__ __forceinline__ float group_sum_dpp(float v)
+{
+    if constexpr (LPR >= 32) v += __shfl_xor(v, 16, 64);
+    if constexpr (LPR >= 16) v = dpp_add<0x140>(v);  // row_mirror: lane i <-> 15 - i
+    if constexpr (LPR >= 8) v = dpp_add<0x141>(v);   // row_half_mirror: lane i <-> 7 - i
+    if constexpr (LPR >= 4) v = dpp_add<0x4e>(v);    // quad_perm [2,3,0,1]
+    if constexpr (LPR >= 2) v = dpp_add<0xb1>(v);    // quad_perm [1,0,3,2]
+    return v;
+}
+
+template <class T, int VEC, int LPR>
+__global__ __launch_bounds__(256) void sddmm_edges_kernel(int nnz, int n_ranges, const int *__restrict__ col_idx,
+                                                          const int *__restrict__ edge_to_row,
+                                                          const void *__restrict__ X,
+                                                          const void *__restrict__ Y, int ld, int D,
+                                                          const float *__restrict__ rs,
+                                                          const float *__restrict__ cs, float alpha,
+                                                          float *__restrict__ out)
+{
+    constexpr int NG = 64 / LPR;
+    constexpr int RUN = SD_R / NG;
+    constexpr int RP = SD_R + NG;
+    __shared__ int s_col_all[4][RP];
+    __shared__ int s_row_all[4][RP];
+    __shared__ float s_dot_all[4][RP];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int g = lane / LPR, sub = lane % LPR;
+    int *s_col = s_col_all[wave];
+    int *s_row = s_row_all[wave];
+    float *s_dot = s_dot_all[wave];
+
+    const int v = blockIdx.x * 4 + wave;
+    const bool active = v < n_ranges;
+    const int base = active ? v * SD_R : 0;
+    const int n_valid = active ? min(SD_R, nnz - base) : 0;
+#pragma unroll
+    for (int j = 0; j < SD_R / 64; ++j) {
+        const int i = j * 64 + lane;
+        if (i < n_valid) {
+            const int p = i + i / RUN;
+            s_col[p] = col_idx[base + i];
+            s_row[p] = edge_to_row[base + i];
+        }
+    }
+    __syncthreads();
+
+    const int rs0 = g * RUN;
+    const int re = min(rs0 + RUN, n_valid);
+    const bool live = sub * VEC < D;
+    float xi[VEC];
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) xi[j] = 0.f;
+    int cur = -1;
+    // every group runs the same number of batches so that the lane shuffles stay converged
+    for (int b = rs0; b < rs0 + RUN; b += SD_B) {
+        int c[SD_B], r[SD_B];
+        bool need[SD_B];
+        RawVec<T, VEC> y[SD_B], xs[SD_B];
+#pragma unroll
+        for (int k = 0; k < SD_B; ++k) {
+            const bool ok = b + k < re;
+            const int p = (ok ? b + k : 0) + (ok ? g : 0);
+            c[k] = ok ? s_col[p] : -1;
+            r[k] = ok ? s_row[p] : -1;
+        }
+        int prev = cur;
+#pragma unroll
+        for (int k = 0; k < SD_B; ++k) {
+            need[k] = r[k] >= 0 && r[k] != prev;
+            if (r[k] >= 0) prev = r[k];
+        }
+#pragma unroll
+        for (int k = 0; k < SD_B; ++k) {
+            if (c[k] >= 0 && live) load_raw<T, VEC>(Y, static_cast<int64_t>(c[k]) * ld + sub * VEC, y[k]);
+            else zero_raw(y[k]);
+            if (need[k] && live) load_raw<T, VEC>(X, static_cast<int64_t>(r[k]) * ld + sub * VEC, xs[k]);
+            else zero_raw(xs[k]);
+        }
+#pragma unroll
+        for (int k = 0; k < SD_B; ++k) {
+            if (need[k]) unpack<T, VEC>(xs[k], xi);
+            float yf[VEC];
+            unpack<T, VEC>(y[k], yf);
+            float d = 0.f;
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) d = fmaf(xi[j], yf[j], d);
+            d = group_sum_dpp<LPR>(d);
+            if (sub == 0 && r[k] >= 0) s_dot[b + k + g] = d;
+        }
+        cur = prev;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < SD_R / 64; ++j) {
+        const int i = j * 64 + lane;
+        if (i < n_valid) {
+            const int p = i + i / RUN;
+            const float scale = alpha * (rs ? rs[s_row[p]] : 1.f) * (cs ? cs[s_col[p]] : 1.f);
+            out[base + i] = scale * s_dot[p];
+        }
+    }
+}
+
+template <class T>
+static void launch_edges_t(int vec, int lpr, unsigned grid, hipStream_t s, int nnz, int n_ranges,
+                           const ftc_csr &g, const int *e2r, const void *X, const void *Y, int ld, int D,
+                           const float *rs, const float *cs, float alpha, float *out)
+{
+    constexpr int VM = T::VEC;
+#define FTC_SD(V, L)                                                                                         \
+    hipLaunchKernelGGL((sddmm_edges_kernel<T, V, L>), dim3(grid), dim3(256), 0, s, nnz, n_ranges, g.col_idx, \
+                       e2r, X, Y, ld, D, rs, cs, alpha, out)
+    if (vec == VM) {
+        if (lpr == 4) FTC_SD(VM, 4);
+        else if (lpr == 8) FTC_SD(VM, 8);
+        else if (lpr == 16) FTC_SD(VM, 16);
+        else FTC_SD(VM, 32);
+    } else if (vec == VM / 2) {
+        FTC_SD(VM / 2, 4);
+    } else {
+        FTC_SD(VM / 4, 4);
+    }
+#undef FTC_SD
+}
+
+// Caller has checked: window index present, seg_shape() accepts (dt, D), rows 16-byte aligned.
+int32_t launch_sddmm_edges(const ftc_csr &g, const ftc_windows &w, const void *X, const void *Y, int ld, int dt,
+                           int D, const float *rs, const float *cs, float alpha, float *out, hipStream_t s)
+{
+    if (g.nnz == 0) return FTC_OK;
+    int vec = 0, lpr = 0;
+    seg_shape(dt, D, &vec, &lpr);
+    const int n_ranges = (g.nnz + SD_R - 1) / SD_R;
+    const unsigned grid = static_cast<unsigned>((n_ranges + 3) / 4);
+    if (dt == FTC_F32)
+        launch_edges_t<F32>(vec, lpr, grid, s, g.nnz, n_ranges, g, w.edge_to_row, X, Y, ld, D, rs, cs, alpha, out);
+    else if (dt == FTC_F16)
+        launch_edges_t<F16>(vec, lpr, grid, s, g.nnz, n_ranges, g, w.edge_to_row, X, Y, ld, D, rs, cs, alpha, out);
+    else
+        launch_edges_t<BF16>(vec, lpr, grid, s, g.nnz, n_ranges, g, w.edge_to_row, X, Y, ld, D, rs, cs, alpha,
+                             out);
+    return launch_status("sddmm_edges");
+}
+
+}  // namespace ftc

@@ -1,0 +1,62 @@
+"""Layer chaining of the two benchmark models (Section VI: 2-layer GCN with hidden size 16,
+4-layer AGNN with hidden size 32), forward only.
+
+Every step is a call into libftc through `binding`; this module only owns the device
+buffers between the calls (allocated once in __init__, so a forward pass allocates nothing).
+"""
+import torch
+
+from . import binding as B
+
+
+class HotPath:
+    """window build + GCN normalisation + 2-layer GCN + 4-layer AGNN on one graph."""
+
+    def __init__(self, g, d_feat=128, gcn_hidden=16, agnn_hidden=32, n_out=8, agnn_layers=4,
+                 act_dtype=torch.float16, path=B.FTC_PATH_AUTO):
+        dev = g.row_ptr.device
+        L = B.lib()
+        self.g, self.path, self.agnn_layers = g, path, agnn_layers
+        self.win = B.Windows(g)
+        n, nnz = g.n, g.nnz
+        f32 = dict(dtype=torch.float32, device=dev)
+        act = dict(dtype=act_dtype, device=dev)
+        self.ws_win = B._workspace(L.ftc_build_windows_workspace_bytes(n, nnz, 16, 8), dev)
+        self.vals = torch.empty(nnz, **f32)
+        self.dinv = torch.empty(n, **f32)
+        self.gcn_h = torch.empty((n, gcn_hidden), **act)
+        self.gcn_out = torch.empty((n, n_out), **f32)
+        ws_gcn = max(L.ftc_gcn_layer_workspace_bytes(n, nnz, d_feat, gcn_hidden),
+                     L.ftc_gcn_layer_workspace_bytes(n, nnz, gcn_hidden, n_out))
+        self.agnn_h = [torch.empty((n, agnn_hidden), **act) for _ in range(2)]
+        self.agnn_out = torch.empty((n, n_out), **f32)
+        ws_agnn = L.ftc_agnn_layer_workspace_bytes(n, nnz, agnn_hidden)
+        self.ws = B._workspace(max(ws_gcn, ws_agnn), dev)
+
+    def build(self):
+        g, w = self.g, self.win
+        B._check(B.lib().ftc_build_windows(B.C.byref(g.c), B.C.byref(w.c), B._ptr(self.ws_win),
+                                           B.C.c_size_t(self.ws_win.numel()), B._stream()))
+        B._check(B.lib().ftc_gcn_norm(B.C.byref(g.c), B.C.byref(w.c), B._ptr(self.vals), B._ptr(self.dinv),
+                                      B._stream()))
+
+    def gcn(self, X, W1, W2):
+        B.ftc_gcn_layer(self.g, self.win, self.vals, X, W1, relu=True, out=self.gcn_h, path=self.path,
+                        ws=self.ws)
+        B.ftc_gcn_layer(self.g, self.win, self.vals, self.gcn_h, W2, relu=False, out=self.gcn_out,
+                        path=self.path, ws=self.ws)
+        return self.gcn_out
+
+    def agnn(self, X, W_in, W_out, betas):
+        a, b = self.agnn_h
+        B.ftc_update_gemm(X, W_in, out=a, relu=True)
+        for layer in range(self.agnn_layers):
+            B.ftc_agnn_layer(self.g, self.win, a, beta=betas[layer], out=b, path=self.path, ws=self.ws)
+            a, b = b, a
+        B.ftc_update_gemm(a, W_out, out=self.agnn_out)
+        return self.agnn_out
+
+    def step(self, X, W1, W2, W_in, W_out, betas):
+        self.build()
+        self.gcn(X, W1, W2)
+        self.agnn(X, W_in, W_out, betas)
