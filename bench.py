@@ -156,11 +156,14 @@ def main():
         rinv = hp.ws[:n * 4].view(torch.float32)
         off = (n * 4 + 255) // 256 * 256
         scores = hp.ws[off:off + nnz * 4].view(torch.float32)
+        off2 = (off + nnz * 4 + 255) // 256 * 256
+        ws_sm = hp.ws[off2:off2 + L.ftc_edge_softmax_workspace_bytes(n, nnz)]
+        ws_rest = hp.ws[off2 + (ws_sm.numel() + 255) // 256 * 256:]
         for l in range(4):
             timed("rnorm", lambda: B.ftc_row_rnorm(a, out=rinv))
             timed("sddmm", lambda: B.ftc_sddmm(dg, hp.win, a, a, rinv, rinv, betas[l], out=scores))
-            timed("softmax", lambda: B.ftc_edge_softmax(dg, scores, out=scores))
-            timed("spmm_d32", lambda: B.ftc_spmm(dg, hp.win, scores, a, out=b))
+            timed("softmax", lambda: B.ftc_edge_softmax(dg, hp.win, scores, out=scores, ws=ws_sm))
+            timed("spmm_d32", lambda: B.ftc_spmm(dg, hp.win, scores, a, out=b, ws=ws_rest))
             a, b = b, a
         timed("agnn_out_gemm", lambda: B.ftc_update_gemm(a, Wout, out=hp.agnn_out))
 

@@ -159,9 +159,13 @@ int32_t ftc_row_rnorm(int32_t n, const void *H, int32_t ld, int32_t dtype, int32
  * Edge softmax over the stored entries of every row (the attention weights of AGNN,
  * which the paper names in Section VI):
  *   p[e] = exp(s[e] - m_i) / sum_{e' in row i} exp(s[e'] - m_i),  m_i = max over row i.
- * p_out may alias e_in.  Rows without entries write nothing.
+ * p_out may alias e_in.  Rows without entries write nothing.  w may be NULL; with a window
+ * index the work is split by edges (edge_to_row), which keeps hub rows from serialising,
+ * and a workspace of ftc_edge_softmax_workspace_bytes is needed (none when w is NULL).
  */
-int32_t ftc_edge_softmax(const ftc_csr *g, const float *e_in, float *p_out, void *stream);
+size_t ftc_edge_softmax_workspace_bytes(int32_t n, int32_t nnz);
+int32_t ftc_edge_softmax(const ftc_csr *g, const ftc_windows *w, const float *e_in, float *p_out,
+                         void *ws, size_t ws_bytes, void *stream);
 
 /*
  * Dense update phase (Section I.A.2): Z = X * W, X n x d_in (dtype), W d_in x d_out
@@ -175,7 +179,7 @@ int32_t ftc_update_gemm(int32_t n, const void *X, int32_t ldx, int32_t dtype, in
 /*
  * GCN layer forward: out = act(A^ * (X * W)) with A^ given by (g, vals); update first,
  * then aggregation (Eq. 1-2 of Section I).  W is d_in x d_out row-major, same dtype as X.
- * The intermediate X * W is kept in fp32 inside the workspace.
+ * The intermediate X * W lives in the workspace: fp16 for fp16 inputs, fp32 otherwise.
  */
 size_t ftc_gcn_layer_workspace_bytes(int32_t n, int32_t nnz, int32_t d_in, int32_t d_out);
 int32_t ftc_gcn_layer(const ftc_csr *g, const ftc_windows *w, const float *vals, const void *X,

@@ -22,7 +22,8 @@ _DTYPES = {torch.float32: FTC_F32, torch.float16: FTC_F16, torch.bfloat16: FTC_B
 
 EXPORTS = ["ftc_version", "ftc_last_error", "ftc_validate_csr", "ftc_build_windows_workspace_bytes",
            "ftc_build_windows", "ftc_gcn_norm", "ftc_spmm_workspace_bytes", "ftc_spmm",
-           "ftc_sddmm_workspace_bytes", "ftc_sddmm", "ftc_row_rnorm", "ftc_edge_softmax",
+           "ftc_sddmm_workspace_bytes", "ftc_sddmm", "ftc_row_rnorm", "ftc_edge_softmax_workspace_bytes",
+           "ftc_edge_softmax",
            "ftc_update_gemm", "ftc_gcn_layer_workspace_bytes", "ftc_gcn_layer",
            "ftc_agnn_layer_workspace_bytes", "ftc_agnn_layer"]
 
@@ -59,8 +60,9 @@ def lib():
         for name in EXPORTS:
             if name.endswith("_workspace_bytes"):
                 getattr(L, name).restype = C.c_size_t
-                getattr(L, name).argtypes = [C.c_int32] * 4 if name in (
-                    "ftc_build_windows_workspace_bytes", "ftc_gcn_layer_workspace_bytes") else [C.c_int32] * 3
+                nargs = {"ftc_build_windows_workspace_bytes": 4, "ftc_gcn_layer_workspace_bytes": 4,
+                         "ftc_edge_softmax_workspace_bytes": 2}.get(name, 3)
+                getattr(L, name).argtypes = [C.c_int32] * nargs
         _lib = L
     return _lib
 
@@ -189,10 +191,13 @@ def ftc_row_rnorm(H, out=None):
     return out
 
 
-def ftc_edge_softmax(g, e_in, out=None):
+def ftc_edge_softmax(g, w, e_in, out=None, ws=None):
     if out is None:
         out = torch.empty_like(e_in)
-    _check(lib().ftc_edge_softmax(C.byref(g.c), _ptr(e_in), _ptr(out), _stream()))
+    if ws is None:
+        ws = _workspace(lib().ftc_edge_softmax_workspace_bytes(g.n, g.nnz) if w is not None else 0, e_in.device)
+    _check(lib().ftc_edge_softmax(C.byref(g.c), _wref(w), _ptr(e_in), _ptr(out), _ptr(ws),
+                                  C.c_size_t(ws.numel()), _stream()))
     return out
 
 

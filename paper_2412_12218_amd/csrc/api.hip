@@ -198,12 +198,28 @@ int32_t ftc_row_rnorm(int32_t n, const void *H, int32_t ld, int32_t dtype, int32
     return launch_row_rnorm(n, H, ld, dtype, D, rinv, static_cast<hipStream_t>(stream));
 }
 
-int32_t ftc_edge_softmax(const ftc_csr *g, const float *e_in, float *p_out, void *stream)
+size_t ftc_edge_softmax_workspace_bytes(int32_t n, int32_t nnz)
+{
+    if (n < 0 || nnz < 0) return 0;
+    return softmax_seg_ws(n, nnz);
+}
+
+int32_t ftc_edge_softmax(const ftc_csr *g, const ftc_windows *w, const float *e_in, float *p_out, void *ws,
+                         size_t ws_bytes, void *stream)
 {
     FTC_TRY(check_csr(g, "ftc_edge_softmax"));
     if (g->n == 0 || g->nnz == 0) return FTC_OK;
     if (!e_in || !p_out) return fail(FTC_EINVAL, "ftc_edge_softmax: NULL edge array");
-    return launch_softmax(*g, e_in, p_out, static_cast<hipStream_t>(stream));
+    if (!w) return launch_softmax(*g, e_in, p_out, static_cast<hipStream_t>(stream));
+    FTC_TRY(check_windows(g, w, "ftc_edge_softmax", false));
+    if (!w->edge_to_row) return fail(FTC_EINVAL, "ftc_edge_softmax: edge_to_row is NULL");
+    const size_t need = softmax_seg_ws(g->n, g->nnz);
+    if (!ws || ws_bytes < need)
+        return fail(FTC_EWORKSPACE, "ftc_edge_softmax: workspace of %zu bytes needed, %zu given", need,
+                    ws ? ws_bytes : static_cast<size_t>(0));
+    if (reinterpret_cast<uintptr_t>(ws) % 256 != 0)
+        return fail(FTC_EALIGN, "ftc_edge_softmax: workspace must be 256-byte aligned");
+    return launch_softmax_seg(*g, *w, e_in, p_out, ws, static_cast<hipStream_t>(stream));
 }
 
 int32_t ftc_update_gemm(int32_t n, const void *X, int32_t ldx, int32_t dtype, int32_t d_in, const void *W,
@@ -260,7 +276,8 @@ size_t ftc_agnn_layer_workspace_bytes(int32_t n, int32_t nnz, int32_t D)
     if (n < 0 || nnz < 0 || D < 1) return 0;
     return align_up(static_cast<size_t>(n) * sizeof(float), 256) +
            align_up(static_cast<size_t>(nnz) * sizeof(float), 256) +
-           align_up(ftc_sddmm_workspace_bytes(n, nnz, D), 256) + ftc_spmm_workspace_bytes(n, nnz, D);
+           align_up(ftc_sddmm_workspace_bytes(n, nnz, D), 256) +
+           align_up(ftc_edge_softmax_workspace_bytes(n, nnz), 256) + ftc_spmm_workspace_bytes(n, nnz, D);
 }
 
 int32_t ftc_agnn_layer(const ftc_csr *g, const ftc_windows *w, const void *H, int32_t ld, int32_t dtype,
@@ -282,10 +299,13 @@ int32_t ftc_agnn_layer(const ftc_csr *g, const ftc_windows *w, const void *H, in
     const size_t sd = align_up(ftc_sddmm_workspace_bytes(g->n, g->nnz, D), 256);
     void *ws_sddmm = p;
     p += sd;
+    const size_t sm = align_up(ftc_edge_softmax_workspace_bytes(g->n, g->nnz), 256);
+    void *ws_softmax = p;
+    p += sm;
     const size_t rest = ws_bytes - static_cast<size_t>(p - static_cast<char *>(ws));
     FTC_TRY(ftc_row_rnorm(g->n, H, ld, dtype, D, rinv, stream));
     FTC_TRY(ftc_sddmm(g, w, H, H, ld, dtype, D, rinv, rinv, beta, scores, path, ws_sddmm, sd, stream));
-    FTC_TRY(ftc_edge_softmax(g, scores, scores, stream));
+    FTC_TRY(ftc_edge_softmax(g, w, scores, scores, ws_softmax, sm, stream));
     return ftc_spmm(g, w, scores, H, ld, dtype, D, out, ldo, out_dtype, 0, path, p, rest, stream);
 }
 

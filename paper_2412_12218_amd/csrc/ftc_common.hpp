@@ -26,6 +26,9 @@ int32_t launch_spmm_rows(const ftc_csr &g, const float *vals, const void *X, int
 int32_t launch_sddmm_rows(const ftc_csr &g, const void *X, const void *Y, int ld, int dt, int D,
                           const float *rs, const float *cs, float alpha, float *out, hipStream_t s);
 int32_t launch_softmax(const ftc_csr &g, const float *in, float *out, hipStream_t s);
+size_t softmax_seg_ws(int n, int nnz);
+int32_t launch_softmax_seg(const ftc_csr &g, const ftc_windows &w, const float *in, float *out, void *ws,
+                           hipStream_t s);
 int32_t launch_row_rnorm(int n, const void *H, int ld, int dt, int D, float *rinv, hipStream_t s);
 int32_t launch_gemm(int n, const void *X, int ldx, int dt, int d_in, const void *W, int d_out, void *Z,
                     int ldz, int zdt, int relu, hipStream_t s);

@@ -94,6 +94,156 @@ int32_t launch_softmax(const ftc_csr &g, const float *in, float *out, hipStream_
 }
 
 // ------------------------------------------------------------------------------------------------
+// Edge-balanced variant for graphs with a window index (edge_to_row known for every edge).
+//
+//   1. stats kernel: a wave takes SMS_R consecutive edges, 64 at a time.  The pair
+//      (running maximum m, sum of exp(s - m)) is an associative reduction, so a segmented
+//      inclusive scan over the 64 lanes (segments = runs of equal row id, found with
+//      edge_to_row) gives every row piece its pair.  Rows that end inside the wave's range and
+//      did not start before it are final and go to stats[row]; the piece entering from the left
+//      and the piece leaving to the right go to a carry buffer.
+//   2. fix-up kernel: pieces of a row cut by range boundaries are combined in edge order.
+//   3. apply kernel: p[e] = exp(s[e] - m[row]) / z[row], one thread per edge.
+constexpr int SMS_R = 1024;
+
+struct MZ {
+    float m, z;
+};
+
+__device__ __forceinline__ MZ mz_combine(MZ a, MZ b)
+{
+    // exp of a non-positive number only; the larger maximum keeps its sum unscaled
+    MZ r;
+    if (a.m >= b.m) { r.m = a.m; r.z = a.z + b.z * __expf(b.m - a.m); }
+    else { r.m = b.m; r.z = b.z + a.z * __expf(a.m - b.m); }
+    return r;
+}
+
+__global__ __launch_bounds__(256) void softmax_stats_kernel(int nnz, int n_ranges,
+                                                            const int *__restrict__ edge_to_row,
+                                                            const float *__restrict__ in,
+                                                            float2 *__restrict__ stats,
+                                                            float2 *__restrict__ carry,  // [n_ranges][2]
+                                                            int *__restrict__ carry_tail_row)
+{
+    const int lane = threadIdx.x & 63;
+    const int v = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (v >= n_ranges) return;  // no workgroup barrier below
+    const int base = v * SMS_R;
+    const int n_valid = min(SMS_R, nnz - base);
+    const int prev_row = base > 0 ? edge_to_row[base - 1] : -1;
+    // the open piece carried from chunk to chunk (same value in every lane)
+    MZ cmz = {-INFINITY, 0.f};
+    int crow = -1;
+    for (int c0 = 0; c0 < n_valid; c0 += 64) {
+        const int i = c0 + lane;
+        const bool ok = i < n_valid;
+        const int row = ok ? edge_to_row[base + i] : -2 - lane;  // distinct ids for the padding lanes
+        MZ x = {ok ? in[base + i] : -INFINITY, ok ? 1.f : 0.f};
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            MZ y;
+            y.m = __shfl_up(x.m, d, 64);
+            y.z = __shfl_up(x.z, d, 64);
+            const int yr = __shfl_up(row, d, 64);
+            if (lane >= d && yr == row) x = mz_combine(y, x);
+        }
+        const int first_row = __shfl(row, 0, 64);
+        if (crow >= 0) {
+            if (row == crow) {
+                x = mz_combine(cmz, x);  // lanes of the first segment continue the carried piece
+            } else if (first_row != crow && lane == 0) {
+                // the carried piece ended exactly at the chunk boundary
+                if (crow == prev_row) carry[2 * static_cast<size_t>(v)] = make_float2(cmz.m, cmz.z);
+                else stats[crow] = make_float2(cmz.m, cmz.z);
+            }
+        }
+        const int last_lane = min(63, n_valid - c0 - 1);
+        const int next_row = __shfl_down(row, 1, 64);
+        if (ok && lane < last_lane && next_row != row) {  // a piece that ends inside the chunk
+            if (row == prev_row) carry[2 * static_cast<size_t>(v)] = make_float2(x.m, x.z);
+            else stats[row] = make_float2(x.m, x.z);
+        }
+        crow = __shfl(row, last_lane, 64);
+        cmz.m = __shfl(x.m, last_lane, 64);
+        cmz.z = __shfl(x.z, last_lane, 64);
+    }
+    if (lane == 0) {
+        const bool right_open = base + n_valid < nnz && edge_to_row[base + n_valid] == crow;
+        int tail = -1;
+        if (crow == prev_row) {
+            carry[2 * static_cast<size_t>(v)] = make_float2(cmz.m, cmz.z);  // closed or spanning the range
+        } else if (right_open) {
+            carry[2 * static_cast<size_t>(v) + 1] = make_float2(cmz.m, cmz.z);
+            tail = crow;
+        } else {
+            stats[crow] = make_float2(cmz.m, cmz.z);
+        }
+        carry_tail_row[v] = tail;
+    }
+}
+
+__global__ __launch_bounds__(256) void softmax_fixup_kernel(int n_ranges, const int *__restrict__ row_ptr,
+                                                            const float2 *__restrict__ carry,
+                                                            const int *__restrict__ carry_tail_row,
+                                                            float2 *__restrict__ stats)
+{
+    const int v = blockIdx.x * 256 + threadIdx.x;
+    if (v >= n_ranges) return;
+    const int r = carry_tail_row[v];
+    if (r < 0) return;
+    const int last = (row_ptr[r + 1] - 1) / SMS_R;
+    float2 t = carry[2 * static_cast<size_t>(v) + 1];
+    MZ acc = {t.x, t.y};
+    for (int u = v + 1; u <= last; ++u) {
+        t = carry[2 * static_cast<size_t>(u)];
+        acc = mz_combine(acc, MZ{t.x, t.y});
+    }
+    stats[r] = make_float2(acc.m, acc.z);
+}
+
+__global__ __launch_bounds__(256) void softmax_apply_kernel(int nnz, const int *__restrict__ edge_to_row,
+                                                            const float2 *__restrict__ stats, const float *in,
+                                                            float *out)
+{
+    const int64_t e = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (e >= nnz) return;
+    const float2 st = stats[edge_to_row[e]];
+    out[e] = expf(in[e] - st.x) / st.y;
+}
+
+size_t softmax_seg_ws(int n, int nnz)
+{
+    const size_t n_ranges = (static_cast<size_t>(nnz) + SMS_R - 1) / SMS_R;
+    return align_up(static_cast<size_t>(n) * sizeof(float2), 256) + align_up(n_ranges * 2 * sizeof(float2), 256) +
+           align_up(n_ranges * sizeof(int), 256);
+}
+
+int32_t launch_softmax_seg(const ftc_csr &g, const ftc_windows &w, const float *in, float *out, void *ws,
+                           hipStream_t s)
+{
+    if (g.n == 0 || g.nnz == 0) return FTC_OK;
+    const int n_ranges = (g.nnz + SMS_R - 1) / SMS_R;
+    char *p = static_cast<char *>(ws);
+    float2 *stats = reinterpret_cast<float2 *>(p);
+    p += align_up(static_cast<size_t>(g.n) * sizeof(float2), 256);
+    float2 *carry = reinterpret_cast<float2 *>(p);
+    p += align_up(static_cast<size_t>(n_ranges) * 2 * sizeof(float2), 256);
+    int *tail_row = reinterpret_cast<int *>(p);
+    hipLaunchKernelGGL(softmax_stats_kernel, dim3((n_ranges + 3) / 4), dim3(256), 0, s, g.nnz, n_ranges,
+                       w.edge_to_row, in, stats, carry, tail_row);
+    int32_t st = launch_status("edge_softmax stats");
+    if (st != FTC_OK) return st;
+    hipLaunchKernelGGL(softmax_fixup_kernel, dim3((n_ranges + 255) / 256), dim3(256), 0, s, n_ranges, g.row_ptr,
+                       carry, tail_row, stats);
+    st = launch_status("edge_softmax fixup");
+    if (st != FTC_OK) return st;
+    hipLaunchKernelGGL(softmax_apply_kernel, dim3((g.nnz + 255) / 256), dim3(256), 0, s, g.nnz, w.edge_to_row,
+                       stats, in, out);
+    return launch_status("edge_softmax apply");
+}
+
+// ------------------------------------------------------------------------------------------------
 // Inverse row norms for the AGNN cosine: a group of LPR lanes per row.
 template <class T, int LPR>
 __global__ __launch_bounds__(256) void row_rnorm_kernel(int n, const void *__restrict__ H, int ld, int D,

@@ -45,7 +45,7 @@ def test_null_graph_is_rejected_on_host():
     assert L.ftc_spmm(None, None, None, None, i, i, i, None, i, i, i, i, None, z, None) == B.FTC_EINVAL
     assert b"graph is NULL" in L.ftc_last_error()
     assert L.ftc_build_windows(None, None, None, z, None) == B.FTC_EINVAL
-    assert L.ftc_edge_softmax(None, None, None, None) == B.FTC_EINVAL
+    assert L.ftc_edge_softmax(None, None, None, None, None, z, None) == B.FTC_EINVAL
     assert L.ftc_gcn_norm(None, None, None, None, None) == B.FTC_EINVAL
 
 

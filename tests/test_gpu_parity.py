@@ -223,33 +223,43 @@ def test_row_rnorm(oracle, dtype, D):
 
 
 @pytest.mark.parametrize("name", GRAPH_NAMES)
-def test_edge_softmax(oracle, graphs, name):
+@pytest.mark.parametrize("with_windows", [True, False])
+def test_edge_softmax(oracle, graphs, name, with_windows):
     g = graphs[name]
-    say(f"edge_softmax {name}")
+    say(f"edge_softmax {name} windows={with_windows}")
     rng = np.random.default_rng(5)
     s32 = (rng.standard_normal(g.nnz) * 2).astype(np.float32)
     ref = oracle.edge_softmax(g.row_ptr, s32.astype(np.float64))
     dg = dev_graph(g)
+    win = B.ftc_build_windows(dg) if with_windows else None
     sd = torch.from_numpy(s32).cuda()
-    p = B.ftc_edge_softmax(dg, sd)
-    assert rel_err(p, ref) < 1e-5
-    B.ftc_edge_softmax(dg, sd, out=sd)           # in place
+    p = B.ftc_edge_softmax(dg, win, sd)
+    err = rel_err(p, ref)
+    say(f"  err {err:.3e}")
+    assert err < 1e-5
+    p2 = B.ftc_edge_softmax(dg, win, sd)
+    assert torch.equal(p, p2)
+    B.ftc_edge_softmax(dg, win, sd, out=sd)           # in place
     assert torch.equal(p, sd)
     rows = np.repeat(np.arange(g.n), np.diff(g.row_ptr))
     sums = np.bincount(rows, weights=p.cpu().double().numpy(), minlength=g.n)
     assert np.allclose(sums[np.diff(g.row_ptr) > 0], 1.0, atol=1e-5)
 
 
-def test_edge_softmax_long_rows(oracle):
-    """Rows of 1, 16, 17, 2048, 2049 and 70000 entries: every length class of the kernel."""
-    lens = [1, 16, 17, 0, 2048, 2049, 70000, 3, 100]
+@pytest.mark.parametrize("with_windows", [True, False])
+def test_edge_softmax_long_rows(oracle, with_windows):
+    """Rows of 1, 16, 17, 2048, 2049 and 70000 entries: every length class of the row kernel, and
+    rows cut by one, two and many edge ranges of the balanced kernel."""
+    lens = [1, 16, 17, 0, 2048, 2049, 70000, 3, 100, 1024, 1024, 5, 1019, 64, 63, 1, 1, 2000]
     row_ptr = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
     nnz = int(row_ptr[-1])
     g = synth.Graph(len(lens), row_ptr, np.zeros(nnz, dtype=np.int32))
     rng = np.random.default_rng(6)
     s32 = (rng.standard_normal(nnz) * 3 + 50).astype(np.float32)
     ref = oracle.edge_softmax(g.row_ptr, s32.astype(np.float64))
-    p = B.ftc_edge_softmax(dev_graph(g), torch.from_numpy(s32).cuda())
+    dg = dev_graph(g)
+    win = B.ftc_build_windows(dg) if with_windows else None
+    p = B.ftc_edge_softmax(dg, win, torch.from_numpy(s32).cuda())
     assert rel_err(p, ref) < 1e-5
 
 
