@@ -87,6 +87,54 @@ def cpu_baseline(scale, seed, g=None):
                       f"same recipe as the workload, {dt:.1f} s"}
 
 
+def kernel_suite(tag, g, feat32, dtype, D, iters=20):
+    """Stand-alone SpMM / SDDMM timings on one graph (events on the launch stream), warm (back to
+    back) and cold (a 1 GiB buffer is overwritten between launches so that neither L2 nor the
+    memory-side cache holds X).  Returns a dict of ms and algorithmic GB/s."""
+    import numpy as np
+    import torch
+    from paper_2412_12218_amd import binding as B
+    dev = torch.device("cuda:0")
+    dg = B.Graph.from_numpy(g.row_ptr, g.col_idx)
+    win = B.ftc_build_windows(dg)
+    vals, _ = B.ftc_gcn_norm(dg, win)
+    X = torch.from_numpy(feat32).to(dtype).to(dev)
+    rinv = B.ftc_row_rnorm(X)
+    out = torch.empty((g.n, D), dtype=torch.float32, device=dev)
+    s_out = torch.empty(g.nnz, dtype=torch.float32, device=dev)
+    ws = B._workspace(B.lib().ftc_spmm_workspace_bytes(g.n, g.nnz, D), dev)
+    flush = torch.empty(1 << 28, dtype=torch.float32, device=dev)
+    sum_uniq = int(win.summary[0].item())
+    e = X.element_size()
+    rp = 4 * (g.n + 1)
+    nbytes = {"spmm": sum_uniq * D * e + g.nnz * 8 + g.n * D * 4 + rp,
+              "sddmm": sum_uniq * D * e + g.n * D * e + g.nnz * 8 + rp}
+    fns = {"spmm": lambda: B.ftc_spmm(dg, win, vals, X, out=out, ws=ws),
+           "sddmm": lambda: B.ftc_sddmm(dg, win, X, X, rinv, rinv, 1.0, out=s_out, ws=ws)}
+    res = {"graph": tag, "n": g.n, "nnz": g.nnz, "sum_uniq": sum_uniq, "D": D, "dtype": str(dtype)[6:]}
+    for op, fn in fns.items():
+        for _ in range(5):
+            fn()
+        for mode in ("warm", "cold"):
+            ts = []
+            for _ in range(iters):
+                if mode == "cold":
+                    flush.zero_()
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                fn()
+                b.record()
+                b.synchronize()
+                ts.append(a.elapsed_time(b))
+            ms = float(np.mean(ts))
+            res[f"{op}_{mode}_ms"] = ms
+            res[f"{op}_{mode}_min_ms"] = float(np.min(ts))
+            res[f"{op}_{mode}_GBs"] = nbytes[op] / (ms * 1e-3) / 1e9
+            res[f"{op}_{mode}_frac"] = nbytes[op] / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS
+        res[f"{op}_alg_bytes"] = nbytes[op]
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -94,6 +142,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--scale", type=int, default=20, help="R-MAT scale (20 = the benchmark workload)")
     ap.add_argument("--cpu-scale", type=int, default=20, help="R-MAT scale of the oracle's sample; 0 = skip")
+    ap.add_argument("--no-kernels", action="store_true", help="skip the stand-alone SpMM/SDDMM section")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives or sharding are part of it); "
@@ -208,6 +257,19 @@ def main():
         "alg_bytes_per_step": total_bytes,
         "input_generation_s": gen_s,
     }
+    # one plain device-to-device copy of known size (256 MiB read + 256 MiB written): the reference
+    # dispatch against which the profiler's FETCH_SIZE / WRITE_SIZE counters are scaled
+    calib_src = torch.ones(1 << 26, dtype=torch.float32, device=dev)
+    calib_dst = torch.empty_like(calib_src)
+    calib_dst.copy_(calib_src)
+    torch.cuda.synchronize()
+    del calib_src, calib_dst
+    if not args.no_kernels:
+        # the two largest graphs: stand-alone aggregation and edge-score kernels, fp32 output
+        k5 = kernel_suite("cfg5 R-MAT", g, synth.normal_features(g.n, 32, seed + 20), torch.float16, 32)
+        g4 = synth.config_graph(4) if args.scale == 20 else synth.config_graph(4, 2.0 ** (args.scale - 20))
+        k4 = kernel_suite("cfg4 SBM", g4, synth.uniform_features(g4.n, 64, 3 + 20), torch.bfloat16, 64)
+        out["kernels"] = [k4, k5]
     if args.cpu_scale > 0:
         out["cpu_baseline"] = cpu_baseline(args.cpu_scale, seed, g if args.cpu_scale == args.scale else None)
     print(json.dumps(out))

@@ -16,7 +16,7 @@
 namespace ftc {
 
 constexpr int SMALL_CAP = 4096;  // edges per window handled in LDS
-constexpr int BIG_SLOTS = 32;    // concurrent bitmap slots for large windows
+constexpr int BIG_SLOTS_MAX = 256;  // concurrent bitmap slots for large windows (one per CU)
 constexpr int BIG_THREADS = 1024;
 
 struct WinWorkspace {
@@ -24,8 +24,9 @@ struct WinWorkspace {
     int *big_list;    // [n_windows]
     int *big_count;   // [1]
     int *tmp_cols;    // [nnz]
-    uint32_t *bitmaps;  // [BIG_SLOTS][2 * words]: bits, then exclusive popcount prefix per word
+    uint32_t *bitmaps;  // [slots][2 * words]: bits, then exclusive popcount prefix per word
     size_t words;
+    int slots;
     size_t total;
 };
 
@@ -44,7 +45,10 @@ static WinWorkspace carve(void *ws, int n, int nnz, int n_windows)
     w.big_count = reinterpret_cast<int *>(take(sizeof(int)));
     w.tmp_cols = reinterpret_cast<int *>(take(sizeof(int) * static_cast<size_t>(nnz)));
     w.words = (static_cast<size_t>(n) + 31) / 32;
-    w.bitmaps = reinterpret_cast<uint32_t *>(take(sizeof(uint32_t) * 2 * w.words * BIG_SLOTS));
+    // two words of workspace per 32 columns and slot; at most 64 MiB in total, at least 8 slots
+    size_t slots = w.words ? (size_t(64) << 20) / (w.words * 2 * sizeof(uint32_t)) : BIG_SLOTS_MAX;
+    w.slots = static_cast<int>(slots < 8 ? 8 : (slots > BIG_SLOTS_MAX ? BIG_SLOTS_MAX : slots));
+    w.bitmaps = reinterpret_cast<uint32_t *>(take(sizeof(uint32_t) * 2 * w.words * w.slots));
     w.total = off;
     return w;
 }
@@ -299,7 +303,7 @@ int32_t launch_build_windows(const ftc_csr &g, ftc_windows &w, void *ws, size_t 
                        k.big_count);
     int32_t st = launch_status("build_windows small");
     if (st != FTC_OK) return st;
-    hipLaunchKernelGGL(win_big_kernel, dim3(BIG_SLOTS), dim3(BIG_THREADS), 0, s, g.n, g.row_ptr, g.col_idx,
+    hipLaunchKernelGGL(win_big_kernel, dim3(k.slots), dim3(BIG_THREADS), 0, s, g.n, g.row_ptr, g.col_idx,
                        w.blk_h, w.edge_to_col, k.uniq_count, k.tmp_cols, k.big_list, k.big_count, k.bitmaps,
                        static_cast<int>(k.words));
     st = launch_status("build_windows big");

@@ -56,6 +56,104 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(int n, const void *X,
     store_elem(Z, row * ldz + o, zdt, relu ? fmaxf(acc, 0.f) : acc);
 }
 
+// ------------------------------------------------------------------------------------------------
+// Matrix-core version for 16-bit inputs.  The update phase is a dense contraction, so it goes to
+// MFMA (v_mfma_f32_16x16x32_{f16,bf16}, fp32 accumulate).  A wave owns tiles of 16 rows of X:
+//   A operand  lane l holds X[row0 + l%16][k0 + (l/16)*8 .. +7]: one 16-byte global load, the four
+//              lane groups of a row cover 64 contiguous bytes, so X streams in fully used lines;
+//   B operand  lane l holds W[k0 + (l/16)*8 .. +7][n0 + l%16]: W is transposed once into LDS
+//              (k contiguous, zero padded to multiples of 32 x 16) and read as 16-byte words;
+//   C          lane l holds Z[row0 + (l/16)*4 + i][n0 + l%16], i = 0..3.
+// The kernel is bound by streaming X from HBM; W (at most 256 x 64) is read once per workgroup.
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bhalf8 __attribute__((ext_vector_type(8)));
+typedef float float4v __attribute__((ext_vector_type(4)));
+
+template <class T>
+__device__ __forceinline__ float4v mfma16(const uint4 &a, const uint4 &b, float4v c)
+{
+    if constexpr (std::is_same<T, F16>::value)
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, a), __builtin_bit_cast(half8, b), c,
+                                                      0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bhalf8, a), __builtin_bit_cast(bhalf8, b),
+                                                       c, 0, 0, 0);
+}
+
+constexpr int GEMM_RT = 2;  // 16-row tiles per wave iteration
+
+template <class T, int KS, int NT>  // KS = ceil(d_in / 32), NT = ceil(d_out / 16)
+__global__ __launch_bounds__(256) void gemm_mfma_kernel(int n, const uint16_t *__restrict__ X, int ldx, int d_in,
+                                                        const uint16_t *__restrict__ W, int d_out,
+                                                        void *__restrict__ Z, int ldz, int zdt, int relu,
+                                                        int n_tiles)
+{
+    constexpr int KP = KS * 32 + 8;  // padded k extent of a W^T row (keeps 16-byte alignment, spreads banks)
+    __shared__ __attribute__((aligned(16))) uint16_t Wt[NT * 16 * KP];
+    for (int t = threadIdx.x; t < NT * 16 * KS * 32; t += 256) {
+        const int nn = t / (KS * 32), k = t % (KS * 32);
+        Wt[nn * KP + k] = (nn < d_out && k < d_in) ? W[static_cast<size_t>(k) * d_out + nn] : uint16_t(0);
+    }
+    __syncthreads();
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int m = lane & 15, kb = lane >> 4;
+    // B operands stay in registers for the whole kernel
+    uint4 breg[KS][NT];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+            breg[ks][nt] = *reinterpret_cast<const uint4 *>(&Wt[(nt * 16 + m) * KP + ks * 32 + kb * 8]);
+
+    const int stride = gridDim.x * 4 * GEMM_RT;
+    for (int tile0 = (blockIdx.x * 4 + wave) * GEMM_RT; tile0 < n_tiles; tile0 += stride) {
+        uint4 a[GEMM_RT][KS];
+#pragma unroll
+        for (int rt = 0; rt < GEMM_RT; ++rt) {
+            const int row = min((tile0 + rt) * 16 + m, n - 1);  // clamped: the store is predicated
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                const int k = ks * 32 + kb * 8;
+                if (k < d_in) a[rt][ks] = *reinterpret_cast<const uint4 *>(X + static_cast<size_t>(row) * ldx + k);
+                else a[rt][ks] = make_uint4(0u, 0u, 0u, 0u);
+            }
+        }
+#pragma unroll
+        for (int rt = 0; rt < GEMM_RT; ++rt) {
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                float4v c = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) c = mfma16<T>(a[rt][ks], breg[ks][nt], c);
+                const int col = nt * 16 + m;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int row = (tile0 + rt) * 16 + kb * 4 + i;
+                    if (row < n && col < d_out)
+                        store_elem(Z, static_cast<int64_t>(row) * ldz + col, zdt, relu ? fmaxf(c[i], 0.f) : c[i]);
+                }
+            }
+        }
+    }
+}
+
+template <class T>
+static bool gemm_mfma_t(int n, const void *X, int ldx, int d_in, const void *W, int d_out, void *Z, int ldz,
+                        int zdt, int relu, hipStream_t s)
+{
+    const int ks = (d_in + 31) / 32, nt = (d_out + 15) / 16;
+    const int n_tiles = (n + 15) / 16;
+    int grid = (n_tiles + 4 * GEMM_RT - 1) / (4 * GEMM_RT);
+    if (grid > 256 * 8) grid = 256 * 8;
+    const uint16_t *x = static_cast<const uint16_t *>(X);
+    const uint16_t *w = static_cast<const uint16_t *>(W);
+#define FTC_G(K, N)                                                                                                 if (ks == K && nt == N) {                                                                                           hipLaunchKernelGGL((gemm_mfma_kernel<T, K, N>), dim3(grid), dim3(256), 0, s, n, x, ldx, d_in, w, d_out, Z,                            ldz, zdt, relu, n_tiles);                                                                    return true;                                                                                                }
+    FTC_G(1, 1) FTC_G(1, 2) FTC_G(2, 1) FTC_G(2, 2) FTC_G(4, 1) FTC_G(4, 2) FTC_G(4, 4) FTC_G(2, 4) FTC_G(1, 4)
+    FTC_G(8, 1) FTC_G(8, 2) FTC_G(8, 4) FTC_G(3, 1) FTC_G(3, 2) FTC_G(3, 4)
+#undef FTC_G
+    return false;
+}
+
 template <class T>
 static void gemm_t(int dpad, int n, const void *X, int ldx, int d_in, const void *W, int wdt, int d_out,
                    void *Z, int ldz, int zdt, int relu, hipStream_t s)
@@ -85,6 +183,12 @@ int32_t launch_gemm(int n, const void *X, int ldx, int dt, int d_in, const void 
     while (dpad < d_out) dpad *= 2;
     const bool fast = aligned16(X) && (static_cast<int64_t>(ldx) * elem_size(dt)) % 16 == 0 && d_in % v == 0 &&
                       dpad <= 64 && static_cast<int64_t>(d_in) * dpad <= 8192;
+    // 16-bit inputs: matrix cores (needs 16-byte row pieces of X)
+    if (dt != FTC_F32 && aligned16(X) && (static_cast<int64_t>(ldx) * 2) % 16 == 0 && d_in % 8 == 0) {
+        const bool done = dt == FTC_F16 ? gemm_mfma_t<F16>(n, X, ldx, d_in, W, d_out, Z, ldz, zdt, relu, s)
+                                        : gemm_mfma_t<BF16>(n, X, ldx, d_in, W, d_out, Z, ldz, zdt, relu, s);
+        if (done) return launch_status("update_gemm mfma");
+    }
     if (fast) {
         if (dt == FTC_F32) gemm_t<F32>(dpad, n, X, ldx, d_in, W, dt, d_out, Z, ldz, zdt, relu, s);
         else if (dt == FTC_F16) gemm_t<F16>(dpad, n, X, ldx, d_in, W, dt, d_out, Z, ldz, zdt, relu, s);
