@@ -74,6 +74,15 @@ static int32_t check_dense(const void *p, int ld, int dtype, int D, const char *
 
 using namespace ftc;
 
+// Windows with at least this many edges per condensed column (average reuse of a gathered row)
+// go to the matrix cores under FTC_PATH_AUTO; measured crossover of the fill sweep.
+static constexpr float SPMM_MFMA_REUSE = 4.0f;
+static constexpr float SDDMM_MFMA_REUSE = 2.0f;
+// Larger windows (hub rows) always stay on the edge-balanced vector kernels.
+static constexpr int MFMA_MAX_WINDOW_EDGES = 4096;
+
+static size_t flag_bytes(int32_t n) { return align_up(static_cast<size_t>((n + 15) / 16), 256); }
+
 #define FTC_TRY(expr)                   \
     do {                                \
         const int32_t st__ = (expr);    \
@@ -125,7 +134,7 @@ int32_t ftc_gcn_norm(const ftc_csr *g, const ftc_windows *w, float *vals, float 
 size_t ftc_spmm_workspace_bytes(int32_t n, int32_t nnz, int32_t D)
 {
     if (n < 0 || nnz < 0 || D < 1) return 0;
-    return spmm_seg_ws(nnz, D);
+    return spmm_seg_ws(nnz, D) + flag_bytes(n);
 }
 
 int32_t ftc_spmm(const ftc_csr *g, const ftc_windows *w, const float *vals, const void *X, int32_t ldx,
@@ -140,20 +149,33 @@ int32_t ftc_spmm(const ftc_csr *g, const ftc_windows *w, const float *vals, cons
     if (w) FTC_TRY(check_windows(g, w, "ftc_spmm", true));
     if (path != FTC_PATH_AUTO && path != FTC_PATH_VALU && path != FTC_PATH_MFMA)
         return fail(FTC_EINVAL, "ftc_spmm: unknown path %d", path);
-    if (path == FTC_PATH_MFMA) return fail(FTC_EUNSUPPORTED, "ftc_spmm: matrix-core path not available");
     int vec, lpr;
     const bool rows16 = aligned16(X) && aligned16(out) &&
                         (static_cast<int64_t>(ldx) * elem_size(x_dtype)) % 16 == 0 &&
                         (static_cast<int64_t>(ldo) * elem_size(out_dtype)) % 16 == 0;
-    if (w && g->nnz > 0 && rows16 && seg_shape(x_dtype, D, &vec, &lpr)) {
-        const size_t need = spmm_seg_ws(g->nnz, D);
+    const bool can_seg = w && g->nnz > 0 && rows16 && seg_shape(x_dtype, D, &vec, &lpr);
+    const bool can_mfma = can_seg && w->blk_h == 16 && mfma_shape_ok(x_dtype, D);
+    if (path == FTC_PATH_MFMA && !can_mfma)
+        return fail(FTC_EUNSUPPORTED,
+                    "ftc_spmm: the matrix-core path needs a window index with blk_h = 16, fp16/bf16 "
+                    "features with D a multiple of 8 (<= 256) and 16-byte aligned rows");
+    if (can_seg) {
+        const size_t need = ftc_spmm_workspace_bytes(g->n, g->nnz, D);
         if (!ws || ws_bytes < need)
             return fail(FTC_EWORKSPACE, "ftc_spmm: workspace of %zu bytes needed, %zu given", need,
                         ws ? ws_bytes : static_cast<size_t>(0));
         if (reinterpret_cast<uintptr_t>(ws) % 256 != 0)
             return fail(FTC_EALIGN, "ftc_spmm: workspace must be 256-byte aligned");
-        return launch_spmm_seg(*g, *w, vals, X, ldx, x_dtype, D, out, ldo, out_dtype, relu, ws,
-                               static_cast<hipStream_t>(stream));
+        hipStream_t hs = static_cast<hipStream_t>(stream);
+        uint8_t *flags = nullptr;
+        if (can_mfma && path != FTC_PATH_VALU) {
+            flags = reinterpret_cast<uint8_t *>(static_cast<char *>(ws) + spmm_seg_ws(g->nnz, D));
+            FTC_TRY(launch_classify(*g, *w, path == FTC_PATH_MFMA ? 0.f : SPMM_MFMA_REUSE, MFMA_MAX_WINDOW_EDGES,
+                                    flags, hs));
+        }
+        FTC_TRY(launch_spmm_seg(*g, *w, vals, X, ldx, x_dtype, D, out, ldo, out_dtype, relu, ws, flags, hs));
+        if (flags) return launch_spmm_mfma(*g, *w, vals, X, ldx, x_dtype, D, out, ldo, out_dtype, relu, flags, hs);
+        return FTC_OK;
     }
     return launch_spmm_rows(*g, vals, X, ldx, x_dtype, D, out, ldo, out_dtype, relu,
                             static_cast<hipStream_t>(stream));
@@ -161,15 +183,14 @@ int32_t ftc_spmm(const ftc_csr *g, const ftc_windows *w, const float *vals, cons
 
 size_t ftc_sddmm_workspace_bytes(int32_t n, int32_t nnz, int32_t D)
 {
-    (void)n; (void)nnz; (void)D;
-    return 0;
+    if (n < 0 || nnz < 0 || D < 1) return 0;
+    return flag_bytes(n);
 }
 
 int32_t ftc_sddmm(const ftc_csr *g, const ftc_windows *w, const void *X, const void *Y, int32_t ld,
                   int32_t dtype, int32_t D, const float *row_scale, const float *col_scale, float alpha,
                   float *edge_out, int32_t path, void *ws, size_t ws_bytes, void *stream)
 {
-    (void)ws; (void)ws_bytes;
     FTC_TRY(check_csr(g, "ftc_sddmm"));
     if (g->n == 0 || g->nnz == 0) return FTC_OK;
     FTC_TRY(check_dense(X, ld, dtype, D, "ftc_sddmm", "X"));
@@ -178,12 +199,31 @@ int32_t ftc_sddmm(const ftc_csr *g, const ftc_windows *w, const void *X, const v
     if (w) FTC_TRY(check_windows(g, w, "ftc_sddmm", true));
     if (path != FTC_PATH_AUTO && path != FTC_PATH_VALU && path != FTC_PATH_MFMA)
         return fail(FTC_EINVAL, "ftc_sddmm: unknown path %d", path);
-    if (path == FTC_PATH_MFMA) return fail(FTC_EUNSUPPORTED, "ftc_sddmm: matrix-core path not available");
     int vec, lpr;
-    if (w && aligned16(X) && aligned16(Y) && (static_cast<int64_t>(ld) * elem_size(dtype)) % 16 == 0 &&
-        seg_shape(dtype, D, &vec, &lpr))
-        return launch_sddmm_edges(*g, *w, X, Y, ld, dtype, D, row_scale, col_scale, alpha, edge_out,
-                                  static_cast<hipStream_t>(stream));
+    const bool can_edges = w && aligned16(X) && aligned16(Y) &&
+                           (static_cast<int64_t>(ld) * elem_size(dtype)) % 16 == 0 && seg_shape(dtype, D, &vec, &lpr);
+    const bool can_mfma = can_edges && w->blk_h == 16 && mfma_shape_ok(dtype, D);
+    if (path == FTC_PATH_MFMA && !can_mfma)
+        return fail(FTC_EUNSUPPORTED,
+                    "ftc_sddmm: the matrix-core path needs a window index with blk_h = 16, fp16/bf16 "
+                    "features with D a multiple of 8 (<= 256) and 16-byte aligned rows");
+    if (can_edges) {
+        hipStream_t hs = static_cast<hipStream_t>(stream);
+        uint8_t *flags = nullptr;
+        if (can_mfma && path != FTC_PATH_VALU) {
+            const size_t need = flag_bytes(g->n);
+            if (!ws || ws_bytes < need)
+                return fail(FTC_EWORKSPACE, "ftc_sddmm: workspace of %zu bytes needed, %zu given", need,
+                            ws ? ws_bytes : static_cast<size_t>(0));
+            flags = static_cast<uint8_t *>(ws);
+            FTC_TRY(launch_classify(*g, *w, path == FTC_PATH_MFMA ? 0.f : SDDMM_MFMA_REUSE, MFMA_MAX_WINDOW_EDGES,
+                                    flags, hs));
+        }
+        FTC_TRY(launch_sddmm_edges(*g, *w, X, Y, ld, dtype, D, row_scale, col_scale, alpha, edge_out, flags, hs));
+        if (flags)
+            return launch_sddmm_mfma(*g, *w, X, Y, ld, dtype, D, row_scale, col_scale, alpha, edge_out, flags, hs);
+        return FTC_OK;
+    }
     return launch_sddmm_rows(*g, X, Y, ld, dtype, D, row_scale, col_scale, alpha, edge_out,
                              static_cast<hipStream_t>(stream));
 }

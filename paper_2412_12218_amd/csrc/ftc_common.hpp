@@ -37,9 +37,19 @@ int32_t launch_validate(const ftc_csr &g, int32_t *flag, hipStream_t s);
 bool seg_shape(int dtype, int D, int *vec, int *lpr);
 size_t spmm_seg_ws(int nnz, int D);
 int32_t launch_spmm_seg(const ftc_csr &g, const ftc_windows &w, const float *vals, const void *X, int ldx,
-                        int xdt, int D, void *out, int ldo, int odt, int relu, void *ws, hipStream_t s);
+                        int xdt, int D, void *out, int ldo, int odt, int relu, void *ws, const uint8_t *dense,
+                        hipStream_t s);
 int32_t launch_sddmm_edges(const ftc_csr &g, const ftc_windows &w, const void *X, const void *Y, int ld, int dt,
-                           int D, const float *rs, const float *cs, float alpha, float *out, hipStream_t s);
+                           int D, const float *rs, const float *cs, float alpha, float *out, const uint8_t *dense,
+                           hipStream_t s);
+bool mfma_shape_ok(int dtype, int D);
+int32_t launch_classify(const ftc_csr &g, const ftc_windows &w, float reuse, int max_edges, uint8_t *flags,
+                        hipStream_t s);
+int32_t launch_sddmm_mfma(const ftc_csr &g, const ftc_windows &w, const void *X, const void *Y, int ld, int dt,
+                          int D, const float *rs, const float *cs, float alpha, float *out, const uint8_t *flags,
+                          hipStream_t s);
+int32_t launch_spmm_mfma(const ftc_csr &g, const ftc_windows &w, const float *vals, const void *X, int ldx, int dt,
+                         int D, void *out, int ldo, int odt, int relu, const uint8_t *flags, hipStream_t s);
 size_t build_windows_ws(int n, int nnz, int blk_h, int blk_w);
 int32_t launch_build_windows(const ftc_csr &g, ftc_windows &w, void *ws, size_t ws_bytes, hipStream_t s);
 

@@ -42,7 +42,8 @@ __global__ __launch_bounds__(256) void sddmm_edges_kernel(int nnz, int n_ranges,
                                                           const void *__restrict__ Y, int ld, int D,
                                                           const float *__restrict__ rs,
                                                           const float *__restrict__ cs, float alpha,
-                                                          float *__restrict__ out)
+                                                          float *__restrict__ out,
+                                                          const uint8_t *__restrict__ dense)
 {
     constexpr int NG = 64 / LPR;
     constexpr int RUN = SD_R / NG;
@@ -65,8 +66,10 @@ __global__ __launch_bounds__(256) void sddmm_edges_kernel(int nnz, int n_ranges,
         const int i = j * 64 + lane;
         if (i < n_valid) {
             const int p = i + i / RUN;
-            s_col[p] = col_idx[base + i];
-            s_row[p] = edge_to_row[base + i];
+            const int er = edge_to_row[base + i];
+            const bool skip = dense && dense[er >> 4];  // that window goes to the matrix cores
+            s_col[p] = skip ? -1 : col_idx[base + i];
+            s_row[p] = skip ? -1 : er;
         }
     }
     __syncthreads();
@@ -120,8 +123,9 @@ __global__ __launch_bounds__(256) void sddmm_edges_kernel(int nnz, int n_ranges,
 #pragma unroll
     for (int j = 0; j < SD_R / 64; ++j) {
         const int i = j * 64 + lane;
-        if (i < n_valid) {
-            const int p = i + i / RUN;
+        const int pp = i + i / RUN;
+        if (i < n_valid && s_col[pp] >= 0) {
+            const int p = pp;
             const float scale = alpha * (rs ? rs[s_row[p]] : 1.f) * (cs ? cs[s_col[p]] : 1.f);
             out[base + i] = scale * s_dot[p];
         }
@@ -131,12 +135,12 @@ __global__ __launch_bounds__(256) void sddmm_edges_kernel(int nnz, int n_ranges,
 template <class T>
 static void launch_edges_t(int vec, int lpr, unsigned grid, hipStream_t s, int nnz, int n_ranges,
                            const ftc_csr &g, const int *e2r, const void *X, const void *Y, int ld, int D,
-                           const float *rs, const float *cs, float alpha, float *out)
+                           const float *rs, const float *cs, float alpha, float *out, const uint8_t *dense)
 {
     constexpr int VM = T::VEC;
 #define FTC_SD(V, L)                                                                                         \
     hipLaunchKernelGGL((sddmm_edges_kernel<T, V, L>), dim3(grid), dim3(256), 0, s, nnz, n_ranges, g.col_idx, \
-                       e2r, X, Y, ld, D, rs, cs, alpha, out)
+                       e2r, X, Y, ld, D, rs, cs, alpha, out, dense)
     if (vec == VM) {
         if (lpr == 4) FTC_SD(VM, 4);
         else if (lpr == 8) FTC_SD(VM, 8);
@@ -152,7 +156,8 @@ static void launch_edges_t(int vec, int lpr, unsigned grid, hipStream_t s, int n
 
 // Caller has checked: window index present, seg_shape() accepts (dt, D), rows 16-byte aligned.
 int32_t launch_sddmm_edges(const ftc_csr &g, const ftc_windows &w, const void *X, const void *Y, int ld, int dt,
-                           int D, const float *rs, const float *cs, float alpha, float *out, hipStream_t s)
+                           int D, const float *rs, const float *cs, float alpha, float *out, const uint8_t *dense,
+                           hipStream_t s)
 {
     if (g.nnz == 0) return FTC_OK;
     int vec = 0, lpr = 0;
@@ -160,12 +165,12 @@ int32_t launch_sddmm_edges(const ftc_csr &g, const ftc_windows &w, const void *X
     const int n_ranges = (g.nnz + SD_R - 1) / SD_R;
     const unsigned grid = static_cast<unsigned>((n_ranges + 3) / 4);
     if (dt == FTC_F32)
-        launch_edges_t<F32>(vec, lpr, grid, s, g.nnz, n_ranges, g, w.edge_to_row, X, Y, ld, D, rs, cs, alpha, out);
+        launch_edges_t<F32>(vec, lpr, grid, s, g.nnz, n_ranges, g, w.edge_to_row, X, Y, ld, D, rs, cs, alpha, out, dense);
     else if (dt == FTC_F16)
-        launch_edges_t<F16>(vec, lpr, grid, s, g.nnz, n_ranges, g, w.edge_to_row, X, Y, ld, D, rs, cs, alpha, out);
+        launch_edges_t<F16>(vec, lpr, grid, s, g.nnz, n_ranges, g, w.edge_to_row, X, Y, ld, D, rs, cs, alpha, out, dense);
     else
         launch_edges_t<BF16>(vec, lpr, grid, s, g.nnz, n_ranges, g, w.edge_to_row, X, Y, ld, D, rs, cs, alpha,
-                             out);
+                             out, dense);
     return launch_status("sddmm_edges");
 }
 

@@ -62,7 +62,8 @@ __global__ __launch_bounds__(256) void spmm_seg_kernel(int nnz, int n_ranges, co
                                                        const float *__restrict__ vals,
                                                        const void *__restrict__ X, int ldx, int D,
                                                        void *__restrict__ out, int ldo, int odt, int relu,
-                                                       float *__restrict__ carry, int *__restrict__ carry_tail_row)
+                                                       float *__restrict__ carry, int *__restrict__ carry_tail_row,
+                                                       const uint8_t *__restrict__ dense)
 {
     constexpr int NG = 64 / LPR;      // groups per wave
     constexpr int RUN = SEG_R / NG;   // edges per group
@@ -89,8 +90,10 @@ __global__ __launch_bounds__(256) void spmm_seg_kernel(int nnz, int n_ranges, co
         const int i = j * 64 + lane;
         if (i < n_valid) {
             const int p = i + i / RUN;
-            s_col[p] = col_idx[base + i];
-            s_row[p] = edge_to_row[base + i];
+            const int er = edge_to_row[base + i];
+            // edges of windows that go to the matrix cores are skipped here (column -1)
+            s_col[p] = (dense && dense[er >> 4]) ? -1 : col_idx[base + i];
+            s_row[p] = er;
             s_val[p] = vals ? vals[base + i] : 1.f;
         }
     }
@@ -109,7 +112,7 @@ __global__ __launch_bounds__(256) void spmm_seg_kernel(int nnz, int n_ranges, co
     int head_row = -1, cur = -1;
 
     auto direct_store = [&](int row) {
-        if (live) {
+        if (live && !(dense && dense[row >> 4])) {
             float o[VEC];
 #pragma unroll
             for (int j = 0; j < VEC; ++j) o[j] = relu ? fmaxf(acc[j], 0.f) : acc[j];
@@ -136,7 +139,7 @@ __global__ __launch_bounds__(256) void spmm_seg_kernel(int nnz, int n_ranges, co
             }
 #pragma unroll
             for (int k = 0; k < SEG_B; ++k) {
-                if (r[k] >= 0 && live) load_raw<T, VEC>(X, static_cast<int64_t>(c[k]) * ldx + sub * VEC, x[k]);
+                if (r[k] >= 0 && c[k] >= 0 && live) load_raw<T, VEC>(X, static_cast<int64_t>(c[k]) * ldx + sub * VEC, x[k]);
                 else zero_raw(x[k]);
             }
 #pragma unroll
@@ -210,7 +213,7 @@ __global__ __launch_bounds__(256) void spmm_seg_kernel(int nnz, int n_ranges, co
                     run += part[(2 * q) * DP + d];
                     if (s_meta[wave][1][q]) {
                         if (from_outside) carry[(static_cast<size_t>(v) * 2) * DP + d] = run;
-                        else if (d < D)
+                        else if (d < D && !(dense && dense[run_row >> 4]))
                             store_elem(out, static_cast<int64_t>(run_row) * ldo + d, odt,
                                        relu ? fmaxf(run, 0.f) : run);
                         run_row = -1;
@@ -238,13 +241,13 @@ __global__ __launch_bounds__(256) void spmm_seg_fixup_kernel(int n, int n_ranges
                                                              const float *__restrict__ carry,
                                                              const int *__restrict__ carry_tail_row, int DP,
                                                              int D, void *__restrict__ out, int ldo, int odt,
-                                                             int relu)
+                                                             int relu, const uint8_t *__restrict__ dense)
 {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int v = blockIdx.x * 4 + wave;
     if (v < n_ranges) {
         const int r = carry_tail_row[v];
-        if (r >= 0) {
+        if (r >= 0 && !(dense && dense[r >> 4])) {
             const int last = (row_ptr[r + 1] - 1) / SEG_R;  // wave range holding the row's final edge
             for (int d = lane; d < D; d += 64) {
                 float sum = carry[(static_cast<size_t>(v) * 2 + 1) * DP + d];
@@ -254,19 +257,19 @@ __global__ __launch_bounds__(256) void spmm_seg_fixup_kernel(int n, int n_ranges
         }
     }
     const int64_t row = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
-    if (row < n && row_ptr[row] == row_ptr[row + 1])
+    if (row < n && row_ptr[row] == row_ptr[row + 1] && !(dense && dense[row >> 4]))
         for (int d = 0; d < D; ++d) store_elem(out, row * ldo + d, odt, 0.f);
 }
 
 template <class T>
 static void launch_seg_t(int vec, int lpr, unsigned grid, hipStream_t s, int nnz, int n_ranges,
                          const ftc_csr &g, const int *e2r, const float *vals, const void *X, int ldx, int D,
-                         void *out, int ldo, int odt, int relu, float *carry, int *tail_row)
+                         void *out, int ldo, int odt, int relu, float *carry, int *tail_row, const uint8_t *dense)
 {
     constexpr int VM = T::VEC;
 #define FTC_SEG(V, L)                                                                                     \
     hipLaunchKernelGGL((spmm_seg_kernel<T, V, L>), dim3(grid), dim3(256), 0, s, nnz, n_ranges, g.col_idx, \
-                       e2r, vals, X, ldx, D, out, ldo, odt, relu, carry, tail_row)
+                       e2r, vals, X, ldx, D, out, ldo, odt, relu, carry, tail_row, dense)
     if (vec == VM) {
         if (lpr == 4) FTC_SEG(VM, 4);
         else if (lpr == 8) FTC_SEG(VM, 8);
@@ -283,7 +286,8 @@ static void launch_seg_t(int vec, int lpr, unsigned grid, hipStream_t s, int nnz
 // Caller has checked: window index present, seg_shape() accepts (xdt, D), X and out rows 16-byte
 // aligned, workspace of spmm_seg_ws() bytes.
 int32_t launch_spmm_seg(const ftc_csr &g, const ftc_windows &w, const float *vals, const void *X, int ldx,
-                        int xdt, int D, void *out, int ldo, int odt, int relu, void *ws, hipStream_t s)
+                        int xdt, int D, void *out, int ldo, int odt, int relu, void *ws, const uint8_t *dense,
+                        hipStream_t s)
 {
     int vec = 0, lpr = 0;
     seg_shape(xdt, D, &vec, &lpr);
@@ -296,13 +300,13 @@ int32_t launch_spmm_seg(const ftc_csr &g, const ftc_windows &w, const float *val
         const unsigned grid = static_cast<unsigned>((n_ranges + 3) / 4);
         if (xdt == FTC_F32)
             launch_seg_t<F32>(vec, lpr, grid, s, g.nnz, n_ranges, g, w.edge_to_row, vals, X, ldx, D, out, ldo,
-                              odt, relu, carry, tail_row);
+                              odt, relu, carry, tail_row, dense);
         else if (xdt == FTC_F16)
             launch_seg_t<F16>(vec, lpr, grid, s, g.nnz, n_ranges, g, w.edge_to_row, vals, X, ldx, D, out, ldo,
-                              odt, relu, carry, tail_row);
+                              odt, relu, carry, tail_row, dense);
         else
             launch_seg_t<BF16>(vec, lpr, grid, s, g.nnz, n_ranges, g, w.edge_to_row, vals, X, ldx, D, out, ldo,
-                               odt, relu, carry, tail_row);
+                               odt, relu, carry, tail_row, dense);
         const int32_t st = launch_status("spmm_seg");
         if (st != FTC_OK) return st;
     }
@@ -310,7 +314,7 @@ int32_t launch_spmm_seg(const ftc_csr &g, const ftc_windows &w, const float *val
     const int64_t blocks_ranges = (n_ranges + 3) / 4;
     const unsigned grid2 = static_cast<unsigned>(blocks_rows > blocks_ranges ? blocks_rows : blocks_ranges);
     hipLaunchKernelGGL(spmm_seg_fixup_kernel, dim3(grid2), dim3(256), 0, s, g.n, n_ranges, g.row_ptr, carry,
-                       tail_row, dp, D, out, ldo, odt, relu);
+                       tail_row, dp, D, out, ldo, odt, relu, dense);
     return launch_status("spmm_seg fixup");
 }
 

@@ -36,6 +36,21 @@ def hub_graph():
     return synth.Graph(n, row_ptr, col, "hub")
 
 
+def mixed_density_graph():
+    """4096 nodes: windows of the first half draw their columns from a pool of 48 (about ten
+    edges per condensed column: matrix-core territory), the second half is Erdos-Renyi sparse."""
+    n = 4096
+    dense = synth.fill_controlled(n, pool=48, k=30, seed=21)
+    sparse = synth.erdos_renyi(n, 4 * n, seed=22)
+    rows = []
+    for r in range(n):
+        src = dense if r < n // 2 else sparse
+        rows.append(src.col_idx[src.row_ptr[r]:src.row_ptr[r + 1]])
+    row_ptr = np.zeros(n + 1, dtype=np.int32)
+    row_ptr[1:] = np.cumsum([len(r) for r in rows])
+    return synth.Graph(n, row_ptr, np.concatenate(rows).astype(np.int32), "mixed")
+
+
 @pytest.fixture(scope="module")
 def graphs():
     gs = {
@@ -45,11 +60,12 @@ def graphs():
         "cfg4s": synth.config_graph(4, 0.03),
         "cfg5s": synth.config_graph(5, 1 / 32),
         "hub": hub_graph(),
+        "mixed": mixed_density_graph(),
     }
     return gs
 
 
-GRAPH_NAMES = ["cfg1", "cfg2s", "cfg3s", "cfg4s", "cfg5s", "hub"]
+GRAPH_NAMES = ["cfg1", "cfg2s", "cfg3s", "cfg4s", "cfg5s", "hub", "mixed"]
 
 
 # ------------------------------------------------------------------ validation kernel
@@ -165,6 +181,39 @@ def test_spmm_epilogues(oracle, graphs, out_dtype):
     assert run_spmm(oracle, g, F32, 16, relu=True) < 1e-5
 
 
+@pytest.mark.parametrize("name", ["mixed", "cfg1", "cfg5s", "hub", "cfg4s"])
+@pytest.mark.parametrize("dtype,D", [(F16, 32), (BF16, 64), (F16, 16), (F16, 8), (F16, 128), (BF16, 24), (F16, 256)])
+@pytest.mark.parametrize("path", [B.FTC_PATH_MFMA, B.FTC_PATH_VALU])
+def test_spmm_paths(oracle, graphs, name, dtype, D, path):
+    """Matrix-core condensed-tile path forced on every eligible window, and the vector path forced
+    on every window, against the oracle."""
+    g = graphs[name]
+    say(f"spmm path={path} {name} {dtype} D={D}")
+    err = run_spmm(oracle, g, dtype, D, path=path)
+    say(f"  err {err:.3e}")
+    assert err < TOL[dtype]
+    if name == "mixed":
+        assert run_spmm(oracle, g, dtype, D, path=path, relu=True, out_dtype=F16) < TOL[dtype]
+
+
+def test_mfma_path_rejected_where_it_cannot_run(graphs):
+    g = graphs["cfg1"]
+    dg = dev_graph(g)
+    win = B.ftc_build_windows(dg)
+    X = torch.zeros((g.n, 16), dtype=F32, device="cuda")
+    with pytest.raises(B.FtcError) as ei:
+        B.ftc_spmm(dg, win, None, X, path=B.FTC_PATH_MFMA)
+    assert ei.value.code == B.FTC_EUNSUPPORTED
+    with pytest.raises(B.FtcError) as ei:
+        B.ftc_sddmm(dg, win, X, X, path=B.FTC_PATH_MFMA)
+    assert ei.value.code == B.FTC_EUNSUPPORTED
+    win8 = B.ftc_build_windows(dg, 8, 4)
+    Xh = torch.zeros((g.n, 16), dtype=F16, device="cuda")
+    with pytest.raises(B.FtcError):
+        B.ftc_spmm(dg, win8, None, Xh, path=B.FTC_PATH_MFMA)
+    B.ftc_spmm(dg, win8, None, Xh)      # the default path still works with other window heights
+
+
 # ------------------------------------------------------------------ SDDMM
 def run_sddmm(oracle, g, dtype, D, *, scales=True, with_windows=True, same=False, seed=1, pad=0,
               path=B.FTC_PATH_AUTO):
@@ -201,6 +250,19 @@ def test_sddmm(oracle, graphs, name, dtype, D, with_windows):
     err = run_sddmm(oracle, g, dtype, D, with_windows=with_windows)
     say(f"  err {err:.3e}")
     assert err < TOL[dtype]
+
+
+@pytest.mark.parametrize("name", ["mixed", "cfg1", "cfg5s", "hub", "cfg4s"])
+@pytest.mark.parametrize("dtype,D", [(F16, 32), (BF16, 64), (F16, 16), (F16, 8), (F16, 128), (BF16, 24), (F16, 256)])
+@pytest.mark.parametrize("path", [B.FTC_PATH_MFMA, B.FTC_PATH_VALU])
+def test_sddmm_paths(oracle, graphs, name, dtype, D, path):
+    g = graphs[name]
+    say(f"sddmm path={path} {name} {dtype} D={D}")
+    err = run_sddmm(oracle, g, dtype, D, path=path)
+    say(f"  err {err:.3e}")
+    assert err < TOL[dtype]
+    if name == "mixed":
+        assert run_sddmm(oracle, g, dtype, D, path=path, scales=False, same=True) < TOL[dtype]
 
 
 @pytest.mark.parametrize("dtype,D,pad", [(F16, 24, 0), (F16, 5, 0), (F32, 7, 1), (BF16, 40, 8), (F16, 32, 32)])
