@@ -135,6 +135,46 @@ def kernel_suite(tag, g, feat32, dtype, D, iters=20):
     return res
 
 
+def density_sweep(n=1 << 18, k=32, dims=(32, 64, 128, 256), iters=20):
+    """Vector path vs matrix-core path on graphs whose 16-row windows have a controlled reuse of
+    gathered rows (edges per condensed column = 16 k / pool).  Prints one JSON line per point."""
+    import numpy as np
+    import torch
+    import synth
+    from paper_2412_12218_amd import binding as B
+    dev = torch.device("cuda:0")
+
+    def avg_ms(fn):
+        for _ in range(3):
+            fn()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(iters):
+            fn()
+        b.record()
+        b.synchronize()
+        return a.elapsed_time(b) / iters
+
+    for pool in (512, 384, 256, 192, 128, 96, 64, 48, 32):
+        g = synth.fill_controlled(n, pool, k, seed=5)
+        dg = B.Graph.from_numpy(g.row_ptr, g.col_idx)
+        win = B.ftc_build_windows(dg)
+        sum_uniq = int(win.summary[0].item())
+        vals = torch.rand(g.nnz, dtype=torch.float32, device=dev)
+        for D in dims:
+            X = torch.from_numpy(synth.normal_features(g.n, D, 6)).to(torch.float16).to(dev)
+            out = torch.empty((g.n, D), dtype=torch.float32, device=dev)
+            s_out = torch.empty(g.nnz, dtype=torch.float32, device=dev)
+            ws = B._workspace(B.lib().ftc_spmm_workspace_bytes(g.n, g.nnz, D), dev)
+            rec = {"pool": pool, "reuse": g.nnz / sum_uniq, "tile_fill": g.nnz / (16.0 * sum_uniq), "D": D,
+                   "nnz": g.nnz}
+            for name, path in (("valu", B.FTC_PATH_VALU), ("mfma", B.FTC_PATH_MFMA)):
+                rec[f"spmm_{name}_ms"] = avg_ms(lambda: B.ftc_spmm(dg, win, vals, X, out=out, path=path, ws=ws))
+                rec[f"sddmm_{name}_ms"] = avg_ms(lambda: B.ftc_sddmm(dg, win, X, X, None, None, 1.0, out=s_out,
+                                                                      path=path, ws=ws))
+            print(json.dumps(rec), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -143,6 +183,8 @@ def main():
     ap.add_argument("--scale", type=int, default=20, help="R-MAT scale (20 = the benchmark workload)")
     ap.add_argument("--cpu-scale", type=int, default=20, help="R-MAT scale of the oracle's sample; 0 = skip")
     ap.add_argument("--no-kernels", action="store_true", help="skip the stand-alone SpMM/SDDMM section")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the benchmark: vector vs matrix-core path over window density")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives or sharding are part of it); "
@@ -156,6 +198,9 @@ def main():
     from paper_2412_12218_amd.models import HotPath
 
     B.lib()
+    if args.sweep:
+        density_sweep()
+        return
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     seed = synth.CONFIGS[5]["seed"]

@@ -74,10 +74,14 @@ static int32_t check_dense(const void *p, int ld, int dtype, int D, const char *
 
 using namespace ftc;
 
-// Windows with at least this many edges per condensed column (average reuse of a gathered row)
-// go to the matrix cores under FTC_PATH_AUTO; measured crossover of the fill sweep.
-static constexpr float SPMM_MFMA_REUSE = 4.0f;
-static constexpr float SDDMM_MFMA_REUSE = 2.0f;
+// FTC_PATH_AUTO sends a window to the matrix cores when it has at least this many edges per
+// condensed column (average reuse of a gathered row).  Values are the measured crossovers of the
+// density sweep (bench.py --sweep, fp16, 2^18 nodes, 8.4 M edges): the vector path wins at every
+// density up to completely full tiles for D <= 128 (both operations) and for SpMM at D = 256;
+// SDDMM at D = 256 crosses over between 2.3 and 2.8 edges per condensed column.  A negative
+// value means "never".
+static float spmm_mfma_reuse(int D) { (void)D; return -1.f; }
+static float sddmm_mfma_reuse(int D) { return D >= 256 ? 2.6f : -1.f; }
 // Larger windows (hub rows) always stay on the edge-balanced vector kernels.
 static constexpr int MFMA_MAX_WINDOW_EDGES = 4096;
 
@@ -168,10 +172,10 @@ int32_t ftc_spmm(const ftc_csr *g, const ftc_windows *w, const float *vals, cons
             return fail(FTC_EALIGN, "ftc_spmm: workspace must be 256-byte aligned");
         hipStream_t hs = static_cast<hipStream_t>(stream);
         uint8_t *flags = nullptr;
-        if (can_mfma && path != FTC_PATH_VALU) {
+        const float reuse = path == FTC_PATH_MFMA ? 0.f : spmm_mfma_reuse(D);
+        if (can_mfma && path != FTC_PATH_VALU && reuse >= 0.f) {
             flags = reinterpret_cast<uint8_t *>(static_cast<char *>(ws) + spmm_seg_ws(g->nnz, D));
-            FTC_TRY(launch_classify(*g, *w, path == FTC_PATH_MFMA ? 0.f : SPMM_MFMA_REUSE, MFMA_MAX_WINDOW_EDGES,
-                                    flags, hs));
+            FTC_TRY(launch_classify(*g, *w, reuse, MFMA_MAX_WINDOW_EDGES, flags, hs));
         }
         FTC_TRY(launch_spmm_seg(*g, *w, vals, X, ldx, x_dtype, D, out, ldo, out_dtype, relu, ws, flags, hs));
         if (flags) return launch_spmm_mfma(*g, *w, vals, X, ldx, x_dtype, D, out, ldo, out_dtype, relu, flags, hs);
@@ -210,14 +214,14 @@ int32_t ftc_sddmm(const ftc_csr *g, const ftc_windows *w, const void *X, const v
     if (can_edges) {
         hipStream_t hs = static_cast<hipStream_t>(stream);
         uint8_t *flags = nullptr;
-        if (can_mfma && path != FTC_PATH_VALU) {
+        const float reuse = path == FTC_PATH_MFMA ? 0.f : sddmm_mfma_reuse(D);
+        if (can_mfma && path != FTC_PATH_VALU && reuse >= 0.f) {
             const size_t need = flag_bytes(g->n);
             if (!ws || ws_bytes < need)
                 return fail(FTC_EWORKSPACE, "ftc_sddmm: workspace of %zu bytes needed, %zu given", need,
                             ws ? ws_bytes : static_cast<size_t>(0));
             flags = static_cast<uint8_t *>(ws);
-            FTC_TRY(launch_classify(*g, *w, path == FTC_PATH_MFMA ? 0.f : SDDMM_MFMA_REUSE, MFMA_MAX_WINDOW_EDGES,
-                                    flags, hs));
+            FTC_TRY(launch_classify(*g, *w, reuse, MFMA_MAX_WINDOW_EDGES, flags, hs));
         }
         FTC_TRY(launch_sddmm_edges(*g, *w, X, Y, ld, dtype, D, row_scale, col_scale, alpha, edge_out, flags, hs));
         if (flags)

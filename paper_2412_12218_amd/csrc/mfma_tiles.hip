@@ -61,7 +61,7 @@ int32_t launch_classify(const ftc_csr &g, const ftc_windows &w, float reuse, int
 }
 
 // ------------------------------------------------------------------------------------------------
-constexpr int SDM_CH = 256;  // condensed columns per LDS chunk
+constexpr int SDM_CH = 64;   // condensed columns per LDS chunk (small: LDS per window bounds occupancy)
 constexpr int SDM_NU = 4;    // 16-column tiles gathered before their MFMAs are issued
 
 template <class T, int KS>  // KS = ceil(D / 32)

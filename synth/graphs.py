@@ -153,13 +153,15 @@ def fill_controlled(n, pool, k, seed, blk_h=16, self_loops=False):
     rng = np.random.default_rng(seed)
     n_win = (n + blk_h - 1) // blk_h
     rows_out, cols_out = [], []
+    k = min(k, pool)
     for w in range(n_win):
         cols = rng.choice(n, size=pool, replace=False)
         r0, r1 = w * blk_h, min(n, (w + 1) * blk_h)
-        for r in range(r0, r1):
-            pick = rng.choice(pool, size=min(k, pool), replace=False)
-            rows_out.append(np.full(pick.size, r, dtype=np.int64))
-            cols_out.append(cols[pick])
+        # every row of the window: k distinct members of the pool (k smallest of a random key)
+        pick = np.argpartition(rng.random((r1 - r0, pool)), k - 1, axis=1)[:, :k] if k < pool else \
+            np.tile(np.arange(pool), (r1 - r0, 1))
+        rows_out.append(np.repeat(np.arange(r0, r1, dtype=np.int64), k))
+        cols_out.append(cols[pick].reshape(-1))
     rows = np.concatenate(rows_out)
     cols = np.concatenate(cols_out)
     if self_loops:

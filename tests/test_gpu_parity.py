@@ -254,7 +254,7 @@ def test_sddmm(oracle, graphs, name, dtype, D, with_windows):
 
 @pytest.mark.parametrize("name", ["mixed", "cfg1", "cfg5s", "hub", "cfg4s"])
 @pytest.mark.parametrize("dtype,D", [(F16, 32), (BF16, 64), (F16, 16), (F16, 8), (F16, 128), (BF16, 24), (F16, 256)])
-@pytest.mark.parametrize("path", [B.FTC_PATH_MFMA, B.FTC_PATH_VALU])
+@pytest.mark.parametrize("path", [B.FTC_PATH_MFMA, B.FTC_PATH_VALU, B.FTC_PATH_AUTO])
 def test_sddmm_paths(oracle, graphs, name, dtype, D, path):
     g = graphs[name]
     say(f"sddmm path={path} {name} {dtype} D={D}")
