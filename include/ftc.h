@@ -190,7 +190,9 @@ int32_t ftc_gcn_layer(const ftc_csr *g, const ftc_windows *w, const float *vals,
 /*
  * AGNN propagation layer forward: s_ij = beta * cos(h_i, h_j) on the stored entries,
  * P = edge softmax of s, out = P * H (H not normalised).  edge_p, when not NULL,
- * receives P (nnz floats).
+ * receives P (nnz floats).  Without edge_p (and with a window index) scores, softmax and
+ * aggregation run fused in one pass over the edges; the softmax is then shifted by |beta|,
+ * an upper bound of every score, instead of by the row maximum (same result; |beta| < 43).
  */
 size_t ftc_agnn_layer_workspace_bytes(int32_t n, int32_t nnz, int32_t D);
 int32_t ftc_agnn_layer(const ftc_csr *g, const ftc_windows *w, const void *H, int32_t ld,

@@ -1,0 +1,349 @@
+// AGNN propagation layer in one pass over the edges: edge scores (SDDMM), edge softmax and the
+// weighted aggregation (SpMM) fused, so every neighbour row H[j,:] is gathered once per edge
+// instead of twice and neither scores nor probabilities travel through HBM.
+//
+//   out[i,:] = sum_j w_ij H[j,:] / sum_j w_ij,   w_ij = exp(beta * cos(h_i, h_j) - |beta|)
+//
+// |cos| <= 1, so |beta| is an upper bound of every score of every row: shifting by it instead of
+// by the row maximum gives the same softmax (numerator and denominator carry the same factor)
+// and makes the pass single-sweep: numerator vector and denominator are plain segmented sums.
+// Safe while exp(-2|beta|) is a normal fp32 number (|beta| < 43).
+//
+// Work partition, run structure and the handling of rows cut by run / wave boundaries are
+// those of the edge-balanced SpMM (spmm_seg.hip): 512 edges per wave staged in LDS, groups of
+// LPR lanes walk contiguous runs, complete rows are stored from registers, cut rows are summed
+// in edge order in LDS and through a carry buffer.  The partial of a cut row is the pair
+// (numerator vector, denominator); the division happens once all pieces are added.
+#include "ftc_common.hpp"
+
+namespace ftc {
+
+constexpr int AG_R = 512;  // edges per wave
+constexpr int AG_B = 4;    // edges per batch
+
+bool seg_shape(int dtype, int D, int *vec, int *lpr);
+
+template <int CTRL>
+__device__ __forceinline__ float ag_dpp_add(float v)
+{
+    const int moved = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false);
+    return v + __int_as_float(moved);
+}
+
+template <int LPR>
+__device__ __forceinline__ float ag_group_sum(float v)
+{
+    if constexpr (LPR >= 32) v += __shfl_xor(v, 16, 64);
+    if constexpr (LPR >= 16) v = ag_dpp_add<0x140>(v);  // row_mirror
+    if constexpr (LPR >= 8) v = ag_dpp_add<0x141>(v);   // row_half_mirror
+    if constexpr (LPR >= 4) v = ag_dpp_add<0x4e>(v);    // quad_perm [2,3,0,1]
+    if constexpr (LPR >= 2) v = ag_dpp_add<0xb1>(v);    // quad_perm [1,0,3,2]
+    return v;
+}
+
+size_t agnn_fused_ws(int nnz, int D)
+{
+    int vec, lpr, dp = 0;
+    if (seg_shape(FTC_F32, D, &vec, &lpr)) dp = vec * lpr;
+    if (seg_shape(FTC_F16, D, &vec, &lpr) && vec * lpr > dp) dp = vec * lpr;
+    if (dp == 0 || nnz == 0) return 0;
+    const size_t n_ranges = (static_cast<size_t>(nnz) + AG_R - 1) / AG_R;
+    return align_up(n_ranges * 2 * (dp + 4) * sizeof(float), 256) + align_up(n_ranges * sizeof(int), 256);
+}
+
+template <class T, int VEC, int LPR>
+__global__ __launch_bounds__(256) void agnn_fused_kernel(int nnz, int n_ranges, const int *__restrict__ col_idx,
+                                                         const int *__restrict__ edge_to_row,
+                                                         const void *__restrict__ H, int ld, int D,
+                                                         const float *__restrict__ rinv, float beta,
+                                                         void *__restrict__ out, int ldo, int odt,
+                                                         float *__restrict__ carry, int *__restrict__ carry_tail_row)
+{
+    constexpr int NG = 64 / LPR;
+    constexpr int RUN = AG_R / NG;
+    constexpr int RP = AG_R + NG;
+    constexpr int DP = LPR * VEC;
+    constexpr int DPZ = DP + 4;  // feature slots, then the denominator
+    static_assert(RUN % AG_B == 0, "runs are whole batches");
+    constexpr int IDX_WORDS = 4 * 2 * RP;
+    constexpr int PART_WORDS = 4 * 2 * NG * DPZ;
+    __shared__ int smem[IDX_WORDS > PART_WORDS ? IDX_WORDS : PART_WORDS];
+    __shared__ int s_meta[4][3][NG];
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int g = lane / LPR, sub = lane % LPR;
+    int *s_col = smem + wave * 2 * RP;
+    int *s_row = s_col + RP;
+
+    const int v = blockIdx.x * 4 + wave;
+    const bool active = v < n_ranges;
+    const int base = active ? v * AG_R : 0;
+    const int n_valid = active ? min(AG_R, nnz - base) : 0;
+#pragma unroll
+    for (int j = 0; j < AG_R / 64; ++j) {
+        const int i = j * 64 + lane;
+        if (i < n_valid) {
+            const int p = i + i / RUN;
+            s_col[p] = col_idx[base + i];
+            s_row[p] = edge_to_row[base + i];
+        }
+    }
+    const int prev_row = (active && base > 0) ? edge_to_row[base - 1] : -1;
+    const int next_row = (active && n_valid == AG_R && base + AG_R < nnz) ? edge_to_row[base + AG_R] : -1;
+    __syncthreads();
+
+    const int rs = g * RUN;
+    const int re = min(rs + RUN, n_valid);
+    const bool has = rs < n_valid;
+    const bool live = sub * VEC < D;
+    const float absb = fabsf(beta);
+    float acc[VEC], hacc[VEC], xi[VEC];
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) { acc[j] = 0.f; hacc[j] = 0.f; xi[j] = 0.f; }
+    float z = 0.f, hz = 0.f, ri = 0.f;
+    bool have_head = false, head_closed = false, have_tail = false;
+    int head_row = -1, cur = -1;
+    bool first = true;
+    const int left_row = !has ? -2 : (rs == 0 ? prev_row : s_row[rs - 1 + g - 1]);
+
+    auto direct_store = [&](int row) {
+        if (live) {
+            const float inv = 1.f / z;
+            float o[VEC];
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) o[j] = acc[j] * inv;
+            store_vec<VEC>(out, static_cast<int64_t>(row) * ldo + sub * VEC, odt, o);
+        }
+    };
+
+    // every group runs the same number of batches: the lane shuffles of the dot product need the
+    // whole wave; edges beyond the group's run are masked
+    for (int b = rs; b < rs + RUN; b += AG_B) {
+        int c[AG_B], r[AG_B];
+        bool need[AG_B];
+        RawVec<T, VEC> y[AG_B], xs[AG_B];
+        float rj[AG_B], rin[AG_B];
+#pragma unroll
+        for (int k = 0; k < AG_B; ++k) {
+            const bool ok = b + k < re;
+            const int p = ok ? b + k + g : 0;
+            c[k] = ok ? s_col[p] : -1;
+            r[k] = ok ? s_row[p] : -1;
+        }
+        int prev = cur;
+#pragma unroll
+        for (int k = 0; k < AG_B; ++k) {
+            need[k] = r[k] >= 0 && r[k] != prev;
+            if (r[k] >= 0) prev = r[k];
+        }
+#pragma unroll
+        for (int k = 0; k < AG_B; ++k) {
+            if (c[k] >= 0 && live) load_raw<T, VEC>(H, static_cast<int64_t>(c[k]) * ld + sub * VEC, y[k]);
+            else zero_raw(y[k]);
+            if (need[k] && live) load_raw<T, VEC>(H, static_cast<int64_t>(r[k]) * ld + sub * VEC, xs[k]);
+            else zero_raw(xs[k]);
+            rj[k] = c[k] >= 0 ? rinv[c[k]] : 0.f;
+            rin[k] = need[k] ? rinv[r[k]] : 0.f;
+        }
+#pragma unroll
+        for (int k = 0; k < AG_B; ++k) {
+            if (need[k]) {  // a new row starts: close the segment of the previous one
+                if (cur >= 0) {
+                    if (first && left_row == cur) {
+#pragma unroll
+                        for (int j = 0; j < VEC; ++j) hacc[j] = acc[j];
+                        hz = z;
+                        have_head = true; head_closed = true; head_row = cur;
+                    } else {
+                        direct_store(cur);
+                    }
+                    first = false;
+                }
+                cur = r[k];
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) acc[j] = 0.f;
+                z = 0.f;
+                unpack<T, VEC>(xs[k], xi);
+                ri = rin[k];
+            }
+            float yf[VEC];
+            unpack<T, VEC>(y[k], yf);
+            float d = 0.f;
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) d = fmaf(xi[j], yf[j], d);
+            d = ag_group_sum<LPR>(d);
+            if (r[k] >= 0) {
+                const float wgt = __expf(beta * ri * rj[k] * d - absb);
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) acc[j] = fmaf(wgt, yf[j], acc[j]);
+                z += wgt;
+            }
+        }
+    }
+    if (has) {  // the run's last segment
+        int right_row;
+        if (re < n_valid) right_row = s_row[re + g + 1];
+        else right_row = next_row;
+        const bool right_open = right_row == cur;
+        if (first && left_row == cur) {
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) hacc[j] = acc[j];
+            hz = z;
+            have_head = true; head_closed = !right_open; head_row = cur;
+        } else if (!right_open) {
+            direct_store(cur);
+        } else {
+            have_tail = true;
+        }
+    }
+    __syncthreads();  // staged indices are dead: the LDS is reused for partials
+
+    float *part = reinterpret_cast<float *>(smem) + wave * 2 * NG * DPZ;
+    if (have_head) {
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) part[(2 * g) * DPZ + sub * VEC + j] = hacc[j];
+        if (sub == 0) part[(2 * g) * DPZ + DP] = hz;
+    }
+    if (have_tail) {
+#pragma unroll
+        for (int j = 0; j < VEC; ++j) part[(2 * g + 1) * DPZ + sub * VEC + j] = acc[j];
+        if (sub == 0) part[(2 * g + 1) * DPZ + DP] = z;
+    }
+    if (sub == 0) {
+        s_meta[wave][0][g] = have_head ? head_row : -1;
+        s_meta[wave][1][g] = head_closed ? 1 : 0;
+        s_meta[wave][2][g] = have_tail ? cur : -1;
+    }
+    __syncthreads();
+
+    if (active) {
+        int tail_out = -1;
+        for (int d = lane; d < DP; d += 64) {
+            float run = 0.f, run_z = 0.f;
+            int run_row = -1;
+            bool from_outside = false;
+            tail_out = -1;
+            float *cv = carry + (static_cast<size_t>(v) * 2) * DPZ;
+            for (int q = 0; q < NG; ++q) {
+                const int hr = s_meta[wave][0][q];
+                if (hr >= 0) {
+                    if (run_row < 0) { run_row = hr; run = 0.f; run_z = 0.f; from_outside = true; }
+                    run += part[(2 * q) * DPZ + d];
+                    run_z += part[(2 * q) * DPZ + DP];
+                    if (s_meta[wave][1][q]) {
+                        if (from_outside) {
+                            cv[d] = run;
+                            if (d == 0) cv[DP] = run_z;
+                        } else if (d < D) {
+                            store_elem(out, static_cast<int64_t>(run_row) * ldo + d, odt, run / run_z);
+                        }
+                        run_row = -1;
+                        from_outside = false;
+                    }
+                }
+                const int tr = s_meta[wave][2][q];
+                if (tr >= 0) {
+                    run_row = tr;
+                    run = part[(2 * q + 1) * DPZ + d];
+                    run_z = part[(2 * q + 1) * DPZ + DP];
+                    from_outside = false;
+                }
+            }
+            if (run_row >= 0) {
+                if (from_outside) {
+                    cv[d] = run;
+                    if (d == 0) cv[DP] = run_z;
+                } else {
+                    cv[DPZ + d] = run;
+                    if (d == 0) cv[DPZ + DP] = run_z;
+                    tail_out = run_row;
+                }
+            }
+        }
+        if (lane == 0) carry_tail_row[v] = tail_out;
+    }
+}
+
+__global__ __launch_bounds__(256) void agnn_fused_fixup_kernel(int n, int n_ranges, const int *__restrict__ row_ptr,
+                                                               const float *__restrict__ carry,
+                                                               const int *__restrict__ carry_tail_row, int DP,
+                                                               int D, void *__restrict__ out, int ldo, int odt)
+{
+    const int DPZ = DP + 4;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int v = blockIdx.x * 4 + wave;
+    if (v < n_ranges) {
+        const int r = carry_tail_row[v];
+        if (r >= 0) {
+            const int last = (row_ptr[r + 1] - 1) / AG_R;
+            float zsum = carry[(static_cast<size_t>(v) * 2 + 1) * DPZ + DP];
+            for (int u = v + 1; u <= last; ++u) zsum += carry[(static_cast<size_t>(u) * 2) * DPZ + DP];
+            for (int d = lane; d < D; d += 64) {
+                float sum = carry[(static_cast<size_t>(v) * 2 + 1) * DPZ + d];
+                for (int u = v + 1; u <= last; ++u) sum += carry[(static_cast<size_t>(u) * 2) * DPZ + d];
+                store_elem(out, static_cast<int64_t>(r) * ldo + d, odt, sum / zsum);
+            }
+        }
+    }
+    const int64_t row = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (row < n && row_ptr[row] == row_ptr[row + 1])
+        for (int d = 0; d < D; ++d) store_elem(out, row * ldo + d, odt, 0.f);
+}
+
+template <class T>
+static void launch_agnn_t(int vec, int lpr, unsigned grid, hipStream_t s, int nnz, int n_ranges, const ftc_csr &g,
+                          const int *e2r, const void *H, int ld, int D, const float *rinv, float beta, void *out,
+                          int ldo, int odt, float *carry, int *tail_row)
+{
+    constexpr int VM = T::VEC;
+#define FTC_AG(V, L)                                                                                        \
+    hipLaunchKernelGGL((agnn_fused_kernel<T, V, L>), dim3(grid), dim3(256), 0, s, nnz, n_ranges, g.col_idx, \
+                       e2r, H, ld, D, rinv, beta, out, ldo, odt, carry, tail_row)
+    if (vec == VM) {
+        if (lpr == 4) FTC_AG(VM, 4);
+        else if (lpr == 8) FTC_AG(VM, 8);
+        else if (lpr == 16) FTC_AG(VM, 16);
+        else FTC_AG(VM, 32);
+    } else if (vec == VM / 2) {
+        FTC_AG(VM / 2, 4);
+    } else {
+        FTC_AG(VM / 4, 4);
+    }
+#undef FTC_AG
+}
+
+// Caller has checked: window index present, seg_shape() accepts (dt, D), rows of H and out 16-byte
+// aligned, workspace of agnn_fused_ws() bytes, rinv filled.
+int32_t launch_agnn_fused(const ftc_csr &g, const ftc_windows &w, const void *H, int ld, int dt, int D,
+                          const float *rinv, float beta, void *out, int ldo, int odt, void *ws, hipStream_t s)
+{
+    int vec = 0, lpr = 0;
+    seg_shape(dt, D, &vec, &lpr);
+    const int dp = vec * lpr;
+    const int n_ranges = (g.nnz + AG_R - 1) / AG_R;
+    float *carry = static_cast<float *>(ws);
+    int *tail_row = reinterpret_cast<int *>(
+        static_cast<char *>(ws) + align_up(static_cast<size_t>(n_ranges) * 2 * (dp + 4) * sizeof(float), 256));
+    if (n_ranges > 0) {
+        const unsigned grid = static_cast<unsigned>((n_ranges + 3) / 4);
+        if (dt == FTC_F32)
+            launch_agnn_t<F32>(vec, lpr, grid, s, g.nnz, n_ranges, g, w.edge_to_row, H, ld, D, rinv, beta, out, ldo,
+                               odt, carry, tail_row);
+        else if (dt == FTC_F16)
+            launch_agnn_t<F16>(vec, lpr, grid, s, g.nnz, n_ranges, g, w.edge_to_row, H, ld, D, rinv, beta, out, ldo,
+                               odt, carry, tail_row);
+        else
+            launch_agnn_t<BF16>(vec, lpr, grid, s, g.nnz, n_ranges, g, w.edge_to_row, H, ld, D, rinv, beta, out, ldo,
+                                odt, carry, tail_row);
+        const int32_t st = launch_status("agnn_fused");
+        if (st != FTC_OK) return st;
+    }
+    const int64_t blocks_rows = (static_cast<int64_t>(g.n) + 255) / 256;
+    const int64_t blocks_ranges = (n_ranges + 3) / 4;
+    const unsigned grid2 = static_cast<unsigned>(blocks_rows > blocks_ranges ? blocks_rows : blocks_ranges);
+    hipLaunchKernelGGL(agnn_fused_fixup_kernel, dim3(grid2), dim3(256), 0, s, g.n, n_ranges, g.row_ptr, carry,
+                       tail_row, dp, D, out, ldo, odt);
+    return launch_status("agnn_fused fixup");
+}
+
+}  // namespace ftc

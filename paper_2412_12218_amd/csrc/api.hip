@@ -315,13 +315,18 @@ int32_t ftc_gcn_layer(const ftc_csr *g, const ftc_windows *w, const float *vals,
                     static_cast<char *>(ws) + zbytes, ws_bytes - zbytes, stream);
 }
 
+static size_t agnn_unfused_bytes(int32_t n, int32_t nnz, int32_t D)
+{
+    return align_up(static_cast<size_t>(nnz) * sizeof(float), 256) +
+           align_up(ftc_sddmm_workspace_bytes(n, nnz, D), 256) +
+           align_up(ftc_edge_softmax_workspace_bytes(n, nnz), 256) + ftc_spmm_workspace_bytes(n, nnz, D);
+}
+
 size_t ftc_agnn_layer_workspace_bytes(int32_t n, int32_t nnz, int32_t D)
 {
     if (n < 0 || nnz < 0 || D < 1) return 0;
-    return align_up(static_cast<size_t>(n) * sizeof(float), 256) +
-           align_up(static_cast<size_t>(nnz) * sizeof(float), 256) +
-           align_up(ftc_sddmm_workspace_bytes(n, nnz, D), 256) +
-           align_up(ftc_edge_softmax_workspace_bytes(n, nnz), 256) + ftc_spmm_workspace_bytes(n, nnz, D);
+    const size_t a = agnn_unfused_bytes(n, nnz, D), b = agnn_fused_ws(nnz, D);
+    return align_up(static_cast<size_t>(n) * sizeof(float), 256) + (a > b ? a : b);
 }
 
 int32_t ftc_agnn_layer(const ftc_csr *g, const ftc_windows *w, const void *H, int32_t ld, int32_t dtype,
@@ -330,6 +335,10 @@ int32_t ftc_agnn_layer(const ftc_csr *g, const ftc_windows *w, const void *H, in
 {
     FTC_TRY(check_csr(g, "ftc_agnn_layer"));
     if (g->n == 0) return FTC_OK;
+    FTC_TRY(check_dense(H, ld, dtype, D, "ftc_agnn_layer", "H"));
+    FTC_TRY(check_dense(out, ldo, out_dtype, D, "ftc_agnn_layer", "out"));
+    if (out == H) return fail(FTC_EINVAL, "ftc_agnn_layer: out aliases H");
+    if (w) FTC_TRY(check_windows(g, w, "ftc_agnn_layer", true));
     const size_t need = ftc_agnn_layer_workspace_bytes(g->n, g->nnz, D);
     if (!ws || ws_bytes < need)
         return fail(FTC_EWORKSPACE, "ftc_agnn_layer: workspace of %zu bytes needed", need);
@@ -338,6 +347,16 @@ int32_t ftc_agnn_layer(const ftc_csr *g, const ftc_windows *w, const void *H, in
     char *p = static_cast<char *>(ws);
     float *rinv = reinterpret_cast<float *>(p);
     p += align_up(static_cast<size_t>(g->n) * sizeof(float), 256);
+    FTC_TRY(ftc_row_rnorm(g->n, H, ld, dtype, D, rinv, stream));
+
+    // One pass over the edges when the probabilities are not asked for and the vector path applies.
+    int vec, lpr;
+    const bool rows16 = aligned16(H) && aligned16(out) && (static_cast<int64_t>(ld) * elem_size(dtype)) % 16 == 0 &&
+                        (static_cast<int64_t>(ldo) * elem_size(out_dtype)) % 16 == 0;
+    if (!edge_p && w && g->nnz > 0 && path != FTC_PATH_MFMA && rows16 && seg_shape(dtype, D, &vec, &lpr))
+        return launch_agnn_fused(*g, *w, H, ld, dtype, D, rinv, beta, out, ldo, out_dtype, p,
+                                 static_cast<hipStream_t>(stream));
+
     float *scores = edge_p ? edge_p : reinterpret_cast<float *>(p);
     p += align_up(static_cast<size_t>(g->nnz) * sizeof(float), 256);
     const size_t sd = align_up(ftc_sddmm_workspace_bytes(g->n, g->nnz, D), 256);
@@ -347,7 +366,6 @@ int32_t ftc_agnn_layer(const ftc_csr *g, const ftc_windows *w, const void *H, in
     void *ws_softmax = p;
     p += sm;
     const size_t rest = ws_bytes - static_cast<size_t>(p - static_cast<char *>(ws));
-    FTC_TRY(ftc_row_rnorm(g->n, H, ld, dtype, D, rinv, stream));
     FTC_TRY(ftc_sddmm(g, w, H, H, ld, dtype, D, rinv, rinv, beta, scores, path, ws_sddmm, sd, stream));
     FTC_TRY(ftc_edge_softmax(g, w, scores, scores, ws_softmax, sm, stream));
     return ftc_spmm(g, w, scores, H, ld, dtype, D, out, ldo, out_dtype, 0, path, p, rest, stream);

@@ -1,13 +1,17 @@
 // Sparse graph transformation (Section V.A) on the GPU.
 //
 // Every row window is independent (the paper parallelises the same step over CPU threads), so
-// one workgroup condenses one window:
-//   1. edge_to_row for the window's edges,
-//   2. small windows (at most SMALL_CAP edges): bitonic sort of the column ids in LDS, strict
-//      de-duplication by a flag scan, rank of every edge by binary search in the unique list;
-//   3. large windows (hub rows of power-law graphs) are queued and condensed by a second kernel
-//      with a bitmap over the n column ids kept in the workspace: set bits, prefix sum of the
-//      per-word popcounts, rank = prefix + popcount of the lower bits.
+// one wave or one workgroup condenses one window; which one depends on the window's edge count:
+//   1. up to WAVE_CAP edges (almost every window): one wave sorts the column ids in registers
+//      with a bitonic network (lane shuffles, no barriers), de-duplicates with a flag scan and
+//      finds every edge's rank by binary search in the unique list parked in LDS;
+//   2. larger windows (hub rows of power-law graphs) are queued and condensed by a 1024-thread
+//      workgroup with a bitmap of 2^20 column ids held in LDS (128 KiB of the CU's 160 KiB):
+//      set bits, prefix sums of popcounts per group of 8 words, rank = group prefix + popcounts
+//      up to the column's bit.  Graphs with more than 2^20 nodes take several passes over
+//      successive column ranges; a pass whose range holds none of the window's columns costs
+//      only the scan of the window's edges.
+// Both also write edge_to_row for their window's edges.
 // The unique lists are first written at the window's edge offset of a temporary array (a
 // window never has more distinct columns than edges), then a scan over the windows gives
 // win_col_ptr / block_partition / summary and a last kernel packs the lists into win_cols.
@@ -15,23 +19,26 @@
 
 namespace ftc {
 
-constexpr int SMALL_CAP = 4096;  // edges per window handled in LDS
-constexpr int BIG_SLOTS_MAX = 256;  // concurrent bitmap slots for large windows (one per CU)
-constexpr int BIG_THREADS = 1024;
+constexpr int WAVE_CAP = 1024;       // edges per window sorted by a single wave in registers
+constexpr int BIG_THREADS = 1024;    // workgroup of the bitmap kernel
+constexpr int RANGE_LOG2 = 20;       // column ids per bitmap pass
+constexpr int RANGE_WORDS = (1 << RANGE_LOG2) / 32;
+constexpr int GROUP_WORDS = 8;       // bitmap words per prefix entry
+constexpr int N_GROUPS = RANGE_WORDS / GROUP_WORDS;
+constexpr int BIG_GRID = 256;        // persistent workgroups, one per CU
+constexpr size_t BIG_LDS_BYTES = sizeof(uint32_t) * (RANGE_WORDS + N_GROUPS);
 
 struct WinWorkspace {
     int *uniq_count;  // [n_windows]
     int *big_list;    // [n_windows]
     int *big_count;   // [1]
     int *tmp_cols;    // [nnz]
-    uint32_t *bitmaps;  // [slots][2 * words]: bits, then exclusive popcount prefix per word
-    size_t words;
-    int slots;
     size_t total;
 };
 
 static WinWorkspace carve(void *ws, int n, int nnz, int n_windows)
 {
+    (void)n;
     WinWorkspace w;
     char *p = static_cast<char *>(ws);
     size_t off = 0;
@@ -44,11 +51,6 @@ static WinWorkspace carve(void *ws, int n, int nnz, int n_windows)
     w.big_list = reinterpret_cast<int *>(take(sizeof(int) * static_cast<size_t>(n_windows)));
     w.big_count = reinterpret_cast<int *>(take(sizeof(int)));
     w.tmp_cols = reinterpret_cast<int *>(take(sizeof(int) * static_cast<size_t>(nnz)));
-    w.words = (static_cast<size_t>(n) + 31) / 32;
-    // two words of workspace per 32 columns and slot; at most 64 MiB in total, at least 8 slots
-    size_t slots = w.words ? (size_t(64) << 20) / (w.words * 2 * sizeof(uint32_t)) : BIG_SLOTS_MAX;
-    w.slots = static_cast<int>(slots < 8 ? 8 : (slots > BIG_SLOTS_MAX ? BIG_SLOTS_MAX : slots));
-    w.bitmaps = reinterpret_cast<uint32_t *>(take(sizeof(uint32_t) * 2 * w.words * w.slots));
     w.total = off;
     return w;
 }
@@ -91,147 +93,244 @@ __device__ __forceinline__ int block_exclusive_scan(int v, int *tmp, int *total)
 
 __global__ void win_clear_kernel(int *counter) { *counter = 0; }
 
-__global__ __launch_bounds__(256) void win_small_kernel(int n, const int *__restrict__ row_ptr,
-                                                        const int *__restrict__ col_idx, int blk_h,
-                                                        int *__restrict__ edge_to_row,
-                                                        int *__restrict__ edge_to_col,
-                                                        int *__restrict__ uniq_count,
-                                                        int *__restrict__ tmp_cols,
-                                                        int *__restrict__ big_list, int *big_count)
+// ---- windows of at most WAVE_CAP edges: one wave, keys in registers --------------------------------
+// Element i of the padded key array lives in lane i / E, register i % E.
+template <int E>
+__device__ __forceinline__ void wave_bitonic_sort(int (&key)[E], int lane)
 {
-    __shared__ int keys[SMALL_CAP];
-    __shared__ int uniq[SMALL_CAP];
-    __shared__ int rp[65];  // row_ptr of the window's rows (blk_h <= 64)
-    __shared__ int scan_tmp[256 / 64 + 1];
-    const int tid = threadIdx.x;
-    const int w = blockIdx.x;
-    const int r0 = w * blk_h;
-    const int r1 = min(n, r0 + blk_h);
-    const int rows = r1 - r0;
-    if (tid <= rows) rp[tid] = row_ptr[r0 + tid];
-    __syncthreads();
-    const int e0 = rp[0], e1 = rp[rows];
-    const int cnt = e1 - e0;
-
-    // 1. row of every edge of the window
-    for (int e = e0 + tid; e < e1; e += 256) {
-        int lo = 0, hi = rows;  // last k with rp[k] <= e
-        while (hi - lo > 1) {
-            const int mid = (lo + hi) >> 1;
-            if (rp[mid] <= e) lo = mid; else hi = mid;
-        }
-        edge_to_row[e] = r0 + lo;
-    }
-    if (cnt == 0) {
-        if (tid == 0) uniq_count[w] = 0;
-        return;
-    }
-    if (cnt > SMALL_CAP) {
-        if (tid == 0) big_list[atomicAdd(big_count, 1)] = w;
-        return;
-    }
-
-    // 2. sort the column ids (padded to a power of two with the largest int)
-    int P = 1;
-    while (P < cnt) P <<= 1;
-    for (int t = tid; t < P; t += 256) keys[t] = t < cnt ? col_idx[e0 + t] : 0x7fffffff;
-    __syncthreads();
-    for (int k = 2; k <= P; k <<= 1) {
-        for (int j = k >> 1; j > 0; j >>= 1) {
-            for (int t = tid; t < (P >> 1); t += 256) {
-                const int i = 2 * t - (t & (j - 1));
-                const int l = i + j;
-                const bool up = (i & k) == 0;
-                const int a = keys[i], b = keys[l];
-                if ((a > b) == up) { keys[i] = b; keys[l] = a; }
+    constexpr int P = 64 * E;
+#pragma unroll
+    for (int kk = 2; kk <= P; kk <<= 1) {
+#pragma unroll
+        for (int j = kk >> 1; j > 0; j >>= 1) {
+            if (j >= E) {  // partner element sits in another lane, same register
+                const int lm = j / E;
+                const bool lower = (lane & lm) == 0;
+#pragma unroll
+                for (int k = 0; k < E; ++k) {
+                    const int other = __shfl_xor(key[k], lm, 64);
+                    const bool up = ((lane * E + k) & kk) == 0;
+                    const int mn = min(key[k], other), mx = max(key[k], other);
+                    key[k] = (lower == up) ? mn : mx;
+                }
+            } else {       // partner element sits in the same lane
+#pragma unroll
+                for (int k = 0; k < E; ++k) {
+                    if ((k & j) == 0) {
+                        const bool up = ((lane * E + k) & kk) == 0;
+                        const int a = key[k], b = key[k | j];
+                        const int mn = min(a, b), mx = max(a, b);
+                        key[k] = up ? mn : mx;
+                        key[k | j] = up ? mx : mn;
+                    }
+                }
             }
-            __syncthreads();
         }
     }
-
-    // 3. strict de-duplication: each thread owns a run of consecutive sorted keys
-    const int per = (P + 255) / 256;
-    const int b0 = tid * per, b1 = min(cnt, b0 + per);
-    int mine = 0;
-    for (int t = b0; t < b1; ++t) mine += (t == 0 || keys[t] != keys[t - 1]) ? 1 : 0;
-    int n_uniq;
-    int pos = block_exclusive_scan<256>(mine, scan_tmp, &n_uniq);
-    for (int t = b0; t < b1; ++t)
-        if (t == 0 || keys[t] != keys[t - 1]) uniq[pos++] = keys[t];
-    __syncthreads();
-
-    // 4. outputs: unique list at the window's edge offset, rank of every edge
-    for (int t = tid; t < n_uniq; t += 256) tmp_cols[e0 + t] = uniq[t];
-    for (int t = tid; t < cnt; t += 256) {
-        const int c = col_idx[e0 + t];
-        int lo = 0, hi = n_uniq;  // first index with uniq[idx] >= c
-        while (lo < hi) {
-            const int mid = (lo + hi) >> 1;
-            if (uniq[mid] < c) lo = mid + 1; else hi = mid;
-        }
-        edge_to_col[e0 + t] = lo;
-    }
-    if (tid == 0) uniq_count[w] = n_uniq;
 }
 
-__global__ __launch_bounds__(BIG_THREADS) void win_big_kernel(int n, const int *__restrict__ row_ptr,
-                                                              const int *__restrict__ col_idx, int blk_h,
-                                                              int *__restrict__ edge_to_col,
-                                                              int *__restrict__ uniq_count,
-                                                              int *__restrict__ tmp_cols,
-                                                              const int *__restrict__ big_list,
-                                                              const int *big_count, uint32_t *bitmaps,
-                                                              int words)
+template <int E>
+__device__ __forceinline__ void condense_window_wave(int w, int r0, int rows, const int *rp, int cnt,
+                                                     const int *__restrict__ col_idx,
+                                                     int *__restrict__ edge_to_row,
+                                                     int *__restrict__ edge_to_col,
+                                                     int *__restrict__ uniq_count, int *__restrict__ tmp_cols,
+                                                     int *uniq_lds)
 {
+    const int lane = threadIdx.x;
+    const int e0 = rp[0];
+    int key[E], orig[E];
+#pragma unroll
+    for (int k = 0; k < E; ++k) {
+        const int i = lane * E + k;
+        orig[k] = i < cnt ? col_idx[e0 + i] : 0x7fffffff;
+        key[k] = orig[k];
+    }
+    wave_bitonic_sort<E>(key, lane);
+    // strict de-duplication of the sorted sequence
+    const int prev_last = __shfl_up(key[E - 1], 1, 64);
+    bool flag[E];
+    int mine = 0;
+#pragma unroll
+    for (int k = 0; k < E; ++k) {
+        const int i = lane * E + k;
+        const int before = k == 0 ? prev_last : key[k - 1];
+        flag[k] = i < cnt && (i == 0 || key[k] != before);
+        mine += flag[k] ? 1 : 0;
+    }
+    int incl = mine;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int up = __shfl_up(incl, d, 64);
+        if (lane >= d) incl += up;
+    }
+    const int n_uniq = __shfl(incl, 63, 64);
+    int pos = incl - mine;
+#pragma unroll
+    for (int k = 0; k < E; ++k) {
+        if (flag[k]) {
+            uniq_lds[pos] = key[k];
+            tmp_cols[e0 + pos] = key[k];
+            ++pos;
+        }
+    }
+    __syncthreads();  // single-wave workgroup: makes the unique list visible to all lanes
+#pragma unroll
+    for (int k = 0; k < E; ++k) {
+        const int i = lane * E + k;
+        if (i < cnt) {
+            int lo = 0, hi = n_uniq;  // first index with uniq[idx] >= column
+            while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                if (uniq_lds[mid] < orig[k]) lo = mid + 1; else hi = mid;
+            }
+            edge_to_col[e0 + i] = lo;
+            int a = 0, b = rows;  // last row index with rp[a] <= edge
+            while (b - a > 1) {
+                const int mid = (a + b) >> 1;
+                if (rp[mid] <= e0 + i) a = mid; else b = mid;
+            }
+            edge_to_row[e0 + i] = r0 + a;
+        }
+    }
+    if (lane == 0) uniq_count[w] = n_uniq;
+}
+
+__global__ __launch_bounds__(64) void win_wave_kernel(int n, const int *__restrict__ row_ptr,
+                                                      const int *__restrict__ col_idx, int blk_h,
+                                                      int *__restrict__ edge_to_row,
+                                                      int *__restrict__ edge_to_col,
+                                                      int *__restrict__ uniq_count, int *__restrict__ tmp_cols,
+                                                      int *__restrict__ big_list, int *big_count)
+{
+    __shared__ int uniq_lds[WAVE_CAP];
+    __shared__ int rp[65];
+    const int w = blockIdx.x;
+    const int r0 = w * blk_h;
+    const int rows = min(n, r0 + blk_h) - r0;
+    for (int t = threadIdx.x; t <= rows; t += 64) rp[t] = row_ptr[r0 + t];
+    __syncthreads();
+    const int cnt = rp[rows] - rp[0];
+    if (cnt > WAVE_CAP) {  // queued for the bitmap kernel
+        if (threadIdx.x == 0) big_list[atomicAdd(big_count, 1)] = w;
+        return;
+    }
+    if (cnt == 0) {
+        if (threadIdx.x == 0) uniq_count[w] = 0;
+        return;
+    }
+#define FTC_WAVE(E) condense_window_wave<E>(w, r0, rows, rp, cnt, col_idx, edge_to_row, edge_to_col, uniq_count, tmp_cols, uniq_lds)
+    if (cnt <= 64) FTC_WAVE(1);
+    else if (cnt <= 128) FTC_WAVE(2);
+    else if (cnt <= 256) FTC_WAVE(4);
+    else if (cnt <= 512) FTC_WAVE(8);
+    else FTC_WAVE(16);
+#undef FTC_WAVE
+}
+
+
+// ---- queued windows: bitmap of 2^20 column ids in LDS ----------------------------------------------
+__global__ __launch_bounds__(BIG_THREADS) void win_bitmap_kernel(int n, const int *__restrict__ row_ptr,
+                                                                 const int *__restrict__ col_idx, int blk_h,
+                                                                 int *__restrict__ edge_to_row,
+                                                                 int *__restrict__ edge_to_col,
+                                                                 int *__restrict__ uniq_count,
+                                                                 int *__restrict__ tmp_cols,
+                                                                 const int *__restrict__ big_list,
+                                                                 const int *big_count)
+{
+    extern __shared__ uint32_t lds[];
+    uint32_t *bits = lds;                                      // [RANGE_WORDS], all zero between passes
+    int *grp = reinterpret_cast<int *>(lds + RANGE_WORDS);     // [N_GROUPS] popcount sums, then prefixes
     __shared__ int scan_tmp[BIG_THREADS / 64 + 1];
-    __shared__ int carry_s;
+    __shared__ int rp[65];
+    __shared__ int any_s;
     const int tid = threadIdx.x;
-    uint32_t *bits = bitmaps + static_cast<size_t>(blockIdx.x) * 2 * words;
-    int *prefix = reinterpret_cast<int *>(bits + words);
+    for (int t = tid; t < RANGE_WORDS; t += BIG_THREADS) bits[t] = 0u;
+    for (int t = tid; t < N_GROUPS; t += BIG_THREADS) grp[t] = 0;
     const int nb = *big_count;
+    const int n_pass = static_cast<int>((static_cast<int64_t>(n) + (1 << RANGE_LOG2) - 1) >> RANGE_LOG2);
     for (int i = blockIdx.x; i < nb; i += gridDim.x) {
         const int w = big_list[i];
         const int r0 = w * blk_h;
-        const int r1 = min(n, r0 + blk_h);
-        const int e0 = row_ptr[r0], e1 = row_ptr[r1];
-        for (int t = tid; t < words; t += BIG_THREADS) bits[t] = 0u;
+        const int rows = min(n, r0 + blk_h) - r0;
+        __syncthreads();  // previous window (or the initial clearing) is done with the LDS
+        if (tid <= rows) rp[tid] = row_ptr[r0 + tid];
         __syncthreads();
+        const int e0 = rp[0], e1 = rp[rows];
         for (int e = e0 + tid; e < e1; e += BIG_THREADS) {
-            const int c = col_idx[e];
-            atomicOr(&bits[c >> 5], 1u << (c & 31));
-        }
-        if (tid == 0) carry_s = 0;
-        __threadfence();  // the atomics above are performed in L2: drop stale L1 lines of the bitmap
-        __syncthreads();
-        // exclusive prefix of the per-word popcounts, BIG_THREADS words per round
-        for (int base = 0; base < words; base += BIG_THREADS) {
-            const int t = base + tid;
-            const int pc = t < words ? __popc(bits[t]) : 0;
-            int round_total;
-            const int ex = block_exclusive_scan<BIG_THREADS>(pc, scan_tmp, &round_total);
-            const int carry = carry_s;
-            if (t < words) prefix[t] = carry + ex;
-            __syncthreads();
-            if (tid == 0) carry_s = carry + round_total;
-            __syncthreads();
-        }
-        const int n_uniq = carry_s;
-        for (int e = e0 + tid; e < e1; e += BIG_THREADS) {
-            const int c = col_idx[e];
-            const uint32_t below = bits[c >> 5] & ((1u << (c & 31)) - 1u);
-            edge_to_col[e] = prefix[c >> 5] + __popc(below);
-        }
-        for (int t = tid; t < words; t += BIG_THREADS) {
-            uint32_t b = bits[t];
-            int k = prefix[t];
-            while (b) {
-                const int bit = __ffs(b) - 1;
-                tmp_cols[e0 + k++] = t * 32 + bit;
-                b &= b - 1;
+            int a = 0, b = rows;  // last row index with rp[a] <= e
+            while (b - a > 1) {
+                const int mid = (a + b) >> 1;
+                if (rp[mid] <= e) a = mid; else b = mid;
             }
+            edge_to_row[e] = r0 + a;
         }
-        if (tid == 0) uniq_count[w] = n_uniq;
-        __syncthreads();  // bitmap slot is reused by the next queued window
+        int base_rank = 0;
+        for (int pass = 0; pass < n_pass; ++pass) {
+            const int lo = pass << RANGE_LOG2;
+            if (tid == 0) any_s = 0;
+            __syncthreads();
+            bool any = false;
+            for (int e = e0 + tid; e < e1; e += BIG_THREADS) {
+                const unsigned c = static_cast<unsigned>(col_idx[e] - lo);
+                if (c < (1u << RANGE_LOG2)) {
+                    atomicOr(&bits[c >> 5], 1u << (c & 31));
+                    any = true;
+                }
+            }
+            if (any) any_s = 1;
+            __syncthreads();
+            if (!any_s) continue;  // uniform: none of the window's columns lies in this range
+            // popcount sums per group of GROUP_WORDS words (coalesced word reads, LDS adds)
+            for (int t = tid; t < RANGE_WORDS; t += BIG_THREADS) {
+                const int pc = __popc(bits[t]);
+                if (pc) atomicAdd(&grp[t / GROUP_WORDS], pc);
+            }
+            __syncthreads();
+            // exclusive prefix over the groups: every thread owns N_GROUPS / BIG_THREADS consecutive groups
+            constexpr int PER = N_GROUPS / BIG_THREADS;
+            int sums[PER];
+            int mine = 0;
+#pragma unroll
+            for (int q = 0; q < PER; ++q) { sums[q] = grp[tid * PER + q]; mine += sums[q]; }
+            int pass_total;
+            int run = block_exclusive_scan<BIG_THREADS>(mine, scan_tmp, &pass_total);
+#pragma unroll
+            for (int q = 0; q < PER; ++q) { grp[tid * PER + q] = run; run += sums[q]; }
+            __syncthreads();
+            // rank of every edge whose column lies in this range
+            for (int e = e0 + tid; e < e1; e += BIG_THREADS) {
+                const unsigned c = static_cast<unsigned>(col_idx[e] - lo);
+                if (c < (1u << RANGE_LOG2)) {
+                    const int word = c >> 5, g0 = word / GROUP_WORDS;
+                    int r = grp[g0];
+                    for (int t = g0 * GROUP_WORDS; t < word; ++t) r += __popc(bits[t]);
+                    r += __popc(bits[word] & ((1u << (c & 31)) - 1u));
+                    edge_to_col[e] = base_rank + r;
+                }
+            }
+            // the unique columns of this range, ascending
+            for (int t = tid; t < RANGE_WORDS; t += BIG_THREADS) {
+                uint32_t b = bits[t];
+                if (b) {
+                    const int g0 = t / GROUP_WORDS;
+                    int k = base_rank + grp[g0];
+                    for (int q = g0 * GROUP_WORDS; q < t; ++q) k += __popc(bits[q]);
+                    while (b) {
+                        const int bit = __ffs(b) - 1;
+                        tmp_cols[e0 + k++] = lo + t * 32 + bit;
+                        b &= b - 1;
+                    }
+                }
+            }
+            __syncthreads();
+            // leave the LDS all zero for the next pass / window
+            for (int t = tid; t < RANGE_WORDS; t += BIG_THREADS) bits[t] = 0u;
+            for (int t = tid; t < N_GROUPS; t += BIG_THREADS) grp[t] = 0;
+            base_rank += pass_total;
+        }
+        if (tid == 0) uniq_count[w] = base_rank;
     }
 }
 
@@ -298,15 +397,22 @@ int32_t launch_build_windows(const ftc_csr &g, ftc_windows &w, void *ws, size_t 
         return launch_status("build_windows scan");
     }
     hipLaunchKernelGGL(win_clear_kernel, dim3(1), dim3(1), 0, s, k.big_count);
-    hipLaunchKernelGGL(win_small_kernel, dim3(w.n_windows), dim3(256), 0, s, g.n, g.row_ptr, g.col_idx,
-                       w.blk_h, w.edge_to_row, w.edge_to_col, k.uniq_count, k.tmp_cols, k.big_list,
-                       k.big_count);
-    int32_t st = launch_status("build_windows small");
+    hipLaunchKernelGGL(win_wave_kernel, dim3(w.n_windows), dim3(64), 0, s, g.n, g.row_ptr, g.col_idx, w.blk_h,
+                       w.edge_to_row, w.edge_to_col, k.uniq_count, k.tmp_cols, k.big_list, k.big_count);
+    int32_t st = launch_status("build_windows wave");
     if (st != FTC_OK) return st;
-    hipLaunchKernelGGL(win_big_kernel, dim3(k.slots), dim3(BIG_THREADS), 0, s, g.n, g.row_ptr, g.col_idx,
-                       w.blk_h, w.edge_to_col, k.uniq_count, k.tmp_cols, k.big_list, k.big_count, k.bitmaps,
-                       static_cast<int>(k.words));
-    st = launch_status("build_windows big");
+    // 144 KiB of dynamic LDS: above the default limit, so the attribute is raised first
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(win_bitmap_kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize,
+                            static_cast<int>(BIG_LDS_BYTES)) != hipSuccess) {
+        (void)hipGetLastError();
+        set_error("build_windows: cannot reserve %zu bytes of LDS", BIG_LDS_BYTES);
+        return FTC_EHIP;
+    }
+    hipLaunchKernelGGL(win_bitmap_kernel, dim3(BIG_GRID), dim3(BIG_THREADS), BIG_LDS_BYTES, s, g.n, g.row_ptr,
+                       g.col_idx, w.blk_h, w.edge_to_row, w.edge_to_col, k.uniq_count, k.tmp_cols, k.big_list,
+                       k.big_count);
+    st = launch_status("build_windows bitmap");
     if (st != FTC_OK) return st;
     hipLaunchKernelGGL(win_scan_kernel, dim3(1), dim3(1024), 0, s, w.n_windows, w.blk_w, k.uniq_count,
                        w.win_col_ptr, w.block_partition, w.summary);

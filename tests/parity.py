@@ -9,6 +9,8 @@ from paper_2412_12218_amd import binding as B
 TOL = {torch.float32: 1e-5, torch.float16: 2e-3, torch.bfloat16: 2e-3}
 # half an ulp of a 16-bit output, relative to the value itself
 OUT_ROUND = {torch.float32: 0.0, torch.float16: 2.0 ** -11, torch.bfloat16: 2.0 ** -8}
+# ... and half the spacing of fp16 subnormals for outputs below the smallest normal fp16 number
+OUT_ROUND_ABS = {torch.float32: 0.0, torch.float16: 2.0 ** -25, torch.bfloat16: 0.0}
 
 
 def dev_graph(g):
@@ -24,7 +26,7 @@ def quantise(x32, dtype):
 def norm_err(got, ref, ab, out_dtype=torch.float32):
     """max |got - ref| / (abs-sum of terms), after removing the output rounding allowance."""
     got = got.detach().cpu().double().numpy()
-    diff = np.abs(got - ref) - OUT_ROUND[out_dtype] * np.abs(ref)
+    diff = np.abs(got - ref) - np.maximum(OUT_ROUND[out_dtype] * np.abs(ref), OUT_ROUND_ABS[out_dtype])
     scale = np.where(ab > 0, ab, 1.0)
     # where no term contributes the result must be exactly zero
     assert np.all(got[ab == 0] == 0)

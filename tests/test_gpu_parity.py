@@ -96,6 +96,31 @@ def test_build_windows(oracle, graphs, name, blk):
     check_windows(win2, ref)
 
 
+def test_build_windows_more_than_one_column_range(oracle):
+    """More than 2^20 nodes: large windows take several bitmap passes (one per 2^20 column ids),
+    including passes that hold none of a window's columns."""
+    rng = np.random.default_rng(77)
+    n = (1 << 20) + 70_000
+    rows = {}
+    rows[5] = rng.integers(0, n, size=3000)                         # both ranges
+    rows[6] = rng.integers(0, n, size=2500)
+    rows[1_060_000] = rng.integers(1 << 20, n, size=2000)           # upper range only
+    rows[500_000] = rng.integers(0, 1 << 20, size=1500)             # lower range only
+    rows[500_001] = np.array([n - 1, 0, (1 << 20) - 1, 1 << 20])    # the range borders
+    for r in rng.integers(0, n, size=4000):
+        rows.setdefault(int(r), rng.integers(0, n, size=rng.integers(1, 40)))
+    deg = np.zeros(n, dtype=np.int64)
+    for r, c in rows.items():
+        deg[r] = len(c)
+    row_ptr = np.zeros(n + 1, dtype=np.int32)
+    row_ptr[1:] = np.cumsum(deg)
+    col = np.concatenate([rows[r] for r in sorted(rows)]).astype(np.int32)
+    g = synth.Graph(n, row_ptr, col)
+    ref = oracle.build_windows(g.row_ptr, g.col_idx)
+    win = B.ftc_build_windows(dev_graph(g))
+    check_windows(win, ref)
+
+
 def test_build_windows_degenerate(oracle):
     # no edges at all, and a single node
     for n in (1, 33):
@@ -364,9 +389,12 @@ def test_gcn_layer(oracle, graphs, name, dtype, d_in, d_out, relu):
 
 
 @pytest.mark.parametrize("name,dtype,D", [("cfg1", F32, 16), ("cfg3s", F16, 32), ("cfg5s", F16, 32),
-                                          ("cfg4s", BF16, 64)])
-@pytest.mark.parametrize("beta", [1.0, 2.5])
+                                          ("cfg4s", BF16, 64), ("hub", F16, 8), ("hub", F16, 128),
+                                          ("mixed", BF16, 16), ("cfg5s", F32, 32), ("hub", F16, 24)])
+@pytest.mark.parametrize("beta", [1.0, 2.5, -3.0])
 def test_agnn_layer(oracle, graphs, name, dtype, D, beta):
+    """Both routes of the layer: the unfused chain (taken when the probabilities are requested) and
+    the single-pass fused kernel, each against the oracle."""
     g = graphs[name]
     say(f"agnn_layer {name} {dtype} D={D} beta={beta}")
     Hd, H64 = quantise(synth.normal_features(g.n, D, seed=11), dtype)
@@ -377,8 +405,27 @@ def test_agnn_layer(oracle, graphs, name, dtype, D, beta):
     out = B.ftc_agnn_layer(dg, win, Hd, beta=beta, edge_p=p)
     err = norm_err(out, ref, ab)
     perr = rel_err(p, pref)
-    say(f"  err {err:.3e} p err {perr:.3e}")
+    say(f"  unfused err {err:.3e} p err {perr:.3e}")
     assert err < TOL[dtype]
     assert perr < (1e-4 if dtype == F32 else 2e-3)
-    out2 = B.ftc_agnn_layer(dg, win, Hd, beta=beta)      # without the optional P output
-    assert torch.equal(out, out2)
+    out2 = B.ftc_agnn_layer(dg, win, Hd, beta=beta)      # fused: no P output
+    err2 = norm_err(out2, ref, ab)
+    say(f"  fused err {err2:.3e}")
+    assert err2 < TOL[dtype]
+    out3 = B.ftc_agnn_layer(dg, win, Hd, beta=beta)
+    assert torch.equal(out2, out3)
+    out4 = B.ftc_agnn_layer(dg, None, Hd, beta=beta)     # no window index: row kernels
+    assert norm_err(out4, ref, ab) < TOL[dtype]
+
+
+def test_agnn_layer_fused_large_beta_and_fp16_out(oracle, graphs):
+    g = graphs["cfg5s"]
+    Hd, H64 = quantise(synth.normal_features(g.n, 32, seed=12), F16)
+    dg = dev_graph(g)
+    win = B.ftc_build_windows(dg)
+    for beta in (20.0, -20.0, 0.0):
+        ref, ab, _ = oracle.agnn_layer(g.row_ptr, g.col_idx, H64, beta)
+        out = B.ftc_agnn_layer(dg, win, Hd, beta=beta, out_dtype=F16)
+        err = norm_err(out, ref, ab, F16)
+        say(f"agnn fused beta={beta} err {err:.3e}")
+        assert err < 2e-3
