@@ -48,10 +48,9 @@ def alg_bytes(n, nnz, sum_uniq, n_win):
     b["gcn_l2_spmm"] = spmm(8, 4, 4)
     b["agnn_in_gemm"] = gemm(128, 32, 2)
     for l in range(4):
+        # fused propagation layer: one gather per condensed column, own rows once, column index once
         b[f"agnn_l{l}_rnorm"] = n * 32 * e + n * 4
-        b[f"agnn_l{l}_sddmm"] = sddmm(32)
-        b[f"agnn_l{l}_softmax"] = nnz * 8 + rp
-        b[f"agnn_l{l}_spmm"] = spmm(32, e, 2)
+        b[f"agnn_l{l}_fused"] = sum_uniq * 32 * e + n * 32 * e + nnz * 4 + n * 32 * 2
     b["agnn_out_gemm"] = gemm(32, 8, 4)
     return b
 
@@ -245,19 +244,8 @@ def main():
         timed("gcn_layer2", lambda: B.ftc_gcn_layer(dg, hp.win, hp.vals, hp.gcn_h, W2, out=hp.gcn_out, ws=hp.ws))
         a, b = hp.agnn_h
         timed("agnn_in_gemm", lambda: B.ftc_update_gemm(X, Win, out=a, relu=True))
-        n, nnz = dg.n, dg.nnz
-        # the AGNN layer is issued call by call so that SDDMM and SpMM get their own events
-        rinv = hp.ws[:n * 4].view(torch.float32)
-        off = (n * 4 + 255) // 256 * 256
-        scores = hp.ws[off:off + nnz * 4].view(torch.float32)
-        off2 = (off + nnz * 4 + 255) // 256 * 256
-        ws_sm = hp.ws[off2:off2 + L.ftc_edge_softmax_workspace_bytes(n, nnz)]
-        ws_rest = hp.ws[off2 + (ws_sm.numel() + 255) // 256 * 256:]
         for l in range(4):
-            timed("rnorm", lambda: B.ftc_row_rnorm(a, out=rinv))
-            timed("sddmm", lambda: B.ftc_sddmm(dg, hp.win, a, a, rinv, rinv, betas[l], out=scores))
-            timed("softmax", lambda: B.ftc_edge_softmax(dg, hp.win, scores, out=scores, ws=ws_sm))
-            timed("spmm_d32", lambda: B.ftc_spmm(dg, hp.win, scores, a, out=b, ws=ws_rest))
+            timed("agnn_layer", lambda: B.ftc_agnn_layer(dg, hp.win, a, beta=betas[l], out=b, ws=hp.ws))
             a, b = b, a
         timed("agnn_out_gemm", lambda: B.ftc_update_gemm(a, Wout, out=hp.agnn_out))
 
@@ -273,14 +261,11 @@ def main():
     for name, a, b in calls:
         per_call.setdefault(name, []).append(a.elapsed_time(b))
     avg_ms = {k: float(np.mean(v)) for k, v in per_call.items()}
-    spmm_bytes = bytes_by_call["agnn_l0_spmm"]
-    sddmm_bytes = bytes_by_call["agnn_l0_sddmm"]
-    spmm_gbs = spmm_bytes / (avg_ms["spmm_d32"] * 1e-3) / 1e9
-    sddmm_gbs = sddmm_bytes / (avg_ms["sddmm"] * 1e-3) / 1e9
-    # dominant kernel: whichever of the two gather kernels takes longer per call
-    dom = "spmm_d32" if avg_ms["spmm_d32"] >= avg_ms["sddmm"] else "sddmm"
-    dom_gbs = spmm_gbs if dom == "spmm_d32" else sddmm_gbs
-
+    # dominant kernel of the step: the fused AGNN propagation kernel (four launches per step); its
+    # call also runs the row-norm kernel and the small fix-up kernel, which are included in the time
+    dom = "agnn_layer"
+    dom_bytes = bytes_by_call["agnn_l0_fused"] + bytes_by_call["agnn_l0_rnorm"]
+    dom_gbs = dom_bytes / (avg_ms[dom] * 1e-3) / 1e9
     out = {
         "metric": "hot-path algorithmic GB/s (window build + GCN norm + 2-layer GCN + 4-layer AGNN forward)",
         "value": total_bytes / (ms_per_step * 1e-3) / 1e9,
@@ -290,25 +275,29 @@ def main():
         "dtype": "f16", "data": "synthetic",
         "config": {"workload": f"cfg5 R-MAT scale {args.scale}: N={g.n}, nnz={g.nnz}, sum_uniq={sum_uniq}, "
                                "fp16 features Nx128, GCN 128-16-8, AGNN 128-32x4-8, fp32 accumulate"},
-        "roofline": {"bound": "hbm", "kernel": dom, "achieved": dom_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": dom_gbs / HBM_PEAK_GBS, "traffic": None,
-                     "alg_bytes_per_launch": spmm_bytes if dom == "spmm_d32" else sddmm_bytes,
-                     "avg_ms": avg_ms[dom]},
-        "spmm_d32_GBs": spmm_gbs, "spmm_d32_frac": spmm_gbs / HBM_PEAK_GBS,
-        "sddmm_d32_GBs": sddmm_gbs, "sddmm_d32_frac": sddmm_gbs / HBM_PEAK_GBS,
+        "roofline": {"bound": "hbm", "kernel": "agnn_fused_kernel (call ftc_agnn_layer)", "achieved": dom_gbs,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": dom_gbs / HBM_PEAK_GBS, "traffic": None,
+                     "alg_bytes_per_launch": dom_bytes, "avg_ms": avg_ms[dom]},
         "gcn_2layer_ms": avg_ms["gcn_layer1"] + avg_ms["gcn_layer2"],
-        "agnn_layer_ms": avg_ms["rnorm"] + avg_ms["sddmm"] + avg_ms["softmax"] + avg_ms["spmm_d32"],
+        "agnn_layer_ms": avg_ms["agnn_layer"],
+        "build_windows_ms": avg_ms["build_windows"],
         "call_ms": avg_ms,
         "alg_bytes_per_step": total_bytes,
         "input_generation_s": gen_s,
     }
-    # one plain device-to-device copy of known size (256 MiB read + 256 MiB written): the reference
-    # dispatch against which the profiler's FETCH_SIZE / WRITE_SIZE counters are scaled
-    calib_src = torch.ones(1 << 26, dtype=torch.float32, device=dev)
+    # one plain device-to-device copy of known size (1 GiB read + 1 GiB written, far larger than any
+    # cache): the reference dispatch against which the profiler's FETCH_SIZE / WRITE_SIZE counters
+    # are scaled
+    calib_src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
     calib_dst = torch.empty_like(calib_src)
     calib_dst.copy_(calib_src)
     torch.cuda.synchronize()
     del calib_src, calib_dst
+    # HBM traffic of the dominant kernel from the committed counter summary (separate profiler runs)
+    traffic_file = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(traffic_file):
+        with open(traffic_file) as f:
+            out["roofline"]["traffic"] = json.load(f).get("agnn_fused_kernel_bytes_per_launch")
     if not args.no_kernels:
         # the two largest graphs: stand-alone aggregation and edge-score kernels, fp32 output
         k5 = kernel_suite("cfg5 R-MAT", g, synth.normal_features(g.n, 32, seed + 20), torch.float16, 32)

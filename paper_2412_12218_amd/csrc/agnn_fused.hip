@@ -276,12 +276,48 @@ __global__ __launch_bounds__(256) void agnn_fused_fixup_kernel(int n, int n_rang
         const int r = carry_tail_row[v];
         if (r >= 0) {
             const int last = (row_ptr[r + 1] - 1) / AG_R;
-            float zsum = carry[(static_cast<size_t>(v) * 2 + 1) * DPZ + DP];
-            for (int u = v + 1; u <= last; ++u) zsum += carry[(static_cast<size_t>(u) * 2) * DPZ + DP];
-            for (int d = lane; d < D; d += 64) {
-                float sum = carry[(static_cast<size_t>(v) * 2 + 1) * DPZ + d];
-                for (int u = v + 1; u <= last; ++u) sum += carry[(static_cast<size_t>(u) * 2) * DPZ + d];
-                store_elem(out, static_cast<int64_t>(r) * ldo + d, odt, sum / zsum);
+            // teams of `dl` lanes (one lane per feature) share the ranges of a long row round-robin,
+            // four loads in flight each; team sums are added in team order (fixed by the shape)
+            int dl = 1;
+            while (dl < D && dl < 64) dl <<= 1;
+            const int parts = 64 / dl;
+            const int part = lane / dl;
+            // denominator: every lane adds all pieces
+            float zsum;
+            {
+                float z0 = 0.f, z1 = 0.f, z2 = 0.f, z3 = 0.f;
+                int u = v + 1 + part;
+                for (; u + 3 * parts <= last; u += 4 * parts) {
+                    z0 += carry[(static_cast<size_t>(u) * 2) * DPZ + DP];
+                    z1 += carry[(static_cast<size_t>(u + parts) * 2) * DPZ + DP];
+                    z2 += carry[(static_cast<size_t>(u + 2 * parts) * 2) * DPZ + DP];
+                    z3 += carry[(static_cast<size_t>(u + 3 * parts) * 2) * DPZ + DP];
+                }
+                for (; u <= last; u += parts) z0 += carry[(static_cast<size_t>(u) * 2) * DPZ + DP];
+                zsum = (z0 + z1) + (z2 + z3);
+                for (int off = 32; off >= dl; off >>= 1) zsum += __shfl_down(zsum, off, 64);
+                zsum = __shfl(zsum, 0, 64) + carry[(static_cast<size_t>(v) * 2 + 1) * DPZ + DP];
+            }
+            for (int d0 = 0; d0 < D; d0 += 64) {
+                const int d = d0 + lane % dl;
+                const bool dok = d < D;
+                const float *base = carry + (dok ? d : 0);
+                float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+                int u = v + 1 + part;
+                for (; u + 3 * parts <= last; u += 4 * parts) {
+                    const float a0 = base[(static_cast<size_t>(u) * 2) * DPZ];
+                    const float a1 = base[(static_cast<size_t>(u + parts) * 2) * DPZ];
+                    const float a2 = base[(static_cast<size_t>(u + 2 * parts) * 2) * DPZ];
+                    const float a3 = base[(static_cast<size_t>(u + 3 * parts) * 2) * DPZ];
+                    s0 += a0; s1 += a1; s2 += a2; s3 += a3;
+                }
+                for (; u <= last; u += parts) s0 += base[(static_cast<size_t>(u) * 2) * DPZ];
+                float sum = (s0 + s1) + (s2 + s3);
+                for (int off = 32; off >= dl; off >>= 1) sum += __shfl_down(sum, off, 64);
+                if (lane < dl && dok) {
+                    sum += carry[(static_cast<size_t>(v) * 2 + 1) * DPZ + d];
+                    store_elem(out, static_cast<int64_t>(r) * ldo + d, odt, sum / zsum);
+                }
             }
         }
     }

@@ -26,12 +26,14 @@ constexpr int RANGE_WORDS = (1 << RANGE_LOG2) / 32;
 constexpr int GROUP_WORDS = 8;       // bitmap words per prefix entry
 constexpr int N_GROUPS = RANGE_WORDS / GROUP_WORDS;
 constexpr int BIG_GRID = 256;        // persistent workgroups, one per CU
-constexpr size_t BIG_LDS_BYTES = sizeof(uint32_t) * (RANGE_WORDS + N_GROUPS);
+constexpr int TOUCH_WORDS = RANGE_WORDS / 32;  // one bit per bitmap word: which words hold any bit
+constexpr size_t BIG_LDS_BYTES = sizeof(uint32_t) * (RANGE_WORDS + N_GROUPS + TOUCH_WORDS);
+static_assert(TOUCH_WORDS == BIG_THREADS, "one coarse word per thread");
 
 struct WinWorkspace {
     int *uniq_count;  // [n_windows]
     int *big_list;    // [n_windows]
-    int *big_count;   // [1]
+    int *big_count;   // [2]
     int *tmp_cols;    // [nnz]
     size_t total;
 };
@@ -49,7 +51,7 @@ static WinWorkspace carve(void *ws, int n, int nnz, int n_windows)
     };
     w.uniq_count = reinterpret_cast<int *>(take(sizeof(int) * static_cast<size_t>(n_windows)));
     w.big_list = reinterpret_cast<int *>(take(sizeof(int) * static_cast<size_t>(n_windows)));
-    w.big_count = reinterpret_cast<int *>(take(sizeof(int)));
+    w.big_count = reinterpret_cast<int *>(take(2 * sizeof(int)));  // queue length, next entry to hand out
     w.tmp_cols = reinterpret_cast<int *>(take(sizeof(int) * static_cast<size_t>(nnz)));
     w.total = off;
     return w;
@@ -91,7 +93,7 @@ __device__ __forceinline__ int block_exclusive_scan(int v, int *tmp, int *total)
     return tmp[wave] + incl - v;
 }
 
-__global__ void win_clear_kernel(int *counter) { *counter = 0; }
+__global__ void win_clear_kernel(int *counters) { counters[0] = 0; counters[1] = 0; }
 
 // ---- windows of at most WAVE_CAP edges: one wave, keys in registers --------------------------------
 // Element i of the padded key array lives in lane i / E, register i % E.
@@ -237,27 +239,52 @@ __global__ __launch_bounds__(BIG_THREADS) void win_bitmap_kernel(int n, const in
                                                                  int *__restrict__ uniq_count,
                                                                  int *__restrict__ tmp_cols,
                                                                  const int *__restrict__ big_list,
-                                                                 const int *big_count)
+                                                                 int *big_count)
 {
     extern __shared__ uint32_t lds[];
     uint32_t *bits = lds;                                      // [RANGE_WORDS], all zero between passes
     int *grp = reinterpret_cast<int *>(lds + RANGE_WORDS);     // [N_GROUPS] popcount sums, then prefixes
+    uint32_t *touched = lds + RANGE_WORDS + N_GROUPS;          // [TOUCH_WORDS] non-empty bitmap words
     __shared__ int scan_tmp[BIG_THREADS / 64 + 1];
     __shared__ int rp[65];
     __shared__ int any_s;
+    __shared__ int next_s;
     const int tid = threadIdx.x;
     for (int t = tid; t < RANGE_WORDS; t += BIG_THREADS) bits[t] = 0u;
     for (int t = tid; t < N_GROUPS; t += BIG_THREADS) grp[t] = 0;
+    touched[tid] = 0u;
     const int nb = *big_count;
     const int n_pass = static_cast<int>((static_cast<int64_t>(n) + (1 << RANGE_LOG2) - 1) >> RANGE_LOG2);
-    for (int i = blockIdx.x; i < nb; i += gridDim.x) {
+    // Workgroups pull queued windows one at a time (window sizes differ by two orders of magnitude);
+    // every workgroup leaves as soon as the queue is empty.
+    for (;;) {
+        __syncthreads();  // previous window (or the initial clearing) is done with the LDS
+        if (tid == 0) next_s = atomicAdd(&big_count[1], 1);
+        __syncthreads();
+        const int i = next_s;
+        if (i >= nb) break;
         const int w = big_list[i];
         const int r0 = w * blk_h;
         const int rows = min(n, r0 + blk_h) - r0;
-        __syncthreads();  // previous window (or the initial clearing) is done with the LDS
         if (tid <= rows) rp[tid] = row_ptr[r0 + tid];
         __syncthreads();
         const int e0 = rp[0], e1 = rp[rows];
+        // The window's column ids are handled in chunks of KREG * 1024 edges held in registers
+        // (KREG independent loads in flight per thread).  A window that fits one chunk reads its
+        // column ids from memory once; longer ones re-read them in the ranking phase.
+        constexpr int KREG = 8;
+        constexpr int CHUNK = KREG * BIG_THREADS;
+        const int n_chunks = (e1 - e0 + CHUNK - 1) / CHUNK;
+        int creg[KREG];
+        auto load_chunk = [&](int ch) {
+#pragma unroll
+            for (int q = 0; q < KREG; ++q) {
+                const int e = e0 + ch * CHUNK + tid + q * BIG_THREADS;
+                creg[q] = e < e1 ? col_idx[e] : -1;
+            }
+        };
+        if (n_chunks == 1) load_chunk(0);
+        const bool track = n_chunks <= 2;  // longer windows touch most words: visit them all instead
         for (int e = e0 + tid; e < e1; e += BIG_THREADS) {
             int a = 0, b = rows;  // last row index with rp[a] <= e
             while (b - a > 1) {
@@ -272,18 +299,30 @@ __global__ __launch_bounds__(BIG_THREADS) void win_bitmap_kernel(int n, const in
             if (tid == 0) any_s = 0;
             __syncthreads();
             bool any = false;
-            for (int e = e0 + tid; e < e1; e += BIG_THREADS) {
-                const unsigned c = static_cast<unsigned>(col_idx[e] - lo);
-                if (c < (1u << RANGE_LOG2)) {
-                    atomicOr(&bits[c >> 5], 1u << (c & 31));
-                    any = true;
+            for (int ch = 0; ch < n_chunks; ++ch) {
+                if (n_chunks > 1) load_chunk(ch);
+#pragma unroll
+                for (int q = 0; q < KREG; ++q) {
+                    const unsigned c = static_cast<unsigned>(creg[q] - lo);
+                    if (creg[q] >= 0 && c < (1u << RANGE_LOG2)) {
+                        atomicOr(&bits[c >> 5], 1u << (c & 31));
+                        if (track) atomicOr(&touched[c >> 10], 1u << ((c >> 5) & 31));
+                        any = true;
+                    }
                 }
             }
             if (any) any_s = 1;
+            if (!track) touched[tid] = 0xffffffffu;
             __syncthreads();
-            if (!any_s) continue;  // uniform: none of the window's columns lies in this range
-            // popcount sums per group of GROUP_WORDS words (coalesced word reads, LDS adds)
-            for (int t = tid; t < RANGE_WORDS; t += BIG_THREADS) {
+            if (!any_s) {  // uniform: none of the window's columns lies in this range
+                touched[tid] = 0u;
+                continue;
+            }
+            // popcount sums per group of GROUP_WORDS words; only words that hold a bit are visited
+            // (thread t owns bitmap words 32 t .. 32 t + 31 through its coarse word)
+            const uint32_t my_touched = touched[tid];
+            for (uint32_t m = my_touched; m; m &= m - 1) {
+                const int t = tid * 32 + (__ffs(m) - 1);
                 const int pc = __popc(bits[t]);
                 if (pc) atomicAdd(&grp[t / GROUP_WORDS], pc);
             }
@@ -300,34 +339,40 @@ __global__ __launch_bounds__(BIG_THREADS) void win_bitmap_kernel(int n, const in
             for (int q = 0; q < PER; ++q) { grp[tid * PER + q] = run; run += sums[q]; }
             __syncthreads();
             // rank of every edge whose column lies in this range
-            for (int e = e0 + tid; e < e1; e += BIG_THREADS) {
-                const unsigned c = static_cast<unsigned>(col_idx[e] - lo);
-                if (c < (1u << RANGE_LOG2)) {
-                    const int word = c >> 5, g0 = word / GROUP_WORDS;
-                    int r = grp[g0];
-                    for (int t = g0 * GROUP_WORDS; t < word; ++t) r += __popc(bits[t]);
-                    r += __popc(bits[word] & ((1u << (c & 31)) - 1u));
-                    edge_to_col[e] = base_rank + r;
+            auto rank_of = [&](unsigned c) {
+                const int word = c >> 5, g0 = word / GROUP_WORDS;
+                int r = grp[g0];
+                for (int t = g0 * GROUP_WORDS; t < word; ++t) r += __popc(bits[t]);
+                return base_rank + r + __popc(bits[word] & ((1u << (c & 31)) - 1u));
+            };
+            for (int ch = 0; ch < n_chunks; ++ch) {
+                if (n_chunks > 1) load_chunk(ch);
+#pragma unroll
+                for (int q = 0; q < KREG; ++q) {
+                    const unsigned c = static_cast<unsigned>(creg[q] - lo);
+                    if (creg[q] >= 0 && c < (1u << RANGE_LOG2))
+                        edge_to_col[e0 + ch * CHUNK + tid + q * BIG_THREADS] = rank_of(c);
                 }
             }
             // the unique columns of this range, ascending
-            for (int t = tid; t < RANGE_WORDS; t += BIG_THREADS) {
+            for (uint32_t m = my_touched; m; m &= m - 1) {
+                const int t = tid * 32 + (__ffs(m) - 1);
                 uint32_t b = bits[t];
-                if (b) {
-                    const int g0 = t / GROUP_WORDS;
-                    int k = base_rank + grp[g0];
-                    for (int q = g0 * GROUP_WORDS; q < t; ++q) k += __popc(bits[q]);
-                    while (b) {
-                        const int bit = __ffs(b) - 1;
-                        tmp_cols[e0 + k++] = lo + t * 32 + bit;
-                        b &= b - 1;
-                    }
+                if (!b) continue;
+                const int g0 = t / GROUP_WORDS;
+                int k = base_rank + grp[g0];
+                for (int q = g0 * GROUP_WORDS; q < t; ++q) k += __popc(bits[q]);
+                while (b) {
+                    const int bit = __ffs(b) - 1;
+                    tmp_cols[e0 + k++] = lo + t * 32 + bit;
+                    b &= b - 1;
                 }
             }
             __syncthreads();
             // leave the LDS all zero for the next pass / window
-            for (int t = tid; t < RANGE_WORDS; t += BIG_THREADS) bits[t] = 0u;
+            for (uint32_t m = my_touched; m; m &= m - 1) bits[tid * 32 + (__ffs(m) - 1)] = 0u;
             for (int t = tid; t < N_GROUPS; t += BIG_THREADS) grp[t] = 0;
+            touched[tid] = 0u;
             base_rank += pass_total;
         }
         if (tid == 0) uniq_count[w] = base_rank;
@@ -375,16 +420,21 @@ __global__ __launch_bounds__(1024) void win_scan_kernel(int n_windows, int blk_w
     }
 }
 
-__global__ __launch_bounds__(256) void win_pack_kernel(int n, const int *__restrict__ row_ptr, int blk_h,
+// Packs the unique lists: one thread per slot of the temporary array.  Slot e belongs to the window
+// of edge e (edge_to_row); it holds a list entry when its offset inside the window is below the
+// window's unique count.
+__global__ __launch_bounds__(256) void win_pack_kernel(int nnz, const int *__restrict__ row_ptr, int blk_h,
+                                                       const int *__restrict__ edge_to_row,
                                                        const int *__restrict__ win_col_ptr,
                                                        const int *__restrict__ tmp_cols,
                                                        int *__restrict__ win_cols)
 {
-    const int w = blockIdx.x;
-    const int src = row_ptr[min(n, w * blk_h)];
+    const int64_t e = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (e >= nnz) return;
+    const int w = edge_to_row[e] / blk_h;
+    const int k = static_cast<int>(e) - row_ptr[w * blk_h];
     const int dst = win_col_ptr[w];
-    const int cnt = win_col_ptr[w + 1] - dst;
-    for (int t = threadIdx.x; t < cnt; t += 256) win_cols[dst + t] = tmp_cols[src + t];
+    if (k < win_col_ptr[w + 1] - dst) win_cols[dst + k] = tmp_cols[e];
 }
 
 int32_t launch_build_windows(const ftc_csr &g, ftc_windows &w, void *ws, size_t ws_bytes, hipStream_t s)
@@ -418,8 +468,9 @@ int32_t launch_build_windows(const ftc_csr &g, ftc_windows &w, void *ws, size_t 
                        w.win_col_ptr, w.block_partition, w.summary);
     st = launch_status("build_windows scan");
     if (st != FTC_OK) return st;
-    hipLaunchKernelGGL(win_pack_kernel, dim3(w.n_windows), dim3(256), 0, s, g.n, g.row_ptr, w.blk_h,
-                       w.win_col_ptr, k.tmp_cols, w.win_cols);
+    if (g.nnz == 0) return FTC_OK;
+    hipLaunchKernelGGL(win_pack_kernel, dim3((g.nnz + 255) / 256), dim3(256), 0, s, g.nnz, g.row_ptr, w.blk_h,
+                       w.edge_to_row, w.win_col_ptr, k.tmp_cols, w.win_cols);
     return launch_status("build_windows pack");
 }
 

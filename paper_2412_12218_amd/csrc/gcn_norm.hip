@@ -28,6 +28,17 @@ __global__ __launch_bounds__(256) void gcn_vals_edges_kernel(int nnz, const int 
     vals[e] = inv_sqrt_deg(row_ptr, edge_to_row[e]) * inv_sqrt_deg(row_ptr, col_idx[e]);
 }
 
+// Same with the per-node factors already in memory: one 4-byte gather per endpoint.
+__global__ __launch_bounds__(256) void gcn_vals_edges_dinv_kernel(int nnz, const int *__restrict__ col_idx,
+                                                                  const int *__restrict__ edge_to_row,
+                                                                  const float *__restrict__ dinv,
+                                                                  float *__restrict__ vals)
+{
+    const int64_t e = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (e >= nnz) return;
+    vals[e] = dinv[edge_to_row[e]] * dinv[col_idx[e]];
+}
+
 // Without a window index: 16 lanes per row.
 __global__ __launch_bounds__(256) void gcn_vals_rows_kernel(int n, const int *__restrict__ row_ptr,
                                                             const int *__restrict__ col_idx,
@@ -49,7 +60,10 @@ int32_t launch_gcn_norm(const ftc_csr &g, const ftc_windows *w, float *vals, flo
         if (st != FTC_OK) return st;
     }
     if (vals && g.nnz > 0) {
-        if (w) {
+        if (w && dinv) {
+            hipLaunchKernelGGL(gcn_vals_edges_dinv_kernel, dim3((g.nnz + 255) / 256), dim3(256), 0, s, g.nnz,
+                               g.col_idx, w->edge_to_row, dinv, vals);
+        } else if (w) {
             hipLaunchKernelGGL(gcn_vals_edges_kernel, dim3((g.nnz + 255) / 256), dim3(256), 0, s, g.nnz,
                                g.row_ptr, g.col_idx, w->edge_to_row, vals);
         } else {

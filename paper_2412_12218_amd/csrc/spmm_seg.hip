@@ -249,10 +249,34 @@ __global__ __launch_bounds__(256) void spmm_seg_fixup_kernel(int n, int n_ranges
         const int r = carry_tail_row[v];
         if (r >= 0 && !(dense && dense[r >> 4])) {
             const int last = (row_ptr[r + 1] - 1) / SEG_R;  // wave range holding the row's final edge
-            for (int d = lane; d < D; d += 64) {
-                float sum = carry[(static_cast<size_t>(v) * 2 + 1) * DP + d];
-                for (int u = v + 1; u <= last; ++u) sum += carry[(static_cast<size_t>(u) * 2) * DP + d];
-                store_elem(out, static_cast<int64_t>(r) * ldo + d, odt, relu ? fmaxf(sum, 0.f) : sum);
+            // A hub row can span hundreds of ranges.  The 64 lanes are split into `parts` teams of
+            // `dl` lanes (one lane per feature); team p adds the head pieces of ranges v+1+p,
+            // v+1+p+parts, ... four at a time, then the teams' sums are added in team order.  The
+            // order is fixed by the shape alone, so the result is reproducible.
+            int dl = 1;
+            while (dl < D && dl < 64) dl <<= 1;
+            const int parts = 64 / dl;
+            const int part = lane / dl;
+            for (int d0 = 0; d0 < D; d0 += 64) {
+                const int d = d0 + lane % dl;
+                const bool dok = d < D;
+                const float *base = carry + (dok ? d : 0);
+                float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+                int u = v + 1 + part;
+                for (; u + 3 * parts <= last; u += 4 * parts) {
+                    const float a0 = base[(static_cast<size_t>(u) * 2) * DP];
+                    const float a1 = base[(static_cast<size_t>(u + parts) * 2) * DP];
+                    const float a2 = base[(static_cast<size_t>(u + 2 * parts) * 2) * DP];
+                    const float a3 = base[(static_cast<size_t>(u + 3 * parts) * 2) * DP];
+                    s0 += a0; s1 += a1; s2 += a2; s3 += a3;
+                }
+                for (; u <= last; u += parts) s0 += base[(static_cast<size_t>(u) * 2) * DP];
+                float sum = (s0 + s1) + (s2 + s3);
+                for (int off = 32; off >= dl; off >>= 1) sum += __shfl_down(sum, off, 64);
+                if (lane < dl && dok) {
+                    sum += carry[(static_cast<size_t>(v) * 2 + 1) * DP + d];
+                    store_elem(out, static_cast<int64_t>(r) * ldo + d, odt, relu ? fmaxf(sum, 0.f) : sum);
+                }
             }
         }
     }
