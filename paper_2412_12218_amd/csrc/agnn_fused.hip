@@ -9,6 +9,10 @@
 // and makes the pass single-sweep: numerator vector and denominator are plain segmented sums.
 // Safe while exp(-2|beta|) is a normal fp32 number (|beta| < 43).
 //
+// The row norms of the cosine are recomputed from the row slices that are in registers anyway
+// (a second DPP reduction in the lane group), so the pass needs no array of inverse norms and no
+// random 4-byte gather per edge.
+//
 // Work partition, run structure and the handling of rows cut by run / wave boundaries are
 // those of the edge-balanced SpMM (spmm_seg.hip): 512 edges per wave staged in LDS, groups of
 // LPR lanes walk contiguous runs, complete rows are stored from registers, cut rows are summed
@@ -54,8 +58,7 @@ size_t agnn_fused_ws(int nnz, int D)
 template <class T, int VEC, int LPR>
 __global__ __launch_bounds__(256) void agnn_fused_kernel(int nnz, int n_ranges, const int *__restrict__ col_idx,
                                                          const int *__restrict__ edge_to_row,
-                                                         const void *__restrict__ H, int ld, int D,
-                                                         const float *__restrict__ rinv, float beta,
+                                                         const void *__restrict__ H, int ld, int D, float beta,
                                                          void *__restrict__ out, int ldo, int odt,
                                                          float *__restrict__ carry, int *__restrict__ carry_tail_row)
 {
@@ -64,8 +67,8 @@ __global__ __launch_bounds__(256) void agnn_fused_kernel(int nnz, int n_ranges, 
     constexpr int RP = AG_R + NG;
     constexpr int DP = LPR * VEC;
     constexpr int DPZ = DP + 4;  // feature slots, then the denominator
-    static_assert(RUN % AG_B == 0, "runs are whole batches");
     constexpr int IDX_WORDS = 4 * 2 * RP;
+    static_assert(RUN % AG_B == 0, "runs are whole batches");
     constexpr int PART_WORDS = 4 * 2 * NG * DPZ;
     __shared__ int smem[IDX_WORDS > PART_WORDS ? IDX_WORDS : PART_WORDS];
     __shared__ int s_meta[4][3][NG];
@@ -108,7 +111,7 @@ __global__ __launch_bounds__(256) void agnn_fused_kernel(int nnz, int n_ranges, 
 
     auto direct_store = [&](int row) {
         if (live) {
-            const float inv = 1.f / z;
+            const float inv = __frcp_rn(z);
             float o[VEC];
 #pragma unroll
             for (int j = 0; j < VEC; ++j) o[j] = acc[j] * inv;
@@ -117,12 +120,13 @@ __global__ __launch_bounds__(256) void agnn_fused_kernel(int nnz, int n_ranges, 
     };
 
     // every group runs the same number of batches: the lane shuffles of the dot product need the
-    // whole wave; edges beyond the group's run are masked
+    // whole wave; edges beyond the group's run are masked.  (Issuing the next batch's gathers before
+    // consuming the current one was tried: the extra registers cost more occupancy than the
+    // overlap gains.)
     for (int b = rs; b < rs + RUN; b += AG_B) {
         int c[AG_B], r[AG_B];
         bool need[AG_B];
         RawVec<T, VEC> y[AG_B], xs[AG_B];
-        float rj[AG_B], rin[AG_B];
 #pragma unroll
         for (int k = 0; k < AG_B; ++k) {
             const bool ok = b + k < re;
@@ -142,8 +146,6 @@ __global__ __launch_bounds__(256) void agnn_fused_kernel(int nnz, int n_ranges, 
             else zero_raw(y[k]);
             if (need[k] && live) load_raw<T, VEC>(H, static_cast<int64_t>(r[k]) * ld + sub * VEC, xs[k]);
             else zero_raw(xs[k]);
-            rj[k] = c[k] >= 0 ? rinv[c[k]] : 0.f;
-            rin[k] = need[k] ? rinv[r[k]] : 0.f;
         }
 #pragma unroll
         for (int k = 0; k < AG_B; ++k) {
@@ -164,16 +166,25 @@ __global__ __launch_bounds__(256) void agnn_fused_kernel(int nnz, int n_ranges, 
                 for (int j = 0; j < VEC; ++j) acc[j] = 0.f;
                 z = 0.f;
                 unpack<T, VEC>(xs[k], xi);
-                ri = rin[k];
+                float q = 0.f;
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) q = fmaf(xi[j], xi[j], q);
+                q = ag_group_sum<LPR>(q);  // all lanes of the group are in this branch together
+                ri = __frsqrt_rn(fmaxf(q, 1e-24f));  // = 1 / max(||h_i||, 1e-12)
             }
             float yf[VEC];
             unpack<T, VEC>(y[k], yf);
-            float d = 0.f;
+            float d = 0.f, qj = 0.f;
 #pragma unroll
-            for (int j = 0; j < VEC; ++j) d = fmaf(xi[j], yf[j], d);
+            for (int j = 0; j < VEC; ++j) {
+                d = fmaf(xi[j], yf[j], d);
+                qj = fmaf(yf[j], yf[j], qj);
+            }
             d = ag_group_sum<LPR>(d);
+            qj = ag_group_sum<LPR>(qj);
             if (r[k] >= 0) {
-                const float wgt = __expf(beta * ri * rj[k] * d - absb);
+                const float rj = __frsqrt_rn(fmaxf(qj, 1e-24f));
+                const float wgt = __expf(beta * ri * rj * d - absb);
 #pragma unroll
                 for (int j = 0; j < VEC; ++j) acc[j] = fmaf(wgt, yf[j], acc[j]);
                 z += wgt;
@@ -328,13 +339,13 @@ __global__ __launch_bounds__(256) void agnn_fused_fixup_kernel(int n, int n_rang
 
 template <class T>
 static void launch_agnn_t(int vec, int lpr, unsigned grid, hipStream_t s, int nnz, int n_ranges, const ftc_csr &g,
-                          const int *e2r, const void *H, int ld, int D, const float *rinv, float beta, void *out,
+                          const int *e2r, const void *H, int ld, int D, float beta, void *out,
                           int ldo, int odt, float *carry, int *tail_row)
 {
     constexpr int VM = T::VEC;
 #define FTC_AG(V, L)                                                                                        \
     hipLaunchKernelGGL((agnn_fused_kernel<T, V, L>), dim3(grid), dim3(256), 0, s, nnz, n_ranges, g.col_idx, \
-                       e2r, H, ld, D, rinv, beta, out, ldo, odt, carry, tail_row)
+                       e2r, H, ld, D, beta, out, ldo, odt, carry, tail_row)
     if (vec == VM) {
         if (lpr == 4) FTC_AG(VM, 4);
         else if (lpr == 8) FTC_AG(VM, 8);
@@ -349,9 +360,9 @@ static void launch_agnn_t(int vec, int lpr, unsigned grid, hipStream_t s, int nn
 }
 
 // Caller has checked: window index present, seg_shape() accepts (dt, D), rows of H and out 16-byte
-// aligned, workspace of agnn_fused_ws() bytes, rinv filled.
+// aligned, workspace of agnn_fused_ws() bytes.
 int32_t launch_agnn_fused(const ftc_csr &g, const ftc_windows &w, const void *H, int ld, int dt, int D,
-                          const float *rinv, float beta, void *out, int ldo, int odt, void *ws, hipStream_t s)
+                          float beta, void *out, int ldo, int odt, void *ws, hipStream_t s)
 {
     int vec = 0, lpr = 0;
     seg_shape(dt, D, &vec, &lpr);
@@ -363,13 +374,13 @@ int32_t launch_agnn_fused(const ftc_csr &g, const ftc_windows &w, const void *H,
     if (n_ranges > 0) {
         const unsigned grid = static_cast<unsigned>((n_ranges + 3) / 4);
         if (dt == FTC_F32)
-            launch_agnn_t<F32>(vec, lpr, grid, s, g.nnz, n_ranges, g, w.edge_to_row, H, ld, D, rinv, beta, out, ldo,
+            launch_agnn_t<F32>(vec, lpr, grid, s, g.nnz, n_ranges, g, w.edge_to_row, H, ld, D, beta, out, ldo,
                                odt, carry, tail_row);
         else if (dt == FTC_F16)
-            launch_agnn_t<F16>(vec, lpr, grid, s, g.nnz, n_ranges, g, w.edge_to_row, H, ld, D, rinv, beta, out, ldo,
+            launch_agnn_t<F16>(vec, lpr, grid, s, g.nnz, n_ranges, g, w.edge_to_row, H, ld, D, beta, out, ldo,
                                odt, carry, tail_row);
         else
-            launch_agnn_t<BF16>(vec, lpr, grid, s, g.nnz, n_ranges, g, w.edge_to_row, H, ld, D, rinv, beta, out, ldo,
+            launch_agnn_t<BF16>(vec, lpr, grid, s, g.nnz, n_ranges, g, w.edge_to_row, H, ld, D, beta, out, ldo,
                                 odt, carry, tail_row);
         const int32_t st = launch_status("agnn_fused");
         if (st != FTC_OK) return st;

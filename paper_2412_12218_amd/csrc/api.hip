@@ -347,16 +347,16 @@ int32_t ftc_agnn_layer(const ftc_csr *g, const ftc_windows *w, const void *H, in
     char *p = static_cast<char *>(ws);
     float *rinv = reinterpret_cast<float *>(p);
     p += align_up(static_cast<size_t>(g->n) * sizeof(float), 256);
-    FTC_TRY(ftc_row_rnorm(g->n, H, ld, dtype, D, rinv, stream));
 
     // One pass over the edges when the probabilities are not asked for and the vector path applies.
     int vec, lpr;
     const bool rows16 = aligned16(H) && aligned16(out) && (static_cast<int64_t>(ld) * elem_size(dtype)) % 16 == 0 &&
                         (static_cast<int64_t>(ldo) * elem_size(out_dtype)) % 16 == 0;
     if (!edge_p && w && g->nnz > 0 && path != FTC_PATH_MFMA && rows16 && seg_shape(dtype, D, &vec, &lpr))
-        return launch_agnn_fused(*g, *w, H, ld, dtype, D, rinv, beta, out, ldo, out_dtype, p,
+        return launch_agnn_fused(*g, *w, H, ld, dtype, D, beta, out, ldo, out_dtype, p,
                                  static_cast<hipStream_t>(stream));
 
+    FTC_TRY(ftc_row_rnorm(g->n, H, ld, dtype, D, rinv, stream));
     float *scores = edge_p ? edge_p : reinterpret_cast<float *>(p);
     p += align_up(static_cast<size_t>(g->nnz) * sizeof(float), 256);
     const size_t sd = align_up(ftc_sddmm_workspace_bytes(g->n, g->nnz, D), 256);

@@ -44,7 +44,7 @@ int32_t launch_sddmm_edges(const ftc_csr &g, const ftc_windows &w, const void *X
                            hipStream_t s);
 size_t agnn_fused_ws(int nnz, int D);
 int32_t launch_agnn_fused(const ftc_csr &g, const ftc_windows &w, const void *H, int ld, int dt, int D,
-                          const float *rinv, float beta, void *out, int ldo, int odt, void *ws, hipStream_t s);
+                          float beta, void *out, int ldo, int odt, void *ws, hipStream_t s);
 bool mfma_shape_ok(int dtype, int D);
 int32_t launch_classify(const ftc_csr &g, const ftc_windows &w, float reuse, int max_edges, uint8_t *flags,
                         hipStream_t s);
