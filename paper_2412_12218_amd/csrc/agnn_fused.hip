@@ -100,9 +100,11 @@ __global__ __launch_bounds__(256) void agnn_fused_kernel(int nnz, int n_ranges, 
     const bool has = rs < n_valid;
     const bool live = sub * VEC < D;
     const float absb = fabsf(beta);
-    float acc[VEC], hacc[VEC], xi[VEC];
+    float acc[VEC], hacc[VEC];
 #pragma unroll
-    for (int j = 0; j < VEC; ++j) { acc[j] = 0.f; hacc[j] = 0.f; xi[j] = 0.f; }
+    for (int j = 0; j < VEC; ++j) { acc[j] = 0.f; hacc[j] = 0.f; }
+    RawVec<T, VEC> xi;  // slice of H[i,:] of the current row, as loaded
+    zero_raw(xi);
     float z = 0.f, hz = 0.f, ri = 0.f;
     bool have_head = false, head_closed = false, have_tail = false;
     int head_row = -1, cur = -1;
@@ -165,26 +167,17 @@ __global__ __launch_bounds__(256) void agnn_fused_kernel(int nnz, int n_ranges, 
 #pragma unroll
                 for (int j = 0; j < VEC; ++j) acc[j] = 0.f;
                 z = 0.f;
-                unpack<T, VEC>(xs[k], xi);
-                float q = 0.f;
-#pragma unroll
-                for (int j = 0; j < VEC; ++j) q = fmaf(xi[j], xi[j], q);
-                q = ag_group_sum<LPR>(q);  // all lanes of the group are in this branch together
+                xi = xs[k];
+                const float q = ag_group_sum<LPR>(dot_raw<T, VEC>(xi, xi, 0.f));  // the group's lanes branch together
                 ri = __frsqrt_rn(fmaxf(q, 1e-24f));  // = 1 / max(||h_i||, 1e-12)
             }
-            float yf[VEC];
-            unpack<T, VEC>(y[k], yf);
-            float d = 0.f, qj = 0.f;
-#pragma unroll
-            for (int j = 0; j < VEC; ++j) {
-                d = fmaf(xi[j], yf[j], d);
-                qj = fmaf(yf[j], yf[j], qj);
-            }
-            d = ag_group_sum<LPR>(d);
-            qj = ag_group_sum<LPR>(qj);
+            const float d = ag_group_sum<LPR>(dot_raw<T, VEC>(xi, y[k], 0.f));
+            const float qj = ag_group_sum<LPR>(dot_raw<T, VEC>(y[k], y[k], 0.f));
             if (r[k] >= 0) {
                 const float rj = __frsqrt_rn(fmaxf(qj, 1e-24f));
                 const float wgt = __expf(beta * ri * rj * d - absb);
+                float yf[VEC];
+                unpack<T, VEC>(y[k], yf);
 #pragma unroll
                 for (int j = 0; j < VEC; ++j) acc[j] = fmaf(wgt, yf[j], acc[j]);
                 z += wgt;

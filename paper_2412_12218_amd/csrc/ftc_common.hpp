@@ -188,6 +188,32 @@ __device__ __forceinline__ void unpack(const RawVec<T, NV> &r, float (&f)[NV])
     }
 }
 
+// acc + sum_k a[k] * b[k] on the packed representation.  16-bit types use the packed dot-product
+// instructions (v_dot2c_f32_f16 / v_dot2c_f32_bf16: two products per instruction, fp32 accumulate),
+// which also saves unpacking the operands.
+template <class T, int NV>
+__device__ __forceinline__ float dot_raw(const RawVec<T, NV> &a, const RawVec<T, NV> &b, float acc)
+{
+    if constexpr (T::BYTES == 4) {
+#pragma unroll
+        for (int k = 0; k < NV; ++k) acc = fmaf(__uint_as_float(a.w[k]), __uint_as_float(b.w[k]), acc);
+    } else {
+        static_assert(NV % 2 == 0, "packed dot products take pairs");
+        typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+        typedef __bf16 bhalf2v __attribute__((ext_vector_type(2)));
+#pragma unroll
+        for (int k = 0; k < NV / 2; ++k) {
+            if constexpr (std::is_same<T, F16>::value)
+                acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2v, a.w[k]), __builtin_bit_cast(half2v, b.w[k]),
+                                             acc, false);
+            else
+                acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bhalf2v, a.w[k]),
+                                                      __builtin_bit_cast(bhalf2v, b.w[k]), acc, false);
+        }
+    }
+    return acc;
+}
+
 template <class T, int NV>
 __device__ __forceinline__ void load_n(const void *base, int64_t idx, float (&f)[NV])
 {

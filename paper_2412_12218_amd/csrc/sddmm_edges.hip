@@ -77,9 +77,8 @@ __global__ __launch_bounds__(256) void sddmm_edges_kernel(int nnz, int n_ranges,
     const int rs0 = g * RUN;
     const int re = min(rs0 + RUN, n_valid);
     const bool live = sub * VEC < D;
-    float xi[VEC];
-#pragma unroll
-    for (int j = 0; j < VEC; ++j) xi[j] = 0.f;
+    RawVec<T, VEC> xi;  // slice of X[i,:] of the current row, as loaded
+    zero_raw(xi);
     int cur = -1;
     // every group runs the same number of batches so that the lane shuffles stay converged
     for (int b = rs0; b < rs0 + RUN; b += SD_B) {
@@ -108,13 +107,8 @@ __global__ __launch_bounds__(256) void sddmm_edges_kernel(int nnz, int n_ranges,
         }
 #pragma unroll
         for (int k = 0; k < SD_B; ++k) {
-            if (need[k]) unpack<T, VEC>(xs[k], xi);
-            float yf[VEC];
-            unpack<T, VEC>(y[k], yf);
-            float d = 0.f;
-#pragma unroll
-            for (int j = 0; j < VEC; ++j) d = fmaf(xi[j], yf[j], d);
-            d = group_sum_dpp<LPR>(d);
+            if (need[k]) xi = xs[k];
+            const float d = group_sum_dpp<LPR>(dot_raw<T, VEC>(xi, y[k], 0.f));
             if (sub == 0 && r[k] >= 0) s_dot[b + k + g] = d;
         }
         cur = prev;
