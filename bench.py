@@ -30,22 +30,23 @@ def alg_bytes(n, nnz, sum_uniq, n_win):
     rp = 4 * (n + 1)
     b = {}
     b["build_windows"] = nnz * 4 + rp + nnz * 8 + sum_uniq * 4 + n_win * 8
-    b["gcn_norm"] = rp + nnz * 4 + nnz * 4 + n * 4
+    b["gcn_norm"] = rp + n * 4   # factored normalisation: only dinv[n] is produced, no per-edge values
 
-    def gemm(di, do, o):
-        return n * di * e + di * do * e + n * do * o
+    def gemm(di, do, o, scaled=False):
+        return n * di * e + di * do * e + n * do * o + (n * 4 if scaled else 0)
 
     def spmm(d, e_in, o):
-        return sum_uniq * d * e_in + nnz * 8 + n * d * o + rp
+        # column index per edge, no edge values (the GCN layers use dinv), dinv[n] for the output scale
+        return sum_uniq * d * e_in + nnz * 4 + n * d * o + n * 4 + rp
 
     def sddmm(d):
         return sum_uniq * d * e + n * d * e + nnz * 8 + rp
 
-    # GCN layer = update GEMM (fp32 Z) + aggregation over Z
-    b["gcn_l1_gemm"] = gemm(128, 16, 4)
-    b["gcn_l1_spmm"] = spmm(16, 4, 2)
-    b["gcn_l2_gemm"] = gemm(16, 8, 4)
-    b["gcn_l2_spmm"] = spmm(8, 4, 4)
+    # GCN layer = update GEMM (fp16 Z, rows scaled by dinv) + aggregation over Z
+    b["gcn_l1_gemm"] = gemm(128, 16, 2, True)
+    b["gcn_l1_spmm"] = spmm(16, 2, 2)
+    b["gcn_l2_gemm"] = gemm(16, 8, 2, True)
+    b["gcn_l2_spmm"] = spmm(8, 2, 4)
     b["agnn_in_gemm"] = gemm(128, 32, 2)
     for l in range(4):
         # fused propagation layer: one gather per condensed column, own rows once, column index once,
@@ -239,9 +240,11 @@ def main():
         timed("build_windows", lambda: B._check(L.ftc_build_windows(
             C.byref(dg.c), C.byref(hp.win.c), B._ptr(hp.ws_win), C.c_size_t(hp.ws_win.numel()), B._stream())))
         timed("gcn_norm", lambda: B._check(L.ftc_gcn_norm(
-            C.byref(dg.c), C.byref(hp.win.c), B._ptr(hp.vals), B._ptr(hp.dinv), B._stream())))
-        timed("gcn_layer1", lambda: B.ftc_gcn_layer(dg, hp.win, hp.vals, X, W1, relu=True, out=hp.gcn_h, ws=hp.ws))
-        timed("gcn_layer2", lambda: B.ftc_gcn_layer(dg, hp.win, hp.vals, hp.gcn_h, W2, out=hp.gcn_out, ws=hp.ws))
+            C.byref(dg.c), C.byref(hp.win.c), None, B._ptr(hp.dinv), B._stream())))
+        timed("gcn_layer1", lambda: B.ftc_gcn_layer(dg, hp.win, None, X, W1, relu=True, out=hp.gcn_h, ws=hp.ws,
+                                                    dinv=hp.dinv))
+        timed("gcn_layer2", lambda: B.ftc_gcn_layer(dg, hp.win, None, hp.gcn_h, W2, out=hp.gcn_out, ws=hp.ws,
+                                                    dinv=hp.dinv))
         a, b = hp.agnn_h
         timed("agnn_in_gemm", lambda: B.ftc_update_gemm(X, Win, out=a, relu=True))
         for l in range(4):

@@ -126,14 +126,15 @@ int32_t ftc_gcn_norm(const ftc_csr *g, const ftc_windows *w, float *vals, float 
  * Sparse neighbour aggregation (Section V.A; SpMM C = A x B of Section I.A.2):
  *   out[i, 0:D] = sum over stored entries e of row i of vals[e] * X[col_idx[e], 0:D]
  * accumulated in fp32.  vals == NULL means all ones.  X has g->n rows of dtype x_dtype;
- * out has g->n rows of dtype out_dtype.  relu != 0 applies max(0, .) before the store.
+ * out has g->n rows of dtype out_dtype.  out_scale (n floats, may be NULL) multiplies output
+ * row i by out_scale[i]; relu != 0 then applies max(0, .) before the store.
  * w may be NULL (vector path on the CSR only).  `path` is an ftc_path.
  */
 size_t ftc_spmm_workspace_bytes(int32_t n, int32_t nnz, int32_t D);
 int32_t ftc_spmm(const ftc_csr *g, const ftc_windows *w, const float *vals, const void *X,
                  int32_t ldx, int32_t x_dtype, int32_t D, void *out, int32_t ldo,
-                 int32_t out_dtype, int32_t relu, int32_t path, void *ws, size_t ws_bytes,
-                 void *stream);
+                 int32_t out_dtype, const float *out_scale, int32_t relu, int32_t path, void *ws,
+                 size_t ws_bytes, void *stream);
 
 /*
  * Sparse edge feature computation (Section V.A; SDDMM D = A o (B x C) of Section I.A.2,
@@ -170,22 +171,27 @@ int32_t ftc_edge_softmax(const ftc_csr *g, const ftc_windows *w, const float *e_
 /*
  * Dense update phase (Section I.A.2): Z = X * W, X n x d_in (dtype), W d_in x d_out
  * row-major of the same dtype, fp32 accumulation, Z n x d_out of z_dtype.
- * d_in <= 256 and d_out <= 64.  relu != 0 applies max(0, .).
+ * d_in <= 256 and d_out <= 64.  row_scale (n floats, may be NULL) multiplies row i of the
+ * product by row_scale[i]; relu != 0 then applies max(0, .).
  */
 int32_t ftc_update_gemm(int32_t n, const void *X, int32_t ldx, int32_t dtype, int32_t d_in,
                         const void *W, int32_t d_out, void *Z, int32_t ldz, int32_t z_dtype,
-                        int32_t relu, void *stream);
+                        const float *row_scale, int32_t relu, void *stream);
 
 /*
  * GCN layer forward: out = act(A^ * (X * W)) with A^ given by (g, vals); update first,
  * then aggregation (Eq. 1-2 of Section I).  W is d_in x d_out row-major, same dtype as X.
  * The intermediate X * W lives in the workspace: fp16 for fp16 inputs, fp32 otherwise.
+ * dinv (n floats, may be NULL) selects the factored form of the symmetric normalisation:
+ * the edge values are dinv[i] * dinv[j], `vals` is ignored (may be NULL), row j of X * W is
+ * scaled by dinv[j] when it is written, the aggregation runs without edge values and output
+ * row i is scaled by dinv[i].  No per-edge value array is read then.
  */
 size_t ftc_gcn_layer_workspace_bytes(int32_t n, int32_t nnz, int32_t d_in, int32_t d_out);
-int32_t ftc_gcn_layer(const ftc_csr *g, const ftc_windows *w, const float *vals, const void *X,
-                      int32_t ldx, int32_t dtype, int32_t d_in, const void *W, int32_t d_out,
-                      int32_t relu, void *out, int32_t ldo, int32_t out_dtype, int32_t path,
-                      void *ws, size_t ws_bytes, void *stream);
+int32_t ftc_gcn_layer(const ftc_csr *g, const ftc_windows *w, const float *vals,
+                      const float *dinv, const void *X, int32_t ldx, int32_t dtype, int32_t d_in,
+                      const void *W, int32_t d_out, int32_t relu, void *out, int32_t ldo,
+                      int32_t out_dtype, int32_t path, void *ws, size_t ws_bytes, void *stream);
 
 /*
  * AGNN propagation layer forward: s_ij = beta * cos(h_i, h_j) on the stored entries,

@@ -20,12 +20,31 @@ FTC_OK, FTC_EINVAL, FTC_EUNSUPPORTED, FTC_EALIGN, FTC_EWORKSPACE, FTC_EHIP = 0, 
 
 _DTYPES = {torch.float32: FTC_F32, torch.float16: FTC_F16, torch.bfloat16: FTC_BF16}
 
-EXPORTS = ["ftc_version", "ftc_last_error", "ftc_validate_csr", "ftc_build_windows_workspace_bytes",
-           "ftc_build_windows", "ftc_gcn_norm", "ftc_spmm_workspace_bytes", "ftc_spmm",
-           "ftc_sddmm_workspace_bytes", "ftc_sddmm", "ftc_row_rnorm", "ftc_edge_softmax_workspace_bytes",
-           "ftc_edge_softmax",
-           "ftc_update_gemm", "ftc_gcn_layer_workspace_bytes", "ftc_gcn_layer",
-           "ftc_agnn_layer_workspace_bytes", "ftc_agnn_layer"]
+_I, _P, _Z, _F = C.c_int32, C.c_void_p, C.c_size_t, C.c_float
+
+# (restype, argtypes) of every export, in the order of include/ftc.h; with these set, ctypes
+# rejects a call with the wrong number of arguments instead of passing garbage.
+_SIGNATURES = {
+    "ftc_version": (_I, []),
+    "ftc_last_error": (C.c_char_p, []),
+    "ftc_validate_csr": (_I, [_P, _P, _P]),
+    "ftc_build_windows_workspace_bytes": (_Z, [_I, _I, _I, _I]),
+    "ftc_build_windows": (_I, [_P, _P, _P, _Z, _P]),
+    "ftc_gcn_norm": (_I, [_P, _P, _P, _P, _P]),
+    "ftc_spmm_workspace_bytes": (_Z, [_I, _I, _I]),
+    "ftc_spmm": (_I, [_P, _P, _P, _P, _I, _I, _I, _P, _I, _I, _P, _I, _I, _P, _Z, _P]),
+    "ftc_sddmm_workspace_bytes": (_Z, [_I, _I, _I]),
+    "ftc_sddmm": (_I, [_P, _P, _P, _P, _I, _I, _I, _P, _P, _F, _P, _I, _P, _Z, _P]),
+    "ftc_row_rnorm": (_I, [_I, _P, _I, _I, _I, _P, _P]),
+    "ftc_edge_softmax_workspace_bytes": (_Z, [_I, _I]),
+    "ftc_edge_softmax": (_I, [_P, _P, _P, _P, _P, _Z, _P]),
+    "ftc_update_gemm": (_I, [_I, _P, _I, _I, _I, _P, _I, _P, _I, _I, _P, _I, _P]),
+    "ftc_gcn_layer_workspace_bytes": (_Z, [_I, _I, _I, _I]),
+    "ftc_gcn_layer": (_I, [_P, _P, _P, _P, _P, _I, _I, _I, _P, _I, _I, _P, _I, _I, _I, _P, _Z, _P]),
+    "ftc_agnn_layer_workspace_bytes": (_Z, [_I, _I, _I]),
+    "ftc_agnn_layer": (_I, [_P, _P, _P, _I, _I, _I, _F, _P, _I, _I, _P, _I, _P, _Z, _P]),
+}
+EXPORTS = list(_SIGNATURES)
 
 
 class FtcError(RuntimeError):
@@ -56,13 +75,10 @@ def lib():
             raise FileNotFoundError(
                 f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'`")
         L = C.CDLL(LIB_PATH)
-        L.ftc_last_error.restype = C.c_char_p
-        for name in EXPORTS:
-            if name.endswith("_workspace_bytes"):
-                getattr(L, name).restype = C.c_size_t
-                nargs = {"ftc_build_windows_workspace_bytes": 4, "ftc_gcn_layer_workspace_bytes": 4,
-                         "ftc_edge_softmax_workspace_bytes": 2}.get(name, 3)
-                getattr(L, name).argtypes = [C.c_int32] * nargs
+        for name, (res, args) in _SIGNATURES.items():
+            fn = getattr(L, name)
+            fn.restype = res
+            fn.argtypes = args
         _lib = L
     return _lib
 
@@ -156,7 +172,8 @@ def ftc_gcn_norm(g, w=None, want_vals=True, want_dinv=True):
     return vals, dinv
 
 
-def ftc_spmm(g, w, vals, X, out=None, out_dtype=torch.float32, relu=False, path=FTC_PATH_AUTO, ws=None):
+def ftc_spmm(g, w, vals, X, out=None, out_dtype=torch.float32, relu=False, path=FTC_PATH_AUTO, ws=None,
+             out_scale=None):
     D = X.shape[1]
     if out is None:
         out = torch.empty((g.n, D), dtype=out_dtype, device=X.device)
@@ -164,8 +181,8 @@ def ftc_spmm(g, w, vals, X, out=None, out_dtype=torch.float32, relu=False, path=
         ws = _workspace(lib().ftc_spmm_workspace_bytes(g.n, g.nnz, D), X.device)
     _check(lib().ftc_spmm(C.byref(g.c), _wref(w), _ptr(vals), _ptr(X), C.c_int32(X.stride(0)),
                           C.c_int32(_dt(X)), C.c_int32(D), _ptr(out), C.c_int32(out.stride(0)),
-                          C.c_int32(_dt(out)), C.c_int32(1 if relu else 0), C.c_int32(path), _ptr(ws),
-                          C.c_size_t(ws.numel()), _stream()))
+                          C.c_int32(_dt(out)), _ptr(out_scale), C.c_int32(1 if relu else 0), C.c_int32(path),
+                          _ptr(ws), C.c_size_t(ws.numel()), _stream()))
     return out
 
 
@@ -201,7 +218,7 @@ def ftc_edge_softmax(g, w, e_in, out=None, ws=None):
     return out
 
 
-def ftc_update_gemm(X, W, out=None, out_dtype=torch.float32, relu=False):
+def ftc_update_gemm(X, W, out=None, out_dtype=torch.float32, relu=False, row_scale=None):
     n, d_in = X.shape
     d_out = W.shape[1]
     assert W.shape[0] == d_in and W.is_contiguous() and W.dtype == X.dtype
@@ -209,13 +226,13 @@ def ftc_update_gemm(X, W, out=None, out_dtype=torch.float32, relu=False):
         out = torch.empty((n, d_out), dtype=out_dtype, device=X.device)
     _check(lib().ftc_update_gemm(C.c_int32(n), _ptr(X), C.c_int32(X.stride(0)), C.c_int32(_dt(X)),
                                  C.c_int32(d_in), _ptr(W), C.c_int32(d_out), _ptr(out),
-                                 C.c_int32(out.stride(0)), C.c_int32(_dt(out)), C.c_int32(1 if relu else 0),
-                                 _stream()))
+                                 C.c_int32(out.stride(0)), C.c_int32(_dt(out)), _ptr(row_scale),
+                                 C.c_int32(1 if relu else 0), _stream()))
     return out
 
 
 def ftc_gcn_layer(g, w, vals, X, W, relu=False, out=None, out_dtype=torch.float32, path=FTC_PATH_AUTO,
-                  ws=None):
+                  ws=None, dinv=None):
     n, d_in = X.shape
     d_out = W.shape[1]
     assert W.shape[0] == d_in and W.is_contiguous() and W.dtype == X.dtype
@@ -223,7 +240,7 @@ def ftc_gcn_layer(g, w, vals, X, W, relu=False, out=None, out_dtype=torch.float3
         out = torch.empty((n, d_out), dtype=out_dtype, device=X.device)
     if ws is None:
         ws = _workspace(lib().ftc_gcn_layer_workspace_bytes(g.n, g.nnz, d_in, d_out), X.device)
-    _check(lib().ftc_gcn_layer(C.byref(g.c), _wref(w), _ptr(vals), _ptr(X), C.c_int32(X.stride(0)),
+    _check(lib().ftc_gcn_layer(C.byref(g.c), _wref(w), _ptr(vals), _ptr(dinv), _ptr(X), C.c_int32(X.stride(0)),
                                C.c_int32(_dt(X)), C.c_int32(d_in), _ptr(W), C.c_int32(d_out),
                                C.c_int32(1 if relu else 0), _ptr(out), C.c_int32(out.stride(0)),
                                C.c_int32(_dt(out)), C.c_int32(path), _ptr(ws), C.c_size_t(ws.numel()),

@@ -142,9 +142,10 @@ size_t ftc_spmm_workspace_bytes(int32_t n, int32_t nnz, int32_t D)
 }
 
 int32_t ftc_spmm(const ftc_csr *g, const ftc_windows *w, const float *vals, const void *X, int32_t ldx,
-                 int32_t x_dtype, int32_t D, void *out, int32_t ldo, int32_t out_dtype, int32_t relu,
-                 int32_t path, void *ws, size_t ws_bytes, void *stream)
+                 int32_t x_dtype, int32_t D, void *out, int32_t ldo, int32_t out_dtype, const float *out_scale,
+                 int32_t relu, int32_t path, void *ws, size_t ws_bytes, void *stream)
 {
+    const Epi epi{relu, out_scale};
     FTC_TRY(check_csr(g, "ftc_spmm"));
     if (g->n == 0) return FTC_OK;
     FTC_TRY(check_dense(X, ldx, x_dtype, D, "ftc_spmm", "X"));
@@ -177,11 +178,11 @@ int32_t ftc_spmm(const ftc_csr *g, const ftc_windows *w, const float *vals, cons
             flags = reinterpret_cast<uint8_t *>(static_cast<char *>(ws) + spmm_seg_ws(g->nnz, D));
             FTC_TRY(launch_classify(*g, *w, reuse, MFMA_MAX_WINDOW_EDGES, flags, hs));
         }
-        FTC_TRY(launch_spmm_seg(*g, *w, vals, X, ldx, x_dtype, D, out, ldo, out_dtype, relu, ws, flags, hs));
-        if (flags) return launch_spmm_mfma(*g, *w, vals, X, ldx, x_dtype, D, out, ldo, out_dtype, relu, flags, hs);
+        FTC_TRY(launch_spmm_seg(*g, *w, vals, X, ldx, x_dtype, D, out, ldo, out_dtype, epi, ws, flags, hs));
+        if (flags) return launch_spmm_mfma(*g, *w, vals, X, ldx, x_dtype, D, out, ldo, out_dtype, epi, flags, hs);
         return FTC_OK;
     }
-    return launch_spmm_rows(*g, vals, X, ldx, x_dtype, D, out, ldo, out_dtype, relu,
+    return launch_spmm_rows(*g, vals, X, ldx, x_dtype, D, out, ldo, out_dtype, epi,
                             static_cast<hipStream_t>(stream));
 }
 
@@ -267,7 +268,8 @@ int32_t ftc_edge_softmax(const ftc_csr *g, const ftc_windows *w, const float *e_
 }
 
 int32_t ftc_update_gemm(int32_t n, const void *X, int32_t ldx, int32_t dtype, int32_t d_in, const void *W,
-                        int32_t d_out, void *Z, int32_t ldz, int32_t z_dtype, int32_t relu, void *stream)
+                        int32_t d_out, void *Z, int32_t ldz, int32_t z_dtype, const float *row_scale, int32_t relu,
+                        void *stream)
 {
     if (n < 0) return fail(FTC_EINVAL, "ftc_update_gemm: negative n");
     if (n == 0) return FTC_OK;
@@ -276,7 +278,8 @@ int32_t ftc_update_gemm(int32_t n, const void *X, int32_t ldx, int32_t dtype, in
     if (!W) return fail(FTC_EINVAL, "ftc_update_gemm: W is NULL");
     if (d_in > 256 || d_out > 64) return fail(FTC_EUNSUPPORTED, "ftc_update_gemm: need d_in <= 256, d_out <= 64");
     if (Z == X) return fail(FTC_EINVAL, "ftc_update_gemm: Z aliases X");
-    return launch_gemm(n, X, ldx, dtype, d_in, W, d_out, Z, ldz, z_dtype, relu, static_cast<hipStream_t>(stream));
+    return launch_gemm(n, X, ldx, dtype, d_in, W, d_out, Z, ldz, z_dtype, Epi{relu, row_scale},
+                       static_cast<hipStream_t>(stream));
 }
 
 // The intermediate Z = X * W: fp16 when the inputs are fp16 (halves the gathered bytes; its rounding,
@@ -294,9 +297,10 @@ size_t ftc_gcn_layer_workspace_bytes(int32_t n, int32_t nnz, int32_t d_in, int32
     return align_up(static_cast<size_t>(n) * ldz * sizeof(float), 256) + ftc_spmm_workspace_bytes(n, nnz, d_out);
 }
 
-int32_t ftc_gcn_layer(const ftc_csr *g, const ftc_windows *w, const float *vals, const void *X, int32_t ldx,
-                      int32_t dtype, int32_t d_in, const void *W, int32_t d_out, int32_t relu, void *out,
-                      int32_t ldo, int32_t out_dtype, int32_t path, void *ws, size_t ws_bytes, void *stream)
+int32_t ftc_gcn_layer(const ftc_csr *g, const ftc_windows *w, const float *vals, const float *dinv,
+                      const void *X, int32_t ldx, int32_t dtype, int32_t d_in, const void *W, int32_t d_out,
+                      int32_t relu, void *out, int32_t ldo, int32_t out_dtype, int32_t path, void *ws,
+                      size_t ws_bytes, void *stream)
 {
     FTC_TRY(check_csr(g, "ftc_gcn_layer"));
     if (g->n == 0) return FTC_OK;
@@ -310,8 +314,10 @@ int32_t ftc_gcn_layer(const ftc_csr *g, const ftc_windows *w, const float *vals,
     const int ldz = z_ld(d_out, zdt);
     void *Z = ws;
     const size_t zbytes = align_up(static_cast<size_t>(g->n) * z_ld(d_out, FTC_F32) * sizeof(float), 256);
-    FTC_TRY(ftc_update_gemm(g->n, X, ldx, dtype, d_in, W, d_out, Z, ldz, zdt, 0, stream));
-    return ftc_spmm(g, w, vals, Z, ldz, zdt, d_out, out, ldo, out_dtype, relu, path,
+    // factored normalisation: rows of X*W are scaled by dinv[j] as they are written, the aggregation
+    // runs without edge values and scales output row i by dinv[i]
+    FTC_TRY(ftc_update_gemm(g->n, X, ldx, dtype, d_in, W, d_out, Z, ldz, zdt, dinv, 0, stream));
+    return ftc_spmm(g, w, dinv ? nullptr : vals, Z, ldz, zdt, d_out, out, ldo, out_dtype, dinv, relu, path,
                     static_cast<char *>(ws) + zbytes, ws_bytes - zbytes, stream);
 }
 
@@ -368,7 +374,7 @@ int32_t ftc_agnn_layer(const ftc_csr *g, const ftc_windows *w, const void *H, in
     const size_t rest = ws_bytes - static_cast<size_t>(p - static_cast<char *>(ws));
     FTC_TRY(ftc_sddmm(g, w, H, H, ld, dtype, D, rinv, rinv, beta, scores, path, ws_sddmm, sd, stream));
     FTC_TRY(ftc_edge_softmax(g, w, scores, scores, ws_softmax, sm, stream));
-    return ftc_spmm(g, w, scores, H, ld, dtype, D, out, ldo, out_dtype, 0, path, p, rest, stream);
+    return ftc_spmm(g, w, scores, H, ld, dtype, D, out, ldo, out_dtype, nullptr, 0, path, p, rest, stream);
 }
 
 }  // extern "C"

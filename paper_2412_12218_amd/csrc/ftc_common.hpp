@@ -20,9 +20,23 @@ inline int elem_size(int dtype) { return dtype == FTC_F32 ? 4 : 2; }
 inline bool valid_dtype(int d) { return d == FTC_F32 || d == FTC_F16 || d == FTC_BF16; }
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// Epilogue of the kernels that produce dense rows: out = act(scale[row] * value), scale optional.
+struct Epi {
+    int relu;
+    const float *scale;
+#if defined(__HIPCC__)
+    __device__ __forceinline__ float factor(int64_t row) const { return scale ? scale[row] : 1.f; }
+    __device__ __forceinline__ float apply(float f, float v) const
+    {
+        v *= f;
+        return relu ? fmaxf(v, 0.f) : v;
+    }
+#endif
+};
+
 // Entry points implemented in the individual .hip files (host launchers, no validation).
 int32_t launch_spmm_rows(const ftc_csr &g, const float *vals, const void *X, int ldx, int xdt, int D,
-                         void *out, int ldo, int odt, int relu, hipStream_t s);
+                         void *out, int ldo, int odt, Epi epi, hipStream_t s);
 int32_t launch_sddmm_rows(const ftc_csr &g, const void *X, const void *Y, int ld, int dt, int D,
                           const float *rs, const float *cs, float alpha, float *out, hipStream_t s);
 int32_t launch_softmax(const ftc_csr &g, const float *in, float *out, hipStream_t s);
@@ -31,13 +45,13 @@ int32_t launch_softmax_seg(const ftc_csr &g, const ftc_windows &w, const float *
                            hipStream_t s);
 int32_t launch_row_rnorm(int n, const void *H, int ld, int dt, int D, float *rinv, hipStream_t s);
 int32_t launch_gemm(int n, const void *X, int ldx, int dt, int d_in, const void *W, int d_out, void *Z,
-                    int ldz, int zdt, int relu, hipStream_t s);
+                    int ldz, int zdt, Epi epi, hipStream_t s);
 int32_t launch_gcn_norm(const ftc_csr &g, const ftc_windows *w, float *vals, float *dinv, hipStream_t s);
 int32_t launch_validate(const ftc_csr &g, int32_t *flag, hipStream_t s);
 bool seg_shape(int dtype, int D, int *vec, int *lpr);
 size_t spmm_seg_ws(int nnz, int D);
 int32_t launch_spmm_seg(const ftc_csr &g, const ftc_windows &w, const float *vals, const void *X, int ldx,
-                        int xdt, int D, void *out, int ldo, int odt, int relu, void *ws, const uint8_t *dense,
+                        int xdt, int D, void *out, int ldo, int odt, Epi epi, void *ws, const uint8_t *dense,
                         hipStream_t s);
 int32_t launch_sddmm_edges(const ftc_csr &g, const ftc_windows &w, const void *X, const void *Y, int ld, int dt,
                            int D, const float *rs, const float *cs, float alpha, float *out, const uint8_t *dense,
@@ -52,7 +66,7 @@ int32_t launch_sddmm_mfma(const ftc_csr &g, const ftc_windows &w, const void *X,
                           int D, const float *rs, const float *cs, float alpha, float *out, const uint8_t *flags,
                           hipStream_t s);
 int32_t launch_spmm_mfma(const ftc_csr &g, const ftc_windows &w, const float *vals, const void *X, int ldx, int dt,
-                         int D, void *out, int ldo, int odt, int relu, const uint8_t *flags, hipStream_t s);
+                         int D, void *out, int ldo, int odt, Epi epi, const uint8_t *flags, hipStream_t s);
 size_t build_windows_ws(int n, int nnz, int blk_h, int blk_w);
 int32_t launch_build_windows(const ftc_csr &g, ftc_windows &w, void *ws, size_t ws_bytes, hipStream_t s);
 

@@ -7,7 +7,7 @@ namespace ftc {
 template <class T, int DOUT>
 __global__ __launch_bounds__(256) void gemm_rows_kernel(int n, const void *__restrict__ X, int ldx, int d_in,
                                                         const void *__restrict__ W, int wdt, int d_out,
-                                                        void *__restrict__ Z, int ldz, int zdt, int relu)
+                                                        void *__restrict__ Z, int ldz, int zdt, Epi epi)
 {
     constexpr int V = T::VEC;
     extern __shared__ float Ws[];  // d_in x DOUT, zero padded beyond d_out
@@ -39,12 +39,12 @@ __global__ __launch_bounds__(256) void gemm_rows_kernel(int n, const void *__res
     }
 #pragma unroll
     for (int o = 0; o < DOUT; ++o)
-        if (o < d_out) store_elem(Z, row * ldz + o, zdt, relu ? fmaxf(acc[o], 0.f) : acc[o]);
+        if (o < d_out) store_elem(Z, row * ldz + o, zdt, epi.apply(epi.factor(row), acc[o]));
 }
 
 __global__ __launch_bounds__(256) void gemm_generic_kernel(int n, const void *X, int ldx, int dt, int d_in,
                                                            const void *W, int d_out, void *Z, int ldz,
-                                                           int zdt, int relu)
+                                                           int zdt, Epi epi)
 {
     const int64_t t = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
     if (t >= static_cast<int64_t>(n) * d_out) return;
@@ -53,7 +53,7 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(int n, const void *X,
     float acc = 0.f;
     for (int k = 0; k < d_in; ++k)
         acc = fmaf(load_elem(X, row * ldx + k, dt), load_elem(W, static_cast<int64_t>(k) * d_out + o, dt), acc);
-    store_elem(Z, row * ldz + o, zdt, relu ? fmaxf(acc, 0.f) : acc);
+    store_elem(Z, row * ldz + o, zdt, epi.apply(epi.factor(row), acc));
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -85,7 +85,7 @@ constexpr int GEMM_RT = 2;  // 16-row tiles per wave iteration
 template <class T, int KS, int NT>  // KS = ceil(d_in / 32), NT = ceil(d_out / 16)
 __global__ __launch_bounds__(256) void gemm_mfma_kernel(int n, const uint16_t *__restrict__ X, int ldx, int d_in,
                                                         const uint16_t *__restrict__ W, int d_out,
-                                                        void *__restrict__ Z, int ldz, int zdt, int relu,
+                                                        void *__restrict__ Z, int ldz, int zdt, Epi epi,
                                                         int n_tiles)
 {
     constexpr int KP = KS * 32 + 8;  // padded k extent of a W^T row (keeps 16-byte alignment, spreads banks)
@@ -130,7 +130,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int n, const uint16_t *_
                 for (int i = 0; i < 4; ++i) {
                     const int row = (tile0 + rt) * 16 + kb * 4 + i;
                     if (row < n && col < d_out)
-                        store_elem(Z, static_cast<int64_t>(row) * ldz + col, zdt, relu ? fmaxf(c[i], 0.f) : c[i]);
+                        store_elem(Z, static_cast<int64_t>(row) * ldz + col, zdt, epi.apply(epi.factor(row), c[i]));
                 }
             }
         }
@@ -139,7 +139,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int n, const uint16_t *_
 
 template <class T>
 static bool gemm_mfma_t(int n, const void *X, int ldx, int d_in, const void *W, int d_out, void *Z, int ldz,
-                        int zdt, int relu, hipStream_t s)
+                        int zdt, Epi epi, hipStream_t s)
 {
     const int ks = (d_in + 31) / 32, nt = (d_out + 15) / 16;
     const int n_tiles = (n + 15) / 16;
@@ -147,7 +147,7 @@ static bool gemm_mfma_t(int n, const void *X, int ldx, int d_in, const void *W, 
     if (grid > 256 * 8) grid = 256 * 8;
     const uint16_t *x = static_cast<const uint16_t *>(X);
     const uint16_t *w = static_cast<const uint16_t *>(W);
-#define FTC_G(K, N)                                                                                                 if (ks == K && nt == N) {                                                                                           hipLaunchKernelGGL((gemm_mfma_kernel<T, K, N>), dim3(grid), dim3(256), 0, s, n, x, ldx, d_in, w, d_out, Z,                            ldz, zdt, relu, n_tiles);                                                                    return true;                                                                                                }
+#define FTC_G(K, N)                                                                                                 if (ks == K && nt == N) {                                                                                           hipLaunchKernelGGL((gemm_mfma_kernel<T, K, N>), dim3(grid), dim3(256), 0, s, n, x, ldx, d_in, w, d_out, Z,                            ldz, zdt, epi, n_tiles);                                                                    return true;                                                                                                }
     FTC_G(1, 1) FTC_G(1, 2) FTC_G(2, 1) FTC_G(2, 2) FTC_G(4, 1) FTC_G(4, 2) FTC_G(4, 4) FTC_G(2, 4) FTC_G(1, 4)
     FTC_G(8, 1) FTC_G(8, 2) FTC_G(8, 4) FTC_G(3, 1) FTC_G(3, 2) FTC_G(3, 4)
 #undef FTC_G
@@ -156,14 +156,14 @@ static bool gemm_mfma_t(int n, const void *X, int ldx, int d_in, const void *W, 
 
 template <class T>
 static void gemm_t(int dpad, int n, const void *X, int ldx, int d_in, const void *W, int wdt, int d_out,
-                   void *Z, int ldz, int zdt, int relu, hipStream_t s)
+                   void *Z, int ldz, int zdt, Epi epi, hipStream_t s)
 {
     const unsigned grid = static_cast<unsigned>((static_cast<int64_t>(n) + 255) / 256);
     const size_t lds = static_cast<size_t>(d_in) * dpad * sizeof(float);
 #define FTC_CASE(P)                                                                                     \
     case P:                                                                                             \
         hipLaunchKernelGGL((gemm_rows_kernel<T, P>), dim3(grid), dim3(256), lds, s, n, X, ldx, d_in, W, \
-                           wdt, d_out, Z, ldz, zdt, relu);                                              \
+                           wdt, d_out, Z, ldz, zdt, epi);                                              \
         break;
     switch (dpad) {
         FTC_CASE(8)
@@ -175,7 +175,7 @@ static void gemm_t(int dpad, int n, const void *X, int ldx, int d_in, const void
 }
 
 int32_t launch_gemm(int n, const void *X, int ldx, int dt, int d_in, const void *W, int d_out, void *Z,
-                    int ldz, int zdt, int relu, hipStream_t s)
+                    int ldz, int zdt, Epi epi, hipStream_t s)
 {
     if (n == 0) return FTC_OK;
     const int v = dt == FTC_F32 ? 4 : 8;
@@ -185,18 +185,18 @@ int32_t launch_gemm(int n, const void *X, int ldx, int dt, int d_in, const void 
                       dpad <= 64 && static_cast<int64_t>(d_in) * dpad <= 8192;
     // 16-bit inputs: matrix cores (needs 16-byte row pieces of X)
     if (dt != FTC_F32 && aligned16(X) && (static_cast<int64_t>(ldx) * 2) % 16 == 0 && d_in % 8 == 0) {
-        const bool done = dt == FTC_F16 ? gemm_mfma_t<F16>(n, X, ldx, d_in, W, d_out, Z, ldz, zdt, relu, s)
-                                        : gemm_mfma_t<BF16>(n, X, ldx, d_in, W, d_out, Z, ldz, zdt, relu, s);
+        const bool done = dt == FTC_F16 ? gemm_mfma_t<F16>(n, X, ldx, d_in, W, d_out, Z, ldz, zdt, epi, s)
+                                        : gemm_mfma_t<BF16>(n, X, ldx, d_in, W, d_out, Z, ldz, zdt, epi, s);
         if (done) return launch_status("update_gemm mfma");
     }
     if (fast) {
-        if (dt == FTC_F32) gemm_t<F32>(dpad, n, X, ldx, d_in, W, dt, d_out, Z, ldz, zdt, relu, s);
-        else if (dt == FTC_F16) gemm_t<F16>(dpad, n, X, ldx, d_in, W, dt, d_out, Z, ldz, zdt, relu, s);
-        else gemm_t<BF16>(dpad, n, X, ldx, d_in, W, dt, d_out, Z, ldz, zdt, relu, s);
+        if (dt == FTC_F32) gemm_t<F32>(dpad, n, X, ldx, d_in, W, dt, d_out, Z, ldz, zdt, epi, s);
+        else if (dt == FTC_F16) gemm_t<F16>(dpad, n, X, ldx, d_in, W, dt, d_out, Z, ldz, zdt, epi, s);
+        else gemm_t<BF16>(dpad, n, X, ldx, d_in, W, dt, d_out, Z, ldz, zdt, epi, s);
     } else {
         const int64_t total = static_cast<int64_t>(n) * d_out;
         hipLaunchKernelGGL(gemm_generic_kernel, dim3(static_cast<unsigned>((total + 255) / 256)), dim3(256), 0,
-                           s, n, X, ldx, dt, d_in, W, d_out, Z, ldz, zdt, relu);
+                           s, n, X, ldx, dt, d_in, W, d_out, Z, ldz, zdt, epi);
     }
     return launch_status("update_gemm");
 }

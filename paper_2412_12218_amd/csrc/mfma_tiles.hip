@@ -160,7 +160,7 @@ __global__ __launch_bounds__(64) void spmm_mfma_kernel(int n, const int *__restr
                                                        const int *__restrict__ win_cols,
                                                        const float *__restrict__ vals,
                                                        const uint16_t *__restrict__ X, int ldx, int D,
-                                                       void *__restrict__ out, int ldo, int odt, int relu,
+                                                       void *__restrict__ out, int ldo, int odt, Epi epi,
                                                        const uint8_t *__restrict__ flags)
 {
     constexpr int DP = NT * 16 + 8;  // halves per staged row (16-byte pad)
@@ -233,7 +233,7 @@ __global__ __launch_bounds__(64) void spmm_mfma_kernel(int n, const int *__restr
             const int row = r0 + kb * 4 + i;
             if (row < n && col < D) {
                 const float v = acc[t][i] * scale;
-                store_elem(out, static_cast<int64_t>(row) * ldo + col, odt, relu ? fmaxf(v, 0.f) : v);
+                store_elem(out, static_cast<int64_t>(row) * ldo + col, odt, epi.apply(epi.factor(row), v));
             }
         }
     }
@@ -275,7 +275,7 @@ int32_t launch_sddmm_mfma(const ftc_csr &g, const ftc_windows &w, const void *X,
 }
 
 int32_t launch_spmm_mfma(const ftc_csr &g, const ftc_windows &w, const float *vals, const void *X, int ldx, int dt,
-                         int D, void *out, int ldo, int odt, int relu, const uint8_t *flags, hipStream_t s)
+                         int D, void *out, int ldo, int odt, Epi epi, const uint8_t *flags, hipStream_t s)
 {
     if (w.n_windows == 0) return FTC_OK;
     const int nt = (D + 15) / 16;
@@ -285,11 +285,11 @@ int32_t launch_spmm_mfma(const ftc_csr &g, const ftc_windows &w, const float *va
         if (dt == FTC_F16)                                                                                     \
             hipLaunchKernelGGL((spmm_mfma_kernel<F16, N>), dim3(w.n_windows), dim3(64), 0, s, g.n, g.row_ptr,  \
                                w.edge_to_row, w.edge_to_col, w.win_col_ptr, w.win_cols, vals, x, ldx, D, out,  \
-                               ldo, odt, relu, flags);                                              \
+                               ldo, odt, epi, flags);                                              \
         else                                                                                                   \
             hipLaunchKernelGGL((spmm_mfma_kernel<BF16, N>), dim3(w.n_windows), dim3(64), 0, s, g.n, g.row_ptr, \
                                w.edge_to_row, w.edge_to_col, w.win_col_ptr, w.win_cols, vals, x, ldx, D, out,  \
-                               ldo, odt, relu, flags);                                              \
+                               ldo, odt, epi, flags);                                              \
         break;
     switch (nt) {
         FTC_PM(1) FTC_PM(2) FTC_PM(3) FTC_PM(4) FTC_PM(6) FTC_PM(8) FTC_PM(12) FTC_PM(16)

@@ -12,7 +12,7 @@ __global__ __launch_bounds__(256) void spmm_rows_kernel(int n, const int *__rest
                                                         const int *__restrict__ col_idx,
                                                         const float *__restrict__ vals,
                                                         const void *__restrict__ X, int ldx, int D,
-                                                        void *__restrict__ out, int ldo, int odt, int relu)
+                                                        void *__restrict__ out, int ldo, int odt, Epi epi)
 {
     constexpr int V = T::VEC;
     constexpr int GROUPS = 256 / LPR;
@@ -50,10 +50,9 @@ __global__ __launch_bounds__(256) void spmm_rows_kernel(int n, const int *__rest
 #pragma unroll
             for (int k = 0; k < V; ++k) acc[k] = fmaf(a, x[k], acc[k]);
         }
-        if (relu) {
+        const float f = epi.factor(row);
 #pragma unroll
-            for (int k = 0; k < V; ++k) acc[k] = fmaxf(acc[k], 0.f);
-        }
+        for (int k = 0; k < V; ++k) acc[k] = epi.apply(f, acc[k]);
         store_vec<V>(out, row * ldo + sub * V, odt, acc);
     }
 }
@@ -63,7 +62,7 @@ __global__ __launch_bounds__(256) void spmm_generic_kernel(int n, const int *__r
                                                            const int *__restrict__ col_idx,
                                                            const float *__restrict__ vals, const void *X,
                                                            int ldx, int xdt, int D, void *out, int ldo,
-                                                           int odt, int relu)
+                                                           int odt, Epi epi)
 {
     const int64_t t = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
     if (t >= static_cast<int64_t>(n) * D) return;
@@ -72,20 +71,20 @@ __global__ __launch_bounds__(256) void spmm_generic_kernel(int n, const int *__r
     float acc = 0.f;
     for (int e = row_ptr[row]; e < row_ptr[row + 1]; ++e)
         acc = fmaf(vals ? vals[e] : 1.f, load_elem(X, static_cast<int64_t>(col_idx[e]) * ldx + k, xdt), acc);
-    if (relu) acc = fmaxf(acc, 0.f);
+    acc = epi.apply(epi.factor(row), acc);
     store_elem(out, row * ldo + k, odt, acc);
 }
 
 template <class T>
 static void launch_rows_t(int lpr, const ftc_csr &g, const float *vals, const void *X, int ldx, int D,
-                          void *out, int ldo, int odt, int relu, hipStream_t s)
+                          void *out, int ldo, int odt, Epi epi, hipStream_t s)
 {
 #define FTC_CASE(L)                                                                                  \
     case L: {                                                                                        \
         const int groups = 256 / L;                                                                  \
         const unsigned grid = static_cast<unsigned>((static_cast<int64_t>(g.n) + groups - 1) / groups); \
         hipLaunchKernelGGL((spmm_rows_kernel<T, L>), dim3(grid), dim3(256), 0, s, g.n, g.row_ptr,    \
-                           g.col_idx, vals, X, ldx, D, out, ldo, odt, relu);                        \
+                           g.col_idx, vals, X, ldx, D, out, ldo, odt, epi);                        \
     } break;
     switch (lpr) {
         FTC_CASE(1)
@@ -106,7 +105,7 @@ static bool vec_ok(const void *p, int ld, int dt, int D)
 }
 
 int32_t launch_spmm_rows(const ftc_csr &g, const float *vals, const void *X, int ldx, int xdt, int D,
-                         void *out, int ldo, int odt, int relu, hipStream_t s)
+                         void *out, int ldo, int odt, Epi epi, hipStream_t s)
 {
     if (g.n == 0) return FTC_OK;
     const int v = xdt == FTC_F32 ? 4 : 8;
@@ -115,14 +114,14 @@ int32_t launch_spmm_rows(const ftc_csr &g, const float *vals, const void *X, int
     if (vec_ok(X, ldx, xdt, D) && aligned16(out) && (static_cast<int64_t>(ldo) * elem_size(odt)) % 16 == 0) {
         int lpr = 1;
         while (lpr * v < D) lpr *= 2;
-        if (xdt == FTC_F32) launch_rows_t<F32>(lpr, g, vals, X, ldx, D, out, ldo, odt, relu, s);
-        else if (xdt == FTC_F16) launch_rows_t<F16>(lpr, g, vals, X, ldx, D, out, ldo, odt, relu, s);
-        else launch_rows_t<BF16>(lpr, g, vals, X, ldx, D, out, ldo, odt, relu, s);
+        if (xdt == FTC_F32) launch_rows_t<F32>(lpr, g, vals, X, ldx, D, out, ldo, odt, epi, s);
+        else if (xdt == FTC_F16) launch_rows_t<F16>(lpr, g, vals, X, ldx, D, out, ldo, odt, epi, s);
+        else launch_rows_t<BF16>(lpr, g, vals, X, ldx, D, out, ldo, odt, epi, s);
     } else {
         const int64_t total = static_cast<int64_t>(g.n) * D;
         const unsigned grid = static_cast<unsigned>((total + 255) / 256);
         hipLaunchKernelGGL(spmm_generic_kernel, dim3(grid), dim3(256), 0, s, g.n, g.row_ptr, g.col_idx, vals,
-                           X, ldx, xdt, D, out, ldo, odt, relu);
+                           X, ldx, xdt, D, out, ldo, odt, epi);
     }
     return launch_status("spmm_rows");
 }

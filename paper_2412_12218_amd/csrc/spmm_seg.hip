@@ -61,7 +61,7 @@ __global__ __launch_bounds__(256) void spmm_seg_kernel(int nnz, int n_ranges, co
                                                        const int *__restrict__ edge_to_row,
                                                        const float *__restrict__ vals,
                                                        const void *__restrict__ X, int ldx, int D,
-                                                       void *__restrict__ out, int ldo, int odt, int relu,
+                                                       void *__restrict__ out, int ldo, int odt, Epi epi,
                                                        float *__restrict__ carry, int *__restrict__ carry_tail_row,
                                                        const uint8_t *__restrict__ dense)
 {
@@ -114,8 +114,9 @@ __global__ __launch_bounds__(256) void spmm_seg_kernel(int nnz, int n_ranges, co
     auto direct_store = [&](int row) {
         if (live && !(dense && dense[row >> 4])) {
             float o[VEC];
+            const float f = epi.factor(row);
 #pragma unroll
-            for (int j = 0; j < VEC; ++j) o[j] = relu ? fmaxf(acc[j], 0.f) : acc[j];
+            for (int j = 0; j < VEC; ++j) o[j] = epi.apply(f, acc[j]);
             store_vec<VEC>(out, static_cast<int64_t>(row) * ldo + sub * VEC, odt, o);
         }
     };
@@ -215,7 +216,7 @@ __global__ __launch_bounds__(256) void spmm_seg_kernel(int nnz, int n_ranges, co
                         if (from_outside) carry[(static_cast<size_t>(v) * 2) * DP + d] = run;
                         else if (d < D && !(dense && dense[run_row >> 4]))
                             store_elem(out, static_cast<int64_t>(run_row) * ldo + d, odt,
-                                       relu ? fmaxf(run, 0.f) : run);
+                                       epi.apply(epi.factor(run_row), run));
                         run_row = -1;
                         from_outside = false;
                     }
@@ -241,7 +242,7 @@ __global__ __launch_bounds__(256) void spmm_seg_fixup_kernel(int n, int n_ranges
                                                              const float *__restrict__ carry,
                                                              const int *__restrict__ carry_tail_row, int DP,
                                                              int D, void *__restrict__ out, int ldo, int odt,
-                                                             int relu, const uint8_t *__restrict__ dense)
+                                                             Epi epi, const uint8_t *__restrict__ dense)
 {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int v = blockIdx.x * 4 + wave;
@@ -275,7 +276,7 @@ __global__ __launch_bounds__(256) void spmm_seg_fixup_kernel(int n, int n_ranges
                 for (int off = 32; off >= dl; off >>= 1) sum += __shfl_down(sum, off, 64);
                 if (lane < dl && dok) {
                     sum += carry[(static_cast<size_t>(v) * 2 + 1) * DP + d];
-                    store_elem(out, static_cast<int64_t>(r) * ldo + d, odt, relu ? fmaxf(sum, 0.f) : sum);
+                    store_elem(out, static_cast<int64_t>(r) * ldo + d, odt, epi.apply(epi.factor(r), sum));
                 }
             }
         }
@@ -288,12 +289,12 @@ __global__ __launch_bounds__(256) void spmm_seg_fixup_kernel(int n, int n_ranges
 template <class T>
 static void launch_seg_t(int vec, int lpr, unsigned grid, hipStream_t s, int nnz, int n_ranges,
                          const ftc_csr &g, const int *e2r, const float *vals, const void *X, int ldx, int D,
-                         void *out, int ldo, int odt, int relu, float *carry, int *tail_row, const uint8_t *dense)
+                         void *out, int ldo, int odt, Epi epi, float *carry, int *tail_row, const uint8_t *dense)
 {
     constexpr int VM = T::VEC;
 #define FTC_SEG(V, L)                                                                                     \
     hipLaunchKernelGGL((spmm_seg_kernel<T, V, L>), dim3(grid), dim3(256), 0, s, nnz, n_ranges, g.col_idx, \
-                       e2r, vals, X, ldx, D, out, ldo, odt, relu, carry, tail_row, dense)
+                       e2r, vals, X, ldx, D, out, ldo, odt, epi, carry, tail_row, dense)
     if (vec == VM) {
         if (lpr == 4) FTC_SEG(VM, 4);
         else if (lpr == 8) FTC_SEG(VM, 8);
@@ -310,7 +311,7 @@ static void launch_seg_t(int vec, int lpr, unsigned grid, hipStream_t s, int nnz
 // Caller has checked: window index present, seg_shape() accepts (xdt, D), X and out rows 16-byte
 // aligned, workspace of spmm_seg_ws() bytes.
 int32_t launch_spmm_seg(const ftc_csr &g, const ftc_windows &w, const float *vals, const void *X, int ldx,
-                        int xdt, int D, void *out, int ldo, int odt, int relu, void *ws, const uint8_t *dense,
+                        int xdt, int D, void *out, int ldo, int odt, Epi epi, void *ws, const uint8_t *dense,
                         hipStream_t s)
 {
     int vec = 0, lpr = 0;
@@ -324,13 +325,13 @@ int32_t launch_spmm_seg(const ftc_csr &g, const ftc_windows &w, const float *val
         const unsigned grid = static_cast<unsigned>((n_ranges + 3) / 4);
         if (xdt == FTC_F32)
             launch_seg_t<F32>(vec, lpr, grid, s, g.nnz, n_ranges, g, w.edge_to_row, vals, X, ldx, D, out, ldo,
-                              odt, relu, carry, tail_row, dense);
+                              odt, epi, carry, tail_row, dense);
         else if (xdt == FTC_F16)
             launch_seg_t<F16>(vec, lpr, grid, s, g.nnz, n_ranges, g, w.edge_to_row, vals, X, ldx, D, out, ldo,
-                              odt, relu, carry, tail_row, dense);
+                              odt, epi, carry, tail_row, dense);
         else
             launch_seg_t<BF16>(vec, lpr, grid, s, g.nnz, n_ranges, g, w.edge_to_row, vals, X, ldx, D, out, ldo,
-                               odt, relu, carry, tail_row, dense);
+                               odt, epi, carry, tail_row, dense);
         const int32_t st = launch_status("spmm_seg");
         if (st != FTC_OK) return st;
     }
@@ -338,7 +339,7 @@ int32_t launch_spmm_seg(const ftc_csr &g, const ftc_windows &w, const float *val
     const int64_t blocks_ranges = (n_ranges + 3) / 4;
     const unsigned grid2 = static_cast<unsigned>(blocks_rows > blocks_ranges ? blocks_rows : blocks_ranges);
     hipLaunchKernelGGL(spmm_seg_fixup_kernel, dim3(grid2), dim3(256), 0, s, g.n, n_ranges, g.row_ptr, carry,
-                       tail_row, dp, D, out, ldo, odt, relu, dense);
+                       tail_row, dp, D, out, ldo, odt, epi, dense);
     return launch_status("spmm_seg fixup");
 }
 

@@ -22,8 +22,7 @@ class HotPath:
         f32 = dict(dtype=torch.float32, device=dev)
         act = dict(dtype=act_dtype, device=dev)
         self.ws_win = B._workspace(L.ftc_build_windows_workspace_bytes(n, nnz, 16, 8), dev)
-        self.vals = torch.empty(nnz, **f32)
-        self.dinv = torch.empty(n, **f32)
+        self.dinv = torch.empty(n, **f32)    # the GCN layers take the factored normalisation: no per-edge values
         self.gcn_h = torch.empty((n, gcn_hidden), **act)
         self.gcn_out = torch.empty((n, n_out), **f32)
         ws_gcn = max(L.ftc_gcn_layer_workspace_bytes(n, nnz, d_feat, gcn_hidden),
@@ -37,14 +36,14 @@ class HotPath:
         g, w = self.g, self.win
         B._check(B.lib().ftc_build_windows(B.C.byref(g.c), B.C.byref(w.c), B._ptr(self.ws_win),
                                            B.C.c_size_t(self.ws_win.numel()), B._stream()))
-        B._check(B.lib().ftc_gcn_norm(B.C.byref(g.c), B.C.byref(w.c), B._ptr(self.vals), B._ptr(self.dinv),
+        B._check(B.lib().ftc_gcn_norm(B.C.byref(g.c), B.C.byref(w.c), None, B._ptr(self.dinv),
                                       B._stream()))
 
     def gcn(self, X, W1, W2):
-        B.ftc_gcn_layer(self.g, self.win, self.vals, X, W1, relu=True, out=self.gcn_h, path=self.path,
-                        ws=self.ws)
-        B.ftc_gcn_layer(self.g, self.win, self.vals, self.gcn_h, W2, relu=False, out=self.gcn_out,
-                        path=self.path, ws=self.ws)
+        B.ftc_gcn_layer(self.g, self.win, None, X, W1, relu=True, out=self.gcn_h, path=self.path,
+                        ws=self.ws, dinv=self.dinv)
+        B.ftc_gcn_layer(self.g, self.win, None, self.gcn_h, W2, relu=False, out=self.gcn_out,
+                        path=self.path, ws=self.ws, dinv=self.dinv)
         return self.gcn_out
 
     def agnn(self, X, W_in, W_out, betas):

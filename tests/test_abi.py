@@ -42,7 +42,7 @@ def test_null_graph_is_rejected_on_host():
     L = B.lib()
     z = C.c_size_t(0)
     i = C.c_int32(0)
-    assert L.ftc_spmm(None, None, None, None, i, i, i, None, i, i, i, i, None, z, None) == B.FTC_EINVAL
+    assert L.ftc_spmm(None, None, None, None, i, i, i, None, i, i, None, i, i, None, z, None) == B.FTC_EINVAL
     assert b"graph is NULL" in L.ftc_last_error()
     assert L.ftc_build_windows(None, None, None, z, None) == B.FTC_EINVAL
     assert L.ftc_edge_softmax(None, None, None, None, None, z, None) == B.FTC_EINVAL
@@ -57,20 +57,20 @@ def test_argument_validation_without_launch():
     I = C.c_int32
     # negative sizes
     bad = B.ftc_csr(-1, 0, 0x1000, 0)
-    assert L.ftc_spmm(C.byref(bad), None, None, fake, I(8), I(1), I(8), fake, I(8), I(0), I(0), I(0),
+    assert L.ftc_spmm(C.byref(bad), None, None, fake, I(8), I(1), I(8), fake, I(8), I(0), None, I(0), I(0),
                       None, z, None) == B.FTC_EINVAL
     # unknown dtype
-    assert L.ftc_spmm(C.byref(g), None, None, fake, I(8), I(7), I(8), C.c_void_p(0x3000), I(8), I(0), I(0),
-                      I(0), None, z, None) == B.FTC_EUNSUPPORTED
+    assert L.ftc_spmm(C.byref(g), None, None, fake, I(8), I(7), I(8), C.c_void_p(0x3000), I(8), I(0), None,
+                      I(0), I(0), None, z, None) == B.FTC_EUNSUPPORTED
     # ld < D
-    assert L.ftc_spmm(C.byref(g), None, None, fake, I(4), I(1), I(8), C.c_void_p(0x3000), I(8), I(0), I(0),
-                      I(0), None, z, None) == B.FTC_EINVAL
+    assert L.ftc_spmm(C.byref(g), None, None, fake, I(4), I(1), I(8), C.c_void_p(0x3000), I(8), I(0), None,
+                      I(0), I(0), None, z, None) == B.FTC_EINVAL
     # out aliases X
-    assert L.ftc_spmm(C.byref(g), None, None, fake, I(8), I(1), I(8), fake, I(8), I(1), I(0), I(0),
+    assert L.ftc_spmm(C.byref(g), None, None, fake, I(8), I(1), I(8), fake, I(8), I(1), None, I(0), I(0),
                       None, z, None) == B.FTC_EINVAL
     # unknown path
-    assert L.ftc_spmm(C.byref(g), None, None, fake, I(8), I(1), I(8), C.c_void_p(0x3000), I(8), I(0), I(0),
-                      I(9), None, z, None) == B.FTC_EINVAL
+    assert L.ftc_spmm(C.byref(g), None, None, fake, I(8), I(1), I(8), C.c_void_p(0x3000), I(8), I(0), None,
+                      I(0), I(9), None, z, None) == B.FTC_EINVAL
     # window descriptor inconsistent with n
     w = B.ftc_windows(16, 8, 5, 0x10, 0x20, 0x30, 0x40, 0x50, 0x60)
     assert L.ftc_build_windows(C.byref(g), C.byref(w), fake, C.c_size_t(1 << 30), None) == B.FTC_EINVAL
@@ -79,12 +79,20 @@ def test_argument_validation_without_launch():
     # workspace too small / missing
     w = B.ftc_windows(16, 8, 1, 0x10, 0x20, 0x30, 0x40, 0x50, 0x60)
     assert L.ftc_build_windows(C.byref(g), C.byref(w), fake, C.c_size_t(8), None) == B.FTC_EWORKSPACE
-    assert L.ftc_gcn_layer(C.byref(g), None, None, fake, I(8), I(1), I(8), fake, I(8), I(0), fake, I(8), I(0),
+    assert L.ftc_gcn_layer(C.byref(g), None, None, None, fake, I(8), I(1), I(8), fake, I(8), I(0), fake, I(8), I(0),
                            I(0), None, z, None) == B.FTC_EWORKSPACE
     assert b"workspace" in L.ftc_last_error()
     # gemm shape limits
-    assert L.ftc_update_gemm(I(4), fake, I(512), I(1), I(512), fake, I(8), C.c_void_p(0x3000), I(8), I(0), I(0),
-                             None) == B.FTC_EUNSUPPORTED
+    assert L.ftc_update_gemm(I(4), fake, I(512), I(1), I(512), fake, I(8), C.c_void_p(0x3000), I(8), I(0), None,
+                             I(0), None) == B.FTC_EUNSUPPORTED
+
+
+def test_wrong_argument_count_is_rejected_by_the_binding():
+    L = B.lib()
+    with pytest.raises(TypeError):
+        L.ftc_spmm(None, None)
+    with pytest.raises(TypeError):
+        L.ftc_gcn_layer(None, None, None)
 
 
 def test_workspace_queries_are_pure_and_monotone():

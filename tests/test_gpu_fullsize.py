@@ -26,6 +26,14 @@ def threads(oracle):
     oracle.set_threads(1)
 
 
+def factored_vals(g, oracle):
+    """fp32 dinv of the oracle and the fp64 products dinv[i] * dinv[j] of those fp32 numbers."""
+    _, dinv64 = oracle.gcn_norm(g.row_ptr, g.col_idx)
+    dinv32 = dinv64.astype(np.float32)
+    rows = np.repeat(np.arange(g.n), np.diff(g.row_ptr))
+    return dinv32, dinv32[rows].astype(np.float64) * dinv32[g.col_idx].astype(np.float64)
+
+
 def test_cfg2_gcn_layer_full(oracle, threads):
     g = synth.config_graph(2)
     say(f"cfg2 n={g.n} nnz={g.nnz}")
@@ -42,6 +50,13 @@ def test_cfg2_gcn_layer_full(oracle, threads):
     out = B.ftc_gcn_layer(dg, win, torch.from_numpy(vals32).cuda(), Xd, Wd)
     err = norm_err(out, ref, ab)
     say(f"  gcn_layer err {err:.3e}")
+    assert err < 2e-3
+    # factored normalisation (dinv instead of per-edge values)
+    dinv32, fvals64 = factored_vals(g, oracle)
+    ref, ab = oracle.gcn_layer(g.row_ptr, g.col_idx, fvals64, X64, W64)
+    out = B.ftc_gcn_layer(dg, win, None, Xd, Wd, dinv=torch.from_numpy(dinv32).cuda())
+    err = norm_err(out, ref, ab)
+    say(f"  gcn_layer (factored) err {err:.3e}")
     assert err < 2e-3
 
 
@@ -108,24 +123,24 @@ def test_cfg5_models_layer_by_layer(oracle, threads):
     torch.cuda.synchronize()
     check_windows(hp.win, oracle.build_windows(g.row_ptr, g.col_idx))
     say("  window index bit-exact")
-    vals64, dinv64 = oracle.gcn_norm(g.row_ptr, g.col_idx)
-    assert np.max(np.abs(hp.vals.cpu().double().numpy() - vals64) / vals64) < 1e-6
-    vals32 = vals64.astype(np.float32)
-    hp.vals.copy_(torch.from_numpy(vals32))          # both sides use the oracle's rounded values
+    _, dinv64 = oracle.gcn_norm(g.row_ptr, g.col_idx)
+    assert np.max(np.abs(hp.dinv.cpu().double().numpy() - dinv64) / dinv64) < 1e-6
+    dinv32, fvals64 = factored_vals(g, oracle)
+    hp.dinv.copy_(torch.from_numpy(dinv32))          # both sides use the oracle's rounded values
 
     def f16(x64):
         t = torch.from_numpy(x64).to(F16)
         return t.cuda(), t.double().numpy()
 
     # ---- GCN
-    ref1, ab1 = oracle.gcn_layer(g.row_ptr, g.col_idx, vals32.astype(np.float64), X64, W1, relu=True)
+    ref1, ab1 = oracle.gcn_layer(g.row_ptr, g.col_idx, fvals64, X64, W1, relu=True)
     chained = hp.gcn(Xd, W1d, W2d).clone()
     e1 = norm_err(hp.gcn_h, ref1, ab1, F16)
     say(f"  gcn layer 1 err {e1:.3e}")
     assert e1 < 2e-3
     h1d, h1 = f16(ref1)
-    ref2, ab2 = oracle.gcn_layer(g.row_ptr, g.col_idx, vals32.astype(np.float64), h1, W2)
-    out2 = B.ftc_gcn_layer(dg, hp.win, hp.vals, h1d, W2d, ws=hp.ws)
+    ref2, ab2 = oracle.gcn_layer(g.row_ptr, g.col_idx, fvals64, h1, W2)
+    out2 = B.ftc_gcn_layer(dg, hp.win, None, h1d, W2d, ws=hp.ws, dinv=hp.dinv)
     e2 = norm_err(out2, ref2, ab2)
     say(f"  gcn layer 2 err {e2:.3e}; chained end-to-end err {norm_err(chained, ref2, ab2):.3e}")
     assert e2 < 2e-3

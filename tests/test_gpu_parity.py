@@ -388,6 +388,70 @@ def test_gcn_layer(oracle, graphs, name, dtype, d_in, d_out, relu):
     assert err < TOL[dtype]
 
 
+@pytest.mark.parametrize("name,dtype,d_in,d_out", [("cfg1", F32, 16, 16), ("cfg2s", F16, 128, 32),
+                                                   ("cfg5s", F16, 128, 16), ("cfg5s", F16, 16, 8),
+                                                   ("hub", BF16, 64, 24), ("mixed", F16, 32, 64)])
+@pytest.mark.parametrize("relu", [False, True])
+@pytest.mark.parametrize("path", [B.FTC_PATH_AUTO, B.FTC_PATH_MFMA])
+def test_gcn_layer_factored(oracle, graphs, name, dtype, d_in, d_out, relu, path):
+    """Factored normalisation: the layer gets dinv instead of per-edge values; the oracle gets the
+    products dinv[i] * dinv[j] of the same fp32 numbers."""
+    g = graphs[name]
+    if path == B.FTC_PATH_MFMA and dtype != F16:
+        pytest.skip("the intermediate X*W is fp32 for these inputs; the matrix-core path is 16-bit only")
+    say(f"gcn_layer factored {name} {dtype} {d_in}->{d_out} relu={relu} path={path}")
+    _, dinv64 = oracle.gcn_norm(g.row_ptr, g.col_idx)
+    dinv32 = np.nan_to_num(dinv64, posinf=0.0).astype(np.float32)
+    rows = np.repeat(np.arange(g.n), np.diff(g.row_ptr))
+    vals64 = dinv32[rows].astype(np.float64) * dinv32[g.col_idx].astype(np.float64)
+    Xd, X64 = quantise(synth.uniform_features(g.n, d_in, seed=9), dtype)
+    Wd, W64 = quantise(synth.glorot_uniform(d_in, d_out, seed=10), dtype)
+    ref, ab = oracle.gcn_layer(g.row_ptr, g.col_idx, vals64, X64, W64, relu=relu)
+    dg = dev_graph(g)
+    win = B.ftc_build_windows(dg)
+    out = B.ftc_gcn_layer(dg, win, None, Xd, Wd, relu=relu, dinv=torch.from_numpy(dinv32).cuda(), path=path)
+    err = norm_err(out, ref, ab)
+    say(f"  err {err:.3e}")
+    assert err < TOL[dtype]
+    out_nw = B.ftc_gcn_layer(dg, None, None, Xd, Wd, relu=relu, dinv=torch.from_numpy(dinv32).cuda())
+    assert norm_err(out_nw, ref, ab) < TOL[dtype]
+
+
+@pytest.mark.parametrize("name", ["cfg1", "hub", "mixed"])
+@pytest.mark.parametrize("dtype,D", [(F16, 32), (F32, 16), (BF16, 24), (F16, 5)])
+@pytest.mark.parametrize("path", [B.FTC_PATH_AUTO, B.FTC_PATH_MFMA, B.FTC_PATH_VALU])
+def test_spmm_out_scale(oracle, graphs, name, dtype, D, path):
+    """out_scale multiplies output row i before the ReLU (negative factors flip what survives)."""
+    g = graphs[name]
+    if path == B.FTC_PATH_MFMA and (dtype == F32 or D % 8):
+        pytest.skip("matrix-core path needs 16-bit rows of 16-byte pieces")
+    rng = np.random.default_rng(31)
+    Xd, X64 = quantise(rng.uniform(-1, 1, size=(g.n, D)).astype(np.float32), dtype)
+    vals32 = rng.uniform(-1, 1, size=g.nnz).astype(np.float32)
+    sc32 = rng.uniform(-2, 2, size=g.n).astype(np.float32)
+    ref, ab = oracle.spmm(g.row_ptr, g.col_idx, vals32.astype(np.float64), X64)
+    ref = np.maximum(ref * sc32.astype(np.float64)[:, None], 0)
+    ab = ab * np.abs(sc32.astype(np.float64))[:, None]
+    dg = dev_graph(g)
+    for win in (B.ftc_build_windows(dg), None):
+        out = B.ftc_spmm(dg, win, torch.from_numpy(vals32).cuda(), Xd, relu=True, path=path if win else 0,
+                         out_scale=torch.from_numpy(sc32).cuda())
+        assert norm_err(out, ref, ab) < TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype,d_in,d_out", [(F16, 128, 16), (BF16, 64, 64), (F32, 16, 8), (F16, 20, 5)])
+def test_update_gemm_row_scale(oracle, dtype, d_in, d_out):
+    n = 2000 + 5
+    Xd, X64 = quantise(synth.uniform_features(n, d_in, seed=7), dtype)
+    Wd, W64 = quantise(synth.glorot_uniform(d_in, d_out, seed=8), dtype)
+    sc32 = np.random.default_rng(32).uniform(-2, 2, size=n).astype(np.float32)
+    ref, ab = oracle.gemm(X64, W64)
+    ref = np.maximum(ref * sc32.astype(np.float64)[:, None], 0)
+    ab = ab * np.abs(sc32.astype(np.float64))[:, None]
+    Z = B.ftc_update_gemm(Xd, Wd, relu=True, row_scale=torch.from_numpy(sc32).cuda())
+    assert norm_err(Z, ref, ab) < TOL[dtype]
+
+
 @pytest.mark.parametrize("name,dtype,D", [("cfg1", F32, 16), ("cfg3s", F16, 32), ("cfg5s", F16, 32),
                                           ("cfg4s", BF16, 64), ("hub", F16, 8), ("hub", F16, 128),
                                           ("mixed", BF16, 16), ("cfg5s", F32, 32), ("hub", F16, 24)])
