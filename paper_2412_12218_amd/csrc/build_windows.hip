@@ -1,17 +1,21 @@
 // Sparse graph transformation (Section V.A) on the GPU.
 //
-// Every row window is independent (the paper parallelises the same step over CPU threads), so
-// one wave or one workgroup condenses one window; which one depends on the window's edge count:
+// Every row window is independent (the paper parallelises the same step over CPU threads).  How
+// a window is condensed depends on its edge count, because power-law graphs have windows of a
+// few edges next to windows of 10^5:
 //   1. up to WAVE_CAP edges (almost every window): one wave sorts the column ids in registers
 //      with a bitonic network (lane shuffles, no barriers), de-duplicates with a flag scan and
 //      finds every edge's rank by binary search in the unique list parked in LDS;
-//   2. larger windows (hub rows of power-law graphs) are queued and condensed by a 1024-thread
-//      workgroup with a bitmap of 2^20 column ids held in LDS (128 KiB of the CU's 160 KiB):
-//      set bits, prefix sums of popcounts per group of 8 words, rank = group prefix + popcounts
-//      up to the column's bit.  Graphs with more than 2^20 nodes take several passes over
-//      successive column ranges; a pass whose range holds none of the window's columns costs
-//      only the scan of the window's edges.
-// Both also write edge_to_row for their window's edges.
+//   2. up to the hub threshold: one workgroup per window walks the column space in ranges of
+//      2^RL ids with a bitmap of one range in LDS: set bits, prefix sums of the words'
+//      popcounts, rank = word prefix + popcount below the column's bit.  The bitmap is small
+//      (16 KiB for 2^17 ids) so that several workgroups share a CU and hide each other's
+//      latencies; the window's column ids stay in registers between the passes when they fit;
+//   3. hub windows (more edges than the threshold, at most HUB_SLOTS_MAX of them by the choice
+//      of the threshold): edge-parallel over the whole GPU with one bitmap of n bits per hub in
+//      global memory: set bits (atomics), one workgroup per hub turns popcounts into prefixes
+//      and emits the unique list, then every edge reads its rank.
+// All of them also write edge_to_row for their window's edges.
 // The unique lists are first written at the window's edge offset of a temporary array (a
 // window never has more distinct columns than edges), then a scan over the windows gives
 // win_col_ptr / block_partition / summary and a last kernel packs the lists into win_cols.
@@ -19,28 +23,51 @@
 
 namespace ftc {
 
-constexpr int WAVE_CAP = 1024;       // edges per window sorted by a single wave in registers
-constexpr int BIG_THREADS = 1024;    // workgroup of the bitmap kernel
-constexpr int RANGE_LOG2 = 20;       // column ids per bitmap pass
-constexpr int RANGE_WORDS = (1 << RANGE_LOG2) / 32;
-constexpr int GROUP_WORDS = 8;       // bitmap words per prefix entry
-constexpr int N_GROUPS = RANGE_WORDS / GROUP_WORDS;
-constexpr int BIG_GRID = 256;        // persistent workgroups, one per CU
-constexpr int TOUCH_WORDS = RANGE_WORDS / 32;  // one bit per bitmap word: which words hold any bit
-constexpr size_t BIG_LDS_BYTES = sizeof(uint32_t) * (RANGE_WORDS + N_GROUPS + TOUCH_WORDS);
-static_assert(TOUCH_WORDS == BIG_THREADS, "one coarse word per thread");
+constexpr int WAVE_CAP = 1024;      // edges per window sorted by a single wave in registers
+constexpr int MID_CAP = 4096;       // edges per window condensed by a 256-thread workgroup
+constexpr int HUB_MIN_EDGES = 16384;
+constexpr int HUB_SLOTS_MAX = 1024; // hub windows handled at once (one thread each in the planning kernel)
+constexpr int HUB_CHUNK = 4096;     // edges per work item of the edge-parallel hub kernels
+constexpr int HUB_GROUP = 8;        // bitmap words per stored prefix (one 32-byte load)
+constexpr int HUB_GRID = 2048;      // workgroups of the edge-parallel hub kernels (grid-stride over chunks)
+constexpr int N_CU = 256;           // compute units: the persistent grids are multiples of it
+
+enum { C_MID = 0, C_LARGE = 1, C_HUB = 2, C_CHUNKS = 3, C_MID_NEXT = 4, C_LARGE_NEXT = 5, C_WORDS = 8 };
+
+// A window is a hub when it has more edges than this.  The three terms keep (a) small windows in
+// LDS, (b) a hub's bitmap (n / 8 bytes) below four bytes per edge of the hub, (c) the number of
+// hubs at or below HUB_SLOTS_MAX.
+static int hub_threshold(int n, int nnz)
+{
+    int t = HUB_MIN_EDGES;
+    if ((n + 31) / 32 > t) t = (n + 31) / 32;
+    const int by_slots = static_cast<int>((static_cast<int64_t>(nnz) + HUB_SLOTS_MAX - 1) / HUB_SLOTS_MAX);
+    return by_slots > t ? by_slots : t;
+}
+static int hub_slots(int n, int nnz)
+{
+    const int s = nnz / hub_threshold(n, nnz);  // more than this many windows above the threshold cannot exist
+    return s < 1 ? 1 : s;
+}
+static int hub_words_per_slot(int n) { return ((n + 31) / 32 + HUB_GROUP - 1) / HUB_GROUP * HUB_GROUP; }
 
 struct WinWorkspace {
-    int *uniq_count;  // [n_windows]
-    int *big_list;    // [n_windows]
-    int *big_count;   // [2]
-    int *tmp_cols;    // [nnz]
+    int *uniq_count;      // [n_windows]
+    int *list_mid;        // [cap_mid]    windows of WAVE_CAP+1 .. MID_CAP edges
+    int *list_large;      // [cap_large]  windows of MID_CAP+1 .. threshold edges
+    int *list_hub;        // [slots]
+    int *counters;        // [C_WORDS]
+    int *hub_chunk_ptr;   // [slots + 1]  first work item of every hub
+    int *chunk_table;     // [nnz / HUB_CHUNK + slots + 1]  hub slot of every work item
+    uint32_t *hub_bits;   // [slots * words_per_slot]
+    int *hub_grp;         // [slots * words_per_slot / HUB_GROUP]
+    int *tmp_cols;        // [nnz]
+    int cap_mid, cap_large, slots, wps;
     size_t total;
 };
 
 static WinWorkspace carve(void *ws, int n, int nnz, int n_windows)
 {
-    (void)n;
     WinWorkspace w;
     char *p = static_cast<char *>(ws);
     size_t off = 0;
@@ -49,9 +76,19 @@ static WinWorkspace carve(void *ws, int n, int nnz, int n_windows)
         off += align_up(bytes, 256);
         return q;
     };
+    w.cap_mid = nnz / (WAVE_CAP + 1) + 1 < n_windows ? nnz / (WAVE_CAP + 1) + 1 : n_windows;
+    w.cap_large = nnz / (MID_CAP + 1) + 1 < n_windows ? nnz / (MID_CAP + 1) + 1 : n_windows;
+    w.slots = hub_slots(n, nnz);
+    w.wps = hub_words_per_slot(n);
     w.uniq_count = reinterpret_cast<int *>(take(sizeof(int) * static_cast<size_t>(n_windows)));
-    w.big_list = reinterpret_cast<int *>(take(sizeof(int) * static_cast<size_t>(n_windows)));
-    w.big_count = reinterpret_cast<int *>(take(2 * sizeof(int)));  // queue length, next entry to hand out
+    w.list_mid = reinterpret_cast<int *>(take(sizeof(int) * static_cast<size_t>(w.cap_mid)));
+    w.list_large = reinterpret_cast<int *>(take(sizeof(int) * static_cast<size_t>(w.cap_large)));
+    w.list_hub = reinterpret_cast<int *>(take(sizeof(int) * static_cast<size_t>(w.slots)));
+    w.counters = reinterpret_cast<int *>(take(sizeof(int) * C_WORDS));
+    w.hub_chunk_ptr = reinterpret_cast<int *>(take(sizeof(int) * static_cast<size_t>(w.slots + 1)));
+    w.chunk_table = reinterpret_cast<int *>(take(sizeof(int) * static_cast<size_t>(nnz / HUB_CHUNK + w.slots + 1)));
+    w.hub_bits = reinterpret_cast<uint32_t *>(take(sizeof(uint32_t) * static_cast<size_t>(w.slots) * w.wps));
+    w.hub_grp = reinterpret_cast<int *>(take(sizeof(int) * static_cast<size_t>(w.slots) * (w.wps / HUB_GROUP)));
     w.tmp_cols = reinterpret_cast<int *>(take(sizeof(int) * static_cast<size_t>(nnz)));
     w.total = off;
     return w;
@@ -93,7 +130,21 @@ __device__ __forceinline__ int block_exclusive_scan(int v, int *tmp, int *total)
     return tmp[wave] + incl - v;
 }
 
-__global__ void win_clear_kernel(int *counters) { counters[0] = 0; counters[1] = 0; }
+__global__ void win_clear_kernel(int *counters)
+{
+    if (threadIdx.x < C_WORDS) counters[threadIdx.x] = 0;
+}
+
+// Index of the row that holds edge e: last a in [0, rows) with rp[a] <= e.
+__device__ __forceinline__ int row_of_edge(const int *rp, int rows, int e)
+{
+    int a = 0, b = rows;
+    while (b - a > 1) {
+        const int mid = (a + b) >> 1;
+        if (rp[mid] <= e) a = mid; else b = mid;
+    }
+    return a;
+}
 
 // ---- windows of at most WAVE_CAP edges: one wave, keys in registers --------------------------------
 // Element i of the padded key array lives in lane i / E, register i % E.
@@ -200,10 +251,11 @@ __device__ __forceinline__ void condense_window_wave(int w, int r0, int rows, co
 
 __global__ __launch_bounds__(64) void win_wave_kernel(int n, const int *__restrict__ row_ptr,
                                                       const int *__restrict__ col_idx, int blk_h,
-                                                      int *__restrict__ edge_to_row,
+                                                      int hub_thr, int *__restrict__ edge_to_row,
                                                       int *__restrict__ edge_to_col,
                                                       int *__restrict__ uniq_count, int *__restrict__ tmp_cols,
-                                                      int *__restrict__ big_list, int *big_count)
+                                                      int *__restrict__ list_mid, int *__restrict__ list_large,
+                                                      int *__restrict__ list_hub, int *counters)
 {
     __shared__ int uniq_lds[WAVE_CAP];
     __shared__ int rp[65];
@@ -213,8 +265,12 @@ __global__ __launch_bounds__(64) void win_wave_kernel(int n, const int *__restri
     for (int t = threadIdx.x; t <= rows; t += 64) rp[t] = row_ptr[r0 + t];
     __syncthreads();
     const int cnt = rp[rows] - rp[0];
-    if (cnt > WAVE_CAP) {  // queued for the bitmap kernel
-        if (threadIdx.x == 0) big_list[atomicAdd(big_count, 1)] = w;
+    if (cnt > WAVE_CAP) {  // queued for the workgroup kernels, by size class
+        if (threadIdx.x == 0) {
+            if (cnt <= MID_CAP) list_mid[atomicAdd(&counters[C_MID], 1)] = w;
+            else if (cnt <= hub_thr) list_large[atomicAdd(&counters[C_LARGE], 1)] = w;
+            else list_hub[atomicAdd(&counters[C_HUB], 1)] = w;
+        }
         return;
     }
     if (cnt == 0) {
@@ -231,184 +287,463 @@ __global__ __launch_bounds__(64) void win_wave_kernel(int n, const int *__restri
 }
 
 
-// ---- queued windows: bitmap of 2^20 column ids in LDS ----------------------------------------------
-__global__ __launch_bounds__(BIG_THREADS) void win_bitmap_kernel(int n, const int *__restrict__ row_ptr,
-                                                                 const int *__restrict__ col_idx, int blk_h,
-                                                                 int *__restrict__ edge_to_row,
-                                                                 int *__restrict__ edge_to_col,
-                                                                 int *__restrict__ uniq_count,
-                                                                 int *__restrict__ tmp_cols,
-                                                                 const int *__restrict__ big_list,
-                                                                 int *big_count)
+// ---- queued windows below the hub threshold: two-level bitmap in LDS ------------------------------
+// A window of c edges touches at most c of the n / 32 bitmap words of the column space, so the
+// bitmap is kept compact.  Per range of 2^CRANGE_LOG2 column ids:
+//   A. a coarse bitmap with one bit per 32-column word says which words the window touches;
+//   B. prefix sums of its popcounts number the touched words in ascending order ("slots");
+//   C. the fine bitmap holds one 32-bit word per slot (FINE_SLOTS slots at a time): set bits,
+//      prefix sums of the popcounts, rank of an edge = prefix of its slot + bits below its own;
+//      the unique list comes out of the same pass, ascending.
+// The cost depends on the window's edge count, not on n; nothing is walked once per column range
+// except the window's own column ids.
+constexpr int CRANGE_LOG2 = 20;
+constexpr int CW = (1 << CRANGE_LOG2) / 1024;  // coarse words per range
+
+// A thread owns a run of consecutive LDS words and moves it with 16-byte accesses.  With a
+// thread-to-thread stride of 8 or 16 words those would fall on a few banks only, so such arrays get
+// a stride whose count of 16-byte pieces is odd.
+constexpr int lds_stride_words(int words_per_thread)
 {
-    extern __shared__ uint32_t lds[];
-    uint32_t *bits = lds;                                      // [RANGE_WORDS], all zero between passes
-    int *grp = reinterpret_cast<int *>(lds + RANGE_WORDS);     // [N_GROUPS] popcount sums, then prefixes
-    uint32_t *touched = lds + RANGE_WORDS + N_GROUPS;          // [TOUCH_WORDS] non-empty bitmap words
-    __shared__ int scan_tmp[BIG_THREADS / 64 + 1];
+    return words_per_thread >= 4 && (words_per_thread / 4) % 2 == 0 ? words_per_thread + 4 : words_per_thread;
+}
+
+// Inclusive prefix sum over the 64 lanes of a wave with data-parallel-primitive moves: shifts by
+// 1, 2, 4, 8 inside rows of 16 lanes, then lane 15 of a row added to the next row (rows 1 and 3) and
+// lane 31 added to rows 2 and 3.
+__device__ __forceinline__ int wave_inclusive_scan(int v)
+{
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true);   // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, true);   // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, true);   // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, true);   // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);  // row_bcast:15 into rows 1, 3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);  // row_bcast:31 into rows 2, 3
+    return v;
+}
+
+// Exclusive scan of one int per thread with a single barrier; `wave_tot` holds NT / 64 ints of LDS
+// and must not be written again before every thread has passed another barrier.
+template <int NT>
+__device__ __forceinline__ int block_scan_one_barrier(int v, int *wave_tot, int *total)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int incl = wave_inclusive_scan(v);
+    if (lane == 63) wave_tot[wave] = incl;
+    __syncthreads();
+    int off = 0, tot = 0;
+#pragma unroll
+    for (int k = 0; k < NT / 64; ++k) {
+        const int t = wave_tot[k];
+        off += k < wave ? t : 0;
+        tot += t;
+    }
+    *total = tot;
+    return off + incl - v;
+}
+
+// NT threads condense one window at a time.  RankT holds a rank inside one pass over the fine
+// bitmap (16 bits when the window has fewer than 2^16 edges).
+template <int NT, int FINE_SLOTS, class RankT, int MIN_WG_PER_CU>
+__global__ __launch_bounds__(NT, MIN_WG_PER_CU) void win_compact_kernel(
+    int n, const int *__restrict__ row_ptr, const int *__restrict__ col_idx, int blk_h,
+    int *__restrict__ edge_to_row, int *__restrict__ edge_to_col, int *__restrict__ uniq_count,
+    int *__restrict__ tmp_cols, const int *__restrict__ list, const int *__restrict__ count, int *next_ticket)
+{
+    constexpr int CPT = CW / NT;                       // coarse words owned by a thread
+    constexpr int FPT = FINE_SLOTS / NT;               // fine words owned by a thread
+    constexpr int RANKS_PER_WORD = 4 / sizeof(RankT);  // ranks packed into one 32-bit LDS word
+    constexpr int RW = FPT / RANKS_PER_WORD;           // 32-bit words of ranks owned by a thread
+    static_assert(CPT >= 1 && FPT >= 4 && FPT % 4 == 0 && RW >= 4 && RW % 4 == 0, "16-byte pieces");
+    constexpr int SF = lds_stride_words(FPT);
+    constexpr int SR = lds_stride_words(RW);
+    __shared__ __attribute__((aligned(16))) uint32_t coarse[CW];        // zero between ranges
+    __shared__ __attribute__((aligned(16))) uint32_t cpre[CW];          // touched words before each coarse word
+    __shared__ __attribute__((aligned(16))) uint32_t fine[NT * SF];     // zero between passes
+    __shared__ __attribute__((aligned(16))) uint32_t fpre[NT * SR];     // unique columns of the pass before each slot
+    __shared__ uint16_t slot_word[FINE_SLOTS];                          // bitmap word (inside the range) of each slot
+    __shared__ int wave_tot[NT / 64];
     __shared__ int rp[65];
-    __shared__ int any_s;
     __shared__ int next_s;
     const int tid = threadIdx.x;
-    for (int t = tid; t < RANGE_WORDS; t += BIG_THREADS) bits[t] = 0u;
-    for (int t = tid; t < N_GROUPS; t += BIG_THREADS) grp[t] = 0;
-    touched[tid] = 0u;
-    const int nb = *big_count;
-    const int n_pass = static_cast<int>((static_cast<int64_t>(n) + (1 << RANGE_LOG2) - 1) >> RANGE_LOG2);
-    // Workgroups pull queued windows one at a time (window sizes differ by two orders of magnitude);
-    // every workgroup leaves as soon as the queue is empty.
-    for (;;) {
-        __syncthreads();  // previous window (or the initial clearing) is done with the LDS
-        if (tid == 0) next_s = atomicAdd(&big_count[1], 1);
-        __syncthreads();
-        const int i = next_s;
-        if (i >= nb) break;
-        const int w = big_list[i];
+    const int n_items = *count;
+    auto fpos = [](int slot) { return (slot / FPT) * SF + (slot % FPT); };
+    auto rpos = [](int slot) { return (slot / FPT) * (SR * RANKS_PER_WORD) + (slot % FPT); };
+    for (int k = 0; k < CPT; ++k) coarse[tid * CPT + k] = 0u;
+#pragma unroll
+    for (int k = 0; k < FPT; k += 4) *reinterpret_cast<uint4 *>(&fine[tid * SF + k]) = make_uint4(0u, 0u, 0u, 0u);
+    // A persistent grid: one workgroup per possible queue entry would start tens of thousands of
+    // workgroups that only find the queue shorter than the bound.  The first item is the
+    // workgroup's own index, later ones come from a ticket counter whose atomic is issued before
+    // the current window is condensed, so that its latency is hidden.
+    for (int item = blockIdx.x; item < n_items;) {  // uniform
+        int ticket = 0;
+        if (tid == 0) ticket = atomicAdd(next_ticket, 1) + static_cast<int>(gridDim.x);
+        const int w = list[item];
         const int r0 = w * blk_h;
         const int rows = min(n, r0 + blk_h) - r0;
+        __syncthreads();  // the previous window is done with rp; the initial clearing is complete
         if (tid <= rows) rp[tid] = row_ptr[r0 + tid];
         __syncthreads();
         const int e0 = rp[0], e1 = rp[rows];
-        // The window's column ids are handled in chunks of KREG * 1024 edges held in registers
-        // (KREG independent loads in flight per thread).  A window that fits one chunk reads its
-        // column ids from memory once; longer ones re-read them in the ranking phase.
-        constexpr int KREG = 8;
-        constexpr int CHUNK = KREG * BIG_THREADS;
-        const int n_chunks = (e1 - e0 + CHUNK - 1) / CHUNK;
-        int creg[KREG];
-        auto load_chunk = [&](int ch) {
+        for (int e = e0 + tid; e < e1; e += NT) edge_to_row[e] = r0 + row_of_edge(rp, rows, e);
+        // f(column, edge) for every edge of the window.  The column ids are read again in every
+        // phase (they come from L2 after the first time): keeping them in registers between the
+        // phases was measured slower, because it halves the number of workgroups a CU can hold.
+        auto for_edges = [&](auto f) {
+            for (int eb = e0 + tid; eb < e1; eb += NT * 8) {
+                int c8[8];
 #pragma unroll
-            for (int q = 0; q < KREG; ++q) {
-                const int e = e0 + ch * CHUNK + tid + q * BIG_THREADS;
-                creg[q] = e < e1 ? col_idx[e] : -1;
+                for (int j = 0; j < 8; ++j) {
+                    const int e = eb + j * NT;
+                    c8[j] = e < e1 ? col_idx[e] : -1;
+                }
+#pragma unroll
+                for (int j = 0; j < 8; ++j) f(c8[j], eb + j * NT);
             }
         };
-        if (n_chunks == 1) load_chunk(0);
-        const bool track = n_chunks <= 2;  // longer windows touch most words: visit them all instead
-        for (int e = e0 + tid; e < e1; e += BIG_THREADS) {
-            int a = 0, b = rows;  // last row index with rp[a] <= e
-            while (b - a > 1) {
-                const int mid = (a + b) >> 1;
-                if (rp[mid] <= e) a = mid; else b = mid;
-            }
-            edge_to_row[e] = r0 + a;
-        }
-        int base_rank = 0;
-        for (int pass = 0; pass < n_pass; ++pass) {
-            const int lo = pass << RANGE_LOG2;
-            if (tid == 0) any_s = 0;
-            __syncthreads();
+        const int n_ranges = static_cast<int>((static_cast<int64_t>(n) + (1 << CRANGE_LOG2) - 1) >> CRANGE_LOG2);
+        int base = 0;  // unique columns found so far
+        for (int range = 0; range < n_ranges; ++range) {
+            const int lo = range << CRANGE_LOG2;
+            // A. which bitmap words of this range does the window touch
             bool any = false;
-            for (int ch = 0; ch < n_chunks; ++ch) {
-                if (n_chunks > 1) load_chunk(ch);
-#pragma unroll
-                for (int q = 0; q < KREG; ++q) {
-                    const unsigned c = static_cast<unsigned>(creg[q] - lo);
-                    if (creg[q] >= 0 && c < (1u << RANGE_LOG2)) {
-                        atomicOr(&bits[c >> 5], 1u << (c & 31));
-                        if (track) atomicOr(&touched[c >> 10], 1u << ((c >> 5) & 31));
-                        any = true;
-                    }
+            for_edges([&](int col, int) {
+                const unsigned c = static_cast<unsigned>(col - lo);
+                if (col >= 0 && c < (1u << CRANGE_LOG2)) {
+                    atomicOr(&coarse[c >> 10], 1u << ((c >> 5) & 31));
+                    any = true;
                 }
-            }
-            if (any) any_s = 1;
-            if (!track) touched[tid] = 0xffffffffu;
-            __syncthreads();
-            if (!any_s) {  // uniform: none of the window's columns lies in this range
-                touched[tid] = 0u;
-                continue;
-            }
-            // popcount sums per group of GROUP_WORDS words; only words that hold a bit are visited
-            // (thread t owns bitmap words 32 t .. 32 t + 31 through its coarse word)
-            const uint32_t my_touched = touched[tid];
-            for (uint32_t m = my_touched; m; m &= m - 1) {
-                const int t = tid * 32 + (__ffs(m) - 1);
-                const int pc = __popc(bits[t]);
-                if (pc) atomicAdd(&grp[t / GROUP_WORDS], pc);
-            }
-            __syncthreads();
-            // exclusive prefix over the groups: every thread owns N_GROUPS / BIG_THREADS consecutive groups
-            constexpr int PER = N_GROUPS / BIG_THREADS;
-            int sums[PER];
+            });
+            if (!__syncthreads_or(any ? 1 : 0)) continue;  // none of the window's columns lies in this range
+            // B. number the touched words
+            uint32_t cwv[CPT];
             int mine = 0;
 #pragma unroll
-            for (int q = 0; q < PER; ++q) { sums[q] = grp[tid * PER + q]; mine += sums[q]; }
-            int pass_total;
-            int run = block_exclusive_scan<BIG_THREADS>(mine, scan_tmp, &pass_total);
+            for (int k = 0; k < CPT; ++k) {
+                cwv[k] = coarse[tid * CPT + k];
+                mine += __popc(cwv[k]);
+            }
+            int n_slots;
+            const int first_slot = block_scan_one_barrier<NT>(mine, wave_tot, &n_slots);
+            {
+                int run = first_slot;
 #pragma unroll
-            for (int q = 0; q < PER; ++q) { grp[tid * PER + q] = run; run += sums[q]; }
-            __syncthreads();
-            // rank of every edge whose column lies in this range
-            auto rank_of = [&](unsigned c) {
-                const int word = c >> 5, g0 = word / GROUP_WORDS;
-                int r = grp[g0];
-                for (int t = g0 * GROUP_WORDS; t < word; ++t) r += __popc(bits[t]);
-                return base_rank + r + __popc(bits[word] & ((1u << (c & 31)) - 1u));
+                for (int k = 0; k < CPT; ++k) {
+                    cpre[tid * CPT + k] = run;
+                    run += __popc(cwv[k]);
+                }
+            }
+            // slot of a column of this range (its bitmap word is touched by construction)
+            auto slot_of = [&](unsigned c) {
+                const int cw = c >> 10;
+                return static_cast<int>(cpre[cw]) + __popc(coarse[cw] & ((1u << ((c >> 5) & 31)) - 1u));
             };
-            for (int ch = 0; ch < n_chunks; ++ch) {
-                if (n_chunks > 1) load_chunk(ch);
+            // C. fine bitmap, FINE_SLOTS slots per pass
+            for (int s0 = 0; s0 < n_slots; s0 += FINE_SLOTS) {  // uniform
+                {   // bitmap word of every slot of this pass, from the owners of the coarse words
+                    int run = first_slot;
 #pragma unroll
-                for (int q = 0; q < KREG; ++q) {
-                    const unsigned c = static_cast<unsigned>(creg[q] - lo);
-                    if (creg[q] >= 0 && c < (1u << RANGE_LOG2))
-                        edge_to_col[e0 + ch * CHUNK + tid + q * BIG_THREADS] = rank_of(c);
+                    for (int k = 0; k < CPT; ++k) {
+                        for (uint32_t m = cwv[k]; m; m &= m - 1) {
+                            const unsigned rel = static_cast<unsigned>(run - s0);
+                            if (rel < static_cast<unsigned>(FINE_SLOTS))
+                                slot_word[rel] = static_cast<uint16_t>((tid * CPT + k) * 32 + (__ffs(m) - 1));
+                            ++run;
+                        }
+                    }
                 }
-            }
-            // the unique columns of this range, ascending
-            for (uint32_t m = my_touched; m; m &= m - 1) {
-                const int t = tid * 32 + (__ffs(m) - 1);
-                uint32_t b = bits[t];
-                if (!b) continue;
-                const int g0 = t / GROUP_WORDS;
-                int k = base_rank + grp[g0];
-                for (int q = g0 * GROUP_WORDS; q < t; ++q) k += __popc(bits[q]);
-                while (b) {
-                    const int bit = __ffs(b) - 1;
-                    tmp_cols[e0 + k++] = lo + t * 32 + bit;
-                    b &= b - 1;
+                __syncthreads();  // cpre (first pass) and slot_word are complete
+                for_edges([&](int col, int) {
+                    const unsigned c = static_cast<unsigned>(col - lo);
+                    if (col >= 0 && c < (1u << CRANGE_LOG2)) {
+                        const unsigned rel = static_cast<unsigned>(slot_of(c) - s0);
+                        if (rel < static_cast<unsigned>(FINE_SLOTS)) atomicOr(&fine[fpos(rel)], 1u << (c & 31));
+                    }
+                });
+                __syncthreads();
+                uint32_t fw[FPT];
+#pragma unroll
+                for (int k = 0; k < FPT; k += 4) {
+                    const uint4 v = *reinterpret_cast<const uint4 *>(&fine[tid * SF + k]);
+                    fw[k] = v.x; fw[k + 1] = v.y; fw[k + 2] = v.z; fw[k + 3] = v.w;
                 }
+                int cnt_mine = 0;
+#pragma unroll
+                for (int k = 0; k < FPT; ++k) cnt_mine += __popc(fw[k]);
+                int pass_total;
+                int run = block_scan_one_barrier<NT>(cnt_mine, wave_tot, &pass_total);
+                uint32_t rw[RW];
+#pragma unroll
+                for (int k = 0; k < RW; ++k) rw[k] = 0u;
+#pragma unroll
+                for (int k = 0; k < FPT; ++k) {
+                    rw[k / RANKS_PER_WORD] |= static_cast<uint32_t>(run) << (8 * sizeof(RankT) * (k % RANKS_PER_WORD));
+                    if (fw[k]) {
+                        const int col0 = lo + static_cast<int>(slot_word[tid * FPT + k]) * 32;
+                        for (uint32_t m = fw[k]; m; m &= m - 1) tmp_cols[e0 + base + run++] = col0 + (__ffs(m) - 1);
+                    }
+                }
+#pragma unroll
+                for (int k = 0; k < RW; k += 4)
+                    *reinterpret_cast<uint4 *>(&fpre[tid * SR + k]) = make_uint4(rw[k], rw[k + 1], rw[k + 2], rw[k + 3]);
+                __syncthreads();
+                const RankT *fpre_e = reinterpret_cast<const RankT *>(fpre);
+                for_edges([&](int col, int e) {
+                    const unsigned c = static_cast<unsigned>(col - lo);
+                    if (col >= 0 && c < (1u << CRANGE_LOG2)) {
+                        const unsigned rel = static_cast<unsigned>(slot_of(c) - s0);
+                        if (rel < static_cast<unsigned>(FINE_SLOTS))
+                            edge_to_col[e] = base + static_cast<int>(fpre_e[rpos(rel)]) +
+                                             __popc(fine[fpos(rel)] & ((1u << (c & 31)) - 1u));
+                    }
+                });
+                base += pass_total;
+                __syncthreads();  // every thread is done reading fine, fpre, slot_word
+#pragma unroll
+                for (int k = 0; k < FPT; k += 4)
+                    if (fw[k] | fw[k + 1] | fw[k + 2] | fw[k + 3])
+                        *reinterpret_cast<uint4 *>(&fine[tid * SF + k]) = make_uint4(0u, 0u, 0u, 0u);
             }
+            // the coarse words were last read in the ranking, before the barrier above
+#pragma unroll
+            for (int k = 0; k < CPT; ++k)
+                if (cwv[k]) coarse[tid * CPT + k] = 0u;
             __syncthreads();
-            // leave the LDS all zero for the next pass / window
-            for (uint32_t m = my_touched; m; m &= m - 1) bits[tid * 32 + (__ffs(m) - 1)] = 0u;
-            for (int t = tid; t < N_GROUPS; t += BIG_THREADS) grp[t] = 0;
-            touched[tid] = 0u;
-            base_rank += pass_total;
         }
-        if (tid == 0) uniq_count[w] = base_rank;
+        if (tid == 0) {
+            uniq_count[w] = base;
+            next_s = ticket;
+        }
+        __syncthreads();
+        item = next_s;
     }
 }
 
-// Single workgroup: exclusive scan of the per-window unique counts.
+// ---- hub windows: one bitmap of n bits per hub in global memory, edge-parallel ---------------------
+// Single workgroup: work items (HUB_CHUNK edges of one hub) and the table that maps an item to its hub.
+__global__ __launch_bounds__(1024) void hub_plan_kernel(int n, const int *__restrict__ row_ptr, int blk_h,
+                                                        const int *__restrict__ list_hub, int *counters,
+                                                        int *__restrict__ hub_chunk_ptr,
+                                                        int *__restrict__ chunk_table)
+{
+    __shared__ int scan_tmp[1024 / 64 + 1];
+    __shared__ int s_ptr[HUB_SLOTS_MAX + 1];
+    const int tid = threadIdx.x;
+    const int nh = counters[C_HUB];
+    int chunks = 0;
+    if (tid < nh) {
+        const int r0 = list_hub[tid] * blk_h;
+        const int cnt = row_ptr[min(n, r0 + blk_h)] - row_ptr[r0];
+        chunks = (cnt + HUB_CHUNK - 1) / HUB_CHUNK;
+    }
+    int total;
+    const int ex = block_exclusive_scan<1024>(chunks, scan_tmp, &total);
+    s_ptr[tid] = ex;
+    if (tid == 0) {
+        s_ptr[HUB_SLOTS_MAX] = total;
+        counters[C_CHUNKS] = total;
+        hub_chunk_ptr[nh] = total;
+    }
+    if (tid < nh) hub_chunk_ptr[tid] = ex;
+    __syncthreads();
+    for (int h = 0; h < nh; ++h) {
+        const int p = s_ptr[h], q = s_ptr[h + 1];  // s_ptr[nh] == total also when nh < HUB_SLOTS_MAX
+        for (int t = p + tid; t < q; t += 1024) chunk_table[t] = h;
+    }
+}
+
+__global__ __launch_bounds__(256) void hub_clear_kernel(const int *__restrict__ counters, uint32_t *hub_bits,
+                                                        int wps)
+{
+    const int64_t total = static_cast<int64_t>(counters[C_HUB]) * (wps / 4);  // 16-byte pieces of the used slots
+    uint4 *p = reinterpret_cast<uint4 *>(hub_bits);
+    for (int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x; i < total;
+         i += static_cast<int64_t>(gridDim.x) * 256)
+        p[i] = make_uint4(0u, 0u, 0u, 0u);
+}
+
+// RANK = false: edge_to_row and the bitmap bits of every hub edge.  RANK = true: edge_to_col from the
+// finished bitmaps and the group prefixes.
+template <bool RANK>
+__global__ __launch_bounds__(256) void hub_edges_kernel(int n, const int *__restrict__ row_ptr,
+                                                        const int *__restrict__ col_idx, int blk_h,
+                                                        const int *__restrict__ list_hub,
+                                                        const int *__restrict__ counters,
+                                                        const int *__restrict__ hub_chunk_ptr,
+                                                        const int *__restrict__ chunk_table,
+                                                        uint32_t *hub_bits, const int *__restrict__ hub_grp,
+                                                        int wps, int *__restrict__ edge_to_row,
+                                                        int *__restrict__ edge_to_col,
+                                                        int *__restrict__ tmp_cols)
+{
+    __shared__ int rp[65];
+    constexpr int PER = HUB_CHUNK / 256;
+    const int tid = threadIdx.x;
+    const int total = counters[C_CHUNKS];
+    if constexpr (RANK) {
+        // unique lists of all hubs: one thread per group of HUB_GROUP bitmap words
+        const int n_groups = wps / HUB_GROUP;
+        const int64_t all = static_cast<int64_t>(counters[C_HUB]) * n_groups;
+        for (int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + tid; i < all;
+             i += static_cast<int64_t>(gridDim.x) * 256) {
+            const int slot = static_cast<int>(i / n_groups), g = static_cast<int>(i % n_groups);
+            const uint32_t *bm = hub_bits + static_cast<size_t>(slot) * wps + g * HUB_GROUP;
+            const uint4 a = *reinterpret_cast<const uint4 *>(bm);
+            const uint4 b = *reinterpret_cast<const uint4 *>(bm + 4);
+            if ((a.x | a.y | a.z | a.w | b.x | b.y | b.z | b.w) == 0u) continue;
+            const uint32_t wv[HUB_GROUP] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+            int dst = row_ptr[list_hub[slot] * blk_h] + hub_grp[static_cast<size_t>(slot) * n_groups + g];
+#pragma unroll
+            for (int k = 0; k < HUB_GROUP; ++k)
+                for (uint32_t m = wv[k]; m; m &= m - 1)
+                    tmp_cols[dst++] = (g * HUB_GROUP + k) * 32 + (__ffs(m) - 1);
+        }
+    }
+    for (int c = blockIdx.x; c < total; c += gridDim.x) {  // uniform trip count per workgroup
+        const int slot = chunk_table[c];
+        const int r0 = list_hub[slot] * blk_h;
+        const int rows = min(n, r0 + blk_h) - r0;
+        __syncthreads();  // the previous item is done with rp
+        if (tid <= rows) rp[tid] = row_ptr[r0 + tid];
+        __syncthreads();
+        const int e0 = rp[0] + (c - hub_chunk_ptr[slot]) * HUB_CHUNK;
+        const int e1 = min(rp[rows], e0 + HUB_CHUNK);
+        uint32_t *bm = hub_bits + static_cast<size_t>(slot) * wps;
+        int col[PER];
+#pragma unroll
+        for (int q = 0; q < PER; ++q) {
+            const int e = e0 + tid + q * 256;
+            col[q] = e < e1 ? col_idx[e] : -1;
+        }
+        if constexpr (!RANK) {
+#pragma unroll
+            for (int q = 0; q < PER; ++q) {
+                const int e = e0 + tid + q * 256;
+                if (col[q] >= 0) {
+                    edge_to_row[e] = r0 + row_of_edge(rp, rows, e);
+                    // Popular columns are hit by thousands of edges of a hub, and atomics on one
+                    // address serialise: read the word first (from L2, where the atomics execute)
+                    // and skip the atomic once the bit is there.  Bits are only ever set, so a set
+                    // bit that is read is never wrong.  (Issuing all the reads of a thread before its
+                    // first atomic was measured slower: fewer reads then see the bit.)
+                    uint32_t *word = &bm[col[q] >> 5];
+                    const uint32_t bit = 1u << (col[q] & 31);
+                    if (!(__hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & bit)) atomicOr(word, bit);
+                }
+            }
+        } else {
+            const int *gp = hub_grp + static_cast<size_t>(slot) * (wps / HUB_GROUP);
+#pragma unroll
+            for (int q = 0; q < PER; ++q) {
+                if (col[q] >= 0) {
+                    const int word = col[q] >> 5, g = word / HUB_GROUP, j = word % HUB_GROUP;
+                    const uint4 a = *reinterpret_cast<const uint4 *>(bm + g * HUB_GROUP);
+                    const uint4 b = *reinterpret_cast<const uint4 *>(bm + g * HUB_GROUP + 4);
+                    const uint32_t wv[HUB_GROUP] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+                    const uint32_t below = (1u << (col[q] & 31)) - 1u;
+                    int r = gp[g];
+#pragma unroll
+                    for (int k = 0; k < HUB_GROUP; ++k) r += __popc(wv[k] & (k < j ? 0xffffffffu : (k == j ? below : 0u)));
+                    edge_to_col[e0 + tid + q * 256] = r;
+                }
+            }
+        }
+    }
+}
+
+// One workgroup per hub: prefix of the popcounts per group of HUB_GROUP words, and the unique count.
+// (The unique lists are written by the ranking kernel, spread over the whole GPU: scattered 4-byte
+// stores cost a CU one cycle per lane, and a hub can have 10^5 distinct columns.)
+__global__ __launch_bounds__(1024) void hub_scan_kernel(const int *__restrict__ list_hub,
+                                                        const int *__restrict__ counters,
+                                                        const uint32_t *__restrict__ hub_bits,
+                                                        int *__restrict__ hub_grp, int wps,
+                                                        int *__restrict__ uniq_count)
+{
+    __shared__ int wave_tot[2][1024 / 64];
+    const int slot = blockIdx.x;
+    if (slot >= counters[C_HUB]) return;  // uniform
+    const int tid = threadIdx.x;
+    const int w = list_hub[slot];
+    const int n_groups = wps / HUB_GROUP;
+    const uint32_t *bm = hub_bits + static_cast<size_t>(slot) * wps;
+    int *gp = hub_grp + static_cast<size_t>(slot) * n_groups;
+    int carry = 0, parity = 0;
+    for (int g0 = 0; g0 < n_groups; g0 += 1024) {  // uniform trip count
+        const int g = g0 + tid;
+        uint32_t wv[HUB_GROUP] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
+        if (g < n_groups) {
+            const uint4 a = *reinterpret_cast<const uint4 *>(bm + g * HUB_GROUP);
+            const uint4 b = *reinterpret_cast<const uint4 *>(bm + g * HUB_GROUP + 4);
+            wv[0] = a.x; wv[1] = a.y; wv[2] = a.z; wv[3] = a.w;
+            wv[4] = b.x; wv[5] = b.y; wv[6] = b.z; wv[7] = b.w;
+        }
+        int mine = 0;
+#pragma unroll
+        for (int k = 0; k < HUB_GROUP; ++k) mine += __popc(wv[k]);
+        int tile_total;
+        // two buffers: a fast thread may start the next scan while a slow one still reads this one's
+        // totals; the scan after that is separated from this one by the next scan's barrier
+        int run = carry + block_scan_one_barrier<1024>(mine, wave_tot[parity], &tile_total);
+        parity ^= 1;
+        if (g < n_groups) gp[g] = run;
+        carry += tile_total;
+    }
+    if (tid == 0) uniq_count[w] = carry;
+}
+
+// Single workgroup: exclusive scan of the per-window unique counts.  A round covers 4096 windows
+// (every thread takes four consecutive ones); the loads of SCAN_ROUNDS rounds are issued together so
+// that a pass over 65536 windows pays the memory latency once.
+constexpr int SCAN_ROUNDS = 16;
 __global__ __launch_bounds__(1024) void win_scan_kernel(int n_windows, int blk_w,
                                                         const int *__restrict__ uniq_count,
                                                         int *__restrict__ win_col_ptr,
                                                         int *__restrict__ block_partition,
                                                         int64_t *__restrict__ summary)
 {
-    __shared__ int scan_tmp[1024 / 64 + 1];
+    __shared__ int wave_tot[2][1024 / 64];
     __shared__ long long blocks_s[16];
     const int tid = threadIdx.x;
-    int carry = 0;
+    const int shift = (blk_w & (blk_w - 1)) == 0 ? __ffs(blk_w) - 1 : -1;  // blk_w a power of two: no division
+    auto blocks_of = [&](int u) { return shift >= 0 ? (u + blk_w - 1) >> shift : (u + blk_w - 1) / blk_w; };
+    int carry = 0, parity = 0;
     long long my_blocks = 0;
-    for (int base = 0; base < n_windows; base += 1024) {
-        const int t = base + tid;
-        const int u = t < n_windows ? uniq_count[t] : 0;
-        int round_total;
-        const int ex = block_exclusive_scan<1024>(u, scan_tmp, &round_total);
-        if (t < n_windows) {
-            win_col_ptr[t] = carry + ex;
-            const int blocks = (u + blk_w - 1) / blk_w;
-            block_partition[t] = blocks;
-            my_blocks += blocks;
+    for (int super0 = 0; super0 < n_windows; super0 += 4096 * SCAN_ROUNDS) {  // uniform trip count
+        int u[SCAN_ROUNDS][4];
+#pragma unroll
+        for (int r = 0; r < SCAN_ROUNDS; ++r) {
+            const int first = super0 + r * 4096 + tid * 4;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) u[r][j] = first + j < n_windows ? uniq_count[first + j] : 0;
         }
-        carry += round_total;
+#pragma unroll
+        for (int r = 0; r < SCAN_ROUNDS; ++r) {
+            const int first = super0 + r * 4096 + tid * 4;
+            if (super0 + r * 4096 < n_windows) {  // uniform
+            int round_total;
+            int run = carry + block_scan_one_barrier<1024>(u[r][0] + u[r][1] + u[r][2] + u[r][3],
+                                                           wave_tot[parity], &round_total);
+            parity ^= 1;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (first + j < n_windows) {
+                    win_col_ptr[first + j] = run;
+                    const int blocks = blocks_of(u[r][j]);
+                    block_partition[first + j] = blocks;
+                    my_blocks += blocks;
+                    run += u[r][j];
+                }
+            }
+            carry += round_total;
+            }
+        }
     }
     // sum of blocks over the workgroup
     long long v = my_blocks;
 #pragma unroll
     for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
-    __syncthreads();
     if ((tid & 63) == 0) blocks_s[tid >> 6] = v;
     __syncthreads();
     if (tid == 0) {
@@ -446,24 +781,47 @@ int32_t launch_build_windows(const ftc_csr &g, ftc_windows &w, void *ws, size_t 
                            w.block_partition, w.summary);
         return launch_status("build_windows scan");
     }
-    hipLaunchKernelGGL(win_clear_kernel, dim3(1), dim3(1), 0, s, k.big_count);
+    const int hub_thr = hub_threshold(g.n, g.nnz);
+    hipLaunchKernelGGL(win_clear_kernel, dim3(1), dim3(64), 0, s, k.counters);
     hipLaunchKernelGGL(win_wave_kernel, dim3(w.n_windows), dim3(64), 0, s, g.n, g.row_ptr, g.col_idx, w.blk_h,
-                       w.edge_to_row, w.edge_to_col, k.uniq_count, k.tmp_cols, k.big_list, k.big_count);
+                       hub_thr, w.edge_to_row, w.edge_to_col, k.uniq_count, k.tmp_cols, k.list_mid, k.list_large,
+                       k.list_hub, k.counters);
     int32_t st = launch_status("build_windows wave");
     if (st != FTC_OK) return st;
-    // 144 KiB of dynamic LDS: above the default limit, so the attribute is raised first
-    if (hipFuncSetAttribute(reinterpret_cast<const void *>(win_bitmap_kernel),
-                            hipFuncAttributeMaxDynamicSharedMemorySize,
-                            static_cast<int>(BIG_LDS_BYTES)) != hipSuccess) {
-        (void)hipGetLastError();
-        set_error("build_windows: cannot reserve %zu bytes of LDS", BIG_LDS_BYTES);
-        return FTC_EHIP;
+    if (g.nnz > WAVE_CAP) {  // otherwise no window can be queued
+        // the grids are upper bounds of the queue lengths; surplus workgroups leave at once
+        // persistent grids: as many workgroups as fit on the chip at once (registers allow three
+        // 256-thread or one 1024-thread workgroup per CU), never more than the queue can hold
+#define FTC_RANGE(NT, SLOTS, RANK, PER_CU, CAP, LIST, COUNTER, NEXT)                                          \
+    hipLaunchKernelGGL((win_compact_kernel<NT, SLOTS, RANK, PER_CU>),                                         \
+                       dim3(CAP < PER_CU * N_CU ? CAP : PER_CU * N_CU),                                       \
+                       dim3(NT), 0, s, g.n, g.row_ptr, g.col_idx, w.blk_h, w.edge_to_row, w.edge_to_col,      \
+                       k.uniq_count, k.tmp_cols, LIST, k.counters + COUNTER, k.counters + NEXT)
+        FTC_RANGE(256, 2048, uint16_t, 5, k.cap_mid, k.list_mid, C_MID, C_MID_NEXT);
+        st = launch_status("build_windows compact (mid)");
+        if (st != FTC_OK) return st;
+        if (g.nnz > MID_CAP) {
+            FTC_RANGE(1024, 8192, uint32_t, 1, k.cap_large, k.list_large, C_LARGE, C_LARGE_NEXT);
+            st = launch_status("build_windows compact (large)");
+            if (st != FTC_OK) return st;
+        }
+#undef FTC_RANGE
+        if (g.nnz > hub_thr) {
+            hipLaunchKernelGGL(hub_plan_kernel, dim3(1), dim3(1024), 0, s, g.n, g.row_ptr, w.blk_h, k.list_hub,
+                               k.counters, k.hub_chunk_ptr, k.chunk_table);
+            hipLaunchKernelGGL(hub_clear_kernel, dim3(512), dim3(256), 0, s, k.counters, k.hub_bits, k.wps);
+            hipLaunchKernelGGL((hub_edges_kernel<false>), dim3(HUB_GRID), dim3(256), 0, s, g.n, g.row_ptr, g.col_idx,
+                               w.blk_h, k.list_hub, k.counters, k.hub_chunk_ptr, k.chunk_table, k.hub_bits,
+                               k.hub_grp, k.wps, w.edge_to_row, w.edge_to_col, k.tmp_cols);
+            hipLaunchKernelGGL(hub_scan_kernel, dim3(k.slots), dim3(1024), 0, s, k.list_hub, k.counters, k.hub_bits,
+                               k.hub_grp, k.wps, k.uniq_count);
+            hipLaunchKernelGGL((hub_edges_kernel<true>), dim3(HUB_GRID), dim3(256), 0, s, g.n, g.row_ptr, g.col_idx,
+                               w.blk_h, k.list_hub, k.counters, k.hub_chunk_ptr, k.chunk_table, k.hub_bits,
+                               k.hub_grp, k.wps, w.edge_to_row, w.edge_to_col, k.tmp_cols);
+            st = launch_status("build_windows hubs");
+            if (st != FTC_OK) return st;
+        }
     }
-    hipLaunchKernelGGL(win_bitmap_kernel, dim3(BIG_GRID), dim3(BIG_THREADS), BIG_LDS_BYTES, s, g.n, g.row_ptr,
-                       g.col_idx, w.blk_h, w.edge_to_row, w.edge_to_col, k.uniq_count, k.tmp_cols, k.big_list,
-                       k.big_count);
-    st = launch_status("build_windows bitmap");
-    if (st != FTC_OK) return st;
     hipLaunchKernelGGL(win_scan_kernel, dim3(1), dim3(1024), 0, s, w.n_windows, w.blk_w, k.uniq_count,
                        w.win_col_ptr, w.block_partition, w.summary);
     st = launch_status("build_windows scan");

@@ -121,6 +121,41 @@ def test_build_windows_more_than_one_column_range(oracle):
     check_windows(win, ref)
 
 
+def size_class_graph(n, seed):
+    """Windows of every size class of the build: a few edges, ~3000 (workgroup, ids in registers),
+    ~10000 and ~20000 (workgroup, larger), and hubs of 33000 / 70001 edges (edge-parallel path),
+    with duplicates, unsorted columns and a hub in the last, short window."""
+    rng = np.random.default_rng(seed)
+    deg = rng.integers(0, 9, size=n)
+    deg[16 * 3:16 * 4] = 190                  # ~3000 edges in window 3
+    deg[16 * 7 + 2] = 10_000                  # one long row
+    deg[16 * 9:16 * 10] = 1250                # 20000 edges over 16 rows
+    deg[16 * 20:16 * 21] = 2063               # hub: 33008 edges
+    deg[16 * 21] = 70_001                     # hub next to it, all in one row
+    deg[n - 3:] = 12_000                      # hub in the last window (3 rows when n % 16 == 3)
+    row_ptr = np.zeros(n + 1, dtype=np.int32)
+    row_ptr[1:] = np.cumsum(deg)
+    col = rng.integers(0, n, size=int(row_ptr[-1])).astype(np.int32)
+    lo, hi = row_ptr[16 * 21], row_ptr[16 * 21 + 1]
+    col[lo:hi] = rng.integers(0, min(n, 5000), size=hi - lo)     # heavy duplication inside a hub
+    return synth.Graph(n, row_ptr, col, "classes")
+
+
+@pytest.mark.parametrize("n,blk", [(40_003, (16, 8)), (40_003, (64, 8)), (40_003, (5, 3)),
+                                   ((1 << 21) + 4099, (16, 8))])
+def test_build_windows_size_classes(oracle, n, blk):
+    """Every size class of the window build, also on a graph with more than 2^21 nodes (wider bitmap
+    ranges in LDS, hub bitmaps of more than 2^16 words)."""
+    g = size_class_graph(n, seed=n % 1000)
+    say(f"build_windows classes n={g.n} nnz={g.nnz} blk={blk}")
+    ref = oracle.build_windows(g.row_ptr, g.col_idx, *blk)
+    dg = dev_graph(g)
+    win = B.ftc_build_windows(dg, *blk)
+    torch.cuda.synchronize()
+    check_windows(win, ref)
+    check_windows(B.ftc_build_windows(dg, *blk), ref)
+
+
 def test_build_windows_degenerate(oracle):
     # no edges at all, and a single node
     for n in (1, 33):
