@@ -582,22 +582,30 @@ __global__ __launch_bounds__(256) void hub_edges_kernel(int n, const int *__rest
     const int tid = threadIdx.x;
     const int total = counters[C_CHUNKS];
     if constexpr (RANK) {
-        // unique lists of all hubs: one thread per group of HUB_GROUP bitmap words
-        const int n_groups = wps / HUB_GROUP;
-        const int64_t all = static_cast<int64_t>(counters[C_HUB]) * n_groups;
-        for (int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + tid; i < all;
-             i += static_cast<int64_t>(gridDim.x) * 256) {
-            const int slot = static_cast<int>(i / n_groups), g = static_cast<int>(i % n_groups);
-            const uint32_t *bm = hub_bits + static_cast<size_t>(slot) * wps + g * HUB_GROUP;
-            const uint4 a = *reinterpret_cast<const uint4 *>(bm);
-            const uint4 b = *reinterpret_cast<const uint4 *>(bm + 4);
-            if ((a.x | a.y | a.z | a.w | b.x | b.y | b.z | b.w) == 0u) continue;
-            const uint32_t wv[HUB_GROUP] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-            int dst = row_ptr[list_hub[slot] * blk_h] + hub_grp[static_cast<size_t>(slot) * n_groups + g];
-#pragma unroll
-            for (int k = 0; k < HUB_GROUP; ++k)
-                for (uint32_t m = wv[k]; m; m &= m - 1)
-                    tmp_cols[dst++] = (g * HUB_GROUP + k) * 32 + (__ffs(m) - 1);
+        // Unique lists of all hubs.  A work item is a tile of 256 bitmap words of one hub: ranks
+        // inside the tile from a workgroup scan, column ids parked in LDS at their rank, then copied
+        // out with consecutive lanes writing consecutive entries.  (Writing them straight from the
+        // thread that owns the word costs a store instruction one cycle per lane, and the low
+        // columns of a hub are dense.)
+        __shared__ int stage[256 * 32];
+        __shared__ int wave_tot[2][4];
+        const int tiles = (wps + 255) / 256;
+        const int items = counters[C_HUB] * tiles;
+        int parity = 0;
+        for (int it = blockIdx.x; it < items; it += gridDim.x) {  // uniform trip count per workgroup
+            const int slot = it / tiles, word = (it % tiles) * 256 + tid;
+            const uint32_t v = word < wps ? hub_bits[static_cast<size_t>(slot) * wps + word] : 0u;
+            int tile_total;
+            int off = block_scan_one_barrier<256>(__popc(v), wave_tot[parity], &tile_total);
+            parity ^= 1;
+            if (tile_total == 0) continue;  // uniform
+            for (uint32_t m = v; m; m &= m - 1) stage[off++] = word * 32 + (__ffs(m) - 1);
+            __syncthreads();
+            // the tile starts at a group boundary (256 is a multiple of HUB_GROUP)
+            const int dst = row_ptr[list_hub[slot] * blk_h] +
+                            hub_grp[static_cast<size_t>(slot) * (wps / HUB_GROUP) + (it % tiles) * (256 / HUB_GROUP)];
+            for (int i = tid; i < tile_total; i += 256) tmp_cols[dst + i] = stage[i];
+            __syncthreads();  // stage is free again
         }
     }
     for (int c = blockIdx.x; c < total; c += gridDim.x) {  // uniform trip count per workgroup
@@ -755,21 +763,34 @@ __global__ __launch_bounds__(1024) void win_scan_kernel(int n_windows, int blk_w
     }
 }
 
-// Packs the unique lists: one thread per slot of the temporary array.  Slot e belongs to the window
-// of edge e (edge_to_row); it holds a list entry when its offset inside the window is below the
-// window's unique count.
+// Packs the unique lists.  Slot e of the temporary array belongs to the window of edge e
+// (edge_to_row); it holds a list entry when its offset inside the window is below the window's
+// unique count.  A thread takes four slots 256 apart so that its loads are independent.
 __global__ __launch_bounds__(256) void win_pack_kernel(int nnz, const int *__restrict__ row_ptr, int blk_h,
                                                        const int *__restrict__ edge_to_row,
                                                        const int *__restrict__ win_col_ptr,
                                                        const int *__restrict__ tmp_cols,
                                                        int *__restrict__ win_cols)
 {
-    const int64_t e = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
-    if (e >= nnz) return;
-    const int w = edge_to_row[e] / blk_h;
-    const int k = static_cast<int>(e) - row_ptr[w * blk_h];
-    const int dst = win_col_ptr[w];
-    if (k < win_col_ptr[w + 1] - dst) win_cols[dst + k] = tmp_cols[e];
+    const int64_t e0 = static_cast<int64_t>(blockIdx.x) * 1024 + threadIdx.x;
+    int w[4], k[4], dst[4], len[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) w[j] = e0 + j * 256 < nnz ? edge_to_row[e0 + j * 256] / blk_h : -1;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        if (w[j] >= 0) {
+            k[j] = static_cast<int>(e0 + j * 256) - row_ptr[w[j] * blk_h];
+            dst[j] = win_col_ptr[w[j]];
+            len[j] = win_col_ptr[w[j] + 1] - dst[j];
+        }
+    }
+    int v[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        if (w[j] >= 0 && k[j] < len[j]) v[j] = tmp_cols[e0 + j * 256];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        if (w[j] >= 0 && k[j] < len[j]) win_cols[dst[j] + k[j]] = v[j];
 }
 
 int32_t launch_build_windows(const ftc_csr &g, ftc_windows &w, void *ws, size_t ws_bytes, hipStream_t s)
@@ -827,7 +848,7 @@ int32_t launch_build_windows(const ftc_csr &g, ftc_windows &w, void *ws, size_t 
     st = launch_status("build_windows scan");
     if (st != FTC_OK) return st;
     if (g.nnz == 0) return FTC_OK;
-    hipLaunchKernelGGL(win_pack_kernel, dim3((g.nnz + 255) / 256), dim3(256), 0, s, g.nnz, g.row_ptr, w.blk_h,
+    hipLaunchKernelGGL(win_pack_kernel, dim3((g.nnz + 1023) / 1024), dim3(256), 0, s, g.nnz, g.row_ptr, w.blk_h,
                        w.edge_to_row, w.win_col_ptr, k.tmp_cols, w.win_cols);
     return launch_status("build_windows pack");
 }
