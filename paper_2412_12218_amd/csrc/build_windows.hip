@@ -135,6 +135,40 @@ __global__ void win_clear_kernel(int *counters)
     if (threadIdx.x < C_WORDS) counters[threadIdx.x] = 0;
 }
 
+// Inclusive prefix sum over the 64 lanes of a wave with data-parallel-primitive moves: shifts by
+// 1, 2, 4, 8 inside rows of 16 lanes, then lane 15 of a row added to the next row (rows 1 and 3) and
+// lane 31 added to rows 2 and 3.
+__device__ __forceinline__ int wave_inclusive_scan(int v)
+{
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true);   // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, true);   // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, true);   // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, true);   // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);  // row_bcast:15 into rows 1, 3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);  // row_bcast:31 into rows 2, 3
+    return v;
+}
+
+// Exclusive scan of one int per thread with a single barrier; `wave_tot` holds NT / 64 ints of LDS
+// and must not be written again before every thread has passed another barrier.
+template <int NT>
+__device__ __forceinline__ int block_scan_one_barrier(int v, int *wave_tot, int *total)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int incl = wave_inclusive_scan(v);
+    if (lane == 63) wave_tot[wave] = incl;
+    __syncthreads();
+    int off = 0, tot = 0;
+#pragma unroll
+    for (int k = 0; k < NT / 64; ++k) {
+        const int t = wave_tot[k];
+        off += k < wave ? t : 0;
+        tot += t;
+    }
+    *total = tot;
+    return off + incl - v;
+}
+
 // Index of the row that holds edge e: last a in [0, rows) with rp[a] <= e.
 __device__ __forceinline__ int row_of_edge(const int *rp, int rows, int e)
 {
@@ -192,10 +226,12 @@ __device__ __forceinline__ void condense_window_wave(int w, int r0, int rows, co
 {
     const int lane = threadIdx.x;
     const int e0 = rp[0];
+    // Register k of lane l starts with the column of edge k * 64 + l, so that loads and the stores
+    // below touch consecutive addresses in consecutive lanes (the sort takes its input in any order).
     int key[E], orig[E];
 #pragma unroll
     for (int k = 0; k < E; ++k) {
-        const int i = lane * E + k;
+        const int i = k * 64 + lane;
         orig[k] = i < cnt ? col_idx[e0 + i] : 0x7fffffff;
         key[k] = orig[k];
     }
@@ -211,26 +247,18 @@ __device__ __forceinline__ void condense_window_wave(int w, int r0, int rows, co
         flag[k] = i < cnt && (i == 0 || key[k] != before);
         mine += flag[k] ? 1 : 0;
     }
-    int incl = mine;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const int up = __shfl_up(incl, d, 64);
-        if (lane >= d) incl += up;
-    }
+    const int incl = wave_inclusive_scan(mine);
     const int n_uniq = __shfl(incl, 63, 64);
     int pos = incl - mine;
 #pragma unroll
     for (int k = 0; k < E; ++k) {
-        if (flag[k]) {
-            uniq_lds[pos] = key[k];
-            tmp_cols[e0 + pos] = key[k];
-            ++pos;
-        }
+        if (flag[k]) uniq_lds[pos++] = key[k];
     }
     __syncthreads();  // single-wave workgroup: makes the unique list visible to all lanes
+    for (int i = lane; i < n_uniq; i += 64) tmp_cols[e0 + i] = uniq_lds[i];
 #pragma unroll
     for (int k = 0; k < E; ++k) {
-        const int i = lane * E + k;
+        const int i = k * 64 + lane;
         if (i < cnt) {
             int lo = 0, hi = n_uniq;  // first index with uniq[idx] >= column
             while (lo < hi) {
@@ -306,40 +334,6 @@ constexpr int CW = (1 << CRANGE_LOG2) / 1024;  // coarse words per range
 constexpr int lds_stride_words(int words_per_thread)
 {
     return words_per_thread >= 4 && (words_per_thread / 4) % 2 == 0 ? words_per_thread + 4 : words_per_thread;
-}
-
-// Inclusive prefix sum over the 64 lanes of a wave with data-parallel-primitive moves: shifts by
-// 1, 2, 4, 8 inside rows of 16 lanes, then lane 15 of a row added to the next row (rows 1 and 3) and
-// lane 31 added to rows 2 and 3.
-__device__ __forceinline__ int wave_inclusive_scan(int v)
-{
-    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true);   // row_shr:1
-    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, true);   // row_shr:2
-    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, true);   // row_shr:4
-    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, true);   // row_shr:8
-    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);  // row_bcast:15 into rows 1, 3
-    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);  // row_bcast:31 into rows 2, 3
-    return v;
-}
-
-// Exclusive scan of one int per thread with a single barrier; `wave_tot` holds NT / 64 ints of LDS
-// and must not be written again before every thread has passed another barrier.
-template <int NT>
-__device__ __forceinline__ int block_scan_one_barrier(int v, int *wave_tot, int *total)
-{
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int incl = wave_inclusive_scan(v);
-    if (lane == 63) wave_tot[wave] = incl;
-    __syncthreads();
-    int off = 0, tot = 0;
-#pragma unroll
-    for (int k = 0; k < NT / 64; ++k) {
-        const int t = wave_tot[k];
-        off += k < wave ? t : 0;
-        tot += t;
-    }
-    *total = tot;
-    return off + incl - v;
 }
 
 // NT threads condense one window at a time.  RankT holds a rank inside one pass over the fine
@@ -716,6 +710,7 @@ __global__ __launch_bounds__(1024) void win_scan_kernel(int n_windows, int blk_w
     const int tid = threadIdx.x;
     const int shift = (blk_w & (blk_w - 1)) == 0 ? __ffs(blk_w) - 1 : -1;  // blk_w a power of two: no division
     auto blocks_of = [&](int u) { return shift >= 0 ? (u + blk_w - 1) >> shift : (u + blk_w - 1) / blk_w; };
+    const bool vec_ok = ((reinterpret_cast<uintptr_t>(win_col_ptr) | reinterpret_cast<uintptr_t>(block_partition)) & 15u) == 0;
     int carry = 0, parity = 0;
     long long my_blocks = 0;
     for (int super0 = 0; super0 < n_windows; super0 += 4096 * SCAN_ROUNDS) {  // uniform trip count
@@ -723,8 +718,13 @@ __global__ __launch_bounds__(1024) void win_scan_kernel(int n_windows, int blk_w
 #pragma unroll
         for (int r = 0; r < SCAN_ROUNDS; ++r) {
             const int first = super0 + r * 4096 + tid * 4;
+            if (first + 3 < n_windows) {  // uniq_count lives in the workspace: 256-byte aligned
+                const int4 v = *reinterpret_cast<const int4 *>(uniq_count + first);
+                u[r][0] = v.x; u[r][1] = v.y; u[r][2] = v.z; u[r][3] = v.w;
+            } else {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) u[r][j] = first + j < n_windows ? uniq_count[first + j] : 0;
+                for (int j = 0; j < 4; ++j) u[r][j] = first + j < n_windows ? uniq_count[first + j] : 0;
+            }
         }
 #pragma unroll
         for (int r = 0; r < SCAN_ROUNDS; ++r) {
@@ -734,14 +734,24 @@ __global__ __launch_bounds__(1024) void win_scan_kernel(int n_windows, int blk_w
             int run = carry + block_scan_one_barrier<1024>(u[r][0] + u[r][1] + u[r][2] + u[r][3],
                                                            wave_tot[parity], &round_total);
             parity ^= 1;
+            if (vec_ok && first + 3 < n_windows) {
+                // one 16-byte store per array: scalar stores with a lane stride of 16 bytes cost the
+                // single CU this kernel runs on four times as many memory instructions
+                const int p1 = run + u[r][0], p2 = p1 + u[r][1], p3 = p2 + u[r][2];
+                const int4 b = make_int4(blocks_of(u[r][0]), blocks_of(u[r][1]), blocks_of(u[r][2]), blocks_of(u[r][3]));
+                *reinterpret_cast<int4 *>(win_col_ptr + first) = make_int4(run, p1, p2, p3);
+                *reinterpret_cast<int4 *>(block_partition + first) = b;
+                my_blocks += static_cast<long long>(b.x) + b.y + b.z + b.w;
+            } else {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                if (first + j < n_windows) {
-                    win_col_ptr[first + j] = run;
-                    const int blocks = blocks_of(u[r][j]);
-                    block_partition[first + j] = blocks;
-                    my_blocks += blocks;
-                    run += u[r][j];
+                for (int j = 0; j < 4; ++j) {
+                    if (first + j < n_windows) {
+                        win_col_ptr[first + j] = run;
+                        const int blocks = blocks_of(u[r][j]);
+                        block_partition[first + j] = blocks;
+                        my_blocks += blocks;
+                        run += u[r][j];
+                    }
                 }
             }
             carry += round_total;
