@@ -99,10 +99,10 @@ def kernel_suite(tag, g, feat32, dtype, D, iters=20):
     win = B.ftc_build_windows(dg)
     vals, _ = B.ftc_gcn_norm(dg, win)
     X = torch.from_numpy(feat32).to(dtype).to(dev)
-    rinv = B.ftc_row_rnorm(X)
     out = torch.empty((g.n, D), dtype=torch.float32, device=dev)
     s_out = torch.empty(g.nnz, dtype=torch.float32, device=dev)
-    ws = B._workspace(B.lib().ftc_spmm_workspace_bytes(g.n, g.nnz, D), dev)
+    ws = B._workspace(max(B.lib().ftc_spmm_workspace_bytes(g.n, g.nnz, D),
+                          B.lib().ftc_sddmm_workspace_bytes(g.n, g.nnz, D)), dev)
     flush = torch.empty(1 << 28, dtype=torch.float32, device=dev)
     sum_uniq = int(win.summary[0].item())
     e = X.element_size()
@@ -110,7 +110,8 @@ def kernel_suite(tag, g, feat32, dtype, D, iters=20):
     nbytes = {"spmm": sum_uniq * D * e + g.nnz * 8 + g.n * D * 4 + rp,
               "sddmm": sum_uniq * D * e + g.n * D * e + g.nnz * 8 + rp}
     fns = {"spmm": lambda: B.ftc_spmm(dg, win, vals, X, out=out, ws=ws),
-           "sddmm": lambda: B.ftc_sddmm(dg, win, X, X, rinv, rinv, 1.0, out=s_out, ws=ws)}
+           # edge scores of AGNN: beta * cos(h_i, h_j), norms recomputed from the gathered rows
+           "sddmm": lambda: B.ftc_sddmm(dg, win, X, X, None, None, 1.0, out=s_out, ws=ws, cosine=True)}
     res = {"graph": tag, "n": g.n, "nnz": g.nnz, "sum_uniq": sum_uniq, "D": D, "dtype": str(dtype)[6:]}
     for op, fn in fns.items():
         for _ in range(5):

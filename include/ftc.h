@@ -143,12 +143,17 @@ int32_t ftc_spmm(const ftc_csr *g, const ftc_windows *w, const float *vals, cons
  *   i = row of e, j = col_idx[e].
  * X and Y have g->n rows, the same dtype and leading dimension, and may be the same
  * matrix.  row_scale / col_scale may be NULL (1.0).
+ * cosine != 0 selects the AGNN edge score instead: the scales are the inverse Euclidean norms of
+ * the rows themselves,
+ *   edge_out[e] = alpha * sum_k X[i,k] * Y[j,k] / (max(||X[i,:]||, 1e-12) * max(||Y[j,:]||, 1e-12)),
+ * row_scale and col_scale must then be NULL; no array of norms has to exist, the vector
+ * kernel recomputes them from the rows it has loaded.
  */
 size_t ftc_sddmm_workspace_bytes(int32_t n, int32_t nnz, int32_t D);
 int32_t ftc_sddmm(const ftc_csr *g, const ftc_windows *w, const void *X, const void *Y,
                   int32_t ld, int32_t dtype, int32_t D, const float *row_scale,
-                  const float *col_scale, float alpha, float *edge_out, int32_t path,
-                  void *ws, size_t ws_bytes, void *stream);
+                  const float *col_scale, float alpha, int32_t cosine, float *edge_out,
+                  int32_t path, void *ws, size_t ws_bytes, void *stream);
 
 /*
  * Inverse Euclidean row norms used by the AGNN cosine: rinv[i] = 1 / max(||H[i,:]||, 1e-12).

@@ -34,7 +34,7 @@ _SIGNATURES = {
     "ftc_spmm_workspace_bytes": (_Z, [_I, _I, _I]),
     "ftc_spmm": (_I, [_P, _P, _P, _P, _I, _I, _I, _P, _I, _I, _P, _I, _I, _P, _Z, _P]),
     "ftc_sddmm_workspace_bytes": (_Z, [_I, _I, _I]),
-    "ftc_sddmm": (_I, [_P, _P, _P, _P, _I, _I, _I, _P, _P, _F, _P, _I, _P, _Z, _P]),
+    "ftc_sddmm": (_I, [_P, _P, _P, _P, _I, _I, _I, _P, _P, _F, _I, _P, _I, _P, _Z, _P]),
     "ftc_row_rnorm": (_I, [_I, _P, _I, _I, _I, _P, _P]),
     "ftc_edge_softmax_workspace_bytes": (_Z, [_I, _I]),
     "ftc_edge_softmax": (_I, [_P, _P, _P, _P, _P, _Z, _P]),
@@ -186,7 +186,8 @@ def ftc_spmm(g, w, vals, X, out=None, out_dtype=torch.float32, relu=False, path=
     return out
 
 
-def ftc_sddmm(g, w, X, Y, row_scale=None, col_scale=None, alpha=1.0, out=None, path=FTC_PATH_AUTO, ws=None):
+def ftc_sddmm(g, w, X, Y, row_scale=None, col_scale=None, alpha=1.0, out=None, path=FTC_PATH_AUTO, ws=None,
+              cosine=False):
     D = X.shape[1]
     assert Y.shape[1] == D and X.stride(0) == Y.stride(0) and X.dtype == Y.dtype
     if out is None:
@@ -195,8 +196,8 @@ def ftc_sddmm(g, w, X, Y, row_scale=None, col_scale=None, alpha=1.0, out=None, p
         ws = _workspace(lib().ftc_sddmm_workspace_bytes(g.n, g.nnz, D), X.device)
     _check(lib().ftc_sddmm(C.byref(g.c), _wref(w), _ptr(X), _ptr(Y), C.c_int32(X.stride(0)),
                            C.c_int32(_dt(X)), C.c_int32(D), _ptr(row_scale), _ptr(col_scale),
-                           C.c_float(alpha), _ptr(out), C.c_int32(path), _ptr(ws), C.c_size_t(ws.numel()),
-                           _stream()))
+                           C.c_float(alpha), C.c_int32(1 if cosine else 0), _ptr(out), C.c_int32(path), _ptr(ws),
+                           C.c_size_t(ws.numel()), _stream()))
     return out
 
 

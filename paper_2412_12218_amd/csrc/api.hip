@@ -189,18 +189,22 @@ int32_t ftc_spmm(const ftc_csr *g, const ftc_windows *w, const float *vals, cons
 size_t ftc_sddmm_workspace_bytes(int32_t n, int32_t nnz, int32_t D)
 {
     if (n < 0 || nnz < 0 || D < 1) return 0;
-    return flag_bytes(n);
+    // window flags of the per-window dispatch, then two arrays of inverse row norms (cosine mode on
+    // the paths that do not recompute the norms from the rows)
+    return align_up(flag_bytes(n), 256) + 2 * align_up(static_cast<size_t>(n) * sizeof(float), 256);
 }
 
 int32_t ftc_sddmm(const ftc_csr *g, const ftc_windows *w, const void *X, const void *Y, int32_t ld,
                   int32_t dtype, int32_t D, const float *row_scale, const float *col_scale, float alpha,
-                  float *edge_out, int32_t path, void *ws, size_t ws_bytes, void *stream)
+                  int32_t cosine, float *edge_out, int32_t path, void *ws, size_t ws_bytes, void *stream)
 {
     FTC_TRY(check_csr(g, "ftc_sddmm"));
     if (g->n == 0 || g->nnz == 0) return FTC_OK;
     FTC_TRY(check_dense(X, ld, dtype, D, "ftc_sddmm", "X"));
     FTC_TRY(check_dense(Y, ld, dtype, D, "ftc_sddmm", "Y"));
     if (!edge_out) return fail(FTC_EINVAL, "ftc_sddmm: edge_out is NULL");
+    if (cosine && (row_scale || col_scale))
+        return fail(FTC_EINVAL, "ftc_sddmm: cosine mode takes no row_scale / col_scale");
     if (w) FTC_TRY(check_windows(g, w, "ftc_sddmm", true));
     if (path != FTC_PATH_AUTO && path != FTC_PATH_VALU && path != FTC_PATH_MFMA)
         return fail(FTC_EINVAL, "ftc_sddmm: unknown path %d", path);
@@ -212,25 +216,42 @@ int32_t ftc_sddmm(const ftc_csr *g, const ftc_windows *w, const void *X, const v
         return fail(FTC_EUNSUPPORTED,
                     "ftc_sddmm: the matrix-core path needs a window index with blk_h = 16, fp16/bf16 "
                     "features with D a multiple of 8 (<= 256) and 16-byte aligned rows");
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    const float reuse = path == FTC_PATH_MFMA ? 0.f : sddmm_mfma_reuse(D);
+    const bool use_mfma = can_mfma && path != FTC_PATH_VALU && reuse >= 0.f;
+    const bool need_ws = use_mfma || (cosine && !can_edges);
+    if (need_ws) {
+        const size_t need = ftc_sddmm_workspace_bytes(g->n, g->nnz, D);
+        if (!ws || ws_bytes < need)
+            return fail(FTC_EWORKSPACE, "ftc_sddmm: workspace of %zu bytes needed, %zu given", need,
+                        ws ? ws_bytes : static_cast<size_t>(0));
+        if (reinterpret_cast<uintptr_t>(ws) % 256 != 0)
+            return fail(FTC_EALIGN, "ftc_sddmm: workspace must be 256-byte aligned");
+    }
+    // Cosine mode: the edge-parallel vector kernel recomputes the norms from the rows it holds; the
+    // other kernels take them as scale arrays, which are produced here.
+    if (cosine && (use_mfma || !can_edges)) {
+        char *p = static_cast<char *>(ws) + align_up(flag_bytes(g->n), 256);
+        float *rx = reinterpret_cast<float *>(p);
+        float *ry = X == Y ? rx : reinterpret_cast<float *>(p + align_up(static_cast<size_t>(g->n) * sizeof(float), 256));
+        FTC_TRY(launch_row_rnorm(g->n, X, ld, dtype, D, rx, hs));
+        if (ry != rx) FTC_TRY(launch_row_rnorm(g->n, Y, ld, dtype, D, ry, hs));
+        row_scale = rx;
+        col_scale = ry;
+    }
     if (can_edges) {
-        hipStream_t hs = static_cast<hipStream_t>(stream);
         uint8_t *flags = nullptr;
-        const float reuse = path == FTC_PATH_MFMA ? 0.f : sddmm_mfma_reuse(D);
-        if (can_mfma && path != FTC_PATH_VALU && reuse >= 0.f) {
-            const size_t need = flag_bytes(g->n);
-            if (!ws || ws_bytes < need)
-                return fail(FTC_EWORKSPACE, "ftc_sddmm: workspace of %zu bytes needed, %zu given", need,
-                            ws ? ws_bytes : static_cast<size_t>(0));
+        if (use_mfma) {
             flags = static_cast<uint8_t *>(ws);
             FTC_TRY(launch_classify(*g, *w, reuse, MFMA_MAX_WINDOW_EDGES, flags, hs));
         }
-        FTC_TRY(launch_sddmm_edges(*g, *w, X, Y, ld, dtype, D, row_scale, col_scale, alpha, edge_out, flags, hs));
+        FTC_TRY(launch_sddmm_edges(*g, *w, X, Y, ld, dtype, D, row_scale, col_scale, alpha, edge_out, flags,
+                                   cosine != 0, hs));
         if (flags)
             return launch_sddmm_mfma(*g, *w, X, Y, ld, dtype, D, row_scale, col_scale, alpha, edge_out, flags, hs);
         return FTC_OK;
     }
-    return launch_sddmm_rows(*g, X, Y, ld, dtype, D, row_scale, col_scale, alpha, edge_out,
-                             static_cast<hipStream_t>(stream));
+    return launch_sddmm_rows(*g, X, Y, ld, dtype, D, row_scale, col_scale, alpha, edge_out, hs);
 }
 
 int32_t ftc_row_rnorm(int32_t n, const void *H, int32_t ld, int32_t dtype, int32_t D, float *rinv,
@@ -332,7 +353,7 @@ size_t ftc_agnn_layer_workspace_bytes(int32_t n, int32_t nnz, int32_t D)
 {
     if (n < 0 || nnz < 0 || D < 1) return 0;
     const size_t a = agnn_unfused_bytes(n, nnz, D), b = agnn_fused_ws(nnz, D);
-    return align_up(static_cast<size_t>(n) * sizeof(float), 256) + (a > b ? a : b);
+    return a > b ? a : b;
 }
 
 int32_t ftc_agnn_layer(const ftc_csr *g, const ftc_windows *w, const void *H, int32_t ld, int32_t dtype,
@@ -351,8 +372,6 @@ int32_t ftc_agnn_layer(const ftc_csr *g, const ftc_windows *w, const void *H, in
     if (reinterpret_cast<uintptr_t>(ws) % 256 != 0)
         return fail(FTC_EALIGN, "ftc_agnn_layer: workspace must be 256-byte aligned");
     char *p = static_cast<char *>(ws);
-    float *rinv = reinterpret_cast<float *>(p);
-    p += align_up(static_cast<size_t>(g->n) * sizeof(float), 256);
 
     // One pass over the edges when the probabilities are not asked for and the vector path applies.
     int vec, lpr;
@@ -362,7 +381,6 @@ int32_t ftc_agnn_layer(const ftc_csr *g, const ftc_windows *w, const void *H, in
         return launch_agnn_fused(*g, *w, H, ld, dtype, D, beta, out, ldo, out_dtype, p,
                                  static_cast<hipStream_t>(stream));
 
-    FTC_TRY(ftc_row_rnorm(g->n, H, ld, dtype, D, rinv, stream));
     float *scores = edge_p ? edge_p : reinterpret_cast<float *>(p);
     p += align_up(static_cast<size_t>(g->nnz) * sizeof(float), 256);
     const size_t sd = align_up(ftc_sddmm_workspace_bytes(g->n, g->nnz, D), 256);
@@ -372,7 +390,7 @@ int32_t ftc_agnn_layer(const ftc_csr *g, const ftc_windows *w, const void *H, in
     void *ws_softmax = p;
     p += sm;
     const size_t rest = ws_bytes - static_cast<size_t>(p - static_cast<char *>(ws));
-    FTC_TRY(ftc_sddmm(g, w, H, H, ld, dtype, D, rinv, rinv, beta, scores, path, ws_sddmm, sd, stream));
+    FTC_TRY(ftc_sddmm(g, w, H, H, ld, dtype, D, nullptr, nullptr, beta, 1, scores, path, ws_sddmm, sd, stream));
     FTC_TRY(ftc_edge_softmax(g, w, scores, scores, ws_softmax, sm, stream));
     return ftc_spmm(g, w, scores, H, ld, dtype, D, out, ldo, out_dtype, nullptr, 0, path, p, rest, stream);
 }

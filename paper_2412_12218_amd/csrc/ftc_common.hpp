@@ -55,7 +55,7 @@ int32_t launch_spmm_seg(const ftc_csr &g, const ftc_windows &w, const float *val
                         hipStream_t s);
 int32_t launch_sddmm_edges(const ftc_csr &g, const ftc_windows &w, const void *X, const void *Y, int ld, int dt,
                            int D, const float *rs, const float *cs, float alpha, float *out, const uint8_t *dense,
-                           hipStream_t s);
+                           bool cosine, hipStream_t s);
 size_t agnn_fused_ws(int nnz, int D);
 int32_t launch_agnn_fused(const ftc_csr &g, const ftc_windows &w, const void *H, int ld, int dt, int D,
                           float beta, void *out, int ldo, int odt, void *ws, hipStream_t s);

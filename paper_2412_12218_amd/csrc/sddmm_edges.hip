@@ -35,7 +35,11 @@ __device__ __forceinline__ float group_sum_dpp(float v)
     return v;
 }
 
-template <class T, int VEC, int LPR>
+// COS: the scores are cosines: every dot product is divided by the Euclidean norms of its two rows
+// (clamped at 1e-12), which are recomputed from the row slices that are in registers anyway (one more
+// packed dot product and lane-group sum per edge) instead of being gathered, 4 bytes at a time,
+// from arrays of inverse norms: on a graph without locality that gather moves a 64-byte sector per edge.
+template <class T, int VEC, int LPR, bool COS>
 __global__ __launch_bounds__(256) void sddmm_edges_kernel(int nnz, int n_ranges, const int *__restrict__ col_idx,
                                                           const int *__restrict__ edge_to_row,
                                                           const void *__restrict__ X,
@@ -79,6 +83,7 @@ __global__ __launch_bounds__(256) void sddmm_edges_kernel(int nnz, int n_ranges,
     const bool live = sub * VEC < D;
     RawVec<T, VEC> xi;  // slice of X[i,:] of the current row, as loaded
     zero_raw(xi);
+    float ri = 0.f;     // COS: 1 / max(||X[i,:]||, 1e-12)
     int cur = -1;
     // every group runs the same number of batches so that the lane shuffles stay converged
     for (int b = rs0; b < rs0 + RUN; b += SD_B) {
@@ -107,8 +112,13 @@ __global__ __launch_bounds__(256) void sddmm_edges_kernel(int nnz, int n_ranges,
         }
 #pragma unroll
         for (int k = 0; k < SD_B; ++k) {
-            if (need[k]) xi = xs[k];
-            const float d = group_sum_dpp<LPR>(dot_raw<T, VEC>(xi, y[k], 0.f));
+            if (need[k]) {  // the group's lanes branch together
+                xi = xs[k];
+                if constexpr (COS) ri = __frsqrt_rn(fmaxf(group_sum_dpp<LPR>(dot_raw<T, VEC>(xi, xi, 0.f)), 1e-24f));
+            }
+            float d = group_sum_dpp<LPR>(dot_raw<T, VEC>(xi, y[k], 0.f));
+            if constexpr (COS)
+                d *= ri * __frsqrt_rn(fmaxf(group_sum_dpp<LPR>(dot_raw<T, VEC>(y[k], y[k], 0.f)), 1e-24f));
             if (sub == 0 && r[k] >= 0) s_dot[b + k + g] = d;
         }
         cur = prev;
@@ -129,12 +139,19 @@ __global__ __launch_bounds__(256) void sddmm_edges_kernel(int nnz, int n_ranges,
 template <class T>
 static void launch_edges_t(int vec, int lpr, unsigned grid, hipStream_t s, int nnz, int n_ranges,
                            const ftc_csr &g, const int *e2r, const void *X, const void *Y, int ld, int D,
-                           const float *rs, const float *cs, float alpha, float *out, const uint8_t *dense)
+                           const float *rs, const float *cs, float alpha, float *out, const uint8_t *dense,
+                           bool cosine)
 {
     constexpr int VM = T::VEC;
-#define FTC_SD(V, L)                                                                                         \
-    hipLaunchKernelGGL((sddmm_edges_kernel<T, V, L>), dim3(grid), dim3(256), 0, s, nnz, n_ranges, g.col_idx, \
-                       e2r, X, Y, ld, D, rs, cs, alpha, out, dense)
+#define FTC_SD(V, L)                                                                                           \
+    do {                                                                                                       \
+        if (cosine)                                                                                            \
+            hipLaunchKernelGGL((sddmm_edges_kernel<T, V, L, true>), dim3(grid), dim3(256), 0, s, nnz, n_ranges, \
+                               g.col_idx, e2r, X, Y, ld, D, nullptr, nullptr, alpha, out, dense);              \
+        else                                                                                                   \
+            hipLaunchKernelGGL((sddmm_edges_kernel<T, V, L, false>), dim3(grid), dim3(256), 0, s, nnz,         \
+                               n_ranges, g.col_idx, e2r, X, Y, ld, D, rs, cs, alpha, out, dense);              \
+    } while (0)
     if (vec == VM) {
         if (lpr == 4) FTC_SD(VM, 4);
         else if (lpr == 8) FTC_SD(VM, 8);
@@ -151,7 +168,7 @@ static void launch_edges_t(int vec, int lpr, unsigned grid, hipStream_t s, int n
 // Caller has checked: window index present, seg_shape() accepts (dt, D), rows 16-byte aligned.
 int32_t launch_sddmm_edges(const ftc_csr &g, const ftc_windows &w, const void *X, const void *Y, int ld, int dt,
                            int D, const float *rs, const float *cs, float alpha, float *out, const uint8_t *dense,
-                           hipStream_t s)
+                           bool cosine, hipStream_t s)
 {
     if (g.nnz == 0) return FTC_OK;
     int vec = 0, lpr = 0;
@@ -159,12 +176,12 @@ int32_t launch_sddmm_edges(const ftc_csr &g, const ftc_windows &w, const void *X
     const int n_ranges = (g.nnz + SD_R - 1) / SD_R;
     const unsigned grid = static_cast<unsigned>((n_ranges + 3) / 4);
     if (dt == FTC_F32)
-        launch_edges_t<F32>(vec, lpr, grid, s, g.nnz, n_ranges, g, w.edge_to_row, X, Y, ld, D, rs, cs, alpha, out, dense);
+        launch_edges_t<F32>(vec, lpr, grid, s, g.nnz, n_ranges, g, w.edge_to_row, X, Y, ld, D, rs, cs, alpha, out, dense, cosine);
     else if (dt == FTC_F16)
-        launch_edges_t<F16>(vec, lpr, grid, s, g.nnz, n_ranges, g, w.edge_to_row, X, Y, ld, D, rs, cs, alpha, out, dense);
+        launch_edges_t<F16>(vec, lpr, grid, s, g.nnz, n_ranges, g, w.edge_to_row, X, Y, ld, D, rs, cs, alpha, out, dense, cosine);
     else
         launch_edges_t<BF16>(vec, lpr, grid, s, g.nnz, n_ranges, g, w.edge_to_row, X, Y, ld, D, rs, cs, alpha,
-                             out, dense);
+                             out, dense, cosine);
     return launch_status("sddmm_edges");
 }
 

@@ -103,6 +103,12 @@ def test_cfg4_spmm_sddmm_full(oracle, threads):
     serr = norm_err(s, sref, sab)
     say(f"  sddmm err {serr:.3e}")
     assert serr < 2e-3
+    # the call bench.py times: cosine mode, norms recomputed in the kernel
+    sref, sab = oracle.sddmm(g.row_ptr, g.col_idx, X64, X64, rinv64, rinv64, 1.0)
+    s = B.ftc_sddmm(dg, win, Xd, Xd, cosine=True)
+    serr = norm_err(s, sref, sab)
+    say(f"  sddmm (cosine) err {serr:.3e}")
+    assert serr < 2e-3
 
 
 def test_cfg5_models_layer_by_layer(oracle, threads):

@@ -325,6 +325,37 @@ def test_sddmm_paths(oracle, graphs, name, dtype, D, path):
         assert run_sddmm(oracle, g, dtype, D, path=path, scales=False, same=True) < TOL[dtype]
 
 
+@pytest.mark.parametrize("name", ["cfg1", "cfg5s", "hub", "mixed"])
+@pytest.mark.parametrize("dtype,D", [(F16, 32), (BF16, 64), (F32, 16), (F16, 8), (F16, 256), (F16, 5)])
+@pytest.mark.parametrize("path", [B.FTC_PATH_AUTO, B.FTC_PATH_MFMA, B.FTC_PATH_VALU])
+@pytest.mark.parametrize("same", [True, False])
+def test_sddmm_cosine(oracle, graphs, name, dtype, D, path, same):
+    """AGNN edge scores alpha * cos(x_i, y_j) without arrays of norms, on every kernel family and
+    without a window index; the oracle gets the inverse norms it computes itself.  One row is zero:
+    its scores must be exactly 0."""
+    g = graphs[name]
+    if path == B.FTC_PATH_MFMA and (dtype == F32 or D % 8):
+        pytest.skip("matrix-core path needs 16-bit rows of 16-byte pieces")
+    rng = np.random.default_rng(41)
+    X32 = rng.standard_normal((g.n, D)).astype(np.float32)
+    X32[3] = 0
+    Xd, X64 = quantise(X32, dtype)
+    if same:
+        Yd, Y64 = Xd, X64
+    else:
+        Yd, Y64 = quantise(rng.standard_normal((g.n, D)).astype(np.float32) * 3, dtype)
+    ref, ab = oracle.sddmm(g.row_ptr, g.col_idx, X64, Y64, oracle.row_rnorm(X64), oracle.row_rnorm(Y64), -1.5)
+    dg = dev_graph(g)
+    for win in (B.ftc_build_windows(dg), None):
+        out = B.ftc_sddmm(dg, win, Xd, Yd, alpha=-1.5, path=path if win else 0, cosine=True)
+        err = norm_err(out, ref, ab)
+        say(f"sddmm cosine {name} {dtype} D={D} path={path} same={same} windows={win is not None} err {err:.3e}")
+        assert err < TOL[dtype]
+        assert float(out.abs().max()) <= 1.5 * (1 + 1e-3)
+    with pytest.raises(B.FtcError):
+        B.ftc_sddmm(dg, None, Xd, Yd, row_scale=torch.ones(g.n, device="cuda"), cosine=True)
+
+
 @pytest.mark.parametrize("dtype,D,pad", [(F16, 24, 0), (F16, 5, 0), (F32, 7, 1), (BF16, 40, 8), (F16, 32, 32)])
 def test_sddmm_odd_shapes(oracle, graphs, dtype, D, pad):
     say(f"sddmm odd {dtype} D={D} pad={pad}")
