@@ -113,7 +113,7 @@ __global__ __launch_bounds__(256) void agnn_fused_kernel(int nnz, int n_ranges, 
 
     auto direct_store = [&](int row) {
         if (live) {
-            const float inv = __frcp_rn(z);
+            const float inv = __builtin_amdgcn_rcpf(z);  // v_rcp_f32: one ulp, one instruction
             float o[VEC];
 #pragma unroll
             for (int j = 0; j < VEC; ++j) o[j] = acc[j] * inv;

@@ -619,19 +619,30 @@ __global__ __launch_bounds__(256) void hub_edges_kernel(int n, const int *__rest
             col[q] = e < e1 ? col_idx[e] : -1;
         }
         if constexpr (!RANK) {
+            const int lane = tid & 63;
 #pragma unroll
             for (int q = 0; q < PER; ++q) {
                 const int e = e0 + tid + q * 256;
-                if (col[q] >= 0) {
-                    edge_to_row[e] = r0 + row_of_edge(rp, rows, e);
-                    // Popular columns are hit by thousands of edges of a hub, and atomics on one
-                    // address serialise: read the word first (from L2, where the atomics execute)
-                    // and skip the atomic once the bit is there.  Bits are only ever set, so a set
-                    // bit that is read is never wrong.  (Issuing all the reads of a thread before its
-                    // first atomic was measured slower: fewer reads then see the bit.)
-                    uint32_t *word = &bm[col[q] >> 5];
-                    const uint32_t bit = 1u << (col[q] & 31);
-                    if (!(__hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & bit)) atomicOr(word, bit);
+                if (col[q] >= 0) edge_to_row[e] = r0 + row_of_edge(rp, rows, e);
+                // Consecutive lanes hold consecutive edges, and inside a (sorted) row consecutive
+                // edges of a hub often fall into the same bitmap word: their bits are OR-ed along
+                // the lanes (a scan over runs of equal words) and only the last lane of a run goes
+                // to memory.  Atomics on one address serialise, and the popular columns of a hub are
+                // hit thousands of times; for the same reason the word is read first (from L2,
+                // where the atomics execute) and the atomic is skipped when nothing is missing.
+                // Bits are only ever set, so a set bit that is read is never wrong.
+                const int word = col[q] >= 0 ? col[q] >> 5 : -1 - lane;  // invalid lanes match nobody
+                uint32_t bits = col[q] >= 0 ? 1u << (col[q] & 31) : 0u;
+#pragma unroll
+                for (int d = 1; d < 64; d <<= 1) {
+                    const int ow = __shfl_up(word, d, 64);
+                    const uint32_t ob = __shfl_up(bits, d, 64);
+                    if (lane >= d && ow == word) bits |= ob;
+                }
+                const int nw = __shfl_down(word, 1, 64);
+                if (col[q] >= 0 && (lane == 63 || nw != word)) {
+                    uint32_t *p = &bm[word];
+                    if ((__hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & bits) != bits) atomicOr(p, bits);
                 }
             }
         } else {
@@ -783,9 +794,15 @@ __global__ __launch_bounds__(256) void win_pack_kernel(int nnz, const int *__res
                                                        int *__restrict__ win_cols)
 {
     const int64_t e0 = static_cast<int64_t>(blockIdx.x) * 1024 + threadIdx.x;
-    int w[4], k[4], dst[4], len[4];
+    int w[4], k[4], dst[4], len[4], v[4];
+    // the slot's content is loaded together with the edge's row (13 % of the slots on the R-MAT
+    // workload hold no list entry and are read in vain): one step less in the chain of dependent loads
 #pragma unroll
-    for (int j = 0; j < 4; ++j) w[j] = e0 + j * 256 < nnz ? edge_to_row[e0 + j * 256] / blk_h : -1;
+    for (int j = 0; j < 4; ++j) {
+        const bool ok = e0 + j * 256 < nnz;
+        w[j] = ok ? edge_to_row[e0 + j * 256] / blk_h : -1;
+        v[j] = ok ? tmp_cols[e0 + j * 256] : 0;
+    }
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         if (w[j] >= 0) {
@@ -794,10 +811,6 @@ __global__ __launch_bounds__(256) void win_pack_kernel(int nnz, const int *__res
             len[j] = win_col_ptr[w[j] + 1] - dst[j];
         }
     }
-    int v[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-        if (w[j] >= 0 && k[j] < len[j]) v[j] = tmp_cols[e0 + j * 256];
 #pragma unroll
     for (int j = 0; j < 4; ++j)
         if (w[j] >= 0 && k[j] < len[j]) win_cols[dst[j] + k[j]] = v[j];
