@@ -52,7 +52,7 @@ size_t agnn_fused_ws(int nnz, int D)
     if (seg_shape(FTC_F16, D, &vec, &lpr) && vec * lpr > dp) dp = vec * lpr;
     if (dp == 0 || nnz == 0) return 0;
     const size_t n_ranges = (static_cast<size_t>(nnz) + AG_R - 1) / AG_R;
-    return align_up(n_ranges * 2 * (dp + 4) * sizeof(float), 256) + align_up(n_ranges * sizeof(int), 256);
+    return align_up(n_ranges * 2 * (dp + 4) * sizeof(float), 256) + align_up(n_ranges * 2 * sizeof(int), 256);
 }
 
 template <class T, int VEC, int LPR>
@@ -93,6 +93,8 @@ __global__ __launch_bounds__(256) void agnn_fused_kernel(int nnz, int n_ranges, 
     }
     const int prev_row = (active && base > 0) ? edge_to_row[base - 1] : -1;
     const int next_row = (active && n_valid == AG_R && base + AG_R < nnz) ? edge_to_row[base + AG_R] : -1;
+    // row of the first edge after the NEXT range: tells whether a row left open here ends there
+    const int far_row = (active && base + 2 * AG_R < nnz) ? edge_to_row[base + 2 * AG_R] : -1;
     __syncthreads();
 
     const int rs = g * RUN;
@@ -264,7 +266,10 @@ __global__ __launch_bounds__(256) void agnn_fused_kernel(int nnz, int n_ranges, 
                 }
             }
         }
-        if (lane == 0) carry_tail_row[v] = tail_out;
+        if (lane == 0) {
+            carry_tail_row[2 * v] = tail_out;
+            carry_tail_row[2 * v + 1] = (tail_out >= 0 && far_row != tail_out) ? 1 : 0;  // ends in range v + 1
+        }
     }
 }
 
@@ -277,8 +282,30 @@ __global__ __launch_bounds__(256) void agnn_fused_fixup_kernel(int n, int n_rang
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int v = blockIdx.x * 4 + wave;
     if (v < n_ranges) {
-        const int r = carry_tail_row[v];
-        if (r >= 0) {
+        // Nearly every open row ends in the next range: numerator and denominator are the head
+        // piece of range v + 1 plus the tail piece of range v.  Their addresses depend on v alone,
+        // so they are loaded together with the range's record instead of after it.
+        const int2 rec = reinterpret_cast<const int2 *>(carry_tail_row)[v];
+        float spec[4], spec_z = 1.f;
+        {
+            const float *hv = carry + (static_cast<size_t>(v + 1) * 2) * DPZ;
+            const float *tv = carry + (static_cast<size_t>(v) * 2 + 1) * DPZ;
+            const bool ok = v + 1 < n_ranges;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int d = i * 64 + lane;
+                spec[i] = (ok && d < D) ? hv[d] + tv[d] : 0.f;
+            }
+            if (ok) spec_z = hv[DP] + tv[DP];
+        }
+        const int r = rec.x;
+        if (r >= 0 && rec.y) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int d = i * 64 + lane;
+                if (d < D) store_elem(out, static_cast<int64_t>(r) * ldo + d, odt, spec[i] / spec_z);
+            }
+        } else if (r >= 0) {
             const int last = (row_ptr[r + 1] - 1) / AG_R;
             // teams of `dl` lanes (one lane per feature) share the ranges of a long row round-robin,
             // four loads in flight each; team sums are added in team order (fixed by the shape)

@@ -53,7 +53,7 @@ size_t spmm_seg_ws(int nnz, int D)
     if (seg_shape(FTC_F16, D, &vec, &lpr) && vec * lpr > dp) dp = vec * lpr;
     if (dp == 0 || nnz == 0) return 0;
     const size_t n_ranges = (static_cast<size_t>(nnz) + SEG_R - 1) / SEG_R;
-    return align_up(n_ranges * 2 * dp * sizeof(float), 256) + align_up(n_ranges * sizeof(int), 256);
+    return align_up(n_ranges * 2 * dp * sizeof(float), 256) + align_up(n_ranges * 2 * sizeof(int), 256);
 }
 
 template <class T, int VEC, int LPR>
@@ -99,6 +99,8 @@ __global__ __launch_bounds__(256) void spmm_seg_kernel(int nnz, int n_ranges, co
     }
     const int prev_row = (active && base > 0) ? edge_to_row[base - 1] : -1;
     const int next_row = (active && n_valid == SEG_R && base + SEG_R < nnz) ? edge_to_row[base + SEG_R] : -1;
+    // row of the first edge after the NEXT range: tells whether a row left open here ends there
+    const int far_row = (active && base + 2 * SEG_R < nnz) ? edge_to_row[base + 2 * SEG_R] : -1;
     __syncthreads();
 
     const int rs = g * RUN;
@@ -233,7 +235,10 @@ __global__ __launch_bounds__(256) void spmm_seg_kernel(int nnz, int n_ranges, co
                 }
             }
         }
-        if (lane == 0) carry_tail_row[v] = tail_out;
+        if (lane == 0) {
+            carry_tail_row[2 * v] = tail_out;
+            carry_tail_row[2 * v + 1] = (tail_out >= 0 && far_row != tail_out) ? 1 : 0;  // ends in range v + 1
+        }
     }
 }
 
@@ -247,8 +252,26 @@ __global__ __launch_bounds__(256) void spmm_seg_fixup_kernel(int n, int n_ranges
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int v = blockIdx.x * 4 + wave;
     if (v < n_ranges) {
-        const int r = carry_tail_row[v];
-        if (r >= 0 && !(dense && dense[r >> 4])) {
+        // Nearly every open row ends in the next range: out = head piece of range v + 1 + tail piece
+        // of range v.  Their addresses depend on v alone, so they are loaded together with the
+        // range's record instead of after it (the kernel is a chain of dependent loads otherwise).
+        const int2 rec = reinterpret_cast<const int2 *>(carry_tail_row)[v];
+        float spec[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int d = i * 64 + lane;
+            spec[i] = 0.f;
+            if (d < D && v + 1 < n_ranges)
+                spec[i] = carry[(static_cast<size_t>(v + 1) * 2) * DP + d] + carry[(static_cast<size_t>(v) * 2 + 1) * DP + d];
+        }
+        const int r = rec.x;
+        if (r >= 0 && !(dense && dense[r >> 4]) && rec.y) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int d = i * 64 + lane;
+                if (d < D) store_elem(out, static_cast<int64_t>(r) * ldo + d, odt, epi.apply(epi.factor(r), spec[i]));
+            }
+        } else if (r >= 0 && !(dense && dense[r >> 4])) {
             const int last = (row_ptr[r + 1] - 1) / SEG_R;  // wave range holding the row's final edge
             // A hub row can span hundreds of ranges.  The 64 lanes are split into `parts` teams of
             // `dl` lanes (one lane per feature); team p adds the head pieces of ranges v+1+p,
