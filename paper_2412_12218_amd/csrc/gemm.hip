@@ -86,7 +86,7 @@ template <class T, int KS, int NT>  // KS = ceil(d_in / 32), NT = ceil(d_out / 1
 __global__ __launch_bounds__(256) void gemm_mfma_kernel(int n, const uint16_t *__restrict__ X, int ldx, int d_in,
                                                         const uint16_t *__restrict__ W, int d_out,
                                                         void *__restrict__ Z, int ldz, int zdt, Epi epi,
-                                                        int n_tiles)
+                                                        int n_tiles, bool vec_store)
 {
     constexpr int KP = KS * 32 + 8;  // padded k extent of a W^T row (keeps 16-byte alignment, spreads banks)
     __shared__ __attribute__((aligned(16))) uint16_t Wt[NT * 16 * KP];
@@ -105,6 +105,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int n, const uint16_t *_
         for (int nt = 0; nt < NT; ++nt)
             breg[ks][nt] = *reinterpret_cast<const uint4 *>(&Wt[(nt * 16 + m) * KP + ks * 32 + kb * 8]);
 
+    constexpr int ZP = NT * 16 + 4;  // row stride of the output patch (16-byte aligned, spreads banks)
+    __shared__ __attribute__((aligned(16))) float Zs[4][16 * ZP];
     const int stride = gridDim.x * 4 * GEMM_RT;
     for (int tile0 = (blockIdx.x * 4 + wave) * GEMM_RT; tile0 < n_tiles; tile0 += stride) {
         uint4 a[GEMM_RT][KS];
@@ -120,17 +122,60 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int n, const uint16_t *_
         }
 #pragma unroll
         for (int rt = 0; rt < GEMM_RT; ++rt) {
+            float4v c[NT];
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
-                float4v c = {0.f, 0.f, 0.f, 0.f};
+                c[nt] = float4v{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) c = mfma16<T>(a[rt][ks], breg[ks][nt], c);
-                const int col = nt * 16 + m;
+                for (int ks = 0; ks < KS; ++ks) c[nt] = mfma16<T>(a[rt][ks], breg[ks][nt], c[nt]);
+            }
+            if (vec_store) {
+                // The accumulators hold columns (lane = column, register = row): written as they are,
+                // a 16-bit output would leave in 2-byte pieces, four store instructions per 16 x 16
+                // tile.  The tile is turned through LDS instead (each wave has its own patch; LDS
+                // operations of one wave execute in order) so that a lane holds 4 NT consecutive
+                // columns of one row and the tile leaves in one or two 8- or 16-byte stores per lane.
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int row = (tile0 + rt) * 16 + kb * 4 + i;
-                    if (row < n && col < d_out)
-                        store_elem(Z, static_cast<int64_t>(row) * ldz + col, zdt, epi.apply(epi.factor(row), c[i]));
+                for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) Zs[wave][(kb * 4 + i) * ZP + nt * 16 + m] = c[nt][i];
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                const int r = lane >> 2, c0 = (lane & 3) * (4 * NT);
+                const int row = (tile0 + rt) * 16 + r;
+                float o[4 * NT];
+#pragma unroll
+                for (int q = 0; q < NT; ++q) {
+                    const float4 v = *reinterpret_cast<const float4 *>(&Zs[wave][r * ZP + c0 + 4 * q]);
+                    o[4 * q] = v.x; o[4 * q + 1] = v.y; o[4 * q + 2] = v.z; o[4 * q + 3] = v.w;
+                }
+                if (row < n && c0 < d_out) {
+                    const float f = epi.factor(row);
+#pragma unroll
+                    for (int j = 0; j < 4 * NT; ++j) o[j] = epi.apply(f, o[j]);
+                    if constexpr (NT == 1) {
+                        store_vec<4>(Z, static_cast<int64_t>(row) * ldz + c0, zdt, reinterpret_cast<float(&)[4]>(o));
+                    } else {
+#pragma unroll
+                        for (int q = 0; q < NT / 2; ++q)
+                            store_vec<8>(Z, static_cast<int64_t>(row) * ldz + c0 + 8 * q, zdt,
+                                         reinterpret_cast<float(&)[8]>(o[8 * q]));
+                    }
+                }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();  // the patch is rewritten by the next tile
+            } else {
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) {
+                    const int col = nt * 16 + m;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const int row = (tile0 + rt) * 16 + kb * 4 + i;
+                        if (row < n && col < d_out)
+                            store_elem(Z, static_cast<int64_t>(row) * ldz + col, zdt,
+                                       epi.apply(epi.factor(row), c[nt][i]));
+                    }
                 }
             }
         }
@@ -147,7 +192,11 @@ static bool gemm_mfma_t(int n, const void *X, int ldx, int d_in, const void *W, 
     if (grid > 256 * 8) grid = 256 * 8;
     const uint16_t *x = static_cast<const uint16_t *>(X);
     const uint16_t *w = static_cast<const uint16_t *>(W);
-#define FTC_G(K, N)                                                                                                 if (ks == K && nt == N) {                                                                                           hipLaunchKernelGGL((gemm_mfma_kernel<T, K, N>), dim3(grid), dim3(256), 0, s, n, x, ldx, d_in, w, d_out, Z,                            ldz, zdt, epi, n_tiles);                                                                    return true;                                                                                                }
+    // whole groups of 4 NT columns per lane, each group 8- or 16-byte aligned in the output
+    const int zsize = zdt == FTC_F32 ? 4 : 2;
+    const bool vec_store = d_out % (4 * nt) == 0 && aligned16(Z) && (static_cast<int64_t>(ldz) * zsize) % 16 == 0 &&
+                           (nt == 1 || nt % 2 == 0);
+#define FTC_G(K, N)                                                                                                 if (ks == K && nt == N) {                                                                                           hipLaunchKernelGGL((gemm_mfma_kernel<T, K, N>), dim3(grid), dim3(256), 0, s, n, x, ldx, d_in, w, d_out, Z,                            ldz, zdt, epi, n_tiles, vec_store);                                                                    return true;                                                                                                }
     FTC_G(1, 1) FTC_G(1, 2) FTC_G(2, 1) FTC_G(2, 2) FTC_G(4, 1) FTC_G(4, 2) FTC_G(4, 4) FTC_G(2, 4) FTC_G(1, 4)
     FTC_G(8, 1) FTC_G(8, 2) FTC_G(8, 4) FTC_G(3, 1) FTC_G(3, 2) FTC_G(3, 4)
 #undef FTC_G
