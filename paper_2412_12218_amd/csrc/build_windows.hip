@@ -21,6 +21,8 @@
 // win_col_ptr / block_partition / summary and a last kernel packs the lists into win_cols.
 #include "ftc_common.hpp"
 
+#include <mutex>
+
 namespace ftc {
 
 constexpr int WAVE_CAP = 1024;      // edges per window sorted by a single wave in registers
@@ -180,6 +182,35 @@ __device__ __forceinline__ int row_of_edge(const int *rp, int rows, int e)
     return a;
 }
 
+// ---- classification: queues of the windows that are too large for a single wave -------------------
+// One thread per window.  Queue positions come from one atomic per size class and workgroup (the
+// entries of a workgroup are numbered in LDS first): thousands of atomics on one address would
+// serialise.
+__global__ __launch_bounds__(1024) void win_classify_kernel(int n, int n_windows, const int *__restrict__ row_ptr,
+                                                            int blk_h, int hub_thr, int *__restrict__ list_mid,
+                                                            int *__restrict__ list_large,
+                                                            int *__restrict__ list_hub, int *counters)
+{
+    __shared__ int cnt_s[3], base_s[3];
+    if (threadIdx.x < 3) cnt_s[threadIdx.x] = 0;
+    __syncthreads();
+    const int w = blockIdx.x * 1024 + threadIdx.x;
+    int cls = -1, pos = 0;
+    if (w < n_windows) {
+        const int r0 = w * blk_h;
+        const int cnt = row_ptr[min(n, r0 + blk_h)] - row_ptr[r0];
+        if (cnt > WAVE_CAP) cls = cnt <= MID_CAP ? 0 : (cnt <= hub_thr ? 1 : 2);
+    }
+    if (cls >= 0) pos = atomicAdd(&cnt_s[cls], 1);
+    __syncthreads();
+    if (threadIdx.x < 3 && cnt_s[threadIdx.x] > 0)
+        base_s[threadIdx.x] = atomicAdd(&counters[threadIdx.x], cnt_s[threadIdx.x]);  // C_MID, C_LARGE, C_HUB
+    __syncthreads();
+    if (cls == 0) list_mid[base_s[0] + pos] = w;
+    else if (cls == 1) list_large[base_s[1] + pos] = w;
+    else if (cls == 2) list_hub[base_s[2] + pos] = w;
+}
+
 // ---- windows of at most WAVE_CAP edges: one wave, keys in registers --------------------------------
 // Element i of the padded key array lives in lane i / E, register i % E.
 template <int E>
@@ -279,11 +310,9 @@ __device__ __forceinline__ void condense_window_wave(int w, int r0, int rows, co
 
 __global__ __launch_bounds__(64) void win_wave_kernel(int n, const int *__restrict__ row_ptr,
                                                       const int *__restrict__ col_idx, int blk_h,
-                                                      int hub_thr, int *__restrict__ edge_to_row,
+                                                      int *__restrict__ edge_to_row,
                                                       int *__restrict__ edge_to_col,
-                                                      int *__restrict__ uniq_count, int *__restrict__ tmp_cols,
-                                                      int *__restrict__ list_mid, int *__restrict__ list_large,
-                                                      int *__restrict__ list_hub, int *counters)
+                                                      int *__restrict__ uniq_count, int *__restrict__ tmp_cols)
 {
     __shared__ int uniq_lds[WAVE_CAP];
     __shared__ int rp[65];
@@ -293,14 +322,7 @@ __global__ __launch_bounds__(64) void win_wave_kernel(int n, const int *__restri
     for (int t = threadIdx.x; t <= rows; t += 64) rp[t] = row_ptr[r0 + t];
     __syncthreads();
     const int cnt = rp[rows] - rp[0];
-    if (cnt > WAVE_CAP) {  // queued for the workgroup kernels, by size class
-        if (threadIdx.x == 0) {
-            if (cnt <= MID_CAP) list_mid[atomicAdd(&counters[C_MID], 1)] = w;
-            else if (cnt <= hub_thr) list_large[atomicAdd(&counters[C_LARGE], 1)] = w;
-            else list_hub[atomicAdd(&counters[C_HUB], 1)] = w;
-        }
-        return;
-    }
+    if (cnt > WAVE_CAP) return;  // queued by the classification kernel for the workgroup kernels
     if (cnt == 0) {
         if (threadIdx.x == 0) uniq_count[w] = 0;
         return;
@@ -816,6 +838,50 @@ __global__ __launch_bounds__(256) void win_pack_kernel(int nnz, const int *__res
         if (w[j] >= 0 && k[j] < len[j]) win_cols[dst[j] + k[j]] = v[j];
 }
 
+// Side streams for the kernels that do not depend on each other (created once per process and
+// device, default priority, never destroyed).  The classes of windows are condensed by different
+// kernels, each of which fills only part of the GPU; after the classification they run side by
+// side: the caller's stream forks into the side streams with an event and joins them again before
+// the scan.  Nothing here waits on the host.
+namespace {
+struct SideStreams {
+    int device = -1;
+    hipStream_t stream[3] = {nullptr, nullptr, nullptr};
+    hipEvent_t fork = nullptr;
+    hipEvent_t join[3] = {nullptr, nullptr, nullptr};
+    bool ok = false;
+};
+SideStreams g_side;
+std::mutex g_side_mutex;
+
+// Returns nullptr when streams or events cannot be created: the caller then runs everything on its
+// own stream.
+SideStreams *side_streams()
+{
+    std::lock_guard<std::mutex> lock(g_side_mutex);
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    if (g_side.ok && g_side.device == dev) return &g_side;
+    if (g_side.ok) return nullptr;  // another device than the one the streams live on: no side streams
+    SideStreams t;
+    t.device = dev;
+    bool good = hipEventCreateWithFlags(&t.fork, hipEventDisableTiming) == hipSuccess;
+    for (int i = 0; i < 3 && good; ++i)
+        good = hipStreamCreateWithFlags(&t.stream[i], hipStreamNonBlocking) == hipSuccess &&
+               hipEventCreateWithFlags(&t.join[i], hipEventDisableTiming) == hipSuccess;
+    if (!good) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    t.ok = true;
+    g_side = t;
+    return &g_side;
+}
+}  // namespace
+
 int32_t launch_build_windows(const ftc_csr &g, ftc_windows &w, void *ws, size_t ws_bytes, hipStream_t s)
 {
     (void)ws_bytes;
@@ -826,46 +892,87 @@ int32_t launch_build_windows(const ftc_csr &g, ftc_windows &w, void *ws, size_t 
         return launch_status("build_windows scan");
     }
     const int hub_thr = hub_threshold(g.n, g.nnz);
-    hipLaunchKernelGGL(win_clear_kernel, dim3(1), dim3(64), 0, s, k.counters);
-    hipLaunchKernelGGL(win_wave_kernel, dim3(w.n_windows), dim3(64), 0, s, g.n, g.row_ptr, g.col_idx, w.blk_h,
-                       hub_thr, w.edge_to_row, w.edge_to_col, k.uniq_count, k.tmp_cols, k.list_mid, k.list_large,
-                       k.list_hub, k.counters);
-    int32_t st = launch_status("build_windows wave");
-    if (st != FTC_OK) return st;
-    if (g.nnz > WAVE_CAP) {  // otherwise no window can be queued
-        // the grids are upper bounds of the queue lengths; surplus workgroups leave at once
-        // persistent grids: as many workgroups as fit on the chip at once (registers allow three
-        // 256-thread or one 1024-thread workgroup per CU), never more than the queue can hold
-#define FTC_RANGE(NT, SLOTS, RANK, PER_CU, CAP, LIST, COUNTER, NEXT)                                          \
-    hipLaunchKernelGGL((win_compact_kernel<NT, SLOTS, RANK, PER_CU>),                                         \
-                       dim3(CAP < PER_CU * N_CU ? CAP : PER_CU * N_CU),                                       \
-                       dim3(NT), 0, s, g.n, g.row_ptr, g.col_idx, w.blk_h, w.edge_to_row, w.edge_to_col,      \
-                       k.uniq_count, k.tmp_cols, LIST, k.counters + COUNTER, k.counters + NEXT)
-        FTC_RANGE(256, 2048, uint16_t, 5, k.cap_mid, k.list_mid, C_MID, C_MID_NEXT);
-        st = launch_status("build_windows compact (mid)");
+    const bool queued = g.nnz > WAVE_CAP;  // otherwise no window can be queued
+    int32_t st;
+    hipStream_t s_mid = s, s_large = s, s_hub = s;
+    SideStreams *side = nullptr;
+    if (queued) {
+        hipLaunchKernelGGL(win_clear_kernel, dim3(1), dim3(64), 0, s, k.counters);
+        hipLaunchKernelGGL(win_classify_kernel, dim3((w.n_windows + 1023) / 1024), dim3(1024), 0, s, g.n,
+                           w.n_windows, g.row_ptr, w.blk_h, hub_thr, k.list_mid, k.list_large, k.list_hub,
+                           k.counters);
+        st = launch_status("build_windows classify");
         if (st != FTC_OK) return st;
-        if (g.nnz > MID_CAP) {
-            FTC_RANGE(1024, 8192, uint32_t, 1, k.cap_large, k.list_large, C_LARGE, C_LARGE_NEXT);
-            st = launch_status("build_windows compact (large)");
-            if (st != FTC_OK) return st;
-        }
-#undef FTC_RANGE
-        if (g.nnz > hub_thr) {
-            hipLaunchKernelGGL(hub_plan_kernel, dim3(1), dim3(1024), 0, s, g.n, g.row_ptr, w.blk_h, k.list_hub,
-                               k.counters, k.hub_chunk_ptr, k.chunk_table);
-            hipLaunchKernelGGL(hub_clear_kernel, dim3(512), dim3(256), 0, s, k.counters, k.hub_bits, k.wps);
-            hipLaunchKernelGGL((hub_edges_kernel<false>), dim3(HUB_GRID), dim3(256), 0, s, g.n, g.row_ptr, g.col_idx,
-                               w.blk_h, k.list_hub, k.counters, k.hub_chunk_ptr, k.chunk_table, k.hub_bits,
-                               k.hub_grp, k.wps, w.edge_to_row, w.edge_to_col, k.tmp_cols);
-            hipLaunchKernelGGL(hub_scan_kernel, dim3(k.slots), dim3(1024), 0, s, k.list_hub, k.counters, k.hub_bits,
-                               k.hub_grp, k.wps, k.uniq_count);
-            hipLaunchKernelGGL((hub_edges_kernel<true>), dim3(HUB_GRID), dim3(256), 0, s, g.n, g.row_ptr, g.col_idx,
-                               w.blk_h, k.list_hub, k.counters, k.hub_chunk_ptr, k.chunk_table, k.hub_bits,
-                               k.hub_grp, k.wps, w.edge_to_row, w.edge_to_col, k.tmp_cols);
-            st = launch_status("build_windows hubs");
-            if (st != FTC_OK) return st;
+        side = side_streams();
+        if (side) {
+            if (hipEventRecord(side->fork, s) != hipSuccess) {
+                (void)hipGetLastError();
+                side = nullptr;
+            } else {
+                bool good = true;
+                for (int i = 0; i < 3; ++i) good = good && hipStreamWaitEvent(side->stream[i], side->fork, 0) == hipSuccess;
+                if (!good) {
+                    // a side stream that did not take the dependency must not be used; the ones that
+                    // did only wait for work that is already queued on s
+                    (void)hipGetLastError();
+                    side = nullptr;
+                } else {
+                    s_mid = side->stream[0];
+                    s_large = side->stream[1];
+                    s_hub = side->stream[2];
+                }
+            }
         }
     }
+    hipLaunchKernelGGL(win_wave_kernel, dim3(w.n_windows), dim3(64), 0, s, g.n, g.row_ptr, g.col_idx, w.blk_h,
+                       w.edge_to_row, w.edge_to_col, k.uniq_count, k.tmp_cols);
+    st = launch_status("build_windows wave");
+    if (queued) {
+        // persistent grids: as many workgroups as fit on the chip at once (five 256-thread or one
+        // 1024-thread workgroup per CU), never more than the queue can hold
+#define FTC_RANGE(NT, SLOTS, RANK, PER_CU, CAP, LIST, COUNTER, NEXT, STREAM)                                  \
+    hipLaunchKernelGGL((win_compact_kernel<NT, SLOTS, RANK, PER_CU>),                                         \
+                       dim3(CAP < PER_CU * N_CU ? CAP : PER_CU * N_CU), dim3(NT), 0, STREAM, g.n, g.row_ptr,  \
+                       g.col_idx, w.blk_h, w.edge_to_row, w.edge_to_col, k.uniq_count, k.tmp_cols, LIST,      \
+                       k.counters + COUNTER, k.counters + NEXT)
+        if (st == FTC_OK) {
+            FTC_RANGE(256, 2048, uint16_t, 5, k.cap_mid, k.list_mid, C_MID, C_MID_NEXT, s_mid);
+            st = launch_status("build_windows compact (mid)");
+        }
+        if (st == FTC_OK && g.nnz > MID_CAP) {
+            FTC_RANGE(1024, 8192, uint32_t, 1, k.cap_large, k.list_large, C_LARGE, C_LARGE_NEXT, s_large);
+            st = launch_status("build_windows compact (large)");
+        }
+#undef FTC_RANGE
+        if (st == FTC_OK && g.nnz > hub_thr) {
+            hipLaunchKernelGGL(hub_plan_kernel, dim3(1), dim3(1024), 0, s_hub, g.n, g.row_ptr, w.blk_h, k.list_hub,
+                               k.counters, k.hub_chunk_ptr, k.chunk_table);
+            hipLaunchKernelGGL(hub_clear_kernel, dim3(512), dim3(256), 0, s_hub, k.counters, k.hub_bits, k.wps);
+            hipLaunchKernelGGL((hub_edges_kernel<false>), dim3(HUB_GRID), dim3(256), 0, s_hub, g.n, g.row_ptr,
+                               g.col_idx, w.blk_h, k.list_hub, k.counters, k.hub_chunk_ptr, k.chunk_table, k.hub_bits,
+                               k.hub_grp, k.wps, w.edge_to_row, w.edge_to_col, k.tmp_cols);
+            hipLaunchKernelGGL(hub_scan_kernel, dim3(k.slots), dim3(1024), 0, s_hub, k.list_hub, k.counters,
+                               k.hub_bits, k.hub_grp, k.wps, k.uniq_count);
+            hipLaunchKernelGGL((hub_edges_kernel<true>), dim3(HUB_GRID), dim3(256), 0, s_hub, g.n, g.row_ptr,
+                               g.col_idx, w.blk_h, k.list_hub, k.counters, k.hub_chunk_ptr, k.chunk_table, k.hub_bits,
+                               k.hub_grp, k.wps, w.edge_to_row, w.edge_to_col, k.tmp_cols);
+            st = launch_status("build_windows hubs");
+        }
+        if (side) {
+            // join: also after a failed launch, so that no side stream is left ahead of the caller's
+            for (int i = 0; i < 3; ++i) {
+                if (hipEventRecord(side->join[i], side->stream[i]) != hipSuccess ||
+                    hipStreamWaitEvent(s, side->join[i], 0) != hipSuccess) {
+                    (void)hipGetLastError();
+                    if (st == FTC_OK) {
+                        set_error("build_windows: cannot join the side streams");
+                        st = FTC_EHIP;
+                    }
+                }
+            }
+        }
+    }
+    if (st != FTC_OK) return st;
     hipLaunchKernelGGL(win_scan_kernel, dim3(1), dim3(1024), 0, s, w.n_windows, w.blk_w, k.uniq_count,
                        w.win_col_ptr, w.block_partition, w.summary);
     st = launch_status("build_windows scan");
