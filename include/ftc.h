@@ -10,7 +10,11 @@
  *    never prints: a call validates its arguments on the host and enqueues kernels on
  *    `stream` (a hipStream_t passed as void*, NULL = the default stream).  Scratch
  *    memory comes from a caller-provided workspace whose size is returned by the
- *    matching *_workspace_bytes query (a pure host function).
+ *    matching *_workspace_bytes query (a pure host function).  The only state the library
+ *    keeps is a set of three side streams and four events, created at the first
+ *    ftc_build_windows of a process (default priority, never destroyed): independent kernels of
+ *    the graph transformation run on them, forked from and joined back into `stream` with
+ *    events, so that for the caller everything still happens in stream order.
  *  - Return value: FTC_OK or a negative ftc_status; ftc_last_error() returns a
  *    thread-local description of the last failure.
  *  - The graph is a CSR adjacency with int32 indices (`nodePointer` / `edgeList` in the
