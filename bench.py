@@ -88,7 +88,7 @@ def cpu_baseline(scale, seed, g=None):
 
 
 def kernel_suite(tag, g, feat32, dtype, D, iters=20):
-    """Stand-alone SpMM / SDDMM timings on one graph (events on the launch stream), warm (back to
+    """Stand-alone SpMM / SDDMM / edge-softmax timings on one graph (events on the launch stream), warm (back to
     back) and cold (a 1 GiB buffer is overwritten between launches so that neither L2 nor the
     memory-side cache holds X).  Returns a dict of ms and algorithmic GB/s."""
     import numpy as np
@@ -108,10 +108,15 @@ def kernel_suite(tag, g, feat32, dtype, D, iters=20):
     e = X.element_size()
     rp = 4 * (g.n + 1)
     nbytes = {"spmm": sum_uniq * D * e + g.nnz * 8 + g.n * D * 4 + rp,
-              "sddmm": sum_uniq * D * e + g.n * D * e + g.nnz * 8 + rp}
+              "sddmm": sum_uniq * D * e + g.n * D * e + g.nnz * 8 + rp,
+              "softmax": g.nnz * 8 + rp}
+    ws_sm = B._workspace(B.lib().ftc_edge_softmax_workspace_bytes(g.n, g.nnz), dev)
+    p_out = torch.empty(g.nnz, dtype=torch.float32, device=dev)
     fns = {"spmm": lambda: B.ftc_spmm(dg, win, vals, X, out=out, ws=ws),
            # edge scores of AGNN: beta * cos(h_i, h_j), norms recomputed from the gathered rows
-           "sddmm": lambda: B.ftc_sddmm(dg, win, X, X, None, None, 1.0, out=s_out, ws=ws, cosine=True)}
+           "sddmm": lambda: B.ftc_sddmm(dg, win, X, X, None, None, 1.0, out=s_out, ws=ws, cosine=True),
+           # edge softmax over the scores the SDDMM has just written
+           "softmax": lambda: B.ftc_edge_softmax(dg, win, s_out, out=p_out, ws=ws_sm)}
     res = {"graph": tag, "n": g.n, "nnz": g.nnz, "sum_uniq": sum_uniq, "D": D, "dtype": str(dtype)[6:]}
     for op, fn in fns.items():
         for _ in range(5):

@@ -137,20 +137,6 @@ __global__ void win_clear_kernel(int *counters)
     if (threadIdx.x < C_WORDS) counters[threadIdx.x] = 0;
 }
 
-// Inclusive prefix sum over the 64 lanes of a wave with data-parallel-primitive moves: shifts by
-// 1, 2, 4, 8 inside rows of 16 lanes, then lane 15 of a row added to the next row (rows 1 and 3) and
-// lane 31 added to rows 2 and 3.
-__device__ __forceinline__ int wave_inclusive_scan(int v)
-{
-    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true);   // row_shr:1
-    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, true);   // row_shr:2
-    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, true);   // row_shr:4
-    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, true);   // row_shr:8
-    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);  // row_bcast:15 into rows 1, 3
-    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);  // row_bcast:31 into rows 2, 3
-    return v;
-}
-
 // Exclusive scan of one int per thread with a single barrier; `wave_tot` holds NT / 64 ints of LDS
 // and must not be written again before every thread has passed another barrier.
 template <int NT>

@@ -96,15 +96,17 @@ int32_t launch_softmax(const ftc_csr &g, const float *in, float *out, hipStream_
 // ------------------------------------------------------------------------------------------------
 // Edge-balanced variant for graphs with a window index (edge_to_row known for every edge).
 //
-//   1. stats kernel: a wave takes SMS_R consecutive edges, 64 at a time.  The pair
-//      (running maximum m, sum of exp(s - m)) is an associative reduction, so a segmented
-//      inclusive scan over the 64 lanes (segments = runs of equal row id, found with
-//      edge_to_row) gives every row piece its pair.  Rows that end inside the wave's range and
-//      did not start before it are final and go to stats[row]; the piece entering from the left
-//      and the piece leaving to the right go to a carry buffer.
+//   1. local kernel: a wave takes SMS_R consecutive edges and keeps their scores and row ids in
+//      registers.  The pair (running maximum m, sum of exp(s - m)) is an associative reduction, so
+//      a segmented inclusive scan over the 64 lanes (segments = runs of equal row id) gives every
+//      row piece its pair.  A row that lies completely inside the wave's range gets its pair into
+//      a table in LDS and its probabilities are written at once from the registers: such edges
+//      cross HBM twice in all (score in, probability out).  The piece entering from the left and
+//      the piece leaving to the right go to a carry buffer together with their extents.
 //   2. fix-up kernel: pieces of a row cut by range boundaries are combined in edge order.
-//   3. apply kernel: p[e] = exp(s[e] - m[row]) / z[row], one thread per edge.
+//   3. cut-row kernel: the probabilities of the cut pieces, by the wave that owns the range.
 constexpr int SMS_R = 1024;
+constexpr int SMS_C = SMS_R / 64;  // 64-edge chunks per wave
 
 struct MZ {
     float m, z;
@@ -119,78 +121,196 @@ __device__ __forceinline__ MZ mz_combine(MZ a, MZ b)
     return r;
 }
 
-__global__ __launch_bounds__(256) void softmax_stats_kernel(int nnz, int n_ranges,
-                                                            const int *__restrict__ edge_to_row,
-                                                            const float *__restrict__ in,
-                                                            float2 *__restrict__ stats,
-                                                            float2 *__restrict__ carry,  // [n_ranges][2]
-                                                            int *__restrict__ carry_tail_row)
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ int dpp_i(int v)
 {
-    const int lane = threadIdx.x & 63;
-    const int v = blockIdx.x * 4 + (threadIdx.x >> 6);
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, ROW_MASK, 0xf, false);
+}
+
+// Segmented inclusive scan of (m, z) over the lanes of a wave; `head` != 0 marks the first lane of a
+// segment.  Data-parallel-primitive moves: shifts by 1, 2, 4, 8 inside rows of 16 lanes, then lane
+// 15 of a row into the next row (rows 1 and 3) and lane 31 into rows 2 and 3.  The head flags are
+// OR-ed along with the values: a lane stops taking from the left once a head lies in its span.
+__device__ __forceinline__ MZ wave_segmented_scan(MZ x, int head, int lane)
+{
+#define FTC_STEP(CTRL, ROW_MASK, VALID)                                                  \
+    {                                                                                    \
+        MZ y;                                                                            \
+        y.m = __int_as_float(dpp_i<CTRL, ROW_MASK>(__float_as_int(x.m)));                \
+        y.z = __int_as_float(dpp_i<CTRL, ROW_MASK>(__float_as_int(x.z)));                \
+        const int yh = dpp_i<CTRL, ROW_MASK>(head);                                      \
+        if (VALID) {                                                                     \
+            if (!head) x = mz_combine(y, x);                                             \
+            head |= yh;                                                                  \
+        }                                                                                \
+    }
+    const int r16 = lane & 15;
+    FTC_STEP(0x111, 0xf, r16 >= 1)
+    FTC_STEP(0x112, 0xf, r16 >= 2)
+    FTC_STEP(0x114, 0xf, r16 >= 4)
+    FTC_STEP(0x118, 0xf, r16 >= 8)
+    FTC_STEP(0x142, 0xa, (lane & 16) != 0)
+    FTC_STEP(0x143, 0xc, lane >= 32)
+#undef FTC_STEP
+    return x;
+}
+
+__device__ __forceinline__ int wave_sum_int(int v)
+{
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+    return v;
+}
+
+// One more score for a running (maximum, sum of exp) pair: one exponential.
+__device__ __forceinline__ void mz_push(MZ &a, float s)
+{
+    if (s <= a.m) {
+        a.z += __expf(s - a.m);
+    } else {
+        a.z = a.z * __expf(a.m - s) + 1.f;  // a.m = -inf, a.z = 0 for an empty pair: 0 * 0 + 1
+        a.m = s;
+    }
+}
+
+// A lane owns SMS_L consecutive edges of the wave's range: it walks them once to build the pairs of
+// the row pieces it holds (rows that begin and end inside the lane are final at once), ONE
+// segmented scan over the lanes joins the pieces that continue from lane to lane, and a second walk
+// writes the probabilities.  Rows are numbered in order of appearance (row ids may skip rows
+// without entries): number 0 is the row that enters the range from the left (it may not exist),
+// the others count the row beginnings; the number indexes the table of final pairs in LDS.
+//
+// Per range: carry[2v] = pair of the piece entering from the left, carry[2v+1] = pair of the piece
+// leaving to the right; meta[v] = {edges of the entering piece, first edge of the leaving piece
+// (n_valid when none), row of the leaving piece or -1, unused}.
+constexpr int SMS_L = SMS_R / 64;
+
+template <bool VEC>
+__global__ __launch_bounds__(256) void softmax_local_kernel(int nnz, int n_ranges,
+                                                            const int *__restrict__ edge_to_row,
+                                                            const float *in, float *out,
+                                                            float2 *__restrict__ carry,
+                                                            int4 *__restrict__ meta)
+{
+    __shared__ float2 table_all[4][SMS_R + 1];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int v = blockIdx.x * 4 + wave;
     if (v >= n_ranges) return;  // no workgroup barrier below
+    float2 *table = table_all[wave];
     const int base = v * SMS_R;
     const int n_valid = min(SMS_R, nnz - base);
     const int prev_row = base > 0 ? edge_to_row[base - 1] : -1;
-    // the open piece carried from chunk to chunk (same value in every lane)
-    MZ cmz = {-INFINITY, 0.f};
-    int crow = -1;
-    for (int c0 = 0; c0 < n_valid; c0 += 64) {
-        const int i = c0 + lane;
-        const bool ok = i < n_valid;
-        const int row = ok ? edge_to_row[base + i] : -2 - lane;  // distinct ids for the padding lanes
-        MZ x = {ok ? in[base + i] : -INFINITY, ok ? 1.f : 0.f};
+    const int next_row = base + n_valid < nnz ? edge_to_row[base + n_valid] : -1;
+    const int e0 = lane * SMS_L;  // first edge of the lane inside the range
+    float sc[SMS_L];
+    int rw[SMS_L];
+    if (VEC && n_valid == SMS_R) {
 #pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            MZ y;
-            y.m = __shfl_up(x.m, d, 64);
-            y.z = __shfl_up(x.z, d, 64);
-            const int yr = __shfl_up(row, d, 64);
-            if (lane >= d && yr == row) x = mz_combine(y, x);
+        for (int q = 0; q < SMS_L / 4; ++q) {
+            const int4 r4 = *reinterpret_cast<const int4 *>(edge_to_row + base + e0 + 4 * q);
+            const float4 s4 = *reinterpret_cast<const float4 *>(in + base + e0 + 4 * q);
+            rw[4 * q] = r4.x; rw[4 * q + 1] = r4.y; rw[4 * q + 2] = r4.z; rw[4 * q + 3] = r4.w;
+            sc[4 * q] = s4.x; sc[4 * q + 1] = s4.y; sc[4 * q + 2] = s4.z; sc[4 * q + 3] = s4.w;
         }
-        const int first_row = __shfl(row, 0, 64);
-        if (crow >= 0) {
-            if (row == crow) {
-                x = mz_combine(cmz, x);  // lanes of the first segment continue the carried piece
-            } else if (first_row != crow && lane == 0) {
-                // the carried piece ended exactly at the chunk boundary
-                if (crow == prev_row) carry[2 * static_cast<size_t>(v)] = make_float2(cmz.m, cmz.z);
-                else stats[crow] = make_float2(cmz.m, cmz.z);
-            }
+    } else {
+#pragma unroll
+        for (int k = 0; k < SMS_L; ++k) {
+            const bool ok = e0 + k < n_valid;
+            rw[k] = ok ? edge_to_row[base + e0 + k] : -2 - (e0 + k);  // padding: rows of their own
+            sc[k] = ok ? in[base + e0 + k] : 0.f;
         }
-        const int last_lane = min(63, n_valid - c0 - 1);
-        const int next_row = __shfl_down(row, 1, 64);
-        if (ok && lane < last_lane && next_row != row) {  // a piece that ends inside the chunk
-            if (row == prev_row) carry[2 * static_cast<size_t>(v)] = make_float2(x.m, x.z);
-            else stats[row] = make_float2(x.m, x.z);
-        }
-        crow = __shfl(row, last_lane, 64);
-        cmz.m = __shfl(x.m, last_lane, 64);
-        cmz.z = __shfl(x.z, last_lane, 64);
     }
-    if (lane == 0) {
-        const bool right_open = base + n_valid < nnz && edge_to_row[base + n_valid] == crow;
-        int tail = -1;
-        if (crow == prev_row) {
-            carry[2 * static_cast<size_t>(v)] = make_float2(cmz.m, cmz.z);  // closed or spanning the range
-        } else if (right_open) {
-            carry[2 * static_cast<size_t>(v) + 1] = make_float2(cmz.m, cmz.z);
-            tail = crow;
+    // row beginnings inside the lane; `left` is the row of the edge before the lane's first
+    int left = __builtin_amdgcn_update_dpp(0, rw[SMS_L - 1], 0x138, 0xf, 0xf, false);  // wave_shr:1
+    if (lane == 0) left = prev_row;
+    unsigned begins = 0;
+#pragma unroll
+    for (int k = 0; k < SMS_L; ++k) begins |= (rw[k] != (k == 0 ? left : rw[k - 1]) ? 1u : 0u) << k;
+    const int nb = __popc(begins);
+    const int first_num = wave_inclusive_scan(nb) - nb;  // number of the row that is open at the lane's start
+    // first walk: pairs of the pieces
+    MZ cur = {-INFINITY, 0.f}, first_piece = {-INFINITY, 0.f};
+    int seen = 0;
+#pragma unroll
+    for (int k = 0; k < SMS_L; ++k) {
+        if (begins >> k & 1u) {
+            if (seen == 0) first_piece = cur;                                  // joined with the lanes on the left below
+            else table[first_num + seen] = make_float2(cur.m, cur.z);           // a row inside the lane: final
+            ++seen;
+            cur = MZ{-INFINITY, 0.f};
+        }
+        mz_push(cur, sc[k]);
+    }
+    if (nb == 0) first_piece = cur;
+    // one segmented scan over the lanes: what flows into a lane from the left
+    const MZ incl = wave_segmented_scan(cur, nb > 0 ? 1 : 0, lane);  // `cur` is the lane's last (or only) piece
+    MZ from_left;
+    from_left.m = __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(-INFINITY), __float_as_int(incl.m), 0x138,
+                                                             0xf, 0xf, false));
+    from_left.z = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(incl.z), 0x138, 0xf, 0xf, false));
+    if (lane == 0) from_left = MZ{-INFINITY, 0.f};
+    if (nb > 0) {  // the row that was open at the lane's start ends at the lane's first beginning
+        const MZ t = mz_combine(from_left, first_piece);
+        if (first_num == 0) carry[2 * static_cast<size_t>(v)] = make_float2(t.m, t.z);  // entered from the left
+        else table[first_num] = make_float2(t.m, t.z);
+    }
+    const int last_num = __shfl(first_num + nb, 63, 64);  // number of the range's last row
+    const int last_row = __shfl(rw[SMS_L - 1], 63, 64);
+    const bool right_open = n_valid == SMS_R && next_row == last_row;
+    if (lane == 63) {
+        if (last_num == 0) carry[2 * static_cast<size_t>(v)] = make_float2(incl.m, incl.z);  // one row, open on the left
+        else if (right_open) carry[2 * static_cast<size_t>(v) + 1] = make_float2(incl.m, incl.z);
+        else table[last_num] = make_float2(incl.m, incl.z);
+    }
+    const int tail_num = (right_open && last_num != 0) ? last_num : -1;
+    // LDS operations of one wave execute in order; the fences keep the compiler from moving the
+    // table reads above the writes
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    // second walk: probabilities of the rows that are complete inside the range
+    float pr[SMS_L];
+    unsigned done = 0;
+    int head_cnt = 0, tail_cnt = 0, num = first_num;
+    float2 t = make_float2(0.f, 1.f);
+    bool have = false;
+#pragma unroll
+    for (int k = 0; k < SMS_L; ++k) {
+        if (begins >> k & 1u) { ++num; have = false; }
+        const bool ok = e0 + k < n_valid;
+        const bool in_head = ok && num == 0, in_tail = ok && num == tail_num;
+        head_cnt += in_head ? 1 : 0;
+        tail_cnt += in_tail ? 1 : 0;
+        pr[k] = 0.f;
+        if (ok && !in_head && !in_tail) {
+            if (!have) { t = table[num]; have = true; }
+            pr[k] = __expf(sc[k] - t.x) / t.y;
+            done |= 1u << k;
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < SMS_L / 4; ++q) {
+        if (VEC && (done >> (4 * q) & 15u) == 15u) {
+            *reinterpret_cast<float4 *>(out + base + e0 + 4 * q) = make_float4(pr[4 * q], pr[4 * q + 1], pr[4 * q + 2], pr[4 * q + 3]);
         } else {
-            stats[crow] = make_float2(cmz.m, cmz.z);
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if (done >> (4 * q + j) & 1u) out[base + e0 + 4 * q + j] = pr[4 * q + j];
         }
-        carry_tail_row[v] = tail;
     }
+    head_cnt = wave_sum_int(head_cnt);
+    tail_cnt = wave_sum_int(tail_cnt);
+    if (lane == 0) meta[v] = make_int4(head_cnt, n_valid - tail_cnt, tail_num >= 0 ? last_row : -1, 0);
 }
 
 __global__ __launch_bounds__(256) void softmax_fixup_kernel(int n_ranges, const int *__restrict__ row_ptr,
                                                             const float2 *__restrict__ carry,
-                                                            const int *__restrict__ carry_tail_row,
+                                                            const int4 *__restrict__ meta,
                                                             float2 *__restrict__ stats)
 {
     const int v = blockIdx.x * 256 + threadIdx.x;
     if (v >= n_ranges) return;
-    const int r = carry_tail_row[v];
+    const int r = meta[v].z;
     if (r < 0) return;
     const int last = (row_ptr[r + 1] - 1) / SMS_R;
     float2 t = carry[2 * static_cast<size_t>(v) + 1];
@@ -202,21 +322,35 @@ __global__ __launch_bounds__(256) void softmax_fixup_kernel(int n_ranges, const 
     stats[r] = make_float2(acc.m, acc.z);
 }
 
-__global__ __launch_bounds__(256) void softmax_apply_kernel(int nnz, const int *__restrict__ edge_to_row,
-                                                            const float2 *__restrict__ stats, const float *in,
-                                                            float *out)
+// Probabilities of the pieces of cut rows: the entering piece (edges [0, head_len) of the range,
+// row = row of the edge before the range) and the leaving piece (edges [tail_start, n_valid)).
+__global__ __launch_bounds__(256) void softmax_cut_kernel(int nnz, int n_ranges,
+                                                          const int *__restrict__ edge_to_row,
+                                                          const float2 *__restrict__ stats,
+                                                          const int4 *__restrict__ meta, const float *in,
+                                                          float *out)
 {
-    const int64_t e = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
-    if (e >= nnz) return;
-    const float2 st = stats[edge_to_row[e]];
-    out[e] = expf(in[e] - st.x) / st.y;
+    const int lane = threadIdx.x & 63;
+    const int v = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (v >= n_ranges) return;
+    const int base = v * SMS_R;
+    const int n_valid = min(SMS_R, nnz - base);
+    const int4 mt = meta[v];
+    if (mt.x > 0) {
+        const float2 st = stats[edge_to_row[base - 1]];  // head_len > 0 implies base > 0
+        for (int i = lane; i < mt.x; i += 64) out[base + i] = __expf(in[base + i] - st.x) / st.y;
+    }
+    if (mt.z >= 0) {
+        const float2 st = stats[mt.z];
+        for (int i = mt.y + lane; i < n_valid; i += 64) out[base + i] = __expf(in[base + i] - st.x) / st.y;
+    }
 }
 
 size_t softmax_seg_ws(int n, int nnz)
 {
     const size_t n_ranges = (static_cast<size_t>(nnz) + SMS_R - 1) / SMS_R;
     return align_up(static_cast<size_t>(n) * sizeof(float2), 256) + align_up(n_ranges * 2 * sizeof(float2), 256) +
-           align_up(n_ranges * sizeof(int), 256);
+           align_up(n_ranges * sizeof(int4), 256);
 }
 
 int32_t launch_softmax_seg(const ftc_csr &g, const ftc_windows &w, const float *in, float *out, void *ws,
@@ -229,18 +363,24 @@ int32_t launch_softmax_seg(const ftc_csr &g, const ftc_windows &w, const float *
     p += align_up(static_cast<size_t>(g.n) * sizeof(float2), 256);
     float2 *carry = reinterpret_cast<float2 *>(p);
     p += align_up(static_cast<size_t>(n_ranges) * 2 * sizeof(float2), 256);
-    int *tail_row = reinterpret_cast<int *>(p);
-    hipLaunchKernelGGL(softmax_stats_kernel, dim3((n_ranges + 3) / 4), dim3(256), 0, s, g.nnz, n_ranges,
-                       w.edge_to_row, in, stats, carry, tail_row);
-    int32_t st = launch_status("edge_softmax stats");
+    int4 *meta = reinterpret_cast<int4 *>(p);
+    // 16-byte loads and stores of the scores / probabilities when the arrays allow it
+    const bool vec = aligned16(in) && aligned16(out) && aligned16(w.edge_to_row);
+    if (vec)
+        hipLaunchKernelGGL(softmax_local_kernel<true>, dim3((n_ranges + 3) / 4), dim3(256), 0, s, g.nnz, n_ranges,
+                           w.edge_to_row, in, out, carry, meta);
+    else
+        hipLaunchKernelGGL(softmax_local_kernel<false>, dim3((n_ranges + 3) / 4), dim3(256), 0, s, g.nnz, n_ranges,
+                           w.edge_to_row, in, out, carry, meta);
+    int32_t st = launch_status("edge_softmax local");
     if (st != FTC_OK) return st;
     hipLaunchKernelGGL(softmax_fixup_kernel, dim3((n_ranges + 255) / 256), dim3(256), 0, s, n_ranges, g.row_ptr,
-                       carry, tail_row, stats);
+                       carry, meta, stats);
     st = launch_status("edge_softmax fixup");
     if (st != FTC_OK) return st;
-    hipLaunchKernelGGL(softmax_apply_kernel, dim3((g.nnz + 255) / 256), dim3(256), 0, s, g.nnz, w.edge_to_row,
-                       stats, in, out);
-    return launch_status("edge_softmax apply");
+    hipLaunchKernelGGL(softmax_cut_kernel, dim3((n_ranges + 3) / 4), dim3(256), 0, s, g.nnz, n_ranges,
+                       w.edge_to_row, stats, meta, in, out);
+    return launch_status("edge_softmax cut rows");
 }
 
 // ------------------------------------------------------------------------------------------------
