@@ -20,7 +20,7 @@
 namespace ftc {
 
 constexpr int SEG_R = 512;  // edges per wave
-constexpr int SEG_B = 8;    // edges per batch (gathers in flight per lane)
+constexpr int SEG_B = 4;    // edges per batch (gathers in flight per lane)
 
 static int pow2_ceil(int x)
 {
