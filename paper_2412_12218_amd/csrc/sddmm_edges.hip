@@ -12,7 +12,7 @@
 namespace ftc {
 
 constexpr int SD_R = 512;  // edges per wave
-constexpr int SD_B = 8;    // edges per batch
+constexpr int SD_B = 4;    // edges per batch
 
 bool seg_shape(int dtype, int D, int *vec, int *lpr);  // spmm_seg.hip: same lane layout
 
