@@ -215,6 +215,18 @@ int32_t ftc_agnn_layer(const ftc_csr *g, const ftc_windows *w, const void *H, in
                        int32_t out_dtype, float *edge_p, int32_t path, void *ws,
                        size_t ws_bytes, void *stream);
 
+/*
+ * Measurement aid (no part of the method): enqueues the bare gather pattern of the aggregation
+ * kernels -- for every index i of idx[0 .. n_idx) (device, int32; a trailing group of fewer than
+ * 512 indices is ignored) the row_bytes (16, 32, 64 or 128) bytes at X + idx[i] * stride_bytes are
+ * loaded, 16 bytes per lane, and discarded.  Every idx[i] * stride_bytes + row_bytes must lie
+ * inside X (not checked).  *sink (device) is written only if the loaded data are not all zero.
+ * bench.py --probe times it on the column indices of the benchmark graphs: the rate at which the
+ * GPU delivers those rows at all.
+ */
+int32_t ftc_gather_probe(const int32_t *idx, int64_t n_idx, const void *X, int32_t row_bytes,
+                         int32_t stride_bytes, float *sink, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -43,6 +43,7 @@ _SIGNATURES = {
     "ftc_gcn_layer": (_I, [_P, _P, _P, _P, _P, _I, _I, _I, _P, _I, _I, _P, _I, _I, _I, _P, _Z, _P]),
     "ftc_agnn_layer_workspace_bytes": (_Z, [_I, _I, _I]),
     "ftc_agnn_layer": (_I, [_P, _P, _P, _I, _I, _I, _F, _P, _I, _I, _P, _I, _P, _Z, _P]),
+    "ftc_gather_probe": (_I, [_P, C.c_int64, _P, _I, _I, _P, _P]),
 }
 EXPORTS = list(_SIGNATURES)
 
@@ -261,3 +262,8 @@ def ftc_agnn_layer(g, w, H, beta=1.0, out=None, out_dtype=torch.float32, edge_p=
                                 C.c_int32(_dt(out)), _ptr(edge_p), C.c_int32(path), _ptr(ws),
                                 C.c_size_t(ws.numel()), _stream()))
     return out
+
+
+def ftc_gather_probe(idx, X, row_bytes, stride_bytes, sink):
+    _check(lib().ftc_gather_probe(_ptr(idx), C.c_int64(idx.numel()), _ptr(X), C.c_int32(row_bytes),
+                                  C.c_int32(stride_bytes), _ptr(sink), _stream()))

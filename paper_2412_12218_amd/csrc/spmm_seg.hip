@@ -56,7 +56,9 @@ size_t spmm_seg_ws(int nnz, int D)
     return align_up(n_ranges * 2 * dp * sizeof(float), 256) + align_up(n_ranges * 2 * sizeof(int), 256);
 }
 
-template <class T, int VEC, int LPR>
+// VALS = false: all edge values are one (vals == NULL): nothing is staged or multiplied for them, which
+// also cuts the LDS footprint by a third (more workgroups per CU).
+template <class T, int VEC, int LPR, bool VALS>
 __global__ __launch_bounds__(256) void spmm_seg_kernel(int nnz, int n_ranges, const int *__restrict__ col_idx,
                                                        const int *__restrict__ edge_to_row,
                                                        const float *__restrict__ vals,
@@ -70,16 +72,16 @@ __global__ __launch_bounds__(256) void spmm_seg_kernel(int nnz, int n_ranges, co
     constexpr int RP = SEG_R + NG;    // one pad word per run keeps the groups on different LDS banks
     constexpr int DP = LPR * VEC;     // padded feature width
     static_assert(RUN % SEG_B == 0, "runs are whole batches");
-    constexpr int IDX_WORDS = 4 * 3 * RP;
+    constexpr int IDX_WORDS = 4 * (VALS ? 3 : 2) * RP;
     constexpr int PART_WORDS = 4 * 2 * NG * DP;
     __shared__ int smem[IDX_WORDS > PART_WORDS ? IDX_WORDS : PART_WORDS];
     __shared__ int s_meta[4][3][NG];
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int g = lane / LPR, sub = lane % LPR;
-    int *s_col = smem + wave * 3 * RP;
+    int *s_col = smem + wave * (VALS ? 3 : 2) * RP;
     int *s_row = s_col + RP;
-    float *s_val = reinterpret_cast<float *>(s_row + RP);
+    float *s_val = reinterpret_cast<float *>(s_row + RP);  // only with VALS
 
     const int v = blockIdx.x * 4 + wave;
     const bool active = v < n_ranges;
@@ -94,7 +96,7 @@ __global__ __launch_bounds__(256) void spmm_seg_kernel(int nnz, int n_ranges, co
             // edges of windows that go to the matrix cores are skipped here (column -1)
             s_col[p] = (dense && dense[er >> 4]) ? -1 : col_idx[base + i];
             s_row[p] = er;
-            s_val[p] = vals ? vals[base + i] : 1.f;
+            if constexpr (VALS) s_val[p] = vals[base + i];
         }
     }
     const int prev_row = (active && base > 0) ? edge_to_row[base - 1] : -1;
@@ -138,7 +140,7 @@ __global__ __launch_bounds__(256) void spmm_seg_kernel(int nnz, int n_ranges, co
                 const int p = (ok ? b + k : rs) + g;
                 c[k] = s_col[p];
                 r[k] = ok ? s_row[p] : -1;
-                a[k] = s_val[p];
+                a[k] = VALS ? s_val[p] : 1.f;
             }
 #pragma unroll
             for (int k = 0; k < SEG_B; ++k) {
@@ -164,7 +166,7 @@ __global__ __launch_bounds__(256) void spmm_seg_kernel(int nnz, int n_ranges, co
                     float xf[VEC];
                     unpack<T, VEC>(x[k], xf);
 #pragma unroll
-                    for (int j = 0; j < VEC; ++j) acc[j] = fmaf(a[k], xf[j], acc[j]);
+                    for (int j = 0; j < VEC; ++j) acc[j] = VALS ? fmaf(a[k], xf[j], acc[j]) : acc[j] + xf[j];
                 }
             }
         }
@@ -315,9 +317,16 @@ static void launch_seg_t(int vec, int lpr, unsigned grid, hipStream_t s, int nnz
                          void *out, int ldo, int odt, Epi epi, float *carry, int *tail_row, const uint8_t *dense)
 {
     constexpr int VM = T::VEC;
-#define FTC_SEG(V, L)                                                                                     \
-    hipLaunchKernelGGL((spmm_seg_kernel<T, V, L>), dim3(grid), dim3(256), 0, s, nnz, n_ranges, g.col_idx, \
-                       e2r, vals, X, ldx, D, out, ldo, odt, epi, carry, tail_row, dense)
+#define FTC_SEG(V, L)                                                                                       \
+    do {                                                                                                    \
+        if (vals)                                                                                           \
+            hipLaunchKernelGGL((spmm_seg_kernel<T, V, L, true>), dim3(grid), dim3(256), 0, s, nnz, n_ranges, \
+                               g.col_idx, e2r, vals, X, ldx, D, out, ldo, odt, epi, carry, tail_row, dense); \
+        else                                                                                                \
+            hipLaunchKernelGGL((spmm_seg_kernel<T, V, L, false>), dim3(grid), dim3(256), 0, s, nnz,         \
+                               n_ranges, g.col_idx, e2r, vals, X, ldx, D, out, ldo, odt, epi, carry,        \
+                               tail_row, dense);                                                            \
+    } while (0)
     if (vec == VM) {
         if (lpr == 4) FTC_SEG(VM, 4);
         else if (lpr == 8) FTC_SEG(VM, 8);
