@@ -794,34 +794,49 @@ __global__ __launch_bounds__(1024) void win_scan_kernel(int n_windows, int blk_w
 
 // Packs the unique lists.  Slot e of the temporary array belongs to the window of edge e
 // (edge_to_row); it holds a list entry when its offset inside the window is below the window's
-// unique count.  A thread takes four slots 256 apart so that its loads are independent.
+// unique count.  A thread takes eight consecutive slots (two 16-byte loads per array; the slot's
+// content is loaded together with the edge's row, although 13 % of the slots on the R-MAT workload
+// hold no list entry: one step less in the chain of dependent loads).
 __global__ __launch_bounds__(256) void win_pack_kernel(int nnz, const int *__restrict__ row_ptr, int blk_h,
                                                        const int *__restrict__ edge_to_row,
                                                        const int *__restrict__ win_col_ptr,
                                                        const int *__restrict__ tmp_cols,
-                                                       int *__restrict__ win_cols)
+                                                       int *__restrict__ win_cols, bool vec)
 {
-    const int64_t e0 = static_cast<int64_t>(blockIdx.x) * 1024 + threadIdx.x;
-    int w[4], k[4], dst[4], len[4], v[4];
-    // the slot's content is loaded together with the edge's row (13 % of the slots on the R-MAT
-    // workload hold no list entry and are read in vain): one step less in the chain of dependent loads
+    const int64_t e0 = (static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x) * 8;
+    if (e0 >= nnz) return;
+    int r[8], v[8];
+    if (vec && e0 + 8 <= nnz) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const bool ok = e0 + j * 256 < nnz;
-        w[j] = ok ? edge_to_row[e0 + j * 256] / blk_h : -1;
-        v[j] = ok ? tmp_cols[e0 + j * 256] : 0;
-    }
+        for (int q = 0; q < 2; ++q) {
+            const int4 a = *reinterpret_cast<const int4 *>(edge_to_row + e0 + 4 * q);
+            const int4 b = *reinterpret_cast<const int4 *>(tmp_cols + e0 + 4 * q);
+            r[4 * q] = a.x; r[4 * q + 1] = a.y; r[4 * q + 2] = a.z; r[4 * q + 3] = a.w;
+            v[4 * q] = b.x; v[4 * q + 1] = b.y; v[4 * q + 2] = b.z; v[4 * q + 3] = b.w;
+        }
+    } else {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        if (w[j] >= 0) {
-            k[j] = static_cast<int>(e0 + j * 256) - row_ptr[w[j] * blk_h];
-            dst[j] = win_col_ptr[w[j]];
-            len[j] = win_col_ptr[w[j] + 1] - dst[j];
+        for (int j = 0; j < 8; ++j) {
+            const bool ok = e0 + j < nnz;
+            r[j] = ok ? edge_to_row[e0 + j] : -1;
+            v[j] = ok ? tmp_cols[e0 + j] : 0;
         }
     }
+    // consecutive slots mostly share their window: its three numbers are looked up once per change
+    int w_prev = -1, first = 0, dst = 0, len = 0;
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
-        if (w[j] >= 0 && k[j] < len[j]) win_cols[dst[j] + k[j]] = v[j];
+    for (int j = 0; j < 8; ++j) {
+        if (r[j] < 0) continue;
+        const int w = r[j] / blk_h;
+        if (w != w_prev) {
+            w_prev = w;
+            first = row_ptr[w * blk_h];
+            dst = win_col_ptr[w];
+            len = win_col_ptr[w + 1] - dst;
+        }
+        const int k = static_cast<int>(e0 + j) - first;
+        if (k < len) win_cols[dst + k] = v[j];
+    }
 }
 
 // Side streams for the kernels that do not depend on each other (created once per process and
@@ -964,8 +979,8 @@ int32_t launch_build_windows(const ftc_csr &g, ftc_windows &w, void *ws, size_t 
     st = launch_status("build_windows scan");
     if (st != FTC_OK) return st;
     if (g.nnz == 0) return FTC_OK;
-    hipLaunchKernelGGL(win_pack_kernel, dim3((g.nnz + 1023) / 1024), dim3(256), 0, s, g.nnz, g.row_ptr, w.blk_h,
-                       w.edge_to_row, w.win_col_ptr, k.tmp_cols, w.win_cols);
+    hipLaunchKernelGGL(win_pack_kernel, dim3((g.nnz + 2047) / 2048), dim3(256), 0, s, g.nnz, g.row_ptr, w.blk_h,
+                       w.edge_to_row, w.win_col_ptr, k.tmp_cols, w.win_cols, aligned16(w.edge_to_row));
     return launch_status("build_windows pack");
 }
 
