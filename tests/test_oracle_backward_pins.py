@@ -1,0 +1,138 @@
+"""Pins of the backward oracle (CPU only): central finite differences of the FORWARD oracle (the C
+routines, which have their own pins), closed-form special cases, and the transposed index against a
+dense transpose."""
+import numpy as np
+import pytest
+
+import synth
+from oracle import ftc_oracle_backward as ob
+
+
+def small_graph(seed, n=14, m=30, symmetric=True):
+    g = synth.erdos_renyi(n, m, seed=seed)          # symmetrised, de-duplicated, with self-loops
+    if symmetric:
+        return g
+    # drop some entries to break the symmetry of the pattern (the oracle must not rely on it)
+    rng = np.random.default_rng(seed)
+    keep = rng.random(g.nnz) > 0.3
+    rows = np.repeat(np.arange(g.n), np.diff(g.row_ptr))
+    keep |= rows == g.col_idx                        # keep the self-loops: no empty rows
+    rp = np.zeros(g.n + 1, dtype=np.int32)
+    rp[1:] = np.cumsum(np.bincount(rows[keep], minlength=g.n))
+    return synth.Graph(g.n, rp, g.col_idx[keep].astype(np.int32))
+
+
+def fd(f, x, eps=1e-6):
+    """Central differences of the scalar function f at the array x."""
+    grad = np.zeros_like(x)
+    it = np.nditer(x, flags=["multi_index"])
+    for _ in it:
+        idx = it.multi_index
+        old = x[idx]
+        x[idx] = old + eps
+        up = f()
+        x[idx] = old - eps
+        dn = f()
+        x[idx] = old
+        grad[idx] = (up - dn) / (2 * eps)
+    return grad
+
+
+@pytest.mark.parametrize("seed", [0, 1])
+@pytest.mark.parametrize("symmetric", [True, False])
+@pytest.mark.parametrize("relu", [False, True])
+def test_gcn_backward_matches_finite_differences(oracle, seed, symmetric, relu):
+    g = small_graph(seed, symmetric=symmetric)
+    rng = np.random.default_rng(10 + seed)
+    vals = rng.uniform(0.2, 1.0, g.nnz)
+    X = rng.standard_normal((g.n, 5))
+    W = rng.standard_normal((5, 3))
+    R = rng.standard_normal((g.n, 3))                # loss = sum(Y * R), so dL/dY = R
+
+    def loss():
+        Y, _ = oracle.gcn_layer(g.row_ptr, g.col_idx, vals, X, W, relu=relu)
+        return float((Y * R).sum())
+
+    Y, _ = oracle.gcn_layer(g.row_ptr, g.col_idx, vals, X, W, relu=relu)
+    assert not relu or np.min(np.abs(Y[Y != 0])) > 1e-4   # no output sits on the kink of the ReLU
+    dX, dW, _ = ob.gcn_layer_backward(g.row_ptr, g.col_idx, vals, X, W, R, Y if relu else None)
+    assert np.allclose(dX, fd(loss, X), rtol=1e-6, atol=1e-7)
+    assert np.allclose(dW, fd(loss, W), rtol=1e-6, atol=1e-7)
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+@pytest.mark.parametrize("symmetric", [True, False])
+@pytest.mark.parametrize("beta", [1.0, -2.5, 0.0])
+def test_agnn_backward_matches_finite_differences(oracle, seed, symmetric, beta):
+    g = small_graph(seed, symmetric=symmetric)
+    rng = np.random.default_rng(20 + seed)
+    H = rng.standard_normal((g.n, 4))
+    R = rng.standard_normal((g.n, 4))
+    b = np.array([beta])
+
+    def loss():
+        Y, _, _ = oracle.agnn_layer(g.row_ptr, g.col_idx, H, float(b[0]))
+        return float((Y * R).sum())
+
+    dH, dbeta = ob.agnn_layer_backward(g.row_ptr, g.col_idx, H, beta, R)
+    assert np.allclose(dH, fd(loss, H), rtol=2e-6, atol=1e-7)
+    assert np.isclose(dbeta, fd(loss, b)[0], rtol=2e-6, atol=1e-7)
+
+
+def test_agnn_backward_beta_zero_is_mean_aggregation():
+    """beta = 0: P = D^-1 A does not depend on H, so dH = P^T dY exactly (dense check)."""
+    g = small_graph(3)
+    rng = np.random.default_rng(5)
+    H, R = rng.standard_normal((g.n, 3)), rng.standard_normal((g.n, 3))
+    P = np.zeros((g.n, g.n))
+    for i in range(g.n):
+        cols = g.col_idx[g.row_ptr[i]:g.row_ptr[i + 1]]
+        P[i, cols] = 1.0 / cols.size
+    dH, _ = ob.agnn_layer_backward(g.row_ptr, g.col_idx, H, 0.0, R)
+    assert np.allclose(dH, P.T @ R, atol=1e-13)
+
+
+def test_gcn_backward_identity_weight_is_transposed_aggregation():
+    g = small_graph(4, symmetric=False)
+    rng = np.random.default_rng(6)
+    vals = rng.uniform(0.2, 1.0, g.nnz)
+    A = np.zeros((g.n, g.n))
+    rows = np.repeat(np.arange(g.n), np.diff(g.row_ptr))
+    A[rows, g.col_idx] = vals
+    X, R = rng.standard_normal((g.n, 4)), rng.standard_normal((g.n, 4))
+    dX, dW, dZ = ob.gcn_layer_backward(g.row_ptr, g.col_idx, vals, X, np.eye(4), R)
+    assert np.allclose(dX, A.T @ R, atol=1e-13) and np.allclose(dZ, dX)
+    assert np.allclose(dW, X.T @ (A.T @ R), atol=1e-12)
+
+
+def test_softmax_backward_properties():
+    g = small_graph(7)
+    rng = np.random.default_rng(8)
+    p = rng.random(g.nnz)
+    rows = np.repeat(np.arange(g.n), np.diff(g.row_ptr))
+    p /= np.bincount(rows, weights=p)[rows]
+    dp = rng.standard_normal(g.nnz)
+    ds = ob.edge_softmax_backward(g.row_ptr, p, dp)
+    assert np.allclose(np.bincount(rows, weights=ds), 0, atol=1e-14)          # softmax is shift invariant
+    assert np.allclose(ob.edge_softmax_backward(g.row_ptr, p, dp + 3.0), ds)   # ... so a row constant drops out
+    # Jacobian of a single row written out: diag(p) - p p^T
+    i = int(np.argmax(np.diff(g.row_ptr)))
+    sl = slice(g.row_ptr[i], g.row_ptr[i + 1])
+    J = np.diag(p[sl]) - np.outer(p[sl], p[sl])
+    assert np.allclose(ds[sl], J @ dp[sl])
+
+
+@pytest.mark.parametrize("seed", [0, 1])
+def test_transpose_index_against_dense(seed):
+    g = small_graph(seed, n=20, m=50)
+    T = ob.transpose_index(g.row_ptr, g.col_idx)
+    rows = np.repeat(np.arange(g.n), np.diff(g.row_ptr))
+    assert np.all(T >= 0)
+    assert np.array_equal(rows[T], g.col_idx) and np.array_equal(g.col_idx[T], rows)
+    assert np.array_equal(T[T], np.arange(g.nnz))
+    gu = small_graph(seed, n=20, m=50, symmetric=False)
+    Tu = ob.transpose_index(gu.row_ptr, gu.col_idx)
+    dense = np.zeros((gu.n, gu.n), dtype=bool)
+    ru = np.repeat(np.arange(gu.n), np.diff(gu.row_ptr))
+    dense[ru, gu.col_idx] = True
+    assert np.array_equal(Tu >= 0, dense.T[ru, gu.col_idx])
