@@ -216,6 +216,75 @@ int32_t ftc_agnn_layer(const ftc_csr *g, const ftc_windows *w, const void *H, in
                        size_t ws_bytes, void *stream);
 
 /*
+ * ---- Backward pass ----------------------------------------------------------------------------
+ * The paper speaks of GNN training as well as inference (Sections II and V) and gives no gradient
+ * formulas; the entry points below compute the derivatives of the forward definitions above.
+ * Gradient arrays are fp32.  The sparse products of the backward pass run on the forward SpMM /
+ * SDDMM kernels.
+ */
+
+/*
+ * Transposed index of a symmetric pattern: T[e] = position of the stored entry (j, i) for the
+ * stored entry e = (i, j), -1 where the pattern does not hold it; *flag (device int32) becomes 1
+ * if any entry has no partner, else 0.  Needs ascending, duplicate-free columns inside every row.
+ * w may be NULL (its edge_to_row only saves a search).
+ */
+int32_t ftc_transpose_index(const ftc_csr *g, const ftc_windows *w, int32_t *T, int32_t *flag,
+                            void *stream);
+
+/*
+ * Derivative of ftc_edge_softmax: ds[e] = p[e] * (dp[e] - sum over the row of p * dp).
+ * ds may alias dp.
+ */
+int32_t ftc_edge_softmax_backward(const ftc_csr *g, const float *p, const float *dp, float *ds,
+                                  void *stream);
+
+/*
+ * Weight gradient of the update phase: dW = X^T * G, X n x d_in (x_dtype), G n x d_out (fp32),
+ * dW d_in x d_out row-major (fp32).  Limits: ceil(d_in / 4) * ceil(d_out / 4) <= 1024 and
+ * d_in + d_out <= 1016 (FTC_EUNSUPPORTED beyond).  Partial sums of row blocks are added in a fixed
+ * order (reproducible).
+ */
+size_t ftc_weight_grad_workspace_bytes(int32_t n, int32_t d_in, int32_t d_out);
+int32_t ftc_weight_grad(int32_t n, const void *X, int32_t ldx, int32_t x_dtype, int32_t d_in,
+                        const float *G, int32_t ldg, int32_t d_out, float *dW, void *ws,
+                        size_t ws_bytes, void *stream);
+
+/*
+ * Backward of ftc_gcn_layer for a loss with dL/d(out) = dY (n x d_out, fp32):
+ *   dP = dY where the layer's output Y was positive (Y == NULL: no ReLU, dP = dY),
+ *   dZ = A^^T * dP,  dW = X^T * dZ (d_in x d_out),  dX = dZ * W^T (n x d_in; dX == NULL: skipped).
+ * (gT, wT, valsT) describe A^^T: the transposed graph, its window index and its edge values; for
+ * the symmetric GCN normalisation they are the forward graph itself.  dinv != NULL selects the
+ * factored normalisation as in ftc_gcn_layer (valsT ignored).  X, W as in the forward call;
+ * d_out <= 64.
+ */
+size_t ftc_gcn_layer_backward_workspace_bytes(int32_t n, int32_t nnz, int32_t d_in, int32_t d_out);
+int32_t ftc_gcn_layer_backward(const ftc_csr *gT, const ftc_windows *wT, const float *valsT,
+                               const float *dinv, const void *X, int32_t ldx, int32_t dtype,
+                               int32_t d_in, const void *W, int32_t d_out, const void *Y,
+                               int32_t ldy, int32_t y_dtype, const float *dY, int32_t lddy,
+                               float *dX, int32_t lddx, float *dW, int32_t path, void *ws,
+                               size_t ws_bytes, void *stream);
+
+/*
+ * Backward of ftc_agnn_layer for a loss with dL/d(out) = dY (n x D, same dtype and leading
+ * dimension as H): dH (n x D, fp32) and *dbeta (device fp32).  p are the probabilities of the
+ * forward pass (edge_p of ftc_agnn_layer), T the transposed index of the pattern, which must be
+ * symmetric (ftc_transpose_index with flag 0).  With hn_i = h_i / max(|h_i|, 1e-12),
+ * c_e = <hn_i, hn_j>:
+ *   dp_e = <dY_i, h_j>,  ds = softmax backward of (p, dp),  dbeta = sum_e ds_e c_e,
+ *   q_i = beta * sum_e (ds_e + ds_T(e)) hn_j,
+ *   dH_i = sum_e p_T(e) dY_j  +  (q_i - hn_i <hn_i, q_i>) / |h_i|.
+ */
+size_t ftc_agnn_layer_backward_workspace_bytes(int32_t n, int32_t nnz, int32_t D);
+int32_t ftc_agnn_layer_backward(const ftc_csr *g, const ftc_windows *w, const int32_t *T,
+                                const void *H, int32_t ld, int32_t dtype, int32_t D, float beta,
+                                const float *p, const void *dY, int32_t lddy, float *dH,
+                                int32_t lddh, float *dbeta, int32_t path, void *ws,
+                                size_t ws_bytes, void *stream);
+
+/*
  * Measurement aid (no part of the method): enqueues the bare gather pattern of the aggregation
  * kernels -- for every index i of idx[0 .. n_idx) (device, int32; a trailing group of fewer than
  * 512 indices is ignored) the row_bytes (16, 32, 64 or 128) bytes at X + idx[i] * stride_bytes are

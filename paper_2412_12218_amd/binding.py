@@ -43,6 +43,15 @@ _SIGNATURES = {
     "ftc_gcn_layer": (_I, [_P, _P, _P, _P, _P, _I, _I, _I, _P, _I, _I, _P, _I, _I, _I, _P, _Z, _P]),
     "ftc_agnn_layer_workspace_bytes": (_Z, [_I, _I, _I]),
     "ftc_agnn_layer": (_I, [_P, _P, _P, _I, _I, _I, _F, _P, _I, _I, _P, _I, _P, _Z, _P]),
+    "ftc_transpose_index": (_I, [_P, _P, _P, _P, _P]),
+    "ftc_edge_softmax_backward": (_I, [_P, _P, _P, _P, _P]),
+    "ftc_weight_grad_workspace_bytes": (_Z, [_I, _I, _I]),
+    "ftc_weight_grad": (_I, [_I, _P, _I, _I, _I, _P, _I, _I, _P, _P, _Z, _P]),
+    "ftc_gcn_layer_backward_workspace_bytes": (_Z, [_I, _I, _I, _I]),
+    "ftc_gcn_layer_backward": (_I, [_P, _P, _P, _P, _P, _I, _I, _I, _P, _I, _P, _I, _I, _P, _I, _P, _I, _P, _I, _P,
+                                    _Z, _P]),
+    "ftc_agnn_layer_backward_workspace_bytes": (_Z, [_I, _I, _I]),
+    "ftc_agnn_layer_backward": (_I, [_P, _P, _P, _P, _I, _I, _I, _F, _P, _P, _I, _P, _I, _P, _I, _P, _Z, _P]),
     "ftc_gather_probe": (_I, [_P, C.c_int64, _P, _I, _I, _P, _P]),
 }
 EXPORTS = list(_SIGNATURES)
@@ -267,3 +276,62 @@ def ftc_agnn_layer(g, w, H, beta=1.0, out=None, out_dtype=torch.float32, edge_p=
 def ftc_gather_probe(idx, X, row_bytes, stride_bytes, sink):
     _check(lib().ftc_gather_probe(_ptr(idx), C.c_int64(idx.numel()), _ptr(X), C.c_int32(row_bytes),
                                   C.c_int32(stride_bytes), _ptr(sink), _stream()))
+
+
+# ---- backward pass (gradients are fp32 tensors) ----------------------------------------------------
+def ftc_transpose_index(g, w=None):
+    T = torch.empty(g.nnz, dtype=torch.int32, device=g.row_ptr.device)
+    flag = torch.empty(1, dtype=torch.int32, device=g.row_ptr.device)
+    _check(lib().ftc_transpose_index(C.byref(g.c), _wref(w), _ptr(T), _ptr(flag), _stream()))
+    return T, flag
+
+
+def ftc_edge_softmax_backward(g, p, dp, out=None):
+    if out is None:
+        out = torch.empty_like(dp)
+    _check(lib().ftc_edge_softmax_backward(C.byref(g.c), _ptr(p), _ptr(dp), _ptr(out), _stream()))
+    return out
+
+
+def ftc_weight_grad(X, G, ws=None):
+    n, d_in = X.shape
+    d_out = G.shape[1]
+    assert G.dtype == torch.float32 and G.shape[0] == n
+    dW = torch.empty((d_in, d_out), dtype=torch.float32, device=X.device)
+    if ws is None:
+        ws = _workspace(lib().ftc_weight_grad_workspace_bytes(n, d_in, d_out), X.device)
+    _check(lib().ftc_weight_grad(C.c_int32(n), _ptr(X), C.c_int32(X.stride(0)), C.c_int32(_dt(X)), C.c_int32(d_in),
+                                 _ptr(G), C.c_int32(G.stride(0)), C.c_int32(d_out), _ptr(dW), _ptr(ws),
+                                 C.c_size_t(ws.numel()), _stream()))
+    return dW
+
+
+def ftc_gcn_layer_backward(gT, wT, valsT, X, W, dY, Y=None, dinv=None, want_dX=True, path=FTC_PATH_AUTO, ws=None):
+    n, d_in = X.shape
+    d_out = W.shape[1]
+    assert dY.dtype == torch.float32 and dY.shape == (n, d_out)
+    dX = torch.empty((n, d_in), dtype=torch.float32, device=X.device) if want_dX else None
+    dW = torch.empty((d_in, d_out), dtype=torch.float32, device=X.device)
+    if ws is None:
+        ws = _workspace(lib().ftc_gcn_layer_backward_workspace_bytes(gT.n, gT.nnz, d_in, d_out), X.device)
+    _check(lib().ftc_gcn_layer_backward(
+        C.byref(gT.c), _wref(wT), _ptr(valsT), _ptr(dinv), _ptr(X), C.c_int32(X.stride(0)), C.c_int32(_dt(X)),
+        C.c_int32(d_in), _ptr(W), C.c_int32(d_out), _ptr(Y), C.c_int32(Y.stride(0) if Y is not None else 0),
+        C.c_int32(_dt(Y) if Y is not None else 0), _ptr(dY), C.c_int32(dY.stride(0)), _ptr(dX),
+        C.c_int32(dX.stride(0) if dX is not None else 0), _ptr(dW), C.c_int32(path), _ptr(ws), C.c_size_t(ws.numel()),
+        _stream()))
+    return dX, dW
+
+
+def ftc_agnn_layer_backward(g, w, T, H, p, dY, beta=1.0, path=FTC_PATH_AUTO, ws=None):
+    n, D = H.shape
+    assert dY.dtype == H.dtype and dY.shape == H.shape and dY.stride(0) == H.stride(0)
+    dH = torch.empty((n, D), dtype=torch.float32, device=H.device)
+    dbeta = torch.empty(1, dtype=torch.float32, device=H.device)
+    if ws is None:
+        ws = _workspace(lib().ftc_agnn_layer_backward_workspace_bytes(g.n, g.nnz, D), H.device)
+    _check(lib().ftc_agnn_layer_backward(
+        C.byref(g.c), _wref(w), _ptr(T), _ptr(H), C.c_int32(H.stride(0)), C.c_int32(_dt(H)), C.c_int32(D),
+        C.c_float(beta), _ptr(p), _ptr(dY), C.c_int32(dY.stride(0)), _ptr(dH), C.c_int32(dH.stride(0)), _ptr(dbeta),
+        C.c_int32(path), _ptr(ws), C.c_size_t(ws.numel()), _stream()))
+    return dH, dbeta

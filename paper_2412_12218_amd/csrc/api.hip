@@ -395,4 +395,153 @@ int32_t ftc_agnn_layer(const ftc_csr *g, const ftc_windows *w, const void *H, in
     return ftc_spmm(g, w, scores, H, ld, dtype, D, out, ldo, out_dtype, nullptr, 0, path, p, rest, stream);
 }
 
+// ---------------------------------------------------------------------------------------------------
+// Backward pass (gradients are fp32)
+
+int32_t ftc_transpose_index(const ftc_csr *g, const ftc_windows *w, int32_t *T, int32_t *flag, void *stream)
+{
+    FTC_TRY(check_csr(g, "ftc_transpose_index"));
+    if (!flag) return fail(FTC_EINVAL, "ftc_transpose_index: flag is NULL");
+    if (g->nnz > 0 && !T) return fail(FTC_EINVAL, "ftc_transpose_index: T is NULL");
+    const int32_t *e2r = nullptr;
+    if (w) {
+        FTC_TRY(check_windows(g, w, "ftc_transpose_index", false));
+        e2r = w->edge_to_row;
+    }
+    return launch_transpose_index(*g, e2r, T, flag, static_cast<hipStream_t>(stream));
+}
+
+int32_t ftc_edge_softmax_backward(const ftc_csr *g, const float *p, const float *dp, float *ds, void *stream)
+{
+    FTC_TRY(check_csr(g, "ftc_edge_softmax_backward"));
+    if (g->n == 0 || g->nnz == 0) return FTC_OK;
+    if (!p || !dp || !ds) return fail(FTC_EINVAL, "ftc_edge_softmax_backward: NULL edge array");
+    return launch_softmax_backward(*g, p, dp, ds, static_cast<hipStream_t>(stream));
+}
+
+size_t ftc_weight_grad_workspace_bytes(int32_t n, int32_t d_in, int32_t d_out)
+{
+    if (n < 0 || d_in < 1 || d_out < 1) return 0;
+    return weight_grad_ws(n, d_in, d_out);
+}
+
+int32_t ftc_weight_grad(int32_t n, const void *X, int32_t ldx, int32_t x_dtype, int32_t d_in, const float *G,
+                        int32_t ldg, int32_t d_out, float *dW, void *ws, size_t ws_bytes, void *stream)
+{
+    if (n < 0) return fail(FTC_EINVAL, "ftc_weight_grad: negative n");
+    FTC_TRY(check_dense(X, ldx, x_dtype, d_in, "ftc_weight_grad", "X"));
+    FTC_TRY(check_dense(G, ldg, FTC_F32, d_out, "ftc_weight_grad", "G"));
+    if (!dW) return fail(FTC_EINVAL, "ftc_weight_grad: dW is NULL");
+    if (!weight_grad_shape_ok(d_in, d_out))
+        return fail(FTC_EUNSUPPORTED, "ftc_weight_grad: need ceil(d_in / 4) * ceil(d_out / 4) <= 1024 and d_in + d_out <= 1016");
+    const size_t need = weight_grad_ws(n, d_in, d_out);
+    if (!ws || ws_bytes < need) return fail(FTC_EWORKSPACE, "ftc_weight_grad: workspace of %zu bytes needed", need);
+    return launch_weight_grad(n, X, ldx, x_dtype, d_in, G, ldg, d_out, dW, ws, static_cast<hipStream_t>(stream));
+}
+
+static int pad4(int d) { return (d + 3) / 4 * 4; }
+
+size_t ftc_gcn_layer_backward_workspace_bytes(int32_t n, int32_t nnz, int32_t d_in, int32_t d_out)
+{
+    if (n < 0 || nnz < 0 || d_in < 1 || d_out < 1) return 0;
+    const size_t mat = align_up(static_cast<size_t>(n) * pad4(d_out) * sizeof(float), 256);
+    return 2 * mat + align_up(ftc_spmm_workspace_bytes(n, nnz, d_out), 256) + weight_grad_ws(n, d_in, d_out);
+}
+
+int32_t ftc_gcn_layer_backward(const ftc_csr *gT, const ftc_windows *wT, const float *valsT, const float *dinv,
+                               const void *X, int32_t ldx, int32_t dtype, int32_t d_in, const void *W, int32_t d_out,
+                               const void *Y, int32_t ldy, int32_t y_dtype, const float *dY, int32_t lddy, float *dX,
+                               int32_t lddx, float *dW, int32_t path, void *ws, size_t ws_bytes, void *stream)
+{
+    FTC_TRY(check_csr(gT, "ftc_gcn_layer_backward"));
+    if (gT->n == 0) return FTC_OK;
+    FTC_TRY(check_dense(X, ldx, dtype, d_in, "ftc_gcn_layer_backward", "X"));
+    FTC_TRY(check_dense(dY, lddy, FTC_F32, d_out, "ftc_gcn_layer_backward", "dY"));
+    if (Y) FTC_TRY(check_dense(Y, ldy, y_dtype, d_out, "ftc_gcn_layer_backward", "Y"));
+    if (dX) FTC_TRY(check_dense(dX, lddx, FTC_F32, d_in, "ftc_gcn_layer_backward", "dX"));
+    if (!W || !dW) return fail(FTC_EINVAL, "ftc_gcn_layer_backward: W or dW is NULL");
+    if (d_out > 64 || !weight_grad_shape_ok(d_in, d_out))
+        return fail(FTC_EUNSUPPORTED, "ftc_gcn_layer_backward: need d_out <= 64, ceil(d_in / 4) * ceil(d_out / 4) <= 1024 and d_in + d_out <= 1016");
+    const size_t need = ftc_gcn_layer_backward_workspace_bytes(gT->n, gT->nnz, d_in, d_out);
+    if (!ws || ws_bytes < need)
+        return fail(FTC_EWORKSPACE, "ftc_gcn_layer_backward: workspace of %zu bytes needed", need);
+    if (reinterpret_cast<uintptr_t>(ws) % 256 != 0)
+        return fail(FTC_EALIGN, "ftc_gcn_layer_backward: workspace must be 256-byte aligned");
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    const int n = gT->n, ldp = pad4(d_out);
+    const size_t mat = align_up(static_cast<size_t>(n) * ldp * sizeof(float), 256);
+    char *p = static_cast<char *>(ws);
+    float *dP = reinterpret_cast<float *>(p);
+    float *dZ = reinterpret_cast<float *>(p + mat);
+    void *ws_spmm = p + 2 * mat;
+    const size_t spmm_bytes = align_up(ftc_spmm_workspace_bytes(n, gT->nnz, d_out), 256);
+    void *ws_wg = p + 2 * mat + spmm_bytes;
+    // dP = dY where the output was positive, rows scaled by dinv in the factored form
+    FTC_TRY(launch_mask_scale(n, d_out, dY, lddy, Y, ldy, y_dtype, dinv, dP, ldp, hs));
+    // dZ = A^T dP on the transposed graph the caller hands over
+    FTC_TRY(ftc_spmm(gT, wT, dinv ? nullptr : valsT, dP, ldp, FTC_F32, d_out, dZ, ldp, FTC_F32, dinv, 0, path,
+                     ws_spmm, spmm_bytes, stream));
+    FTC_TRY(launch_weight_grad(n, X, ldx, dtype, d_in, dZ, ldp, d_out, dW, ws_wg, hs));
+    if (dX) FTC_TRY(launch_input_grad(n, dZ, ldp, d_out, W, dtype, d_in, dX, lddx, hs));
+    return FTC_OK;
+}
+
+size_t ftc_agnn_layer_backward_workspace_bytes(int32_t n, int32_t nnz, int32_t D)
+{
+    if (n < 0 || nnz < 0 || D < 1) return 0;
+    const size_t edge = align_up(static_cast<size_t>(nnz) * sizeof(float), 256);
+    return 3 * edge + align_up(static_cast<size_t>(n) * sizeof(float), 256) +
+           align_up(static_cast<size_t>(n) * pad4(D) * sizeof(float), 256) +
+           align_up(ftc_sddmm_workspace_bytes(n, nnz, D), 256) + align_up(ftc_spmm_workspace_bytes(n, nnz, D), 256) +
+           edge_dot_ws();
+}
+
+int32_t ftc_agnn_layer_backward(const ftc_csr *g, const ftc_windows *w, const int32_t *T, const void *H, int32_t ld,
+                                int32_t dtype, int32_t D, float beta, const float *p, const void *dY, int32_t lddy,
+                                float *dH, int32_t lddh, float *dbeta, int32_t path, void *ws, size_t ws_bytes,
+                                void *stream)
+{
+    FTC_TRY(check_csr(g, "ftc_agnn_layer_backward"));
+    if (g->n == 0) return FTC_OK;
+    FTC_TRY(check_dense(H, ld, dtype, D, "ftc_agnn_layer_backward", "H"));
+    FTC_TRY(check_dense(dY, lddy, dtype, D, "ftc_agnn_layer_backward", "dY"));
+    FTC_TRY(check_dense(dH, lddh, FTC_F32, D, "ftc_agnn_layer_backward", "dH"));
+    if (!dbeta) return fail(FTC_EINVAL, "ftc_agnn_layer_backward: dbeta is NULL");
+    if (g->nnz > 0 && (!T || !p)) return fail(FTC_EINVAL, "ftc_agnn_layer_backward: T or p is NULL");
+    if (dH == H || dH == dY) return fail(FTC_EINVAL, "ftc_agnn_layer_backward: dH aliases an input");
+    if (ld != lddy) return fail(FTC_EINVAL, "ftc_agnn_layer_backward: H and dY need the same leading dimension");
+    const size_t need = ftc_agnn_layer_backward_workspace_bytes(g->n, g->nnz, D);
+    if (!ws || ws_bytes < need)
+        return fail(FTC_EWORKSPACE, "ftc_agnn_layer_backward: workspace of %zu bytes needed", need);
+    if (reinterpret_cast<uintptr_t>(ws) % 256 != 0)
+        return fail(FTC_EALIGN, "ftc_agnn_layer_backward: workspace must be 256-byte aligned");
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    const int n = g->n, nnz = g->nnz, ldq = pad4(D);
+    const size_t edge = align_up(static_cast<size_t>(nnz) * sizeof(float), 256);
+    char *q8 = static_cast<char *>(ws);
+    float *c = reinterpret_cast<float *>(q8); q8 += edge;       // cosines
+    float *ds = reinterpret_cast<float *>(q8); q8 += edge;      // dL/dp, then dL/ds
+    float *v = reinterpret_cast<float *>(q8); q8 += edge;       // edge values of the two transposed products
+    float *rinv = reinterpret_cast<float *>(q8); q8 += align_up(static_cast<size_t>(n) * sizeof(float), 256);
+    float *q = reinterpret_cast<float *>(q8); q8 += align_up(static_cast<size_t>(n) * ldq * sizeof(float), 256);
+    void *ws_sd = q8; const size_t sd = align_up(ftc_sddmm_workspace_bytes(n, nnz, D), 256); q8 += sd;
+    void *ws_sp = q8; const size_t sp = align_up(ftc_spmm_workspace_bytes(n, nnz, D), 256); q8 += sp;
+    void *ws_dot = q8;
+    FTC_TRY(launch_row_rnorm(n, H, ld, dtype, D, rinv, hs));
+    // c_e = cos(h_i, h_j);  dp_e = <dY_i, h_j>  (y_i = sum_e p_e h_j)
+    FTC_TRY(ftc_sddmm(g, w, H, H, ld, dtype, D, nullptr, nullptr, 1.f, 1, c, path, ws_sd, sd, stream));
+    FTC_TRY(ftc_sddmm(g, w, dY, H, ld, dtype, D, nullptr, nullptr, 1.f, 0, ds, path, ws_sd, sd, stream));
+    FTC_TRY(launch_softmax_backward(*g, p, ds, ds, hs));
+    FTC_TRY(launch_edge_dot(nnz, ds, c, dbeta, ws_dot, hs));  // s = beta * c, so dL/dbeta = sum_e ds_e c_e
+    // gradient with respect to the normalised rows: q_i = sum_e (dc_e + dc_T(e)) hn_j, dc = beta * ds,
+    // hn_j = rinv_j h_j folded into the edge values so that H itself is the gathered matrix
+    FTC_TRY(launch_edge_combine(nnz, ds, T, 1.f, 1.f, beta, rinv, g->col_idx, v, hs));
+    FTC_TRY(ftc_spmm(g, w, v, H, ld, dtype, D, q, ldq, FTC_F32, nullptr, 0, path, ws_sp, sp, stream));
+    // through the aggregated rows: dH = P^T dY, (P^T)_e = p_T(e) on the symmetric pattern
+    FTC_TRY(launch_edge_combine(nnz, p, T, 0.f, 1.f, 1.f, nullptr, g->col_idx, v, hs));
+    FTC_TRY(ftc_spmm(g, w, v, dY, lddy, dtype, D, dH, lddh, FTC_F32, nullptr, 0, path, ws_sp, sp, stream));
+    // ... plus the derivative of the normalisation
+    return launch_cos_backward_rows(n, H, ld, dtype, D, rinv, q, ldq, dH, lddh, hs);
+}
+
 }  // extern "C"

@@ -67,6 +67,23 @@ int32_t launch_sddmm_mfma(const ftc_csr &g, const ftc_windows &w, const void *X,
                           hipStream_t s);
 int32_t launch_spmm_mfma(const ftc_csr &g, const ftc_windows &w, const float *vals, const void *X, int ldx, int dt,
                          int D, void *out, int ldo, int odt, Epi epi, const uint8_t *flags, hipStream_t s);
+// backward.hip
+int32_t launch_transpose_index(const ftc_csr &g, const int *edge_to_row, int *T, int *flag, hipStream_t s);
+int32_t launch_softmax_backward(const ftc_csr &g, const float *p, const float *dp, float *ds, hipStream_t s);
+int32_t launch_mask_scale(int n, int d, const float *dY, int lddy, const void *Y, int ldy, int ydt,
+                          const float *scale, float *out, int ldo, hipStream_t s);
+bool weight_grad_shape_ok(int d_in, int d_out);
+size_t weight_grad_ws(int n, int d_in, int d_out);
+int32_t launch_weight_grad(int n, const void *X, int ldx, int xdt, int d_in, const float *G, int ldg, int d_out,
+                           float *dW, void *ws, hipStream_t s);
+int32_t launch_input_grad(int n, const float *G, int ldg, int d_out, const void *W, int wdt, int d_in, float *dX,
+                          int lddx, hipStream_t s);
+int32_t launch_edge_combine(int nnz, const float *a, const int *T, float wa, float wb, float alpha, const float *cs,
+                            const int *col_idx, float *out, hipStream_t s);
+size_t edge_dot_ws();
+int32_t launch_edge_dot(int nnz, const float *a, const float *b, float *out, void *ws, hipStream_t s);
+int32_t launch_cos_backward_rows(int n, const void *H, int ld, int dt, int D, const float *rinv, const float *q, int ldq,
+                                 float *dH, int lddh, hipStream_t s);
 size_t build_windows_ws(int n, int nnz, int blk_h, int blk_w);
 int32_t launch_build_windows(const ftc_csr &g, ftc_windows &w, void *ws, size_t ws_bytes, hipStream_t s);
 

@@ -1,0 +1,293 @@
+"""GPU parity of the backward pass: every backward entry point of libftc, called through the C
+ABI, against the fp64 backward oracle on the same seeded inputs.
+
+Integer outputs (the transposed index) are bit-exact.  A gradient element is compared as
+|gpu - ref| / (max |ref| over its row + 0.01 * max |ref| over the array) for per-node gradients and
+|gpu - ref| / max |ref| for the small dense ones (dW, dbeta): 1e-4 for fp32 inputs, 2e-3 for 16-bit
+inputs.  (A gradient is a difference of sums that nearly cancel in places, the softmax backward
+above all, so single elements are not compared relative to themselves.)"""
+import numpy as np
+import pytest
+import scipy.sparse as sp
+import torch
+
+import synth
+from oracle import ftc_oracle_backward as OB
+from parity import dev_graph, quantise
+from paper_2412_12218_amd import binding as B
+
+pytestmark = pytest.mark.gpu
+
+F32, F16, BF16 = torch.float32, torch.float16, torch.bfloat16
+GTOL = {F32: 1e-4, F16: 2e-3, BF16: 2e-3}
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def row_err(got, ref):
+    got = got.detach().cpu().double().numpy()
+    assert np.all(np.isfinite(got))
+    scale = np.abs(ref).max(axis=1, keepdims=True) + 0.01 * np.abs(ref).max()
+    return float(np.max(np.abs(got - ref) / np.where(scale > 0, scale, 1.0))) if ref.size else 0.0
+
+
+def arr_err(got, ref):
+    got = got.detach().cpu().double().numpy()
+    assert np.all(np.isfinite(got))
+    m = np.abs(ref).max() if ref.size else 0.0
+    return float(np.max(np.abs(got - ref)) / (m if m > 0 else 1.0)) if ref.size else 0.0
+
+
+def directed_graph(n, m, seed):
+    """Non-symmetric pattern with ascending, duplicate-free rows, a few empty rows, self-loops on
+    half the nodes."""
+    rng = np.random.default_rng(seed)
+    u = np.concatenate([rng.integers(0, n, size=m), np.arange(0, n, 2)])
+    v = np.concatenate([rng.integers(0, n, size=m), np.arange(0, n, 2)])
+    keep = (u % 97) != 5                               # rows 5, 102, ... stay empty
+    A = sp.csr_matrix((np.ones(keep.sum()), (u[keep], v[keep])), shape=(n, n))
+    A.sum_duplicates()
+    A.sort_indices()
+    return synth.Graph(n, A.indptr.astype(np.int32), A.indices.astype(np.int32), "directed")
+
+
+def host_transpose(g, vals):
+    """CSR of the transposed matrix with every stored entry kept (stable order inside a row)."""
+    rows = np.repeat(np.arange(g.n), np.diff(g.row_ptr))
+    order = np.argsort(g.col_idx, kind="stable")
+    rpT = np.zeros(g.n + 1, dtype=np.int32)
+    rpT[1:] = np.cumsum(np.bincount(g.col_idx, minlength=g.n))
+    gT = synth.Graph(g.n, rpT, rows[order].astype(np.int32), "T")
+    return gT, (None if vals is None else vals[order])
+
+
+@pytest.fixture(scope="module")
+def graphs():
+    return {
+        "cfg1": synth.config_graph(1),
+        "cfg3s": synth.config_graph(3, 0.1),
+        "cfg5s": synth.config_graph(5, 1 / 32),
+        "directed": directed_graph(5003, 40_000, seed=5),
+    }
+
+
+# ------------------------------------------------------------------ transposed index (bit-exact)
+@pytest.mark.parametrize("name", ["cfg1", "cfg3s", "cfg5s", "directed"])
+@pytest.mark.parametrize("with_windows", [True, False])
+def test_transpose_index(graphs, name, with_windows):
+    g = graphs[name]
+    say(f"transpose_index {name} n={g.n} nnz={g.nnz} windows={with_windows}")
+    ref = OB.transpose_index(g.row_ptr, g.col_idx)
+    dg = dev_graph(g)
+    win = B.ftc_build_windows(dg) if with_windows else None
+    T, flag = B.ftc_transpose_index(dg, win)
+    assert np.array_equal(T.cpu().numpy().astype(np.int64), ref)
+    assert int(flag.item()) == int((ref < 0).any())
+    if name == "directed":
+        assert (ref < 0).any() and (ref >= 0).any()
+
+
+def test_transpose_index_empty_graph():
+    g = synth.Graph(40, np.zeros(41, dtype=np.int32), np.zeros(0, dtype=np.int32), "empty")
+    T, flag = B.ftc_transpose_index(dev_graph(g))
+    assert T.numel() == 0 and int(flag.item()) == 0
+
+
+# ------------------------------------------------------------------ softmax backward
+def long_row_graph():
+    """Rows of every class of the kernel: empty, a few entries, hundreds, one above 2048."""
+    rng = np.random.default_rng(3)
+    n = 3000
+    deg = rng.integers(0, 14, size=n)
+    deg[7] = 0
+    deg[100:110] = 300
+    deg[555] = 2048
+    deg[556] = 2049
+    deg[1200] = 9000
+    deg[n - 1] = 17
+    row_ptr = np.zeros(n + 1, dtype=np.int32)
+    row_ptr[1:] = np.cumsum(deg)
+    col = rng.integers(0, n, size=int(row_ptr[-1])).astype(np.int32)
+    return synth.Graph(n, row_ptr, col, "long_rows")
+
+
+@pytest.mark.parametrize("name", ["cfg1", "cfg5s", "long_rows"])
+def test_edge_softmax_backward(oracle, graphs, name):
+    g = long_row_graph() if name == "long_rows" else graphs[name]
+    say(f"softmax_backward {name} n={g.n} nnz={g.nnz}")
+    rng = np.random.default_rng(8)
+    s = rng.normal(size=g.nnz).astype(np.float32) * 3
+    p64 = oracle.edge_softmax(g.row_ptr, s.astype(np.float64))
+    p32 = p64.astype(np.float32)
+    dp32 = rng.normal(size=g.nnz).astype(np.float32)
+    ref = OB.edge_softmax_backward(g.row_ptr, p32.astype(np.float64), dp32.astype(np.float64))
+    dg = dev_graph(g)
+    p, dp = torch.from_numpy(p32).cuda(), torch.from_numpy(dp32).cuda()
+    ds = B.ftc_edge_softmax_backward(dg, p, dp)
+    # every term is bounded by p * (|dp| + sum p |dp|): compare against that
+    rows = np.repeat(np.arange(g.n), np.diff(g.row_ptr))
+    ab = np.zeros(g.n)
+    np.add.at(ab, rows, p32.astype(np.float64) * np.abs(dp32))
+    bound = p32.astype(np.float64) * (np.abs(dp32) + ab[rows])
+    got = ds.cpu().double().numpy()
+    err = float(np.max(np.abs(got - ref) / np.where(bound > 0, bound, 1.0)))
+    say(f"  err {err:.3e}")
+    assert err < 1e-5
+    assert np.all(got[bound == 0] == 0)
+    ds2 = B.ftc_edge_softmax_backward(dg, p, dp.clone(), out=None)
+    assert torch.equal(ds, ds2)
+    dpc = dp.clone()
+    B.ftc_edge_softmax_backward(dg, p, dpc, out=dpc)      # in place
+    assert torch.equal(dpc, ds)
+
+
+# ------------------------------------------------------------------ weight gradient
+@pytest.mark.parametrize("n", [1, 15, 1000, 70_001])
+@pytest.mark.parametrize("dtype,d_in,d_out", [(F32, 16, 16), (F16, 64, 16), (BF16, 30, 7), (F16, 128, 32),
+                                              (F32, 5, 64)])
+def test_weight_grad(n, dtype, d_in, d_out):
+    say(f"weight_grad n={n} {dtype} {d_in}x{d_out}")
+    Xd, X64 = quantise(synth.uniform_features(n, d_in, seed=1), dtype)
+    G32 = synth.normal_features(n, d_out, seed=2).astype(np.float32)
+    ref = X64.T @ G32.astype(np.float64)
+    ab = np.abs(X64).T @ np.abs(G32).astype(np.float64)
+    G = torch.from_numpy(G32).cuda()
+    dW = B.ftc_weight_grad(Xd, G)
+    err = float(np.max(np.abs(dW.cpu().double().numpy() - ref) / ab))
+    say(f"  err {err:.3e}")
+    assert err < 1e-5
+    assert torch.equal(dW, B.ftc_weight_grad(Xd, G))          # fixed summation order
+
+
+def test_weight_grad_strided_inputs():
+    n, d_in, d_out = 777, 20, 12
+    Xf = torch.from_numpy(synth.uniform_features(n, 40, seed=3)).to(F16).cuda()
+    Gf = torch.from_numpy(synth.normal_features(n, 16, seed=4).astype(np.float32)).cuda()
+    X, G = Xf[:, :d_in], Gf[:, :d_out]
+    ref = X.double().cpu().numpy().T @ G.double().cpu().numpy()
+    dW = B.ftc_weight_grad(X, G)
+    assert arr_err(dW, ref) < 1e-5
+
+
+# ------------------------------------------------------------------ GCN layer backward
+@pytest.mark.parametrize("name", ["cfg1", "cfg3s", "cfg5s", "directed"])
+@pytest.mark.parametrize("dtype,d_in,d_out", [(F16, 64, 16), (F32, 16, 16), (BF16, 30, 7), (F16, 16, 40)])
+@pytest.mark.parametrize("relu", [False, True])
+@pytest.mark.parametrize("factored", [False, True])
+def test_gcn_layer_backward(oracle, graphs, name, dtype, d_in, d_out, relu, factored):
+    g = graphs[name]
+    if name in ("cfg3s", "cfg5s") and (dtype, d_in, d_out) not in ((F16, 64, 16), (F32, 16, 16)):
+        pytest.skip("odd shapes are covered on the small graphs")
+    say(f"gcn_layer_backward {name} {dtype} {d_in}->{d_out} relu={relu} factored={factored}")
+    _, dinv64 = oracle.gcn_norm(g.row_ptr, g.col_idx)
+    dinv32 = np.nan_to_num(dinv64, posinf=0.0).astype(np.float32)       # empty rows: 0
+    rows = np.repeat(np.arange(g.n), np.diff(g.row_ptr))
+    vals_ref = dinv32[rows].astype(np.float64) * dinv32[g.col_idx].astype(np.float64)
+    if factored:
+        vals32 = None
+    else:
+        vals32 = vals_ref.astype(np.float32)
+        vals_ref = vals32.astype(np.float64)
+    Xd, X64 = quantise(synth.uniform_features(g.n, d_in, seed=9), dtype)
+    Wd, W64 = quantise(synth.glorot_uniform(d_in, d_out, seed=10), dtype)
+    dY32 = synth.normal_features(g.n, d_out, seed=13).astype(np.float32)
+    dg = dev_graph(g)
+    win = B.ftc_build_windows(dg)
+    dinv_d = torch.from_numpy(dinv32).cuda() if factored else None
+    vals_d = torch.from_numpy(vals32).cuda() if vals32 is not None else None
+    # forward on the GPU: the ReLU mask of the backward pass is the layer's own output
+    Y = B.ftc_gcn_layer(dg, win, vals_d, Xd, Wd, relu=relu, dinv=dinv_d) if relu else None
+    Y64 = Y.cpu().double().numpy() if relu else None
+    dX_ref, dW_ref, _ = OB.gcn_layer_backward(g.row_ptr, g.col_idx, vals_ref, X64, W64,
+                                              dY32.astype(np.float64), Y64)
+    # the transposed operator: the graph itself when the pattern is symmetric
+    if name == "directed":
+        gT, valsT = host_transpose(g, vals32)
+        dgT = dev_graph(gT)
+        winT = B.ftc_build_windows(dgT)
+        valsT_d = torch.from_numpy(valsT).cuda() if valsT is not None else None
+    else:
+        dgT, winT, valsT_d = dg, win, vals_d
+    dY = torch.from_numpy(dY32).cuda()
+    dX, dW = B.ftc_gcn_layer_backward(dgT, winT, valsT_d, Xd, Wd, dY, Y=Y, dinv=dinv_d)
+    ex, ew = row_err(dX, dX_ref), arr_err(dW, dW_ref)
+    say(f"  dX err {ex:.3e} dW err {ew:.3e}")
+    assert ex < GTOL[dtype] and ew < GTOL[dtype]
+    dX2, dW2 = B.ftc_gcn_layer_backward(dgT, None, valsT_d, Xd, Wd, dY, Y=Y, dinv=dinv_d)   # row kernels
+    assert row_err(dX2, dX_ref) < GTOL[dtype] and arr_err(dW2, dW_ref) < GTOL[dtype]
+    none, dW3 = B.ftc_gcn_layer_backward(dgT, winT, valsT_d, Xd, Wd, dY, Y=Y, dinv=dinv_d, want_dX=False)
+    assert none is None and torch.equal(dW3, dW)
+
+
+# ------------------------------------------------------------------ AGNN layer backward
+@pytest.mark.parametrize("name", ["cfg1", "cfg3s", "cfg5s"])
+@pytest.mark.parametrize("dtype,D", [(F32, 16), (F16, 32), (BF16, 24), (F16, 64), (F32, 5)])
+@pytest.mark.parametrize("beta", [1.0, -2.5])
+def test_agnn_layer_backward(graphs, name, dtype, D, beta):
+    g = graphs[name]
+    if name != "cfg1" and (dtype, D) not in ((F32, 16), (F16, 32)):
+        pytest.skip("odd widths are covered on the small graph")
+    say(f"agnn_layer_backward {name} {dtype} D={D} beta={beta}")
+    Hd, H64 = quantise(synth.normal_features(g.n, D, seed=11), dtype)
+    dYd, dY64 = quantise(synth.normal_features(g.n, D, seed=14), dtype)
+    dH_ref, dbeta_ref = OB.agnn_layer_backward(g.row_ptr, g.col_idx, H64, beta, dY64)
+    dg = dev_graph(g)
+    win = B.ftc_build_windows(dg)
+    T, flag = B.ftc_transpose_index(dg, win)
+    assert int(flag.item()) == 0
+    p = torch.empty(g.nnz, dtype=F32, device="cuda")
+    B.ftc_agnn_layer(dg, win, Hd, beta=beta, edge_p=p)       # forward pass keeps its probabilities
+    dH, dbeta = B.ftc_agnn_layer_backward(dg, win, T, Hd, p, dYd, beta=beta)
+    eh = row_err(dH, dH_ref)
+    # dbeta sums nnz signed terms ds_e c_e: compare against the size of a typical partial sum
+    db = abs(float(dbeta.item()) - dbeta_ref)
+    say(f"  dH err {eh:.3e} dbeta {float(dbeta.item()):.6g} ref {dbeta_ref:.6g}")
+    assert eh < GTOL[dtype]
+    assert db < GTOL[dtype] * max(abs(dbeta_ref), np.sqrt(g.n) * 1e-2)
+    dH2, dbeta2 = B.ftc_agnn_layer_backward(dg, None, T, Hd, p, dYd, beta=beta)      # row kernels
+    assert row_err(dH2, dH_ref) < GTOL[dtype]
+    dH3, dbeta3 = B.ftc_agnn_layer_backward(dg, win, T, Hd, p, dYd, beta=beta)
+    assert torch.equal(dH, dH3) and torch.equal(dbeta, dbeta3)
+
+
+def test_agnn_layer_backward_zero_rows_and_isolated_nodes():
+    """Nodes whose only neighbour is themselves, and an all-zero feature row (its direction is
+    undefined: the forward definition clamps the norm, the gradient through it stays finite)."""
+    g = synth.config_graph(1)
+    D = 16
+    H32 = synth.normal_features(g.n, D, seed=21)
+    H32[17] = 0.0
+    Hd, H64 = quantise(H32, F32)
+    dYd, dY64 = quantise(synth.normal_features(g.n, D, seed=22), F32)
+    dH_ref, dbeta_ref = OB.agnn_layer_backward(g.row_ptr, g.col_idx, H64, 1.5, dY64)
+    dg = dev_graph(g)
+    win = B.ftc_build_windows(dg)
+    T, _ = B.ftc_transpose_index(dg, win)
+    p = torch.empty(g.nnz, dtype=F32, device="cuda")
+    B.ftc_agnn_layer(dg, win, Hd, beta=1.5, edge_p=p)
+    dH, dbeta = B.ftc_agnn_layer_backward(dg, win, T, Hd, p, dYd, beta=1.5)
+    keep = np.ones(g.n, dtype=bool)
+    keep[17] = False                       # d/dh of h/max(|h|, eps) at h = 0 is 1/eps: not compared
+    assert row_err(dH[torch.from_numpy(keep).cuda()], dH_ref[keep]) < 1e-4
+    assert np.all(np.isfinite(dH.cpu().numpy()))
+    assert abs(float(dbeta.item()) - dbeta_ref) < 1e-4 * max(abs(dbeta_ref), 1.0)
+
+
+def test_backward_rejects_bad_arguments():
+    g = synth.config_graph(1)
+    dg = dev_graph(g)
+    H = torch.zeros((g.n, 16), dtype=F16, device="cuda")
+    dY32 = torch.zeros((g.n, 16), dtype=F32, device="cuda")
+    T = torch.zeros(g.nnz, dtype=torch.int32, device="cuda")
+    p = torch.zeros(g.nnz, dtype=F32, device="cuda")
+    with pytest.raises(B.FtcError):        # workspace too small
+        B.ftc_agnn_layer_backward(dg, None, T, H, p, H.clone(), ws=torch.empty(256, dtype=torch.uint8, device="cuda"))
+    W = torch.zeros((16, 80), dtype=F16, device="cuda")
+    with pytest.raises(B.FtcError):        # d_out above 64
+        B.ftc_gcn_layer_backward(dg, None, None, H, W, torch.zeros((g.n, 80), dtype=F32, device="cuda"))
+    with pytest.raises(B.FtcError):        # weight gradient larger than the register tiling covers
+        B.ftc_weight_grad(torch.zeros((10, 512), dtype=F16, device="cuda"),
+                          torch.zeros((10, 64), dtype=F32, device="cuda"))
+    del dY32
