@@ -226,6 +226,58 @@ def gather_probe(iters=10):
     run("cfg4 SBM col_idx", c4, g4.n, 128)
 
 
+def train_suite(scale, iters=10):
+    """Forward + backward of the two benchmark models on the benchmark graph (TrainPath): per-call
+    times from events on the launch stream.  Prints one JSON line of its own; the benchmark metric
+    stays the forward hot path."""
+    import numpy as np
+    import torch
+    import synth
+    from paper_2412_12218_amd import binding as B
+    from paper_2412_12218_amd.models import TrainPath
+    dev = torch.device("cuda:0")
+    seed = synth.CONFIGS[5]["seed"]
+    g = synth.rmat(scale, 16, seed)
+    dg = B.Graph.from_numpy(g.row_ptr, g.col_idx)
+    win = B.ftc_build_windows(dg)
+    _, dinv = B.ftc_gcn_norm(dg, win, want_vals=False)
+    h16 = lambda a: torch.from_numpy(a).to(torch.float16).to(dev)
+    X = h16(synth.normal_features(g.n, 128, seed + 10))
+    W1, W2 = h16(synth.glorot_uniform(128, 16, seed + 11)), h16(synth.glorot_uniform(16, 8, seed + 12))
+    H0 = h16(synth.normal_features(g.n, 32, seed + 20))
+    d_gcn = torch.from_numpy(synth.normal_features(g.n, 8, seed + 21)).to(dev)
+    d_agnn = h16(synth.normal_features(g.n, 32, seed + 22))
+    betas = [1.0] * 4
+    times = {}
+
+    def timed(name, fn):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        r = fn()
+        b.record()
+        b.synchronize()
+        times.setdefault(name, []).append(a.elapsed_time(b))
+        return r
+
+    for it in range(iters + 2):
+        if it == 2:
+            times.clear()
+        timed("transpose_index", lambda: B.ftc_transpose_index(dg, win))
+    tp = TrainPath(dg, win, dinv)
+    for it in range(iters + 2):
+        if it == 2:
+            keep = times.pop("transpose_index")
+            times.clear()
+            times["transpose_index"] = keep
+        timed("gcn_forward_2layers", lambda: tp.gcn_forward(X, W1, W2))
+        timed("gcn_backward_2layers", lambda: tp.gcn_backward(X, W1, W2, d_gcn))
+        timed("agnn_forward_4layers_keeping_p", lambda: tp.agnn_forward(H0, betas))
+        timed("agnn_backward_4layers", lambda: tp.agnn_backward(betas, d_agnn))
+    print(json.dumps({"workload": f"cfg5 R-MAT scale {scale}: N={g.n}, nnz={g.nnz}, fp16 activations, fp32 gradients "
+                                  "of weights, GCN 128-16-8, AGNN 32 x 4 layers",
+                      "ms": {k: float(np.mean(v)) for k, v in times.items()}}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -236,6 +288,8 @@ def main():
     ap.add_argument("--no-kernels", action="store_true", help="skip the stand-alone SpMM/SDDMM section")
     ap.add_argument("--probe", action="store_true",
                     help="instead of the benchmark: the bare gather rate of the GPU on the benchmark graphs' indices")
+    ap.add_argument("--train", action="store_true",
+                    help="instead of the benchmark: forward + backward times of the two models on the benchmark graph")
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the benchmark: vector vs matrix-core path over window density")
     args = ap.parse_args()
@@ -256,6 +310,9 @@ def main():
         return
     if args.probe:
         gather_probe()
+        return
+    if args.train:
+        train_suite(args.scale)
         return
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)

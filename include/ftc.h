@@ -234,9 +234,11 @@ int32_t ftc_transpose_index(const ftc_csr *g, const ftc_windows *w, int32_t *T, 
 
 /*
  * Derivative of ftc_edge_softmax: ds[e] = p[e] * (dp[e] - sum over the row of p * dp).
- * ds may alias dp.
+ * ds may alias dp.  w and the workspace (ftc_edge_softmax_workspace_bytes) as in ftc_edge_softmax:
+ * with the window index the work is split by entries, not rows (no long-row imbalance).
  */
-int32_t ftc_edge_softmax_backward(const ftc_csr *g, const float *p, const float *dp, float *ds,
+int32_t ftc_edge_softmax_backward(const ftc_csr *g, const ftc_windows *w, const float *p,
+                                  const float *dp, float *ds, void *ws, size_t ws_bytes,
                                   void *stream);
 
 /*
@@ -269,7 +271,8 @@ int32_t ftc_gcn_layer_backward(const ftc_csr *gT, const ftc_windows *wT, const f
 
 /*
  * Backward of ftc_agnn_layer for a loss with dL/d(out) = dY (n x D, same dtype and leading
- * dimension as H): dH (n x D, fp32) and *dbeta (device fp32).  p are the probabilities of the
+ * dimension as H): dH (n x D, of type dh_dtype: fp32, or a 16-bit type when the layer below takes
+ * its incoming gradient in that type) and *dbeta (device fp32).  p are the probabilities of the
  * forward pass (edge_p of ftc_agnn_layer), T the transposed index of the pattern, which must be
  * symmetric (ftc_transpose_index with flag 0).  With hn_i = h_i / max(|h_i|, 1e-12),
  * c_e = <hn_i, hn_j>:
@@ -280,9 +283,9 @@ int32_t ftc_gcn_layer_backward(const ftc_csr *gT, const ftc_windows *wT, const f
 size_t ftc_agnn_layer_backward_workspace_bytes(int32_t n, int32_t nnz, int32_t D);
 int32_t ftc_agnn_layer_backward(const ftc_csr *g, const ftc_windows *w, const int32_t *T,
                                 const void *H, int32_t ld, int32_t dtype, int32_t D, float beta,
-                                const float *p, const void *dY, int32_t lddy, float *dH,
-                                int32_t lddh, float *dbeta, int32_t path, void *ws,
-                                size_t ws_bytes, void *stream);
+                                const float *p, const void *dY, int32_t lddy, void *dH,
+                                int32_t lddh, int32_t dh_dtype, float *dbeta, int32_t path,
+                                void *ws, size_t ws_bytes, void *stream);
 
 /*
  * Measurement aid (no part of the method): enqueues the bare gather pattern of the aggregation

@@ -44,14 +44,14 @@ _SIGNATURES = {
     "ftc_agnn_layer_workspace_bytes": (_Z, [_I, _I, _I]),
     "ftc_agnn_layer": (_I, [_P, _P, _P, _I, _I, _I, _F, _P, _I, _I, _P, _I, _P, _Z, _P]),
     "ftc_transpose_index": (_I, [_P, _P, _P, _P, _P]),
-    "ftc_edge_softmax_backward": (_I, [_P, _P, _P, _P, _P]),
+    "ftc_edge_softmax_backward": (_I, [_P, _P, _P, _P, _P, _P, _Z, _P]),
     "ftc_weight_grad_workspace_bytes": (_Z, [_I, _I, _I]),
     "ftc_weight_grad": (_I, [_I, _P, _I, _I, _I, _P, _I, _I, _P, _P, _Z, _P]),
     "ftc_gcn_layer_backward_workspace_bytes": (_Z, [_I, _I, _I, _I]),
     "ftc_gcn_layer_backward": (_I, [_P, _P, _P, _P, _P, _I, _I, _I, _P, _I, _P, _I, _I, _P, _I, _P, _I, _P, _I, _P,
                                     _Z, _P]),
     "ftc_agnn_layer_backward_workspace_bytes": (_Z, [_I, _I, _I]),
-    "ftc_agnn_layer_backward": (_I, [_P, _P, _P, _P, _I, _I, _I, _F, _P, _P, _I, _P, _I, _P, _I, _P, _Z, _P]),
+    "ftc_agnn_layer_backward": (_I, [_P, _P, _P, _P, _I, _I, _I, _F, _P, _P, _I, _P, _I, _I, _P, _I, _P, _Z, _P]),
     "ftc_gather_probe": (_I, [_P, C.c_int64, _P, _I, _I, _P, _P]),
 }
 EXPORTS = list(_SIGNATURES)
@@ -286,10 +286,13 @@ def ftc_transpose_index(g, w=None):
     return T, flag
 
 
-def ftc_edge_softmax_backward(g, p, dp, out=None):
+def ftc_edge_softmax_backward(g, w, p, dp, out=None, ws=None):
     if out is None:
         out = torch.empty_like(dp)
-    _check(lib().ftc_edge_softmax_backward(C.byref(g.c), _ptr(p), _ptr(dp), _ptr(out), _stream()))
+    if ws is None:
+        ws = _workspace(lib().ftc_edge_softmax_workspace_bytes(g.n, g.nnz), dp.device)
+    _check(lib().ftc_edge_softmax_backward(C.byref(g.c), _wref(w), _ptr(p), _ptr(dp), _ptr(out), _ptr(ws),
+                                           C.c_size_t(ws.numel()), _stream()))
     return out
 
 
@@ -323,15 +326,18 @@ def ftc_gcn_layer_backward(gT, wT, valsT, X, W, dY, Y=None, dinv=None, want_dX=T
     return dX, dW
 
 
-def ftc_agnn_layer_backward(g, w, T, H, p, dY, beta=1.0, path=FTC_PATH_AUTO, ws=None):
+def ftc_agnn_layer_backward(g, w, T, H, p, dY, beta=1.0, dH=None, dh_dtype=torch.float32, dbeta=None,
+                            path=FTC_PATH_AUTO, ws=None):
     n, D = H.shape
     assert dY.dtype == H.dtype and dY.shape == H.shape and dY.stride(0) == H.stride(0)
-    dH = torch.empty((n, D), dtype=torch.float32, device=H.device)
-    dbeta = torch.empty(1, dtype=torch.float32, device=H.device)
+    if dH is None:
+        dH = torch.empty((n, D), dtype=dh_dtype, device=H.device)
+    if dbeta is None:
+        dbeta = torch.empty(1, dtype=torch.float32, device=H.device)
     if ws is None:
         ws = _workspace(lib().ftc_agnn_layer_backward_workspace_bytes(g.n, g.nnz, D), H.device)
     _check(lib().ftc_agnn_layer_backward(
         C.byref(g.c), _wref(w), _ptr(T), _ptr(H), C.c_int32(H.stride(0)), C.c_int32(_dt(H)), C.c_int32(D),
-        C.c_float(beta), _ptr(p), _ptr(dY), C.c_int32(dY.stride(0)), _ptr(dH), C.c_int32(dH.stride(0)), _ptr(dbeta),
-        C.c_int32(path), _ptr(ws), C.c_size_t(ws.numel()), _stream()))
+        C.c_float(beta), _ptr(p), _ptr(dY), C.c_int32(dY.stride(0)), _ptr(dH), C.c_int32(dH.stride(0)),
+        C.c_int32(_dt(dH)), _ptr(dbeta), C.c_int32(path), _ptr(ws), C.c_size_t(ws.numel()), _stream()))
     return dH, dbeta

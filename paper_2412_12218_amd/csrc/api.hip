@@ -411,12 +411,22 @@ int32_t ftc_transpose_index(const ftc_csr *g, const ftc_windows *w, int32_t *T, 
     return launch_transpose_index(*g, e2r, T, flag, static_cast<hipStream_t>(stream));
 }
 
-int32_t ftc_edge_softmax_backward(const ftc_csr *g, const float *p, const float *dp, float *ds, void *stream)
+int32_t ftc_edge_softmax_backward(const ftc_csr *g, const ftc_windows *w, const float *p, const float *dp, float *ds,
+                                  void *ws, size_t ws_bytes, void *stream)
 {
     FTC_TRY(check_csr(g, "ftc_edge_softmax_backward"));
     if (g->n == 0 || g->nnz == 0) return FTC_OK;
     if (!p || !dp || !ds) return fail(FTC_EINVAL, "ftc_edge_softmax_backward: NULL edge array");
-    return launch_softmax_backward(*g, p, dp, ds, static_cast<hipStream_t>(stream));
+    if (!w) return launch_softmax_backward(*g, p, dp, ds, static_cast<hipStream_t>(stream));
+    FTC_TRY(check_windows(g, w, "ftc_edge_softmax_backward", false));
+    if (!w->edge_to_row) return fail(FTC_EINVAL, "ftc_edge_softmax_backward: edge_to_row is NULL");
+    const size_t need = softmax_seg_ws(g->n, g->nnz);
+    if (!ws || ws_bytes < need)
+        return fail(FTC_EWORKSPACE, "ftc_edge_softmax_backward: workspace of %zu bytes needed, %zu given", need,
+                    ws ? ws_bytes : static_cast<size_t>(0));
+    if (reinterpret_cast<uintptr_t>(ws) % 256 != 0)
+        return fail(FTC_EALIGN, "ftc_edge_softmax_backward: workspace must be 256-byte aligned");
+    return launch_softmax_backward_seg(*g, *w, p, dp, ds, ws, static_cast<hipStream_t>(stream));
 }
 
 size_t ftc_weight_grad_workspace_bytes(int32_t n, int32_t d_in, int32_t d_out)
@@ -491,21 +501,21 @@ size_t ftc_agnn_layer_backward_workspace_bytes(int32_t n, int32_t nnz, int32_t D
     if (n < 0 || nnz < 0 || D < 1) return 0;
     const size_t edge = align_up(static_cast<size_t>(nnz) * sizeof(float), 256);
     return 3 * edge + align_up(static_cast<size_t>(n) * sizeof(float), 256) +
-           align_up(static_cast<size_t>(n) * pad4(D) * sizeof(float), 256) +
+           2 * align_up(static_cast<size_t>(n) * pad4(D) * sizeof(float), 256) +
            align_up(ftc_sddmm_workspace_bytes(n, nnz, D), 256) + align_up(ftc_spmm_workspace_bytes(n, nnz, D), 256) +
-           edge_dot_ws();
+           align_up(softmax_seg_ws(n, nnz), 256) + edge_dot_ws();
 }
 
 int32_t ftc_agnn_layer_backward(const ftc_csr *g, const ftc_windows *w, const int32_t *T, const void *H, int32_t ld,
                                 int32_t dtype, int32_t D, float beta, const float *p, const void *dY, int32_t lddy,
-                                float *dH, int32_t lddh, float *dbeta, int32_t path, void *ws, size_t ws_bytes,
-                                void *stream)
+                                void *dH, int32_t lddh, int32_t dh_dtype, float *dbeta, int32_t path, void *ws,
+                                size_t ws_bytes, void *stream)
 {
     FTC_TRY(check_csr(g, "ftc_agnn_layer_backward"));
     if (g->n == 0) return FTC_OK;
     FTC_TRY(check_dense(H, ld, dtype, D, "ftc_agnn_layer_backward", "H"));
     FTC_TRY(check_dense(dY, lddy, dtype, D, "ftc_agnn_layer_backward", "dY"));
-    FTC_TRY(check_dense(dH, lddh, FTC_F32, D, "ftc_agnn_layer_backward", "dH"));
+    FTC_TRY(check_dense(dH, lddh, dh_dtype, D, "ftc_agnn_layer_backward", "dH"));
     if (!dbeta) return fail(FTC_EINVAL, "ftc_agnn_layer_backward: dbeta is NULL");
     if (g->nnz > 0 && (!T || !p)) return fail(FTC_EINVAL, "ftc_agnn_layer_backward: T or p is NULL");
     if (dH == H || dH == dY) return fail(FTC_EINVAL, "ftc_agnn_layer_backward: dH aliases an input");
@@ -524,14 +534,16 @@ int32_t ftc_agnn_layer_backward(const ftc_csr *g, const ftc_windows *w, const in
     float *v = reinterpret_cast<float *>(q8); q8 += edge;       // edge values of the two transposed products
     float *rinv = reinterpret_cast<float *>(q8); q8 += align_up(static_cast<size_t>(n) * sizeof(float), 256);
     float *q = reinterpret_cast<float *>(q8); q8 += align_up(static_cast<size_t>(n) * ldq * sizeof(float), 256);
+    float *agg = reinterpret_cast<float *>(q8); q8 += align_up(static_cast<size_t>(n) * ldq * sizeof(float), 256);
     void *ws_sd = q8; const size_t sd = align_up(ftc_sddmm_workspace_bytes(n, nnz, D), 256); q8 += sd;
     void *ws_sp = q8; const size_t sp = align_up(ftc_spmm_workspace_bytes(n, nnz, D), 256); q8 += sp;
+    void *ws_sm = q8; const size_t sm = align_up(softmax_seg_ws(n, nnz), 256); q8 += sm;
     void *ws_dot = q8;
     FTC_TRY(launch_row_rnorm(n, H, ld, dtype, D, rinv, hs));
     // c_e = cos(h_i, h_j);  dp_e = <dY_i, h_j>  (y_i = sum_e p_e h_j)
     FTC_TRY(ftc_sddmm(g, w, H, H, ld, dtype, D, nullptr, nullptr, 1.f, 1, c, path, ws_sd, sd, stream));
     FTC_TRY(ftc_sddmm(g, w, dY, H, ld, dtype, D, nullptr, nullptr, 1.f, 0, ds, path, ws_sd, sd, stream));
-    FTC_TRY(launch_softmax_backward(*g, p, ds, ds, hs));
+    FTC_TRY(ftc_edge_softmax_backward(g, w, p, ds, ds, ws_sm, sm, stream));
     FTC_TRY(launch_edge_dot(nnz, ds, c, dbeta, ws_dot, hs));  // s = beta * c, so dL/dbeta = sum_e ds_e c_e
     // gradient with respect to the normalised rows: q_i = sum_e (dc_e + dc_T(e)) hn_j, dc = beta * ds,
     // hn_j = rinv_j h_j folded into the edge values so that H itself is the gathered matrix
@@ -539,9 +551,9 @@ int32_t ftc_agnn_layer_backward(const ftc_csr *g, const ftc_windows *w, const in
     FTC_TRY(ftc_spmm(g, w, v, H, ld, dtype, D, q, ldq, FTC_F32, nullptr, 0, path, ws_sp, sp, stream));
     // through the aggregated rows: dH = P^T dY, (P^T)_e = p_T(e) on the symmetric pattern
     FTC_TRY(launch_edge_combine(nnz, p, T, 0.f, 1.f, 1.f, nullptr, g->col_idx, v, hs));
-    FTC_TRY(ftc_spmm(g, w, v, dY, lddy, dtype, D, dH, lddh, FTC_F32, nullptr, 0, path, ws_sp, sp, stream));
-    // ... plus the derivative of the normalisation
-    return launch_cos_backward_rows(n, H, ld, dtype, D, rinv, q, ldq, dH, lddh, hs);
+    FTC_TRY(ftc_spmm(g, w, v, dY, lddy, dtype, D, agg, ldq, FTC_F32, nullptr, 0, path, ws_sp, sp, stream));
+    // ... plus the derivative of the normalisation, rounded once to the requested type
+    return launch_cos_backward_rows(n, H, ld, dtype, D, rinv, q, ldq, agg, ldq, dH, lddh, dh_dtype, hs);
 }
 
 }  // extern "C"

@@ -373,13 +373,15 @@ int32_t launch_edge_dot(int nnz, const float *a, const float *b, float *out, voi
     return launch_status("edge_dot");
 }
 
-// ---- dH += rinv * (q - hn <hn, q>), hn = rinv * h -------------------------------------------------
-// q is the gradient with respect to the normalised rows; eight lanes per row.  A row whose norm
-// was clamped (|h| <= 1e-12) is a plain scaling: no projection.
+// ---- dH = base + rinv * (q - hn <hn, q>), hn = rinv * h --------------------------------------------
+// q is the gradient with respect to the normalised rows, base the part of dH that reaches h through
+// the aggregated rows; eight lanes per row.  A row whose norm was clamped (|h| <= 1e-12) is a plain
+// scaling: no projection.  base may be dH itself (fp32, in place).
 __global__ __launch_bounds__(256) void cos_backward_rows_kernel(int n, const void *__restrict__ H, int ld, int dt, int D,
                                                                 const float *__restrict__ rinv,
                                                                 const float *__restrict__ q, int ldq,
-                                                                float *__restrict__ dH, int lddh)
+                                                                const float *base, int ldb, void *dH, int lddh,
+                                                                int dh_dt)
 {
     const int sub = threadIdx.x & 7;
     const int64_t row = (static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x) >> 3;
@@ -395,16 +397,17 @@ __global__ __launch_bounds__(256) void cos_backward_rows_kernel(int n, const voi
     if (ok)
         for (int k = sub; k < D; k += 8) {
             const float hn = load_elem(H, row * ld + k, dt) * ri;
-            dH[row * lddh + k] += ri * (q[row * ldq + k] - hn * proj);
+            store_elem(dH, row * lddh + k, dh_dt, base[row * ldb + k] + ri * (q[row * ldq + k] - hn * proj));
         }
 }
 
 int32_t launch_cos_backward_rows(int n, const void *H, int ld, int dt, int D, const float *rinv, const float *q, int ldq,
-                                 float *dH, int lddh, hipStream_t s)
+                                 const float *base, int ldb, void *dH, int lddh, int dh_dt, hipStream_t s)
 {
     if (n == 0) return FTC_OK;
     const unsigned grid = static_cast<unsigned>((static_cast<int64_t>(n) * 8 + 255) / 256);
-    hipLaunchKernelGGL(cos_backward_rows_kernel, dim3(grid), dim3(256), 0, s, n, H, ld, dt, D, rinv, q, ldq, dH, lddh);
+    hipLaunchKernelGGL(cos_backward_rows_kernel, dim3(grid), dim3(256), 0, s, n, H, ld, dt, D, rinv, q, ldq, base, ldb,
+                       dH, lddh, dh_dt);
     return launch_status("cos_backward_rows");
 }
 

@@ -70,6 +70,8 @@ int32_t launch_spmm_mfma(const ftc_csr &g, const ftc_windows &w, const float *va
 // backward.hip
 int32_t launch_transpose_index(const ftc_csr &g, const int *edge_to_row, int *T, int *flag, hipStream_t s);
 int32_t launch_softmax_backward(const ftc_csr &g, const float *p, const float *dp, float *ds, hipStream_t s);
+int32_t launch_softmax_backward_seg(const ftc_csr &g, const ftc_windows &w, const float *p, const float *dp, float *ds,
+                                    void *ws, hipStream_t s);
 int32_t launch_mask_scale(int n, int d, const float *dY, int lddy, const void *Y, int ldy, int ydt,
                           const float *scale, float *out, int ldo, hipStream_t s);
 bool weight_grad_shape_ok(int d_in, int d_out);
@@ -83,7 +85,7 @@ int32_t launch_edge_combine(int nnz, const float *a, const int *T, float wa, flo
 size_t edge_dot_ws();
 int32_t launch_edge_dot(int nnz, const float *a, const float *b, float *out, void *ws, hipStream_t s);
 int32_t launch_cos_backward_rows(int n, const void *H, int ld, int dt, int D, const float *rinv, const float *q, int ldq,
-                                 float *dH, int lddh, hipStream_t s);
+                                 const float *base, int ldb, void *dH, int lddh, int dh_dt, hipStream_t s);
 size_t build_windows_ws(int n, int nnz, int blk_h, int blk_w);
 int32_t launch_build_windows(const ftc_csr &g, ftc_windows &w, void *ws, size_t ws_bytes, hipStream_t s);
 

@@ -131,6 +131,7 @@ __device__ __forceinline__ int dpp_i(int v)
 // segment.  Data-parallel-primitive moves: shifts by 1, 2, 4, 8 inside rows of 16 lanes, then lane
 // 15 of a row into the next row (rows 1 and 3) and lane 31 into rows 2 and 3.  The head flags are
 // OR-ed along with the values: a lane stops taking from the left once a head lies in its span.
+template <class Op>
 __device__ __forceinline__ MZ wave_segmented_scan(MZ x, int head, int lane)
 {
 #define FTC_STEP(CTRL, ROW_MASK, VALID)                                                  \
@@ -140,7 +141,7 @@ __device__ __forceinline__ MZ wave_segmented_scan(MZ x, int head, int lane)
         y.z = __int_as_float(dpp_i<CTRL, ROW_MASK>(__float_as_int(x.z)));                \
         const int yh = dpp_i<CTRL, ROW_MASK>(head);                                      \
         if (VALID) {                                                                     \
-            if (!head) x = mz_combine(y, x);                                             \
+            if (!head) x = Op::combine(y, x);                                            \
             head |= yh;                                                                  \
         }                                                                                \
     }
@@ -173,6 +174,26 @@ __device__ __forceinline__ void mz_push(MZ &a, float s)
     }
 }
 
+// The two row-wise edge operations that run on the range kernels below.  Both reduce a row to a
+// pair and then map every edge with it:
+//   forward   pair = (maximum, sum of exp) of the scores;           p  = exp(s - m) / z
+//   backward  pair = (unused, sum of p * dp) of the row's entries;  ds = p * (dp - sum)
+struct SoftmaxFwd {
+    static constexpr bool TWO_INPUTS = false;
+    __device__ static MZ identity() { return MZ{-INFINITY, 0.f}; }
+    __device__ static void push(MZ &a, float s, float) { mz_push(a, s); }
+    __device__ static MZ combine(MZ a, MZ b) { return mz_combine(a, b); }
+    __device__ static float result(float s, float, float2 t) { return __expf(s - t.x) / t.y; }
+};
+
+struct SoftmaxBwd {
+    static constexpr bool TWO_INPUTS = true;
+    __device__ static MZ identity() { return MZ{0.f, 0.f}; }
+    __device__ static void push(MZ &a, float p, float dp) { a.z = fmaf(p, dp, a.z); }
+    __device__ static MZ combine(MZ a, MZ b) { return MZ{0.f, a.z + b.z}; }
+    __device__ static float result(float p, float dp, float2 t) { return p * (dp - t.y); }
+};
+
 // A lane owns SMS_L consecutive edges of the wave's range: it walks them once to build the pairs of
 // the row pieces it holds (rows that begin and end inside the lane are final at once), ONE
 // segmented scan over the lanes joins the pieces that continue from lane to lane, and a second walk
@@ -185,10 +206,10 @@ __device__ __forceinline__ void mz_push(MZ &a, float s)
 // (n_valid when none), row of the leaving piece or -1, unused}.
 constexpr int SMS_L = SMS_R / 64;
 
-template <bool VEC>
+template <class Op, bool VEC>
 __global__ __launch_bounds__(256) void softmax_local_kernel(int nnz, int n_ranges,
                                                             const int *__restrict__ edge_to_row,
-                                                            const float *in, float *out,
+                                                            const float *in, const float *in2, float *out,
                                                             float2 *__restrict__ carry,
                                                             int4 *__restrict__ meta)
 {
@@ -202,7 +223,7 @@ __global__ __launch_bounds__(256) void softmax_local_kernel(int nnz, int n_range
     const int prev_row = base > 0 ? edge_to_row[base - 1] : -1;
     const int next_row = base + n_valid < nnz ? edge_to_row[base + n_valid] : -1;
     const int e0 = lane * SMS_L;  // first edge of the lane inside the range
-    float sc[SMS_L];
+    float sc[SMS_L], sc2[Op::TWO_INPUTS ? SMS_L : 1];
     int rw[SMS_L];
     if (VEC && n_valid == SMS_R) {
 #pragma unroll
@@ -211,6 +232,10 @@ __global__ __launch_bounds__(256) void softmax_local_kernel(int nnz, int n_range
             const float4 s4 = *reinterpret_cast<const float4 *>(in + base + e0 + 4 * q);
             rw[4 * q] = r4.x; rw[4 * q + 1] = r4.y; rw[4 * q + 2] = r4.z; rw[4 * q + 3] = r4.w;
             sc[4 * q] = s4.x; sc[4 * q + 1] = s4.y; sc[4 * q + 2] = s4.z; sc[4 * q + 3] = s4.w;
+            if constexpr (Op::TWO_INPUTS) {
+                const float4 t4 = *reinterpret_cast<const float4 *>(in2 + base + e0 + 4 * q);
+                sc2[4 * q] = t4.x; sc2[4 * q + 1] = t4.y; sc2[4 * q + 2] = t4.z; sc2[4 * q + 3] = t4.w;
+            }
         }
     } else {
 #pragma unroll
@@ -218,6 +243,7 @@ __global__ __launch_bounds__(256) void softmax_local_kernel(int nnz, int n_range
             const bool ok = e0 + k < n_valid;
             rw[k] = ok ? edge_to_row[base + e0 + k] : -2 - (e0 + k);  // padding: rows of their own
             sc[k] = ok ? in[base + e0 + k] : 0.f;
+            if constexpr (Op::TWO_INPUTS) sc2[k] = ok ? in2[base + e0 + k] : 0.f;
         }
     }
     // row beginnings inside the lane; `left` is the row of the edge before the lane's first
@@ -229,7 +255,7 @@ __global__ __launch_bounds__(256) void softmax_local_kernel(int nnz, int n_range
     const int nb = __popc(begins);
     const int first_num = wave_inclusive_scan(nb) - nb;  // number of the row that is open at the lane's start
     // first walk: pairs of the pieces
-    MZ cur = {-INFINITY, 0.f}, first_piece = {-INFINITY, 0.f};
+    MZ cur = Op::identity(), first_piece = Op::identity();
     int seen = 0;
 #pragma unroll
     for (int k = 0; k < SMS_L; ++k) {
@@ -237,20 +263,19 @@ __global__ __launch_bounds__(256) void softmax_local_kernel(int nnz, int n_range
             if (seen == 0) first_piece = cur;                                  // joined with the lanes on the left below
             else table[first_num + seen] = make_float2(cur.m, cur.z);           // a row inside the lane: final
             ++seen;
-            cur = MZ{-INFINITY, 0.f};
+            cur = Op::identity();
         }
-        mz_push(cur, sc[k]);
+        Op::push(cur, sc[k], sc2[Op::TWO_INPUTS ? k : 0]);
     }
     if (nb == 0) first_piece = cur;
     // one segmented scan over the lanes: what flows into a lane from the left
-    const MZ incl = wave_segmented_scan(cur, nb > 0 ? 1 : 0, lane);  // `cur` is the lane's last (or only) piece
+    const MZ incl = wave_segmented_scan<Op>(cur, nb > 0 ? 1 : 0, lane);  // `cur` is the lane's last (or only) piece
     MZ from_left;
-    from_left.m = __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(-INFINITY), __float_as_int(incl.m), 0x138,
-                                                             0xf, 0xf, false));
+    from_left.m = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(incl.m), 0x138, 0xf, 0xf, false));
     from_left.z = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(incl.z), 0x138, 0xf, 0xf, false));
-    if (lane == 0) from_left = MZ{-INFINITY, 0.f};
+    if (lane == 0) from_left = Op::identity();
     if (nb > 0) {  // the row that was open at the lane's start ends at the lane's first beginning
-        const MZ t = mz_combine(from_left, first_piece);
+        const MZ t = Op::combine(from_left, first_piece);
         if (first_num == 0) carry[2 * static_cast<size_t>(v)] = make_float2(t.m, t.z);  // entered from the left
         else table[first_num] = make_float2(t.m, t.z);
     }
@@ -284,7 +309,7 @@ __global__ __launch_bounds__(256) void softmax_local_kernel(int nnz, int n_range
         pr[k] = 0.f;
         if (ok && !in_head && !in_tail) {
             if (!have) { t = table[num]; have = true; }
-            pr[k] = __expf(sc[k] - t.x) / t.y;
+            pr[k] = Op::result(sc[k], sc2[Op::TWO_INPUTS ? k : 0], t);
             done |= 1u << k;
         }
     }
@@ -303,6 +328,7 @@ __global__ __launch_bounds__(256) void softmax_local_kernel(int nnz, int n_range
     if (lane == 0) meta[v] = make_int4(head_cnt, n_valid - tail_cnt, tail_num >= 0 ? last_row : -1, 0);
 }
 
+template <class Op>
 __global__ __launch_bounds__(256) void softmax_fixup_kernel(int n_ranges, const int *__restrict__ row_ptr,
                                                             const float2 *__restrict__ carry,
                                                             const int4 *__restrict__ meta,
@@ -317,18 +343,19 @@ __global__ __launch_bounds__(256) void softmax_fixup_kernel(int n_ranges, const 
     MZ acc = {t.x, t.y};
     for (int u = v + 1; u <= last; ++u) {
         t = carry[2 * static_cast<size_t>(u)];
-        acc = mz_combine(acc, MZ{t.x, t.y});
+        acc = Op::combine(acc, MZ{t.x, t.y});
     }
     stats[r] = make_float2(acc.m, acc.z);
 }
 
 // Probabilities of the pieces of cut rows: the entering piece (edges [0, head_len) of the range,
 // row = row of the edge before the range) and the leaving piece (edges [tail_start, n_valid)).
+template <class Op>
 __global__ __launch_bounds__(256) void softmax_cut_kernel(int nnz, int n_ranges,
                                                           const int *__restrict__ edge_to_row,
                                                           const float2 *__restrict__ stats,
                                                           const int4 *__restrict__ meta, const float *in,
-                                                          float *out)
+                                                          const float *in2, float *out)
 {
     const int lane = threadIdx.x & 63;
     const int v = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -338,11 +365,13 @@ __global__ __launch_bounds__(256) void softmax_cut_kernel(int nnz, int n_ranges,
     const int4 mt = meta[v];
     if (mt.x > 0) {
         const float2 st = stats[edge_to_row[base - 1]];  // head_len > 0 implies base > 0
-        for (int i = lane; i < mt.x; i += 64) out[base + i] = __expf(in[base + i] - st.x) / st.y;
+        for (int i = lane; i < mt.x; i += 64)
+            out[base + i] = Op::result(in[base + i], Op::TWO_INPUTS ? in2[base + i] : 0.f, st);
     }
     if (mt.z >= 0) {
         const float2 st = stats[mt.z];
-        for (int i = mt.y + lane; i < n_valid; i += 64) out[base + i] = __expf(in[base + i] - st.x) / st.y;
+        for (int i = mt.y + lane; i < n_valid; i += 64)
+            out[base + i] = Op::result(in[base + i], Op::TWO_INPUTS ? in2[base + i] : 0.f, st);
     }
 }
 
@@ -353,8 +382,9 @@ size_t softmax_seg_ws(int n, int nnz)
            align_up(n_ranges * sizeof(int4), 256);
 }
 
-int32_t launch_softmax_seg(const ftc_csr &g, const ftc_windows &w, const float *in, float *out, void *ws,
-                           hipStream_t s)
+template <class Op>
+static int32_t launch_ranges(const ftc_csr &g, const ftc_windows &w, const float *in, const float *in2, float *out,
+                             void *ws, hipStream_t s)
 {
     if (g.n == 0 || g.nnz == 0) return FTC_OK;
     const int n_ranges = (g.nnz + SMS_R - 1) / SMS_R;
@@ -364,23 +394,36 @@ int32_t launch_softmax_seg(const ftc_csr &g, const ftc_windows &w, const float *
     float2 *carry = reinterpret_cast<float2 *>(p);
     p += align_up(static_cast<size_t>(n_ranges) * 2 * sizeof(float2), 256);
     int4 *meta = reinterpret_cast<int4 *>(p);
-    // 16-byte loads and stores of the scores / probabilities when the arrays allow it
-    const bool vec = aligned16(in) && aligned16(out) && aligned16(w.edge_to_row);
+    // 16-byte loads and stores of the edge arrays when they allow it
+    const bool vec = aligned16(in) && aligned16(out) && aligned16(w.edge_to_row) && (!in2 || aligned16(in2));
     if (vec)
-        hipLaunchKernelGGL(softmax_local_kernel<true>, dim3((n_ranges + 3) / 4), dim3(256), 0, s, g.nnz, n_ranges,
-                           w.edge_to_row, in, out, carry, meta);
+        hipLaunchKernelGGL((softmax_local_kernel<Op, true>), dim3((n_ranges + 3) / 4), dim3(256), 0, s, g.nnz,
+                           n_ranges, w.edge_to_row, in, in2, out, carry, meta);
     else
-        hipLaunchKernelGGL(softmax_local_kernel<false>, dim3((n_ranges + 3) / 4), dim3(256), 0, s, g.nnz, n_ranges,
-                           w.edge_to_row, in, out, carry, meta);
+        hipLaunchKernelGGL((softmax_local_kernel<Op, false>), dim3((n_ranges + 3) / 4), dim3(256), 0, s, g.nnz,
+                           n_ranges, w.edge_to_row, in, in2, out, carry, meta);
     int32_t st = launch_status("edge_softmax local");
     if (st != FTC_OK) return st;
-    hipLaunchKernelGGL(softmax_fixup_kernel, dim3((n_ranges + 255) / 256), dim3(256), 0, s, n_ranges, g.row_ptr,
+    hipLaunchKernelGGL(softmax_fixup_kernel<Op>, dim3((n_ranges + 255) / 256), dim3(256), 0, s, n_ranges, g.row_ptr,
                        carry, meta, stats);
     st = launch_status("edge_softmax fixup");
     if (st != FTC_OK) return st;
-    hipLaunchKernelGGL(softmax_cut_kernel, dim3((n_ranges + 3) / 4), dim3(256), 0, s, g.nnz, n_ranges,
-                       w.edge_to_row, stats, meta, in, out);
+    hipLaunchKernelGGL(softmax_cut_kernel<Op>, dim3((n_ranges + 3) / 4), dim3(256), 0, s, g.nnz, n_ranges,
+                       w.edge_to_row, stats, meta, in, in2, out);
     return launch_status("edge_softmax cut rows");
+}
+
+int32_t launch_softmax_seg(const ftc_csr &g, const ftc_windows &w, const float *in, float *out, void *ws,
+                           hipStream_t s)
+{
+    return launch_ranges<SoftmaxFwd>(g, w, in, nullptr, out, ws, s);
+}
+
+// ds = p * (dp - sum over the row of p * dp), same workspace as the forward call; ds may alias dp
+int32_t launch_softmax_backward_seg(const ftc_csr &g, const ftc_windows &w, const float *p, const float *dp, float *ds,
+                                    void *ws, hipStream_t s)
+{
+    return launch_ranges<SoftmaxBwd>(g, w, p, dp, ds, ws, s);
 }
 
 // ------------------------------------------------------------------------------------------------

@@ -1,5 +1,6 @@
 """Layer chaining of the two benchmark models (Section VI: 2-layer GCN with hidden size 16,
-4-layer AGNN with hidden size 32), forward only.
+4-layer AGNN with hidden size 32): HotPath is the forward pass the benchmark times, TrainPath
+the forward + backward pass of the same two models.
 
 Every step is a call into libftc through `binding`; this module only owns the device
 buffers between the calls (allocated once in __init__, so a forward pass allocates nothing).
@@ -59,3 +60,69 @@ class HotPath:
         self.build()
         self.gcn(X, W1, W2)
         self.agnn(X, W_in, W_out, betas)
+
+
+class TrainPath:
+    """Forward + backward of the two models on one graph with a symmetric pattern (the paper
+    names training in Sections II and V and gives no formulas: the gradients are the derivatives
+    of the forward definitions).  The GCN normalisation is the factored one, whose transposed
+    operator is the operator itself; the AGNN backward needs the transposed index, built once here."""
+
+    def __init__(self, g, win, dinv, d_feat=128, gcn_hidden=16, agnn_hidden=32, n_out=8, agnn_layers=4,
+                 act_dtype=torch.float16, path=B.FTC_PATH_AUTO):
+        dev = g.row_ptr.device
+        L = B.lib()
+        self.g, self.win, self.dinv, self.path, self.agnn_layers = g, win, dinv, path, agnn_layers
+        n, nnz = g.n, g.nnz
+        self.T, flag = B.ftc_transpose_index(g, win)
+        if int(flag.item()) != 0:
+            raise ValueError("TrainPath needs a symmetric sparsity pattern with ascending, duplicate-free rows")
+        f32 = dict(dtype=torch.float32, device=dev)
+        act = dict(dtype=act_dtype, device=dev)
+        self.gcn_h = torch.empty((n, gcn_hidden), **act)
+        self.gcn_out = torch.empty((n, n_out), **f32)
+        self.agnn_h = [None] + [torch.empty((n, agnn_hidden), **act) for _ in range(agnn_layers)]
+        self.agnn_p = [torch.empty(nnz, **f32) for _ in range(agnn_layers)]
+        self.d_agnn_h = [torch.empty((n, agnn_hidden), **act) for _ in range(2)]
+        self.dbeta = torch.empty(agnn_layers, **f32)
+        self.ws = B._workspace(max(
+            L.ftc_gcn_layer_workspace_bytes(n, nnz, d_feat, gcn_hidden),
+            L.ftc_gcn_layer_workspace_bytes(n, nnz, gcn_hidden, n_out),
+            L.ftc_gcn_layer_backward_workspace_bytes(n, nnz, d_feat, gcn_hidden),
+            L.ftc_gcn_layer_backward_workspace_bytes(n, nnz, gcn_hidden, n_out),
+            L.ftc_agnn_layer_workspace_bytes(n, nnz, agnn_hidden),
+            L.ftc_agnn_layer_backward_workspace_bytes(n, nnz, agnn_hidden)), dev)
+
+    def gcn_forward(self, X, W1, W2):
+        B.ftc_gcn_layer(self.g, self.win, None, X, W1, relu=True, out=self.gcn_h, path=self.path, ws=self.ws,
+                        dinv=self.dinv)
+        B.ftc_gcn_layer(self.g, self.win, None, self.gcn_h, W2, relu=False, out=self.gcn_out, path=self.path,
+                        ws=self.ws, dinv=self.dinv)
+        return self.gcn_out
+
+    def gcn_backward(self, X, W1, W2, d_out):
+        """d_out = dL/d(gcn_out), fp32.  Returns (dW1, dW2); the input features get no gradient."""
+        d_h, dW2 = B.ftc_gcn_layer_backward(self.g, self.win, None, self.gcn_h, W2, d_out, dinv=self.dinv,
+                                            path=self.path, ws=self.ws)
+        _, dW1 = B.ftc_gcn_layer_backward(self.g, self.win, None, X, W1, d_h, Y=self.gcn_h, dinv=self.dinv,
+                                          want_dX=False, path=self.path, ws=self.ws)
+        return dW1, dW2
+
+    def agnn_forward(self, H0, betas):
+        """Propagation layers only (the dense layers around them are ftc_update_gemm / ftc_weight_grad);
+        every layer keeps its attention probabilities for the backward pass."""
+        self.agnn_h[0] = H0
+        for l in range(self.agnn_layers):
+            B.ftc_agnn_layer(self.g, self.win, self.agnn_h[l], beta=betas[l], out=self.agnn_h[l + 1],
+                             edge_p=self.agnn_p[l], path=self.path, ws=self.ws)
+        return self.agnn_h[self.agnn_layers]
+
+    def agnn_backward(self, betas, d_out):
+        """d_out = dL/d(last layer's output), in the activation type.  Returns (dL/dH0, dbeta[layers])."""
+        d = d_out
+        for l in reversed(range(self.agnn_layers)):
+            nxt = self.d_agnn_h[l & 1]
+            B.ftc_agnn_layer_backward(self.g, self.win, self.T, self.agnn_h[l], self.agnn_p[l], d, beta=betas[l],
+                                      dH=nxt, dbeta=self.dbeta[l:l + 1], path=self.path, ws=self.ws)
+            d = nxt
+        return d, self.dbeta

@@ -3,8 +3,9 @@ ABI, against the fp64 backward oracle on the same seeded inputs.
 
 Integer outputs (the transposed index) are bit-exact.  A gradient element is compared as
 |gpu - ref| / (max |ref| over its row + 0.01 * max |ref| over the array) for per-node gradients and
-|gpu - ref| / max |ref| for the small dense ones (dW, dbeta): 1e-4 for fp32 inputs, 2e-3 for 16-bit
-inputs.  (A gradient is a difference of sums that nearly cancel in places, the softmax backward
+|gpu - ref| / max |ref| for the small dense ones (dW, dbeta), and must stay below 1e-5 for every
+input type: the oracle gets the rounded 16-bit inputs exactly and every intermediate of the backward
+pass is fp32.  (A gradient is a difference of sums that nearly cancel in places, the softmax backward
 above all, so single elements are not compared relative to themselves.)"""
 import numpy as np
 import pytest
@@ -19,7 +20,7 @@ from paper_2412_12218_amd import binding as B
 pytestmark = pytest.mark.gpu
 
 F32, F16, BF16 = torch.float32, torch.float16, torch.bfloat16
-GTOL = {F32: 1e-4, F16: 2e-3, BF16: 2e-3}
+GTOL = {F32: 1e-5, F16: 1e-5, BF16: 1e-5}
 
 
 def say(msg):
@@ -114,7 +115,8 @@ def long_row_graph():
 
 
 @pytest.mark.parametrize("name", ["cfg1", "cfg5s", "long_rows"])
-def test_edge_softmax_backward(oracle, graphs, name):
+@pytest.mark.parametrize("with_windows", [True, False])
+def test_edge_softmax_backward(oracle, graphs, name, with_windows):
     g = long_row_graph() if name == "long_rows" else graphs[name]
     say(f"softmax_backward {name} n={g.n} nnz={g.nnz}")
     rng = np.random.default_rng(8)
@@ -124,8 +126,9 @@ def test_edge_softmax_backward(oracle, graphs, name):
     dp32 = rng.normal(size=g.nnz).astype(np.float32)
     ref = OB.edge_softmax_backward(g.row_ptr, p32.astype(np.float64), dp32.astype(np.float64))
     dg = dev_graph(g)
+    win = B.ftc_build_windows(dg) if with_windows else None      # entry-balanced kernels / row kernel
     p, dp = torch.from_numpy(p32).cuda(), torch.from_numpy(dp32).cuda()
-    ds = B.ftc_edge_softmax_backward(dg, p, dp)
+    ds = B.ftc_edge_softmax_backward(dg, win, p, dp)
     # every term is bounded by p * (|dp| + sum p |dp|): compare against that
     rows = np.repeat(np.arange(g.n), np.diff(g.row_ptr))
     ab = np.zeros(g.n)
@@ -136,10 +139,10 @@ def test_edge_softmax_backward(oracle, graphs, name):
     say(f"  err {err:.3e}")
     assert err < 1e-5
     assert np.all(got[bound == 0] == 0)
-    ds2 = B.ftc_edge_softmax_backward(dg, p, dp.clone(), out=None)
+    ds2 = B.ftc_edge_softmax_backward(dg, win, p, dp.clone(), out=None)
     assert torch.equal(ds, ds2)
     dpc = dp.clone()
-    B.ftc_edge_softmax_backward(dg, p, dpc, out=dpc)      # in place
+    B.ftc_edge_softmax_backward(dg, win, p, dpc, out=dpc)      # in place
     assert torch.equal(dpc, ds)
 
 
@@ -243,9 +246,9 @@ def test_agnn_layer_backward(graphs, name, dtype, D, beta):
     eh = row_err(dH, dH_ref)
     # dbeta sums nnz signed terms ds_e c_e: compare against the size of a typical partial sum
     db = abs(float(dbeta.item()) - dbeta_ref)
-    say(f"  dH err {eh:.3e} dbeta {float(dbeta.item()):.6g} ref {dbeta_ref:.6g}")
+    say(f"  dH err {eh:.3e} dbeta {float(dbeta.item()):.6g} ref {dbeta_ref:.6g} diff {db:.2e}")
     assert eh < GTOL[dtype]
-    assert db < GTOL[dtype] * max(abs(dbeta_ref), np.sqrt(g.n) * 1e-2)
+    assert db < 1e-4 * max(abs(dbeta_ref), np.sqrt(g.n) * 1e-2)     # a sum of nnz signed fp32 terms
     dH2, dbeta2 = B.ftc_agnn_layer_backward(dg, None, T, Hd, p, dYd, beta=beta)      # row kernels
     assert row_err(dH2, dH_ref) < GTOL[dtype]
     dH3, dbeta3 = B.ftc_agnn_layer_backward(dg, win, T, Hd, p, dYd, beta=beta)
@@ -273,6 +276,77 @@ def test_agnn_layer_backward_zero_rows_and_isolated_nodes():
     assert row_err(dH[torch.from_numpy(keep).cuda()], dH_ref[keep]) < 1e-4
     assert np.all(np.isfinite(dH.cpu().numpy()))
     assert abs(float(dbeta.item()) - dbeta_ref) < 1e-4 * max(abs(dbeta_ref), 1.0)
+
+
+def test_agnn_layer_backward_16bit_gradient_output(graphs):
+    """dH written in the activation type (what the layer below takes as its incoming gradient):
+    the fp32 result rounded once."""
+    g = graphs["cfg1"]
+    Hd, _ = quantise(synth.normal_features(g.n, 32, seed=11), F16)
+    dYd, _ = quantise(synth.normal_features(g.n, 32, seed=14), F16)
+    dg = dev_graph(g)
+    win = B.ftc_build_windows(dg)
+    T, _ = B.ftc_transpose_index(dg, win)
+    p = torch.empty(g.nnz, dtype=F32, device="cuda")
+    B.ftc_agnn_layer(dg, win, Hd, beta=1.0, edge_p=p)
+    dH32, db32 = B.ftc_agnn_layer_backward(dg, win, T, Hd, p, dYd)
+    for dt in (F16, BF16):
+        dH16, db16 = B.ftc_agnn_layer_backward(dg, win, T, Hd, p, dYd, dh_dtype=dt)
+        assert dH16.dtype == dt and torch.equal(dH16, dH32.to(dt)) and torch.equal(db16, db32)
+
+
+def test_train_path_stacks_against_chained_oracle(oracle):
+    """TrainPath (2-layer GCN, 3 AGNN propagation layers, fp32 activations) against the per-layer
+    oracles chained on the CPU."""
+    from paper_2412_12218_amd.models import TrainPath
+    g = synth.config_graph(1)
+    n = g.n
+    dg = dev_graph(g)
+    win = B.ftc_build_windows(dg)
+    _, dinv = B.ftc_gcn_norm(dg, win)
+    tp = TrainPath(dg, win, dinv, d_feat=24, gcn_hidden=16, agnn_hidden=12, n_out=8, agnn_layers=3, act_dtype=F32)
+    dinv64 = dinv.cpu().double().numpy()
+    rows = np.repeat(np.arange(n), np.diff(g.row_ptr))
+    vals = dinv64[rows] * dinv64[g.col_idx]
+    # GCN
+    Xd, X64 = quantise(synth.uniform_features(n, 24, seed=31), F32)
+    W1d, W164 = quantise(synth.glorot_uniform(24, 16, seed=32), F32)
+    W2d, W264 = quantise(synth.glorot_uniform(16, 8, seed=33), F32)
+    dOutd, dOut64 = quantise(synth.normal_features(n, 8, seed=34), F32)
+    tp.gcn_forward(Xd, W1d, W2d)
+    dW1, dW2 = tp.gcn_backward(Xd, W1d, W2d, dOutd)
+    H1 = tp.gcn_h.cpu().double().numpy()
+    dH1_ref, dW2_ref, _ = OB.gcn_layer_backward(g.row_ptr, g.col_idx, vals, H1, W264, dOut64)
+    _, dW1_ref, _ = OB.gcn_layer_backward(g.row_ptr, g.col_idx, vals, X64, W164, dH1_ref, Y=H1)
+    e1, e2 = arr_err(dW1, dW1_ref), arr_err(dW2, dW2_ref)
+    say(f"gcn stack dW1 err {e1:.3e} dW2 err {e2:.3e}")
+    assert e1 < 1e-4 and e2 < 1e-4
+    # AGNN
+    betas = [1.0, -0.7, 2.0]
+    H0d, H064 = quantise(synth.normal_features(n, 12, seed=35), F32)
+    dYd, dY64 = quantise(synth.normal_features(n, 12, seed=36), F32)
+    tp.agnn_forward(H0d, betas)
+    dH0, dbeta = tp.agnn_backward(betas, dYd)
+    Hs = [H064]
+    for l in range(3):
+        Hs.append(oracle.agnn_layer(g.row_ptr, g.col_idx, Hs[l], betas[l])[0])
+    d, db_ref = dY64, [0.0] * 3
+    for l in reversed(range(3)):
+        d, db_ref[l] = OB.agnn_layer_backward(g.row_ptr, g.col_idx, Hs[l], betas[l], d)
+    eh = row_err(dH0, d)
+    say(f"agnn stack dH0 err {eh:.3e} dbeta {dbeta.cpu().numpy()} ref {db_ref}")
+    assert eh < 1e-4
+    assert np.allclose(dbeta.cpu().double().numpy(), db_ref, rtol=1e-3, atol=1e-3 * np.sqrt(n) * 1e-2)
+
+
+def test_train_path_rejects_a_non_symmetric_pattern():
+    from paper_2412_12218_amd.models import TrainPath
+    g = directed_graph(300, 1500, seed=2)
+    dg = dev_graph(g)
+    win = B.ftc_build_windows(dg)
+    _, dinv = B.ftc_gcn_norm(dg, win)
+    with pytest.raises(ValueError):
+        TrainPath(dg, win, dinv)
 
 
 def test_backward_rejects_bad_arguments():
