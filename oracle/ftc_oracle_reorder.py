@@ -1,0 +1,61 @@
+"""CPU oracle of the locality reordering used in preprocessing (TEST INFRASTRUCTURE ONLY).
+
+The paper's sparse graph transformation condenses the columns of a row window (Section IV.A); how
+many columns the rows of a window share depends on the numbering of the nodes, which the paper
+takes as given.  Relabelling the nodes before the transformation is the preprocessing step defined
+here: a permutation of the node ids, the relabelled CSR, and the row maps that carry features into
+the new numbering and results back (permutation in, permutation out).  Everything is integer work
+with a unique result, written as plain loops and numpy sorts.  Nothing in the product library
+imports this file, and it shares no code with the HIP kernels.
+
+perm[new] = old id of the node that gets the id `new`;  inv[old] = new.
+"""
+import numpy as np
+
+ORDER_DEGREE = 0          # descending number of stored entries of the row, ties by ascending id
+ORDER_DEGREE_CLASSES = 1  # descending bit length of that number, ties by ascending id
+
+
+def bit_length(x):
+    """Number of bits of x (0 for 0): the power-of-two class of a degree."""
+    x = np.asarray(x, dtype=np.int64)
+    out = np.zeros(x.shape, dtype=np.int64)
+    v = x.copy()
+    while np.any(v > 0):
+        out += v > 0
+        v >>= 1
+    return out
+
+
+def degree_order(row_ptr, mode=ORDER_DEGREE):
+    """(perm, inv) of the ordering `mode`."""
+    row_ptr = np.asarray(row_ptr, dtype=np.int64)
+    deg = np.diff(row_ptr)
+    key = deg if mode == ORDER_DEGREE else bit_length(deg)
+    n = deg.size
+    perm = np.array(sorted(range(n), key=lambda i: (-int(key[i]), i)), dtype=np.int64)
+    inv = np.empty(n, dtype=np.int64)
+    inv[perm] = np.arange(n)
+    return perm, inv
+
+
+def permute_graph(row_ptr, col_idx, perm, inv):
+    """CSR of the relabelled graph: row `new` holds the entries of row perm[new] with every column c
+    replaced by inv[c], in ascending order (duplicates kept)."""
+    row_ptr = np.asarray(row_ptr, dtype=np.int64)
+    col = np.asarray(col_idx, dtype=np.int64)
+    n = row_ptr.size - 1
+    rp = np.zeros(n + 1, dtype=np.int64)
+    out = []
+    for new in range(n):
+        old = perm[new]
+        cols = np.sort(inv[col[row_ptr[old]:row_ptr[old + 1]]])
+        out.append(cols)
+        rp[new + 1] = rp[new] + cols.size
+    ci = np.concatenate(out) if out else np.zeros(0, dtype=np.int64)
+    return rp, ci.astype(np.int64)
+
+
+def permute_rows(X, index):
+    """out[r] = X[index[r]]: index = perm carries rows into the new numbering, index = inv back."""
+    return np.asarray(X)[np.asarray(index, dtype=np.int64)]
