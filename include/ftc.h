@@ -288,6 +288,48 @@ int32_t ftc_agnn_layer_backward(const ftc_csr *g, const ftc_windows *w, const in
                                 void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * ---- Locality reordering (preprocessing) ------------------------------------------------------
+ * The sparse graph transformation (Section IV.A) condenses the columns that the rows of a window
+ * share; how many they share, and how often a gathered feature row is still in cache, depends on
+ * the numbering of the nodes, which the paper takes as given.  These calls relabel the nodes before
+ * the transformation and keep a permutation-in / permutation-out contract:
+ *   perm[new] = old id, inv[old] = new id (device, int32, n entries each);
+ *   features enter the new numbering with ftc_permute_rows(map = perm), results leave it with
+ *   ftc_permute_rows(map = inv); the layers themselves run on the relabelled graph unchanged.
+ * All results are unique (stable sorts) and reproducible.
+ */
+enum {
+    FTC_ORDER_DEGREE = 0,         /* descending number of stored entries of the row, ties: ascending id */
+    FTC_ORDER_DEGREE_CLASSES = 1  /* descending bit length of that number (power-of-two classes), ties:
+                                     ascending id -- keeps the given order inside a class */
+};
+
+/* Workspace of ftc_degree_order and ftc_permute_graph. */
+size_t ftc_reorder_workspace_bytes(int32_t n, int32_t nnz);
+
+/* perm and inv of the ordering `mode` of g's nodes. */
+int32_t ftc_degree_order(const ftc_csr *g, int32_t mode, int32_t *perm, int32_t *inv, void *ws,
+                         size_t ws_bytes, void *stream);
+
+/*
+ * Relabelled graph: row `new` of the output holds the entries of row perm[new] of g with every
+ * column c replaced by inv[c], ascending inside the row, duplicates kept.  row_ptr_out has n + 1
+ * entries, col_idx_out nnz.  (perm, inv) may come from ftc_degree_order or from the caller (e.g. a
+ * community ordering); *flag (device int32) becomes 1 if they are not a permutation and its
+ * inverse -- no index is followed unchecked, the output is then unspecified -- else 0.
+ */
+int32_t ftc_permute_graph(const ftc_csr *g, const int32_t *perm, const int32_t *inv,
+                          int32_t *row_ptr_out, int32_t *col_idx_out, int32_t *flag, void *ws,
+                          size_t ws_bytes, void *stream);
+
+/*
+ * out[r, :] = X[map[r], :] for r in [0, n): X and out are n x D matrices of the same dtype; a map
+ * entry outside [0, n) gives a row of zeros.  out must not alias X.
+ */
+int32_t ftc_permute_rows(int32_t n, const void *X, int32_t ldx, int32_t dtype, int32_t D,
+                         const int32_t *map, void *out, int32_t ldo, void *stream);
+
+/*
  * Measurement aid (no part of the method): enqueues the bare gather pattern of the aggregation
  * kernels -- for every index i of idx[0 .. n_idx) (device, int32; a trailing group of fewer than
  * 512 indices is ignored) the row_bytes (16, 32, 64 or 128) bytes at X + idx[i] * stride_bytes are

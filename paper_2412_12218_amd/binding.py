@@ -52,6 +52,10 @@ _SIGNATURES = {
                                     _Z, _P]),
     "ftc_agnn_layer_backward_workspace_bytes": (_Z, [_I, _I, _I]),
     "ftc_agnn_layer_backward": (_I, [_P, _P, _P, _P, _I, _I, _I, _F, _P, _P, _I, _P, _I, _I, _P, _I, _P, _Z, _P]),
+    "ftc_reorder_workspace_bytes": (_Z, [_I, _I]),
+    "ftc_degree_order": (_I, [_P, _I, _P, _P, _P, _Z, _P]),
+    "ftc_permute_graph": (_I, [_P, _P, _P, _P, _P, _P, _P, _Z, _P]),
+    "ftc_permute_rows": (_I, [_I, _P, _I, _I, _I, _P, _P, _I, _P]),
     "ftc_gather_probe": (_I, [_P, C.c_int64, _P, _I, _I, _P, _P]),
 }
 EXPORTS = list(_SIGNATURES)
@@ -341,3 +345,40 @@ def ftc_agnn_layer_backward(g, w, T, H, p, dY, beta=1.0, dH=None, dh_dtype=torch
         C.c_float(beta), _ptr(p), _ptr(dY), C.c_int32(dY.stride(0)), _ptr(dH), C.c_int32(dH.stride(0)),
         C.c_int32(_dt(dH)), _ptr(dbeta), C.c_int32(path), _ptr(ws), C.c_size_t(ws.numel()), _stream()))
     return dH, dbeta
+
+
+# ---- locality reordering ------------------------------------------------------------------------------
+FTC_ORDER_DEGREE, FTC_ORDER_DEGREE_CLASSES = 0, 1
+
+
+def ftc_degree_order(g, mode=FTC_ORDER_DEGREE, ws=None):
+    dev = g.row_ptr.device
+    perm = torch.empty(g.n, dtype=torch.int32, device=dev)
+    inv = torch.empty(g.n, dtype=torch.int32, device=dev)
+    if ws is None:
+        ws = _workspace(lib().ftc_reorder_workspace_bytes(g.n, g.nnz), dev)
+    _check(lib().ftc_degree_order(C.byref(g.c), C.c_int32(mode), _ptr(perm), _ptr(inv), _ptr(ws),
+                                  C.c_size_t(ws.numel()), _stream()))
+    return perm, inv
+
+
+def ftc_permute_graph(g, perm, inv, ws=None):
+    """Returns (relabelled Graph, flag tensor: 0 if (perm, inv) is a permutation and its inverse)."""
+    dev = g.row_ptr.device
+    row_ptr = torch.empty(g.n + 1, dtype=torch.int32, device=dev)
+    col_idx = torch.empty(g.nnz, dtype=torch.int32, device=dev)
+    flag = torch.empty(1, dtype=torch.int32, device=dev)
+    if ws is None:
+        ws = _workspace(lib().ftc_reorder_workspace_bytes(g.n, g.nnz), dev)
+    _check(lib().ftc_permute_graph(C.byref(g.c), _ptr(perm), _ptr(inv), _ptr(row_ptr), _ptr(col_idx), _ptr(flag),
+                                   _ptr(ws), C.c_size_t(ws.numel()), _stream()))
+    return Graph(row_ptr, col_idx), flag
+
+
+def ftc_permute_rows(X, index, out=None):
+    n, D = X.shape
+    if out is None:
+        out = torch.empty((n, D), dtype=X.dtype, device=X.device)
+    _check(lib().ftc_permute_rows(C.c_int32(n), _ptr(X), C.c_int32(X.stride(0)), C.c_int32(_dt(X)), C.c_int32(D),
+                                  _ptr(index), _ptr(out), C.c_int32(out.stride(0)), _stream()))
+    return out

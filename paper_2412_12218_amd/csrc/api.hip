@@ -556,4 +556,57 @@ int32_t ftc_agnn_layer_backward(const ftc_csr *g, const ftc_windows *w, const in
     return launch_cos_backward_rows(n, H, ld, dtype, D, rinv, q, ldq, agg, ldq, dH, lddh, dh_dtype, hs);
 }
 
+// ---- locality reordering (preprocessing) ---------------------------------------------------------
+size_t ftc_reorder_workspace_bytes(int32_t n, int32_t nnz)
+{
+    if (n < 0 || nnz < 0) return 0;
+    return reorder_ws(n, nnz);
+}
+
+static int32_t check_reorder_ws(const char *who, int n, int nnz, void *ws, size_t ws_bytes)
+{
+    const size_t need = reorder_ws(n, nnz);
+    if (!ws || ws_bytes < need) return fail(FTC_EWORKSPACE, "%s: workspace of %zu bytes needed", who, need);
+    if (reinterpret_cast<uintptr_t>(ws) % 256 != 0) return fail(FTC_EALIGN, "%s: workspace must be 256-byte aligned", who);
+    return FTC_OK;
+}
+
+int32_t ftc_degree_order(const ftc_csr *g, int32_t mode, int32_t *perm, int32_t *inv, void *ws, size_t ws_bytes,
+                         void *stream)
+{
+    FTC_TRY(check_csr(g, "ftc_degree_order"));
+    if (mode != FTC_ORDER_DEGREE && mode != FTC_ORDER_DEGREE_CLASSES)
+        return fail(FTC_EINVAL, "ftc_degree_order: unknown mode %d", mode);
+    if (g->n == 0) return FTC_OK;
+    if (!perm || !inv) return fail(FTC_EINVAL, "ftc_degree_order: perm or inv is NULL");
+    FTC_TRY(check_reorder_ws("ftc_degree_order", g->n, g->nnz, ws, ws_bytes));
+    return launch_degree_order(*g, mode, perm, inv, ws, static_cast<hipStream_t>(stream));
+}
+
+int32_t ftc_permute_graph(const ftc_csr *g, const int32_t *perm, const int32_t *inv, int32_t *row_ptr_out,
+                          int32_t *col_idx_out, int32_t *flag, void *ws, size_t ws_bytes, void *stream)
+{
+    FTC_TRY(check_csr(g, "ftc_permute_graph"));
+    if (!flag) return fail(FTC_EINVAL, "ftc_permute_graph: flag is NULL");
+    if (!row_ptr_out) return fail(FTC_EINVAL, "ftc_permute_graph: row_ptr_out is NULL");
+    if (g->n > 0 && (!perm || !inv)) return fail(FTC_EINVAL, "ftc_permute_graph: perm or inv is NULL");
+    if (g->nnz > 0 && !col_idx_out) return fail(FTC_EINVAL, "ftc_permute_graph: col_idx_out is NULL");
+    if (row_ptr_out == g->row_ptr || (col_idx_out && col_idx_out == g->col_idx))
+        return fail(FTC_EINVAL, "ftc_permute_graph: the output aliases the input graph");
+    FTC_TRY(check_reorder_ws("ftc_permute_graph", g->n, g->nnz, ws, ws_bytes));
+    return launch_permute_graph(*g, perm, inv, row_ptr_out, col_idx_out, flag, ws, static_cast<hipStream_t>(stream));
+}
+
+int32_t ftc_permute_rows(int32_t n, const void *X, int32_t ldx, int32_t dtype, int32_t D, const int32_t *map, void *out,
+                         int32_t ldo, void *stream)
+{
+    if (n < 0) return fail(FTC_EINVAL, "ftc_permute_rows: negative n");
+    if (n == 0) return FTC_OK;
+    FTC_TRY(check_dense(X, ldx, dtype, D, "ftc_permute_rows", "X"));
+    FTC_TRY(check_dense(out, ldo, dtype, D, "ftc_permute_rows", "out"));
+    if (!map) return fail(FTC_EINVAL, "ftc_permute_rows: map is NULL");
+    if (out == X) return fail(FTC_EINVAL, "ftc_permute_rows: out aliases X");
+    return launch_permute_rows(n, X, ldx, dtype, D, map, out, ldo, static_cast<hipStream_t>(stream));
+}
+
 }  // extern "C"

@@ -86,6 +86,13 @@ size_t edge_dot_ws();
 int32_t launch_edge_dot(int nnz, const float *a, const float *b, float *out, void *ws, hipStream_t s);
 int32_t launch_cos_backward_rows(int n, const void *H, int ld, int dt, int D, const float *rinv, const float *q, int ldq,
                                  const float *base, int ldb, void *dH, int lddh, int dh_dt, hipStream_t s);
+// reorder.hip
+size_t reorder_ws(int n, int nnz);
+int32_t launch_degree_order(const ftc_csr &g, int mode, int *perm, int *inv, void *ws, hipStream_t s);
+int32_t launch_permute_graph(const ftc_csr &g, const int *perm, const int *inv, int *row_ptr_out, int *col_idx_out,
+                             int *flag, void *ws, hipStream_t s);
+int32_t launch_permute_rows(int n, const void *X, int ldx, int dt, int D, const int *map, void *out, int ldo,
+                            hipStream_t s);
 size_t build_windows_ws(int n, int nnz, int blk_h, int blk_w);
 int32_t launch_build_windows(const ftc_csr &g, ftc_windows &w, void *ws, size_t ws_bytes, hipStream_t s);
 
