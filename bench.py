@@ -226,6 +226,64 @@ def gather_probe(iters=10):
     run("cfg4 SBM col_idx", c4, g4.n, 128)
 
 
+def reorder_suite(iters=10):
+    """What the locality reordering costs and what it buys: per benchmark graph and ordering, the time
+    of ftc_degree_order + ftc_permute_graph, the share of distinct window columns (sum_uniq / nnz) and
+    the aggregation kernels before and after.  One JSON line per (graph, ordering)."""
+    import torch
+    import synth
+    from paper_2412_12218_amd import binding as B
+    dev = torch.device("cuda:0")
+
+    def ms_of(fn, reps=iters):
+        for _ in range(2):
+            fn()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        b.synchronize()
+        return a.elapsed_time(b) / reps
+
+    def kernels(dg, D, dtype):
+        win = B.ftc_build_windows(dg)
+        X = torch.randn(dg.n, D, device=dev).to(dtype)
+        X16 = torch.randn(dg.n, 16, device=dev).to(torch.float16)
+        out = torch.empty(dg.n, D, device=dev)
+        out16 = torch.empty(dg.n, 16, device=dev)
+        outh = torch.empty(dg.n, D, device=dev, dtype=dtype)
+        sc = torch.empty(dg.nnz, device=dev)
+        L = B.lib()
+        ws = B._workspace(max(L.ftc_agnn_layer_workspace_bytes(dg.n, dg.nnz, D), L.ftc_spmm_workspace_bytes(dg.n, dg.nnz, D),
+                              L.ftc_sddmm_workspace_bytes(dg.n, dg.nnz, D)), dev)
+        return {"uniq_per_nnz": int(win.summary[0].item()) / max(dg.nnz, 1),
+                "spmm_ms": ms_of(lambda: B.ftc_spmm(dg, win, None, X, out=out, ws=ws)),
+                "spmm_d16_ms": ms_of(lambda: B.ftc_spmm(dg, win, None, X16, out=out16, ws=ws)),
+                "sddmm_cos_ms": ms_of(lambda: B.ftc_sddmm(dg, win, X, X, None, None, 1.0, out=sc, ws=ws, cosine=True)),
+                "agnn_fused_ms": ms_of(lambda: B.ftc_agnn_layer(dg, win, X, out=outh, ws=ws))}
+
+    for cfg, D, dtype in ((5, 32, torch.float16), (4, 64, torch.bfloat16), (3, 32, torch.float16), (2, 32, torch.float16)):
+        g = synth.config_graph(cfg)
+        dg = B.Graph.from_numpy(g.row_ptr, g.col_idx)
+        base = kernels(dg, D, dtype)
+        print(json.dumps({"graph": f"cfg{cfg}", "n": g.n, "nnz": g.nnz, "D": D, "ordering": "as given", **base}), flush=True)
+        ws = B._workspace(B.lib().ftc_reorder_workspace_bytes(g.n, g.nnz), dev)
+        for mode, tag in ((B.FTC_ORDER_DEGREE, "degree"), (B.FTC_ORDER_DEGREE_CLASSES, "degree classes")):
+            t_order = ms_of(lambda: B.ftc_degree_order(dg, mode, ws=ws), 5)
+            perm, inv = B.ftc_degree_order(dg, mode, ws=ws)
+            t_graph = ms_of(lambda: B.ftc_permute_graph(dg, perm, inv, ws=ws), 5)
+            pg, flag = B.ftc_permute_graph(dg, perm, inv, ws=ws)
+            assert int(flag.item()) == 0
+            Xf = torch.randn(g.n, D, device=dev).to(dtype)
+            t_rows = ms_of(lambda: B.ftc_permute_rows(Xf, perm))
+            r = kernels(pg, D, dtype)
+            print(json.dumps({"graph": f"cfg{cfg}", "ordering": tag, "degree_order_ms": t_order, "permute_graph_ms": t_graph,
+                              "permute_rows_ms": t_rows, **r}), flush=True)
+            del pg, perm, inv
+        del dg, ws
+
+
 def train_suite(scale, iters=10):
     """Forward + backward of the two benchmark models on the benchmark graph (TrainPath): per-call
     times from events on the launch stream.  Prints one JSON line of its own; the benchmark metric
@@ -288,6 +346,8 @@ def main():
     ap.add_argument("--no-kernels", action="store_true", help="skip the stand-alone SpMM/SDDMM section")
     ap.add_argument("--probe", action="store_true",
                     help="instead of the benchmark: the bare gather rate of the GPU on the benchmark graphs' indices")
+    ap.add_argument("--reorder", action="store_true",
+                    help="instead of the benchmark: cost and effect of the locality reordering on the benchmark graphs")
     ap.add_argument("--train", action="store_true",
                     help="instead of the benchmark: forward + backward times of the two models on the benchmark graph")
     ap.add_argument("--sweep", action="store_true",
@@ -313,6 +373,9 @@ def main():
         return
     if args.train:
         train_suite(args.scale)
+        return
+    if args.reorder:
+        reorder_suite()
         return
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)

@@ -173,3 +173,105 @@ def test_cfg5_models_layer_by_layer(oracle, threads):
     e = norm_err(out, ref, ab)
     say(f"  agnn out-projection err {e:.3e}; chained end-to-end err {norm_err(chained, ref, ab):.3e}")
     assert e < 2e-3
+
+
+def test_cfg5_reorder_full():
+    """Degree order and relabelled CSR of the R-MAT workload, every entry, against the oracle."""
+    from oracle import ftc_oracle_reorder as OR
+    g = synth.config_graph(5)
+    dg = dev_graph(g)
+    for mode in (B.FTC_ORDER_DEGREE, B.FTC_ORDER_DEGREE_CLASSES):
+        say(f"cfg5 reorder mode {mode}")
+        perm_ref, inv_ref = OR.degree_order(g.row_ptr, mode)
+        perm, inv = B.ftc_degree_order(dg, mode)
+        assert np.array_equal(perm.cpu().numpy(), perm_ref)
+        assert np.array_equal(inv.cpu().numpy(), inv_ref)
+        pg, flag = B.ftc_permute_graph(dg, perm, inv)
+        assert int(flag.item()) == 0
+        rp_ref, ci_ref = OR.permute_graph(g.row_ptr, g.col_idx, perm_ref, inv_ref)
+        assert np.array_equal(pg.row_ptr.cpu().numpy(), rp_ref)
+        assert np.array_equal(pg.col_idx.cpu().numpy(), ci_ref)
+        del pg, rp_ref, ci_ref
+
+
+def test_cfg5_quarter_backward_every_element(oracle, threads):
+    """Backward of a GCN layer and an AGNN layer on the R-MAT recipe at a quarter of the benchmark
+    size (262 144 nodes, 8 M entries, hub rows of tens of thousands of entries): every gradient
+    element against the numpy backward oracle, which needs minutes and gigabytes beyond that size."""
+    from oracle import ftc_oracle_backward as OB
+    from test_gpu_backward import arr_err, row_err
+    g = synth.config_graph(5, 0.25)
+    say(f"cfg5/4 n={g.n} nnz={g.nnz}")
+    dg = dev_graph(g)
+    win = B.ftc_build_windows(dg)
+    dinv32, fvals64 = factored_vals(g, oracle)
+    dinv = torch.from_numpy(dinv32).cuda()
+    Xd, X64 = quantise(synth.normal_features(g.n, 32, 5), F16)
+    Wd, W64 = quantise(synth.glorot_uniform(32, 16, 6), F16)
+    dY32 = synth.normal_features(g.n, 16, 7).astype(np.float32)
+    Y = B.ftc_gcn_layer(dg, win, None, Xd, Wd, relu=True, dinv=dinv)
+    dX, dW = B.ftc_gcn_layer_backward(dg, win, None, Xd, Wd, torch.from_numpy(dY32).cuda(), Y=Y, dinv=dinv)
+    dX_ref, dW_ref, _ = OB.gcn_layer_backward(g.row_ptr, g.col_idx, fvals64, X64, W64, dY32.astype(np.float64),
+                                              Y.cpu().double().numpy())
+    ex, ew = row_err(dX, dX_ref), arr_err(dW, dW_ref)
+    say(f"  gcn backward dX err {ex:.3e} dW err {ew:.3e}")
+    assert ex < 1e-5 and ew < 1e-5
+    del dX_ref, dX
+    Hd, H64 = quantise(synth.normal_features(g.n, 32, 8), F16)
+    dYd, dY64 = quantise(synth.normal_features(g.n, 32, 9), F16)
+    T, flag = B.ftc_transpose_index(dg, win)
+    assert int(flag.item()) == 0
+    p = torch.empty(g.nnz, dtype=F32, device="cuda")
+    B.ftc_agnn_layer(dg, win, Hd, beta=1.0, edge_p=p)
+    dH, dbeta = B.ftc_agnn_layer_backward(dg, win, T, Hd, p, dYd, beta=1.0)
+    dH_ref, dbeta_ref = OB.agnn_layer_backward(g.row_ptr, g.col_idx, H64, 1.0, dY64)
+    eh = row_err(dH, dH_ref)
+    say(f"  agnn backward dH err {eh:.3e} dbeta {float(dbeta.item()):.6g} ref {dbeta_ref:.6g}")
+    assert eh < 1e-5
+    assert abs(float(dbeta.item()) - dbeta_ref) < 1e-4 * max(abs(dbeta_ref), 1.0)
+
+
+def test_cfg5_backward_identities_full():
+    """Backward pass at the full benchmark size, in the buffers bench.py --train times (TrainPath),
+    checked through identities that hold at any size.  Both models are positively homogeneous of
+    degree one in their parameters / inputs (ReLU and the cosine softmax included), so by Euler's
+    theorem <dL/dW, W> = <dL/dX, X> = L for the loss L = <dOut, out> of a GCN layer and
+    <dL/dH, H> = L for an AGNN layer; dL/dbeta is compared with a central difference of the GPU
+    forward pass (itself checked against the oracle at this size above)."""
+    from paper_2412_12218_amd.models import TrainPath
+    seed = synth.CONFIGS[5]["seed"]
+    g = synth.config_graph(5)
+    dg = dev_graph(g)
+    win = B.ftc_build_windows(dg)
+    _, dinv = B.ftc_gcn_norm(dg, win, want_vals=False)
+    tp = TrainPath(dg, win, dinv)
+    dev = dinv.device
+    h16 = lambda a: torch.from_numpy(a).to(F16).to(dev)
+    X = h16(synth.normal_features(g.n, 128, seed + 10))
+    W1, W2 = h16(synth.glorot_uniform(128, 16, seed + 11)), h16(synth.glorot_uniform(16, 8, seed + 12))
+    d_out = torch.from_numpy(synth.normal_features(g.n, 8, seed + 21)).to(dev)
+    out = tp.gcn_forward(X, W1, W2)
+    L = float((out.double() * d_out.double()).sum())
+    dW1, dW2 = tp.gcn_backward(X, W1, W2, d_out)
+    scale = float((out.double().abs() * d_out.double().abs()).sum())
+    l1, l2 = float((dW1.double() * W1.double()).sum()), float((dW2.double() * W2.double()).sum())
+    say(f"  gcn: L {L:.6g} <dW1,W1> {l1:.6g} <dW2,W2> {l2:.6g} (sum of |terms| {scale:.3g})")
+    # the hidden activations are rounded to fp16 between the layers: 2^-11 relative per element
+    assert abs(l1 - L) < 2e-3 * scale and abs(l2 - L) < 2e-3 * scale
+    H0 = h16(synth.normal_features(g.n, 32, seed + 20))
+    d_agnn = h16(synth.normal_features(g.n, 32, seed + 22))
+    betas = [1.0]
+    tp1 = TrainPath(dg, win, dinv, agnn_layers=1)
+    Y = tp1.agnn_forward(H0, betas)
+    L = float((Y.double() * d_agnn.double()).sum())
+    scale = float((Y.double().abs() * d_agnn.double().abs()).sum())
+    dH, dbeta = tp1.agnn_backward(betas, d_agnn)
+    lh = float((dH.double() * H0.double()).sum())
+    say(f"  agnn: L {L:.6g} <dH,H> {lh:.6g} (sum of |terms| {scale:.3g})")
+    assert abs(lh - L) < 2e-3 * scale
+    eps = 1e-2
+    Yp = B.ftc_agnn_layer(dg, win, H0, beta=1.0 + eps)
+    Ym = B.ftc_agnn_layer(dg, win, H0, beta=1.0 - eps)
+    fd = float(((Yp.double() - Ym.double()) * d_agnn.double()).sum()) / (2 * eps)
+    say(f"  agnn: dbeta {float(dbeta[0]):.6g} central difference {fd:.6g}")
+    assert abs(float(dbeta[0]) - fd) < 2e-2 * max(abs(fd), 1e-3 * scale)
