@@ -329,7 +329,7 @@ def train_suite(scale, iters=10):
             times["transpose_index"] = keep
         timed("gcn_forward_2layers", lambda: tp.gcn_forward(X, W1, W2))
         timed("gcn_backward_2layers", lambda: tp.gcn_backward(X, W1, W2, d_gcn))
-        timed("agnn_forward_4layers_keeping_p", lambda: tp.agnn_forward(H0, betas))
+        timed("agnn_forward_4layers_keeping_row_z_and_fp32_output", lambda: tp.agnn_forward(H0, betas))
         timed("agnn_backward_4layers", lambda: tp.agnn_backward(betas, d_agnn))
     print(json.dumps({"workload": f"cfg5 R-MAT scale {scale}: N={g.n}, nnz={g.nnz}, fp16 activations, fp32 gradients "
                                   "of weights, GCN 128-16-8, AGNN 32 x 4 layers",

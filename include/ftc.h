@@ -208,12 +208,19 @@ int32_t ftc_gcn_layer(const ftc_csr *g, const ftc_windows *w, const float *vals,
  * receives P (nnz floats).  Without edge_p (and with a window index) scores, softmax and
  * aggregation run fused in one pass over the edges; the softmax is then shifted by |beta|,
  * an upper bound of every score, instead of by the row maximum (same result; |beta| < 43).
+ * row_z, when not NULL, receives the softmax denominators of that pass,
+ * z_i = sum over row i of exp(beta * cos - |beta|) (n floats, 0 for a row without entries): what
+ * ftc_agnn_layer_backward_fused needs instead of P.  out_f32, when not NULL, receives the result
+ * once more, unrounded (n x D fp32, leading dimension ld_f32, a multiple of 4; rows 16-byte
+ * aligned): the backward pass takes <dY_i, out_i> from it when `out` itself is 16-bit.  Only the
+ * fused pass produces these two (FTC_EUNSUPPORTED together with edge_p, without a window index or
+ * for shapes it does not cover).
  */
 size_t ftc_agnn_layer_workspace_bytes(int32_t n, int32_t nnz, int32_t D);
 int32_t ftc_agnn_layer(const ftc_csr *g, const ftc_windows *w, const void *H, int32_t ld,
                        int32_t dtype, int32_t D, float beta, void *out, int32_t ldo,
-                       int32_t out_dtype, float *edge_p, int32_t path, void *ws,
-                       size_t ws_bytes, void *stream);
+                       int32_t out_dtype, float *edge_p, float *row_z, float *out_f32,
+                       int32_t ld_f32, int32_t path, void *ws, size_t ws_bytes, void *stream);
 
 /*
  * ---- Backward pass ----------------------------------------------------------------------------
@@ -244,7 +251,7 @@ int32_t ftc_edge_softmax_backward(const ftc_csr *g, const ftc_windows *w, const 
 /*
  * Weight gradient of the update phase: dW = X^T * G, X n x d_in (x_dtype), G n x d_out (fp32),
  * dW d_in x d_out row-major (fp32).  Limits: ceil(d_in / 4) * ceil(d_out / 4) <= 1024 and
- * d_in + d_out <= 1016 (FTC_EUNSUPPORTED beyond).  Partial sums of row blocks are added in a fixed
+ * d_in + d_out <= 506 (FTC_EUNSUPPORTED beyond).  Partial sums of row blocks are added in a fixed
  * order (reproducible).
  */
 size_t ftc_weight_grad_workspace_bytes(int32_t n, int32_t d_in, int32_t d_out);
@@ -286,6 +293,26 @@ int32_t ftc_agnn_layer_backward(const ftc_csr *g, const ftc_windows *w, const in
                                 const float *p, const void *dY, int32_t lddy, void *dH,
                                 int32_t lddh, int32_t dh_dtype, float *dbeta, int32_t path,
                                 void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * The same gradients in one pass over the entries, for a symmetric pattern: every entry gathers
+ * h_j and dY_j once and the per-node pair (1 / z_j, <dY_j, Y_j>); no edge array (probabilities,
+ * transposed index) is read or written.  row_z are the denominators of the forward pass (row_z of
+ * ftc_agnn_layer with the same H and beta), Y its output (n x D, any dtype; it enters through
+ * <dY_i, Y_i> = sum over row i of p * dp, so a 16-bit Y costs accuracy -- a few 1e-3 of a row's
+ * largest gradient entry with bf16 -- and out_f32 of the forward call is the better choice).
+ * H and dY share dtype and leading dimension, rows 16-byte aligned; the window index is required;
+ * D up to 128 (fp32: 64 when D is not a multiple of 4).  FTC_EUNSUPPORTED otherwise: use
+ * ftc_agnn_layer_backward.  The pattern is taken to be symmetric (ftc_transpose_index, flag 0,
+ * checks it); on another pattern the result is the gradient of nothing.
+ */
+size_t ftc_agnn_layer_backward_fused_workspace_bytes(int32_t n, int32_t nnz, int32_t D);
+int32_t ftc_agnn_layer_backward_fused(const ftc_csr *g, const ftc_windows *w, const void *H,
+                                      int32_t ld, int32_t dtype, int32_t D, float beta,
+                                      const float *row_z, const void *Y, int32_t ldy,
+                                      int32_t y_dtype, const void *dY, int32_t lddy, void *dH,
+                                      int32_t lddh, int32_t dh_dtype, float *dbeta, void *ws,
+                                      size_t ws_bytes, void *stream);
 
 /*
  * ---- Locality reordering (preprocessing) ------------------------------------------------------

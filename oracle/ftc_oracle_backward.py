@@ -56,6 +56,21 @@ def edge_softmax_backward(row_ptr, p, dp):
     return p * (dp - rowsum[rows])
 
 
+def agnn_row_z(row_ptr, col_idx, H, beta):
+    """z_i = sum over row i of exp(beta * c_e - |beta|): the softmax denominators in the form the
+    single-pass forward keeps them for the backward pass (|c| <= 1, so |beta| bounds every score).
+    0 for a row without entries."""
+    row_ptr = np.asarray(row_ptr, dtype=np.int64)
+    col = np.asarray(col_idx, dtype=np.int64)
+    rows = _rows(row_ptr)
+    H = np.asarray(H, dtype=np.float64)
+    Hn = H / np.maximum(np.sqrt((H * H).sum(axis=1)), 1e-12)[:, None]
+    c = (Hn[rows] * Hn[col]).sum(axis=1)
+    z = np.zeros(H.shape[0])
+    np.add.at(z, rows, np.exp(beta * c - abs(beta)))
+    return z
+
+
 def agnn_layer_backward(row_ptr, col_idx, H, beta, dY):
     """Forward: hn_i = h_i / max(|h_i|, 1e-12), c_e = <hn_i, hn_j>, p = row softmax of beta * c,
     y_i = sum_e p_e h_j.  Returns (dH [n, D], dbeta) for a loss with dL/dY = dY."""

@@ -42,7 +42,7 @@ _SIGNATURES = {
     "ftc_gcn_layer_workspace_bytes": (_Z, [_I, _I, _I, _I]),
     "ftc_gcn_layer": (_I, [_P, _P, _P, _P, _P, _I, _I, _I, _P, _I, _I, _P, _I, _I, _I, _P, _Z, _P]),
     "ftc_agnn_layer_workspace_bytes": (_Z, [_I, _I, _I]),
-    "ftc_agnn_layer": (_I, [_P, _P, _P, _I, _I, _I, _F, _P, _I, _I, _P, _I, _P, _Z, _P]),
+    "ftc_agnn_layer": (_I, [_P, _P, _P, _I, _I, _I, _F, _P, _I, _I, _P, _P, _P, _I, _I, _P, _Z, _P]),
     "ftc_transpose_index": (_I, [_P, _P, _P, _P, _P]),
     "ftc_edge_softmax_backward": (_I, [_P, _P, _P, _P, _P, _P, _Z, _P]),
     "ftc_weight_grad_workspace_bytes": (_Z, [_I, _I, _I]),
@@ -52,6 +52,8 @@ _SIGNATURES = {
                                     _Z, _P]),
     "ftc_agnn_layer_backward_workspace_bytes": (_Z, [_I, _I, _I]),
     "ftc_agnn_layer_backward": (_I, [_P, _P, _P, _P, _I, _I, _I, _F, _P, _P, _I, _P, _I, _I, _P, _I, _P, _Z, _P]),
+    "ftc_agnn_layer_backward_fused_workspace_bytes": (_Z, [_I, _I, _I]),
+    "ftc_agnn_layer_backward_fused": (_I, [_P, _P, _P, _I, _I, _I, _F, _P, _P, _I, _I, _P, _I, _P, _I, _I, _P, _P, _Z, _P]),
     "ftc_reorder_workspace_bytes": (_Z, [_I, _I]),
     "ftc_degree_order": (_I, [_P, _I, _P, _P, _P, _Z, _P]),
     "ftc_permute_graph": (_I, [_P, _P, _P, _P, _P, _P, _P, _Z, _P]),
@@ -264,7 +266,7 @@ def ftc_gcn_layer(g, w, vals, X, W, relu=False, out=None, out_dtype=torch.float3
 
 
 def ftc_agnn_layer(g, w, H, beta=1.0, out=None, out_dtype=torch.float32, edge_p=None, path=FTC_PATH_AUTO,
-                   ws=None):
+                   ws=None, row_z=None, out_f32=None):
     n, D = H.shape
     if out is None:
         out = torch.empty((n, D), dtype=out_dtype, device=H.device)
@@ -272,7 +274,8 @@ def ftc_agnn_layer(g, w, H, beta=1.0, out=None, out_dtype=torch.float32, edge_p=
         ws = _workspace(lib().ftc_agnn_layer_workspace_bytes(g.n, g.nnz, D), H.device)
     _check(lib().ftc_agnn_layer(C.byref(g.c), _wref(w), _ptr(H), C.c_int32(H.stride(0)), C.c_int32(_dt(H)),
                                 C.c_int32(D), C.c_float(beta), _ptr(out), C.c_int32(out.stride(0)),
-                                C.c_int32(_dt(out)), _ptr(edge_p), C.c_int32(path), _ptr(ws),
+                                C.c_int32(_dt(out)), _ptr(edge_p), _ptr(row_z), _ptr(out_f32),
+                                C.c_int32(out_f32.stride(0) if out_f32 is not None else 0), C.c_int32(path), _ptr(ws),
                                 C.c_size_t(ws.numel()), _stream()))
     return out
 
@@ -344,6 +347,22 @@ def ftc_agnn_layer_backward(g, w, T, H, p, dY, beta=1.0, dH=None, dh_dtype=torch
         C.byref(g.c), _wref(w), _ptr(T), _ptr(H), C.c_int32(H.stride(0)), C.c_int32(_dt(H)), C.c_int32(D),
         C.c_float(beta), _ptr(p), _ptr(dY), C.c_int32(dY.stride(0)), _ptr(dH), C.c_int32(dH.stride(0)),
         C.c_int32(_dt(dH)), _ptr(dbeta), C.c_int32(path), _ptr(ws), C.c_size_t(ws.numel()), _stream()))
+    return dH, dbeta
+
+
+def ftc_agnn_layer_backward_fused(g, w, H, row_z, Y, dY, beta=1.0, dH=None, dh_dtype=torch.float32, dbeta=None, ws=None):
+    n, D = H.shape
+    assert dY.dtype == H.dtype and dY.shape == H.shape and dY.stride(0) == H.stride(0) and Y.shape == H.shape
+    if dH is None:
+        dH = torch.empty((n, D), dtype=dh_dtype, device=H.device)
+    if dbeta is None:
+        dbeta = torch.empty(1, dtype=torch.float32, device=H.device)
+    if ws is None:
+        ws = _workspace(lib().ftc_agnn_layer_backward_fused_workspace_bytes(g.n, g.nnz, D), H.device)
+    _check(lib().ftc_agnn_layer_backward_fused(
+        C.byref(g.c), _wref(w), _ptr(H), C.c_int32(H.stride(0)), C.c_int32(_dt(H)), C.c_int32(D), C.c_float(beta),
+        _ptr(row_z), _ptr(Y), C.c_int32(Y.stride(0)), C.c_int32(_dt(Y)), _ptr(dY), C.c_int32(dY.stride(0)), _ptr(dH),
+        C.c_int32(dH.stride(0)), C.c_int32(_dt(dH)), _ptr(dbeta), _ptr(ws), C.c_size_t(ws.numel()), _stream()))
     return dH, dbeta
 
 

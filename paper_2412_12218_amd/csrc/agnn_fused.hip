@@ -22,28 +22,10 @@
 
 namespace ftc {
 
-constexpr int AG_R = 512;  // edges per wave
+constexpr int AG_R = SEG_R;  // edges per wave
 constexpr int AG_B = 4;    // edges per batch
 
 bool seg_shape(int dtype, int D, int *vec, int *lpr);
-
-template <int CTRL>
-__device__ __forceinline__ float ag_dpp_add(float v)
-{
-    const int moved = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false);
-    return v + __int_as_float(moved);
-}
-
-template <int LPR>
-__device__ __forceinline__ float ag_group_sum(float v)
-{
-    if constexpr (LPR >= 32) v += __shfl_xor(v, 16, 64);
-    if constexpr (LPR >= 16) v = ag_dpp_add<0x140>(v);  // row_mirror
-    if constexpr (LPR >= 8) v = ag_dpp_add<0x141>(v);   // row_half_mirror
-    if constexpr (LPR >= 4) v = ag_dpp_add<0x4e>(v);    // quad_perm [2,3,0,1]
-    if constexpr (LPR >= 2) v = ag_dpp_add<0xb1>(v);    // quad_perm [1,0,3,2]
-    return v;
-}
 
 size_t agnn_fused_ws(int nnz, int D)
 {
@@ -60,7 +42,9 @@ __global__ __launch_bounds__(256) void agnn_fused_kernel(int nnz, int n_ranges, 
                                                          const int *__restrict__ edge_to_row,
                                                          const void *__restrict__ H, int ld, int D, float beta,
                                                          void *__restrict__ out, int ldo, int odt,
-                                                         float *__restrict__ carry, int *__restrict__ carry_tail_row)
+                                                         float *__restrict__ carry, int *__restrict__ carry_tail_row,
+                                                         float *__restrict__ row_z, float *__restrict__ out32,
+                                                         int ld32)
 {
     constexpr int NG = 64 / LPR;
     constexpr int RUN = AG_R / NG;
@@ -120,7 +104,9 @@ __global__ __launch_bounds__(256) void agnn_fused_kernel(int nnz, int n_ranges, 
 #pragma unroll
             for (int j = 0; j < VEC; ++j) o[j] = acc[j] * inv;
             store_vec<VEC>(out, static_cast<int64_t>(row) * ldo + sub * VEC, odt, o);
+            if (out32) store_vec<VEC>(out32, static_cast<int64_t>(row) * ld32 + sub * VEC, FTC_F32, o);  // unrounded copy
         }
+        if (row_z && sub == 0) row_z[row] = z;  // softmax denominator (shifted by |beta|), kept for the backward pass
     };
 
     // every group runs the same number of batches: the lane shuffles of the dot product need the
@@ -170,11 +156,11 @@ __global__ __launch_bounds__(256) void agnn_fused_kernel(int nnz, int n_ranges, 
                 for (int j = 0; j < VEC; ++j) acc[j] = 0.f;
                 z = 0.f;
                 xi = xs[k];
-                const float q = ag_group_sum<LPR>(dot_raw<T, VEC>(xi, xi, 0.f));  // the group's lanes branch together
+                const float q = group_sum_dpp<LPR>(dot_raw<T, VEC>(xi, xi, 0.f));  // the group's lanes branch together
                 ri = __frsqrt_rn(fmaxf(q, 1e-24f));  // = 1 / max(||h_i||, 1e-12)
             }
-            const float d = ag_group_sum<LPR>(dot_raw<T, VEC>(xi, y[k], 0.f));
-            const float qj = ag_group_sum<LPR>(dot_raw<T, VEC>(y[k], y[k], 0.f));
+            const float d = group_sum_dpp<LPR>(dot_raw<T, VEC>(xi, y[k], 0.f));
+            const float qj = group_sum_dpp<LPR>(dot_raw<T, VEC>(y[k], y[k], 0.f));
             if (r[k] >= 0) {
                 const float rj = __frsqrt_rn(fmaxf(qj, 1e-24f));
                 const float wgt = __expf(beta * ri * rj * d - absb);
@@ -240,8 +226,10 @@ __global__ __launch_bounds__(256) void agnn_fused_kernel(int nnz, int n_ranges, 
                         if (from_outside) {
                             cv[d] = run;
                             if (d == 0) cv[DP] = run_z;
-                        } else if (d < D) {
-                            store_elem(out, static_cast<int64_t>(run_row) * ldo + d, odt, run / run_z);
+                        } else {
+                            if (d < D) store_elem(out, static_cast<int64_t>(run_row) * ldo + d, odt, run / run_z);
+                            if (out32 && d < D) out32[static_cast<int64_t>(run_row) * ld32 + d] = run / run_z;
+                            if (row_z && d == 0) row_z[run_row] = run_z;
                         }
                         run_row = -1;
                         from_outside = false;
@@ -276,7 +264,9 @@ __global__ __launch_bounds__(256) void agnn_fused_kernel(int nnz, int n_ranges, 
 __global__ __launch_bounds__(256) void agnn_fused_fixup_kernel(int n, int n_ranges, const int *__restrict__ row_ptr,
                                                                const float *__restrict__ carry,
                                                                const int *__restrict__ carry_tail_row, int DP,
-                                                               int D, void *__restrict__ out, int ldo, int odt)
+                                                               int D, void *__restrict__ out, int ldo, int odt,
+                                                               float *__restrict__ row_z, float *__restrict__ out32,
+                                                               int ld32)
 {
     const int DPZ = DP + 4;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -304,7 +294,9 @@ __global__ __launch_bounds__(256) void agnn_fused_fixup_kernel(int n, int n_rang
             for (int i = 0; i < 4; ++i) {
                 const int d = i * 64 + lane;
                 if (d < D) store_elem(out, static_cast<int64_t>(r) * ldo + d, odt, spec[i] / spec_z);
+                if (out32 && d < D) out32[static_cast<int64_t>(r) * ld32 + d] = spec[i] / spec_z;
             }
+            if (row_z && lane == 0) row_z[r] = spec_z;
         } else if (r >= 0) {
             const int last = (row_ptr[r + 1] - 1) / AG_R;
             // teams of `dl` lanes (one lane per feature) share the ranges of a long row round-robin,
@@ -328,6 +320,7 @@ __global__ __launch_bounds__(256) void agnn_fused_fixup_kernel(int n, int n_rang
                 zsum = (z0 + z1) + (z2 + z3);
                 for (int off = 32; off >= dl; off >>= 1) zsum += __shfl_down(zsum, off, 64);
                 zsum = __shfl(zsum, 0, 64) + carry[(static_cast<size_t>(v) * 2 + 1) * DPZ + DP];
+                if (row_z && lane == 0) row_z[r] = zsum;
             }
             for (int d0 = 0; d0 < D; d0 += 64) {
                 const int d = d0 + lane % dl;
@@ -348,24 +341,29 @@ __global__ __launch_bounds__(256) void agnn_fused_fixup_kernel(int n, int n_rang
                 if (lane < dl && dok) {
                     sum += carry[(static_cast<size_t>(v) * 2 + 1) * DPZ + d];
                     store_elem(out, static_cast<int64_t>(r) * ldo + d, odt, sum / zsum);
+                    if (out32) out32[static_cast<int64_t>(r) * ld32 + d] = sum / zsum;
                 }
             }
         }
     }
     const int64_t row = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
-    if (row < n && row_ptr[row] == row_ptr[row + 1])
+    if (row < n && row_ptr[row] == row_ptr[row + 1]) {
         for (int d = 0; d < D; ++d) store_elem(out, row * ldo + d, odt, 0.f);
+        if (out32)
+            for (int d = 0; d < D; ++d) out32[row * ld32 + d] = 0.f;
+        if (row_z) row_z[row] = 0.f;
+    }
 }
 
 template <class T>
 static void launch_agnn_t(int vec, int lpr, unsigned grid, hipStream_t s, int nnz, int n_ranges, const ftc_csr &g,
                           const int *e2r, const void *H, int ld, int D, float beta, void *out,
-                          int ldo, int odt, float *carry, int *tail_row)
+                          int ldo, int odt, float *carry, int *tail_row, float *row_z, float *out32, int ld32)
 {
     constexpr int VM = T::VEC;
 #define FTC_AG(V, L)                                                                                        \
     hipLaunchKernelGGL((agnn_fused_kernel<T, V, L>), dim3(grid), dim3(256), 0, s, nnz, n_ranges, g.col_idx, \
-                       e2r, H, ld, D, beta, out, ldo, odt, carry, tail_row)
+                       e2r, H, ld, D, beta, out, ldo, odt, carry, tail_row, row_z, out32, ld32)
     if (vec == VM) {
         if (lpr == 4) FTC_AG(VM, 4);
         else if (lpr == 8) FTC_AG(VM, 8);
@@ -382,7 +380,8 @@ static void launch_agnn_t(int vec, int lpr, unsigned grid, hipStream_t s, int nn
 // Caller has checked: window index present, seg_shape() accepts (dt, D), rows of H and out 16-byte
 // aligned, workspace of agnn_fused_ws() bytes.
 int32_t launch_agnn_fused(const ftc_csr &g, const ftc_windows &w, const void *H, int ld, int dt, int D,
-                          float beta, void *out, int ldo, int odt, void *ws, hipStream_t s)
+                          float beta, void *out, int ldo, int odt, float *row_z, float *out32, int ld32, void *ws,
+                          hipStream_t s)
 {
     int vec = 0, lpr = 0;
     seg_shape(dt, D, &vec, &lpr);
@@ -395,13 +394,13 @@ int32_t launch_agnn_fused(const ftc_csr &g, const ftc_windows &w, const void *H,
         const unsigned grid = static_cast<unsigned>((n_ranges + 3) / 4);
         if (dt == FTC_F32)
             launch_agnn_t<F32>(vec, lpr, grid, s, g.nnz, n_ranges, g, w.edge_to_row, H, ld, D, beta, out, ldo,
-                               odt, carry, tail_row);
+                               odt, carry, tail_row, row_z, out32, ld32);
         else if (dt == FTC_F16)
             launch_agnn_t<F16>(vec, lpr, grid, s, g.nnz, n_ranges, g, w.edge_to_row, H, ld, D, beta, out, ldo,
-                               odt, carry, tail_row);
+                               odt, carry, tail_row, row_z, out32, ld32);
         else
             launch_agnn_t<BF16>(vec, lpr, grid, s, g.nnz, n_ranges, g, w.edge_to_row, H, ld, D, beta, out, ldo,
-                                odt, carry, tail_row);
+                                odt, carry, tail_row, row_z, out32, ld32);
         const int32_t st = launch_status("agnn_fused");
         if (st != FTC_OK) return st;
     }
@@ -409,7 +408,7 @@ int32_t launch_agnn_fused(const ftc_csr &g, const ftc_windows &w, const void *H,
     const int64_t blocks_ranges = (n_ranges + 3) / 4;
     const unsigned grid2 = static_cast<unsigned>(blocks_rows > blocks_ranges ? blocks_rows : blocks_ranges);
     hipLaunchKernelGGL(agnn_fused_fixup_kernel, dim3(grid2), dim3(256), 0, s, g.n, n_ranges, g.row_ptr, carry,
-                       tail_row, dp, D, out, ldo, odt);
+                       tail_row, dp, D, out, ldo, odt, row_z, out32, ld32);
     return launch_status("agnn_fused fixup");
 }
 

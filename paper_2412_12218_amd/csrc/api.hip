@@ -357,8 +357,8 @@ size_t ftc_agnn_layer_workspace_bytes(int32_t n, int32_t nnz, int32_t D)
 }
 
 int32_t ftc_agnn_layer(const ftc_csr *g, const ftc_windows *w, const void *H, int32_t ld, int32_t dtype,
-                       int32_t D, float beta, void *out, int32_t ldo, int32_t out_dtype, float *edge_p,
-                       int32_t path, void *ws, size_t ws_bytes, void *stream)
+                       int32_t D, float beta, void *out, int32_t ldo, int32_t out_dtype, float *edge_p, float *row_z,
+                       float *out_f32, int32_t ld_f32, int32_t path, void *ws, size_t ws_bytes, void *stream)
 {
     FTC_TRY(check_csr(g, "ftc_agnn_layer"));
     if (g->n == 0) return FTC_OK;
@@ -377,9 +377,21 @@ int32_t ftc_agnn_layer(const ftc_csr *g, const ftc_windows *w, const void *H, in
     int vec, lpr;
     const bool rows16 = aligned16(H) && aligned16(out) && (static_cast<int64_t>(ld) * elem_size(dtype)) % 16 == 0 &&
                         (static_cast<int64_t>(ldo) * elem_size(out_dtype)) % 16 == 0;
-    if (!edge_p && w && g->nnz > 0 && path != FTC_PATH_MFMA && rows16 && seg_shape(dtype, D, &vec, &lpr))
-        return launch_agnn_fused(*g, *w, H, ld, dtype, D, beta, out, ldo, out_dtype, p,
+    if (out_f32) {
+        FTC_TRY(check_dense(out_f32, ld_f32, FTC_F32, D, "ftc_agnn_layer", "out_f32"));
+        if (!aligned16(out_f32) || ld_f32 % 4 != 0)
+            return fail(FTC_EALIGN, "ftc_agnn_layer: rows of out_f32 must be 16-byte aligned");
+        if (static_cast<void *>(out_f32) == out || static_cast<const void *>(out_f32) == H)
+            return fail(FTC_EINVAL, "ftc_agnn_layer: out_f32 aliases out or H");
+    }
+    const bool keep = row_z || out_f32;
+    if (!edge_p && w && (g->nnz > 0 || keep) && path != FTC_PATH_MFMA && rows16 && seg_shape(dtype, D, &vec, &lpr))
+        return launch_agnn_fused(*g, *w, H, ld, dtype, D, beta, out, ldo, out_dtype, row_z, out_f32, ld_f32, p,
                                  static_cast<hipStream_t>(stream));
+    if (keep)
+        return fail(FTC_EUNSUPPORTED,
+                    "ftc_agnn_layer: row_z and out_f32 come from the single-pass route only (window index, no edge_p, not "
+                    "FTC_PATH_MFMA, 16-byte aligned rows, a width the edge-balanced kernels cover)");
 
     float *scores = edge_p ? edge_p : reinterpret_cast<float *>(p);
     p += align_up(static_cast<size_t>(g->nnz) * sizeof(float), 256);
@@ -443,7 +455,7 @@ int32_t ftc_weight_grad(int32_t n, const void *X, int32_t ldx, int32_t x_dtype, 
     FTC_TRY(check_dense(G, ldg, FTC_F32, d_out, "ftc_weight_grad", "G"));
     if (!dW) return fail(FTC_EINVAL, "ftc_weight_grad: dW is NULL");
     if (!weight_grad_shape_ok(d_in, d_out))
-        return fail(FTC_EUNSUPPORTED, "ftc_weight_grad: need ceil(d_in / 4) * ceil(d_out / 4) <= 1024 and d_in + d_out <= 1016");
+        return fail(FTC_EUNSUPPORTED, "ftc_weight_grad: need ceil(d_in / 4) * ceil(d_out / 4) <= 1024 and d_in + d_out <= 506");
     const size_t need = weight_grad_ws(n, d_in, d_out);
     if (!ws || ws_bytes < need) return fail(FTC_EWORKSPACE, "ftc_weight_grad: workspace of %zu bytes needed", need);
     return launch_weight_grad(n, X, ldx, x_dtype, d_in, G, ldg, d_out, dW, ws, static_cast<hipStream_t>(stream));
@@ -471,7 +483,7 @@ int32_t ftc_gcn_layer_backward(const ftc_csr *gT, const ftc_windows *wT, const f
     if (dX) FTC_TRY(check_dense(dX, lddx, FTC_F32, d_in, "ftc_gcn_layer_backward", "dX"));
     if (!W || !dW) return fail(FTC_EINVAL, "ftc_gcn_layer_backward: W or dW is NULL");
     if (d_out > 64 || !weight_grad_shape_ok(d_in, d_out))
-        return fail(FTC_EUNSUPPORTED, "ftc_gcn_layer_backward: need d_out <= 64, ceil(d_in / 4) * ceil(d_out / 4) <= 1024 and d_in + d_out <= 1016");
+        return fail(FTC_EUNSUPPORTED, "ftc_gcn_layer_backward: need d_out <= 64, ceil(d_in / 4) * ceil(d_out / 4) <= 1024 and d_in + d_out <= 506");
     const size_t need = ftc_gcn_layer_backward_workspace_bytes(gT->n, gT->nnz, d_in, d_out);
     if (!ws || ws_bytes < need)
         return fail(FTC_EWORKSPACE, "ftc_gcn_layer_backward: workspace of %zu bytes needed", need);
@@ -554,6 +566,44 @@ int32_t ftc_agnn_layer_backward(const ftc_csr *g, const ftc_windows *w, const in
     FTC_TRY(ftc_spmm(g, w, v, dY, lddy, dtype, D, agg, ldq, FTC_F32, nullptr, 0, path, ws_sp, sp, stream));
     // ... plus the derivative of the normalisation, rounded once to the requested type
     return launch_cos_backward_rows(n, H, ld, dtype, D, rinv, q, ldq, agg, ldq, dH, lddh, dh_dtype, hs);
+}
+
+size_t ftc_agnn_layer_backward_fused_workspace_bytes(int32_t n, int32_t nnz, int32_t D)
+{
+    if (n < 0 || nnz < 0 || D < 1) return 0;
+    return agnn_backward_fused_ws(n, nnz, D);
+}
+
+int32_t ftc_agnn_layer_backward_fused(const ftc_csr *g, const ftc_windows *w, const void *H, int32_t ld, int32_t dtype,
+                                      int32_t D, float beta, const float *row_z, const void *Y, int32_t ldy,
+                                      int32_t y_dtype, const void *dY, int32_t lddy, void *dH, int32_t lddh,
+                                      int32_t dh_dtype, float *dbeta, void *ws, size_t ws_bytes, void *stream)
+{
+    FTC_TRY(check_csr(g, "ftc_agnn_layer_backward_fused"));
+    if (g->n == 0) return FTC_OK;
+    FTC_TRY(check_dense(H, ld, dtype, D, "ftc_agnn_layer_backward_fused", "H"));
+    FTC_TRY(check_dense(dY, lddy, dtype, D, "ftc_agnn_layer_backward_fused", "dY"));
+    FTC_TRY(check_dense(Y, ldy, y_dtype, D, "ftc_agnn_layer_backward_fused", "Y"));
+    FTC_TRY(check_dense(dH, lddh, dh_dtype, D, "ftc_agnn_layer_backward_fused", "dH"));
+    if (!dbeta || !row_z) return fail(FTC_EINVAL, "ftc_agnn_layer_backward_fused: dbeta or row_z is NULL");
+    if (dH == H || dH == dY || dH == Y) return fail(FTC_EINVAL, "ftc_agnn_layer_backward_fused: dH aliases an input");
+    if (ld != lddy)
+        return fail(FTC_EINVAL, "ftc_agnn_layer_backward_fused: H and dY need the same leading dimension");
+    if (!w) return fail(FTC_EINVAL, "ftc_agnn_layer_backward_fused: the window index is required");
+    FTC_TRY(check_windows(g, w, "ftc_agnn_layer_backward_fused", false));
+    if (!w->edge_to_row) return fail(FTC_EINVAL, "ftc_agnn_layer_backward_fused: edge_to_row is NULL");
+    const bool rows16 = aligned16(H) && aligned16(dY) && (static_cast<int64_t>(ld) * elem_size(dtype)) % 16 == 0;
+    if (!rows16 || !agnn_backward_fused_shape(dtype, D))
+        return fail(FTC_EUNSUPPORTED,
+                    "ftc_agnn_layer_backward_fused: needs 16-byte aligned rows and a width the edge-balanced kernels "
+                    "cover with 2 * D <= 256 padded slots; use ftc_agnn_layer_backward");
+    const size_t need = agnn_backward_fused_ws(g->n, g->nnz, D);
+    if (!ws || ws_bytes < need)
+        return fail(FTC_EWORKSPACE, "ftc_agnn_layer_backward_fused: workspace of %zu bytes needed", need);
+    if (reinterpret_cast<uintptr_t>(ws) % 256 != 0)
+        return fail(FTC_EALIGN, "ftc_agnn_layer_backward_fused: workspace must be 256-byte aligned");
+    return launch_agnn_backward_fused(*g, *w, H, dY, ld, dtype, D, beta, row_z, Y, ldy, y_dtype, dH, lddh, dh_dtype,
+                                      dbeta, ws, static_cast<hipStream_t>(stream));
 }
 
 // ---- locality reordering (preprocessing) ---------------------------------------------------------

@@ -145,15 +145,17 @@ int32_t launch_mask_scale(int n, int d, const float *dY, int lddy, const void *Y
 // ---- dW = X^T G -----------------------------------------------------------------------------------
 // A workgroup walks a contiguous share of the rows, WG_ROWS at a time staged in LDS as fp32; a
 // thread owns 4 x 4 tiles of the d_in x d_out result (two 16-byte LDS reads per 16 multiply-adds)
-// and keeps them in registers for all of its rows.  The workgroups' partial results are added by a
-// second kernel in workgroup order: reproducible, no floating-point atomics.
-constexpr int WG_ROWS = 16;
-constexpr int WG_MAX_BLOCKS = 1024;
+// and keeps them in registers for all of its rows.  When the result has fewer than 256 tiles the
+// threads form 256 / tiles slices that split the staged rows between them, and the slices' tiles
+// are added in slice order through LDS at the end.  The workgroups' partial results are added by
+// a second kernel in workgroup order: reproducible, no floating-point atomics.
+constexpr int WG_ROWS = 32;
+constexpr int WG_MAX_BLOCKS = 512;
 constexpr int WG_TILES = 4;  // 4 x 4 tiles per thread at most: d_in * d_out <= 256 * 16 * WG_TILES
 
 __global__ __launch_bounds__(256) void weight_grad_kernel(int n, const void *__restrict__ X, int ldx, int xdt, int d_in,
                                                           const float *__restrict__ G, int ldg, int d_out,
-                                                          float *__restrict__ partial)
+                                                          float *__restrict__ partial, int x_vec, int g_vec)
 {
     extern __shared__ __attribute__((aligned(16))) float lds[];
     const int dip = (d_in + 3) / 4 * 4, dop = (d_out + 3) / 4 * 4;
@@ -161,6 +163,10 @@ __global__ __launch_bounds__(256) void weight_grad_kernel(int n, const void *__r
     float *Gs = lds + WG_ROWS * dip;  // [WG_ROWS][dop]
     const int tid = threadIdx.x;
     const int tiles_b = dop / 4, n_tiles = (dip / 4) * tiles_b;
+    const int slices = n_tiles < 256 ? 256 / n_tiles : 1;
+    const int slice = n_tiles < 256 ? tid / n_tiles : 0;
+    const int tile0 = n_tiles < 256 ? tid % n_tiles : tid;
+    const bool worker = slice < slices;
     float acc[WG_TILES][16];
 #pragma unroll
     for (int u = 0; u < WG_TILES; ++u)
@@ -168,36 +174,88 @@ __global__ __launch_bounds__(256) void weight_grad_kernel(int n, const void *__r
         for (int q = 0; q < 16; ++q) acc[u][q] = 0.f;
     const int64_t per = (static_cast<int64_t>(n) + gridDim.x - 1) / gridDim.x;
     const int64_t r_begin = per * blockIdx.x, r_end = min(static_cast<int64_t>(n), r_begin + per);
+    const int xv = xdt == FTC_F32 ? 4 : 8;  // elements per 16-byte piece of X
     for (int64_t r0 = r_begin; r0 < r_end; r0 += WG_ROWS) {
         __syncthreads();  // the previous rows are consumed
-        for (int t = tid; t < WG_ROWS * dip; t += 256) {
-            const int r = t / dip, a = t % dip;
-            Xs[t] = (r0 + r < r_end && a < d_in) ? load_elem(X, (r0 + r) * ldx + a, xdt) : 0.f;
+        if (x_vec) {      // d_in is a multiple of the piece, rows are 16-byte aligned
+            const int ppr = d_in / xv;
+            for (int t = tid; t < WG_ROWS * ppr; t += 256) {
+                const int r = t / ppr, a = (t % ppr) * xv;
+                float f[8];
+                const bool ok = r0 + r < r_end;
+                if (xdt == FTC_F32) {
+                    const float4 v = ok ? *reinterpret_cast<const float4 *>(static_cast<const float *>(X) + (r0 + r) * ldx + a)
+                                        : make_float4(0.f, 0.f, 0.f, 0.f);
+                    *reinterpret_cast<float4 *>(&Xs[r * dip + a]) = v;
+                } else {
+                    if (ok) {
+                        if (xdt == FTC_F16) load_vec<F16>(X, (r0 + r) * ldx + a, f);
+                        else load_vec<BF16>(X, (r0 + r) * ldx + a, f);
+                    } else {
+#pragma unroll
+                        for (int q = 0; q < 8; ++q) f[q] = 0.f;
+                    }
+                    *reinterpret_cast<float4 *>(&Xs[r * dip + a]) = make_float4(f[0], f[1], f[2], f[3]);
+                    *reinterpret_cast<float4 *>(&Xs[r * dip + a + 4]) = make_float4(f[4], f[5], f[6], f[7]);
+                }
+            }
+        } else {
+            for (int t = tid; t < WG_ROWS * dip; t += 256) {
+                const int r = t / dip, a = t % dip;
+                Xs[t] = (r0 + r < r_end && a < d_in) ? load_elem(X, (r0 + r) * ldx + a, xdt) : 0.f;
+            }
         }
-        for (int t = tid; t < WG_ROWS * dop; t += 256) {
-            const int r = t / dop, b = t % dop;
-            Gs[t] = (r0 + r < r_end && b < d_out) ? G[(r0 + r) * ldg + b] : 0.f;
+        if (g_vec) {  // d_out is a multiple of 4, rows of G are 16-byte aligned
+            for (int t = tid; t < WG_ROWS * tiles_b; t += 256) {
+                const int r = t / tiles_b, b = (t % tiles_b) * 4;
+                *reinterpret_cast<float4 *>(&Gs[r * dop + b]) =
+                    r0 + r < r_end ? *reinterpret_cast<const float4 *>(G + (r0 + r) * ldg + b) : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+        } else {
+            for (int t = tid; t < WG_ROWS * dop; t += 256) {
+                const int r = t / dop, b = t % dop;
+                Gs[t] = (r0 + r < r_end && b < d_out) ? G[(r0 + r) * ldg + b] : 0.f;
+            }
         }
         __syncthreads();
+        if (worker) {
 #pragma unroll
-        for (int u = 0; u < WG_TILES; ++u) {
-            const int tile = tid + u * 256;
-            if (tile < n_tiles) {
-                const int a0 = (tile / tiles_b) * 4, b0 = (tile % tiles_b) * 4;
-#pragma unroll 4
-                for (int r = 0; r < WG_ROWS; ++r) {
-                    const float4 x = *reinterpret_cast<const float4 *>(&Xs[r * dip + a0]);
-                    const float4 gq = *reinterpret_cast<const float4 *>(&Gs[r * dop + b0]);
-                    const float xv[4] = {x.x, x.y, x.z, x.w}, gv[4] = {gq.x, gq.y, gq.z, gq.w};
+            for (int u = 0; u < WG_TILES; ++u) {
+                const int tile = tile0 + u * 256;
+                if (tile < n_tiles && (u == 0 || n_tiles >= 256)) {
+                    const int a0 = (tile / tiles_b) * 4, b0 = (tile % tiles_b) * 4;
+                    for (int r = slice; r < WG_ROWS; r += slices) {
+                        const float4 x = *reinterpret_cast<const float4 *>(&Xs[r * dip + a0]);
+                        const float4 gq = *reinterpret_cast<const float4 *>(&Gs[r * dop + b0]);
+                        const float xq[4] = {x.x, x.y, x.z, x.w}, gv[4] = {gq.x, gq.y, gq.z, gq.w};
 #pragma unroll
-                    for (int i = 0; i < 4; ++i)
+                        for (int i = 0; i < 4; ++i)
 #pragma unroll
-                        for (int j = 0; j < 4; ++j) acc[u][i * 4 + j] = fmaf(xv[i], gv[j], acc[u][i * 4 + j]);
+                            for (int j = 0; j < 4; ++j) acc[u][i * 4 + j] = fmaf(xq[i], gv[j], acc[u][i * 4 + j]);
+                    }
                 }
             }
         }
     }
     float *out = partial + static_cast<size_t>(blockIdx.x) * d_in * d_out;
+    if (n_tiles < 256) {
+        // add the slices' tiles in slice order; red[slice][tile][16] reuses the staging memory
+        __syncthreads();
+        float *red = lds;
+        if (worker) {
+#pragma unroll
+            for (int q = 0; q < 16; ++q) red[(slice * n_tiles + tile0) * 16 + q] = acc[0][q];
+        }
+        __syncthreads();
+        for (int e = tid; e < n_tiles * 16; e += 256) {
+            float t = 0.f;
+            for (int sl = 0; sl < slices; ++sl) t += red[sl * n_tiles * 16 + e];
+            const int tile = e / 16, q = e % 16;
+            const int a = (tile / tiles_b) * 4 + q / 4, b = (tile % tiles_b) * 4 + q % 4;
+            if (a < d_in && b < d_out) out[a * d_out + b] = t;
+        }
+        return;
+    }
 #pragma unroll
     for (int u = 0; u < WG_TILES; ++u) {
         const int tile = tid + u * 256;
@@ -217,16 +275,14 @@ __global__ __launch_bounds__(256) void sum_partials_kernel(int count, int n_part
 {
     const int t = blockIdx.x * 256 + threadIdx.x;
     if (t >= count) return;
-    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     int b = 0;
-    for (; b + 3 < n_partials; b += 4) {
-        s0 += partial[static_cast<size_t>(b) * count + t];
-        s1 += partial[static_cast<size_t>(b + 1) * count + t];
-        s2 += partial[static_cast<size_t>(b + 2) * count + t];
-        s3 += partial[static_cast<size_t>(b + 3) * count + t];
+    for (; b + 7 < n_partials; b += 8) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) s[k] += partial[static_cast<size_t>(b + k) * count + t];
     }
-    for (; b < n_partials; ++b) s0 += partial[static_cast<size_t>(b) * count + t];
-    out[t] = (s0 + s1) + (s2 + s3);
+    for (; b < n_partials; ++b) s[0] += partial[static_cast<size_t>(b) * count + t];
+    out[t] = ((s[0] + s[1]) + (s[2] + s[3])) + ((s[4] + s[5]) + (s[6] + s[7]));
 }
 
 static int weight_grad_blocks(int n)
@@ -239,7 +295,7 @@ bool weight_grad_shape_ok(int d_in, int d_out)
 {
     // register tiles of one workgroup cover the result; the staged rows fit 64 KB of LDS
     return d_in >= 1 && d_out >= 1 && ((d_in + 3) / 4) * ((d_out + 3) / 4) <= 256 * WG_TILES &&
-           (d_in + 3) / 4 * 4 + (d_out + 3) / 4 * 4 <= 1024;
+           (d_in + 3) / 4 * 4 + (d_out + 3) / 4 * 4 <= 512;
 }
 
 size_t weight_grad_ws(int n, int d_in, int d_out)
@@ -251,10 +307,19 @@ int32_t launch_weight_grad(int n, const void *X, int ldx, int xdt, int d_in, con
                            float *dW, void *ws, hipStream_t s)
 {
     const int blocks = weight_grad_blocks(n);
-    const size_t lds = static_cast<size_t>(WG_ROWS) * ((d_in + 3) / 4 * 4 + (d_out + 3) / 4 * 4) * sizeof(float);
+    const int dip = (d_in + 3) / 4 * 4, dop = (d_out + 3) / 4 * 4;
+    const int n_tiles = (dip / 4) * (dop / 4);
+    size_t lds = static_cast<size_t>(WG_ROWS) * (dip + dop) * sizeof(float);
+    if (n_tiles < 256) {  // room for the slices' tiles
+        const size_t red = static_cast<size_t>(256 / n_tiles) * n_tiles * 16 * sizeof(float);
+        if (red > lds) lds = red;
+    }
+    const int xv = xdt == FTC_F32 ? 4 : 8;
+    const int x_vec = d_in % xv == 0 && (static_cast<int64_t>(ldx) * elem_size(xdt)) % 16 == 0 && aligned16(X);
+    const int g_vec = d_out % 4 == 0 && ldg % 4 == 0 && aligned16(G);
     float *partial = static_cast<float *>(ws);
-    hipLaunchKernelGGL(weight_grad_kernel, dim3(blocks), dim3(256), lds, s, n, X, ldx, xdt, d_in, G, ldg, d_out,
-                       partial);
+    hipLaunchKernelGGL(weight_grad_kernel, dim3(blocks), dim3(256), lds, s, n, X, ldx, xdt, d_in, G, ldg, d_out, partial,
+                       x_vec, g_vec);
     hipLaunchKernelGGL(sum_partials_kernel, dim3((d_in * d_out + 255) / 256), dim3(256), 0, s, d_in * d_out, blocks,
                        partial, dW);
     return launch_status("weight_grad");
@@ -377,28 +442,67 @@ int32_t launch_edge_dot(int nnz, const float *a, const float *b, float *out, voi
 // q is the gradient with respect to the normalised rows, base the part of dH that reaches h through
 // the aggregated rows; eight lanes per row.  A row whose norm was clamped (|h| <= 1e-12) is a plain
 // scaling: no projection.  base may be dH itself (fp32, in place).
+// VEC4: four consecutive elements per lane and step (16-byte loads of q and base; every leading
+// dimension a multiple of 4, D too, pointers 16-byte aligned), else element by element.
+template <bool VEC4>
 __global__ __launch_bounds__(256) void cos_backward_rows_kernel(int n, const void *__restrict__ H, int ld, int dt, int D,
                                                                 const float *__restrict__ rinv,
                                                                 const float *__restrict__ q, int ldq,
                                                                 const float *base, int ldb, void *dH, int lddh,
                                                                 int dh_dt)
 {
+    constexpr int W = VEC4 ? 4 : 1;
     const int sub = threadIdx.x & 7;
     const int64_t row = (static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x) >> 3;
     const bool ok = row < n;
     const float ri = ok ? rinv[row] : 0.f;
     float proj = 0.f;
-    if (ok)
-        for (int k = sub; k < D; k += 8) proj = fmaf(load_elem(H, row * ld + k, dt) * ri, q[row * ldq + k], proj);
+    // the row has at most 256 elements: 8 lanes x 4 elements x 8 steps, kept in registers between the passes
+    float hq[VEC4 ? 8 : 1][W], qq[VEC4 ? 8 : 1][W];
+    if (ok) {
+        if constexpr (VEC4) {
+#pragma unroll
+            for (int s = 0; s < 8; ++s) {
+                const int k = (s * 8 + sub) * 4;
+                if (k < D) {
+                    const float4 q4 = *reinterpret_cast<const float4 *>(q + row * ldq + k);
+                    qq[s][0] = q4.x; qq[s][1] = q4.y; qq[s][2] = q4.z; qq[s][3] = q4.w;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        hq[s][e] = load_elem(H, row * ld + k + e, dt) * ri;
+                        proj = fmaf(hq[s][e], qq[s][e], proj);
+                    }
+                }
+            }
+        } else {
+            for (int k = sub; k < D; k += 8) proj = fmaf(load_elem(H, row * ld + k, dt) * ri, q[row * ldq + k], proj);
+        }
+    }
     proj += __shfl_xor(proj, 1, 64);
     proj += __shfl_xor(proj, 2, 64);
     proj += __shfl_xor(proj, 4, 64);
     if (ri >= 0.999e12f) proj = 0.f;  // the clamp of the row-norm kernel took effect
-    if (ok)
-        for (int k = sub; k < D; k += 8) {
-            const float hn = load_elem(H, row * ld + k, dt) * ri;
-            store_elem(dH, row * lddh + k, dh_dt, base[row * ldb + k] + ri * (q[row * ldq + k] - hn * proj));
+    if (ok) {
+        if constexpr (VEC4) {
+#pragma unroll
+            for (int s = 0; s < 8; ++s) {
+                const int k = (s * 8 + sub) * 4;
+                if (k < D) {
+                    const float4 b4 = *reinterpret_cast<const float4 *>(base + row * ldb + k);
+                    const float bb[4] = {b4.x, b4.y, b4.z, b4.w};
+                    float o[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) o[e] = bb[e] + ri * (qq[s][e] - hq[s][e] * proj);
+                    store_vec<4>(dH, row * lddh + k, dh_dt, o);
+                }
+            }
+        } else {
+            for (int k = sub; k < D; k += 8) {
+                const float hn = load_elem(H, row * ld + k, dt) * ri;
+                store_elem(dH, row * lddh + k, dh_dt, base[row * ldb + k] + ri * (q[row * ldq + k] - hn * proj));
+            }
         }
+    }
 }
 
 int32_t launch_cos_backward_rows(int n, const void *H, int ld, int dt, int D, const float *rinv, const float *q, int ldq,
@@ -406,8 +510,14 @@ int32_t launch_cos_backward_rows(int n, const void *H, int ld, int dt, int D, co
 {
     if (n == 0) return FTC_OK;
     const unsigned grid = static_cast<unsigned>((static_cast<int64_t>(n) * 8 + 255) / 256);
-    hipLaunchKernelGGL(cos_backward_rows_kernel, dim3(grid), dim3(256), 0, s, n, H, ld, dt, D, rinv, q, ldq, base, ldb,
-                       dH, lddh, dh_dt);
+    const bool vec4 = D % 4 == 0 && D <= 256 && ld % 4 == 0 && ldq % 4 == 0 && ldb % 4 == 0 && lddh % 4 == 0 &&
+                      aligned16(q) && aligned16(base) && aligned16(dH) && aligned16(H);
+    if (vec4)
+        hipLaunchKernelGGL(cos_backward_rows_kernel<true>, dim3(grid), dim3(256), 0, s, n, H, ld, dt, D, rinv, q, ldq, base,
+                           ldb, dH, lddh, dh_dt);
+    else
+        hipLaunchKernelGGL(cos_backward_rows_kernel<false>, dim3(grid), dim3(256), 0, s, n, H, ld, dt, D, rinv, q, ldq,
+                           base, ldb, dH, lddh, dh_dt);
     return launch_status("cos_backward_rows");
 }
 

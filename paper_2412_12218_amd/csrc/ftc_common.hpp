@@ -10,6 +10,7 @@
 namespace ftc {
 
 constexpr int WAVE = 64;
+constexpr int SEG_R = 512;  // edges per wave of the edge-balanced kernels (SpMM, fused AGNN forward / backward)
 
 // ---- host side -------------------------------------------------------------------------------
 void set_error(const char *fmt, ...);
@@ -58,7 +59,13 @@ int32_t launch_sddmm_edges(const ftc_csr &g, const ftc_windows &w, const void *X
                            bool cosine, hipStream_t s);
 size_t agnn_fused_ws(int nnz, int D);
 int32_t launch_agnn_fused(const ftc_csr &g, const ftc_windows &w, const void *H, int ld, int dt, int D,
-                          float beta, void *out, int ldo, int odt, void *ws, hipStream_t s);
+                          float beta, void *out, int ldo, int odt, float *row_z, float *out32, int ld32, void *ws,
+                          hipStream_t s);
+bool agnn_backward_fused_shape(int dtype, int D);
+size_t agnn_backward_fused_ws(int n, int nnz, int D);
+int32_t launch_agnn_backward_fused(const ftc_csr &g, const ftc_windows &w, const void *H, const void *dY, int ld, int dt,
+                                   int D, float beta, const float *row_z, const void *Y, int ldy, int ydt, void *dH,
+                                   int lddh, int dh_dt, float *dbeta, void *ws, hipStream_t s);
 bool mfma_shape_ok(int dtype, int D);
 int32_t launch_classify(const ftc_csr &g, const ftc_windows &w, float reuse, int max_edges, uint8_t *flags,
                         hipStream_t s);
@@ -296,6 +303,32 @@ __device__ __forceinline__ void store_vec(void *base, int64_t idx, int dtype, co
         }
     }
 }
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float v)
+{
+    const int moved = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false);
+    return v + __int_as_float(moved);
+}
+
+// Sum over the LPR consecutive lanes of a group; every lane of the group gets the total.
+template <int LPR>
+__device__ __forceinline__ float group_sum_dpp(float v)
+{
+    if constexpr (LPR >= 32) v += __shfl_xor(v, 16, 64);
+    if constexpr (LPR >= 16) v = dpp_add<0x140>(v);  // row_mirror: lane i <-> 15 - i
+    if constexpr (LPR >= 8) v = dpp_add<0x141>(v);   // row_half_mirror: lane i <-> 7 - i
+    if constexpr (LPR >= 4) v = dpp_add<0x4e>(v);    // quad_perm [2,3,0,1]
+    if constexpr (LPR >= 2) v = dpp_add<0xb1>(v);    // quad_perm [1,0,3,2]
+    return v;
+}
+
+// Second pass of the edge-balanced kernels (spmm_seg.hip): finishes the rows cut by a wave boundary
+// from the carry buffer and zero-fills the rows without entries.
+__global__ void spmm_seg_fixup_kernel(int n, int n_ranges, const int *__restrict__ row_ptr,
+                                      const float *__restrict__ carry, const int *__restrict__ carry_tail_row, int DP,
+                                      int D, void *__restrict__ out, int ldo, int odt, Epi epi,
+                                      const uint8_t *__restrict__ dense);
 
 // Inclusive prefix sum over the 64 lanes of a wave with data-parallel-primitive moves: shifts by
 // 1, 2, 4, 8 inside rows of 16 lanes, then lane 15 of a row added to the next row (rows 1 and 3) and

@@ -16,25 +16,6 @@ constexpr int SD_B = 4;    // edges per batch
 
 bool seg_shape(int dtype, int D, int *vec, int *lpr);  // spmm_seg.hip: same lane layout
 
-template <int CTRL>
-__device__ __forceinline__ float dpp_add(float v)
-{
-    const int moved = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false);
-    return v + __int_as_float(moved);
-}
-
-// Sum over the LPR consecutive lanes of a group; every lane of the group gets the total.
-template <int LPR>
-__device__ __forceinline__ float group_sum_dpp(float v)
-{
-    if constexpr (LPR >= 32) v += __shfl_xor(v, 16, 64);
-    if constexpr (LPR >= 16) v = dpp_add<0x140>(v);  // row_mirror: lane i <-> 15 - i
-    if constexpr (LPR >= 8) v = dpp_add<0x141>(v);   // row_half_mirror: lane i <-> 7 - i
-    if constexpr (LPR >= 4) v = dpp_add<0x4e>(v);    // quad_perm [2,3,0,1]
-    if constexpr (LPR >= 2) v = dpp_add<0xb1>(v);    // quad_perm [1,0,3,2]
-    return v;
-}
-
 // COS: the scores are cosines: every dot product is divided by the Euclidean norms of its two rows
 // (clamped at 1e-12), which are recomputed from the row slices that are in registers anyway (one more
 // packed dot product and lane-group sum per edge) instead of being gathered, 4 bytes at a time,

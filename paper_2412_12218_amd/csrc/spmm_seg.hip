@@ -19,7 +19,6 @@
 
 namespace ftc {
 
-constexpr int SEG_R = 512;  // edges per wave
 constexpr int SEG_B = 4;    // edges per batch (gathers in flight per lane)
 
 static int pow2_ceil(int x)

@@ -69,7 +69,7 @@ class TrainPath:
     operator is the operator itself; the AGNN backward needs the transposed index, built once here."""
 
     def __init__(self, g, win, dinv, d_feat=128, gcn_hidden=16, agnn_hidden=32, n_out=8, agnn_layers=4,
-                 act_dtype=torch.float16, path=B.FTC_PATH_AUTO):
+                 act_dtype=torch.float16, path=B.FTC_PATH_AUTO, fused=True):
         dev = g.row_ptr.device
         L = B.lib()
         self.g, self.win, self.dinv, self.path, self.agnn_layers = g, win, dinv, path, agnn_layers
@@ -82,7 +82,16 @@ class TrainPath:
         self.gcn_h = torch.empty((n, gcn_hidden), **act)
         self.gcn_out = torch.empty((n, n_out), **f32)
         self.agnn_h = [None] + [torch.empty((n, agnn_hidden), **act) for _ in range(agnn_layers)]
-        self.agnn_p = [torch.empty(nnz, **f32) for _ in range(agnn_layers)]
+        # single-pass forward / backward pair when the shape allows it: per-row softmax denominators are
+        # kept instead of the per-entry probabilities, and no transposed index is read
+        self.fused = bool(fused and win is not None and L.ftc_agnn_layer_backward_fused_workspace_bytes(n, nnz, agnn_hidden) > 0
+                          and (agnn_hidden * self.agnn_h_itemsize(act_dtype)) % 16 == 0)
+        self.agnn_z = [torch.empty(n, **f32) for _ in range(agnn_layers)] if self.fused else []
+        # 16-bit activations: every layer also keeps its unrounded output for the backward pass
+        self.keep_f32 = self.fused and act_dtype != torch.float32
+        self.agnn_y32 = [torch.empty((n, (agnn_hidden + 3) // 4 * 4), **f32) for _ in range(agnn_layers)] \
+            if self.keep_f32 else []
+        self.agnn_p = [torch.empty(nnz, **f32) for _ in range(agnn_layers)] if not self.fused else []
         self.d_agnn_h = [torch.empty((n, agnn_hidden), **act) for _ in range(2)]
         self.dbeta = torch.empty(agnn_layers, **f32)
         self.ws = B._workspace(max(
@@ -91,7 +100,12 @@ class TrainPath:
             L.ftc_gcn_layer_backward_workspace_bytes(n, nnz, d_feat, gcn_hidden),
             L.ftc_gcn_layer_backward_workspace_bytes(n, nnz, gcn_hidden, n_out),
             L.ftc_agnn_layer_workspace_bytes(n, nnz, agnn_hidden),
-            L.ftc_agnn_layer_backward_workspace_bytes(n, nnz, agnn_hidden)), dev)
+            L.ftc_agnn_layer_backward_workspace_bytes(n, nnz, agnn_hidden),
+            L.ftc_agnn_layer_backward_fused_workspace_bytes(n, nnz, agnn_hidden)), dev)
+
+    @staticmethod
+    def agnn_h_itemsize(dtype):
+        return torch.empty(0, dtype=dtype).element_size()
 
     def gcn_forward(self, X, W1, W2):
         B.ftc_gcn_layer(self.g, self.win, None, X, W1, relu=True, out=self.gcn_h, path=self.path, ws=self.ws,
@@ -113,8 +127,11 @@ class TrainPath:
         every layer keeps its attention probabilities for the backward pass."""
         self.agnn_h[0] = H0
         for l in range(self.agnn_layers):
+            keep = dict(row_z=self.agnn_z[l]) if self.fused else dict(edge_p=self.agnn_p[l])
+            if self.keep_f32:
+                keep["out_f32"] = self.agnn_y32[l]
             B.ftc_agnn_layer(self.g, self.win, self.agnn_h[l], beta=betas[l], out=self.agnn_h[l + 1],
-                             edge_p=self.agnn_p[l], path=self.path, ws=self.ws)
+                             path=self.path, ws=self.ws, **keep)
         return self.agnn_h[self.agnn_layers]
 
     def agnn_backward(self, betas, d_out):
@@ -122,7 +139,12 @@ class TrainPath:
         d = d_out
         for l in reversed(range(self.agnn_layers)):
             nxt = self.d_agnn_h[l & 1]
-            B.ftc_agnn_layer_backward(self.g, self.win, self.T, self.agnn_h[l], self.agnn_p[l], d, beta=betas[l],
-                                      dH=nxt, dbeta=self.dbeta[l:l + 1], path=self.path, ws=self.ws)
+            if self.fused:
+                y = self.agnn_y32[l][:, :self.agnn_h[l].shape[1]] if self.keep_f32 else self.agnn_h[l + 1]
+                B.ftc_agnn_layer_backward_fused(self.g, self.win, self.agnn_h[l], self.agnn_z[l], y, d,
+                                                beta=betas[l], dH=nxt, dbeta=self.dbeta[l:l + 1], ws=self.ws)
+            else:
+                B.ftc_agnn_layer_backward(self.g, self.win, self.T, self.agnn_h[l], self.agnn_p[l], d, beta=betas[l],
+                                          dH=nxt, dbeta=self.dbeta[l:l + 1], path=self.path, ws=self.ws)
             d = nxt
         return d, self.dbeta

@@ -255,6 +255,97 @@ def test_agnn_layer_backward(graphs, name, dtype, D, beta):
     assert torch.equal(dH, dH3) and torch.equal(dbeta, dbeta3)
 
 
+# ------------------------------------------------------------------ single-pass AGNN backward
+@pytest.mark.parametrize("name", ["cfg1", "cfg3s", "cfg5s"])
+@pytest.mark.parametrize("dtype,D", [(F32, 16), (F16, 32), (BF16, 24), (F16, 64), (F32, 12), (F16, 8), (F16, 128),
+                                     (F32, 64)])
+@pytest.mark.parametrize("beta", [1.0, -2.5])
+def test_agnn_forward_row_z_and_fused_backward(oracle, graphs, name, dtype, D, beta):
+    g = graphs[name]
+    if name != "cfg1" and (dtype, D) not in ((F32, 16), (F16, 32)):
+        pytest.skip("odd widths are covered on the small graph")
+    say(f"agnn fused backward {name} {dtype} D={D} beta={beta}")
+    Hd, H64 = quantise(synth.normal_features(g.n, D, seed=11), dtype)
+    dYd, dY64 = quantise(synth.normal_features(g.n, D, seed=14), dtype)
+    dg = dev_graph(g)
+    win = B.ftc_build_windows(dg)
+    row_z = torch.empty(g.n, dtype=F32, device="cuda")
+    Y = B.ftc_agnn_layer(dg, win, Hd, beta=beta, row_z=row_z)           # fp32 output of the single-pass forward
+    z_ref = OB.agnn_row_z(g.row_ptr, g.col_idx, H64, beta)
+    ez = float(np.max(np.abs(row_z.cpu().double().numpy() - z_ref) / np.maximum(z_ref, 1e-300)))
+    say(f"  row_z err {ez:.3e}")
+    assert ez < (1e-5 if dtype == F32 else 1e-4)
+    assert torch.equal(Y, B.ftc_agnn_layer(dg, win, Hd, beta=beta))    # the extra output changes nothing
+    dH_ref, dbeta_ref = OB.agnn_layer_backward(g.row_ptr, g.col_idx, H64, beta, dY64)
+    dH, dbeta = B.ftc_agnn_layer_backward_fused(dg, win, Hd, row_z, Y, dYd, beta=beta)
+    eh = row_err(dH, dH_ref)
+    db = abs(float(dbeta.item()) - dbeta_ref)
+    say(f"  dH err {eh:.3e} dbeta {float(dbeta.item()):.6g} ref {dbeta_ref:.6g} diff {db:.2e}")
+    assert eh < GTOL[dtype]                                             # fp32 Y: the full-precision bar
+    assert db < 1e-4 * max(abs(dbeta_ref), np.sqrt(g.n) * 1e-2)
+    dH2, dbeta2 = B.ftc_agnn_layer_backward_fused(dg, win, Hd, row_z, Y, dYd, beta=beta)
+    assert torch.equal(dH, dH2) and torch.equal(dbeta, dbeta2)
+    if dtype != F32:
+        # the layer's output in the activation type plus its unrounded copy: what a 16-bit layer stack keeps
+        y32 = torch.empty((g.n, (D + 3) // 4 * 4), dtype=F32, device="cuda")
+        Y16 = B.ftc_agnn_layer(dg, win, Hd, beta=beta, out_dtype=dtype, row_z=row_z, out_f32=y32)
+        assert torch.equal(y32[:, :D], Y) and torch.equal(Y16, Y.to(dtype))
+        dH16, dbeta16 = B.ftc_agnn_layer_backward_fused(dg, win, Hd, row_z, y32[:, :D], dYd, beta=beta, dh_dtype=dtype)
+        assert torch.equal(dH16, dH.to(dtype)) and torch.equal(dbeta16, dbeta)
+
+
+def test_agnn_fused_backward_matches_the_unfused_route_on_hub_rows():
+    """Rows far longer than a wave's range (thousands of entries) and empty rows: both routes of the
+    backward pass against each other and against the oracle."""
+    rng = np.random.default_rng(12)
+    n = 6000
+    import scipy.sparse as sp
+    u = np.concatenate([rng.integers(0, n, size=20_000), np.full(4000, 77), np.full(1500, 3001)])
+    v = np.concatenate([rng.integers(0, n, size=20_000), rng.integers(0, n, size=4000), rng.integers(0, n, size=1500)])
+    keep = (u % 50 != 9) & (v % 50 != 9)                      # nodes 9, 59, ... stay isolated: empty rows
+    A = sp.csr_matrix((np.ones(keep.sum()), (u[keep], v[keep])), shape=(n, n))
+    A = (A + A.T).tocsr()
+    A.sum_duplicates()
+    A.sort_indices()
+    g = synth.Graph(n, A.indptr.astype(np.int32), A.indices.astype(np.int32), "hubs")
+    assert np.diff(g.row_ptr).max() > 2000 and np.diff(g.row_ptr).min() == 0
+    Hd, H64 = quantise(synth.normal_features(n, 32, seed=1), F16)
+    dYd, dY64 = quantise(synth.normal_features(n, 32, seed=2), F16)
+    dg = dev_graph(g)
+    win = B.ftc_build_windows(dg)
+    T, flag = B.ftc_transpose_index(dg, win)
+    assert int(flag.item()) == 0
+    p = torch.empty(g.nnz, dtype=F32, device="cuda")
+    B.ftc_agnn_layer(dg, win, Hd, beta=2.0, edge_p=p)
+    dH_u, db_u = B.ftc_agnn_layer_backward(dg, win, T, Hd, p, dYd, beta=2.0)
+    row_z = torch.empty(n, dtype=F32, device="cuda")
+    Y = B.ftc_agnn_layer(dg, win, Hd, beta=2.0, row_z=row_z)
+    dH_f, db_f = B.ftc_agnn_layer_backward_fused(dg, win, Hd, row_z, Y, dYd, beta=2.0)
+    dH_ref, db_ref = OB.agnn_layer_backward(g.row_ptr, g.col_idx, H64, 2.0, dY64)
+    eu, ef = row_err(dH_u, dH_ref), row_err(dH_f, dH_ref)
+    say(f"hub rows: unfused err {eu:.3e} fused err {ef:.3e} dbeta {float(db_u.item()):.6g} {float(db_f.item()):.6g} ref {db_ref:.6g}")
+    assert eu < 1e-5 and ef < 1e-5
+    assert abs(float(db_f.item()) - db_ref) < 1e-4 * max(abs(db_ref), 1.0)
+    empty = torch.from_numpy(np.diff(g.row_ptr) == 0).cuda()
+    assert torch.all(dH_f[empty] == 0) and torch.all(row_z[empty] == 0)
+
+
+def test_agnn_row_z_needs_the_single_pass_route(graphs):
+    g = graphs["cfg1"]
+    dg = dev_graph(g)
+    win = B.ftc_build_windows(dg)
+    H = torch.zeros((g.n, 16), dtype=F16, device="cuda")
+    z = torch.empty(g.n, dtype=F32, device="cuda")
+    with pytest.raises(B.FtcError):
+        B.ftc_agnn_layer(dg, None, H, row_z=z)                                    # no window index
+    with pytest.raises(B.FtcError):
+        B.ftc_agnn_layer(dg, win, H, row_z=z, edge_p=torch.empty(g.nnz, dtype=F32, device="cuda"))
+    with pytest.raises(B.FtcError):                                               # 2 * 256 slots: too wide
+        B.ftc_agnn_layer_backward_fused(dg, win, torch.zeros((g.n, 256), dtype=F16, device="cuda"), z,
+                                        torch.zeros((g.n, 256), dtype=F32, device="cuda"),
+                                        torch.zeros((g.n, 256), dtype=F16, device="cuda"))
+
+
 def test_agnn_layer_backward_zero_rows_and_isolated_nodes():
     """Nodes whose only neighbour is themselves, and an all-zero feature row (its direction is
     undefined: the forward definition clamps the norm, the gradient through it stays finite)."""
@@ -295,16 +386,20 @@ def test_agnn_layer_backward_16bit_gradient_output(graphs):
         assert dH16.dtype == dt and torch.equal(dH16, dH32.to(dt)) and torch.equal(db16, db32)
 
 
-def test_train_path_stacks_against_chained_oracle(oracle):
+@pytest.mark.parametrize("fused", [True, False])
+def test_train_path_stacks_against_chained_oracle(oracle, fused):
     """TrainPath (2-layer GCN, 3 AGNN propagation layers, fp32 activations) against the per-layer
-    oracles chained on the CPU."""
+    oracles chained on the CPU; the AGNN layers through the single-pass pair and through the
+    edge-array route."""
     from paper_2412_12218_amd.models import TrainPath
     g = synth.config_graph(1)
     n = g.n
     dg = dev_graph(g)
     win = B.ftc_build_windows(dg)
     _, dinv = B.ftc_gcn_norm(dg, win)
-    tp = TrainPath(dg, win, dinv, d_feat=24, gcn_hidden=16, agnn_hidden=12, n_out=8, agnn_layers=3, act_dtype=F32)
+    tp = TrainPath(dg, win, dinv, d_feat=24, gcn_hidden=16, agnn_hidden=12, n_out=8, agnn_layers=3, act_dtype=F32,
+                   fused=fused)
+    assert tp.fused == fused
     dinv64 = dinv.cpu().double().numpy()
     rows = np.repeat(np.arange(n), np.diff(g.row_ptr))
     vals = dinv64[rows] * dinv64[g.col_idx]

@@ -136,3 +136,20 @@ def test_transpose_index_against_dense(seed):
     ru = np.repeat(np.arange(gu.n), np.diff(gu.row_ptr))
     dense[ru, gu.col_idx] = True
     assert np.array_equal(Tu >= 0, dense.T[ru, gu.col_idx])
+
+
+@pytest.mark.parametrize("beta", [1.0, -3.0, 0.0])
+def test_row_z_is_the_denominator_of_the_forward_oracles_probabilities(oracle, beta):
+    """p_e * z_i = exp(beta * c_e - |beta|) with p from the C forward oracle (independent code) and
+    c_e from its SDDMM on the normalised rows; a row of identical neighbours has z = deg * exp(beta - |beta|)."""
+    g = synth.config_graph(1)
+    H = synth.normal_features(g.n, 12, seed=3).astype(np.float64)
+    _, _, p = oracle.agnn_layer(g.row_ptr, g.col_idx, H, beta)
+    Hn = H / np.sqrt((H * H).sum(axis=1))[:, None]
+    c, _ = oracle.sddmm(g.row_ptr, g.col_idx, Hn, Hn)
+    z = ob.agnn_row_z(g.row_ptr, g.col_idx, H, beta)
+    rows = np.repeat(np.arange(g.n), np.diff(g.row_ptr))
+    assert np.allclose(p * z[rows], np.exp(beta * c - abs(beta)), rtol=1e-12, atol=0)
+    same = np.tile(H[:1], (g.n, 1))                      # every cosine is 1
+    z1 = ob.agnn_row_z(g.row_ptr, g.col_idx, same, beta)
+    assert np.allclose(z1, np.diff(g.row_ptr) * np.exp(beta - abs(beta)), rtol=1e-12)
