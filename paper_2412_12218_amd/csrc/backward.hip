@@ -150,7 +150,7 @@ int32_t launch_mask_scale(int n, int d, const float *dY, int lddy, const void *Y
 // are added in slice order through LDS at the end.  The workgroups' partial results are added by
 // a second kernel in workgroup order: reproducible, no floating-point atomics.
 constexpr int WG_ROWS = 32;
-constexpr int WG_MAX_BLOCKS = 512;
+constexpr int WG_MAX_BLOCKS = 1024;
 constexpr int WG_TILES = 4;  // 4 x 4 tiles per thread at most: d_in * d_out <= 256 * 16 * WG_TILES
 
 __global__ __launch_bounds__(256) void weight_grad_kernel(int n, const void *__restrict__ X, int ldx, int xdt, int d_in,
