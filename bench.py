@@ -267,7 +267,10 @@ def reorder_suite(iters=10):
         g = synth.config_graph(cfg)
         dg = B.Graph.from_numpy(g.row_ptr, g.col_idx)
         base = kernels(dg, D, dtype)
-        print(json.dumps({"graph": f"cfg{cfg}", "n": g.n, "nnz": g.nnz, "D": D, "ordering": "as given", **base}), flush=True)
+        stats = B.ftc_degree_stats(dg).cpu().numpy()
+        plan = B.ftc_plan_graph(g.n, g.nnz, int(stats[0]), int(round(base["uniq_per_nnz"] * g.nnz)), D, dtype)
+        print(json.dumps({"graph": f"cfg{cfg}", "n": g.n, "nnz": g.nnz, "D": D, "ordering": "as given", **base,
+                          "plan": plan}), flush=True)
         ws = B._workspace(B.lib().ftc_reorder_workspace_bytes(g.n, g.nnz), dev)
         for mode, tag in ((B.FTC_ORDER_DEGREE, "degree"), (B.FTC_ORDER_DEGREE_CLASSES, "degree classes")):
             t_order = ms_of(lambda: B.ftc_degree_order(dg, mode, ws=ws), 5)

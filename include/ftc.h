@@ -326,6 +326,7 @@ int32_t ftc_agnn_layer_backward_fused(const ftc_csr *g, const ftc_windows *w, co
  * All results are unique (stable sorts) and reproducible.
  */
 enum {
+    FTC_ORDER_NONE = -1,          /* keep the numbering (a value of ftc_plan.reorder only) */
     FTC_ORDER_DEGREE = 0,         /* descending number of stored entries of the row, ties: ascending id */
     FTC_ORDER_DEGREE_CLASSES = 1  /* descending bit length of that number (power-of-two classes), ties:
                                      ascending id -- keeps the given order inside a class */
@@ -355,6 +356,37 @@ int32_t ftc_permute_graph(const ftc_csr *g, const int32_t *perm, const int32_t *
  */
 int32_t ftc_permute_rows(int32_t n, const void *X, int32_t ldx, int32_t dtype, int32_t D,
                          const int32_t *map, void *out, int32_t ldo, void *stream);
+
+/*
+ * ---- Per-graph plan ---------------------------------------------------------------------------
+ * The paper's outlook (Section VII) names a framework that adapts its use of the hardware to the
+ * input graph.  Here the adaptation has two levels.  Per window: FTC_PATH_AUTO sends a window to the
+ * matrix cores or to the vector kernels by its density, with measured crossovers (ftc_spmm,
+ * ftc_sddmm).  Per graph: ftc_plan_graph turns a few statistics, gathered once at build time, into
+ * the choices that hold for the whole graph.  The statistics live on the device (ftc_degree_stats,
+ * and summary[0] of ftc_build_windows); the caller copies them to the host once per graph.
+ */
+
+/* stats[0] = sum over the rows of (stored entries)^2, stats[1] = longest row (device, int64[2]). */
+int32_t ftc_degree_stats(const ftc_csr *g, int64_t *stats, void *stream);
+
+typedef struct {
+    double skew;          /* n * sum_deg_sq / nnz^2: mean popularity of the node an entry points to, relative to
+                             the mean row length (1 for a regular graph; row lengths stand in for column counts,
+                             exact on symmetric patterns) */
+    double reuse;         /* nnz / sum_uniq: stored entries per condensed column, averaged over the windows */
+    int32_t reorder;      /* FTC_ORDER_NONE or the ordering to apply with ftc_degree_order / ftc_permute_graph:
+                             skew >= 2 and a feature matrix (n * D elements) larger than one L2 (4 MiB) */
+    int32_t agnn_single_pass;           /* ftc_agnn_layer without edge_p runs as one pass for this (dtype, D) */
+    int32_t agnn_backward_single_pass;  /* ftc_agnn_layer_backward_fused covers this (dtype, D) */
+    int32_t spmm_mfma_windows;   /* FTC_PATH_AUTO may send windows of this (dtype, D) to the matrix cores ... */
+    int32_t sddmm_mfma_windows;  /* ... for SpMM / for SDDMM */
+    float mfma_min_reuse;        /* entries per condensed column from which a window goes there (< 0: never) */
+} ftc_plan;
+
+/* Host-only, pure.  sum_deg_sq from ftc_degree_stats, sum_uniq = summary[0] of ftc_build_windows. */
+int32_t ftc_plan_graph(int32_t n, int32_t nnz, int64_t sum_deg_sq, int64_t sum_uniq, int32_t D,
+                       int32_t dtype, ftc_plan *plan);
 
 /*
  * Measurement aid (no part of the method): enqueues the bare gather pattern of the aggregation

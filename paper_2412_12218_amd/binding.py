@@ -58,6 +58,8 @@ _SIGNATURES = {
     "ftc_degree_order": (_I, [_P, _I, _P, _P, _P, _Z, _P]),
     "ftc_permute_graph": (_I, [_P, _P, _P, _P, _P, _P, _P, _Z, _P]),
     "ftc_permute_rows": (_I, [_I, _P, _I, _I, _I, _P, _P, _I, _P]),
+    "ftc_degree_stats": (_I, [_P, _P, _P]),
+    "ftc_plan_graph": (_I, [_I, _I, C.c_int64, C.c_int64, _I, _I, _P]),
     "ftc_gather_probe": (_I, [_P, C.c_int64, _P, _I, _I, _P, _P]),
 }
 EXPORTS = list(_SIGNATURES)
@@ -401,3 +403,27 @@ def ftc_permute_rows(X, index, out=None):
     _check(lib().ftc_permute_rows(C.c_int32(n), _ptr(X), C.c_int32(X.stride(0)), C.c_int32(_dt(X)), C.c_int32(D),
                                   _ptr(index), _ptr(out), C.c_int32(out.stride(0)), _stream()))
     return out
+
+
+# ---- per-graph plan -------------------------------------------------------------------------------------
+FTC_ORDER_NONE = -1
+
+
+class ftc_plan(C.Structure):
+    _fields_ = [("skew", C.c_double), ("reuse", C.c_double), ("reorder", C.c_int32), ("agnn_single_pass", C.c_int32),
+                ("agnn_backward_single_pass", C.c_int32), ("spmm_mfma_windows", C.c_int32),
+                ("sddmm_mfma_windows", C.c_int32), ("mfma_min_reuse", C.c_float)]
+
+
+def ftc_degree_stats(g):
+    stats = torch.empty(2, dtype=torch.int64, device=g.row_ptr.device)
+    _check(lib().ftc_degree_stats(C.byref(g.c), _ptr(stats), _stream()))
+    return stats
+
+
+def ftc_plan_graph(n, nnz, sum_deg_sq, sum_uniq, D, dtype):
+    """Host-only: the per-graph choices as a dict (dtype: a torch dtype)."""
+    plan = ftc_plan()
+    _check(lib().ftc_plan_graph(C.c_int32(n), C.c_int32(nnz), C.c_int64(int(sum_deg_sq)), C.c_int64(int(sum_uniq)),
+                                C.c_int32(D), C.c_int32(_DTYPES[dtype]), C.byref(plan)))
+    return {name: getattr(plan, name) for name, _ in ftc_plan._fields_}

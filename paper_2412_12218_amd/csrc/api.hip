@@ -659,4 +659,42 @@ int32_t ftc_permute_rows(int32_t n, const void *X, int32_t ldx, int32_t dtype, i
     return launch_permute_rows(n, X, ldx, dtype, D, map, out, ldo, static_cast<hipStream_t>(stream));
 }
 
+// ---- per-graph plan --------------------------------------------------------------------------------
+int32_t ftc_degree_stats(const ftc_csr *g, int64_t *stats, void *stream)
+{
+    FTC_TRY(check_csr(g, "ftc_degree_stats"));
+    if (!stats) return fail(FTC_EINVAL, "ftc_degree_stats: stats is NULL");
+    return launch_degree_stats(*g, stats, static_cast<hipStream_t>(stream));
+}
+
+// Thresholds of the plan, from measurements on the benchmark graphs (bench.py --reorder, --sweep):
+// relabelling by degree class paid 5 to 17 % on the gather kernels of the graphs with skew 7.8, 9.3
+// and 70 and nothing on those with skew 1.03 and 1.1; it cannot pay while the whole feature matrix
+// fits the 4 MiB L2 of one XCD.
+static constexpr double PLAN_SKEW_MIN = 2.0;
+static constexpr double PLAN_L2_BYTES = 4.0 * 1024 * 1024;
+
+int32_t ftc_plan_graph(int32_t n, int32_t nnz, int64_t sum_deg_sq, int64_t sum_uniq, int32_t D, int32_t dtype,
+                       ftc_plan *plan)
+{
+    if (!plan) return fail(FTC_EINVAL, "ftc_plan_graph: plan is NULL");
+    if (n < 0 || nnz < 0 || D < 1 || !valid_dtype(dtype) || sum_deg_sq < 0 || sum_uniq < 0 || sum_uniq > nnz)
+        return fail(FTC_EINVAL, "ftc_plan_graph: bad argument");
+    plan->skew = nnz > 0 ? static_cast<double>(n) * static_cast<double>(sum_deg_sq) /
+                               (static_cast<double>(nnz) * static_cast<double>(nnz))
+                         : 0.0;
+    plan->reuse = sum_uniq > 0 ? static_cast<double>(nnz) / static_cast<double>(sum_uniq) : 0.0;
+    const double feature_bytes = static_cast<double>(n) * D * elem_size(dtype);
+    plan->reorder = (plan->skew >= PLAN_SKEW_MIN && feature_bytes > PLAN_L2_BYTES) ? FTC_ORDER_DEGREE_CLASSES : FTC_ORDER_NONE;
+    int vec, lpr;
+    const bool seg = seg_shape(dtype, D, &vec, &lpr);
+    plan->agnn_single_pass = seg ? 1 : 0;
+    plan->agnn_backward_single_pass = agnn_backward_fused_shape(dtype, D) ? 1 : 0;
+    // FTC_PATH_AUTO splits the windows between the two kernels only where the matrix cores can win
+    plan->spmm_mfma_windows = (mfma_shape_ok(dtype, D) && spmm_mfma_reuse(D) >= 0.f) ? 1 : 0;
+    plan->sddmm_mfma_windows = (mfma_shape_ok(dtype, D) && sddmm_mfma_reuse(D) >= 0.f) ? 1 : 0;
+    plan->mfma_min_reuse = sddmm_mfma_reuse(D);
+    return FTC_OK;
+}
+
 }  // extern "C"

@@ -221,6 +221,47 @@ static int bit_length(uint32_t x)
     return b;
 }
 
+// ---- degree statistics ---------------------------------------------------------------------------
+// stats[0] = sum of squared row lengths, stats[1] = longest row (both exact integers).
+__global__ __launch_bounds__(256) void degree_stats_kernel(int n, const int *__restrict__ row_ptr,
+                                                           unsigned long long *__restrict__ stats)
+{
+    __shared__ unsigned long long red_s[4], red_m[4];
+    unsigned long long sq = 0, mx = 0;
+    for (int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x; i < n; i += static_cast<int64_t>(gridDim.x) * 256) {
+        const unsigned long long d = static_cast<unsigned long long>(row_ptr[i + 1] - row_ptr[i]);
+        sq += d * d;
+        mx = d > mx ? d : mx;
+    }
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) {
+        sq += __shfl_xor(sq, m, 64);
+        const unsigned long long o = __shfl_xor(mx, m, 64);
+        mx = o > mx ? o : mx;
+    }
+    if ((threadIdx.x & 63) == 0) { red_s[threadIdx.x >> 6] = sq; red_m[threadIdx.x >> 6] = mx; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        unsigned long long m2 = red_m[0];
+        for (int w = 1; w < 4; ++w) m2 = red_m[w] > m2 ? red_m[w] : m2;
+        atomicAdd(&stats[0], red_s[0] + red_s[1] + red_s[2] + red_s[3]);
+        atomicMax(&stats[1], m2);
+    }
+}
+
+__global__ void clear_stats_kernel(unsigned long long *stats) { stats[0] = 0; stats[1] = 0; }
+
+int32_t launch_degree_stats(const ftc_csr &g, int64_t *stats, hipStream_t s)
+{
+    unsigned long long *st = reinterpret_cast<unsigned long long *>(stats);
+    hipLaunchKernelGGL(clear_stats_kernel, dim3(1), dim3(1), 0, s, st);
+    if (g.n > 0) {
+        const int blocks = (g.n + 255) / 256 < 1024 ? (g.n + 255) / 256 : 1024;
+        hipLaunchKernelGGL(degree_stats_kernel, dim3(blocks), dim3(256), 0, s, g.n, g.row_ptr, st);
+    }
+    return launch_status("degree statistics");
+}
+
 // ---- degree order --------------------------------------------------------------------------------
 // key = largest key - (degree or its bit length): ascending sort = descending degree; value = node id
 __global__ __launch_bounds__(256) void degree_keys_kernel(int n, const int *__restrict__ row_ptr, int mode,

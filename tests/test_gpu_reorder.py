@@ -151,3 +151,21 @@ def test_layers_on_the_relabelled_graph_match_the_original(oracle, graphs, name)
     err = norm_err(out, ref, ab)
     say(f"agnn layer through the reordering, {name}: err {err:.3e}")
     assert err < TOL[F16]
+
+
+@pytest.mark.parametrize("name", ["cfg1", "cfg5s", "skewed", "no_edges"])
+def test_degree_stats_and_plan_from_device_numbers(graphs, name):
+    """Sum of squared row lengths and longest row, exact; then the plan from the numbers the device
+    produced (statistics + the window build's summary)."""
+    g = graphs[name]
+    deg = np.diff(g.row_ptr).astype(np.int64)
+    dg = dev_graph(g)
+    stats = B.ftc_degree_stats(dg).cpu().numpy()
+    assert int(stats[0]) == int((deg * deg).sum()) and int(stats[1]) == int(deg.max())
+    win = B.ftc_build_windows(dg)
+    plan = B.ftc_plan_graph(g.n, g.nnz, int(stats[0]), int(win.summary[0].item()), 32, F16)
+    say(f"plan {name}: {plan}")
+    expect = name in ("cfg5s",) and g.n * 64 > 4 << 20
+    assert (plan["reorder"] != B.FTC_ORDER_NONE) == expect
+    if g.nnz:
+        assert plan["reuse"] >= 1.0 and plan["skew"] >= 1.0 - 1e-9
