@@ -591,7 +591,7 @@ int32_t ftc_agnn_layer_backward_fused(const ftc_csr *g, const ftc_windows *w, co
         return fail(FTC_EINVAL, "ftc_agnn_layer_backward_fused: H and dY need the same leading dimension");
     if (!w) return fail(FTC_EINVAL, "ftc_agnn_layer_backward_fused: the window index is required");
     FTC_TRY(check_windows(g, w, "ftc_agnn_layer_backward_fused", false));
-    if (!w->edge_to_row) return fail(FTC_EINVAL, "ftc_agnn_layer_backward_fused: edge_to_row is NULL");
+    if (g->nnz > 0 && !w->edge_to_row) return fail(FTC_EINVAL, "ftc_agnn_layer_backward_fused: edge_to_row is NULL");
     const bool rows16 = aligned16(H) && aligned16(dY) && (static_cast<int64_t>(ld) * elem_size(dtype)) % 16 == 0;
     if (!rows16 || !agnn_backward_fused_shape(dtype, D))
         return fail(FTC_EUNSUPPORTED,

@@ -330,6 +330,26 @@ def test_agnn_fused_backward_matches_the_unfused_route_on_hub_rows():
     assert torch.all(dH_f[empty] == 0) and torch.all(row_z[empty] == 0)
 
 
+def test_backward_on_a_graph_without_entries():
+    g = synth.Graph(70, np.zeros(71, dtype=np.int32), np.zeros(0, dtype=np.int32), "no_edges")
+    dg = dev_graph(g)
+    win = B.ftc_build_windows(dg)
+    H = torch.from_numpy(synth.normal_features(70, 16, seed=1)).to(F16).cuda()
+    dY = torch.from_numpy(synth.normal_features(70, 16, seed=2)).to(F16).cuda()
+    z = torch.full((70,), -1.0, dtype=F32, device="cuda")
+    Y = B.ftc_agnn_layer(dg, win, H, row_z=z)
+    assert torch.all(Y == 0) and torch.all(z == 0)
+    dH, dbeta = B.ftc_agnn_layer_backward_fused(dg, win, H, z, Y, dY)
+    assert torch.all(dH == 0) and float(dbeta.item()) == 0.0
+    T, flag = B.ftc_transpose_index(dg, win)
+    p = torch.empty(0, dtype=F32, device="cuda")
+    dH2, dbeta2 = B.ftc_agnn_layer_backward(dg, win, T, H, p, dY)
+    assert torch.all(dH2 == 0) and float(dbeta2.item()) == 0.0
+    W = torch.from_numpy(synth.glorot_uniform(16, 8, seed=3)).to(F16).cuda()
+    dX, dW = B.ftc_gcn_layer_backward(dg, win, None, H, W, torch.ones((70, 8), dtype=F32, device="cuda"))
+    assert torch.all(dX == 0) and torch.all(dW == 0)
+
+
 def test_agnn_row_z_needs_the_single_pass_route(graphs):
     g = graphs["cfg1"]
     dg = dev_graph(g)
