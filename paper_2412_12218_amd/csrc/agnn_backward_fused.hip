@@ -457,7 +457,7 @@ int32_t launch_agnn_backward_fused(const ftc_csr &g, const ftc_windows &w, const
     const unsigned grid2 = static_cast<unsigned>(blocks_rows > blocks_ranges ? blocks_rows : blocks_ranges);
     hipLaunchKernelGGL(spmm_seg_fixup_kernel, dim3(grid2), dim3(256), 0, s, n, n_ranges, g.row_ptr, carry, tail_row, dp2,
                        dp2, static_cast<void *>(QA), dp2, static_cast<int>(FTC_F32), Epi{0, nullptr},
-                       static_cast<const uint8_t *>(nullptr));
+                       static_cast<const uint8_t *>(nullptr), SEG_R);
     hipLaunchKernelGGL(dbeta_sum_kernel, dim3(1), dim3(1024), 0, s, n_ranges, dbeta_part, dbeta);
     int32_t st = launch_status("agnn_backward_fused fixup");
     if (st != FTC_OK) return st;

@@ -51,6 +51,10 @@ int32_t launch_gcn_norm(const ftc_csr &g, const ftc_windows *w, float *vals, flo
 int32_t launch_validate(const ftc_csr &g, int32_t *flag, hipStream_t s);
 bool seg_shape(int dtype, int D, int *vec, int *lpr);
 size_t spmm_seg_ws(int nnz, int D);
+bool spmm_lane_shape(int xdt, int D, int ldx);
+size_t spmm_lane_ws(int nnz);
+int32_t launch_spmm_lane(const ftc_csr &g, const ftc_windows &w, const float *vals, const void *X, int ldx, int xdt,
+                         int D, void *out, int ldo, int odt, Epi epi, void *ws, hipStream_t s);
 int32_t launch_spmm_seg(const ftc_csr &g, const ftc_windows &w, const float *vals, const void *X, int ldx,
                         int xdt, int D, void *out, int ldo, int odt, Epi epi, void *ws, const uint8_t *dense,
                         hipStream_t s);
@@ -329,7 +333,7 @@ __device__ __forceinline__ float group_sum_dpp(float v)
 __global__ void spmm_seg_fixup_kernel(int n, int n_ranges, const int *__restrict__ row_ptr,
                                       const float *__restrict__ carry, const int *__restrict__ carry_tail_row, int DP,
                                       int D, void *__restrict__ out, int ldo, int odt, Epi epi,
-                                      const uint8_t *__restrict__ dense);
+                                      const uint8_t *__restrict__ dense, int seg_r);
 
 // Inclusive prefix sum over the 64 lanes of a wave with data-parallel-primitive moves: shifts by
 // 1, 2, 4, 8 inside rows of 16 lanes, then lane 15 of a row added to the next row (rows 1 and 3) and

@@ -52,7 +52,9 @@ size_t spmm_seg_ws(int nnz, int D)
     if (seg_shape(FTC_F16, D, &vec, &lpr) && vec * lpr > dp) dp = vec * lpr;
     if (dp == 0 || nnz == 0) return 0;
     const size_t n_ranges = (static_cast<size_t>(nnz) + SEG_R - 1) / SEG_R;
-    return align_up(n_ranges * 2 * dp * sizeof(float), 256) + align_up(n_ranges * 2 * sizeof(int), 256);
+    const size_t seg = align_up(n_ranges * 2 * dp * sizeof(float), 256) + align_up(n_ranges * 2 * sizeof(int), 256);
+    const size_t lane = D <= 8 ? spmm_lane_ws(nnz) : 0;  // narrow rows may take the lane-per-edge kernel
+    return seg > lane ? seg : lane;
 }
 
 // VALS = false: all edge values are one (vals == NULL): nothing is staged or multiplied for them, which
@@ -248,7 +250,7 @@ __global__ __launch_bounds__(256) void spmm_seg_fixup_kernel(int n, int n_ranges
                                                              const float *__restrict__ carry,
                                                              const int *__restrict__ carry_tail_row, int DP,
                                                              int D, void *__restrict__ out, int ldo, int odt,
-                                                             Epi epi, const uint8_t *__restrict__ dense)
+                                                             Epi epi, const uint8_t *__restrict__ dense, int seg_r)
 {
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int v = blockIdx.x * 4 + wave;
@@ -273,7 +275,7 @@ __global__ __launch_bounds__(256) void spmm_seg_fixup_kernel(int n, int n_ranges
                 if (d < D) store_elem(out, static_cast<int64_t>(r) * ldo + d, odt, epi.apply(epi.factor(r), spec[i]));
             }
         } else if (r >= 0 && !(dense && dense[r >> 4])) {
-            const int last = (row_ptr[r + 1] - 1) / SEG_R;  // wave range holding the row's final edge
+            const int last = (row_ptr[r + 1] - 1) / seg_r;  // wave range holding the row's final edge
             // A hub row can span hundreds of ranges.  The 64 lanes are split into `parts` teams of
             // `dl` lanes (one lane per feature); team p adds the head pieces of ranges v+1+p,
             // v+1+p+parts, ... four at a time, then the teams' sums are added in team order.  The
@@ -345,6 +347,9 @@ int32_t launch_spmm_seg(const ftc_csr &g, const ftc_windows &w, const float *val
                         int xdt, int D, void *out, int ldo, int odt, Epi epi, void *ws, const uint8_t *dense,
                         hipStream_t s)
 {
+    // rows of at most 16 bytes: a lane per edge run instead of four lanes per row
+    if (!dense && spmm_lane_shape(xdt, D, ldx))
+        return launch_spmm_lane(g, w, vals, X, ldx, xdt, D, out, ldo, odt, epi, ws, s);
     int vec = 0, lpr = 0;
     seg_shape(xdt, D, &vec, &lpr);
     const int dp = vec * lpr;
@@ -370,7 +375,7 @@ int32_t launch_spmm_seg(const ftc_csr &g, const ftc_windows &w, const float *val
     const int64_t blocks_ranges = (n_ranges + 3) / 4;
     const unsigned grid2 = static_cast<unsigned>(blocks_rows > blocks_ranges ? blocks_rows : blocks_ranges);
     hipLaunchKernelGGL(spmm_seg_fixup_kernel, dim3(grid2), dim3(256), 0, s, g.n, n_ranges, g.row_ptr, carry,
-                       tail_row, dp, D, out, ldo, odt, epi, dense);
+                       tail_row, dp, D, out, ldo, odt, epi, dense, SEG_R);
     return launch_status("spmm_seg fixup");
 }
 

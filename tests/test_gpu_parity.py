@@ -205,7 +205,7 @@ def run_spmm(oracle, g, dtype, D, *, use_vals=True, with_windows=True, relu=Fals
     vd = torch.from_numpy(vals32).cuda() if use_vals else None
     out = torch.full((g.n, D + pad), 777.0, dtype=out_dtype, device="cuda")[:, :D]
     B.ftc_spmm(dg, win, vd, Xd, out=out, relu=relu, path=path)
-    out2 = torch.empty((g.n, D), dtype=out_dtype, device="cuda")
+    out2 = torch.empty((g.n, D + pad), dtype=out_dtype, device="cuda")[:, :D]    # the same call once more
     B.ftc_spmm(dg, win, vd, Xd, out=out2, relu=relu, path=path)
     torch.cuda.synchronize()
     assert torch.equal(out, out2), "two runs differ"
@@ -230,6 +230,19 @@ def test_spmm_odd_shapes(oracle, graphs, dtype, D, pad):
     say(f"spmm odd {dtype} D={D} pad={pad}")
     assert run_spmm(oracle, graphs["cfg1"], dtype, D, pad=pad) < TOL[dtype]
     assert run_spmm(oracle, graphs["hub"], dtype, D, pad=pad) < TOL[dtype]
+
+
+@pytest.mark.parametrize("name", ["cfg1", "cfg5s", "hub"])
+@pytest.mark.parametrize("dtype,D,pad", [(F16, 8, 0), (F16, 16, 0), (BF16, 16, 16), (F16, 12, 4), (F16, 6, 2), (F32, 8, 0),
+                                         (F32, 6, 2), (F32, 4, 4), (BF16, 2, 6)])
+def test_spmm_narrow_rows(oracle, graphs, name, dtype, D, pad):
+    """Rows of at most 16 bytes take the lane-per-edge kernel (the wider ones here the four-lane
+    layout): with and without edge values, ReLU, 16-bit output, widths below the padded 16 bytes."""
+    g = graphs[name]
+    say(f"spmm narrow {name} {dtype} D={D} pad={pad}")
+    assert run_spmm(oracle, g, dtype, D, pad=pad) < TOL[dtype]
+    assert run_spmm(oracle, g, dtype, D, pad=pad, use_vals=False, relu=True) < TOL[dtype]
+    assert run_spmm(oracle, g, dtype, D, pad=pad, out_dtype=F16, seed=3) < TOL[dtype]
 
 
 @pytest.mark.parametrize("out_dtype", [F16, BF16])
