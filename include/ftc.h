@@ -302,7 +302,8 @@ int32_t ftc_agnn_layer_backward(const ftc_csr *g, const ftc_windows *w, const in
  * <dY_i, Y_i> = sum over row i of p * dp, so a 16-bit Y costs accuracy -- a few 1e-3 of a row's
  * largest gradient entry with bf16 -- and out_f32 of the forward call is the better choice).
  * H and dY share dtype and leading dimension, rows 16-byte aligned; the window index is required;
- * D up to 128 (fp32: 64 when D is not a multiple of 4).  FTC_EUNSUPPORTED otherwise: use
+ * (dtype, D) must be a width the single-pass forward covers, with at most 128 elements once
+ * padded to its lane layout (ftc_plan_graph reports it).  FTC_EUNSUPPORTED otherwise: use
  * ftc_agnn_layer_backward.  The pattern is taken to be symmetric (ftc_transpose_index, flag 0,
  * checks it); on another pattern the result is the gradient of nothing.
  */
