@@ -147,12 +147,18 @@ __global__ __launch_bounds__(256) void radix_scatter_kernel(const uint32_t *__re
     wave_lds_fence();
     const int64_t base = tile * RX_TILE;
     const uint64_t below = (1ull << lane) - 1ull;
+    // the whole tile is loaded before the first element is placed: 2 * RX_ROUNDS loads in flight per lane
+    uint32_t key[RX_ROUNDS], val[RX_ROUNDS];
+#pragma unroll
     for (int r = 0; r < RX_ROUNDS; ++r) {
         const int64_t i = base + r * 64 + lane;
-        const bool ok = i < count;
-        const uint32_t key = ok ? keys[i] : 0u;
-        const uint32_t val = ok ? vals[i] : 0u;
-        const uint32_t d = (key >> shift) & 255u;
+        key[r] = i < count ? keys[i] : 0u;
+        val[r] = i < count ? vals[i] : 0u;
+    }
+#pragma unroll
+    for (int r = 0; r < RX_ROUNDS; ++r) {
+        const bool ok = base + r * 64 + lane < count;
+        const uint32_t d = (key[r] >> shift) & 255u;
         uint64_t peers = __builtin_amdgcn_ballot_w64(ok);  // lanes that hold the same digit
 #pragma unroll
         for (int b = 0; b < 8; ++b) {
@@ -166,8 +172,8 @@ __global__ __launch_bounds__(256) void radix_scatter_kernel(const uint32_t *__re
         if (ok && rank == 0) next[d] = first + __popcll(peers);
         wave_lds_fence();
         if (ok) {
-            keys_out[first + rank] = key;
-            vals_out[first + rank] = val;
+            keys_out[first + rank] = key[r];
+            vals_out[first + rank] = val[r];
         }
     }
 }
