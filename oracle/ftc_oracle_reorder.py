@@ -59,3 +59,36 @@ def permute_graph(row_ptr, col_idx, perm, inv):
 def permute_rows(X, index):
     """out[r] = X[index[r]]: index = perm carries rows into the new numbering, index = inv back."""
     return np.asarray(X)[np.asarray(index, dtype=np.int64)]
+
+
+def order_by_key(keys):
+    """(perm, inv) of the ascending order of `keys`, ties by ascending id: nodes with the same key (for
+    instance the same community label) become neighbours in the new numbering."""
+    keys = np.asarray(keys, dtype=np.int64)
+    n = keys.size
+    perm = np.array(sorted(range(n), key=lambda i: (int(keys[i]), i)), dtype=np.int64)
+    inv = np.empty(n, dtype=np.int64)
+    inv[perm] = np.arange(n)
+    return perm, inv
+
+
+def label_propagation(row_ptr, col_idx, iters):
+    """Synchronous label propagation, the community heuristic behind the community ordering: every node
+    starts with its own id as label; in each of `iters` rounds every node takes the label that occurs
+    most often among the stored entries of its row (duplicates count, a self-loop counts the node's
+    own label), the smallest such label on a tie, all nodes at once from the labels of the previous
+    round.  A node without entries keeps its label.  Returns the labels after the last round."""
+    row_ptr = np.asarray(row_ptr, dtype=np.int64)
+    col = np.asarray(col_idx, dtype=np.int64)
+    n = row_ptr.size - 1
+    label = np.arange(n, dtype=np.int64)
+    for _ in range(iters):
+        new = label.copy()
+        for i in range(n):
+            nb = label[col[row_ptr[i]:row_ptr[i + 1]]]
+            if nb.size == 0:
+                continue
+            values, counts = np.unique(nb, return_counts=True)     # values ascending
+            new[i] = values[np.argmax(counts)]                      # first maximum = smallest label
+        label = new
+    return label

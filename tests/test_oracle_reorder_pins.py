@@ -94,3 +94,54 @@ def test_degree_order_concentrates_the_columns_of_a_skewed_graph(oracle):
     before = oracle.build_windows(g.row_ptr, g.col_idx)["summary"][0]
     after = oracle.build_windows(rp.astype(np.int32), ci.astype(np.int32))["summary"][0]
     assert after < before
+
+
+def csr_of(n, pairs):
+    rows = [[] for _ in range(n)]
+    for a, b in pairs:
+        rows[a].append(b)
+    row_ptr = np.concatenate([[0], np.cumsum([len(r) for r in rows])])
+    col = np.array([c for r in rows for c in r], dtype=np.int64)
+    return row_ptr, col
+
+
+def test_label_propagation_hand_worked_round():
+    # path 0 - 1 - 2 with self-loops, plus node 3 without entries and node 4 pointing twice at 2 and once at 0
+    row_ptr, col = csr_of(5, [(0, 0), (0, 1), (1, 0), (1, 1), (1, 2), (2, 1), (2, 2), (4, 2), (4, 2), (4, 0)])
+    # round 1 from labels 0..4: node 0 sees {0, 1} -> tie -> 0; node 1 sees {0, 1, 2} -> 0; node 2 sees {1, 2} -> 1;
+    # node 3 keeps 3; node 4 sees {2, 2, 0} -> 2
+    assert R.label_propagation(row_ptr, col, 1).tolist() == [0, 0, 1, 3, 2]
+    # round 2 from [0, 0, 1, 3, 2]: node 0 sees {0, 0} -> 0; node 1 sees {0, 0, 1} -> 0; node 2 sees {0, 1} -> 0;
+    # node 4 sees {1, 1, 0} -> 1
+    assert R.label_propagation(row_ptr, col, 2).tolist() == [0, 0, 0, 3, 1]
+    assert R.label_propagation(row_ptr, col, 0).tolist() == [0, 1, 2, 3, 4]
+
+
+def test_label_propagation_separates_disjoint_cliques():
+    a, b = [0, 2, 4, 6, 8], [1, 3, 5, 7, 9, 10]
+    pairs = [(u, v) for grp in (a, b) for u in grp for v in grp]
+    row_ptr, col = csr_of(11, pairs)
+    lab = R.label_propagation(row_ptr, col, 3)
+    assert set(lab[a]) == {0} and set(lab[b]) == {1}
+
+
+def test_label_propagation_recovers_a_planted_partition():
+    """Stochastic block model with permuted ids: after ten rounds nearly every node carries the label of
+    its planted community (the generator's permutation is undone through the edges themselves: two
+    nodes joined by an in-community edge get the same label)."""
+    g = synth.sbm(12, 200, 14 * 12 * 200, 2 * 12 * 200, seed=5)
+    lab = R.label_propagation(g.row_ptr, g.col_idx, 10)
+    values, counts = np.unique(lab, return_counts=True)
+    big = values[counts >= 100]
+    assert big.size == 12                                   # one label per planted community ...
+    assert counts[counts >= 100].sum() >= 0.97 * g.n        # ... holding nearly all nodes
+    rows = np.repeat(np.arange(g.n), np.diff(g.row_ptr))
+    same = lab[rows] == lab[g.col_idx]
+    assert same.mean() > 0.85                               # 14 of 16 sampled pairs are in-community
+
+
+def test_order_by_key_groups_equal_keys_and_keeps_their_order():
+    keys = np.array([7, 3, 7, 0, 3, 3, 9, 0])
+    perm, inv = R.order_by_key(keys)
+    assert perm.tolist() == [3, 7, 1, 4, 5, 0, 2, 6]
+    assert np.array_equal(inv[perm], np.arange(8))
