@@ -272,16 +272,21 @@ def reorder_suite(iters=10):
         print(json.dumps({"graph": f"cfg{cfg}", "n": g.n, "nnz": g.nnz, "D": D, "ordering": "as given", **base,
                           "plan": plan}), flush=True)
         ws = B._workspace(B.lib().ftc_reorder_workspace_bytes(g.n, g.nnz), dev)
-        for mode, tag in ((B.FTC_ORDER_DEGREE, "degree"), (B.FTC_ORDER_DEGREE_CLASSES, "degree classes")):
-            t_order = ms_of(lambda: B.ftc_degree_order(dg, mode, ws=ws), 5)
-            perm, inv = B.ftc_degree_order(dg, mode, ws=ws)
+        for mode, tag in ((B.FTC_ORDER_DEGREE, "degree"), (B.FTC_ORDER_DEGREE_CLASSES, "degree classes"),
+                          (None, "communities (10 rounds of label propagation)")):
+            if mode is None:
+                order = lambda: B.ftc_order_by_key(B.ftc_label_propagation(dg, 10, ws=ws), ws=ws)[:2]
+            else:
+                order = lambda: B.ftc_degree_order(dg, mode, ws=ws)
+            t_order = ms_of(order, 3)
+            perm, inv = order()
             t_graph = ms_of(lambda: B.ftc_permute_graph(dg, perm, inv, ws=ws), 5)
             pg, flag = B.ftc_permute_graph(dg, perm, inv, ws=ws)
             assert int(flag.item()) == 0
             Xf = torch.randn(g.n, D, device=dev).to(dtype)
             t_rows = ms_of(lambda: B.ftc_permute_rows(Xf, perm))
             r = kernels(pg, D, dtype)
-            print(json.dumps({"graph": f"cfg{cfg}", "ordering": tag, "degree_order_ms": t_order, "permute_graph_ms": t_graph,
+            print(json.dumps({"graph": f"cfg{cfg}", "ordering": tag, "ordering_ms": t_order, "permute_graph_ms": t_graph,
                               "permute_rows_ms": t_rows, **r}), flush=True)
             del pg, perm, inv
         del dg, ws

@@ -333,12 +333,31 @@ enum {
                                      ascending id -- keeps the given order inside a class */
 };
 
-/* Workspace of ftc_degree_order and ftc_permute_graph. */
+/* Workspace of ftc_degree_order, ftc_order_by_key, ftc_label_propagation and ftc_permute_graph. */
 size_t ftc_reorder_workspace_bytes(int32_t n, int32_t nnz);
 
 /* perm and inv of the ordering `mode` of g's nodes. */
 int32_t ftc_degree_order(const ftc_csr *g, int32_t mode, int32_t *perm, int32_t *inv, void *ws,
                          size_t ws_bytes, void *stream);
+
+/*
+ * perm and inv of the ascending order of keys[0 .. n) (device, int32, >= 0), ties by ascending id:
+ * nodes with equal keys -- the same community label, say -- become neighbours in the new numbering.
+ * *flag (device int32) becomes 1 if a key is negative (it is then ordered as 0), else 0.
+ */
+int32_t ftc_order_by_key(int32_t n, const int32_t *keys, int32_t *perm, int32_t *inv,
+                         int32_t *flag, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Community labels by synchronous label propagation, for a community ordering with
+ * ftc_order_by_key: every node starts with its own id; in each of `rounds` rounds every node takes
+ * the label that occurs most often among the stored entries of its row (duplicates count, a
+ * self-loop counts the node's own label; the smallest label on a tie), all nodes at once from the
+ * labels of the round before; a row without entries keeps its label.  labels: device int32[n].
+ * Ten rounds recover the blocks of the stochastic-block-model benchmark graph.  Unique result.
+ */
+int32_t ftc_label_propagation(const ftc_csr *g, int32_t rounds, int32_t *labels, void *ws,
+                              size_t ws_bytes, void *stream);
 
 /*
  * Relabelled graph: row `new` of the output holds the entries of row perm[new] of g with every

@@ -56,6 +56,8 @@ _SIGNATURES = {
     "ftc_agnn_layer_backward_fused": (_I, [_P, _P, _P, _I, _I, _I, _F, _P, _P, _I, _I, _P, _I, _P, _I, _I, _P, _P, _Z, _P]),
     "ftc_reorder_workspace_bytes": (_Z, [_I, _I]),
     "ftc_degree_order": (_I, [_P, _I, _P, _P, _P, _Z, _P]),
+    "ftc_order_by_key": (_I, [_I, _P, _P, _P, _P, _P, _Z, _P]),
+    "ftc_label_propagation": (_I, [_P, _I, _P, _P, _Z, _P]),
     "ftc_permute_graph": (_I, [_P, _P, _P, _P, _P, _P, _P, _Z, _P]),
     "ftc_permute_rows": (_I, [_I, _P, _I, _I, _I, _P, _P, _I, _P]),
     "ftc_degree_stats": (_I, [_P, _P, _P]),
@@ -381,6 +383,30 @@ def ftc_degree_order(g, mode=FTC_ORDER_DEGREE, ws=None):
     _check(lib().ftc_degree_order(C.byref(g.c), C.c_int32(mode), _ptr(perm), _ptr(inv), _ptr(ws),
                                   C.c_size_t(ws.numel()), _stream()))
     return perm, inv
+
+
+def ftc_order_by_key(keys, ws=None):
+    """Returns (perm, inv, flag): ascending keys, ties by id."""
+    n = keys.numel()
+    dev = keys.device
+    perm = torch.empty(n, dtype=torch.int32, device=dev)
+    inv = torch.empty(n, dtype=torch.int32, device=dev)
+    flag = torch.empty(1, dtype=torch.int32, device=dev)
+    if ws is None:
+        ws = _workspace(lib().ftc_reorder_workspace_bytes(n, 0), dev)
+    _check(lib().ftc_order_by_key(C.c_int32(n), _ptr(keys), _ptr(perm), _ptr(inv), _ptr(flag), _ptr(ws),
+                                  C.c_size_t(ws.numel()), _stream()))
+    return perm, inv, flag
+
+
+def ftc_label_propagation(g, rounds=10, ws=None):
+    dev = g.row_ptr.device
+    labels = torch.empty(g.n, dtype=torch.int32, device=dev)
+    if ws is None:
+        ws = _workspace(lib().ftc_reorder_workspace_bytes(g.n, g.nnz), dev)
+    _check(lib().ftc_label_propagation(C.byref(g.c), C.c_int32(rounds), _ptr(labels), _ptr(ws), C.c_size_t(ws.numel()),
+                                       _stream()))
+    return labels
 
 
 def ftc_permute_graph(g, perm, inv, ws=None):

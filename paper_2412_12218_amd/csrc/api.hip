@@ -633,6 +633,26 @@ int32_t ftc_degree_order(const ftc_csr *g, int32_t mode, int32_t *perm, int32_t 
     return launch_degree_order(*g, mode, perm, inv, ws, static_cast<hipStream_t>(stream));
 }
 
+int32_t ftc_order_by_key(int32_t n, const int32_t *keys, int32_t *perm, int32_t *inv, int32_t *flag, void *ws,
+                         size_t ws_bytes, void *stream)
+{
+    if (n < 0) return fail(FTC_EINVAL, "ftc_order_by_key: negative n");
+    if (!flag) return fail(FTC_EINVAL, "ftc_order_by_key: flag is NULL");
+    if (n > 0 && (!keys || !perm || !inv)) return fail(FTC_EINVAL, "ftc_order_by_key: keys, perm or inv is NULL");
+    FTC_TRY(check_reorder_ws("ftc_order_by_key", n, 0, ws, ws_bytes));
+    return launch_order_by_key(n, keys, perm, inv, flag, ws, static_cast<hipStream_t>(stream));
+}
+
+int32_t ftc_label_propagation(const ftc_csr *g, int32_t rounds, int32_t *labels, void *ws, size_t ws_bytes, void *stream)
+{
+    FTC_TRY(check_csr(g, "ftc_label_propagation"));
+    if (rounds < 0) return fail(FTC_EINVAL, "ftc_label_propagation: negative number of rounds");
+    if (g->n == 0) return FTC_OK;
+    if (!labels) return fail(FTC_EINVAL, "ftc_label_propagation: labels is NULL");
+    FTC_TRY(check_reorder_ws("ftc_label_propagation", g->n, g->nnz, ws, ws_bytes));
+    return launch_label_propagation(*g, rounds, labels, ws, static_cast<hipStream_t>(stream));
+}
+
 int32_t ftc_permute_graph(const ftc_csr *g, const int32_t *perm, const int32_t *inv, int32_t *row_ptr_out,
                           int32_t *col_idx_out, int32_t *flag, void *ws, size_t ws_bytes, void *stream)
 {

@@ -100,6 +100,8 @@ int32_t launch_cos_backward_rows(int n, const void *H, int ld, int dt, int D, co
 // reorder.hip
 size_t reorder_ws(int n, int nnz);
 int32_t launch_degree_stats(const ftc_csr &g, int64_t *stats, hipStream_t s);
+int32_t launch_order_by_key(int n, const int *keys, int *perm, int *inv, int *flag, void *ws, hipStream_t s);
+int32_t launch_label_propagation(const ftc_csr &g, int iters, int *labels, void *ws, hipStream_t s);
 int32_t launch_degree_order(const ftc_csr &g, int mode, int *perm, int *inv, void *ws, hipStream_t s);
 int32_t launch_permute_graph(const ftc_csr &g, const int *perm, const int *inv, int *row_ptr_out, int *col_idx_out,
                              int *flag, void *ws, hipStream_t s);

@@ -227,6 +227,8 @@ static int bit_length(uint32_t x)
     return b;
 }
 
+__global__ void reorder_set_int_kernel(int *p, int v) { *p = v; }
+
 // ---- degree statistics ---------------------------------------------------------------------------
 // stats[0] = sum of squared row lengths, stats[1] = longest row (both exact integers).
 __global__ __launch_bounds__(256) void degree_stats_kernel(int n, const int *__restrict__ row_ptr,
@@ -286,10 +288,14 @@ __global__ __launch_bounds__(256) void invert_perm_kernel(int n, const int *__re
     if (r < n) inv[perm[r]] = r;
 }
 
+size_t label_propagation_ws(int n, int nnz);
+
 size_t reorder_ws(int n, int nnz)
 {
     const int64_t m = n > nnz ? n : nnz;
-    return 4 * align_up(static_cast<size_t>(m) * sizeof(uint32_t), 256) + radix_ws(m) + scan_ws(static_cast<int64_t>(n) + 1);
+    const size_t order = 4 * align_up(static_cast<size_t>(m) * sizeof(uint32_t), 256) + radix_ws(m) + scan_ws(static_cast<int64_t>(n) + 1);
+    const size_t lpa = label_propagation_ws(n, nnz);
+    return order > lpa ? order : lpa;
 }
 
 int32_t launch_degree_order(const ftc_csr &g, int mode, int *perm, int *inv, void *ws, hipStream_t s)
@@ -308,6 +314,176 @@ int32_t launch_degree_order(const ftc_csr &g, int mode, int *perm, int *inv, voi
     if (st != FTC_OK) return st;
     hipLaunchKernelGGL(invert_perm_kernel, dim3((n + 255) / 256), dim3(256), 0, s, n, perm, inv);
     return launch_status("degree order");
+}
+
+// ---- order by key ---------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void key_pairs_kernel(int n, const int *__restrict__ keys_in, uint32_t *__restrict__ keys,
+                                                        uint32_t *__restrict__ vals, int *flag)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    const int k = keys_in[i];
+    if (k < 0) atomicOr(flag, 1);  // negative keys are not ordered: reported, treated as 0
+    keys[i] = k < 0 ? 0u : static_cast<uint32_t>(k);
+    vals[i] = static_cast<uint32_t>(i);
+}
+
+int32_t launch_order_by_key(int n, const int *keys_in, int *perm, int *inv, int *flag, void *ws, hipStream_t s)
+{
+    hipLaunchKernelGGL(reorder_set_int_kernel, dim3(1), dim3(1), 0, s, flag, 0);
+    if (n == 0) return launch_status("order by key");
+    const size_t arr = align_up(static_cast<size_t>(n) * sizeof(uint32_t), 256);
+    char *p = static_cast<char *>(ws);
+    uint32_t *k0 = reinterpret_cast<uint32_t *>(p), *v0 = reinterpret_cast<uint32_t *>(p + arr);
+    uint32_t *k1 = reinterpret_cast<uint32_t *>(p + 2 * arr), *v1 = reinterpret_cast<uint32_t *>(p + 3 * arr);
+    void *ws_sort = p + 4 * arr;
+    hipLaunchKernelGGL(key_pairs_kernel, dim3((n + 255) / 256), dim3(256), 0, s, n, keys_in, k0, v0, flag);
+    uint32_t *kr, *vr;
+    const int32_t st = radix_sort_pairs(k0, v0, k1, v1, n, 31, reinterpret_cast<uint32_t *>(perm), &kr, &vr, ws_sort, s);
+    if (st != FTC_OK) return st;
+    hipLaunchKernelGGL(invert_perm_kernel, dim3((n + 255) / 256), dim3(256), 0, s, n, perm, inv);
+    return launch_status("order by key");
+}
+
+// ---- label propagation ---------------------------------------------------------------------------
+// Every round: pairs (label of the entry's column, row) sorted by label and then, stably, by row put
+// equal labels of a row side by side; a run of equal (row, label) is one candidate, its length the
+// number of votes.  The candidate with the most votes and, among those, the smallest label wins:
+// the maximum of (votes << 32 | ~label), taken with a 64-bit atomic maximum per row (the maximum
+// does not depend on the order of the updates, so the result is reproducible).
+__global__ __launch_bounds__(256) void entry_rows_kernel(int n, int nnz, const int *__restrict__ row_ptr,
+                                                         uint32_t *__restrict__ rows)
+{
+    const int64_t e = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (e >= nnz) return;
+    int a = 0, b = n;  // last row with row_ptr[row] <= e
+    while (b - a > 1) {
+        const int mid = (a + b) >> 1;
+        if (row_ptr[mid] <= e) a = mid; else b = mid;
+    }
+    rows[e] = static_cast<uint32_t>(a);
+}
+
+__global__ __launch_bounds__(256) void iota_kernel(int n, int *__restrict__ out)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n) out[i] = i;
+}
+
+__global__ __launch_bounds__(256) void gather_labels_kernel(int n, int nnz, const int *__restrict__ col_idx,
+                                                            const int *__restrict__ label,
+                                                            const uint32_t *__restrict__ rows,
+                                                            uint32_t *__restrict__ keys, uint32_t *__restrict__ vals)
+{
+    const int64_t e = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (e >= nnz) return;
+    const int c = col_idx[e];
+    keys[e] = (c >= 0 && c < n) ? static_cast<uint32_t>(label[c]) : 0u;  // a column out of range votes for label 0
+    vals[e] = rows[e];
+}
+
+// flags[p] = 1 where a run of equal (row, label) begins; sorted_rows / sorted_labels are grouped by row
+__global__ __launch_bounds__(256) void run_flags_kernel(int nnz, const uint32_t *__restrict__ sorted_rows,
+                                                        const uint32_t *__restrict__ sorted_labels, int *__restrict__ flags)
+{
+    const int64_t p = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (p >= nnz) return;
+    flags[p] = (p == 0 || sorted_rows[p] != sorted_rows[p - 1] || sorted_labels[p] != sorted_labels[p - 1]) ? 1 : 0;
+}
+
+// run_id[p] (exclusive scan of the flags) -> starts[run] = p at every run start
+__global__ __launch_bounds__(256) void run_starts_kernel(int nnz, const uint32_t *__restrict__ sorted_rows,
+                                                         const uint32_t *__restrict__ sorted_labels,
+                                                         const int *__restrict__ run_id, int *__restrict__ starts)
+{
+    const int64_t p = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (p >= nnz) return;
+    if (p == 0 || sorted_rows[p] != sorted_rows[p - 1] || sorted_labels[p] != sorted_labels[p - 1]) starts[run_id[p]] = static_cast<int>(p);
+}
+
+__global__ __launch_bounds__(256) void clear_u64_kernel(int n, unsigned long long *a)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n) a[i] = 0ull;
+}
+
+// one thread per run; n_runs = run_id[nnz] (the scan's total)
+__global__ __launch_bounds__(256) void run_votes_kernel(int nnz, const int *__restrict__ n_runs_ptr,
+                                                        const int *__restrict__ starts,
+                                                        const uint32_t *__restrict__ sorted_rows,
+                                                        const uint32_t *__restrict__ sorted_labels,
+                                                        unsigned long long *__restrict__ best)
+{
+    const int n_runs = *n_runs_ptr;
+    for (int64_t r = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x; r < n_runs; r += static_cast<int64_t>(gridDim.x) * 256) {
+        const int p = starts[r];
+        const int end = r + 1 < n_runs ? starts[r + 1] : nnz;
+        const unsigned long long cand = (static_cast<unsigned long long>(end - p) << 32) | (0xffffffffu - sorted_labels[p]);
+        atomicMax(&best[sorted_rows[p]], cand);
+    }
+}
+
+__global__ __launch_bounds__(256) void take_labels_kernel(int n, const unsigned long long *__restrict__ best,
+                                                          int *__restrict__ label)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    const unsigned long long b = best[i];
+    if (b != 0ull) label[i] = static_cast<int>(0xffffffffu - static_cast<uint32_t>(b & 0xffffffffull));
+}
+
+size_t label_propagation_ws(int n, int nnz)
+{
+    const int64_t m = n > nnz ? n : nnz;
+    const size_t arr = align_up(static_cast<size_t>(m) * sizeof(uint32_t), 256);
+    // rows, four pair buffers, run ids (+ total), starts, best votes, sort and scan scratch
+    return 5 * arr + 2 * align_up((static_cast<size_t>(m) + 1) * sizeof(int), 256) +
+           align_up(static_cast<size_t>(n) * sizeof(unsigned long long), 256) + radix_ws(m) + scan_ws(static_cast<int64_t>(m) + 1);
+}
+
+int32_t launch_label_propagation(const ftc_csr &g, int iters, int *labels, void *ws, hipStream_t s)
+{
+    const int n = g.n, nnz = g.nnz;
+    if (n == 0) return FTC_OK;
+    hipLaunchKernelGGL(iota_kernel, dim3((n + 255) / 256), dim3(256), 0, s, n, labels);
+    if (nnz == 0 || iters <= 0) return launch_status("label propagation");
+    const int64_t m = n > nnz ? n : nnz;
+    const size_t arr = align_up(static_cast<size_t>(m) * sizeof(uint32_t), 256);
+    const size_t arr1 = align_up((static_cast<size_t>(m) + 1) * sizeof(int), 256);
+    char *p = static_cast<char *>(ws);
+    uint32_t *rows = reinterpret_cast<uint32_t *>(p); p += arr;
+    uint32_t *k0 = reinterpret_cast<uint32_t *>(p); p += arr;
+    uint32_t *v0 = reinterpret_cast<uint32_t *>(p); p += arr;
+    uint32_t *k1 = reinterpret_cast<uint32_t *>(p); p += arr;
+    uint32_t *v1 = reinterpret_cast<uint32_t *>(p); p += arr;
+    int *run_id = reinterpret_cast<int *>(p); p += arr1;
+    int *starts = reinterpret_cast<int *>(p); p += arr1;
+    unsigned long long *best = reinterpret_cast<unsigned long long *>(p);
+    p += align_up(static_cast<size_t>(n) * sizeof(unsigned long long), 256);
+    void *ws_sort = p; p += radix_ws(m);
+    void *ws_scan = p;
+    const unsigned ge = static_cast<unsigned>((nnz + 255) / 256), gn = static_cast<unsigned>((n + 255) / 256);
+    hipLaunchKernelGGL(entry_rows_kernel, dim3(ge), dim3(256), 0, s, n, nnz, g.row_ptr, rows);
+    const int bits = bit_length(static_cast<uint32_t>(n - 1));
+    for (int it = 0; it < iters; ++it) {
+        hipLaunchKernelGGL(gather_labels_kernel, dim3(ge), dim3(256), 0, s, n, nnz, g.col_idx, labels, rows, k0, v0);
+        uint32_t *kr, *vr;  // after the first sort: keys = labels, values = rows
+        int32_t st = radix_sort_pairs(k0, v0, k1, v1, nnz, bits, nullptr, &kr, &vr, ws_sort, s);
+        if (st != FTC_OK) return st;
+        uint32_t *k_other = kr == k0 ? k1 : k0, *v_other = vr == v0 ? v1 : v0;
+        uint32_t *rows_sorted, *labels_sorted;  // second sort: keys = rows, values = labels
+        st = radix_sort_pairs(vr, kr, v_other, k_other, nnz, bits, nullptr, &rows_sorted, &labels_sorted, ws_sort, s);
+        if (st != FTC_OK) return st;
+        hipLaunchKernelGGL(run_flags_kernel, dim3(ge), dim3(256), 0, s, nnz, rows_sorted, labels_sorted, run_id);
+        st = exclusive_scan(run_id, nnz, run_id, true, ws_scan, s);  // run_id[nnz] = number of runs
+        if (st != FTC_OK) return st;
+        hipLaunchKernelGGL(run_starts_kernel, dim3(ge), dim3(256), 0, s, nnz, rows_sorted, labels_sorted, run_id, starts);
+        hipLaunchKernelGGL(clear_u64_kernel, dim3(gn), dim3(256), 0, s, n, best);
+        hipLaunchKernelGGL(run_votes_kernel, dim3(ge < 4096u ? ge : 4096u), dim3(256), 0, s, nnz, run_id + nnz, starts,
+                           rows_sorted, labels_sorted, best);
+        hipLaunchKernelGGL(take_labels_kernel, dim3(gn), dim3(256), 0, s, n, best, labels);
+    }
+    return launch_status("label propagation");
 }
 
 // ---- relabelled graph ----------------------------------------------------------------------------
@@ -354,8 +530,6 @@ __global__ __launch_bounds__(256) void relabel_kernel(int n, int nnz, const int 
     keys[dst] = static_cast<uint32_t>(c_new);
     vals[dst] = static_cast<uint32_t>(r_new);
 }
-
-__global__ void reorder_set_int_kernel(int *p, int v) { *p = v; }
 
 // keys the relabel kernel leaves unwritten (only for an invalid permutation) must still be defined
 __global__ __launch_bounds__(256) void fill_u32_kernel(uint32_t *a, uint32_t *b, int64_t count)

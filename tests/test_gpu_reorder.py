@@ -169,3 +169,54 @@ def test_degree_stats_and_plan_from_device_numbers(graphs, name):
     assert (plan["reorder"] != B.FTC_ORDER_NONE) == expect
     if g.nnz:
         assert plan["reuse"] >= 1.0 and plan["skew"] >= 1.0 - 1e-9
+
+
+# ------------------------------------------------------------------ community ordering
+def sbm_small():
+    return synth.sbm(12, 200, 14 * 12 * 200, 2 * 12 * 200, seed=5)
+
+
+@pytest.mark.parametrize("name", ["cfg1", "sbm", "skewed", "one", "no_edges"])
+@pytest.mark.parametrize("rounds", [0, 1, 4])
+def test_label_propagation(graphs, name, rounds):
+    g = sbm_small() if name == "sbm" else graphs[name]
+    say(f"label propagation {name} n={g.n} nnz={g.nnz} rounds={rounds}")
+    ref = OR.label_propagation(g.row_ptr, g.col_idx, rounds)
+    lab = B.ftc_label_propagation(dev_graph(g), rounds)
+    assert np.array_equal(lab.cpu().numpy().astype(np.int64), ref)
+
+
+def test_community_order_recovers_the_blocks_and_concentrates_the_columns(oracle):
+    """Ten rounds on the permuted block model, then the ordering by label: bit-exact against the
+    oracle, and the relabelled graph's windows hold far fewer distinct columns."""
+    g = sbm_small()
+    dg = dev_graph(g)
+    lab = B.ftc_label_propagation(dg, 10)
+    ref = OR.label_propagation(g.row_ptr, g.col_idx, 10)
+    assert np.array_equal(lab.cpu().numpy().astype(np.int64), ref)
+    perm, inv, flag = B.ftc_order_by_key(lab)
+    perm_ref, inv_ref = OR.order_by_key(ref)
+    assert int(flag.item()) == 0
+    assert np.array_equal(perm.cpu().numpy().astype(np.int64), perm_ref)
+    assert np.array_equal(inv.cpu().numpy().astype(np.int64), inv_ref)
+    pg, pflag = B.ftc_permute_graph(dg, perm, inv)
+    assert int(pflag.item()) == 0
+    before = int(B.ftc_build_windows(dg).summary[0].item())
+    after = int(B.ftc_build_windows(pg).summary[0].item())
+    say(f"distinct window columns {before} -> {after} of {g.nnz} entries")
+    assert after < 0.75 * before
+
+
+def test_order_by_key_random_keys_and_negative_flag():
+    rng = np.random.default_rng(3)
+    n = 70_001
+    keys = rng.integers(0, 50, size=n).astype(np.int32)
+    keys[::1000] = rng.integers(1 << 20, (1 << 31) - 1, size=keys[::1000].size)     # all four digit passes matter
+    perm_ref, inv_ref = OR.order_by_key(keys)
+    perm, inv, flag = B.ftc_order_by_key(torch.from_numpy(keys).cuda())
+    assert int(flag.item()) == 0
+    assert np.array_equal(perm.cpu().numpy().astype(np.int64), perm_ref)
+    assert np.array_equal(inv.cpu().numpy().astype(np.int64), inv_ref)
+    keys[5] = -3
+    _, _, flag = B.ftc_order_by_key(torch.from_numpy(keys).cuda())
+    assert int(flag.item()) == 1
