@@ -275,3 +275,37 @@ def test_cfg5_backward_identities_full():
     fd = float(((Yp.double() - Ym.double()) * d_agnn.double()).sum()) / (2 * eps)
     say(f"  agnn: dbeta {float(dbeta[0]):.6g} central difference {fd:.6g}")
     assert abs(float(dbeta[0]) - fd) < 2e-2 * max(abs(fd), 1e-3 * scale)
+
+
+def test_cfg4_label_propagation():
+    """Label propagation on the permuted block model: every label against the oracle at a tenth of
+    the benchmark size; at the full size (1000 blocks of 1000 nodes) through what the planted
+    partition fixes: one label per block, holding nearly all nodes, and a relabelled graph whose
+    windows hold fewer distinct columns."""
+    from oracle import ftc_oracle_reorder as OR
+    g = synth.config_graph(4, 0.1)
+    say(f"cfg4/10 n={g.n} nnz={g.nnz}")
+    ref = OR.label_propagation(g.row_ptr, g.col_idx, 6)
+    lab = B.ftc_label_propagation(dev_graph(g), 6)
+    assert np.array_equal(lab.cpu().numpy(), ref)
+    g = synth.config_graph(4)
+    dg = dev_graph(g)
+    lab = B.ftc_label_propagation(dg, 10)
+    counts = np.bincount(lab.cpu().numpy(), minlength=g.n)
+    big = counts[counts >= 500]
+    say(f"cfg4 n={g.n}: {np.count_nonzero(counts)} labels, {big.size} with at least 500 nodes covering {big.sum()} nodes")
+    assert big.size == 1000 and big.sum() >= 0.97 * g.n
+    perm, inv, flag = B.ftc_order_by_key(lab)
+    assert int(flag.item()) == 0
+    pn = perm.cpu().numpy()
+    assert np.array_equal(np.sort(pn), np.arange(g.n)) and np.array_equal(inv.cpu().numpy()[pn], np.arange(g.n))
+    ln = lab.cpu().numpy()[pn]
+    assert np.all(np.diff(ln) >= 0)                                   # grouped by label, ...
+    same = np.flatnonzero(np.diff(ln) == 0)
+    assert np.all(pn[same] < pn[same + 1])                            # ... ascending id inside a label
+    pg, pflag = B.ftc_permute_graph(dg, perm, inv)
+    assert int(pflag.item()) == 0
+    before = int(B.ftc_build_windows(dg).summary[0].item())
+    after = int(B.ftc_build_windows(pg).summary[0].item())
+    say(f"  distinct window columns {before} -> {after}")
+    assert after < 0.9 * before
