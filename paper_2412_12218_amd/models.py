@@ -61,6 +61,18 @@ class HotPath:
         self.gcn(X, W1, W2)
         self.agnn(X, W_in, W_out, betas)
 
+    def capture(self, X, W1, W2, W_in, W_out, betas):
+        """The step as a HIP graph: every call of the library only enqueues kernels (and the window build's
+        fork / join events) on the stream it is given and allocates nothing, so the whole step can be
+        captured once and replayed with one launch; the results land in the same buffers as step()'s.
+        The step runs once eagerly first (creates the library's side streams outside the capture)."""
+        self.step(X, W1, W2, W_in, W_out, betas)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            self.step(X, W1, W2, W_in, W_out, betas)
+        return graph
+
 
 class TrainPath:
     """Forward + backward of the two models on one graph with a symmetric pattern (the paper

@@ -572,3 +572,43 @@ def test_agnn_layer_fused_large_beta_and_fp16_out(oracle, graphs):
         err = norm_err(out, ref, ab, F16)
         say(f"agnn fused beta={beta} err {err:.3e}")
         assert err < 2e-3
+
+
+# ------------------------------------------------------------------ the step as a HIP graph
+def test_hot_path_step_replayed_as_a_graph_matches_eager_runs():
+    """Capture the whole step (window build with its side streams, both models) once, replay it several
+    times with eager work and synchronisations in between, and compare every replay with the eager
+    result bit for bit (the kernels are reproducible); the outputs are poisoned before each replay."""
+    from paper_2412_12218_amd.models import HotPath
+    g = synth.config_graph(5, 1 / 32)
+    dg = dev_graph(g)
+    hp = HotPath(dg)
+    h16 = lambda a: torch.from_numpy(a).to(F16).cuda()
+    X = h16(synth.normal_features(g.n, 128, 1))
+    W1, W2 = h16(synth.glorot_uniform(128, 16, 2)), h16(synth.glorot_uniform(16, 8, 3))
+    Win, Wout = h16(synth.glorot_uniform(128, 32, 4)), h16(synth.glorot_uniform(32, 8, 5))
+    betas = [1.0, 0.5, -1.0, 2.0]
+    hp.step(X, W1, W2, Win, Wout, betas)
+    torch.cuda.synchronize()
+    keep = [t.clone() for t in (hp.gcn_out, hp.agnn_out, hp.win.edge_to_col, hp.win.win_cols, hp.win.summary, hp.dinv)]
+    graph = hp.capture(X, W1, W2, Win, Wout, betas)
+    for rep in range(4):
+        for t in (hp.gcn_out, hp.agnn_out, hp.dinv):
+            t.fill_(float("nan"))
+        hp.win.edge_to_col.fill_(-7)
+        hp.win.summary.zero_()
+        scratch = torch.randn(1 << 20, device="cuda").sum()          # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        now = (hp.gcn_out, hp.agnn_out, hp.win.edge_to_col, hp.win.win_cols, hp.win.summary, hp.dinv)
+        n_cols = int(hp.win.summary[0].item())
+        for a, b in zip(keep, now):
+            if a is keep[3]:
+                assert torch.equal(a[:n_cols], b[:n_cols]), f"replay {rep}"
+            else:
+                assert torch.equal(a, b), f"replay {rep}"
+        del scratch
+    hp.step(X, W1, W2, Win, Wout, betas)                              # and eager calls still work afterwards
+    torch.cuda.synchronize()
+    assert torch.equal(hp.agnn_out, keep[1])
