@@ -87,6 +87,48 @@ def test_argument_validation_without_launch():
                              I(0), None) == B.FTC_EUNSUPPORTED
 
 
+def test_backward_and_reordering_validate_on_the_host():
+    """The backward, reordering and plan entry points refuse bad arguments before anything is launched
+    (the fake pointers are never dereferenced)."""
+    L = B.lib()
+    fake, other = C.c_void_p(0x1000), C.c_void_p(0x3000)
+    g = B.ftc_csr(4, 10, 0x1000, 0x2000)
+    w = B.ftc_windows(16, 8, 1, 0x10, 0x20, 0x30, 0x40, 0x50, 0x60)
+    z, big = C.c_size_t(0), C.c_size_t(1 << 30)
+    I, F = C.c_int32, C.c_float
+    assert L.ftc_transpose_index(None, None, fake, fake, None) == B.FTC_EINVAL
+    assert L.ftc_transpose_index(C.byref(g), None, fake, None, None) == B.FTC_EINVAL                 # flag missing
+    assert L.ftc_edge_softmax_backward(C.byref(g), None, None, fake, fake, None, z, None) == B.FTC_EINVAL
+    assert L.ftc_edge_softmax_backward(C.byref(g), C.byref(w), fake, fake, fake, None, z, None) == B.FTC_EWORKSPACE
+    assert L.ftc_weight_grad(I(8), fake, I(512), I(1), I(512), fake, I(64), I(64), other, fake, big, None) \
+        == B.FTC_EUNSUPPORTED                                                                          # too wide
+    assert L.ftc_weight_grad(I(8), fake, I(16), I(1), I(16), fake, I(8), I(8), other, None, z, None) == B.FTC_EWORKSPACE
+    assert L.ftc_gcn_layer_backward(C.byref(g), None, None, None, fake, I(16), I(1), I(16), fake, I(80), None, I(0), I(0),
+                                    fake, I(80), other, I(16), other, I(0), fake, big, None) == B.FTC_EUNSUPPORTED
+    # H and dY with different leading dimensions
+    assert L.ftc_agnn_layer_backward(C.byref(g), None, fake, fake, I(16), I(1), I(16), F(1.0), fake, other, I(24), other,
+                                     I(16), I(0), fake, I(0), fake, big, None) == B.FTC_EINVAL
+    # the single-pass route needs the window index
+    assert L.ftc_agnn_layer_backward_fused(C.byref(g), None, fake, I(16), I(1), I(16), F(1.0), fake, other, I(16), I(0),
+                                           other, I(16), C.c_void_p(0x5000), I(16), I(0), fake, fake, big, None) == B.FTC_EINVAL
+    assert b"window index" in L.ftc_last_error()
+    # ... and a width it covers
+    assert L.ftc_agnn_layer_backward_fused(C.byref(g), C.byref(w), fake, I(256), I(1), I(256), F(1.0), fake, other, I(256),
+                                           I(0), other, I(256), C.c_void_p(0x5000), I(256), I(0), fake, fake, big, None) \
+        == B.FTC_EUNSUPPORTED
+    assert L.ftc_degree_order(C.byref(g), I(7), fake, fake, fake, big, None) == B.FTC_EINVAL          # unknown ordering
+    assert L.ftc_degree_order(C.byref(g), I(0), fake, fake, fake, C.c_size_t(16), None) == B.FTC_EWORKSPACE
+    assert L.ftc_permute_graph(C.byref(g), fake, fake, C.c_void_p(0x1000), other, fake, fake, big, None) == B.FTC_EINVAL
+    assert b"aliases" in L.ftc_last_error()
+    assert L.ftc_label_propagation(C.byref(g), I(-1), fake, fake, big, None) == B.FTC_EINVAL
+    assert L.ftc_order_by_key(I(5), None, fake, fake, fake, fake, big, None) == B.FTC_EINVAL
+    assert L.ftc_permute_rows(I(5), fake, I(8), I(1), I(8), fake, fake, I(8), None) == B.FTC_EINVAL     # out aliases X
+    assert L.ftc_degree_stats(C.byref(g), None, None) == B.FTC_EINVAL
+    assert L.ftc_reorder_workspace_bytes(1000, 5000) > 5000 * 4 * 4
+    assert L.ftc_agnn_layer_backward_fused_workspace_bytes(1000, 5000, 32) > 1000 * 64 * 4
+    assert L.ftc_agnn_layer_backward_fused_workspace_bytes(1000, 5000, 512) == 0
+
+
 def test_wrong_argument_count_is_rejected_by_the_binding():
     L = B.lib()
     with pytest.raises(TypeError):
