@@ -46,6 +46,15 @@ def gcn_layer_backward(row_ptr, col_idx, vals, X, W, dY, Y=None):
     return dZ @ W.T, X.T @ dZ, dZ
 
 
+def update_gemm_backward(X, W, dZ, Z=None):
+    """Dense update Z = act(X W) (act = ReLU when Z, the layer's output, is given; identity otherwise).
+    Returns (dX [n, d_in], dW [d_in, d_out]) for a loss with dL/dZ = dZ:
+      dP = dZ where Z > 0 (ReLU) else dZ;  dW = X^T dP;  dX = dP W^T."""
+    X, W, dZ = (np.asarray(a, dtype=np.float64) for a in (X, W, dZ))
+    dP = dZ if Z is None else dZ * (np.asarray(Z, dtype=np.float64) > 0)
+    return dP @ W.T, X.T @ dP
+
+
 def edge_softmax_backward(row_ptr, p, dp):
     """ds[e] = p[e] * (dp[e] - sum over the row of p * dp): derivative of the row-wise softmax."""
     rows = _rows(row_ptr)

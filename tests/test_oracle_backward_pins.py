@@ -153,3 +153,30 @@ def test_row_z_is_the_denominator_of_the_forward_oracles_probabilities(oracle, b
     same = np.tile(H[:1], (g.n, 1))                      # every cosine is 1
     z1 = ob.agnn_row_z(g.row_ptr, g.col_idx, same, beta)
     assert np.allclose(z1, np.diff(g.row_ptr) * np.exp(beta - abs(beta)), rtol=1e-12)
+
+
+@pytest.mark.parametrize("relu", [False, True])
+def test_update_gemm_backward_against_finite_differences(oracle, relu):
+    """Central differences of the forward C oracle's dense product (with the ReLU applied here)."""
+    rng = np.random.default_rng(11)
+    n, d_in, d_out = 9, 5, 4
+    X, W = rng.normal(size=(n, d_in)), rng.normal(size=(d_in, d_out))
+    dZ = rng.normal(size=(n, d_out))
+
+    def loss(Xv, Wv):
+        Z, _ = oracle.gemm(Xv, Wv)
+        return float(((np.maximum(Z, 0) if relu else Z) * dZ).sum())
+
+    Z0, _ = oracle.gemm(X, W)
+    dX, dW = ob.update_gemm_backward(X, W, dZ, np.maximum(Z0, 0) if relu else None)
+    eps = 1e-6
+    for (i, j) in [(0, 0), (3, 2), (8, 4)]:
+        Xp, Xm = X.copy(), X.copy()
+        Xp[i, j] += eps
+        Xm[i, j] -= eps
+        assert dX[i, j] == pytest.approx((loss(Xp, W) - loss(Xm, W)) / (2 * eps), rel=1e-6, abs=1e-8)
+    for (a, b) in [(0, 0), (2, 3), (4, 1)]:
+        Wp, Wm = W.copy(), W.copy()
+        Wp[a, b] += eps
+        Wm[a, b] -= eps
+        assert dW[a, b] == pytest.approx((loss(X, Wp) - loss(X, Wm)) / (2 * eps), rel=1e-6, abs=1e-8)
