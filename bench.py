@@ -310,6 +310,7 @@ def train_suite(scale, iters=10):
     h16 = lambda a: torch.from_numpy(a).to(torch.float16).to(dev)
     X = h16(synth.normal_features(g.n, 128, seed + 10))
     W1, W2 = h16(synth.glorot_uniform(128, 16, seed + 11)), h16(synth.glorot_uniform(16, 8, seed + 12))
+    Win, Wout = h16(synth.glorot_uniform(128, 32, seed + 13)), h16(synth.glorot_uniform(32, 8, seed + 14))
     H0 = h16(synth.normal_features(g.n, 32, seed + 20))
     d_gcn = torch.from_numpy(synth.normal_features(g.n, 8, seed + 21)).to(dev)
     d_agnn = h16(synth.normal_features(g.n, 32, seed + 22))
@@ -339,6 +340,8 @@ def train_suite(scale, iters=10):
         timed("gcn_backward_2layers", lambda: tp.gcn_backward(X, W1, W2, d_gcn))
         timed("agnn_forward_4layers_keeping_row_z_and_fp32_output", lambda: tp.agnn_forward(H0, betas))
         timed("agnn_backward_4layers", lambda: tp.agnn_backward(betas, d_agnn))
+        timed("agnn_model_forward", lambda: tp.agnn_model_forward(X, Win, Wout, betas))
+        timed("agnn_model_backward", lambda: tp.agnn_model_backward(X, Win, Wout, betas, d_gcn))
     print(json.dumps({"workload": f"cfg5 R-MAT scale {scale}: N={g.n}, nnz={g.nnz}, fp16 activations, fp32 gradients "
                                   "of weights, GCN 128-16-8, AGNN 32 x 4 layers",
                       "ms": {k: float(np.mean(v)) for k, v in times.items()}}))

@@ -260,6 +260,19 @@ int32_t ftc_weight_grad(int32_t n, const void *X, int32_t ldx, int32_t x_dtype, 
                         size_t ws_bytes, void *stream);
 
 /*
+ * Backward of ftc_update_gemm (Z = act(X * W), no row scale) for a loss with dL/dZ = dZ (n x d_out,
+ * fp32): dP = dZ where the layer's output Z was positive (Z == NULL: no ReLU, dP = dZ),
+ * dW = X^T * dP (d_in x d_out, fp32), dX = dP * W^T (n x d_in, of type dx_dtype; dX == NULL:
+ * skipped).  Limits of ftc_weight_grad and d_out <= 64.
+ */
+size_t ftc_update_gemm_backward_workspace_bytes(int32_t n, int32_t d_in, int32_t d_out);
+int32_t ftc_update_gemm_backward(int32_t n, const void *X, int32_t ldx, int32_t dtype, int32_t d_in,
+                                 const void *W, int32_t d_out, const void *Z, int32_t ldz,
+                                 int32_t z_dtype, const float *dZ, int32_t lddz, void *dX,
+                                 int32_t lddx, int32_t dx_dtype, float *dW, void *ws,
+                                 size_t ws_bytes, void *stream);
+
+/*
  * Backward of ftc_gcn_layer for a loss with dL/d(out) = dY (n x d_out, fp32):
  *   dP = dY where the layer's output Y was positive (Y == NULL: no ReLU, dP = dY),
  *   dZ = A^^T * dP,  dW = X^T * dZ (d_in x d_out),  dX = dZ * W^T (n x d_in; dX == NULL: skipped).

@@ -47,6 +47,8 @@ _SIGNATURES = {
     "ftc_edge_softmax_backward": (_I, [_P, _P, _P, _P, _P, _P, _Z, _P]),
     "ftc_weight_grad_workspace_bytes": (_Z, [_I, _I, _I]),
     "ftc_weight_grad": (_I, [_I, _P, _I, _I, _I, _P, _I, _I, _P, _P, _Z, _P]),
+    "ftc_update_gemm_backward_workspace_bytes": (_Z, [_I, _I, _I]),
+    "ftc_update_gemm_backward": (_I, [_I, _P, _I, _I, _I, _P, _I, _P, _I, _I, _P, _I, _P, _I, _I, _P, _P, _Z, _P]),
     "ftc_gcn_layer_backward_workspace_bytes": (_Z, [_I, _I, _I, _I]),
     "ftc_gcn_layer_backward": (_I, [_P, _P, _P, _P, _P, _I, _I, _I, _P, _I, _P, _I, _I, _P, _I, _P, _I, _P, _I, _P,
                                     _Z, _P]),
@@ -318,6 +320,23 @@ def ftc_weight_grad(X, G, ws=None):
                                  _ptr(G), C.c_int32(G.stride(0)), C.c_int32(d_out), _ptr(dW), _ptr(ws),
                                  C.c_size_t(ws.numel()), _stream()))
     return dW
+
+
+def ftc_update_gemm_backward(X, W, dZ, Z=None, want_dX=True, dx_dtype=torch.float32, dX=None, ws=None):
+    n, d_in = X.shape
+    d_out = W.shape[1]
+    assert dZ.dtype == torch.float32 and dZ.shape == (n, d_out)
+    if dX is None and want_dX:
+        dX = torch.empty((n, d_in), dtype=dx_dtype, device=X.device)
+    dW = torch.empty((d_in, d_out), dtype=torch.float32, device=X.device)
+    if ws is None:
+        ws = _workspace(lib().ftc_update_gemm_backward_workspace_bytes(n, d_in, d_out), X.device)
+    _check(lib().ftc_update_gemm_backward(
+        C.c_int32(n), _ptr(X), C.c_int32(X.stride(0)), C.c_int32(_dt(X)), C.c_int32(d_in), _ptr(W), C.c_int32(d_out),
+        _ptr(Z), C.c_int32(Z.stride(0) if Z is not None else 0), C.c_int32(_dt(Z) if Z is not None else 0), _ptr(dZ),
+        C.c_int32(dZ.stride(0)), _ptr(dX), C.c_int32(dX.stride(0) if dX is not None else 0),
+        C.c_int32(_dt(dX) if dX is not None else 0), _ptr(dW), _ptr(ws), C.c_size_t(ws.numel()), _stream()))
+    return dX, dW
 
 
 def ftc_gcn_layer_backward(gT, wT, valsT, X, W, dY, Y=None, dinv=None, want_dX=True, path=FTC_PATH_AUTO, ws=None):

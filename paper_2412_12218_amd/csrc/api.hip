@@ -463,6 +463,48 @@ int32_t ftc_weight_grad(int32_t n, const void *X, int32_t ldx, int32_t x_dtype, 
 
 static int pad4(int d) { return (d + 3) / 4 * 4; }
 
+size_t ftc_update_gemm_backward_workspace_bytes(int32_t n, int32_t d_in, int32_t d_out)
+{
+    if (n < 0 || d_in < 1 || d_out < 1) return 0;
+    return align_up(static_cast<size_t>(n) * pad4(d_out) * sizeof(float), 256) + weight_grad_ws(n, d_in, d_out);
+}
+
+int32_t ftc_update_gemm_backward(int32_t n, const void *X, int32_t ldx, int32_t dtype, int32_t d_in, const void *W,
+                                 int32_t d_out, const void *Z, int32_t ldz, int32_t z_dtype, const float *dZ,
+                                 int32_t lddz, void *dX, int32_t lddx, int32_t dx_dtype, float *dW, void *ws,
+                                 size_t ws_bytes, void *stream)
+{
+    if (n < 0) return fail(FTC_EINVAL, "ftc_update_gemm_backward: negative n");
+    if (n == 0) return FTC_OK;
+    FTC_TRY(check_dense(X, ldx, dtype, d_in, "ftc_update_gemm_backward", "X"));
+    FTC_TRY(check_dense(dZ, lddz, FTC_F32, d_out, "ftc_update_gemm_backward", "dZ"));
+    if (Z) FTC_TRY(check_dense(Z, ldz, z_dtype, d_out, "ftc_update_gemm_backward", "Z"));
+    if (dX) FTC_TRY(check_dense(dX, lddx, dx_dtype, d_in, "ftc_update_gemm_backward", "dX"));
+    if (!W || !dW) return fail(FTC_EINVAL, "ftc_update_gemm_backward: W or dW is NULL");
+    if (dX == X) return fail(FTC_EINVAL, "ftc_update_gemm_backward: dX aliases X");
+    if (d_out > 64 || !weight_grad_shape_ok(d_in, d_out))
+        return fail(FTC_EUNSUPPORTED, "ftc_update_gemm_backward: need d_out <= 64, ceil(d_in / 4) * ceil(d_out / 4) <= 1024 and d_in + d_out <= 506");
+    const size_t need = ftc_update_gemm_backward_workspace_bytes(n, d_in, d_out);
+    if (!ws || ws_bytes < need)
+        return fail(FTC_EWORKSPACE, "ftc_update_gemm_backward: workspace of %zu bytes needed", need);
+    if (reinterpret_cast<uintptr_t>(ws) % 256 != 0)
+        return fail(FTC_EALIGN, "ftc_update_gemm_backward: workspace must be 256-byte aligned");
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    const float *dP = dZ;
+    int ldp = lddz;
+    char *p = static_cast<char *>(ws);
+    if (Z) {  // ReLU: the gradient passes where the output was positive
+        float *masked = reinterpret_cast<float *>(p);
+        ldp = pad4(d_out);
+        FTC_TRY(launch_mask_scale(n, d_out, dZ, lddz, Z, ldz, z_dtype, nullptr, masked, ldp, hs));
+        dP = masked;
+    }
+    void *ws_wg = p + align_up(static_cast<size_t>(n) * pad4(d_out) * sizeof(float), 256);
+    FTC_TRY(launch_weight_grad(n, X, ldx, dtype, d_in, dP, ldp, d_out, dW, ws_wg, hs));
+    if (dX) FTC_TRY(launch_input_grad(n, dP, ldp, d_out, W, dtype, d_in, dX, lddx, dx_dtype, hs));
+    return FTC_OK;
+}
+
 size_t ftc_gcn_layer_backward_workspace_bytes(int32_t n, int32_t nnz, int32_t d_in, int32_t d_out)
 {
     if (n < 0 || nnz < 0 || d_in < 1 || d_out < 1) return 0;
@@ -504,7 +546,7 @@ int32_t ftc_gcn_layer_backward(const ftc_csr *gT, const ftc_windows *wT, const f
     FTC_TRY(ftc_spmm(gT, wT, dinv ? nullptr : valsT, dP, ldp, FTC_F32, d_out, dZ, ldp, FTC_F32, dinv, 0, path,
                      ws_spmm, spmm_bytes, stream));
     FTC_TRY(launch_weight_grad(n, X, ldx, dtype, d_in, dZ, ldp, d_out, dW, ws_wg, hs));
-    if (dX) FTC_TRY(launch_input_grad(n, dZ, ldp, d_out, W, dtype, d_in, dX, lddx, hs));
+    if (dX) FTC_TRY(launch_input_grad(n, dZ, ldp, d_out, W, dtype, d_in, dX, lddx, FTC_F32, hs));
     return FTC_OK;
 }
 

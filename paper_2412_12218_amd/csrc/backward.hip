@@ -333,7 +333,7 @@ constexpr int IG_ROWS = 64;
 template <int DOUT>  // d_out padded to a multiple of 4
 __global__ __launch_bounds__(256) void input_grad_kernel(int n, const float *__restrict__ G, int ldg, int d_out,
                                                          const void *__restrict__ W, int wdt, int d_in,
-                                                         float *__restrict__ dX, int lddx)
+                                                         void *__restrict__ dX, int lddx, int dx_dt)
 {
     __shared__ __attribute__((aligned(16))) float Gs[IG_ROWS * DOUT];
     const int tid = threadIdx.x;
@@ -357,18 +357,19 @@ __global__ __launch_bounds__(256) void input_grad_kernel(int n, const float *__r
                 acc = fmaf(z.z, w[b + 2], acc);
                 acc = fmaf(z.w, w[b + 3], acc);
             }
-            dX[(r0 + r) * lddx + a] = acc;
+            store_elem(dX, (r0 + r) * lddx + a, dx_dt, acc);
         }
     }
 }
 
-int32_t launch_input_grad(int n, const float *G, int ldg, int d_out, const void *W, int wdt, int d_in, float *dX,
-                          int lddx, hipStream_t s)
+int32_t launch_input_grad(int n, const float *G, int ldg, int d_out, const void *W, int wdt, int d_in, void *dX,
+                          int lddx, int dx_dt, hipStream_t s)
 {
     if (n == 0) return FTC_OK;
     const unsigned grid = static_cast<unsigned>((static_cast<int64_t>(n) + IG_ROWS - 1) / IG_ROWS);
 #define FTC_IG(P)                                                                                               \
-    hipLaunchKernelGGL(input_grad_kernel<P>, dim3(grid), dim3(256), 0, s, n, G, ldg, d_out, W, wdt, d_in, dX, lddx)
+    hipLaunchKernelGGL(input_grad_kernel<P>, dim3(grid), dim3(256), 0, s, n, G, ldg, d_out, W, wdt, d_in, dX, lddx, \
+                       dx_dt)
     if (d_out <= 8) FTC_IG(8);
     else if (d_out <= 16) FTC_IG(16);
     else if (d_out <= 32) FTC_IG(32);

@@ -89,8 +89,8 @@ bool weight_grad_shape_ok(int d_in, int d_out);
 size_t weight_grad_ws(int n, int d_in, int d_out);
 int32_t launch_weight_grad(int n, const void *X, int ldx, int xdt, int d_in, const float *G, int ldg, int d_out,
                            float *dW, void *ws, hipStream_t s);
-int32_t launch_input_grad(int n, const float *G, int ldg, int d_out, const void *W, int wdt, int d_in, float *dX,
-                          int lddx, hipStream_t s);
+int32_t launch_input_grad(int n, const float *G, int ldg, int d_out, const void *W, int wdt, int d_in, void *dX,
+                          int lddx, int dx_dt, hipStream_t s);
 int32_t launch_edge_combine(int nnz, const float *a, const int *T, float wa, float wb, float alpha, const float *cs,
                             const int *col_idx, float *out, hipStream_t s);
 size_t edge_dot_ws();

@@ -105,6 +105,9 @@ class TrainPath:
             if self.keep_f32 else []
         self.agnn_p = [torch.empty(nnz, **f32) for _ in range(agnn_layers)] if not self.fused else []
         self.d_agnn_h = [torch.empty((n, agnn_hidden), **act) for _ in range(2)]
+        self.agnn_h0 = torch.empty((n, agnn_hidden), **act)     # output of the in-projection
+        self.d_agnn_h0 = torch.empty((n, agnn_hidden), **f32)   # gradient entering the in-projection
+        self.agnn_out = torch.empty((n, n_out), **f32)
         self.dbeta = torch.empty(agnn_layers, **f32)
         self.ws = B._workspace(max(
             L.ftc_gcn_layer_workspace_bytes(n, nnz, d_feat, gcn_hidden),
@@ -113,7 +116,9 @@ class TrainPath:
             L.ftc_gcn_layer_backward_workspace_bytes(n, nnz, gcn_hidden, n_out),
             L.ftc_agnn_layer_workspace_bytes(n, nnz, agnn_hidden),
             L.ftc_agnn_layer_backward_workspace_bytes(n, nnz, agnn_hidden),
-            L.ftc_agnn_layer_backward_fused_workspace_bytes(n, nnz, agnn_hidden)), dev)
+            L.ftc_agnn_layer_backward_fused_workspace_bytes(n, nnz, agnn_hidden),
+            L.ftc_update_gemm_backward_workspace_bytes(n, d_feat, agnn_hidden),
+            L.ftc_update_gemm_backward_workspace_bytes(n, agnn_hidden, n_out)), dev)
 
     @staticmethod
     def agnn_h_itemsize(dtype):
@@ -135,8 +140,9 @@ class TrainPath:
         return dW1, dW2
 
     def agnn_forward(self, H0, betas):
-        """Propagation layers only (the dense layers around them are ftc_update_gemm / ftc_weight_grad);
-        every layer keeps its attention probabilities for the backward pass."""
+        """Propagation layers only; every layer keeps what its backward pass needs: the softmax
+        denominators (and its unrounded output when the activations are 16-bit) on the single-pass route,
+        the attention probabilities on the edge-array route."""
         self.agnn_h[0] = H0
         for l in range(self.agnn_layers):
             keep = dict(row_z=self.agnn_z[l]) if self.fused else dict(edge_p=self.agnn_p[l])
@@ -146,11 +152,12 @@ class TrainPath:
                              path=self.path, ws=self.ws, **keep)
         return self.agnn_h[self.agnn_layers]
 
-    def agnn_backward(self, betas, d_out):
-        """d_out = dL/d(last layer's output), in the activation type.  Returns (dL/dH0, dbeta[layers])."""
+    def agnn_backward(self, betas, d_out, first_in_f32=False):
+        """d_out = dL/d(last layer's output), in the activation type.  Returns (dL/dH0, dbeta[layers]);
+        dL/dH0 in fp32 when first_in_f32 (what the backward of the in-projection takes)."""
         d = d_out
         for l in reversed(range(self.agnn_layers)):
-            nxt = self.d_agnn_h[l & 1]
+            nxt = self.d_agnn_h0 if (l == 0 and first_in_f32) else self.d_agnn_h[l & 1]
             if self.fused:
                 y = self.agnn_y32[l][:, :self.agnn_h[l].shape[1]] if self.keep_f32 else self.agnn_h[l + 1]
                 B.ftc_agnn_layer_backward_fused(self.g, self.win, self.agnn_h[l], self.agnn_z[l], y, d,
@@ -160,3 +167,18 @@ class TrainPath:
                                           dH=nxt, dbeta=self.dbeta[l:l + 1], path=self.path, ws=self.ws)
             d = nxt
         return d, self.dbeta
+
+    def agnn_model_forward(self, X, W_in, W_out, betas):
+        """The whole AGNN model of the benchmark: ReLU in-projection, propagation layers, out-projection."""
+        B.ftc_update_gemm(X, W_in, out=self.agnn_h0, relu=True)
+        h = self.agnn_forward(self.agnn_h0, betas)
+        B.ftc_update_gemm(h, W_out, out=self.agnn_out)
+        return self.agnn_out
+
+    def agnn_model_backward(self, X, W_in, W_out, betas, d_out):
+        """d_out = dL/d(agnn_out), fp32.  Returns (dW_in, dW_out, dbeta[layers])."""
+        h_last = self.agnn_h[self.agnn_layers]
+        d_h, dW_out = B.ftc_update_gemm_backward(h_last, W_out, d_out, dX=self.d_agnn_h[self.agnn_layers & 1], ws=self.ws)
+        d_h0, dbeta = self.agnn_backward(betas, d_h, first_in_f32=True)
+        _, dW_in = B.ftc_update_gemm_backward(X, W_in, d_h0, Z=self.agnn_h0, want_dX=False, ws=self.ws)
+        return dW_in, dW_out, dbeta

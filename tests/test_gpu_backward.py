@@ -174,6 +174,28 @@ def test_weight_grad_strided_inputs():
     assert arr_err(dW, ref) < 1e-5
 
 
+# ------------------------------------------------------------------ dense update backward
+@pytest.mark.parametrize("n", [1, 1000, 70_001])
+@pytest.mark.parametrize("dtype,d_in,d_out", [(F16, 128, 32), (F32, 16, 16), (BF16, 30, 7), (F16, 32, 8)])
+@pytest.mark.parametrize("relu", [False, True])
+def test_update_gemm_backward(n, dtype, d_in, d_out, relu):
+    say(f"update_gemm_backward n={n} {dtype} {d_in}->{d_out} relu={relu}")
+    Xd, X64 = quantise(synth.uniform_features(n, d_in, seed=1), dtype)
+    Wd, W64 = quantise(synth.glorot_uniform(d_in, d_out, seed=2), dtype)
+    dZ32 = synth.normal_features(n, d_out, seed=3).astype(np.float32)
+    Z = B.ftc_update_gemm(Xd, Wd, relu=True, out_dtype=dtype) if relu else None      # the mask is the layer's own output
+    dX_ref, dW_ref = OB.update_gemm_backward(X64, W64, dZ32.astype(np.float64), Z.cpu().double().numpy() if relu else None)
+    dZ = torch.from_numpy(dZ32).cuda()
+    dX, dW = B.ftc_update_gemm_backward(Xd, Wd, dZ, Z=Z)
+    ex, ew = row_err(dX, dX_ref), arr_err(dW, dW_ref)
+    say(f"  dX err {ex:.3e} dW err {ew:.3e}")
+    assert ex < 1e-5 and ew < 1e-5
+    dX16, dW2 = B.ftc_update_gemm_backward(Xd, Wd, dZ, Z=Z, dx_dtype=F16)
+    assert torch.equal(dX16, dX.to(F16)) and torch.equal(dW2, dW)
+    none, dW3 = B.ftc_update_gemm_backward(Xd, Wd, dZ, Z=Z, want_dX=False)
+    assert none is None and torch.equal(dW3, dW)
+
+
 # ------------------------------------------------------------------ GCN layer backward
 @pytest.mark.parametrize("name", ["cfg1", "cfg3s", "cfg5s", "directed"])
 @pytest.mark.parametrize("dtype,d_in,d_out", [(F16, 64, 16), (F32, 16, 16), (BF16, 30, 7), (F16, 16, 40)])
@@ -452,6 +474,39 @@ def test_train_path_stacks_against_chained_oracle(oracle, fused):
     say(f"agnn stack dH0 err {eh:.3e} dbeta {dbeta.cpu().numpy()} ref {db_ref}")
     assert eh < 1e-4
     assert np.allclose(dbeta.cpu().double().numpy(), db_ref, rtol=1e-3, atol=1e-3 * np.sqrt(n) * 1e-2)
+
+
+@pytest.mark.parametrize("act", [F32, F16])
+def test_train_path_whole_agnn_model_against_chained_oracle(oracle, act):
+    """In-projection with ReLU, three propagation layers, out-projection: weight and beta gradients of
+    TrainPath against the per-layer oracles chained on the CPU.  With fp16 activations the oracle
+    chain starts every layer from the GPU's own (rounded) activations, as the layer tests do."""
+    from paper_2412_12218_amd.models import TrainPath
+    g = synth.config_graph(1)
+    n = g.n
+    dg = dev_graph(g)
+    win = B.ftc_build_windows(dg)
+    _, dinv = B.ftc_gcn_norm(dg, win)
+    tp = TrainPath(dg, win, dinv, d_feat=24, gcn_hidden=16, agnn_hidden=16, n_out=8, agnn_layers=3, act_dtype=act)
+    Xd, X64 = quantise(synth.uniform_features(n, 24, seed=41), act)
+    Wid, Wi64 = quantise(synth.glorot_uniform(24, 16, seed=42), act)
+    Wod, Wo64 = quantise(synth.glorot_uniform(16, 8, seed=43), act)
+    dOutd, dOut64 = quantise(synth.normal_features(n, 8, seed=44), F32)
+    betas = [1.0, -0.7, 2.0]
+    tp.agnn_model_forward(Xd, Wid, Wod, betas)
+    dW_in, dW_out, dbeta = tp.agnn_model_backward(Xd, Wid, Wod, betas, dOutd)
+    Hs = [tp.agnn_h0.cpu().double().numpy()] + [tp.agnn_h[l].cpu().double().numpy() for l in (1, 2, 3)]
+    d, dWo_ref = OB.update_gemm_backward(Hs[3], Wo64, dOut64)
+    db_ref = [0.0] * 3
+    for l in reversed(range(3)):
+        d_in = torch.from_numpy(d).to(act).double().numpy()      # the chain hands gradients on in the activation type
+        d, db_ref[l] = OB.agnn_layer_backward(g.row_ptr, g.col_idx, Hs[l], betas[l], d_in)
+    _, dWi_ref = OB.update_gemm_backward(X64, Wi64, d, Hs[0])
+    ei, eo = arr_err(dW_in, dWi_ref), arr_err(dW_out, dWo_ref)
+    say(f"agnn model ({act}): dW_in err {ei:.3e} dW_out err {eo:.3e} dbeta {dbeta.cpu().numpy()} ref {db_ref}")
+    tol = 1e-5 if act == F32 else 2e-3
+    assert ei < tol and eo < 1e-5
+    assert np.allclose(dbeta.cpu().double().numpy(), db_ref, rtol=10 * tol, atol=10 * tol)
 
 
 def test_train_path_rejects_a_non_symmetric_pattern():
