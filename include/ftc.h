@@ -342,8 +342,11 @@ int32_t ftc_agnn_layer_backward_fused(const ftc_csr *g, const ftc_windows *w, co
 enum {
     FTC_ORDER_NONE = -1,          /* keep the numbering (a value of ftc_plan.reorder only) */
     FTC_ORDER_DEGREE = 0,         /* descending number of stored entries of the row, ties: ascending id */
-    FTC_ORDER_DEGREE_CLASSES = 1  /* descending bit length of that number (power-of-two classes), ties:
+    FTC_ORDER_DEGREE_CLASSES = 1, /* descending bit length of that number (power-of-two classes), ties:
                                      ascending id -- keeps the given order inside a class */
+    FTC_ORDER_COMMUNITIES = 2     /* a value of ftc_plan.reorder only: ftc_label_propagation +
+                                     ftc_order_by_key are worth a trial (keep the result if the window
+                                     build's sum_uniq drops) */
 };
 
 /* Workspace of ftc_degree_order, ftc_order_by_key, ftc_label_propagation and ftc_permute_graph. */
@@ -408,8 +411,10 @@ typedef struct {
                              the mean row length (1 for a regular graph; row lengths stand in for column counts,
                              exact on symmetric patterns) */
     double reuse;         /* nnz / sum_uniq: stored entries per condensed column, averaged over the windows */
-    int32_t reorder;      /* FTC_ORDER_NONE or the ordering to apply with ftc_degree_order / ftc_permute_graph:
-                             skew >= 2 and a feature matrix (n * D elements) larger than one L2 (4 MiB) */
+    int32_t reorder;      /* the ordering to apply, for a feature matrix (n * D elements) larger than one L2
+                             (4 MiB): FTC_ORDER_DEGREE_CLASSES when skew >= 2, FTC_ORDER_COMMUNITIES (a trial
+                             of the community ordering) for flatter degrees with at least 8 entries per row on
+                             average; else FTC_ORDER_NONE */
     int32_t agnn_single_pass;           /* ftc_agnn_layer without edge_p runs as one pass for this (dtype, D) */
     int32_t agnn_backward_single_pass;  /* ftc_agnn_layer_backward_fused covers this (dtype, D) */
     int32_t spmm_mfma_windows;   /* FTC_PATH_AUTO may send windows of this (dtype, D) to the matrix cores ... */

@@ -390,7 +390,7 @@ def ftc_agnn_layer_backward_fused(g, w, H, row_z, Y, dY, beta=1.0, dH=None, dh_d
 
 
 # ---- locality reordering ------------------------------------------------------------------------------
-FTC_ORDER_DEGREE, FTC_ORDER_DEGREE_CLASSES = 0, 1
+FTC_ORDER_DEGREE, FTC_ORDER_DEGREE_CLASSES, FTC_ORDER_COMMUNITIES = 0, 1, 2
 
 
 def ftc_degree_order(g, mode=FTC_ORDER_DEGREE, ws=None):

@@ -732,7 +732,9 @@ int32_t ftc_degree_stats(const ftc_csr *g, int64_t *stats, void *stream)
 // Thresholds of the plan, from measurements on the benchmark graphs (bench.py --reorder, --sweep):
 // relabelling by degree class paid 5 to 17 % on the gather kernels of the graphs with skew 7.8, 9.3
 // and 70 and nothing on those with skew 1.03 and 1.1; it cannot pay while the whole feature matrix
-// fits the 4 MiB L2 of one XCD.
+// fits the 4 MiB L2 of one XCD.  With flat degrees only a community ordering can help (block-model
+// graph: -28 to -52 % after ten rounds of label propagation); whether the graph has communities is
+// not visible in these statistics, so the plan proposes a trial.
 static constexpr double PLAN_SKEW_MIN = 2.0;
 static constexpr double PLAN_L2_BYTES = 4.0 * 1024 * 1024;
 
@@ -747,7 +749,11 @@ int32_t ftc_plan_graph(int32_t n, int32_t nnz, int64_t sum_deg_sq, int64_t sum_u
                          : 0.0;
     plan->reuse = sum_uniq > 0 ? static_cast<double>(nnz) / static_cast<double>(sum_uniq) : 0.0;
     const double feature_bytes = static_cast<double>(n) * D * elem_size(dtype);
-    plan->reorder = (plan->skew >= PLAN_SKEW_MIN && feature_bytes > PLAN_L2_BYTES) ? FTC_ORDER_DEGREE_CLASSES : FTC_ORDER_NONE;
+    plan->reorder = FTC_ORDER_NONE;
+    if (feature_bytes > PLAN_L2_BYTES) {
+        if (plan->skew >= PLAN_SKEW_MIN) plan->reorder = FTC_ORDER_DEGREE_CLASSES;
+        else if (nnz >= 8.0 * n) plan->reorder = FTC_ORDER_COMMUNITIES;  // flat degrees: only communities can help
+    }
     int vec, lpr;
     const bool seg = seg_shape(dtype, D, &vec, &lpr);
     plan->agnn_single_pass = seg ? 1 : 0;

@@ -17,13 +17,17 @@ def stats_of(g, oracle):
     return int((deg * deg).sum()), sum_uniq
 
 
+NONE, CLASSES, COMM = B.FTC_ORDER_NONE, B.FTC_ORDER_DEGREE_CLASSES, B.FTC_ORDER_COMMUNITIES
+
+
 @pytest.mark.parametrize("cfg,scale,D,dtype,reorder", [
-    (1, 1.0, 16, F32, False),      # Erdos-Renyi: skew 1.1
-    (2, 1.0, 32, F16, True),       # Chung-Lu, skew 9.3, 6.4 MB of features
-    (3, 1.0, 32, F16, True),       # Chung-Lu, skew 7.8
-    (4, 0.1, 64, BF16, False),     # SBM: flat degrees
-    (5, 0.25, 32, F16, True),      # R-MAT at a quarter of the benchmark size: 16 MB of features
-    (5, 1 / 64, 32, F16, False),   # the same skew, but 1 MB of features: everything stays in L2
+    (1, 1.0, 16, F32, NONE),       # Erdos-Renyi: skew 1.1, 128 KB of features
+    (2, 1.0, 32, F16, CLASSES),    # Chung-Lu, skew 9.3, 6.4 MB of features
+    (3, 1.0, 32, F16, CLASSES),    # Chung-Lu, skew 7.8
+    (4, 0.1, 64, BF16, COMM),      # SBM: flat degrees, 12.8 MB of features: only communities can help
+    (4, 0.02, 64, BF16, NONE),     # ... but not while everything fits one L2
+    (5, 0.25, 32, F16, CLASSES),   # R-MAT at a quarter of the benchmark size: 16 MB of features
+    (5, 1 / 64, 32, F16, NONE),    # the same skew, but 1 MB of features: everything stays in L2
 ])
 def test_plan_reorders_where_the_measurements_say_it_pays(oracle, cfg, scale, D, dtype, reorder):
     g = synth.config_graph(cfg, scale)
@@ -32,7 +36,7 @@ def test_plan_reorders_where_the_measurements_say_it_pays(oracle, cfg, scale, D,
     deg = np.diff(g.row_ptr).astype(np.float64)
     assert plan["skew"] == pytest.approx(g.n * (deg * deg).sum() / g.nnz ** 2, rel=1e-12)
     assert plan["reuse"] == pytest.approx(g.nnz / su, rel=1e-12)
-    assert plan["reorder"] == (B.FTC_ORDER_DEGREE_CLASSES if reorder else B.FTC_ORDER_NONE)
+    assert plan["reorder"] == reorder
 
 
 def test_plan_reports_what_the_kernels_cover():
