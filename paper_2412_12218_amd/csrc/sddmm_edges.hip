@@ -3,7 +3,7 @@
 // The output has one value per stored entry (`EdgeValList`), so equal numbers of EDGES per wave
 // balance the work however skewed the rows are; edge_to_row of the window index gives each
 // edge its row.  A wave stages the (column, row) pairs of SEG_R consecutive edges in LDS, groups
-// of LPR lanes walk contiguous runs of them, eight edges at a time: eight independent gathers of
+// of LPR lanes walk contiguous runs of them, SD_B edges at a time: SD_B independent gathers of
 // Y rows in flight per lane, the X row is re-read only when the row changes.  Dot products are
 // reduced inside the group with DPP lane shuffles, parked in LDS, and written back scaled
 // (alpha * row_scale[i] * col_scale[j]) with fully coalesced stores.

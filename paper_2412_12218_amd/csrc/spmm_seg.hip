@@ -8,7 +8,7 @@
 //   - A wave owns SEG_R consecutive edges.  Their (column, value, row) triples are loaded once,
 //     coalesced, into LDS.
 //   - The wave is cut into groups of LPR lanes; a group walks a contiguous run of the wave's
-//     edges, eight at a time (eight independent 16-byte gathers of X rows in flight per lane),
+//     edges, SEG_B at a time (SEG_B independent 16-byte gathers of X rows in flight per lane),
 //     and accumulates in registers while the row stays the same.
 //   - A row that lies completely inside one run is stored straight from registers.  A row cut by
 //     a run boundary leaves a partial sum: the pieces inside one wave are added in LDS in edge
