@@ -894,7 +894,7 @@ int32_t launch_build_windows(const ftc_csr &g, ftc_windows &w, void *ws, size_t 
     }
     const int hub_thr = hub_threshold(g.n, g.nnz);
     const bool queued = g.nnz > WAVE_CAP;  // otherwise no window can be queued
-    int32_t st;
+    int32_t st = FTC_OK;
     hipStream_t s_mid = s, s_large = s, s_hub = s;
     SideStreams *side = nullptr;
     if (queued) {
