@@ -535,3 +535,50 @@ def test_backward_rejects_bad_arguments():
         B.ftc_weight_grad(torch.zeros((10, 512), dtype=F16, device="cuda"),
                           torch.zeros((10, 64), dtype=F32, device="cuda"))
     del dY32
+
+
+# ------------------------------------------------------------------ seeded sweep over shapes
+@pytest.mark.parametrize("case", range(16))
+def test_agnn_backward_random_shapes(case):
+    """Symmetric random graphs from 1 to a few thousand nodes (isolated nodes, self-loops on some,
+    a long row in the larger ones), widths from 1 to 64: the edge-array route always, the single-pass
+    route where it covers the shape, both against the oracle."""
+    import scipy.sparse as sp
+    rng = np.random.default_rng(2000 + case)
+    n = int(rng.choice([1, 2, 17, 64, 500, 1025, 3000]))
+    m = int(n * rng.integers(1, 8))
+    u, v = rng.integers(0, n, size=m), rng.integers(0, n, size=m)
+    if n >= 500:
+        hub = int(rng.integers(0, n))
+        u = np.concatenate([u, np.full(900, hub)])
+        v = np.concatenate([v, rng.integers(0, n, size=900)])
+    loops = np.flatnonzero(rng.random(n) < 0.5)
+    A = sp.csr_matrix((np.ones(u.size + loops.size), (np.concatenate([u, loops]), np.concatenate([v, loops]))), shape=(n, n))
+    A = (A + A.T).tocsr()
+    A.sum_duplicates()
+    A.sort_indices()
+    g = synth.Graph(n, A.indptr.astype(np.int32), A.indices.astype(np.int32), "random")
+    dtype = [F32, F16, BF16][case % 3]
+    D = int(rng.choice([1, 3, 4, 8, 12, 16, 24, 32, 40, 64]))
+    beta = float(rng.choice([1.0, -1.5, 3.0]))
+    say(f"random case {case}: n={n} nnz={g.nnz} {dtype} D={D} beta={beta}")
+    Hd, H64 = quantise(synth.normal_features(n, D, seed=case), dtype)
+    dYd, dY64 = quantise(synth.normal_features(n, D, seed=100 + case), dtype)
+    dH_ref, dbeta_ref = OB.agnn_layer_backward(g.row_ptr, g.col_idx, H64, beta, dY64)
+    dg = dev_graph(g)
+    win = B.ftc_build_windows(dg)
+    T, flag = B.ftc_transpose_index(dg, win)
+    assert int(flag.item()) == 0
+    p = torch.empty(g.nnz, dtype=F32, device="cuda")
+    B.ftc_agnn_layer(dg, win, Hd, beta=beta, edge_p=p)
+    dH, dbeta = B.ftc_agnn_layer_backward(dg, win, T, Hd, p, dYd, beta=beta)
+    assert row_err(dH, dH_ref) < 1e-5
+    assert abs(float(dbeta.item()) - dbeta_ref) < 1e-4 * max(abs(dbeta_ref), 1.0)
+    fused_ok = B.lib().ftc_agnn_layer_backward_fused_workspace_bytes(n, g.nnz, D) > 0 and (D * Hd.element_size()) % 16 == 0
+    if fused_ok:
+        row_z = torch.empty(n, dtype=F32, device="cuda")
+        Y = B.ftc_agnn_layer(dg, win, Hd, beta=beta, row_z=row_z)
+        dH2, dbeta2 = B.ftc_agnn_layer_backward_fused(dg, win, Hd, row_z, Y, dYd, beta=beta)
+        assert row_err(dH2, dH_ref) < 1e-5
+        assert abs(float(dbeta2.item()) - dbeta_ref) < 1e-4 * max(abs(dbeta_ref), 1.0)
+        say("  single-pass route checked too")

@@ -612,3 +612,46 @@ def test_hot_path_step_replayed_as_a_graph_matches_eager_runs():
     hp.step(X, W1, W2, Win, Wout, betas)                              # and eager calls still work afterwards
     torch.cuda.synchronize()
     assert torch.equal(hp.agnn_out, keep[1])
+
+
+# ------------------------------------------------------------------ seeded sweep over shapes
+def random_graph(rng, n):
+    """Random degrees with empty rows, a few long rows (several wave ranges) and duplicates."""
+    deg = rng.integers(0, 12, size=n)
+    deg[rng.random(n) < 0.2] = 0
+    # (long rows only where the columns are spread: a thousand copies of the same term make fp32
+    # summation drift by a rounding error per term, beyond the 1e-5 bar, whatever the order)
+    for _ in range(rng.integers(0, 3) if n >= 500 else 0):
+        deg[rng.integers(0, n)] = rng.integers(600, 2600)
+    row_ptr = np.zeros(n + 1, dtype=np.int32)
+    row_ptr[1:] = np.cumsum(deg)
+    col = rng.integers(0, n, size=int(row_ptr[-1])).astype(np.int32)
+    return synth.Graph(n, row_ptr, col, "random")
+
+
+@pytest.mark.parametrize("case", range(24))
+def test_spmm_sddmm_agnn_random_shapes(oracle, case):
+    """Seeded sweep: node counts from 1 to a few thousand, every feature width from 1 to 40 with the
+    padding that makes rows 16-byte aligned or not, all three element types, with and without edge
+    values: SpMM (whichever kernel the shape selects), cosine SDDMM and the AGNN layer."""
+    rng = np.random.default_rng(1000 + case)
+    n = int(rng.choice([1, 2, 15, 16, 17, 63, 500, 1025, 3000]))
+    g = random_graph(rng, n)
+    dtype = [F32, F16, BF16][case % 3]
+    D = int(rng.integers(1, 41))
+    pad = int(rng.choice([0, (-D) % 8, (-D) % 4, 3]))
+    say(f"random case {case}: n={n} nnz={g.nnz} {dtype} D={D} pad={pad}")
+    assert run_spmm(oracle, g, dtype, D, pad=pad, use_vals=bool(case & 1), relu=bool(case & 2), seed=case) < TOL[dtype]
+    if g.nnz == 0:
+        return
+    Hd, H64 = quantise(synth.normal_features(n, D + pad, seed=case), dtype)
+    Hd, H64 = Hd[:, :D], H64[:, :D]
+    dg = dev_graph(g)
+    win = B.ftc_build_windows(dg)
+    ref, ab, _ = oracle.agnn_layer(g.row_ptr, g.col_idx, H64, 1.5)
+    out = B.ftc_agnn_layer(dg, win, Hd, beta=1.5)
+    assert norm_err(out, ref, ab) < TOL[dtype]
+    Hn = H64 / np.maximum(np.sqrt((H64 * H64).sum(axis=1)), 1e-12)[:, None]
+    sref, sab = oracle.sddmm(g.row_ptr, g.col_idx, Hn, Hn)
+    s = B.ftc_sddmm(dg, win, Hd, Hd, cosine=True)
+    assert float(np.max(np.abs(s.cpu().double().numpy() - sref))) < (1e-5 if dtype == F32 else 4e-3)
