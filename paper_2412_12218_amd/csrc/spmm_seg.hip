@@ -53,7 +53,7 @@ size_t spmm_seg_ws(int nnz, int D)
     if (dp == 0 || nnz == 0) return 0;
     const size_t n_ranges = (static_cast<size_t>(nnz) + SEG_R - 1) / SEG_R;
     const size_t seg = align_up(n_ranges * 2 * dp * sizeof(float), 256) + align_up(n_ranges * 2 * sizeof(int), 256);
-    const size_t lane = D <= 8 ? spmm_lane_ws(nnz) : 0;  // narrow rows may take the lane-per-edge kernel
+    const size_t lane = D <= 16 ? spmm_lane_ws(nnz) : 0;  // narrow rows may take the lane-per-edge kernel
     return seg > lane ? seg : lane;
 }
 
@@ -347,7 +347,7 @@ int32_t launch_spmm_seg(const ftc_csr &g, const ftc_windows &w, const float *val
                         int xdt, int D, void *out, int ldo, int odt, Epi epi, void *ws, const uint8_t *dense,
                         hipStream_t s)
 {
-    // rows of at most 16 bytes: a lane per edge run instead of four lanes per row
+    // rows of at most 32 bytes: one or two lanes per run of edges instead of four lanes per row
     if (!dense && spmm_lane_shape(xdt, D, ldx))
         return launch_spmm_lane(g, w, vals, X, ldx, xdt, D, out, ldo, odt, epi, ws, s);
     int vec = 0, lpr = 0;
