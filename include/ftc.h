@@ -207,7 +207,8 @@ int32_t ftc_gcn_layer(const ftc_csr *g, const ftc_windows *w, const float *vals,
  * P = edge softmax of s, out = P * H (H not normalised).  edge_p, when not NULL,
  * receives P (nnz floats).  Without edge_p (and with a window index) scores, softmax and
  * aggregation run fused in one pass over the edges; the softmax is then shifted by |beta|,
- * an upper bound of every score, instead of by the row maximum (same result; |beta| < 43).
+ * an upper bound of every score, instead of by the row maximum (same result); for |beta| >= 43 the
+ * unfused chain with the row-wise softmax is used.
  * row_z, when not NULL, receives the softmax denominators of that pass,
  * z_i = sum over row i of exp(beta * cos - |beta|) (n floats, 0 for a row without entries): what
  * ftc_agnn_layer_backward_fused needs instead of P.  out_f32, when not NULL, receives the result
@@ -316,7 +317,7 @@ int32_t ftc_agnn_layer_backward(const ftc_csr *g, const ftc_windows *w, const in
  * largest gradient entry with bf16 -- and out_f32 of the forward call is the better choice).
  * H and dY share dtype and leading dimension, rows 16-byte aligned; the window index is required;
  * (dtype, D) must be a width the single-pass forward covers, with at most 128 elements once
- * padded to its lane layout (ftc_plan_graph reports it).  FTC_EUNSUPPORTED otherwise: use
+ * padded to its lane layout (ftc_plan_graph reports it), and |beta| < 43.  FTC_EUNSUPPORTED otherwise: use
  * ftc_agnn_layer_backward.  The pattern is taken to be symmetric (ftc_transpose_index, flag 0,
  * checks it); on another pattern the result is the gradient of nothing.
  */

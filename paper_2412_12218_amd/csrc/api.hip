@@ -84,6 +84,8 @@ static float spmm_mfma_reuse(int D) { (void)D; return -1.f; }
 static float sddmm_mfma_reuse(int D) { return D >= 256 ? 2.6f : -1.f; }
 // Larger windows (hub rows) always stay on the edge-balanced vector kernels.
 static constexpr int MFMA_MAX_WINDOW_EDGES = 4096;
+// |beta| up to which the single-pass AGNN kernels (forward and backward) are used
+static constexpr float AGNN_FUSED_MAX_BETA = 43.f;
 
 static size_t flag_bytes(int32_t n) { return align_up(static_cast<size_t>((n + 15) / 16), 256); }
 
@@ -385,12 +387,16 @@ int32_t ftc_agnn_layer(const ftc_csr *g, const ftc_windows *w, const void *H, in
             return fail(FTC_EINVAL, "ftc_agnn_layer: out_f32 aliases out or H");
     }
     const bool keep = row_z || out_f32;
-    if (!edge_p && w && (g->nnz > 0 || keep) && path != FTC_PATH_MFMA && rows16 && seg_shape(dtype, D, &vec, &lpr))
+    // the single pass shifts the softmax by |beta| instead of the row maximum: exp(-2 |beta|) must stay a
+    // normal fp32 number; beyond that the chain with the row-wise softmax takes over
+    const bool beta_ok = fabsf(beta) < AGNN_FUSED_MAX_BETA;
+    if (!edge_p && w && beta_ok && (g->nnz > 0 || keep) && path != FTC_PATH_MFMA && rows16 &&
+        seg_shape(dtype, D, &vec, &lpr))
         return launch_agnn_fused(*g, *w, H, ld, dtype, D, beta, out, ldo, out_dtype, row_z, out_f32, ld_f32, p,
                                  static_cast<hipStream_t>(stream));
     if (keep)
         return fail(FTC_EUNSUPPORTED,
-                    "ftc_agnn_layer: row_z and out_f32 come from the single-pass route only (window index, no edge_p, not "
+                    "ftc_agnn_layer: |beta| < 43 is needed, and row_z and out_f32 come from the single-pass route only (window index, no edge_p, not "
                     "FTC_PATH_MFMA, 16-byte aligned rows, a width the edge-balanced kernels cover)");
 
     float *scores = edge_p ? edge_p : reinterpret_cast<float *>(p);
@@ -635,10 +641,10 @@ int32_t ftc_agnn_layer_backward_fused(const ftc_csr *g, const ftc_windows *w, co
     FTC_TRY(check_windows(g, w, "ftc_agnn_layer_backward_fused", false));
     if (g->nnz > 0 && !w->edge_to_row) return fail(FTC_EINVAL, "ftc_agnn_layer_backward_fused: edge_to_row is NULL");
     const bool rows16 = aligned16(H) && aligned16(dY) && (static_cast<int64_t>(ld) * elem_size(dtype)) % 16 == 0;
-    if (!rows16 || !agnn_backward_fused_shape(dtype, D))
+    if (!rows16 || !agnn_backward_fused_shape(dtype, D) || !(fabsf(beta) < AGNN_FUSED_MAX_BETA))
         return fail(FTC_EUNSUPPORTED,
-                    "ftc_agnn_layer_backward_fused: needs 16-byte aligned rows and a width the edge-balanced kernels "
-                    "cover with 2 * D <= 256 padded slots; use ftc_agnn_layer_backward");
+                    "ftc_agnn_layer_backward_fused: needs |beta| < 43, 16-byte aligned rows and a width the "
+                    "edge-balanced kernels cover with 2 * D <= 256 padded slots; use ftc_agnn_layer_backward");
     const size_t need = agnn_backward_fused_ws(g->n, g->nnz, D);
     if (!ws || ws_bytes < need)
         return fail(FTC_EWORKSPACE, "ftc_agnn_layer_backward_fused: workspace of %zu bytes needed", need);

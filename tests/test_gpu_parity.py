@@ -561,6 +561,25 @@ def test_agnn_layer(oracle, graphs, name, dtype, D, beta):
     assert norm_err(out4, ref, ab) < TOL[dtype]
 
 
+def test_agnn_layer_beyond_the_single_pass_beta_range(oracle, graphs):
+    """|beta| >= 43: exp(-2 |beta|) is no fp32 number any more; the layer takes the chain with the
+    row-wise softmax, and the outputs only the single pass can give are refused."""
+    g = graphs["cfg1"]
+    Hd, H64 = quantise(synth.normal_features(g.n, 32, seed=12), F16)
+    dg = dev_graph(g)
+    win = B.ftc_build_windows(dg)
+    for beta in (60.0, -75.0):
+        ref, ab, _ = oracle.agnn_layer(g.row_ptr, g.col_idx, H64, beta)
+        out = B.ftc_agnn_layer(dg, win, Hd, beta=beta)
+        assert torch.all(torch.isfinite(out))
+        assert norm_err(out, ref, ab) < 2e-3
+    with pytest.raises(B.FtcError):
+        B.ftc_agnn_layer(dg, win, Hd, beta=60.0, row_z=torch.empty(g.n, dtype=F32, device="cuda"))
+    z = torch.ones(g.n, dtype=F32, device="cuda")
+    with pytest.raises(B.FtcError):
+        B.ftc_agnn_layer_backward_fused(dg, win, Hd, z, Hd.float(), Hd.clone(), beta=60.0)
+
+
 def test_agnn_layer_fused_large_beta_and_fp16_out(oracle, graphs):
     g = graphs["cfg5s"]
     Hd, H64 = quantise(synth.normal_features(g.n, 32, seed=12), F16)
