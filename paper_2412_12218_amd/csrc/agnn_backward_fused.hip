@@ -117,7 +117,7 @@ __global__ __launch_bounds__(256) void agnn_backward_fused_kernel(
     int *s_col = smem + wave * 2 * RP;
     int *s_row = s_col + RP;
 
-    const int v = blockIdx.x * 4 + wave;
+    const int v = xcd_chunked_block(blockIdx.x, gridDim.x) * 4 + wave;
     const bool active = v < n_ranges;
     const int base = active ? v * SEG_R : 0;
     const int n_valid = active ? min(SEG_R, nnz - base) : 0;

@@ -337,6 +337,23 @@ __global__ void spmm_seg_fixup_kernel(int n, int n_ranges, const int *__restrict
                                       int D, void *__restrict__ out, int ldo, int odt, Epi epi,
                                       const uint8_t *__restrict__ dense, int seg_r);
 
+// Workgroups are handed to the eight XCDs round-robin by their index, and every XCD has an L2 of its
+// own.  The edge-balanced kernels walk the edges in order, so neighbouring workgroups gather
+// neighbouring rows' columns: this maps the workgroups so that every XCD works on chunks of
+// XCD_CHUNK consecutive logical blocks (the k-th workgroup of XCD x takes block k % XCD_CHUNK of chunk
+// (k / XCD_CHUNK) * 8 + x) instead of on every eighth block.  Chunks, not one contiguous eighth of
+// the edges per XCD: the cost of a block varies along the edge list of a skewed graph, and whole
+// eighths were measured 10 to 40 % slower there.  The blocks beyond the last full group of eight
+// chunks keep their index.
+constexpr int XCD_CHUNK = 16;
+__device__ __forceinline__ int xcd_chunked_block(int b, int grid)
+{
+    const int full = grid / (8 * XCD_CHUNK) * (8 * XCD_CHUNK);
+    if (b >= full) return b;
+    const int x = b & 7, k = b >> 3;
+    return ((k / XCD_CHUNK) * 8 + x) * XCD_CHUNK + k % XCD_CHUNK;
+}
+
 // Inclusive prefix sum over the 64 lanes of a wave with data-parallel-primitive moves: shifts by
 // 1, 2, 4, 8 inside rows of 16 lanes, then lane 15 of a row added to the next row (rows 1 and 3) and
 // lane 31 added to rows 2 and 3.

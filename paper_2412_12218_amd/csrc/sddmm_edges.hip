@@ -42,7 +42,7 @@ __global__ __launch_bounds__(256) void sddmm_edges_kernel(int nnz, int n_ranges,
     int *s_row = s_row_all[wave];
     float *s_dot = s_dot_all[wave];
 
-    const int v = blockIdx.x * 4 + wave;
+    const int v = xcd_chunked_block(blockIdx.x, gridDim.x) * 4 + wave;
     const bool active = v < n_ranges;
     const int base = active ? v * SD_R : 0;
     const int n_valid = active ? min(SD_R, nnz - base) : 0;

@@ -93,7 +93,7 @@ __global__ __launch_bounds__(256) void spmm_lane_kernel(int nnz, int n_ranges, c
     constexpr int RANGE = SL_R / LPE;          // edges per wave
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int slot = lane / LPE, piece = lane % LPE;
-    const int v = blockIdx.x * 4 + wave;
+    const int v = xcd_chunked_block(blockIdx.x, gridDim.x) * 4 + wave;
     if (v >= n_ranges) return;  // no workgroup barrier below
     const int base = v * RANGE;
     const int n_valid = min(RANGE, nnz - base);

@@ -84,7 +84,7 @@ __global__ __launch_bounds__(256) void spmm_seg_kernel(int nnz, int n_ranges, co
     int *s_row = s_col + RP;
     float *s_val = reinterpret_cast<float *>(s_row + RP);  // only with VALS
 
-    const int v = blockIdx.x * 4 + wave;
+    const int v = xcd_chunked_block(blockIdx.x, gridDim.x) * 4 + wave;
     const bool active = v < n_ranges;
     const int base = active ? v * SEG_R : 0;
     const int n_valid = active ? min(SEG_R, nnz - base) : 0;
