@@ -674,3 +674,24 @@ def test_spmm_sddmm_agnn_random_shapes(oracle, case):
     sref, sab = oracle.sddmm(g.row_ptr, g.col_idx, Hn, Hn)
     s = B.ftc_sddmm(dg, win, Hd, Hd, cosine=True)
     assert float(np.max(np.abs(s.cpu().double().numpy() - sref))) < (1e-5 if dtype == F32 else 4e-3)
+
+
+def test_spmm_narrow_rows_at_slot_and_wave_boundaries(oracle):
+    """Row lengths that end exactly on slot (16 edges) and wave (512 / 1024 edges) boundaries, a row
+    covering several whole waves, empty rows in between, and a total that is a multiple of 1024."""
+    deg = [16, 0, 16, 32, 0, 0, 1024, 1, 15, 512, 3000, 0, 48, 1024 - 16, 2048, 0, 7]
+    deg.append((-sum(deg)) % 1024 + 1024)
+    n = len(deg)
+    row_ptr = np.zeros(n + 1, dtype=np.int32)
+    row_ptr[1:] = np.cumsum(deg)
+    assert row_ptr[-1] % 1024 == 0
+    rng = np.random.default_rng(5)
+    g = synth.Graph(n, row_ptr, rng.integers(0, n, size=int(row_ptr[-1])).astype(np.int32), "boundaries")
+    for dtype, D in ((F16, 8), (F16, 16), (F32, 4), (F32, 8), (BF16, 5)):
+        pad = (-D) % (4 if dtype == F32 else 8)
+        say(f"boundaries {dtype} D={D}")
+        # n is tiny, so every column repeats hundreds of times in the long rows: fp32 sums of equal
+        # terms drift by a rounding error per term, hence the looser bar for fp32 here
+        tol = 1e-4 if dtype == F32 else TOL[dtype]
+        assert run_spmm(oracle, g, dtype, D, pad=pad) < tol
+        assert run_spmm(oracle, g, dtype, D, pad=pad, use_vals=False) < tol
