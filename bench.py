@@ -87,7 +87,7 @@ def cpu_baseline(scale, seed, g=None):
                       f"same recipe as the workload, {dt:.1f} s"}
 
 
-def kernel_suite(tag, g, feat32, dtype, D, iters=20):
+def kernel_suite(tag, g, feat32, dtype, D, iters=20, oracle=False):
     """Stand-alone SpMM / SDDMM / edge-softmax timings on one graph (events on the launch stream), warm (back to
     back) and cold (a 1 GiB buffer is overwritten between launches so that neither L2 nor the
     memory-side cache holds X).  Returns a dict of ms and algorithmic GB/s."""
@@ -138,6 +138,39 @@ def kernel_suite(tag, g, feat32, dtype, D, iters=20):
             res[f"{op}_{mode}_GBs"] = nbytes[op] / (ms * 1e-3) / 1e9
             res[f"{op}_{mode}_frac"] = nbytes[op] / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS
         res[f"{op}_alg_bytes"] = nbytes[op]
+    if oracle:
+        del X, out, s_out, p_out, flush, ws, ws_sm
+        res["oracle"] = oracle_kernel_times(g, feat32, dtype, nbytes)
+    return res
+
+
+def oracle_kernel_times(g, feat32, dtype, nbytes):
+    """The oracle's SpMM / SDDMM (cosine scores) / edge softmax on the same graph and the same quantised
+    features, one thread and all host threads: seconds and GB/s by the same algorithmic byte counts."""
+    import numpy as np
+    import torch
+    from oracle import ftc_oracle as orc
+    X = torch.from_numpy(feat32).to(dtype).to(torch.float64).numpy()
+    vals, _ = orc.gcn_norm(g.row_ptr, g.col_idx)
+    rinv = orc.row_rnorm(X)
+    s = orc.sddmm(g.row_ptr, g.col_idx, X, X, rinv, rinv, 1.0)
+    fns = {"spmm": lambda: orc.spmm(g.row_ptr, g.col_idx, vals, X),
+           "sddmm": lambda: orc.sddmm(g.row_ptr, g.col_idx, X, X, rinv, rinv, 1.0),
+           "softmax": lambda: orc.edge_softmax(g.row_ptr, s)}
+    res = {}
+    orc.set_threads(0)
+    for fn in fns.values():     # untimed: thread pool start-up, first touch of the allocator's pages
+        fn()
+    for label, t in (("1_thread", 1), ("all_threads", 0)):
+        used = orc.set_threads(t)
+        for op, fn in fns.items():
+            t0 = time.perf_counter()
+            fn()
+            dt = time.perf_counter() - t0
+            res[f"{op}_{label}_s"] = dt
+            res[f"{op}_{label}_GBs"] = nbytes[op] / dt / 1e9
+        res[f"{label}_count"] = used
+    orc.set_threads(1)
     return res
 
 
@@ -539,9 +572,11 @@ def main():
         del hp2, pg, Xp, ws_ro
     if not args.no_kernels:
         # the two largest graphs: stand-alone aggregation and edge-score kernels, fp32 output
-        k5 = kernel_suite("cfg5 R-MAT", g, synth.normal_features(g.n, 32, seed + 20), torch.float16, 32)
+        k5 = kernel_suite("cfg5 R-MAT", g, synth.normal_features(g.n, 32, seed + 20), torch.float16, 32,
+                          oracle=args.cpu_scale > 0)
         g4 = synth.config_graph(4) if args.scale == 20 else synth.config_graph(4, 2.0 ** (args.scale - 20))
-        k4 = kernel_suite("cfg4 SBM", g4, synth.uniform_features(g4.n, 64, 3 + 20), torch.bfloat16, 64)
+        k4 = kernel_suite("cfg4 SBM", g4, synth.uniform_features(g4.n, 64, 3 + 20), torch.bfloat16, 64,
+                          oracle=args.cpu_scale > 0)
         out["kernels"] = [k4, k5]
     if args.cpu_scale > 0:
         out["cpu_baseline"] = cpu_baseline(args.cpu_scale, seed, g if args.cpu_scale == args.scale else None)
