@@ -442,7 +442,8 @@ int32_t launch_edge_dot(int nnz, const float *a, const float *b, float *out, voi
 // ---- dH = base + rinv * (q - hn <hn, q>), hn = rinv * h --------------------------------------------
 // q is the gradient with respect to the normalised rows, base the part of dH that reaches h through
 // the aggregated rows; eight lanes per row.  A row whose norm was clamped (|h| <= 1e-12) is a plain
-// scaling: no projection.  base may be dH itself (fp32, in place).
+// scaling: no projection; a row of one element gets nothing through its direction unless clamped.
+// base may be dH itself (fp32, in place).
 // VEC4: four consecutive elements per lane and step (16-byte loads of q and base; every leading
 // dimension a multiple of 4, D too, pointers 16-byte aligned), else element by element.
 template <bool VEC4>
@@ -482,7 +483,11 @@ __global__ __launch_bounds__(256) void cos_backward_rows_kernel(int n, const voi
     proj += __shfl_xor(proj, 1, 64);
     proj += __shfl_xor(proj, 2, 64);
     proj += __shfl_xor(proj, 4, 64);
-    if (ri >= 0.999e12f) proj = 0.f;  // the clamp of the row-norm kernel took effect
+    const bool clamped = ri >= 0.999e12f;  // the clamp of the row-norm kernel took effect
+    if (clamped) proj = 0.f;
+    // A one-element row normalises to its sign, whose derivative is zero: q - hn <hn, q> would leave the
+    // rounding of hn * hn against 1, multiplied by 1 / |h|.
+    const float ri_out = (D == 1 && !clamped) ? 0.f : ri;
     if (ok) {
         if constexpr (VEC4) {
 #pragma unroll
@@ -500,7 +505,7 @@ __global__ __launch_bounds__(256) void cos_backward_rows_kernel(int n, const voi
         } else {
             for (int k = sub; k < D; k += 8) {
                 const float hn = load_elem(H, row * ld + k, dt) * ri;
-                store_elem(dH, row * lddh + k, dh_dt, base[row * ldb + k] + ri * (q[row * ldq + k] - hn * proj));
+                store_elem(dH, row * lddh + k, dh_dt, base[row * ldb + k] + ri_out * (q[row * ldq + k] - hn * proj));
             }
         }
     }

@@ -27,10 +27,15 @@ def say(msg):
     print(msg, flush=True)
 
 
-def row_err(got, ref):
+def row_err(got, ref, cancelled=None):
+    """Largest error of a row relative to the row's largest reference value plus 1 % of the overall largest.
+    cancelled[i], if given, is the size of the terms that cancel inside row i's result before they reach it:
+    eight fp32 roundings (2^-24 each) of them are allowed on top of a 1e-5 bar."""
     got = got.detach().cpu().double().numpy()
     assert np.all(np.isfinite(got))
     scale = np.abs(ref).max(axis=1, keepdims=True) + 0.01 * np.abs(ref).max()
+    if cancelled is not None:
+        scale = scale + (8 * 2.0 ** -24 / 1e-5) * np.asarray(cancelled).reshape(-1, 1)
     return float(np.max(np.abs(got - ref) / np.where(scale > 0, scale, 1.0))) if ref.size else 0.0
 
 
@@ -538,11 +543,13 @@ def test_backward_rejects_bad_arguments():
 
 
 # ------------------------------------------------------------------ seeded sweep over shapes
-@pytest.mark.parametrize("case", range(16))
+@pytest.mark.parametrize("case", list(range(16)) + [33, 39, 132, 384])
 def test_agnn_backward_random_shapes(case):
     """Symmetric random graphs from 1 to a few thousand nodes (isolated nodes, self-loops on some,
     a long row in the larger ones), widths from 1 to 64: the edge-array route always, the single-pass
-    route where it covers the shape, both against the oracle."""
+    route where it covers the shape, both against the oracle.  (Cases 39 and 132: one-element rows with
+    norms down to 1e-4, where the gradient through the direction is exactly zero; case 33: a row with a
+    single neighbour on the single-pass route; case 384: a signed sum of one-element rows that nearly cancels.)"""
     import scipy.sparse as sp
     rng = np.random.default_rng(2000 + case)
     n = int(rng.choice([1, 2, 17, 64, 500, 1025, 3000]))
@@ -572,13 +579,24 @@ def test_agnn_backward_random_shapes(case):
     p = torch.empty(g.nnz, dtype=F32, device="cuda")
     B.ftc_agnn_layer(dg, win, Hd, beta=beta, edge_p=p)
     dH, dbeta = B.ftc_agnn_layer_backward(dg, win, T, Hd, p, dYd, beta=beta)
-    assert row_err(dH, dH_ref) < 1e-5
+    # the part of dH_i that arrives through the aggregated rows is the signed sum of p_ji dY_j over the
+    # rows j that hold i: its terms cancel (visibly so with one-element rows)
+    from oracle import ftc_oracle
+    Y_ref, _, p_ref = ftc_oracle.agnn_layer(g.row_ptr, g.col_idx, H64, beta)
+    P = sp.csr_matrix((p_ref, g.col_idx, g.row_ptr), shape=(n, n))
+    agg_abs = np.asarray(P.T @ np.abs(dY64)).max(axis=1) if g.nnz else np.zeros(n)
+    assert row_err(dH, dH_ref, agg_abs) < 1e-5
     assert abs(float(dbeta.item()) - dbeta_ref) < 1e-4 * max(abs(dbeta_ref), 1.0)
     fused_ok = B.lib().ftc_agnn_layer_backward_fused_workspace_bytes(n, g.nnz, D) > 0 and (D * Hd.element_size()) % 16 == 0
     if fused_ok:
         row_z = torch.empty(n, dtype=F32, device="cuda")
         Y = B.ftc_agnn_layer(dg, win, Hd, beta=beta, row_z=row_z)
         dH2, dbeta2 = B.ftc_agnn_layer_backward_fused(dg, win, Hd, row_z, Y, dYd, beta=beta)
-        assert row_err(dH2, dH_ref) < 1e-5
+        # The single pass takes t_i = <dY_i, y_i> from the stored output instead of summing p dp, so
+        # p (dp - t_i) keeps a rounding of the two terms where they cancel (a row whose attention sits on
+        # one neighbour); it reaches dH_i as |beta| |dY_i| |y_i| / |h_i|.
+        nrm = lambda a: np.sqrt((a * a).sum(axis=1))
+        cancelled = abs(beta) * nrm(dY64) * nrm(Y_ref) / np.maximum(nrm(H64), 1e-12)
+        assert row_err(dH2, dH_ref, agg_abs + cancelled) < 1e-5
         assert abs(float(dbeta2.item()) - dbeta_ref) < 1e-4 * max(abs(dbeta_ref), 1.0)
         say("  single-pass route checked too")
