@@ -160,12 +160,14 @@ int32_t ftc_spmm(const ftc_csr *g, const ftc_windows *w, const float *vals, cons
     const bool rows16 = aligned16(X) && aligned16(out) &&
                         (static_cast<int64_t>(ldx) * elem_size(x_dtype)) % 16 == 0 &&
                         (static_cast<int64_t>(ldo) * elem_size(out_dtype)) % 16 == 0;
-    const bool can_seg = w && g->nnz > 0 && rows16 && seg_shape(x_dtype, D, &vec, &lpr);
-    const bool can_mfma = can_seg && w->blk_h == 16 && mfma_shape_ok(x_dtype, D);
-    if (path == FTC_PATH_MFMA && !can_mfma)
+    const bool seg_ok = w && rows16 && seg_shape(x_dtype, D, &vec, &lpr);
+    const bool mfma_ok = seg_ok && w->blk_h == 16 && mfma_shape_ok(x_dtype, D);
+    if (path == FTC_PATH_MFMA && !mfma_ok)
         return fail(FTC_EUNSUPPORTED,
                     "ftc_spmm: the matrix-core path needs a window index with blk_h = 16, fp16/bf16 "
                     "features with D a multiple of 8 (<= 256) and 16-byte aligned rows");
+    // a graph without entries only has its output rows cleared, whatever the path
+    const bool can_seg = seg_ok && g->nnz > 0, can_mfma = mfma_ok && g->nnz > 0;
     if (can_seg) {
         const size_t need = ftc_spmm_workspace_bytes(g->n, g->nnz, D);
         if (!ws || ws_bytes < need)

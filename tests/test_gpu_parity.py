@@ -287,6 +287,23 @@ def test_mfma_path_rejected_where_it_cannot_run(graphs):
     B.ftc_spmm(dg, win8, None, Xh)      # the default path still works with other window heights
 
 
+def test_forced_paths_on_a_graph_without_entries():
+    """No entries: every path clears the output rows (SpMM, AGNN layer) or has nothing to write (SDDMM)."""
+    n = 33
+    g = synth.Graph(n, np.zeros(n + 1, dtype=np.int32), np.zeros(0, dtype=np.int32), "no_edges")
+    dg = dev_graph(g)
+    win = B.ftc_build_windows(dg)
+    X = torch.randn((n, 32), device="cuda").to(F16)
+    for path in (B.FTC_PATH_AUTO, B.FTC_PATH_MFMA, B.FTC_PATH_VALU):
+        out = torch.full((n, 32), 5.0, device="cuda")
+        B.ftc_spmm(dg, win, None, X, out=out, path=path)
+        assert float(out.abs().max()) == 0.0
+        assert B.ftc_sddmm(dg, win, X, X, path=path).numel() == 0
+        out = torch.full((n, 32), 5.0, device="cuda")
+        B.ftc_agnn_layer(dg, win, X, out=out, path=path)
+        assert float(out.abs().max()) == 0.0
+
+
 # ------------------------------------------------------------------ SDDMM
 def run_sddmm(oracle, g, dtype, D, *, scales=True, with_windows=True, same=False, seed=1, pad=0,
               path=B.FTC_PATH_AUTO):
