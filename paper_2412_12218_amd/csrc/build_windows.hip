@@ -53,6 +53,8 @@ static int hub_slots(int n, int nnz)
 }
 static int hub_words_per_slot(int n) { return ((n + 31) / 32 + HUB_GROUP - 1) / HUB_GROUP * HUB_GROUP; }
 
+constexpr int PACK_PER_WAVE = 1024;  // entries of win_cols that one wave of the pack kernel copies
+
 struct WinWorkspace {
     int *uniq_count;      // [n_windows]
     int *list_mid;        // [cap_mid]    windows of WAVE_CAP+1 .. MID_CAP edges
@@ -64,6 +66,7 @@ struct WinWorkspace {
     uint32_t *hub_bits;   // [slots * words_per_slot]
     int *hub_grp;         // [slots * words_per_slot / HUB_GROUP]
     int *tmp_cols;        // [nnz]
+    int *pack_win;        // [nnz / PACK_PER_WAVE + 2]  window of every PACK_PER_WAVE-th entry of win_cols
     int cap_mid, cap_large, slots, wps;
     size_t total;
 };
@@ -92,6 +95,7 @@ static WinWorkspace carve(void *ws, int n, int nnz, int n_windows)
     w.hub_bits = reinterpret_cast<uint32_t *>(take(sizeof(uint32_t) * static_cast<size_t>(w.slots) * w.wps));
     w.hub_grp = reinterpret_cast<int *>(take(sizeof(int) * static_cast<size_t>(w.slots) * (w.wps / HUB_GROUP)));
     w.tmp_cols = reinterpret_cast<int *>(take(sizeof(int) * static_cast<size_t>(nnz)));
+    w.pack_win = reinterpret_cast<int *>(take(sizeof(int) * (static_cast<size_t>(nnz) / PACK_PER_WAVE + 2)));
     w.total = off;
     return w;
 }
@@ -792,51 +796,107 @@ __global__ __launch_bounds__(1024) void win_scan_kernel(int n_windows, int blk_w
     }
 }
 
-// Packs the unique lists.  Slot e of the temporary array belongs to the window of edge e
-// (edge_to_row); it holds a list entry when its offset inside the window is below the window's
-// unique count.  A thread takes eight consecutive slots (two 16-byte loads per array; the slot's
-// content is loaded together with the edge's row, although 13 % of the slots on the R-MAT workload
-// hold no list entry: one step less in the chain of dependent loads).
-__global__ __launch_bounds__(256) void win_pack_kernel(int nnz, const int *__restrict__ row_ptr, int blk_h,
-                                                       const int *__restrict__ edge_to_row,
-                                                       const int *__restrict__ win_col_ptr,
-                                                       const int *__restrict__ tmp_cols,
-                                                       int *__restrict__ win_cols, bool vec)
+// The pack kernel's work units are runs of PACK_PER_WAVE entries of win_cols.  Every window names
+// itself to the runs that begin inside its list (none for most windows; at most n / PACK_PER_WAVE + 1
+// for one window, since a list has at most n entries); the entry after the last run holds the last
+// window, so that a run always finds the window of its successor's first entry.
+__global__ __launch_bounds__(256) void win_pack_plan_kernel(int n_windows, const int *__restrict__ win_col_ptr,
+                                                            int *__restrict__ pack_win)
 {
-    const int64_t e0 = (static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x) * 8;
-    if (e0 >= nnz) return;
-    int r[8], v[8];
-    if (vec && e0 + 8 <= nnz) {
+    const int w = blockIdx.x * 256 + threadIdx.x;
+    if (w >= n_windows) return;
+    const int b = win_col_ptr[w], e = win_col_ptr[w + 1];
+    for (int c = static_cast<int>((b + static_cast<long long>(PACK_PER_WAVE) - 1) / PACK_PER_WAVE);
+         c * static_cast<long long>(PACK_PER_WAVE) < e; ++c)
+        pack_win[c] = w;
+    if (w == n_windows - 1) pack_win[(e + static_cast<long long>(PACK_PER_WAVE) - 1) / PACK_PER_WAVE] = w;
+}
+
+// Packs the unique lists.  Window w's list lies at the start of its slot range of the temporary array
+// (the slot of an edge is its index) and goes to win_cols[win_col_ptr[w] ...].  The work is balanced
+// over the OUTPUT: a wave copies PACK_PER_WAVE consecutive entries of win_cols, so only list entries
+// are read (13 % of the slots on the R-MAT workload hold none) and no per-edge array is needed to
+// name the window.  The plan kernel has left the window of every run's first entry in pack_win (a
+// search over win_col_ptr here, 64 or 256 scattered probes per wave and round, cost more memory
+// requests than the copy itself); the list starts and slot starts of the run's windows are fetched
+// one per lane, every entry picks its window from those registers, then all reads of the temporary
+// array are issued together.
+// More than 256 windows in a wave's run (lists of under four entries on average): binary search per entry.
+constexpr int PACK_WPL = 4;  // windows per lane held in registers
+
+__global__ __launch_bounds__(256) void win_pack_kernel(int n_windows, const int *__restrict__ row_ptr, int blk_h,
+                                                       const int *__restrict__ win_col_ptr,
+                                                       const int *__restrict__ pack_win,
+                                                       const int *__restrict__ tmp_cols,
+                                                       int *__restrict__ win_cols)
+{
+    constexpr int STEPS = PACK_PER_WAVE / 64;
+    const int lane = threadIdx.x & 63;
+    const int64_t run = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    const int total = win_col_ptr[n_windows];
+    if (run * PACK_PER_WAVE >= total) return;  // the whole wave (the grid is sized for the capacity of win_cols)
+    const int o_first = static_cast<int>(run) * PACK_PER_WAVE;
+    const int o_last = (o_first + PACK_PER_WAVE < total ? o_first + PACK_PER_WAVE : total) - 1;
+    // pack_win[run + 1] is the window of the next run's first entry, or the last window
+    const int w_lo = pack_win[run], w_hi = pack_win[run + 1], n_win = w_hi - w_lo + 1;
+    int src[STEPS];
+    if (n_win <= 64 * PACK_WPL) {
+        int begin_l[PACK_WPL], first_l[PACK_WPL];  // of window w_lo + 64 q + lane
 #pragma unroll
-        for (int q = 0; q < 2; ++q) {
-            const int4 a = *reinterpret_cast<const int4 *>(edge_to_row + e0 + 4 * q);
-            const int4 b = *reinterpret_cast<const int4 *>(tmp_cols + e0 + 4 * q);
-            r[4 * q] = a.x; r[4 * q + 1] = a.y; r[4 * q + 2] = a.z; r[4 * q + 3] = a.w;
-            v[4 * q] = b.x; v[4 * q + 1] = b.y; v[4 * q + 2] = b.z; v[4 * q + 3] = b.w;
+        for (int q = 0; q < PACK_WPL; ++q) {
+            const bool in = q * 64 + lane < n_win;
+            begin_l[q] = in ? win_col_ptr[w_lo + q * 64 + lane] : INT32_MAX;
+            first_l[q] = in ? row_ptr[(w_lo + q * 64 + lane) * blk_h] : 0;
+        }
+        int begin[STEPS], first[STEPS];
+#pragma unroll
+        for (int j = 0; j < STEPS; ++j) { begin[j] = 0; first[j] = 0; }
+#pragma unroll
+        for (int q = 0; q < PACK_WPL; ++q) {
+            const int n_q = n_win - q * 64 < 64 ? n_win - q * 64 : 64;
+            for (int t = 0; t < n_q; ++t) {  // list starts are non-decreasing: the last window that starts at or before the entry
+                const int bt = __builtin_amdgcn_readlane(begin_l[q], t), ft = __builtin_amdgcn_readlane(first_l[q], t);
+#pragma unroll
+                for (int j = 0; j < STEPS; ++j) {
+                    if (o_first + j * 64 + lane >= bt) { begin[j] = bt; first[j] = ft; }
+                }
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < STEPS; ++j) {
+            const int o = o_first + j * 64 + lane;
+            src[j] = o <= o_last ? first[j] + (o - begin[j]) : -1;
         }
     } else {
+        int w = w_lo;
+        int w_begin = win_col_ptr[w], w_end = win_col_ptr[w + 1], first = row_ptr[w * blk_h];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const bool ok = e0 + j < nnz;
-            r[j] = ok ? edge_to_row[e0 + j] : -1;
-            v[j] = ok ? tmp_cols[e0 + j] : 0;
+        for (int j = 0; j < STEPS; ++j) {
+            const int o = o_first + j * 64 + lane;
+            src[j] = -1;
+            if (o <= o_last) {
+                if (o >= w_end) {  // the entry's window lies in (w, w_hi]
+                    int a = w + 1 < w_hi ? w + 1 : w_hi, b = w_hi;
+                    while (a < b) {
+                        const int m = (a + b + 1) >> 1;
+                        if (win_col_ptr[m] <= o) a = m;
+                        else b = m - 1;
+                    }
+                    w = a;
+                    w_begin = win_col_ptr[w];
+                    w_end = win_col_ptr[w + 1];
+                    first = row_ptr[w * blk_h];
+                }
+                src[j] = first + (o - w_begin);
+            }
         }
     }
-    // consecutive slots mostly share their window: its three numbers are looked up once per change
-    int w_prev = -1, first = 0, dst = 0, len = 0;
+    int val[STEPS];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        if (r[j] < 0) continue;
-        const int w = r[j] / blk_h;
-        if (w != w_prev) {
-            w_prev = w;
-            first = row_ptr[w * blk_h];
-            dst = win_col_ptr[w];
-            len = win_col_ptr[w + 1] - dst;
-        }
-        const int k = static_cast<int>(e0 + j) - first;
-        if (k < len) win_cols[dst + k] = v[j];
-    }
+    for (int j = 0; j < STEPS; ++j) val[j] = src[j] >= 0 ? tmp_cols[src[j]] : 0;
+#pragma unroll
+    for (int j = 0; j < STEPS; ++j)
+        if (src[j] >= 0) win_cols[o_first + j * 64 + lane] = val[j];
 }
 
 // Side streams for the kernels that do not depend on each other (created once per process and
@@ -979,8 +1039,10 @@ int32_t launch_build_windows(const ftc_csr &g, ftc_windows &w, void *ws, size_t 
     st = launch_status("build_windows scan");
     if (st != FTC_OK) return st;
     if (g.nnz == 0) return FTC_OK;
-    hipLaunchKernelGGL(win_pack_kernel, dim3((g.nnz + 2047) / 2048), dim3(256), 0, s, g.nnz, g.row_ptr, w.blk_h,
-                       w.edge_to_row, w.win_col_ptr, k.tmp_cols, w.win_cols, aligned16(w.edge_to_row));
+    hipLaunchKernelGGL(win_pack_plan_kernel, dim3((w.n_windows + 255) / 256), dim3(256), 0, s, w.n_windows, w.win_col_ptr,
+                       k.pack_win);
+    hipLaunchKernelGGL(win_pack_kernel, dim3((g.nnz + 4 * PACK_PER_WAVE - 1) / (4 * PACK_PER_WAVE)), dim3(256), 0, s,
+                       w.n_windows, g.row_ptr, w.blk_h, w.win_col_ptr, k.pack_win, k.tmp_cols, w.win_cols);
     return launch_status("build_windows pack");
 }
 
