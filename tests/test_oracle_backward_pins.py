@@ -79,6 +79,31 @@ def test_agnn_backward_matches_finite_differences(oracle, seed, symmetric, beta)
     assert np.isclose(dbeta, fd(loss, b)[0], rtol=2e-6, atol=1e-7)
 
 
+def test_agnn_backward_of_a_row_below_the_norm_clamp(oracle):
+    """|h_i| <= 1e-12: the forward pass scales the row by 1e12 instead of normalising it, so the row enters
+    linearly and its gradient has no projection term.  Central differences with a step far below the row's
+    own size (the forward oracle is smooth there) pin exactly that."""
+    g = small_graph(1, symmetric=True)
+    rng = np.random.default_rng(31)
+    H = rng.standard_normal((g.n, 4))
+    R = rng.standard_normal((g.n, 4))
+    i = 5
+    H[i] = 5e-13 * rng.standard_normal(4) / 2.0
+    assert np.linalg.norm(H[i]) < 1e-12 and g.row_ptr[i + 1] > g.row_ptr[i]
+
+    def loss():
+        Y, _, _ = oracle.agnn_layer(g.row_ptr, g.col_idx, H, 1.5)
+        return float((Y * R).sum())
+
+    dH, _ = ob.agnn_layer_backward(g.row_ptr, g.col_idx, H, 1.5, R)
+    row = H[i:i + 1]                                   # a view: fd() perturbs H in place
+    num = fd(loss, row, eps=1e-16)
+    assert np.abs(num).max() > 1e9                     # the 1e12 scaling is visible
+    assert np.allclose(dH[i], num[0], rtol=1e-5)
+    others = np.delete(np.arange(g.n), i)
+    assert np.allclose(dH[others], fd(loss, H)[others], rtol=2e-6, atol=1e-7)
+
+
 def test_agnn_backward_beta_zero_is_mean_aggregation():
     """beta = 0: P = D^-1 A does not depend on H, so dH = P^T dY exactly (dense check)."""
     g = small_graph(3)

@@ -324,6 +324,10 @@ def test_softmax_large_scores_do_not_overflow(oracle):
     p = oracle.edge_softmax(np.array([0, 3]), np.array([1000.0, 1001.0, 999.0]))
     want = np.exp([-1.0, 0.0, -2.0]); want /= want.sum()
     assert np.allclose(p, want, rtol=1e-14)
+    # a spread that only the shift by the row MAXIMUM survives (exp(1600) is no double)
+    p = oracle.edge_softmax(np.array([0, 3]), np.array([800.0, -800.0, 799.0]))
+    e = np.exp(-1.0)
+    assert np.allclose(p, [1.0 / (1.0 + e), 0.0, e / (1.0 + e)], rtol=1e-14, atol=0)
 
 
 # ---------------------------------------------------------------- layers
