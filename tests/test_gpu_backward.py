@@ -410,10 +410,20 @@ def test_agnn_layer_backward_zero_rows_and_isolated_nodes():
     B.ftc_agnn_layer(dg, win, Hd, beta=1.5, edge_p=p)
     dH, dbeta = B.ftc_agnn_layer_backward(dg, win, T, Hd, p, dYd, beta=1.5)
     keep = np.ones(g.n, dtype=bool)
-    keep[17] = False                       # d/dh of h/max(|h|, eps) at h = 0 is 1/eps: not compared
+    keep[17] = False                       # d/dh of h/max(|h|, eps) at h = 0 is 1/eps: compared on its own scale
     assert row_err(dH[torch.from_numpy(keep).cuda()], dH_ref[keep]) < 1e-4
     assert np.all(np.isfinite(dH.cpu().numpy()))
     assert abs(float(dbeta.item()) - dbeta_ref) < 1e-4 * max(abs(dbeta_ref), 1.0)
+    # the clamped row is the plain scaling by 1e12 that the forward pass applies: no projection term
+    assert np.abs(dH_ref[17]).max() > 1e9
+    assert np.max(np.abs(dH[17].cpu().double().numpy() - dH_ref[17])) < 1e-4 * np.abs(dH_ref[17]).max()
+    # the same through the single-pass route
+    row_z = torch.empty(g.n, dtype=F32, device="cuda")
+    Y = B.ftc_agnn_layer(dg, win, Hd, beta=1.5, row_z=row_z)
+    dH2, dbeta2 = B.ftc_agnn_layer_backward_fused(dg, win, Hd, row_z, Y, dYd, beta=1.5)
+    assert row_err(dH2[torch.from_numpy(keep).cuda()], dH_ref[keep]) < 1e-4
+    assert np.max(np.abs(dH2[17].cpu().double().numpy() - dH_ref[17])) < 1e-4 * np.abs(dH_ref[17]).max()
+    assert abs(float(dbeta2.item()) - dbeta_ref) < 1e-4 * max(abs(dbeta_ref), 1.0)
 
 
 def test_agnn_layer_backward_16bit_gradient_output(graphs):
