@@ -180,8 +180,10 @@ int32_t ftc_edge_softmax(const ftc_csr *g, const ftc_windows *w, const float *e_
 /*
  * Dense update phase (Section I.A.2): Z = X * W, X n x d_in (dtype), W d_in x d_out
  * row-major of the same dtype, fp32 accumulation, Z n x d_out of z_dtype.
- * d_in <= 256 and d_out <= 64.  row_scale (n floats, may be NULL) multiplies row i of the
- * product by row_scale[i]; relu != 0 then applies max(0, .).
+ * Any d_in, d_out >= 1: W stays on chip for d_in <= 256 and d_out <= 64 (the benchmark models);
+ * wider inputs are contracted in chunks, wider outputs written in groups of 64 columns (X is read
+ * once per group).  row_scale (n floats, may be NULL) multiplies row i of the product by
+ * row_scale[i]; relu != 0 then applies max(0, .).
  */
 int32_t ftc_update_gemm(int32_t n, const void *X, int32_t ldx, int32_t dtype, int32_t d_in,
                         const void *W, int32_t d_out, void *Z, int32_t ldz, int32_t z_dtype,

@@ -301,7 +301,6 @@ int32_t ftc_update_gemm(int32_t n, const void *X, int32_t ldx, int32_t dtype, in
     FTC_TRY(check_dense(X, ldx, dtype, d_in, "ftc_update_gemm", "X"));
     FTC_TRY(check_dense(Z, ldz, z_dtype, d_out, "ftc_update_gemm", "Z"));
     if (!W) return fail(FTC_EINVAL, "ftc_update_gemm: W is NULL");
-    if (d_in > 256 || d_out > 64) return fail(FTC_EUNSUPPORTED, "ftc_update_gemm: need d_in <= 256, d_out <= 64");
     if (Z == X) return fail(FTC_EINVAL, "ftc_update_gemm: Z aliases X");
     return launch_gemm(n, X, ldx, dtype, d_in, W, d_out, Z, ldz, z_dtype, Epi{relu, row_scale},
                        static_cast<hipStream_t>(stream));

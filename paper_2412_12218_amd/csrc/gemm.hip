@@ -1,45 +1,56 @@
-// Dense update phase Z = X * W for tall-skinny shapes (n rows, d_in <= 256, d_out <= 64):
-// X is streamed once, W sits in LDS as fp32.
+// Dense update phase Z = X * W for tall-skinny shapes: X is streamed once, W sits in LDS.  The shapes of
+// the benchmark models (d_in <= 256, d_out <= 64) keep all of W on chip for the whole kernel; wider
+// inputs (the feature matrices of citation graphs have thousands of columns) go through the same
+// kernels in chunks of the contraction dimension, wider outputs in groups of 64 columns.
 #include "ftc_common.hpp"
 
 namespace ftc {
 
+// One row of X per thread, DOUT accumulators.  W columns [col0, col0 + d_out) of a matrix with w_ld columns;
+// K_CHUNK rows of W are staged at a time (all of them when d_in <= K_CHUNK).
 template <class T, int DOUT>
 __global__ __launch_bounds__(256) void gemm_rows_kernel(int n, const void *__restrict__ X, int ldx, int d_in,
-                                                        const void *__restrict__ W, int wdt, int d_out,
-                                                        void *__restrict__ Z, int ldz, int zdt, Epi epi)
+                                                        const void *__restrict__ W, int wdt, int w_ld, int col0,
+                                                        int d_out, void *__restrict__ Z, int ldz, int zdt, Epi epi)
 {
     constexpr int V = T::VEC;
-    extern __shared__ float Ws[];  // d_in x DOUT, zero padded beyond d_out
-    for (int t = threadIdx.x; t < d_in * DOUT; t += 256) {
-        const int k = t / DOUT, o = t % DOUT;
-        Ws[t] = o < d_out ? load_elem(W, static_cast<int64_t>(k) * d_out + o, wdt) : 0.f;
-    }
-    __syncthreads();
+    constexpr int K_CHUNK = 8192 / DOUT;  // 32 KB of fp32; a multiple of V
+    extern __shared__ float Ws[];         // min(d_in, K_CHUNK) x DOUT, zero padded beyond d_out
     const int64_t row = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
-    if (row >= n) return;
     float acc[DOUT];
 #pragma unroll
     for (int o = 0; o < DOUT; ++o) acc[o] = 0.f;
-    for (int k0 = 0; k0 < d_in; k0 += V) {
-        float x[V];
-        load_vec<T>(X, row * ldx + k0, x);
+    for (int kc0 = 0; kc0 < d_in; kc0 += K_CHUNK) {  // uniform
+        const int kn = d_in - kc0 < K_CHUNK ? d_in - kc0 : K_CHUNK;
+        if (kc0 > 0) __syncthreads();  // the previous chunk has been consumed
+        for (int t = threadIdx.x; t < kn * DOUT; t += 256) {
+            const int k = t / DOUT, o = t % DOUT;
+            Ws[t] = o < d_out ? load_elem(W, static_cast<int64_t>(kc0 + k) * w_ld + col0 + o, wdt) : 0.f;
+        }
+        __syncthreads();
+        if (row < n) {
+            for (int k0 = 0; k0 < kn; k0 += V) {
+                float x[V];
+                load_vec<T>(X, row * ldx + kc0 + k0, x);
 #pragma unroll
-        for (int kk = 0; kk < V; ++kk) {
-            const float4 *w4 = reinterpret_cast<const float4 *>(Ws + (k0 + kk) * DOUT);
+                for (int kk = 0; kk < V; ++kk) {
+                    const float4 *w4 = reinterpret_cast<const float4 *>(Ws + (k0 + kk) * DOUT);
 #pragma unroll
-            for (int o = 0; o < DOUT / 4; ++o) {
-                const float4 w = w4[o];
-                acc[4 * o] = fmaf(x[kk], w.x, acc[4 * o]);
-                acc[4 * o + 1] = fmaf(x[kk], w.y, acc[4 * o + 1]);
-                acc[4 * o + 2] = fmaf(x[kk], w.z, acc[4 * o + 2]);
-                acc[4 * o + 3] = fmaf(x[kk], w.w, acc[4 * o + 3]);
+                    for (int o = 0; o < DOUT / 4; ++o) {
+                        const float4 w = w4[o];
+                        acc[4 * o] = fmaf(x[kk], w.x, acc[4 * o]);
+                        acc[4 * o + 1] = fmaf(x[kk], w.y, acc[4 * o + 1]);
+                        acc[4 * o + 2] = fmaf(x[kk], w.z, acc[4 * o + 2]);
+                        acc[4 * o + 3] = fmaf(x[kk], w.w, acc[4 * o + 3]);
+                    }
+                }
             }
         }
     }
+    if (row >= n) return;
 #pragma unroll
     for (int o = 0; o < DOUT; ++o)
-        if (o < d_out) store_elem(Z, row * ldz + o, zdt, epi.apply(epi.factor(row), acc[o]));
+        if (o < d_out) store_elem(Z, row * ldz + col0 + o, zdt, epi.apply(epi.factor(row), acc[o]));
 }
 
 __global__ __launch_bounds__(256) void gemm_generic_kernel(int n, const void *X, int ldx, int dt, int d_in,
@@ -182,6 +193,97 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(int n, const uint16_t *_
     }
 }
 
+// The same contraction for any d_in (rows of X 16-byte aligned; the last piece of a width that is no
+// multiple of 8 is read element by element) and a group of up to 64 output columns [col0, col0 + d_out)
+// of a W with w_ld columns: W^T is staged in chunks of 256 rows of W, a workgroup keeps the
+// accumulators of 4 x RT tiles of 16 rows across the chunks, and B operands come from LDS.
+constexpr int WIDE_KC = 256;
+
+template <class T, int WIDE_RT>
+__global__ __launch_bounds__(256) void gemm_mfma_wide_kernel(int n, const uint16_t *__restrict__ X, int ldx, int d_in,
+                                                             const uint16_t *__restrict__ W, int w_ld, int col0,
+                                                             int d_out, void *__restrict__ Z, int ldz, int zdt,
+                                                             Epi epi, int n_batches)
+{
+    constexpr int NT = 4, KP = WIDE_KC + 8;
+    __shared__ __attribute__((aligned(16))) uint16_t Wt[NT * 16 * KP];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int m = lane & 15, kb = lane >> 4;
+    const int nt_n = (d_out + 15) / 16;
+    for (int batch = blockIdx.x; batch < n_batches; batch += gridDim.x) {  // uniform over the workgroup
+        const int tile0 = (batch * 4 + wave) * WIDE_RT;
+        float4v c[WIDE_RT][NT];
+#pragma unroll
+        for (int rt = 0; rt < WIDE_RT; ++rt)
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) c[rt][nt] = float4v{0.f, 0.f, 0.f, 0.f};
+        for (int kc0 = 0; kc0 < d_in; kc0 += WIDE_KC) {
+            __syncthreads();  // the previous chunk (or batch) has been consumed
+            const int nn_n = nt_n * 16;  // only the column tiles that are used
+            for (int t = threadIdx.x; t < nn_n * WIDE_KC; t += 256) {
+                const int k = t / nn_n, nn = t % nn_n;  // consecutive threads read consecutive columns of W
+                Wt[nn * KP + k] = (nn < d_out && kc0 + k < d_in) ? W[static_cast<size_t>(kc0 + k) * w_ld + col0 + nn]
+                                                                 : uint16_t(0);
+            }
+            __syncthreads();
+#pragma unroll
+            for (int ks = 0; ks < WIDE_KC / 32; ++ks) {
+                const int k = kc0 + ks * 32 + kb * 8;
+                uint4 a[WIDE_RT];
+#pragma unroll
+                for (int rt = 0; rt < WIDE_RT; ++rt) {
+                    const int64_t row = min(static_cast<int64_t>(tile0 + rt) * 16 + m, static_cast<int64_t>(n) - 1);
+                    if (k + 8 <= d_in) {
+                        a[rt] = *reinterpret_cast<const uint4 *>(X + row * ldx + k);
+                    } else {  // the last piece of a width that is no multiple of 8: element by element, nothing beyond d_in is read
+                        unsigned h[8];
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) h[j] = k + j < d_in ? X[row * ldx + k + j] : 0u;
+                        a[rt] = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+                    }
+                }
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) {
+                    if (nt < nt_n) {
+                        const uint4 b = *reinterpret_cast<const uint4 *>(&Wt[(nt * 16 + m) * KP + ks * 32 + kb * 8]);
+#pragma unroll
+                        for (int rt = 0; rt < WIDE_RT; ++rt) c[rt][nt] = mfma16<T>(a[rt], b, c[rt][nt]);
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int rt = 0; rt < WIDE_RT; ++rt)
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                const int col = nt * 16 + m;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int64_t row = static_cast<int64_t>(tile0 + rt) * 16 + kb * 4 + i;
+                    if (row < n && col < d_out)
+                        store_elem(Z, row * ldz + col0 + col, zdt, epi.apply(epi.factor(static_cast<int>(row)), c[rt][nt][i]));
+                }
+            }
+    }
+}
+
+template <class T>
+static void gemm_mfma_wide_t(int n, const void *X, int ldx, int d_in, const void *W, int d_out, void *Z, int ldz,
+                             int zdt, Epi epi, hipStream_t s)
+{
+    const int64_t n_tiles = (static_cast<int64_t>(n) + 15) / 16;
+    // four tiles per wave: W is re-staged once per 256 rows (one tile per wave was measured 2.4 times slower
+    // at 100 k rows, although it starts four times as many workgroups)
+    const int64_t n_batches = (n_tiles + 15) / 16;
+    const unsigned grid = static_cast<unsigned>(n_batches < 256 * 4 ? n_batches : 256 * 4);
+    for (int col0 = 0; col0 < d_out; col0 += 64) {
+        const int cols = d_out - col0 < 64 ? d_out - col0 : 64;
+        hipLaunchKernelGGL((gemm_mfma_wide_kernel<T, 4>), dim3(grid), dim3(256), 0, s, n,
+                           static_cast<const uint16_t *>(X), ldx, d_in, static_cast<const uint16_t *>(W), d_out, col0,
+                           cols, Z, ldz, zdt, epi, static_cast<int>(n_batches));
+    }
+}
+
 template <class T>
 static bool gemm_mfma_t(int n, const void *X, int ldx, int d_in, const void *W, int d_out, void *Z, int ldz,
                         int zdt, Epi epi, hipStream_t s)
@@ -204,44 +306,55 @@ static bool gemm_mfma_t(int n, const void *X, int ldx, int d_in, const void *W, 
 }
 
 template <class T>
-static void gemm_t(int dpad, int n, const void *X, int ldx, int d_in, const void *W, int wdt, int d_out,
-                   void *Z, int ldz, int zdt, Epi epi, hipStream_t s)
+static void gemm_t(int n, const void *X, int ldx, int d_in, const void *W, int wdt, int d_out, void *Z, int ldz, int zdt,
+                   Epi epi, hipStream_t s)
 {
     const unsigned grid = static_cast<unsigned>((static_cast<int64_t>(n) + 255) / 256);
-    const size_t lds = static_cast<size_t>(d_in) * dpad * sizeof(float);
-#define FTC_CASE(P)                                                                                     \
-    case P:                                                                                             \
-        hipLaunchKernelGGL((gemm_rows_kernel<T, P>), dim3(grid), dim3(256), lds, s, n, X, ldx, d_in, W, \
-                           wdt, d_out, Z, ldz, zdt, epi);                                              \
+    for (int col0 = 0; col0 < d_out; col0 += 64) {
+        const int cols = d_out - col0 < 64 ? d_out - col0 : 64;
+        int dpad = 8;
+        while (dpad < cols) dpad *= 2;
+        const int k_chunk = 8192 / dpad;
+        const size_t lds = static_cast<size_t>(d_in < k_chunk ? d_in : k_chunk) * dpad * sizeof(float);
+#define FTC_CASE(P)                                                                                          \
+    case P:                                                                                                  \
+        hipLaunchKernelGGL((gemm_rows_kernel<T, P>), dim3(grid), dim3(256), lds, s, n, X, ldx, d_in, W, wdt, \
+                           d_out, col0, cols, Z, ldz, zdt, epi);                                             \
         break;
-    switch (dpad) {
-        FTC_CASE(8)
-        FTC_CASE(16)
-        FTC_CASE(32)
-        FTC_CASE(64)
-    }
+        switch (dpad) {
+            FTC_CASE(8)
+            FTC_CASE(16)
+            FTC_CASE(32)
+            FTC_CASE(64)
+        }
 #undef FTC_CASE
+    }
 }
 
-int32_t launch_gemm(int n, const void *X, int ldx, int dt, int d_in, const void *W, int d_out, void *Z,
-                    int ldz, int zdt, Epi epi, hipStream_t s)
+int32_t launch_gemm(int n, const void *X, int ldx, int dt, int d_in, const void *W, int d_out, void *Z, int ldz,
+                    int zdt, Epi epi, hipStream_t s)
 {
     if (n == 0) return FTC_OK;
     const int v = dt == FTC_F32 ? 4 : 8;
-    int dpad = 8;
-    while (dpad < d_out) dpad *= 2;
-    const bool fast = aligned16(X) && (static_cast<int64_t>(ldx) * elem_size(dt)) % 16 == 0 && d_in % v == 0 &&
-                      dpad <= 64 && static_cast<int64_t>(d_in) * dpad <= 8192;
+    // vector loads of X: 16-byte aligned rows, whole vectors
+    const bool fast = aligned16(X) && (static_cast<int64_t>(ldx) * elem_size(dt)) % 16 == 0 && d_in % v == 0;
     // 16-bit inputs: matrix cores (needs 16-byte row pieces of X)
-    if (dt != FTC_F32 && aligned16(X) && (static_cast<int64_t>(ldx) * 2) % 16 == 0 && d_in % 8 == 0) {
-        const bool done = dt == FTC_F16 ? gemm_mfma_t<F16>(n, X, ldx, d_in, W, d_out, Z, ldz, zdt, epi, s)
-                                        : gemm_mfma_t<BF16>(n, X, ldx, d_in, W, d_out, Z, ldz, zdt, epi, s);
+    const bool rows16 = aligned16(X) && (static_cast<int64_t>(ldx) * elem_size(dt)) % 16 == 0;
+    if (dt != FTC_F32 && rows16) {
+        const bool done = fast && (dt == FTC_F16 ? gemm_mfma_t<F16>(n, X, ldx, d_in, W, d_out, Z, ldz, zdt, epi, s)
+                                                 : gemm_mfma_t<BF16>(n, X, ldx, d_in, W, d_out, Z, ldz, zdt, epi, s));
         if (done) return launch_status("update_gemm mfma");
+        // beyond the register-resident shapes, or a width that is no multiple of 8 in padded rows
+        if (d_in > 256 || d_out > 64 || !fast) {
+            if (dt == FTC_F16) gemm_mfma_wide_t<F16>(n, X, ldx, d_in, W, d_out, Z, ldz, zdt, epi, s);
+            else gemm_mfma_wide_t<BF16>(n, X, ldx, d_in, W, d_out, Z, ldz, zdt, epi, s);
+            return launch_status("update_gemm mfma (wide)");
+        }
     }
     if (fast) {
-        if (dt == FTC_F32) gemm_t<F32>(dpad, n, X, ldx, d_in, W, dt, d_out, Z, ldz, zdt, epi, s);
-        else if (dt == FTC_F16) gemm_t<F16>(dpad, n, X, ldx, d_in, W, dt, d_out, Z, ldz, zdt, epi, s);
-        else gemm_t<BF16>(dpad, n, X, ldx, d_in, W, dt, d_out, Z, ldz, zdt, epi, s);
+        if (dt == FTC_F32) gemm_t<F32>(n, X, ldx, d_in, W, dt, d_out, Z, ldz, zdt, epi, s);
+        else if (dt == FTC_F16) gemm_t<F16>(n, X, ldx, d_in, W, dt, d_out, Z, ldz, zdt, epi, s);
+        else gemm_t<BF16>(n, X, ldx, d_in, W, dt, d_out, Z, ldz, zdt, epi, s);
     } else {
         const int64_t total = static_cast<int64_t>(n) * d_out;
         hipLaunchKernelGGL(gemm_generic_kernel, dim3(static_cast<unsigned>((total + 255) / 256)), dim3(256), 0,

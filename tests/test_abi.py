@@ -82,9 +82,13 @@ def test_argument_validation_without_launch():
     assert L.ftc_gcn_layer(C.byref(g), None, None, None, fake, I(8), I(1), I(8), fake, I(8), I(0), fake, I(8), I(0),
                            I(0), None, z, None) == B.FTC_EWORKSPACE
     assert b"workspace" in L.ftc_last_error()
-    # gemm shape limits
-    assert L.ftc_update_gemm(I(4), fake, I(512), I(1), I(512), fake, I(8), C.c_void_p(0x3000), I(8), I(0), None,
-                             I(0), None) == B.FTC_EUNSUPPORTED
+    # gemm arguments: a leading dimension shorter than the row, an output that is the input, no weights
+    assert L.ftc_update_gemm(I(4), fake, I(256), I(1), I(512), fake, I(8), C.c_void_p(0x3000), I(8), I(0), None,
+                             I(0), None) == B.FTC_EINVAL
+    assert L.ftc_update_gemm(I(4), fake, I(512), I(1), I(512), fake, I(8), fake, I(8), I(0), None,
+                             I(0), None) == B.FTC_EINVAL
+    assert L.ftc_update_gemm(I(4), fake, I(512), I(1), I(512), None, I(8), C.c_void_p(0x3000), I(8), I(0), None,
+                             I(0), None) == B.FTC_EINVAL
 
 
 def test_backward_and_reordering_validate_on_the_host():

@@ -464,6 +464,56 @@ def test_update_gemm(oracle, dtype, d_in, d_out, relu):
     assert norm_err(Zh, ref, ab, F16) < TOL[dtype]
 
 
+@pytest.mark.parametrize("dtype,d_in,d_out", [(F16, 1432, 16), (F16, 3704, 7), (BF16, 264, 64), (F16, 128, 100),
+                                              (BF16, 520, 130), (F32, 1000, 16), (F32, 300, 70), (F32, 4100, 5),
+                                              (F16, 1433, 16), (F32, 3703, 6), (BF16, 257, 65)])
+def test_update_gemm_wide_shapes(oracle, dtype, d_in, d_out):
+    """Beyond the shapes that keep W on chip: the contraction dimension in chunks, more than 64 output
+    columns in groups (feature matrices of citation graphs have 1433 and 3703 columns); odd widths take
+    the element-wise kernel.  A ragged last row tile, ReLU, row scales and a 16-bit output ride along."""
+    say(f"gemm wide {dtype} {d_in}x{d_out}")
+    n = 1000 + 21
+    Xd, X64 = quantise(synth.uniform_features(n, d_in, seed=7), dtype)
+    Wd, W64 = quantise(synth.glorot_uniform(d_in, d_out, seed=8), dtype)
+    ref, ab = oracle.gemm(X64, W64)
+    Z = B.ftc_update_gemm(Xd, Wd)
+    assert norm_err(Z, ref, ab) < TOL[dtype]
+    sc32 = np.random.default_rng(5).uniform(-2, 2, size=n).astype(np.float32)
+    ref2 = np.maximum(ref * sc32.astype(np.float64)[:, None], 0)
+    Zh = B.ftc_update_gemm(Xd, Wd, relu=True, row_scale=torch.from_numpy(sc32).cuda(), out_dtype=F16)
+    assert norm_err(Zh, ref2, ab * np.abs(sc32.astype(np.float64))[:, None], F16) < TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype,d_in,d_out,pad", [(F16, 1433, 16, 7), (BF16, 100, 24, 4), (F16, 3703, 6, 1),
+                                                  (F16, 9, 3, 7), (BF16, 250, 70, 6)])
+def test_update_gemm_odd_width_in_padded_rows(oracle, dtype, d_in, d_out, pad):
+    """A width that is no multiple of 8 stored in 16-byte aligned rows: the matrix cores still take it, and
+    the padding of the rows (NaN here) never reaches the result."""
+    n = 777
+    X32 = synth.uniform_features(n, d_in + pad, seed=3)
+    X32[:, d_in:] = np.nan
+    Xd, X64 = quantise(X32, dtype)
+    Xd, X64 = Xd[:, :d_in], X64[:, :d_in]
+    Wd, W64 = quantise(synth.glorot_uniform(d_in, d_out, seed=4), dtype)
+    ref, ab = oracle.gemm(X64, W64)
+    Z = B.ftc_update_gemm(Xd, Wd)
+    assert norm_err(Z, ref, ab) < TOL[dtype]
+
+
+def test_gcn_layer_with_a_wide_input(oracle, graphs):
+    """First layer of a GCN on a feature matrix wider than the on-chip shapes (d_in = 1432 -> 16)."""
+    g = graphs["cfg1"]
+    vals64, _ = oracle.gcn_norm(g.row_ptr, g.col_idx)
+    vals32 = vals64.astype(np.float32)
+    Xd, X64 = quantise(synth.uniform_features(g.n, 1432, seed=9), F16)
+    Wd, W64 = quantise(synth.glorot_uniform(1432, 16, seed=10), F16)
+    ref, ab = oracle.gcn_layer(g.row_ptr, g.col_idx, vals32.astype(np.float64), X64, W64, relu=True)
+    dg = dev_graph(g)
+    win = B.ftc_build_windows(dg)
+    out = B.ftc_gcn_layer(dg, win, torch.from_numpy(vals32).cuda(), Xd, Wd, relu=True)
+    assert norm_err(out, ref, ab) < 2 * TOL[F16]
+
+
 @pytest.mark.parametrize("name,dtype,d_in,d_out", [("cfg1", F32, 16, 16), ("cfg2s", F16, 128, 32),
                                                    ("cfg5s", F16, 128, 16), ("cfg5s", F16, 16, 8),
                                                    ("hub", BF16, 64, 24)])
