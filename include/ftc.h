@@ -253,8 +253,9 @@ int32_t ftc_edge_softmax_backward(const ftc_csr *g, const ftc_windows *w, const 
 
 /*
  * Weight gradient of the update phase: dW = X^T * G, X n x d_in (x_dtype), G n x d_out (fp32),
- * dW d_in x d_out row-major (fp32).  Limits: ceil(d_in / 4) * ceil(d_out / 4) <= 1024 and
- * d_in + d_out <= 506 (FTC_EUNSUPPORTED beyond).  Partial sums of row blocks are added in a fixed
+ * dW d_in x d_out row-major (fp32).  One pass covers ceil(d_in / 4) * ceil(d_out / 4) <= 1024 and
+ * d_in + d_out <= 506; a wider X is taken in groups of up to 256 input columns (every pass reads G
+ * again), d_out <= 504 (FTC_EUNSUPPORTED beyond).  Partial sums of row blocks are added in a fixed
  * order (reproducible).
  */
 size_t ftc_weight_grad_workspace_bytes(int32_t n, int32_t d_in, int32_t d_out);
@@ -266,7 +267,7 @@ int32_t ftc_weight_grad(int32_t n, const void *X, int32_t ldx, int32_t x_dtype, 
  * Backward of ftc_update_gemm (Z = act(X * W), no row scale) for a loss with dL/dZ = dZ (n x d_out,
  * fp32): dP = dZ where the layer's output Z was positive (Z == NULL: no ReLU, dP = dZ),
  * dW = X^T * dP (d_in x d_out, fp32), dX = dP * W^T (n x d_in, of type dx_dtype; dX == NULL:
- * skipped).  Limits of ftc_weight_grad and d_out <= 64.
+ * skipped).  Any d_in; d_out <= 64.
  */
 size_t ftc_update_gemm_backward_workspace_bytes(int32_t n, int32_t d_in, int32_t d_out);
 int32_t ftc_update_gemm_backward(int32_t n, const void *X, int32_t ldx, int32_t dtype, int32_t d_in,

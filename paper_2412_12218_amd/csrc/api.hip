@@ -461,8 +461,8 @@ int32_t ftc_weight_grad(int32_t n, const void *X, int32_t ldx, int32_t x_dtype, 
     FTC_TRY(check_dense(X, ldx, x_dtype, d_in, "ftc_weight_grad", "X"));
     FTC_TRY(check_dense(G, ldg, FTC_F32, d_out, "ftc_weight_grad", "G"));
     if (!dW) return fail(FTC_EINVAL, "ftc_weight_grad: dW is NULL");
-    if (!weight_grad_shape_ok(d_in, d_out))
-        return fail(FTC_EUNSUPPORTED, "ftc_weight_grad: need ceil(d_in / 4) * ceil(d_out / 4) <= 1024 and d_in + d_out <= 506");
+    if (d_in < 1 || d_out < 1 || weight_grad_group(d_in, d_out) == 0)
+        return fail(FTC_EUNSUPPORTED, "ftc_weight_grad: d_out too wide (8 input columns next to it must fit: d_out <= 504)");
     const size_t need = weight_grad_ws(n, d_in, d_out);
     if (!ws || ws_bytes < need) return fail(FTC_EWORKSPACE, "ftc_weight_grad: workspace of %zu bytes needed", need);
     return launch_weight_grad(n, X, ldx, x_dtype, d_in, G, ldg, d_out, dW, ws, static_cast<hipStream_t>(stream));
@@ -489,8 +489,7 @@ int32_t ftc_update_gemm_backward(int32_t n, const void *X, int32_t ldx, int32_t 
     if (dX) FTC_TRY(check_dense(dX, lddx, dx_dtype, d_in, "ftc_update_gemm_backward", "dX"));
     if (!W || !dW) return fail(FTC_EINVAL, "ftc_update_gemm_backward: W or dW is NULL");
     if (dX == X) return fail(FTC_EINVAL, "ftc_update_gemm_backward: dX aliases X");
-    if (d_out > 64 || !weight_grad_shape_ok(d_in, d_out))
-        return fail(FTC_EUNSUPPORTED, "ftc_update_gemm_backward: need d_out <= 64, ceil(d_in / 4) * ceil(d_out / 4) <= 1024 and d_in + d_out <= 506");
+    if (d_out > 64) return fail(FTC_EUNSUPPORTED, "ftc_update_gemm_backward: need d_out <= 64");
     const size_t need = ftc_update_gemm_backward_workspace_bytes(n, d_in, d_out);
     if (!ws || ws_bytes < need)
         return fail(FTC_EWORKSPACE, "ftc_update_gemm_backward: workspace of %zu bytes needed", need);
@@ -531,8 +530,7 @@ int32_t ftc_gcn_layer_backward(const ftc_csr *gT, const ftc_windows *wT, const f
     if (Y) FTC_TRY(check_dense(Y, ldy, y_dtype, d_out, "ftc_gcn_layer_backward", "Y"));
     if (dX) FTC_TRY(check_dense(dX, lddx, FTC_F32, d_in, "ftc_gcn_layer_backward", "dX"));
     if (!W || !dW) return fail(FTC_EINVAL, "ftc_gcn_layer_backward: W or dW is NULL");
-    if (d_out > 64 || !weight_grad_shape_ok(d_in, d_out))
-        return fail(FTC_EUNSUPPORTED, "ftc_gcn_layer_backward: need d_out <= 64, ceil(d_in / 4) * ceil(d_out / 4) <= 1024 and d_in + d_out <= 506");
+    if (d_out > 64) return fail(FTC_EUNSUPPORTED, "ftc_gcn_layer_backward: need d_out <= 64");
     const size_t need = ftc_gcn_layer_backward_workspace_bytes(gT->n, gT->nnz, d_in, d_out);
     if (!ws || ws_bytes < need)
         return fail(FTC_EWORKSPACE, "ftc_gcn_layer_backward: workspace of %zu bytes needed", need);

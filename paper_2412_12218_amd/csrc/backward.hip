@@ -298,30 +298,50 @@ bool weight_grad_shape_ok(int d_in, int d_out)
            (d_in + 3) / 4 * 4 + (d_out + 3) / 4 * 4 <= 512;
 }
 
-size_t weight_grad_ws(int n, int d_in, int d_out)
+// Input columns that one pass covers next to d_out output columns: all of them when the register tiles
+// and the staged rows allow it, else the largest multiple of 8 that does (at most 256); 0 if none.
+int weight_grad_group(int d_in, int d_out)
 {
-    return align_up(static_cast<size_t>(weight_grad_blocks(n)) * d_in * d_out * sizeof(float), 256);
+    if (weight_grad_shape_ok(d_in, d_out)) return d_in;
+    for (int gk = 256; gk >= 8; gk -= 8)
+        if (gk < d_in && weight_grad_shape_ok(gk, d_out)) return gk;
+    return 0;
 }
 
+size_t weight_grad_ws(int n, int d_in, int d_out)
+{
+    const int gk = weight_grad_group(d_in, d_out);
+    return align_up(static_cast<size_t>(weight_grad_blocks(n)) * (gk > 0 ? gk : d_in) * d_out * sizeof(float), 256);
+}
+
+// dW = X^T G.  A wider X is taken in groups of input columns: rows [k0, k0 + gk) of dW are one contiguous
+// block, each pass reads its columns of X and all of G, and the passes share the workspace (they run
+// one after the other on the stream).
 int32_t launch_weight_grad(int n, const void *X, int ldx, int xdt, int d_in, const float *G, int ldg, int d_out,
                            float *dW, void *ws, hipStream_t s)
 {
     const int blocks = weight_grad_blocks(n);
-    const int dip = (d_in + 3) / 4 * 4, dop = (d_out + 3) / 4 * 4;
-    const int n_tiles = (dip / 4) * (dop / 4);
-    size_t lds = static_cast<size_t>(WG_ROWS) * (dip + dop) * sizeof(float);
-    if (n_tiles < 256) {  // room for the slices' tiles
-        const size_t red = static_cast<size_t>(256 / n_tiles) * n_tiles * 16 * sizeof(float);
-        if (red > lds) lds = red;
-    }
+    const int group = weight_grad_group(d_in, d_out);
+    const int dop = (d_out + 3) / 4 * 4;
     const int xv = xdt == FTC_F32 ? 4 : 8;
-    const int x_vec = d_in % xv == 0 && (static_cast<int64_t>(ldx) * elem_size(xdt)) % 16 == 0 && aligned16(X);
     const int g_vec = d_out % 4 == 0 && ldg % 4 == 0 && aligned16(G);
     float *partial = static_cast<float *>(ws);
-    hipLaunchKernelGGL(weight_grad_kernel, dim3(blocks), dim3(256), lds, s, n, X, ldx, xdt, d_in, G, ldg, d_out, partial,
-                       x_vec, g_vec);
-    hipLaunchKernelGGL(sum_partials_kernel, dim3((d_in * d_out + 255) / 256), dim3(256), 0, s, d_in * d_out, blocks,
-                       partial, dW);
+    for (int k0 = 0; k0 < d_in; k0 += group) {
+        const int dk = d_in - k0 < group ? d_in - k0 : group;
+        const int dip = (dk + 3) / 4 * 4;
+        const int n_tiles = (dip / 4) * (dop / 4);
+        size_t lds = static_cast<size_t>(WG_ROWS) * (dip + dop) * sizeof(float);
+        if (n_tiles < 256) {  // room for the slices' tiles
+            const size_t red = static_cast<size_t>(256 / n_tiles) * n_tiles * 16 * sizeof(float);
+            if (red > lds) lds = red;
+        }
+        const void *Xk = static_cast<const char *>(X) + static_cast<size_t>(k0) * elem_size(xdt);
+        const int x_vec = dk % xv == 0 && (static_cast<int64_t>(ldx) * elem_size(xdt)) % 16 == 0 && aligned16(Xk);
+        hipLaunchKernelGGL(weight_grad_kernel, dim3(blocks), dim3(256), lds, s, n, Xk, ldx, xdt, dk, G, ldg, d_out,
+                           partial, x_vec, g_vec);
+        hipLaunchKernelGGL(sum_partials_kernel, dim3((dk * d_out + 255) / 256), dim3(256), 0, s, dk * d_out, blocks,
+                           partial, dW + static_cast<size_t>(k0) * d_out);
+    }
     return launch_status("weight_grad");
 }
 

@@ -86,6 +86,7 @@ int32_t launch_softmax_backward_seg(const ftc_csr &g, const ftc_windows &w, cons
 int32_t launch_mask_scale(int n, int d, const float *dY, int lddy, const void *Y, int ldy, int ydt,
                           const float *scale, float *out, int ldo, hipStream_t s);
 bool weight_grad_shape_ok(int d_in, int d_out);
+int weight_grad_group(int d_in, int d_out);
 size_t weight_grad_ws(int n, int d_in, int d_out);
 int32_t launch_weight_grad(int n, const void *X, int ldx, int xdt, int d_in, const float *G, int ldg, int d_out,
                            float *dW, void *ws, hipStream_t s);

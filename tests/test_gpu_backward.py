@@ -169,6 +169,36 @@ def test_weight_grad(n, dtype, d_in, d_out):
     assert torch.equal(dW, B.ftc_weight_grad(Xd, G))          # fixed summation order
 
 
+@pytest.mark.parametrize("dtype,d_in,d_out", [(F16, 1432, 16), (F16, 1433, 16), (F32, 3703, 6), (BF16, 520, 64),
+                                              (F32, 300, 128), (F16, 40, 300), (F32, 257, 1)])
+def test_weight_grad_wide(dtype, d_in, d_out):
+    """More input columns than one pass covers: groups of input columns (the last one ragged), and output
+    widths that shrink the group."""
+    n = 2000 + 3
+    say(f"weight_grad wide {dtype} {d_in}x{d_out}")
+    Xd, X64 = quantise(synth.uniform_features(n, d_in, seed=1), dtype)
+    G32 = synth.normal_features(n, d_out, seed=2).astype(np.float32)
+    ref = X64.T @ G32.astype(np.float64)
+    ab = np.abs(X64).T @ np.abs(G32).astype(np.float64)
+    G = torch.from_numpy(G32).cuda()
+    dW = B.ftc_weight_grad(Xd, G)
+    assert float(np.max(np.abs(dW.cpu().double().numpy() - ref) / ab)) < 1e-5
+    assert torch.equal(dW, B.ftc_weight_grad(Xd, G))
+
+
+@pytest.mark.parametrize("dtype,d_in,d_out", [(F16, 1432, 16), (F32, 1433, 7)])
+def test_update_gemm_backward_wide_input(dtype, d_in, d_out):
+    """The first layer of a model on a wide feature matrix: forward, then dW and dX."""
+    n = 1500 + 1
+    Xd, X64 = quantise(synth.uniform_features(n, d_in, seed=1), dtype)
+    Wd, W64 = quantise(synth.glorot_uniform(d_in, d_out, seed=2), dtype)
+    dZ32 = synth.normal_features(n, d_out, seed=3).astype(np.float32)
+    Z = B.ftc_update_gemm(Xd, Wd, relu=True, out_dtype=dtype)
+    dX_ref, dW_ref = OB.update_gemm_backward(X64, W64, dZ32.astype(np.float64), Z.cpu().double().numpy())
+    dX, dW = B.ftc_update_gemm_backward(Xd, Wd, torch.from_numpy(dZ32).cuda(), Z=Z)
+    assert row_err(dX, dX_ref) < 1e-5 and arr_err(dW, dW_ref) < 1e-5
+
+
 def test_weight_grad_strided_inputs():
     n, d_in, d_out = 777, 20, 12
     Xf = torch.from_numpy(synth.uniform_features(n, 40, seed=3)).to(F16).cuda()
@@ -546,9 +576,9 @@ def test_backward_rejects_bad_arguments():
     W = torch.zeros((16, 80), dtype=F16, device="cuda")
     with pytest.raises(B.FtcError):        # d_out above 64
         B.ftc_gcn_layer_backward(dg, None, None, H, W, torch.zeros((g.n, 80), dtype=F32, device="cuda"))
-    with pytest.raises(B.FtcError):        # weight gradient larger than the register tiling covers
-        B.ftc_weight_grad(torch.zeros((10, 512), dtype=F16, device="cuda"),
-                          torch.zeros((10, 64), dtype=F32, device="cuda"))
+    with pytest.raises(B.FtcError):        # more output columns than a pass of the weight gradient covers
+        B.ftc_weight_grad(torch.zeros((10, 16), dtype=F16, device="cuda"),
+                          torch.zeros((10, 508), dtype=F32, device="cuda"))
     del dY32
 
 
