@@ -267,7 +267,8 @@ int32_t ftc_weight_grad(int32_t n, const void *X, int32_t ldx, int32_t x_dtype, 
  * Backward of ftc_update_gemm (Z = act(X * W), no row scale) for a loss with dL/dZ = dZ (n x d_out,
  * fp32): dP = dZ where the layer's output Z was positive (Z == NULL: no ReLU, dP = dZ),
  * dW = X^T * dP (d_in x d_out, fp32), dX = dP * W^T (n x d_in, of type dx_dtype; dX == NULL:
- * skipped).  Any d_in; d_out <= 64.
+ * skipped).  Any d_in; d_out <= 504 (beyond 64 output columns dX is computed by the kernels of
+ * ftc_update_gemm on the transposed weights).
  */
 size_t ftc_update_gemm_backward_workspace_bytes(int32_t n, int32_t d_in, int32_t d_out);
 int32_t ftc_update_gemm_backward(int32_t n, const void *X, int32_t ldx, int32_t dtype, int32_t d_in,
@@ -283,7 +284,7 @@ int32_t ftc_update_gemm_backward(int32_t n, const void *X, int32_t ldx, int32_t 
  * (gT, wT, valsT) describe A^^T: the transposed graph, its window index and its edge values; for
  * the symmetric GCN normalisation they are the forward graph itself.  dinv != NULL selects the
  * factored normalisation as in ftc_gcn_layer (valsT ignored).  X, W as in the forward call;
- * d_out <= 64.
+ * d_out <= 504.
  */
 size_t ftc_gcn_layer_backward_workspace_bytes(int32_t n, int32_t nnz, int32_t d_in, int32_t d_out);
 int32_t ftc_gcn_layer_backward(const ftc_csr *gT, const ftc_windows *wT, const float *valsT,

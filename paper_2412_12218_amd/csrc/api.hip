@@ -473,7 +473,8 @@ static int pad4(int d) { return (d + 3) / 4 * 4; }
 size_t ftc_update_gemm_backward_workspace_bytes(int32_t n, int32_t d_in, int32_t d_out)
 {
     if (n < 0 || d_in < 1 || d_out < 1) return 0;
-    return align_up(static_cast<size_t>(n) * pad4(d_out) * sizeof(float), 256) + weight_grad_ws(n, d_in, d_out);
+    return align_up(static_cast<size_t>(n) * pad4(d_out) * sizeof(float), 256) + weight_grad_ws(n, d_in, d_out) +
+           input_grad_ws(d_in, d_out);
 }
 
 int32_t ftc_update_gemm_backward(int32_t n, const void *X, int32_t ldx, int32_t dtype, int32_t d_in, const void *W,
@@ -489,7 +490,7 @@ int32_t ftc_update_gemm_backward(int32_t n, const void *X, int32_t ldx, int32_t 
     if (dX) FTC_TRY(check_dense(dX, lddx, dx_dtype, d_in, "ftc_update_gemm_backward", "dX"));
     if (!W || !dW) return fail(FTC_EINVAL, "ftc_update_gemm_backward: W or dW is NULL");
     if (dX == X) return fail(FTC_EINVAL, "ftc_update_gemm_backward: dX aliases X");
-    if (d_out > 64) return fail(FTC_EUNSUPPORTED, "ftc_update_gemm_backward: need d_out <= 64");
+    if (weight_grad_group(d_in, d_out) == 0) return fail(FTC_EUNSUPPORTED, "ftc_update_gemm_backward: need d_out <= 504");
     const size_t need = ftc_update_gemm_backward_workspace_bytes(n, d_in, d_out);
     if (!ws || ws_bytes < need)
         return fail(FTC_EWORKSPACE, "ftc_update_gemm_backward: workspace of %zu bytes needed", need);
@@ -507,7 +508,9 @@ int32_t ftc_update_gemm_backward(int32_t n, const void *X, int32_t ldx, int32_t 
     }
     void *ws_wg = p + align_up(static_cast<size_t>(n) * pad4(d_out) * sizeof(float), 256);
     FTC_TRY(launch_weight_grad(n, X, ldx, dtype, d_in, dP, ldp, d_out, dW, ws_wg, hs));
-    if (dX) FTC_TRY(launch_input_grad(n, dP, ldp, d_out, W, dtype, d_in, dX, lddx, dx_dtype, hs));
+    if (dX)
+        FTC_TRY(launch_input_grad_any(n, dP, ldp, d_out, W, dtype, d_in, dX, lddx, dx_dtype,
+                                      static_cast<char *>(ws_wg) + weight_grad_ws(n, d_in, d_out), hs));
     return FTC_OK;
 }
 
@@ -515,7 +518,8 @@ size_t ftc_gcn_layer_backward_workspace_bytes(int32_t n, int32_t nnz, int32_t d_
 {
     if (n < 0 || nnz < 0 || d_in < 1 || d_out < 1) return 0;
     const size_t mat = align_up(static_cast<size_t>(n) * pad4(d_out) * sizeof(float), 256);
-    return 2 * mat + align_up(ftc_spmm_workspace_bytes(n, nnz, d_out), 256) + weight_grad_ws(n, d_in, d_out);
+    return 2 * mat + align_up(ftc_spmm_workspace_bytes(n, nnz, d_out), 256) + weight_grad_ws(n, d_in, d_out) +
+           input_grad_ws(d_in, d_out);
 }
 
 int32_t ftc_gcn_layer_backward(const ftc_csr *gT, const ftc_windows *wT, const float *valsT, const float *dinv,
@@ -530,7 +534,7 @@ int32_t ftc_gcn_layer_backward(const ftc_csr *gT, const ftc_windows *wT, const f
     if (Y) FTC_TRY(check_dense(Y, ldy, y_dtype, d_out, "ftc_gcn_layer_backward", "Y"));
     if (dX) FTC_TRY(check_dense(dX, lddx, FTC_F32, d_in, "ftc_gcn_layer_backward", "dX"));
     if (!W || !dW) return fail(FTC_EINVAL, "ftc_gcn_layer_backward: W or dW is NULL");
-    if (d_out > 64) return fail(FTC_EUNSUPPORTED, "ftc_gcn_layer_backward: need d_out <= 64");
+    if (weight_grad_group(d_in, d_out) == 0) return fail(FTC_EUNSUPPORTED, "ftc_gcn_layer_backward: need d_out <= 504");
     const size_t need = ftc_gcn_layer_backward_workspace_bytes(gT->n, gT->nnz, d_in, d_out);
     if (!ws || ws_bytes < need)
         return fail(FTC_EWORKSPACE, "ftc_gcn_layer_backward: workspace of %zu bytes needed", need);
@@ -551,7 +555,9 @@ int32_t ftc_gcn_layer_backward(const ftc_csr *gT, const ftc_windows *wT, const f
     FTC_TRY(ftc_spmm(gT, wT, dinv ? nullptr : valsT, dP, ldp, FTC_F32, d_out, dZ, ldp, FTC_F32, dinv, 0, path,
                      ws_spmm, spmm_bytes, stream));
     FTC_TRY(launch_weight_grad(n, X, ldx, dtype, d_in, dZ, ldp, d_out, dW, ws_wg, hs));
-    if (dX) FTC_TRY(launch_input_grad(n, dZ, ldp, d_out, W, dtype, d_in, dX, lddx, FTC_F32, hs));
+    if (dX)
+        FTC_TRY(launch_input_grad_any(n, dZ, ldp, d_out, W, dtype, d_in, dX, lddx, FTC_F32,
+                                      static_cast<char *>(ws_wg) + weight_grad_ws(n, d_in, d_out), hs));
     return FTC_OK;
 }
 

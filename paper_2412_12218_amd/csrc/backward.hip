@@ -398,6 +398,37 @@ int32_t launch_input_grad(int n, const float *G, int ldg, int d_out, const void 
     return launch_status("input_grad");
 }
 
+// More than 64 output columns: dX = G W^T is the dense update of the fp32 matrix G with the weights W^T, so
+// W is transposed into the workspace as fp32 (d_out x d_in) and the forward kernels do the rest.
+__global__ __launch_bounds__(256) void transpose_weights_kernel(int d_in, int d_out, const void *__restrict__ W,
+                                                                int wdt, float *__restrict__ Wt)
+{
+    const int64_t t = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (t >= static_cast<int64_t>(d_in) * d_out) return;
+    const int b = static_cast<int>(t / d_in), a = static_cast<int>(t % d_in);  // consecutive threads write consecutive entries
+    Wt[t] = load_elem(W, static_cast<int64_t>(a) * d_out + b, wdt);
+}
+
+size_t input_grad_ws(int d_in, int d_out)
+{
+    return d_out > 64 ? align_up(static_cast<size_t>(d_in) * d_out * sizeof(float), 256) : 0;
+}
+
+// ws: input_grad_ws(d_in, d_out) bytes, used when d_out > 64
+int32_t launch_input_grad_any(int n, const float *G, int ldg, int d_out, const void *W, int wdt, int d_in, void *dX,
+                              int lddx, int dx_dt, void *ws, hipStream_t s)
+{
+    if (d_out <= 64) return launch_input_grad(n, G, ldg, d_out, W, wdt, d_in, dX, lddx, dx_dt, s);
+    if (n == 0) return FTC_OK;
+    float *Wt = static_cast<float *>(ws);
+    const int64_t total = static_cast<int64_t>(d_in) * d_out;
+    hipLaunchKernelGGL(transpose_weights_kernel, dim3(static_cast<unsigned>((total + 255) / 256)), dim3(256), 0, s, d_in,
+                       d_out, W, wdt, Wt);
+    const int32_t st = launch_status("input_grad transpose");
+    if (st != FTC_OK) return st;
+    return launch_gemm(n, G, ldg, FTC_F32, d_out, Wt, d_in, dX, lddx, dx_dt, Epi{0, nullptr}, s);
+}
+
 // ---- out[e] = alpha * (wa * a[e] + wb * a[T[e]]) * cs[col[e]] -------------------------------------
 __global__ __launch_bounds__(256) void edge_combine_kernel(int nnz, const float *__restrict__ a,
                                                            const int *__restrict__ T, float wa, float wb, float alpha,

@@ -87,6 +87,9 @@ int32_t launch_mask_scale(int n, int d, const float *dY, int lddy, const void *Y
                           const float *scale, float *out, int ldo, hipStream_t s);
 bool weight_grad_shape_ok(int d_in, int d_out);
 int weight_grad_group(int d_in, int d_out);
+size_t input_grad_ws(int d_in, int d_out);
+int32_t launch_input_grad_any(int n, const float *G, int ldg, int d_out, const void *W, int wdt, int d_in, void *dX,
+                              int lddx, int dx_dt, void *ws, hipStream_t s);
 size_t weight_grad_ws(int n, int d_in, int d_out);
 int32_t launch_weight_grad(int n, const void *X, int ldx, int xdt, int d_in, const float *G, int ldg, int d_out,
                            float *dW, void *ws, hipStream_t s);

@@ -107,8 +107,8 @@ def test_backward_and_reordering_validate_on_the_host():
     assert L.ftc_weight_grad(I(8), fake, I(16), I(1), I(16), fake, I(508), I(508), other, fake, big, None) \
         == B.FTC_EUNSUPPORTED                                                                          # too many output columns
     assert L.ftc_weight_grad(I(8), fake, I(16), I(1), I(16), fake, I(8), I(8), other, None, z, None) == B.FTC_EWORKSPACE
-    assert L.ftc_gcn_layer_backward(C.byref(g), None, None, None, fake, I(16), I(1), I(16), fake, I(80), None, I(0), I(0),
-                                    fake, I(80), other, I(16), other, I(0), fake, big, None) == B.FTC_EUNSUPPORTED
+    assert L.ftc_gcn_layer_backward(C.byref(g), None, None, None, fake, I(16), I(1), I(16), fake, I(508), None, I(0), I(0),
+                                    fake, I(508), other, I(16), other, I(0), fake, big, None) == B.FTC_EUNSUPPORTED
     # H and dY with different leading dimensions
     assert L.ftc_agnn_layer_backward(C.byref(g), None, fake, fake, I(16), I(1), I(16), F(1.0), fake, other, I(24), other,
                                      I(16), I(0), fake, I(0), fake, big, None) == B.FTC_EINVAL

@@ -186,9 +186,11 @@ def test_weight_grad_wide(dtype, d_in, d_out):
     assert torch.equal(dW, B.ftc_weight_grad(Xd, G))
 
 
-@pytest.mark.parametrize("dtype,d_in,d_out", [(F16, 1432, 16), (F32, 1433, 7)])
+@pytest.mark.parametrize("dtype,d_in,d_out", [(F16, 1432, 16), (F32, 1433, 7), (F16, 128, 128), (BF16, 96, 80),
+                                              (F32, 70, 130), (F16, 264, 256)])
 def test_update_gemm_backward_wide_input(dtype, d_in, d_out):
-    """The first layer of a model on a wide feature matrix: forward, then dW and dX."""
+    """The first layer of a model on a wide feature matrix, and hidden sizes above 64 (the input gradient
+    then runs as a dense update with the transposed weights): forward, then dW and dX."""
     n = 1500 + 1
     Xd, X64 = quantise(synth.uniform_features(n, d_in, seed=1), dtype)
     Wd, W64 = quantise(synth.glorot_uniform(d_in, d_out, seed=2), dtype)
@@ -196,6 +198,24 @@ def test_update_gemm_backward_wide_input(dtype, d_in, d_out):
     Z = B.ftc_update_gemm(Xd, Wd, relu=True, out_dtype=dtype)
     dX_ref, dW_ref = OB.update_gemm_backward(X64, W64, dZ32.astype(np.float64), Z.cpu().double().numpy())
     dX, dW = B.ftc_update_gemm_backward(Xd, Wd, torch.from_numpy(dZ32).cuda(), Z=Z)
+    assert row_err(dX, dX_ref) < 1e-5 and arr_err(dW, dW_ref) < 1e-5
+
+
+@pytest.mark.parametrize("dtype,d_in,d_out", [(F16, 64, 128), (F32, 40, 72)])
+def test_gcn_layer_backward_wide_hidden(oracle, graphs, dtype, d_in, d_out):
+    g = graphs["cfg1"]
+    vals64, _ = oracle.gcn_norm(g.row_ptr, g.col_idx)
+    vals32 = vals64.astype(np.float32)
+    Xd, X64 = quantise(synth.uniform_features(g.n, d_in, seed=4), dtype)
+    Wd, W64 = quantise(synth.glorot_uniform(d_in, d_out, seed=5), dtype)
+    dY32 = synth.normal_features(g.n, d_out, seed=6).astype(np.float32)
+    dg = dev_graph(g)
+    win = B.ftc_build_windows(dg)
+    vd = torch.from_numpy(vals32).cuda()
+    Y = B.ftc_gcn_layer(dg, win, vd, Xd, Wd, relu=True)
+    dX_ref, dW_ref, _ = OB.gcn_layer_backward(g.row_ptr, g.col_idx, vals32.astype(np.float64), X64, W64,
+                                              dY32.astype(np.float64), Y.cpu().double().numpy())
+    dX, dW = B.ftc_gcn_layer_backward(dg, win, vd, Xd, Wd, torch.from_numpy(dY32).cuda(), Y=Y)
     assert row_err(dX, dX_ref) < 1e-5 and arr_err(dW, dW_ref) < 1e-5
 
 
@@ -573,9 +593,9 @@ def test_backward_rejects_bad_arguments():
     p = torch.zeros(g.nnz, dtype=F32, device="cuda")
     with pytest.raises(B.FtcError):        # workspace too small
         B.ftc_agnn_layer_backward(dg, None, T, H, p, H.clone(), ws=torch.empty(256, dtype=torch.uint8, device="cuda"))
-    W = torch.zeros((16, 80), dtype=F16, device="cuda")
-    with pytest.raises(B.FtcError):        # d_out above 64
-        B.ftc_gcn_layer_backward(dg, None, None, H, W, torch.zeros((g.n, 80), dtype=F32, device="cuda"))
+    W = torch.zeros((16, 508), dtype=F16, device="cuda")
+    with pytest.raises(B.FtcError):        # more output columns than the weight gradient covers
+        B.ftc_gcn_layer_backward(dg, None, None, H, W, torch.zeros((g.n, 508), dtype=F32, device="cuda"))
     with pytest.raises(B.FtcError):        # more output columns than a pass of the weight gradient covers
         B.ftc_weight_grad(torch.zeros((10, 16), dtype=F16, device="cuda"),
                           torch.zeros((10, 508), dtype=F32, device="cuda"))
