@@ -494,27 +494,29 @@ def test_agnn_layer_backward_16bit_gradient_output(graphs):
 
 
 @pytest.mark.parametrize("fused", [True, False])
-def test_train_path_stacks_against_chained_oracle(oracle, fused):
+@pytest.mark.parametrize("sizes", [(24, 16, 12, 8), (300, 128, 40, 10)])
+def test_train_path_stacks_against_chained_oracle(oracle, fused, sizes):
     """TrainPath (2-layer GCN, 3 AGNN propagation layers, fp32 activations) against the per-layer
     oracles chained on the CPU; the AGNN layers through the single-pass pair and through the
-    edge-array route."""
+    edge-array route.  Once with the small widths, once with a 300-column input and a hidden size of 128."""
     from paper_2412_12218_amd.models import TrainPath
+    d_feat, hid, dh, n_out = sizes
     g = synth.config_graph(1)
     n = g.n
     dg = dev_graph(g)
     win = B.ftc_build_windows(dg)
     _, dinv = B.ftc_gcn_norm(dg, win)
-    tp = TrainPath(dg, win, dinv, d_feat=24, gcn_hidden=16, agnn_hidden=12, n_out=8, agnn_layers=3, act_dtype=F32,
+    tp = TrainPath(dg, win, dinv, d_feat=d_feat, gcn_hidden=hid, agnn_hidden=dh, n_out=n_out, agnn_layers=3, act_dtype=F32,
                    fused=fused)
     assert tp.fused == fused
     dinv64 = dinv.cpu().double().numpy()
     rows = np.repeat(np.arange(n), np.diff(g.row_ptr))
     vals = dinv64[rows] * dinv64[g.col_idx]
     # GCN
-    Xd, X64 = quantise(synth.uniform_features(n, 24, seed=31), F32)
-    W1d, W164 = quantise(synth.glorot_uniform(24, 16, seed=32), F32)
-    W2d, W264 = quantise(synth.glorot_uniform(16, 8, seed=33), F32)
-    dOutd, dOut64 = quantise(synth.normal_features(n, 8, seed=34), F32)
+    Xd, X64 = quantise(synth.uniform_features(n, d_feat, seed=31), F32)
+    W1d, W164 = quantise(synth.glorot_uniform(d_feat, hid, seed=32), F32)
+    W2d, W264 = quantise(synth.glorot_uniform(hid, n_out, seed=33), F32)
+    dOutd, dOut64 = quantise(synth.normal_features(n, n_out, seed=34), F32)
     tp.gcn_forward(Xd, W1d, W2d)
     dW1, dW2 = tp.gcn_backward(Xd, W1d, W2d, dOutd)
     H1 = tp.gcn_h.cpu().double().numpy()
@@ -525,8 +527,8 @@ def test_train_path_stacks_against_chained_oracle(oracle, fused):
     assert e1 < 1e-4 and e2 < 1e-4
     # AGNN
     betas = [1.0, -0.7, 2.0]
-    H0d, H064 = quantise(synth.normal_features(n, 12, seed=35), F32)
-    dYd, dY64 = quantise(synth.normal_features(n, 12, seed=36), F32)
+    H0d, H064 = quantise(synth.normal_features(n, dh, seed=35), F32)
+    dYd, dY64 = quantise(synth.normal_features(n, dh, seed=36), F32)
     tp.agnn_forward(H0d, betas)
     dH0, dbeta = tp.agnn_backward(betas, dYd)
     Hs = [H064]
