@@ -53,18 +53,57 @@ __global__ __launch_bounds__(256) void gemm_rows_kernel(int n, const void *__res
         if (o < d_out) store_elem(Z, row * ldz + col0 + o, zdt, epi.apply(epi.factor(row), acc[o]));
 }
 
-__global__ __launch_bounds__(256) void gemm_generic_kernel(int n, const void *X, int ldx, int dt, int d_in,
-                                                           const void *W, int d_out, void *Z, int ldz,
-                                                           int zdt, Epi epi)
+// Any element type, any alignment (rows of X that are not 16-byte aligned, widths that are no multiple of
+// the vector length): a workgroup takes 64 rows and up to 64 output columns [col0, col0 + d_out), and
+// walks the contraction dimension in chunks of 64.  The chunk of X is read element by element with
+// consecutive threads on consecutive columns and parked in LDS as fp32 next to the chunk of W; a thread
+// then owns one row and 16 output columns.
+constexpr int GU_ROWS = 64, GU_K = 64;
+
+__global__ __launch_bounds__(256) void gemm_unaligned_kernel(int n, const void *__restrict__ X, int ldx, int dt, int d_in,
+                                                             const void *__restrict__ W, int w_ld, int col0, int d_out,
+                                                             void *__restrict__ Z, int ldz, int zdt, Epi epi)
 {
-    const int64_t t = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
-    if (t >= static_cast<int64_t>(n) * d_out) return;
-    const int64_t row = t / d_out;
-    const int o = static_cast<int>(t - row * d_out);
-    float acc = 0.f;
-    for (int k = 0; k < d_in; ++k)
-        acc = fmaf(load_elem(X, row * ldx + k, dt), load_elem(W, static_cast<int64_t>(k) * d_out + o, dt), acc);
-    store_elem(Z, row * ldz + o, zdt, epi.apply(epi.factor(row), acc));
+    __shared__ float Xs[GU_ROWS][GU_K + 1];  // odd stride: the 64 rows read by a wave fall on different banks
+    __shared__ __attribute__((aligned(16))) float Ws[GU_K][64];
+    const int tid = threadIdx.x;
+    const int64_t r0 = static_cast<int64_t>(blockIdx.x) * GU_ROWS;
+    const int r = tid & 63, og = tid >> 6;  // row of the tile, group of 16 output columns
+    float acc[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) acc[j] = 0.f;
+    for (int k0 = 0; k0 < d_in; k0 += GU_K) {  // uniform
+        if (k0 > 0) __syncthreads();
+        for (int t = tid; t < GU_ROWS * GU_K; t += 256) {
+            const int rr = t / GU_K, kk = t % GU_K;
+            Xs[rr][kk] = (r0 + rr < n && k0 + kk < d_in) ? load_elem(X, (r0 + rr) * ldx + k0 + kk, dt) : 0.f;
+        }
+        for (int t = tid; t < GU_K * 64; t += 256) {
+            const int kk = t / 64, o = t % 64;
+            Ws[kk][o] = (k0 + kk < d_in && o < d_out) ? load_elem(W, static_cast<int64_t>(k0 + kk) * w_ld + col0 + o, dt) : 0.f;
+        }
+        __syncthreads();
+#pragma unroll 8
+        for (int kk = 0; kk < GU_K; ++kk) {
+            const float x = Xs[r][kk];
+#pragma unroll
+            for (int j = 0; j < 16; j += 4) {
+                const float4 w = *reinterpret_cast<const float4 *>(&Ws[kk][og * 16 + j]);
+                acc[j] = fmaf(x, w.x, acc[j]);
+                acc[j + 1] = fmaf(x, w.y, acc[j + 1]);
+                acc[j + 2] = fmaf(x, w.z, acc[j + 2]);
+                acc[j + 3] = fmaf(x, w.w, acc[j + 3]);
+            }
+        }
+    }
+    const int64_t row = r0 + r;
+    if (row >= n) return;
+    const float f = epi.factor(static_cast<int>(row));
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+        const int o = og * 16 + j;
+        if (o < d_out) store_elem(Z, row * ldz + col0 + o, zdt, epi.apply(f, acc[j]));
+    }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -356,9 +395,12 @@ int32_t launch_gemm(int n, const void *X, int ldx, int dt, int d_in, const void 
         else if (dt == FTC_F16) gemm_t<F16>(n, X, ldx, d_in, W, dt, d_out, Z, ldz, zdt, epi, s);
         else gemm_t<BF16>(n, X, ldx, d_in, W, dt, d_out, Z, ldz, zdt, epi, s);
     } else {
-        const int64_t total = static_cast<int64_t>(n) * d_out;
-        hipLaunchKernelGGL(gemm_generic_kernel, dim3(static_cast<unsigned>((total + 255) / 256)), dim3(256), 0,
-                           s, n, X, ldx, dt, d_in, W, d_out, Z, ldz, zdt, epi);
+        const unsigned grid = static_cast<unsigned>((static_cast<int64_t>(n) + GU_ROWS - 1) / GU_ROWS);
+        for (int col0 = 0; col0 < d_out; col0 += 64) {
+            const int cols = d_out - col0 < 64 ? d_out - col0 : 64;
+            hipLaunchKernelGGL(gemm_unaligned_kernel, dim3(grid), dim3(256), 0, s, n, X, ldx, dt, d_in, W, d_out, col0,
+                               cols, Z, ldz, zdt, epi);
+        }
     }
     return launch_status("update_gemm");
 }
