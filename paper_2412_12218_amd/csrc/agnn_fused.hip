@@ -37,7 +37,8 @@ size_t agnn_fused_ws(int nnz, int D)
     return align_up(n_ranges * 2 * (dp + 4) * sizeof(float), 256) + align_up(n_ranges * 2 * sizeof(int), 256);
 }
 
-template <class T, int VEC, int LPR>
+// KEEP: also write what the backward pass needs (row_z, out32); compiled out of the inference kernel.
+template <class T, int VEC, int LPR, bool KEEP>
 __global__ __launch_bounds__(256) void agnn_fused_kernel(int nnz, int n_ranges, const int *__restrict__ col_idx,
                                                          const int *__restrict__ edge_to_row,
                                                          const void *__restrict__ H, int ld, int D, float beta,
@@ -104,9 +105,11 @@ __global__ __launch_bounds__(256) void agnn_fused_kernel(int nnz, int n_ranges, 
 #pragma unroll
             for (int j = 0; j < VEC; ++j) o[j] = acc[j] * inv;
             store_vec<VEC>(out, static_cast<int64_t>(row) * ldo + sub * VEC, odt, o);
-            if (out32) store_vec<VEC>(out32, static_cast<int64_t>(row) * ld32 + sub * VEC, FTC_F32, o);  // unrounded copy
+            if constexpr (KEEP)
+                if (out32) store_vec<VEC>(out32, static_cast<int64_t>(row) * ld32 + sub * VEC, FTC_F32, o);  // unrounded copy
         }
-        if (row_z && sub == 0) row_z[row] = z;  // softmax denominator (shifted by |beta|), kept for the backward pass
+        if constexpr (KEEP)
+            if (row_z && sub == 0) row_z[row] = z;  // softmax denominator (shifted by |beta|), kept for the backward pass
     };
 
     // every group runs the same number of batches: the lane shuffles of the dot product need the
@@ -228,8 +231,10 @@ __global__ __launch_bounds__(256) void agnn_fused_kernel(int nnz, int n_ranges, 
                             if (d == 0) cv[DP] = run_z;
                         } else {
                             if (d < D) store_elem(out, static_cast<int64_t>(run_row) * ldo + d, odt, run / run_z);
-                            if (out32 && d < D) out32[static_cast<int64_t>(run_row) * ld32 + d] = run / run_z;
-                            if (row_z && d == 0) row_z[run_row] = run_z;
+                            if constexpr (KEEP) {
+                                if (out32 && d < D) out32[static_cast<int64_t>(run_row) * ld32 + d] = run / run_z;
+                                if (row_z && d == 0) row_z[run_row] = run_z;
+                            }
                         }
                         run_row = -1;
                         from_outside = false;
@@ -361,14 +366,18 @@ static void launch_agnn_t(int vec, int lpr, unsigned grid, hipStream_t s, int nn
                           int ldo, int odt, float *carry, int *tail_row, float *row_z, float *out32, int ld32)
 {
     constexpr int VM = T::VEC;
-#define FTC_AG(V, L)                                                                                        \
-    hipLaunchKernelGGL((agnn_fused_kernel<T, V, L>), dim3(grid), dim3(256), 0, s, nnz, n_ranges, g.col_idx, \
-                       e2r, H, ld, D, beta, out, ldo, odt, carry, tail_row, row_z, out32, ld32)
+#define FTC_AG(V, L)                                                                                                  \
+    if (row_z || out32)                                                                                               \
+        hipLaunchKernelGGL((agnn_fused_kernel<T, V, L, true>), dim3(grid), dim3(256), 0, s, nnz, n_ranges, g.col_idx, \
+                           e2r, H, ld, D, beta, out, ldo, odt, carry, tail_row, row_z, out32, ld32);                  \
+    else                                                                                                              \
+        hipLaunchKernelGGL((agnn_fused_kernel<T, V, L, false>), dim3(grid), dim3(256), 0, s, nnz, n_ranges,           \
+                           g.col_idx, e2r, H, ld, D, beta, out, ldo, odt, carry, tail_row, row_z, out32, ld32)
     if (vec == VM) {
-        if (lpr == 4) FTC_AG(VM, 4);
-        else if (lpr == 8) FTC_AG(VM, 8);
-        else if (lpr == 16) FTC_AG(VM, 16);
-        else FTC_AG(VM, 32);
+        if (lpr == 4) { FTC_AG(VM, 4); }
+        else if (lpr == 8) { FTC_AG(VM, 8); }
+        else if (lpr == 16) { FTC_AG(VM, 16); }
+        else { FTC_AG(VM, 32); }
     } else if (vec == VM / 2) {
         FTC_AG(VM / 2, 4);
     } else {
