@@ -79,7 +79,7 @@ __global__ __launch_bounds__(256) void agnn_fused_kernel(int nnz, int n_ranges, 
     const int prev_row = (active && base > 0) ? edge_to_row[base - 1] : -1;
     const int next_row = (active && n_valid == AG_R && base + AG_R < nnz) ? edge_to_row[base + AG_R] : -1;
     // row of the first edge after the NEXT range: tells whether a row left open here ends there
-    const int far_row = (active && base + 2 * AG_R < nnz) ? edge_to_row[base + 2 * AG_R] : -1;
+    const int far_row = (active && static_cast<int64_t>(base) + 2 * AG_R < nnz) ? edge_to_row[base + 2 * AG_R] : -1;
     __syncthreads();
 
     const int rs = g * RUN;

@@ -836,7 +836,7 @@ __global__ __launch_bounds__(256) void win_pack_kernel(int n_windows, const int 
     const int total = win_col_ptr[n_windows];
     if (run * PACK_PER_WAVE >= total) return;  // the whole wave (the grid is sized for the capacity of win_cols)
     const int o_first = static_cast<int>(run) * PACK_PER_WAVE;
-    const int o_last = (o_first + PACK_PER_WAVE < total ? o_first + PACK_PER_WAVE : total) - 1;
+    const int n_here = total - o_first < PACK_PER_WAVE ? total - o_first : PACK_PER_WAVE;  // entries of this run
     // pack_win[run + 1] is the window of the next run's first entry, or the last window
     const int w_lo = pack_win[run], w_hi = pack_win[run + 1], n_win = w_hi - w_lo + 1;
     int src[STEPS];
@@ -858,23 +858,23 @@ __global__ __launch_bounds__(256) void win_pack_kernel(int n_windows, const int 
                 const int bt = __builtin_amdgcn_readlane(begin_l[q], t), ft = __builtin_amdgcn_readlane(first_l[q], t);
 #pragma unroll
                 for (int j = 0; j < STEPS; ++j) {
-                    if (o_first + j * 64 + lane >= bt) { begin[j] = bt; first[j] = ft; }
+                    if (j * 64 + lane >= bt - o_first) { begin[j] = bt; first[j] = ft; }  // entry o_first + 64 j + lane
                 }
             }
         }
 #pragma unroll
         for (int j = 0; j < STEPS; ++j) {
-            const int o = o_first + j * 64 + lane;
-            src[j] = o <= o_last ? first[j] + (o - begin[j]) : -1;
+            const int rel = j * 64 + lane;
+            src[j] = rel < n_here ? first[j] + (o_first - begin[j]) + rel : -1;
         }
     } else {
         int w = w_lo;
         int w_begin = win_col_ptr[w], w_end = win_col_ptr[w + 1], first = row_ptr[w * blk_h];
 #pragma unroll
         for (int j = 0; j < STEPS; ++j) {
-            const int o = o_first + j * 64 + lane;
             src[j] = -1;
-            if (o <= o_last) {
+            if (j * 64 + lane < n_here) {
+                const int o = o_first + j * 64 + lane;
                 if (o >= w_end) {  // the entry's window lies in (w, w_hi]
                     int a = w + 1 < w_hi ? w + 1 : w_hi, b = w_hi;
                     while (a < b) {

@@ -103,7 +103,7 @@ __global__ __launch_bounds__(256) void spmm_seg_kernel(int nnz, int n_ranges, co
     const int prev_row = (active && base > 0) ? edge_to_row[base - 1] : -1;
     const int next_row = (active && n_valid == SEG_R && base + SEG_R < nnz) ? edge_to_row[base + SEG_R] : -1;
     // row of the first edge after the NEXT range: tells whether a row left open here ends there
-    const int far_row = (active && base + 2 * SEG_R < nnz) ? edge_to_row[base + 2 * SEG_R] : -1;
+    const int far_row = (active && static_cast<int64_t>(base) + 2 * SEG_R < nnz) ? edge_to_row[base + 2 * SEG_R] : -1;
     __syncthreads();
 
     const int rs = g * RUN;
