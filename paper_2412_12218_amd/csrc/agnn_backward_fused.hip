@@ -413,7 +413,7 @@ int32_t launch_agnn_backward_fused(const ftc_csr &g, const ftc_windows &w, const
     seg_shape(dt, D, &vec, &lpr);
     const int dp = vec * lpr, dp2 = 2 * dp;
     const int n = g.n;
-    const int n_ranges = (g.nnz + SEG_R - 1) / SEG_R;
+    const int n_ranges = ceil_div(g.nnz, SEG_R);
     char *p = static_cast<char *>(ws);
     float *QA = reinterpret_cast<float *>(p);
     p += align_up(static_cast<size_t>(n) * dp2 * sizeof(float), 256);

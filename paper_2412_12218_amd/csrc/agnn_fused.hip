@@ -395,7 +395,7 @@ int32_t launch_agnn_fused(const ftc_csr &g, const ftc_windows &w, const void *H,
     int vec = 0, lpr = 0;
     seg_shape(dt, D, &vec, &lpr);
     const int dp = vec * lpr;
-    const int n_ranges = (g.nnz + AG_R - 1) / AG_R;
+    const int n_ranges = ceil_div(g.nnz, AG_R);
     float *carry = static_cast<float *>(ws);
     int *tail_row = reinterpret_cast<int *>(
         static_cast<char *>(ws) + align_up(static_cast<size_t>(n_ranges) * 2 * (dp + 4) * sizeof(float), 256));

@@ -47,7 +47,7 @@ int32_t launch_transpose_index(const ftc_csr &g, const int *edge_to_row, int *T,
 {
     hipLaunchKernelGGL(set_int_kernel, dim3(1), dim3(1), 0, s, flag, 0);
     if (g.nnz > 0)
-        hipLaunchKernelGGL(transpose_index_kernel, dim3((g.nnz + 255) / 256), dim3(256), 0, s, g.n, g.nnz, g.row_ptr,
+        hipLaunchKernelGGL(transpose_index_kernel, dim3(ceil_div(g.nnz, 256)), dim3(256), 0, s, g.n, g.nnz, g.row_ptr,
                            g.col_idx, edge_to_row, T, flag);
     return launch_status("transpose_index");
 }
@@ -447,7 +447,7 @@ int32_t launch_edge_combine(int nnz, const float *a, const int *T, float wa, flo
                             const int *col_idx, float *out, hipStream_t s)
 {
     if (nnz == 0) return FTC_OK;
-    hipLaunchKernelGGL(edge_combine_kernel, dim3((nnz + 255) / 256), dim3(256), 0, s, nnz, a, T, wa, wb, alpha, cs,
+    hipLaunchKernelGGL(edge_combine_kernel, dim3(ceil_div(nnz, 256)), dim3(256), 0, s, nnz, a, T, wa, wb, alpha, cs,
                        col_idx, out);
     return launch_status("edge_combine");
 }

@@ -1041,7 +1041,7 @@ int32_t launch_build_windows(const ftc_csr &g, ftc_windows &w, void *ws, size_t 
     if (g.nnz == 0) return FTC_OK;
     hipLaunchKernelGGL(win_pack_plan_kernel, dim3((w.n_windows + 255) / 256), dim3(256), 0, s, w.n_windows, w.win_col_ptr,
                        k.pack_win);
-    hipLaunchKernelGGL(win_pack_kernel, dim3((g.nnz + 4 * PACK_PER_WAVE - 1) / (4 * PACK_PER_WAVE)), dim3(256), 0, s,
+    hipLaunchKernelGGL(win_pack_kernel, dim3(ceil_div(g.nnz, 4 * PACK_PER_WAVE)), dim3(256), 0, s,
                        w.n_windows, g.row_ptr, w.blk_h, w.win_col_ptr, k.pack_win, k.tmp_cols, w.win_cols);
     return launch_status("build_windows pack");
 }

@@ -21,6 +21,9 @@ inline int elem_size(int dtype) { return dtype == FTC_F32 ? 4 : 2; }
 inline bool valid_dtype(int d) { return d == FTC_F32 || d == FTC_F16 || d == FTC_BF16; }
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// ceil(a / b) for non-negative a up to INT32_MAX (the sum a + b - 1 would not fit)
+inline int ceil_div(int a, int b) { return static_cast<int>((static_cast<int64_t>(a) + b - 1) / b); }
+
 // Epilogue of the kernels that produce dense rows: out = act(scale[row] * value), scale optional.
 struct Epi {
     int relu;

@@ -61,10 +61,10 @@ int32_t launch_gcn_norm(const ftc_csr &g, const ftc_windows *w, float *vals, flo
     }
     if (vals && g.nnz > 0) {
         if (w && dinv) {
-            hipLaunchKernelGGL(gcn_vals_edges_dinv_kernel, dim3((g.nnz + 255) / 256), dim3(256), 0, s, g.nnz,
+            hipLaunchKernelGGL(gcn_vals_edges_dinv_kernel, dim3(ceil_div(g.nnz, 256)), dim3(256), 0, s, g.nnz,
                                g.col_idx, w->edge_to_row, dinv, vals);
         } else if (w) {
-            hipLaunchKernelGGL(gcn_vals_edges_kernel, dim3((g.nnz + 255) / 256), dim3(256), 0, s, g.nnz,
+            hipLaunchKernelGGL(gcn_vals_edges_kernel, dim3(ceil_div(g.nnz, 256)), dim3(256), 0, s, g.nnz,
                                g.row_ptr, g.col_idx, w->edge_to_row, vals);
         } else {
             hipLaunchKernelGGL(gcn_vals_rows_kernel, dim3((g.n + 15) / 16), dim3(256), 0, s, g.n, g.row_ptr,

@@ -462,7 +462,7 @@ int32_t launch_label_propagation(const ftc_csr &g, int iters, int *labels, void 
     p += align_up(static_cast<size_t>(n) * sizeof(unsigned long long), 256);
     void *ws_sort = p; p += radix_ws(m);
     void *ws_scan = p;
-    const unsigned ge = static_cast<unsigned>((nnz + 255) / 256), gn = static_cast<unsigned>((n + 255) / 256);
+    const unsigned ge = static_cast<unsigned>(ceil_div(nnz, 256)), gn = static_cast<unsigned>((n + 255) / 256);
     hipLaunchKernelGGL(entry_rows_kernel, dim3(ge), dim3(256), 0, s, n, nnz, g.row_ptr, rows);
     const int bits = bit_length(static_cast<uint32_t>(n - 1));
     for (int it = 0; it < iters; ++it) {
@@ -558,8 +558,8 @@ int32_t launch_permute_graph(const ftc_csr &g, const int *perm, const int *inv, 
     int32_t st = exclusive_scan(deg, n, row_ptr_out, true, ws_scan, s);
     if (st != FTC_OK) return st;
     if (nnz == 0) return FTC_OK;
-    hipLaunchKernelGGL(fill_u32_kernel, dim3((nnz + 255) / 256), dim3(256), 0, s, k0, v0, static_cast<int64_t>(nnz));
-    hipLaunchKernelGGL(relabel_kernel, dim3((nnz + 255) / 256), dim3(256), 0, s, n, nnz, g.row_ptr, g.col_idx, inv, perm,
+    hipLaunchKernelGGL(fill_u32_kernel, dim3(ceil_div(nnz, 256)), dim3(256), 0, s, k0, v0, static_cast<int64_t>(nnz));
+    hipLaunchKernelGGL(relabel_kernel, dim3(ceil_div(nnz, 256)), dim3(256), 0, s, n, nnz, g.row_ptr, g.col_idx, inv, perm,
                        row_ptr_out, k0, v0, flag);
     // ascending (row, column): stable sort by column, then by row (rows are the values of the first
     // sort and the keys of the second)

@@ -154,7 +154,7 @@ int32_t launch_sddmm_edges(const ftc_csr &g, const ftc_windows &w, const void *X
     if (g.nnz == 0) return FTC_OK;
     int vec = 0, lpr = 0;
     seg_shape(dt, D, &vec, &lpr);
-    const int n_ranges = (g.nnz + SD_R - 1) / SD_R;
+    const int n_ranges = ceil_div(g.nnz, SD_R);
     const unsigned grid = static_cast<unsigned>((n_ranges + 3) / 4);
     if (dt == FTC_F32)
         launch_edges_t<F32>(vec, lpr, grid, s, g.nnz, n_ranges, g, w.edge_to_row, X, Y, ld, D, rs, cs, alpha, out, dense, cosine);

@@ -387,7 +387,7 @@ static int32_t launch_ranges(const ftc_csr &g, const ftc_windows &w, const float
                              void *ws, hipStream_t s)
 {
     if (g.n == 0 || g.nnz == 0) return FTC_OK;
-    const int n_ranges = (g.nnz + SMS_R - 1) / SMS_R;
+    const int n_ranges = ceil_div(g.nnz, SMS_R);
     char *p = static_cast<char *>(ws);
     float2 *stats = reinterpret_cast<float2 *>(p);
     p += align_up(static_cast<size_t>(g.n) * sizeof(float2), 256);

@@ -285,7 +285,7 @@ int32_t launch_spmm_lane(const ftc_csr &g, const ftc_windows &w, const float *va
 {
     const int per = xdt == FTC_F32 ? 4 : 8;
     const int lpe = (D + per - 1) / per, dp = per * lpe, range = SL_R / lpe;
-    const int n_ranges = (g.nnz + range - 1) / range;
+    const int n_ranges = ceil_div(g.nnz, range);
     float *carry = static_cast<float *>(ws);
     int *tail_row = reinterpret_cast<int *>(static_cast<char *>(ws) +
                                             align_up(static_cast<size_t>(n_ranges) * 2 * dp * sizeof(float), 256));

@@ -353,7 +353,7 @@ int32_t launch_spmm_seg(const ftc_csr &g, const ftc_windows &w, const float *val
     int vec = 0, lpr = 0;
     seg_shape(xdt, D, &vec, &lpr);
     const int dp = vec * lpr;
-    const int n_ranges = (g.nnz + SEG_R - 1) / SEG_R;
+    const int n_ranges = ceil_div(g.nnz, SEG_R);
     float *carry = static_cast<float *>(ws);
     int *tail_row = reinterpret_cast<int *>(static_cast<char *>(ws) +
                                             align_up(static_cast<size_t>(n_ranges) * 2 * dp * sizeof(float), 256));
