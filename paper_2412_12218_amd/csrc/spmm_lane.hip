@@ -22,6 +22,7 @@ namespace ftc {
 constexpr int SL_L = 16;         // consecutive edges per lane
 constexpr int SL_R = 64 * SL_L;  // edges per wave
 constexpr int SL_B = 8;          // gathers issued together
+constexpr int SL_ROWS = 256;     // row starts per range that are held in registers (four per lane)
 
 template <int CTRL, int ROW_MASK>
 __device__ __forceinline__ int sl_dpp(int v)
@@ -81,7 +82,8 @@ __device__ __forceinline__ void wave_segmented_sum_slots(float (&x)[N], int head
 // halves of a row, so a load instruction still touches one contiguous 32-byte segment per edge).
 // VALS = false: all edge values are one.
 template <class T, int LPE, bool VALS>
-__global__ __launch_bounds__(256) void spmm_lane_kernel(int nnz, int n_ranges, const int *__restrict__ col_idx,
+__global__ __launch_bounds__(256) void spmm_lane_kernel(int nnz, int n_ranges, const int *__restrict__ row_ptr,
+                                                        const int *__restrict__ col_idx,
                                                         const int *__restrict__ edge_to_row,
                                                         const float *__restrict__ vals, const void *__restrict__ X,
                                                         int ldx, int D, void *__restrict__ out, int ldo, int odt, Epi epi,
@@ -107,12 +109,59 @@ __global__ __launch_bounds__(256) void spmm_lane_kernel(int nnz, int n_ranges, c
 #pragma unroll
         for (int q = 0; q < SL_L / 4; ++q) {
             const int4 c4 = *reinterpret_cast<const int4 *>(col_idx + base + e0 + 4 * q);
-            const int4 r4 = *reinterpret_cast<const int4 *>(edge_to_row + base + e0 + 4 * q);
             c[4 * q] = c4.x; c[4 * q + 1] = c4.y; c[4 * q + 2] = c4.z; c[4 * q + 3] = c4.w;
-            r[4 * q] = r4.x; r[4 * q + 1] = r4.y; r[4 * q + 2] = r4.z; r[4 * q + 3] = r4.w;
             if constexpr (VALS) {
                 const float4 a4 = *reinterpret_cast<const float4 *>(vals + base + e0 + 4 * q);
                 a[4 * q] = a4.x; a[4 * q + 1] = a4.y; a[4 * q + 2] = a4.z; a[4 * q + 3] = a4.w;
+            }
+        }
+        // The rows of the wave's edges.  Reading edge_to_row for every edge is a second 4-byte stream next to
+        // the column ids; the rows of a full range are also known from its first and last row and the
+        // row starts in between: with at most SL_ROWS rows and no empty row among them, the starts are
+        // fetched one per lane, a lane counts those at or before its first edge and marks those inside
+        // its 16 edges, and the row of an edge is the first row plus the starts up to it.
+        const int r_first = edge_to_row[base], r_last = edge_to_row[base + RANGE - 1];
+        const int n_starts = r_last - r_first;  // rows r_first + 1 .. r_last begin inside the range
+        bool from_starts = n_starts <= SL_ROWS;
+        int start_l[SL_ROWS / 64];
+        if (from_starts) {
+#pragma unroll
+            for (int q = 0; q < SL_ROWS / 64; ++q) {
+                const int t = q * 64 + lane;
+                start_l[q] = t < n_starts ? row_ptr[r_first + 1 + t] : INT32_MAX;
+            }
+            // an empty row shares its start with the next row: the count of starts would still be right, the
+            // marks inside a lane's edges would not tell how many rows begin at one edge
+            bool dup = false;
+#pragma unroll
+            for (int q = 0; q < SL_ROWS / 64; ++q) {
+                const int over = q + 1 < SL_ROWS / 64 ? __shfl(start_l[q + 1 < SL_ROWS / 64 ? q + 1 : q], 0, 64) : INT32_MAX;
+                int nxt = __shfl_down(start_l[q], 1, 64);  // every lane takes part in both moves
+                if (lane == 63) nxt = over;
+                dup = dup || (start_l[q] != INT32_MAX && start_l[q] == nxt);
+            }
+            from_starts = __builtin_amdgcn_ballot_w64(dup) == 0ull;
+        }
+        if (from_starts) {
+            const int first_edge = base + e0;
+            int before = 0;          // starts at or before the lane's first edge
+            unsigned inside = 0u;    // bit k: a row starts at edge k of the lane (k = 1 .. 15)
+#pragma unroll
+            for (int q = 0; q < SL_ROWS / 64; ++q) {
+                const int n_q = n_starts - q * 64 < 64 ? n_starts - q * 64 : 64;
+                for (int t = 0; t < n_q; ++t) {
+                    const int rel = __builtin_amdgcn_readlane(start_l[q], t) - first_edge;
+                    if (rel <= 0) ++before;
+                    else if (rel < SL_L) inside |= 1u << rel;
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < SL_L; ++k) r[k] = r_first + before + __popc(inside & ((2u << k) - 1u));
+        } else {
+#pragma unroll
+            for (int q = 0; q < SL_L / 4; ++q) {
+                const int4 r4 = *reinterpret_cast<const int4 *>(edge_to_row + base + e0 + 4 * q);
+                r[4 * q] = r4.x; r[4 * q + 1] = r4.y; r[4 * q + 2] = r4.z; r[4 * q + 3] = r4.w;
             }
         }
     } else {
@@ -266,7 +315,7 @@ static void launch_lane_t(int lpe, unsigned grid, hipStream_t s, int nnz, int n_
                           float *carry, int *tail_row, int idx_vec, int out_vec)
 {
 #define FTC_LANE(LPE, VALS)                                                                                         \
-    hipLaunchKernelGGL((spmm_lane_kernel<T, LPE, VALS>), dim3(grid), dim3(256), 0, s, nnz, n_ranges, g.col_idx, e2r, \
+    hipLaunchKernelGGL((spmm_lane_kernel<T, LPE, VALS>), dim3(grid), dim3(256), 0, s, nnz, n_ranges, g.row_ptr, g.col_idx, e2r, \
                        vals, X, ldx, D, out, ldo, odt, epi, carry, tail_row, idx_vec, out_vec)
     if (lpe == 1) {
         if (vals) FTC_LANE(1, true);
