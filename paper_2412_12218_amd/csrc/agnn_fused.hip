@@ -39,7 +39,8 @@ size_t agnn_fused_ws(int nnz, int D)
 
 // KEEP: also write what the backward pass needs (row_z, out32); compiled out of the inference kernel.
 template <class T, int VEC, int LPR, bool KEEP>
-__global__ __launch_bounds__(256) void agnn_fused_kernel(int nnz, int n_ranges, const int *__restrict__ col_idx,
+__global__ __launch_bounds__(256) void agnn_fused_kernel(int nnz, int n_ranges, const int *__restrict__ row_ptr,
+                                                         const int *__restrict__ col_idx,
                                                          const int *__restrict__ edge_to_row,
                                                          const void *__restrict__ H, int ld, int D, float beta,
                                                          void *__restrict__ out, int ldo, int odt,
@@ -67,13 +68,24 @@ __global__ __launch_bounds__(256) void agnn_fused_kernel(int nnz, int n_ranges, 
     const bool active = v < n_ranges;
     const int base = active ? v * AG_R : 0;
     const int n_valid = active ? min(AG_R, nnz - base) : 0;
+    int rows[AG_R / 64];
+    if (n_valid == AG_R && rows_from_starts<AG_R>(row_ptr, edge_to_row, base, lane, rows)) {
 #pragma unroll
-    for (int j = 0; j < AG_R / 64; ++j) {
-        const int i = j * 64 + lane;
-        if (i < n_valid) {
+        for (int j = 0; j < AG_R / 64; ++j) {
+            const int i = j * 64 + lane;
             const int p = i + i / RUN;
             s_col[p] = col_idx[base + i];
-            s_row[p] = edge_to_row[base + i];
+            s_row[p] = rows[j];
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < AG_R / 64; ++j) {
+            const int i = j * 64 + lane;
+            if (i < n_valid) {
+                const int p = i + i / RUN;
+                s_col[p] = col_idx[base + i];
+                s_row[p] = edge_to_row[base + i];
+            }
         }
     }
     const int prev_row = (active && base > 0) ? edge_to_row[base - 1] : -1;
@@ -368,11 +380,11 @@ static void launch_agnn_t(int vec, int lpr, unsigned grid, hipStream_t s, int nn
     constexpr int VM = T::VEC;
 #define FTC_AG(V, L)                                                                                                  \
     if (row_z || out32)                                                                                               \
-        hipLaunchKernelGGL((agnn_fused_kernel<T, V, L, true>), dim3(grid), dim3(256), 0, s, nnz, n_ranges, g.col_idx, \
-                           e2r, H, ld, D, beta, out, ldo, odt, carry, tail_row, row_z, out32, ld32);                  \
+        hipLaunchKernelGGL((agnn_fused_kernel<T, V, L, true>), dim3(grid), dim3(256), 0, s, nnz, n_ranges, g.row_ptr, \
+                           g.col_idx, e2r, H, ld, D, beta, out, ldo, odt, carry, tail_row, row_z, out32, ld32);       \
     else                                                                                                              \
         hipLaunchKernelGGL((agnn_fused_kernel<T, V, L, false>), dim3(grid), dim3(256), 0, s, nnz, n_ranges,           \
-                           g.col_idx, e2r, H, ld, D, beta, out, ldo, odt, carry, tail_row, row_z, out32, ld32)
+                           g.row_ptr, g.col_idx, e2r, H, ld, D, beta, out, ldo, odt, carry, tail_row, row_z, out32, ld32)
     if (vec == VM) {
         if (lpr == 4) { FTC_AG(VM, 4); }
         else if (lpr == 8) { FTC_AG(VM, 8); }

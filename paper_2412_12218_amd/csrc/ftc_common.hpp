@@ -361,6 +361,33 @@ __device__ __forceinline__ int xcd_chunked_block(int b, int grid)
     return ((k / XCD_CHUNK) * 8 + x) * XCD_CHUNK + k % XCD_CHUNK;
 }
 
+// Rows of the R consecutive edges [base, base + R) of a FULL range, for a wave that stages edge 64 j + lane
+// in step j: rows[j] = row of that edge.  Reading edge_to_row for every edge is a second 4-byte stream next
+// to the column ids; the rows are also known from the range's first and last row and the starts of the
+// rows in between: with at most 64 of those, every lane fetches one start and an edge's row is the first
+// row plus the number of starts at or before it (empty rows count themselves in).  Returns false
+// (wave-uniform) when the range holds more rows than that: the caller then reads edge_to_row.
+template <int R>
+__device__ __forceinline__ bool rows_from_starts(const int *__restrict__ row_ptr, const int *__restrict__ edge_to_row,
+                                                 int base, int lane, int (&rows)[R / 64])
+{
+    const int r_first = edge_to_row[base], r_last = edge_to_row[base + R - 1];
+    const int n_starts = r_last - r_first;  // rows r_first + 1 .. r_last begin inside the range
+    if (n_starts > 64) return false;
+    const int start = lane < n_starts ? row_ptr[r_first + 1 + lane] - base : INT32_MAX;
+    int cnt[R / 64];
+#pragma unroll
+    for (int j = 0; j < R / 64; ++j) cnt[j] = 0;
+    for (int t = 0; t < n_starts; ++t) {
+        const int rel = __builtin_amdgcn_readlane(start, t) - lane;  // the start seen from this lane's edge of step 0
+#pragma unroll
+        for (int j = 0; j < R / 64; ++j) cnt[j] += rel <= j * 64 ? 1 : 0;
+    }
+#pragma unroll
+    for (int j = 0; j < R / 64; ++j) rows[j] = r_first + cnt[j];
+    return true;
+}
+
 // Inclusive prefix sum over the 64 lanes of a wave with data-parallel-primitive moves: shifts by
 // 1, 2, 4, 8 inside rows of 16 lanes, then lane 15 of a row added to the next row (rows 1 and 3) and
 // lane 31 added to rows 2 and 3.
