@@ -21,7 +21,8 @@ bool seg_shape(int dtype, int D, int *vec, int *lpr);  // spmm_seg.hip: same lan
 // packed dot product and lane-group sum per edge) instead of being gathered, 4 bytes at a time,
 // from arrays of inverse norms: on a graph without locality that gather moves a 64-byte sector per edge.
 template <class T, int VEC, int LPR, bool COS>
-__global__ __launch_bounds__(256) void sddmm_edges_kernel(int nnz, int n_ranges, const int *__restrict__ col_idx,
+__global__ __launch_bounds__(256) void sddmm_edges_kernel(int nnz, int n_ranges, const int *__restrict__ row_ptr,
+                                                          const int *__restrict__ col_idx,
                                                           const int *__restrict__ edge_to_row,
                                                           const void *__restrict__ X,
                                                           const void *__restrict__ Y, int ld, int D,
@@ -46,12 +47,14 @@ __global__ __launch_bounds__(256) void sddmm_edges_kernel(int nnz, int n_ranges,
     const bool active = v < n_ranges;
     const int base = active ? v * SD_R : 0;
     const int n_valid = active ? min(SD_R, nnz - base) : 0;
+    int rows[SD_R / 64];
+    const bool from_starts = n_valid == SD_R && rows_from_starts<SD_R>(row_ptr, edge_to_row, base, lane, rows);
 #pragma unroll
     for (int j = 0; j < SD_R / 64; ++j) {
         const int i = j * 64 + lane;
         if (i < n_valid) {
             const int p = i + i / RUN;
-            const int er = edge_to_row[base + i];
+            const int er = from_starts ? rows[j] : edge_to_row[base + i];
             const bool skip = dense && dense[er >> 4];  // that window goes to the matrix cores
             s_col[p] = skip ? -1 : col_idx[base + i];
             s_row[p] = skip ? -1 : er;
@@ -128,10 +131,10 @@ static void launch_edges_t(int vec, int lpr, unsigned grid, hipStream_t s, int n
     do {                                                                                                       \
         if (cosine)                                                                                            \
             hipLaunchKernelGGL((sddmm_edges_kernel<T, V, L, true>), dim3(grid), dim3(256), 0, s, nnz, n_ranges, \
-                               g.col_idx, e2r, X, Y, ld, D, nullptr, nullptr, alpha, out, dense);              \
+                               g.row_ptr, g.col_idx, e2r, X, Y, ld, D, nullptr, nullptr, alpha, out, dense);   \
         else                                                                                                   \
             hipLaunchKernelGGL((sddmm_edges_kernel<T, V, L, false>), dim3(grid), dim3(256), 0, s, nnz,         \
-                               n_ranges, g.col_idx, e2r, X, Y, ld, D, rs, cs, alpha, out, dense);              \
+                               n_ranges, g.row_ptr, g.col_idx, e2r, X, Y, ld, D, rs, cs, alpha, out, dense);   \
     } while (0)
     if (vec == VM) {
         if (lpr == 4) FTC_SD(VM, 4);

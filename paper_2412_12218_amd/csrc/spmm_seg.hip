@@ -60,7 +60,8 @@ size_t spmm_seg_ws(int nnz, int D)
 // VALS = false: all edge values are one (vals == NULL): nothing is staged or multiplied for them, which
 // also cuts the LDS footprint by a third (more workgroups per CU).
 template <class T, int VEC, int LPR, bool VALS>
-__global__ __launch_bounds__(256) void spmm_seg_kernel(int nnz, int n_ranges, const int *__restrict__ col_idx,
+__global__ __launch_bounds__(256) void spmm_seg_kernel(int nnz, int n_ranges, const int *__restrict__ row_ptr,
+                                                       const int *__restrict__ col_idx,
                                                        const int *__restrict__ edge_to_row,
                                                        const float *__restrict__ vals,
                                                        const void *__restrict__ X, int ldx, int D,
@@ -88,12 +89,14 @@ __global__ __launch_bounds__(256) void spmm_seg_kernel(int nnz, int n_ranges, co
     const bool active = v < n_ranges;
     const int base = active ? v * SEG_R : 0;
     const int n_valid = active ? min(SEG_R, nnz - base) : 0;
+    int rows[SEG_R / 64];
+    const bool from_starts = n_valid == SEG_R && rows_from_starts<SEG_R>(row_ptr, edge_to_row, base, lane, rows);
 #pragma unroll
     for (int j = 0; j < SEG_R / 64; ++j) {
         const int i = j * 64 + lane;
         if (i < n_valid) {
             const int p = i + i / RUN;
-            const int er = edge_to_row[base + i];
+            const int er = from_starts ? rows[j] : edge_to_row[base + i];
             // edges of windows that go to the matrix cores are skipped here (column -1)
             s_col[p] = (dense && dense[er >> 4]) ? -1 : col_idx[base + i];
             s_row[p] = er;
@@ -322,11 +325,12 @@ static void launch_seg_t(int vec, int lpr, unsigned grid, hipStream_t s, int nnz
     do {                                                                                                    \
         if (vals)                                                                                           \
             hipLaunchKernelGGL((spmm_seg_kernel<T, V, L, true>), dim3(grid), dim3(256), 0, s, nnz, n_ranges, \
-                               g.col_idx, e2r, vals, X, ldx, D, out, ldo, odt, epi, carry, tail_row, dense); \
+                               g.row_ptr, g.col_idx, e2r, vals, X, ldx, D, out, ldo, odt, epi, carry,        \
+                               tail_row, dense);                                                            \
         else                                                                                                \
             hipLaunchKernelGGL((spmm_seg_kernel<T, V, L, false>), dim3(grid), dim3(256), 0, s, nnz,         \
-                               n_ranges, g.col_idx, e2r, vals, X, ldx, D, out, ldo, odt, epi, carry,        \
-                               tail_row, dense);                                                            \
+                               n_ranges, g.row_ptr, g.col_idx, e2r, vals, X, ldx, D, out, ldo, odt, epi,    \
+                               carry, tail_row, dense);                                                     \
     } while (0)
     if (vec == VM) {
         if (lpr == 4) FTC_SEG(VM, 4);
