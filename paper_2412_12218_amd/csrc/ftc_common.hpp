@@ -388,6 +388,54 @@ __device__ __forceinline__ bool rows_from_starts(const int *__restrict__ row_ptr
     return true;
 }
 
+// The same for a wave whose lanes own L CONSECUTIVE edges each (the lane's first edge is base + e0; lanes
+// of one slot may share it): rows[k] = row of edge base + e0 + k, for a full range of `range` edges.
+// Up to 256 row starts are held four per lane; a lane counts the starts at or before its first edge and
+// marks those inside its L <= 32 edges.  An empty row shares its start with the next row, and a mark
+// cannot say how many rows begin at one edge: such ranges, and ranges with more rows, return false
+// (wave-uniform) and the caller reads edge_to_row.  All 64 lanes must be active.
+template <int L>
+__device__ __forceinline__ bool lane_rows_from_starts(const int *__restrict__ row_ptr,
+                                                      const int *__restrict__ edge_to_row, int base, int range, int e0,
+                                                      int lane, int (&rows)[L])
+{
+    static_assert(L <= 32, "one mark per edge in a 32-bit word");
+    constexpr int Q = 4;  // starts per lane
+    const int r_first = edge_to_row[base], r_last = edge_to_row[base + range - 1];
+    const int n_starts = r_last - r_first;  // rows r_first + 1 .. r_last begin inside the range
+    if (n_starts > 64 * Q) return false;
+    int start_l[Q];
+#pragma unroll
+    for (int q = 0; q < Q; ++q) {
+        const int t = q * 64 + lane;
+        start_l[q] = t < n_starts ? row_ptr[r_first + 1 + t] : INT32_MAX;
+    }
+    bool dup = false;
+#pragma unroll
+    for (int q = 0; q < Q; ++q) {
+        const int over = q + 1 < Q ? __shfl(start_l[q + 1 < Q ? q + 1 : q], 0, 64) : INT32_MAX;
+        int nxt = __shfl_down(start_l[q], 1, 64);  // every lane takes part in both moves
+        if (lane == 63) nxt = over;
+        dup = dup || (start_l[q] != INT32_MAX && start_l[q] == nxt);
+    }
+    if (__builtin_amdgcn_ballot_w64(dup) != 0ull) return false;
+    const int first_edge = base + e0;
+    int before = 0;        // starts at or before the lane's first edge
+    unsigned inside = 0u;  // bit k: a row starts at edge k of the lane (k = 1 .. L - 1)
+#pragma unroll
+    for (int q = 0; q < Q; ++q) {
+        const int n_q = n_starts - q * 64 < 64 ? n_starts - q * 64 : 64;
+        for (int t = 0; t < n_q; ++t) {
+            const int rel = __builtin_amdgcn_readlane(start_l[q], t) - first_edge;
+            if (rel <= 0) ++before;
+            else if (rel < L) inside |= 1u << rel;
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < L; ++k) rows[k] = r_first + before + __popc(inside & ((2u << k) - 1u));
+    return true;
+}
+
 // Inclusive prefix sum over the 64 lanes of a wave with data-parallel-primitive moves: shifts by
 // 1, 2, 4, 8 inside rows of 16 lanes, then lane 15 of a row added to the next row (rows 1 and 3) and
 // lane 31 added to rows 2 and 3.

@@ -22,7 +22,6 @@ namespace ftc {
 constexpr int SL_L = 16;         // consecutive edges per lane
 constexpr int SL_R = 64 * SL_L;  // edges per wave
 constexpr int SL_B = 8;          // gathers issued together
-constexpr int SL_ROWS = 256;     // row starts per range that are held in registers (four per lane)
 
 template <int CTRL, int ROW_MASK>
 __device__ __forceinline__ int sl_dpp(int v)
@@ -115,49 +114,8 @@ __global__ __launch_bounds__(256) void spmm_lane_kernel(int nnz, int n_ranges, c
                 a[4 * q] = a4.x; a[4 * q + 1] = a4.y; a[4 * q + 2] = a4.z; a[4 * q + 3] = a4.w;
             }
         }
-        // The rows of the wave's edges.  Reading edge_to_row for every edge is a second 4-byte stream next to
-        // the column ids; the rows of a full range are also known from its first and last row and the
-        // row starts in between: with at most SL_ROWS rows and no empty row among them, the starts are
-        // fetched one per lane, a lane counts those at or before its first edge and marks those inside
-        // its 16 edges, and the row of an edge is the first row plus the starts up to it.
-        const int r_first = edge_to_row[base], r_last = edge_to_row[base + RANGE - 1];
-        const int n_starts = r_last - r_first;  // rows r_first + 1 .. r_last begin inside the range
-        bool from_starts = n_starts <= SL_ROWS;
-        int start_l[SL_ROWS / 64];
-        if (from_starts) {
-#pragma unroll
-            for (int q = 0; q < SL_ROWS / 64; ++q) {
-                const int t = q * 64 + lane;
-                start_l[q] = t < n_starts ? row_ptr[r_first + 1 + t] : INT32_MAX;
-            }
-            // an empty row shares its start with the next row: the count of starts would still be right, the
-            // marks inside a lane's edges would not tell how many rows begin at one edge
-            bool dup = false;
-#pragma unroll
-            for (int q = 0; q < SL_ROWS / 64; ++q) {
-                const int over = q + 1 < SL_ROWS / 64 ? __shfl(start_l[q + 1 < SL_ROWS / 64 ? q + 1 : q], 0, 64) : INT32_MAX;
-                int nxt = __shfl_down(start_l[q], 1, 64);  // every lane takes part in both moves
-                if (lane == 63) nxt = over;
-                dup = dup || (start_l[q] != INT32_MAX && start_l[q] == nxt);
-            }
-            from_starts = __builtin_amdgcn_ballot_w64(dup) == 0ull;
-        }
-        if (from_starts) {
-            const int first_edge = base + e0;
-            int before = 0;          // starts at or before the lane's first edge
-            unsigned inside = 0u;    // bit k: a row starts at edge k of the lane (k = 1 .. 15)
-#pragma unroll
-            for (int q = 0; q < SL_ROWS / 64; ++q) {
-                const int n_q = n_starts - q * 64 < 64 ? n_starts - q * 64 : 64;
-                for (int t = 0; t < n_q; ++t) {
-                    const int rel = __builtin_amdgcn_readlane(start_l[q], t) - first_edge;
-                    if (rel <= 0) ++before;
-                    else if (rel < SL_L) inside |= 1u << rel;
-                }
-            }
-#pragma unroll
-            for (int k = 0; k < SL_L; ++k) r[k] = r_first + before + __popc(inside & ((2u << k) - 1u));
-        } else {
+        // the rows of the lane's edges: from the row starts of the range where that works, else the per-entry stream
+        if (!lane_rows_from_starts<SL_L>(row_ptr, edge_to_row, base, RANGE, e0, lane, r)) {
 #pragma unroll
             for (int q = 0; q < SL_L / 4; ++q) {
                 const int4 r4 = *reinterpret_cast<const int4 *>(edge_to_row + base + e0 + 4 * q);
