@@ -11,10 +11,11 @@
 //          of the window picks its value by (edge_to_row, edge_to_col).  Each neighbour row is
 //          gathered once per window instead of once per edge.
 //   SpMM   out[16 x D] = A_w[16 x |S_w|] * X[S_w].  The contraction runs over condensed columns,
-//          32 per step: the edge values are scattered into an fp32 tile in LDS (duplicates add),
-//          scaled by a power of two into [-1, 1] and split into a high and a low 16-bit part (two
-//          MFMAs, so the values keep ~2^-17 relative accuracy or better); the 32 gathered rows are
-//          staged row-major in LDS and read back element-wise in operand order.
+//          32 per step: the edge values are added into an fp32 tile in LDS by the lane that owns
+//          the cell (storage order, so duplicates add reproducibly), every tile value is split
+//          into two bf16 pieces (full fp32 exponent range, 2^-17 relative accuracy per value,
+//          no common scale) and the 32 gathered rows are staged row-major in LDS and read back
+//          element-wise in operand order.
 //
 // Windows are selected by a per-window flag (see win_classify_kernel); the vector kernels skip
 // exactly the flagged windows.
@@ -138,23 +139,22 @@ __global__ __launch_bounds__(64) void sddmm_mfma_kernel(int n, const int *__rest
 }
 
 // ------------------------------------------------------------------------------------------------
-template <class T>
-__device__ __forceinline__ void split_hi_lo(float v, uint32_t &hi, uint32_t &lo)
+// An fp32 value as the sum of two bf16 pieces.  bf16 keeps the exponent range of fp32, so the pair
+// carries every value with a relative error of at most 2^-17 whatever its magnitude: no scale is
+// needed and a small value next to a large one in the same tile keeps its own accuracy.
+__device__ __forceinline__ void split_bf16_pair(float v, uint32_t &hi, uint32_t &lo)
 {
-    if constexpr (std::is_same<T, F16>::value) {
-        const _Float16 h = static_cast<_Float16>(v);
-        const _Float16 l = static_cast<_Float16>(v - static_cast<float>(h));
-        hi = __builtin_bit_cast(uint16_t, h);
-        lo = __builtin_bit_cast(uint16_t, l);
-    } else {
-        hi = f32_to_bf16_bits(v);
-        lo = f32_to_bf16_bits(v - __uint_as_float(hi << 16));
-    }
+    hi = f32_to_bf16_bits(v);
+    const bool finite = (hi & 0x7f80u) != 0x7f80u;
+    lo = finite ? f32_to_bf16_bits(v - __uint_as_float(hi << 16)) : 0u;
 }
 
+// The tile product always runs on v_mfma_f32_16x16x32_bf16.  bf16 features enter as they are (two
+// MFMAs per step: value high and low piece).  An fp16 feature (11 significant bits) is the exact sum
+// of two bf16 pieces; three MFMAs per step (high x high, low x high, high x low) leave out only the
+// low x low product, 2^-18 of a term.
 template <class T, int NT>  // NT = ceil(D / 16)
 __global__ __launch_bounds__(64) void spmm_mfma_kernel(int n, const int *__restrict__ row_ptr,
-                                                       const int *__restrict__ edge_to_row,
                                                        const int *__restrict__ edge_to_col,
                                                        const int *__restrict__ win_col_ptr,
                                                        const int *__restrict__ win_cols,
@@ -163,28 +163,27 @@ __global__ __launch_bounds__(64) void spmm_mfma_kernel(int n, const int *__restr
                                                        void *__restrict__ out, int ldo, int odt, Epi epi,
                                                        const uint8_t *__restrict__ flags)
 {
-    constexpr int DP = NT * 16 + 8;  // halves per staged row (16-byte pad)
+    constexpr bool SPLIT_X = std::is_same<T, F16>::value;
+    constexpr int DP = NT * 16 + 8;  // 16-bit elements per staged row (16-byte pad)
     __shared__ float As[16][36];     // 16 rows x 32 condensed columns (+pad)
-    __shared__ __attribute__((aligned(16))) uint16_t Xs[32 * DP];
+    __shared__ __attribute__((aligned(16))) uint16_t Xs[(SPLIT_X ? 2 : 1) * 32 * DP];
+    uint16_t *const Xlo = Xs + 32 * DP;  // low pieces of fp16 features
     const int w = blockIdx.x;
     const int r0 = w * 16;
-    const int e0 = row_ptr[r0], e1 = row_ptr[min(n, r0 + 16)];
     if (!flags[w]) return;
     const int u0 = win_col_ptr[w];
     const int uniq = win_col_ptr[w + 1] - u0;
     const int lane = threadIdx.x, m = lane & 15, kb = lane >> 4;
 
-    // power-of-two scale that brings the window's values into [-1, 1]
-    float vmax = 0.f;
-    if (vals)
-        for (int e = e0 + lane; e < e1; e += 64) vmax = fmaxf(vmax, fabsf(vals[e]));
-    else
-        vmax = 1.f;
-#pragma unroll
-    for (int s = 32; s >= 1; s >>= 1) vmax = fmaxf(vmax, __shfl_xor(vmax, s, 64));
-    int ex = 0;
-    if (vmax > 0.f) frexpf(vmax, &ex);
-    const float scale = ldexpf(1.f, ex), inv_scale = ldexpf(1.f, -ex);
+    // Lane (m, kb) owns the tile cells (m, c) with c % 4 == kb and adds the entries of row r0 + m
+    // that fall into them in storage order: no atomics, duplicates add in one fixed order.  With
+    // ascending condensed columns in every row of the window (the usual case) a cursor per row walks
+    // each entry once; otherwise every chunk scans the whole row.
+    const int rb = row_ptr[min(n, r0 + m)], re = row_ptr[min(n, r0 + m + 1)];
+    bool ascending = true;
+    for (int e = rb + 1 + kb; e < re; e += 4) ascending = ascending && edge_to_col[e - 1] <= edge_to_col[e];
+    const bool cursor_mode = __builtin_amdgcn_ballot_w64(!ascending) == 0ull;
+    int cur = rb;
 
     float4v acc[NT];
 #pragma unroll
@@ -194,21 +193,46 @@ __global__ __launch_bounds__(64) void spmm_mfma_kernel(int n, const int *__restr
     for (int c0 = 0; c0 < uniq; c0 += 32) {
         for (int t = lane; t < 16 * 36; t += 64) (&As[0][0])[t] = 0.f;
         __syncthreads();
-        for (int e = e0 + lane; e < e1; e += 64) {
-            const int cc = edge_to_col[e] - c0;
-            if (cc >= 0 && cc < 32) atomicAdd(&As[edge_to_row[e] - r0][cc], (vals ? vals[e] : 1.f) * inv_scale);
+        if (cursor_mode) {
+            int e = cur;
+            for (; e < re; ++e) {
+                const int cc = edge_to_col[e] - c0;  // >= 0: earlier chunks took everything below c0
+                if (cc >= 32) break;
+                if ((cc & 3) == kb) As[m][cc] += vals ? vals[e] : 1.f;
+            }
+            cur = e;
+        } else {
+            for (int e = rb; e < re; ++e) {
+                const int cc = edge_to_col[e] - c0;
+                if (cc >= 0 && cc < 32 && (cc & 3) == kb) As[m][cc] += vals ? vals[e] : 1.f;
+            }
         }
         for (int t = lane; t < 32 * pieces; t += 64) {
             const int k = t / pieces, piece = t % pieces;
             uint4 v = make_uint4(0u, 0u, 0u, 0u);
             if (c0 + k < uniq && piece * 8 < D)
                 v = *reinterpret_cast<const uint4 *>(X + static_cast<size_t>(win_cols[u0 + c0 + k]) * ldx + piece * 8);
-            *reinterpret_cast<uint4 *>(&Xs[k * DP + piece * 8]) = v;
+            if constexpr (SPLIT_X) {
+                const uint32_t in[4] = {v.x, v.y, v.z, v.w};
+                uint32_t h[4], l[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    uint32_t h0, l0, h1, l1;
+                    split_bf16_pair(f16_bits_to_f32(in[j] & 0xffffu), h0, l0);
+                    split_bf16_pair(f16_bits_to_f32(in[j] >> 16), h1, l1);
+                    h[j] = h0 | (h1 << 16);
+                    l[j] = l0 | (l1 << 16);
+                }
+                *reinterpret_cast<uint4 *>(&Xs[k * DP + piece * 8]) = make_uint4(h[0], h[1], h[2], h[3]);
+                *reinterpret_cast<uint4 *>(&Xlo[k * DP + piece * 8]) = make_uint4(l[0], l[1], l[2], l[3]);
+            } else {
+                *reinterpret_cast<uint4 *>(&Xs[k * DP + piece * 8]) = v;
+            }
         }
         __syncthreads();
         uint32_t hi[8], lo[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) split_hi_lo<T>(As[m][kb * 8 + j], hi[j], lo[j]);
+        for (int j = 0; j < 8; ++j) split_bf16_pair(As[m][kb * 8 + j], hi[j], lo[j]);
         const uint4 ahi = make_uint4(hi[0] | (hi[1] << 16), hi[2] | (hi[3] << 16), hi[4] | (hi[5] << 16),
                                      hi[6] | (hi[7] << 16));
         const uint4 alo = make_uint4(lo[0] | (lo[1] << 16), lo[2] | (lo[3] << 16), lo[4] | (lo[5] << 16),
@@ -220,8 +244,15 @@ __global__ __launch_bounds__(64) void spmm_mfma_kernel(int n, const int *__restr
             for (int j = 0; j < 8; ++j) x[j] = Xs[(kb * 8 + j) * DP + t * 16 + m];
             const uint4 b = make_uint4(x[0] | (x[1] << 16), x[2] | (x[3] << 16), x[4] | (x[5] << 16),
                                        x[6] | (x[7] << 16));
-            acc[t] = mfma16x16x32<T>(ahi, b, acc[t]);
-            acc[t] = mfma16x16x32<T>(alo, b, acc[t]);
+            acc[t] = mfma16x16x32<BF16>(alo, b, acc[t]);
+            if constexpr (SPLIT_X) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) x[j] = Xlo[(kb * 8 + j) * DP + t * 16 + m];
+                const uint4 bl = make_uint4(x[0] | (x[1] << 16), x[2] | (x[3] << 16), x[4] | (x[5] << 16),
+                                            x[6] | (x[7] << 16));
+                acc[t] = mfma16x16x32<BF16>(ahi, bl, acc[t]);
+            }
+            acc[t] = mfma16x16x32<BF16>(ahi, b, acc[t]);
         }
         __syncthreads();
     }
@@ -231,10 +262,8 @@ __global__ __launch_bounds__(64) void spmm_mfma_kernel(int n, const int *__restr
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int row = r0 + kb * 4 + i;
-            if (row < n && col < D) {
-                const float v = acc[t][i] * scale;
-                store_elem(out, static_cast<int64_t>(row) * ldo + col, odt, epi.apply(epi.factor(row), v));
-            }
+            if (row < n && col < D)
+                store_elem(out, static_cast<int64_t>(row) * ldo + col, odt, epi.apply(epi.factor(row), acc[t][i]));
         }
     }
 }
@@ -284,12 +313,12 @@ int32_t launch_spmm_mfma(const ftc_csr &g, const ftc_windows &w, const float *va
     case N:                                                                                                    \
         if (dt == FTC_F16)                                                                                     \
             hipLaunchKernelGGL((spmm_mfma_kernel<F16, N>), dim3(w.n_windows), dim3(64), 0, s, g.n, g.row_ptr,  \
-                               w.edge_to_row, w.edge_to_col, w.win_col_ptr, w.win_cols, vals, x, ldx, D, out,  \
-                               ldo, odt, epi, flags);                                              \
+                               w.edge_to_col, w.win_col_ptr, w.win_cols, vals, x, ldx, D, out, ldo, odt, epi, \
+                               flags);                                                                         \
         else                                                                                                   \
             hipLaunchKernelGGL((spmm_mfma_kernel<BF16, N>), dim3(w.n_windows), dim3(64), 0, s, g.n, g.row_ptr, \
-                               w.edge_to_row, w.edge_to_col, w.win_col_ptr, w.win_cols, vals, x, ldx, D, out,  \
-                               ldo, odt, epi, flags);                                              \
+                               w.edge_to_col, w.win_col_ptr, w.win_cols, vals, x, ldx, D, out, ldo, odt, epi, \
+                               flags);                                                                         \
         break;
     switch (nt) {
         FTC_PM(1) FTC_PM(2) FTC_PM(3) FTC_PM(4) FTC_PM(6) FTC_PM(8) FTC_PM(12) FTC_PM(16)

@@ -12,6 +12,7 @@ from paper_2412_12218_amd import binding as B
 pytestmark = pytest.mark.gpu
 
 F32, F16, BF16 = torch.float32, torch.float16, torch.bfloat16
+P_TOL = 1e-5     # attention probabilities, relative, whatever the input type (the inputs are exact on both sides)
 
 
 def say(msg):
@@ -269,6 +270,70 @@ def test_spmm_paths(oracle, graphs, name, dtype, D, path):
         assert run_spmm(oracle, g, dtype, D, path=path, relu=True, out_dtype=F16) < TOL[dtype]
 
 
+@pytest.mark.parametrize("name", ["mixed", "hub", "cfg5s"])
+@pytest.mark.parametrize("dtype,D", [(F16, 32), (BF16, 64), (F16, 8), (BF16, 128)])
+def test_spmm_mfma_values_of_very_different_size_in_one_tile(oracle, graphs, name, dtype, D):
+    """Forced matrix-core path with edge values from 1 down to 2^-60 inside every window, features that are
+    exactly zero half of the time (as after a ReLU: an output element may then consist of small terms only)
+    and, on `hub`, duplicate entries and unsorted rows.  Every element keeps the bar relative to its own
+    terms, and two runs agree bit for bit."""
+    g = graphs[name]
+    rng = np.random.default_rng(77)
+    X32 = rng.uniform(-1, 1, size=(g.n, D)).astype(np.float32)
+    X32[rng.random((g.n, D)) < 0.5] = 0.0
+    Xd, X64 = quantise(X32, dtype)
+    mag = np.exp2(-rng.integers(0, 61, size=g.nnz).astype(np.float64))
+    vals32 = (mag * rng.uniform(0.5, 1.0, size=g.nnz) * rng.choice([-1.0, 1.0], g.nnz)).astype(np.float32)
+    ref, ab = oracle.spmm(g.row_ptr, g.col_idx, vals32.astype(np.float64), X64)
+    dg = dev_graph(g)
+    win = B.ftc_build_windows(dg)
+    vd = torch.from_numpy(vals32).cuda()
+    out = B.ftc_spmm(dg, win, vd, Xd, path=B.FTC_PATH_MFMA)
+    out2 = B.ftc_spmm(dg, win, vd, Xd, path=B.FTC_PATH_MFMA)
+    assert torch.equal(out, out2)
+    err = norm_err(out, ref, ab)
+    say(f"spmm mfma wide-range values {name} {dtype} D={D} err {err:.3e}")
+    assert err < TOL[dtype]
+
+
+@pytest.mark.parametrize("name", ["mixed", "hub"])
+@pytest.mark.parametrize("dtype,D", [(F16, 32), (BF16, 64)])
+@pytest.mark.parametrize("beta", [50.0, -50.0, 8.0])
+def test_agnn_layer_on_the_matrix_core_path_with_a_large_beta(oracle, graphs, name, dtype, D, beta):
+    """The unfused chain with both sparse products forced onto the matrix cores; at |beta| = 50 the
+    probabilities of one window span more than forty orders of magnitude."""
+    g = graphs[name]
+    Hd, H64 = quantise(synth.normal_features(g.n, D, seed=13), dtype)
+    ref, ab, pref = oracle.agnn_layer(g.row_ptr, g.col_idx, H64, beta)
+    dg = dev_graph(g)
+    win = B.ftc_build_windows(dg)
+    p = torch.empty(g.nnz, dtype=F32, device="cuda")
+    out = B.ftc_agnn_layer(dg, win, Hd, beta=beta, edge_p=p, path=B.FTC_PATH_MFMA)
+    err = norm_err(out, ref, ab)
+    say(f"agnn mfma {name} {dtype} D={D} beta={beta} err {err:.3e}")
+    assert err < TOL[dtype]
+
+
+def test_cfg1_as_written(oracle):
+    """The first benchmark configuration literally: the normalised adjacency from the normalisation call goes
+    into the aggregation; Erdos-Renyi graph of 2048 nodes, X fp32 2048 x 16 uniform[-1, 1], seed 0; bar 1e-5."""
+    g = synth.config_graph(1)
+    assert g.n == 2048
+    X32 = synth.uniform_features(g.n, 16, seed=0)
+    vals64, _ = oracle.gcn_norm(g.row_ptr, g.col_idx)
+    ref, ab = oracle.spmm(g.row_ptr, g.col_idx, vals64.astype(np.float32).astype(np.float64), X32.astype(np.float64))
+    ref64, _ = oracle.spmm(g.row_ptr, g.col_idx, vals64, X32.astype(np.float64))
+    dg = dev_graph(g)
+    Xd = torch.from_numpy(X32).cuda()
+    for win in (B.ftc_build_windows(dg), None):
+        vals, _ = B.ftc_gcn_norm(dg, win)
+        out = B.ftc_spmm(dg, win, vals, Xd)
+        err = norm_err(out, ref, ab)
+        err64 = norm_err(out, ref64, ab)        # against the chain that never rounds the edge values
+        say(f"cfg1 as written, windows={win is not None}: err {err:.3e} (unrounded values: {err64:.3e})")
+        assert err < 1e-5 and err64 < 1e-5
+
+
 def test_mfma_path_rejected_where_it_cannot_run(graphs):
     g = graphs["cfg1"]
     dg = dev_graph(g)
@@ -511,7 +576,9 @@ def test_gcn_layer_with_a_wide_input(oracle, graphs):
     dg = dev_graph(g)
     win = B.ftc_build_windows(dg)
     out = B.ftc_gcn_layer(dg, win, torch.from_numpy(vals32).cuda(), Xd, Wd, relu=True)
-    assert norm_err(out, ref, ab) < 2 * TOL[F16]
+    err = norm_err(out, ref, ab)
+    say(f"gcn_layer wide input err {err:.3e}")
+    assert err < TOL[F16]
 
 
 @pytest.mark.parametrize("name,dtype,d_in,d_out", [("cfg1", F32, 16, 16), ("cfg2s", F16, 128, 32),
@@ -617,7 +684,7 @@ def test_agnn_layer(oracle, graphs, name, dtype, D, beta):
     perr = rel_err(p, pref)
     say(f"  unfused err {err:.3e} p err {perr:.3e}")
     assert err < TOL[dtype]
-    assert perr < (1e-4 if dtype == F32 else 2e-3)
+    assert perr < P_TOL
     out2 = B.ftc_agnn_layer(dg, win, Hd, beta=beta)      # fused: no P output
     err2 = norm_err(out2, ref, ab)
     say(f"  fused err {err2:.3e}")
@@ -740,7 +807,9 @@ def test_spmm_sddmm_agnn_random_shapes(oracle, case):
     Hn = H64 / np.maximum(np.sqrt((H64 * H64).sum(axis=1)), 1e-12)[:, None]
     sref, sab = oracle.sddmm(g.row_ptr, g.col_idx, Hn, Hn)
     s = B.ftc_sddmm(dg, win, Hd, Hd, cosine=True)
-    assert float(np.max(np.abs(s.cpu().double().numpy() - sref))) < (1e-5 if dtype == F32 else 4e-3)
+    serr = norm_err(s, sref, sab)
+    say(f"  cosine sddmm err {serr:.3e}")
+    assert serr < TOL[dtype]
 
 
 def test_spmm_narrow_rows_at_slot_and_wave_boundaries(oracle):
@@ -757,8 +826,7 @@ def test_spmm_narrow_rows_at_slot_and_wave_boundaries(oracle):
     for dtype, D in ((F16, 8), (F16, 16), (F32, 4), (F32, 8), (BF16, 5)):
         pad = (-D) % (4 if dtype == F32 else 8)
         say(f"boundaries {dtype} D={D}")
-        # n is tiny, so every column repeats hundreds of times in the long rows: fp32 sums of equal
-        # terms drift by a rounding error per term, hence the looser bar for fp32 here
-        tol = 1e-4 if dtype == F32 else TOL[dtype]
-        assert run_spmm(oracle, g, dtype, D, pad=pad) < tol
-        assert run_spmm(oracle, g, dtype, D, pad=pad, use_vals=False) < tol
+        e1 = run_spmm(oracle, g, dtype, D, pad=pad)
+        e2 = run_spmm(oracle, g, dtype, D, pad=pad, use_vals=False)
+        say(f"  err {e1:.3e} {e2:.3e}")
+        assert e1 < TOL[dtype] and e2 < TOL[dtype]
