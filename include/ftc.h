@@ -141,6 +141,23 @@ int32_t ftc_spmm(const ftc_csr *g, const ftc_windows *w, const float *vals, cons
                  size_t ws_bytes, void *stream);
 
 /*
+ * ftc_spmm for callers that cannot allocate device memory and have no workspace to pass: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid allocation.  Same arguments, same
+ * kernels and bit-identical results; the scratch memory is a buffer of FTC_NOALLOC_SCRATCH_MIB MiB
+ * built into the library (one copy per GPU, held until the process ends).  The call allocates and
+ * frees nothing.  FTC_EWORKSPACE when ftc_spmm_workspace_bytes(n, nnz, D) exceeds the buffer (about
+ * nnz * D > 4e9 with 16-bit features).  The device that `stream` belongs to must be current.  All
+ * calls on one GPU share the buffer: calls that overlap in time on one GPU (different streams, or
+ * several host threads) race; calls in one stream are safe.  Nothing in the buffer has to be zero and
+ * nothing is kept between calls.  The first call on a device looks up the buffer's address.
+ */
+#define FTC_NOALLOC_SCRATCH_MIB 64
+int32_t ftc_spmm_noalloc(const ftc_csr *g, const ftc_windows *w, const float *vals, const void *X,
+                         int32_t ldx, int32_t x_dtype, int32_t D, void *out, int32_t ldo,
+                         int32_t out_dtype, const float *out_scale, int32_t relu, int32_t path,
+                         void *stream);
+
+/*
  * Sparse edge feature computation (Section V.A; SDDMM D = A o (B x C) of Section I.A.2,
  * A taken as the 0/1 pattern), result laid out like col_idx (`EdgeValList`):
  *   edge_out[e] = alpha * row_scale[i] * col_scale[j] * sum_k X[i,k] * Y[j,k],

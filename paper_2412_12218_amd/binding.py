@@ -33,6 +33,7 @@ _SIGNATURES = {
     "ftc_gcn_norm": (_I, [_P, _P, _P, _P, _P]),
     "ftc_spmm_workspace_bytes": (_Z, [_I, _I, _I]),
     "ftc_spmm": (_I, [_P, _P, _P, _P, _I, _I, _I, _P, _I, _I, _P, _I, _I, _P, _Z, _P]),
+    "ftc_spmm_noalloc": (_I, [_P, _P, _P, _P, _I, _I, _I, _P, _I, _I, _P, _I, _I, _P]),
     "ftc_sddmm_workspace_bytes": (_Z, [_I, _I, _I]),
     "ftc_sddmm": (_I, [_P, _P, _P, _P, _I, _I, _I, _P, _P, _F, _I, _P, _I, _P, _Z, _P]),
     "ftc_row_rnorm": (_I, [_I, _P, _I, _I, _I, _P, _P]),
@@ -205,6 +206,16 @@ def ftc_spmm(g, w, vals, X, out=None, out_dtype=torch.float32, relu=False, path=
                           C.c_int32(_dt(X)), C.c_int32(D), _ptr(out), C.c_int32(out.stride(0)),
                           C.c_int32(_dt(out)), _ptr(out_scale), C.c_int32(1 if relu else 0), C.c_int32(path),
                           _ptr(ws), C.c_size_t(ws.numel()), _stream()))
+    return out
+
+
+def ftc_spmm_noalloc(g, w, vals, X, out, relu=False, path=FTC_PATH_AUTO, out_scale=None):
+    """ftc_spmm on the library's built-in scratch buffer; `out` is the caller's (nothing is allocated here)."""
+    D = X.shape[1]
+    _check(lib().ftc_spmm_noalloc(C.byref(g.c), _wref(w), _ptr(vals), _ptr(X), C.c_int32(X.stride(0)),
+                                  C.c_int32(_dt(X)), C.c_int32(D), _ptr(out), C.c_int32(out.stride(0)),
+                                  C.c_int32(_dt(out)), _ptr(out_scale), C.c_int32(1 if relu else 0), C.c_int32(path),
+                                  _stream()))
     return out
 
 

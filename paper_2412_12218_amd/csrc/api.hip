@@ -2,6 +2,7 @@
 // contract of every entry point.
 #include <cstdarg>
 #include <cstdio>
+#include <mutex>
 
 #include "ftc_common.hpp"
 
@@ -188,6 +189,60 @@ int32_t ftc_spmm(const ftc_csr *g, const ftc_windows *w, const float *vals, cons
     }
     return launch_spmm_rows(*g, vals, X, ldx, x_dtype, D, out, ldo, out_dtype, epi,
                             static_cast<hipStream_t>(stream));
+}
+
+// ftc_spmm for callers that can neither allocate nor hand over a workspace: the scratch memory of the
+// aggregation kernels (carry rows of the cut rows, window flags) lives in this file-scope device array,
+// one copy per GPU, held until the process ends.  In host code the array's name is only a stand-in; its
+// device address is asked for once per device and kept.
+}  // extern "C"
+namespace {
+constexpr size_t NOALLOC_SCRATCH_BYTES = static_cast<size_t>(FTC_NOALLOC_SCRATCH_MIB) << 20;
+static __device__ __align__(256) unsigned char scratch[NOALLOC_SCRATCH_BYTES];
+constexpr int NOALLOC_MAX_DEVICES = 64;
+void *g_scratch_ptr[NOALLOC_MAX_DEVICES];  // device address of `scratch` on every device that has asked
+std::mutex g_scratch_mutex;
+
+int32_t scratch_of_current_device(void **ptr)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= NOALLOC_MAX_DEVICES) {
+        (void)hipGetLastError();
+        return fail(FTC_EHIP, "ftc_spmm_noalloc: no current device (or a device index beyond %d)", NOALLOC_MAX_DEVICES - 1);
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return fail(FTC_EHIP, "ftc_spmm_noalloc: hipGetSymbolAddress failed (%d: %s)", static_cast<int>(e),
+                        hipGetErrorString(e));
+        }
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return FTC_OK;
+}
+}  // namespace
+extern "C" {
+
+int32_t ftc_spmm_noalloc(const ftc_csr *g, const ftc_windows *w, const float *vals, const void *X, int32_t ldx,
+                         int32_t x_dtype, int32_t D, void *out, int32_t ldo, int32_t out_dtype, const float *out_scale,
+                         int32_t relu, int32_t path, void *stream)
+{
+    FTC_TRY(check_csr(g, "ftc_spmm_noalloc"));
+    if (D < 1) return fail(FTC_EINVAL, "ftc_spmm_noalloc: need D >= 1");
+    const size_t need = ftc_spmm_workspace_bytes(g->n, g->nnz, D);
+    if (need > NOALLOC_SCRATCH_BYTES)
+        return fail(FTC_EWORKSPACE,
+                    "ftc_spmm_noalloc: this graph and width need %zu bytes of scratch memory, the built-in buffer holds "
+                    "%zu; use ftc_spmm with a workspace",
+                    need, NOALLOC_SCRATCH_BYTES);
+    void *ptr = nullptr;
+    FTC_TRY(scratch_of_current_device(&ptr));
+    return ftc_spmm(g, w, vals, X, ldx, x_dtype, D, out, ldo, out_dtype, out_scale, relu, path, ptr, NOALLOC_SCRATCH_BYTES,
+                    stream);
 }
 
 size_t ftc_sddmm_workspace_bytes(int32_t n, int32_t nnz, int32_t D)
