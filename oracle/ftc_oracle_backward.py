@@ -115,3 +115,73 @@ def agnn_layer_backward(row_ptr, col_idx, H, beta, dY):
     proj[clamped] = 0.0
     dH += rinv[:, None] * (dHn - Hn * proj[:, None])
     return dH, dbeta
+
+
+# ---- error denominators -------------------------------------------------------------------------------
+# The forward oracle returns, next to every sum, the sum of the absolute values of its terms: the
+# yardstick an fp32 evaluation is measured against (a result that is small only because its terms
+# cancel is not held to its own size).  The functions below give the same yardstick for the gradients:
+# the backward formulas above evaluated with every factor replaced by its absolute value and every
+# subtraction by an addition, carried through the chain (a running bound of the terms).  `dY_terms`
+# is the yardstick of the incoming gradient when that is itself a computed quantity (a layer stack);
+# by default the incoming gradient is exact data and its yardstick is |dY|.
+
+def gcn_layer_backward_terms(row_ptr, col_idx, vals, X, W, dY, Y=None, dY_terms=None):
+    """Yardsticks (dX_terms, dW_terms, dZ_terms) of gcn_layer_backward's three results."""
+    col = np.asarray(col_idx, dtype=np.int64)
+    rows = _rows(row_ptr)
+    vals = np.ones(col.size) if vals is None else np.abs(np.asarray(vals, dtype=np.float64))
+    X, W = np.abs(np.asarray(X, dtype=np.float64)), np.abs(np.asarray(W, dtype=np.float64))
+    dP = np.abs(np.asarray(dY, dtype=np.float64)) if dY_terms is None else np.asarray(dY_terms, dtype=np.float64)
+    if Y is not None:
+        dP = dP * (np.asarray(Y, dtype=np.float64) > 0)
+    dZ = np.zeros_like(dP)
+    np.add.at(dZ, col, vals[:, None] * dP[rows])
+    return dZ @ W.T, X.T @ dZ, dZ
+
+
+def update_gemm_backward_terms(X, W, dZ, Z=None, dZ_terms=None):
+    """Yardsticks (dX_terms, dW_terms) of update_gemm_backward's two results."""
+    X, W = np.abs(np.asarray(X, dtype=np.float64)), np.abs(np.asarray(W, dtype=np.float64))
+    dP = np.abs(np.asarray(dZ, dtype=np.float64)) if dZ_terms is None else np.asarray(dZ_terms, dtype=np.float64)
+    if Z is not None:
+        dP = dP * (np.asarray(Z, dtype=np.float64) > 0)
+    return dP @ W.T, X.T @ dP
+
+
+def agnn_layer_backward_terms(row_ptr, col_idx, H, beta, dY, dY_terms=None):
+    """Yardsticks (dH_terms [n, D], dbeta_terms) of agnn_layer_backward's two results."""
+    row_ptr = np.asarray(row_ptr, dtype=np.int64)
+    col = np.asarray(col_idx, dtype=np.int64)
+    rows = _rows(row_ptr)
+    H = np.asarray(H, dtype=np.float64)
+    aY = np.abs(np.asarray(dY, dtype=np.float64)) if dY_terms is None else np.asarray(dY_terms, dtype=np.float64)
+    n = H.shape[0]
+    nrm = np.sqrt((H * H).sum(axis=1))
+    clamped = nrm <= 1e-12
+    rinv = 1.0 / np.maximum(nrm, 1e-12)
+    Hn = H * rinv[:, None]
+    aH, aHn = np.abs(H), np.abs(Hn)
+    c = (Hn[rows] * Hn[col]).sum(axis=1)
+    c_terms = (aHn[rows] * aHn[col]).sum(axis=1)
+    s = beta * c
+    m = np.full(n, -np.inf)
+    np.maximum.at(m, rows, s)
+    ex = np.exp(s - m[rows])
+    z = np.zeros(n)
+    np.add.at(z, rows, ex)
+    p = ex / z[rows]                                        # positive: its own yardstick
+    dp_terms = (aY[rows] * aH[col]).sum(axis=1)
+    t_terms = np.zeros(n)
+    np.add.at(t_terms, rows, p * dp_terms)
+    ds_terms = p * (dp_terms + t_terms[rows])
+    dbeta_terms = float((ds_terms * c_terms).sum())
+    dHn_terms = np.zeros_like(H)
+    np.add.at(dHn_terms, rows, abs(beta) * ds_terms[:, None] * aHn[col])
+    np.add.at(dHn_terms, col, abs(beta) * ds_terms[:, None] * aHn[rows])
+    proj_terms = (aHn * dHn_terms).sum(axis=1)
+    proj_terms[clamped] = 0.0
+    dH_terms = np.zeros_like(H)
+    np.add.at(dH_terms, col, p[:, None] * aY[rows])
+    dH_terms += rinv[:, None] * (dHn_terms + aHn * proj_terms[:, None])
+    return dH_terms, dbeta_terms

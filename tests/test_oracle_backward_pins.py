@@ -205,3 +205,54 @@ def test_update_gemm_backward_against_finite_differences(oracle, relu):
         Wp[a, b] += eps
         Wm[a, b] -= eps
         assert dW[a, b] == pytest.approx((loss(X, Wp) - loss(X, Wm)) / (2 * eps), rel=1e-6, abs=1e-8)
+
+
+# ---- the yardsticks (sums of absolute terms) of the gradients --------------------------------------
+def test_agnn_backward_terms_single_node_closed_form():
+    """One node with a self-loop, h = (3, 4), dY = (1, -2), beta = 2, worked by hand: |h| = 5,
+    hn = (0.6, 0.8), p = 1, sum |dY h| = 11 (twice: once as dp, once as the row sum), so the terms of
+    ds add up to 22 and those of dbeta to 22 * 1; the terms of dhn are 2 * 22 * hn from each of the two
+    roles of the loop, (52.8, 70.4), their projection onto |hn| is 88, and
+    dH_terms = |dY| + (dhn_terms + |hn| * 88) / 5 = (22.12, 30.16)."""
+    rp, ci = np.array([0, 1]), np.array([0])
+    H, dY = np.array([[3.0, 4.0]]), np.array([[1.0, -2.0]])
+    terms, dbeta_terms = ob.agnn_layer_backward_terms(rp, ci, H, 2.0, dY)
+    assert np.allclose(terms, [[22.12, 30.16]], rtol=1e-12)
+    assert abs(dbeta_terms - 22.0) < 1e-12
+    dH, dbeta = ob.agnn_layer_backward(rp, ci, H, 2.0, dY)
+    assert np.allclose(dH, dY) and abs(dbeta) < 1e-15        # softmax of one entry: only the aggregated part is left
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_backward_terms_bound_the_gradients_and_scale_with_them(oracle, seed):
+    """Triangle inequality: every yardstick is at least the size of the value it belongs to; it does not
+    change when the incoming gradient changes sign and scales with its size; with non-negative data and
+    no subtraction in the chain (GCN without ReLU) it equals the value."""
+    g = small_graph(seed, symmetric=bool(seed & 1))
+    rng = np.random.default_rng(30 + seed)
+    H = rng.standard_normal((g.n, 4))
+    dY = rng.standard_normal((g.n, 4))
+    dH, dbeta = ob.agnn_layer_backward(g.row_ptr, g.col_idx, H, -1.7, dY)
+    tH, tb = ob.agnn_layer_backward_terms(g.row_ptr, g.col_idx, H, -1.7, dY)
+    assert np.all(tH >= np.abs(dH) * (1 - 1e-12)) and tb >= abs(dbeta)
+    tH2, tb2 = ob.agnn_layer_backward_terms(g.row_ptr, g.col_idx, H, -1.7, -3.0 * dY)
+    assert np.allclose(tH2, 3.0 * tH, rtol=1e-12) and np.isclose(tb2, 3.0 * tb, rtol=1e-12)
+    # an incoming yardstick larger than |dY| gives larger yardsticks (it is carried through linearly)
+    tH3, _ = ob.agnn_layer_backward_terms(g.row_ptr, g.col_idx, H, -1.7, dY, dY_terms=2.0 * np.abs(dY))
+    assert np.allclose(tH3, 2.0 * tH, rtol=1e-12)
+
+    vals = rng.uniform(-1.0, 1.0, g.nnz)
+    X, W, R = rng.standard_normal((g.n, 5)), rng.standard_normal((5, 3)), rng.standard_normal((g.n, 3))
+    Y, _ = oracle.gcn_layer(g.row_ptr, g.col_idx, vals, X, W, relu=True)
+    dX, dW, dZ = ob.gcn_layer_backward(g.row_ptr, g.col_idx, vals, X, W, R, Y)
+    tX, tW, tZ = ob.gcn_layer_backward_terms(g.row_ptr, g.col_idx, vals, X, W, R, Y)
+    for v, t in ((dX, tX), (dW, tW), (dZ, tZ)):
+        assert np.all(t >= np.abs(v) * (1 - 1e-12))
+    pos = [np.abs(a) for a in (vals, X, W, R)]
+    dXp, dWp, dZp = ob.gcn_layer_backward(g.row_ptr, g.col_idx, *pos)
+    tXp, tWp, tZp = ob.gcn_layer_backward_terms(g.row_ptr, g.col_idx, *pos)
+    assert np.allclose(dXp, tXp, rtol=1e-12) and np.allclose(dWp, tWp, rtol=1e-12) and np.allclose(dZp, tZp, rtol=1e-12)
+    dXu, dWu = ob.update_gemm_backward(X, W, R, Y)
+    tXu, tWu = ob.update_gemm_backward_terms(X, W, R, Y)
+    assert np.all(tXu >= np.abs(dXu) * (1 - 1e-12)) and np.all(tWu >= np.abs(dWu) * (1 - 1e-12))
+    assert np.allclose(ob.update_gemm_backward_terms(pos[1], pos[2], pos[3])[1], pos[1].T @ pos[3], rtol=1e-12)
