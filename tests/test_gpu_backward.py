@@ -1,12 +1,12 @@
 """GPU parity of the backward pass: every backward entry point of libftc, called through the C
 ABI, against the fp64 backward oracle on the same seeded inputs.
 
-Integer outputs (the transposed index) are bit-exact.  A gradient element is compared as
-|gpu - ref| / (max |ref| over its row + 0.01 * max |ref| over the array) for per-node gradients and
-|gpu - ref| / max |ref| for the small dense ones (dW, dbeta), and must stay below 1e-5 for every
-input type: the oracle gets the rounded 16-bit inputs exactly and every intermediate of the backward
-pass is fp32.  (A gradient is a difference of sums that nearly cancel in places, the softmax backward
-above all, so single elements are not compared relative to themselves.)"""
+Integer outputs (the transposed index) are bit-exact.  A gradient element is compared the way the
+forward results are: |gpu - ref| / (sum of the absolute values of the terms it is made of), the
+backward oracle's `*_terms` functions giving that sum for every element, and must stay below 1e-5 for
+every input type: the oracle gets the rounded 16-bit inputs exactly and every intermediate of the
+backward pass is fp32.  A chain of layers is held to the same bar, against terms carried through the
+chain."""
 import numpy as np
 import pytest
 import scipy.sparse as sp
@@ -27,23 +27,13 @@ def say(msg):
     print(msg, flush=True)
 
 
-def row_err(got, ref, cancelled=None):
-    """Largest error of a row relative to the row's largest reference value plus 1 % of the overall largest.
-    cancelled[i], if given, is the size of the terms that cancel inside row i's result before they reach it:
-    eight fp32 roundings (2^-24 each) of them are allowed on top of a 1e-5 bar."""
-    got = got.detach().cpu().double().numpy()
+def term_err(got, ref, terms):
+    """max |got - ref| / terms, elementwise; where no term contributes the result must be exactly zero."""
+    got = got.detach().cpu().double().numpy() if torch.is_tensor(got) else np.asarray(got, dtype=np.float64)
     assert np.all(np.isfinite(got))
-    scale = np.abs(ref).max(axis=1, keepdims=True) + 0.01 * np.abs(ref).max()
-    if cancelled is not None:
-        scale = scale + (8 * 2.0 ** -24 / 1e-5) * np.asarray(cancelled).reshape(-1, 1)
-    return float(np.max(np.abs(got - ref) / np.where(scale > 0, scale, 1.0))) if ref.size else 0.0
-
-
-def arr_err(got, ref):
-    got = got.detach().cpu().double().numpy()
-    assert np.all(np.isfinite(got))
-    m = np.abs(ref).max() if ref.size else 0.0
-    return float(np.max(np.abs(got - ref)) / (m if m > 0 else 1.0)) if ref.size else 0.0
+    terms = np.broadcast_to(terms, ref.shape)
+    assert np.all(got[terms == 0] == 0)
+    return float(np.max(np.abs(got - ref) / np.where(terms > 0, terms, 1.0))) if ref.size else 0.0
 
 
 def directed_graph(n, m, seed):
@@ -197,8 +187,11 @@ def test_update_gemm_backward_wide_input(dtype, d_in, d_out):
     dZ32 = synth.normal_features(n, d_out, seed=3).astype(np.float32)
     Z = B.ftc_update_gemm(Xd, Wd, relu=True, out_dtype=dtype)
     dX_ref, dW_ref = OB.update_gemm_backward(X64, W64, dZ32.astype(np.float64), Z.cpu().double().numpy())
+    tX, tW = OB.update_gemm_backward_terms(X64, W64, dZ32.astype(np.float64), Z.cpu().double().numpy())
     dX, dW = B.ftc_update_gemm_backward(Xd, Wd, torch.from_numpy(dZ32).cuda(), Z=Z)
-    assert row_err(dX, dX_ref) < 1e-5 and arr_err(dW, dW_ref) < 1e-5
+    ex, ew = term_err(dX, dX_ref, tX), term_err(dW, dW_ref, tW)
+    say(f"update_gemm_backward wide {dtype} {d_in}->{d_out}: dX err {ex:.3e} dW err {ew:.3e}")
+    assert ex < 1e-5 and ew < 1e-5
 
 
 @pytest.mark.parametrize("dtype,d_in,d_out", [(F16, 64, 128), (F32, 40, 72)])
@@ -215,8 +208,12 @@ def test_gcn_layer_backward_wide_hidden(oracle, graphs, dtype, d_in, d_out):
     Y = B.ftc_gcn_layer(dg, win, vd, Xd, Wd, relu=True)
     dX_ref, dW_ref, _ = OB.gcn_layer_backward(g.row_ptr, g.col_idx, vals32.astype(np.float64), X64, W64,
                                               dY32.astype(np.float64), Y.cpu().double().numpy())
+    tX, tW, _ = OB.gcn_layer_backward_terms(g.row_ptr, g.col_idx, vals32.astype(np.float64), X64, W64,
+                                            dY32.astype(np.float64), Y.cpu().double().numpy())
     dX, dW = B.ftc_gcn_layer_backward(dg, win, vd, Xd, Wd, torch.from_numpy(dY32).cuda(), Y=Y)
-    assert row_err(dX, dX_ref) < 1e-5 and arr_err(dW, dW_ref) < 1e-5
+    ex, ew = term_err(dX, dX_ref, tX), term_err(dW, dW_ref, tW)
+    say(f"gcn_layer_backward wide hidden {dtype}: dX err {ex:.3e} dW err {ew:.3e}")
+    assert ex < 1e-5 and ew < 1e-5
 
 
 def test_weight_grad_strided_inputs():
@@ -225,8 +222,9 @@ def test_weight_grad_strided_inputs():
     Gf = torch.from_numpy(synth.normal_features(n, 16, seed=4).astype(np.float32)).cuda()
     X, G = Xf[:, :d_in], Gf[:, :d_out]
     ref = X.double().cpu().numpy().T @ G.double().cpu().numpy()
+    ab = X.double().abs().cpu().numpy().T @ G.double().abs().cpu().numpy()
     dW = B.ftc_weight_grad(X, G)
-    assert arr_err(dW, ref) < 1e-5
+    assert term_err(dW, ref, ab) < 1e-5
 
 
 # ------------------------------------------------------------------ dense update backward
@@ -240,9 +238,10 @@ def test_update_gemm_backward(n, dtype, d_in, d_out, relu):
     dZ32 = synth.normal_features(n, d_out, seed=3).astype(np.float32)
     Z = B.ftc_update_gemm(Xd, Wd, relu=True, out_dtype=dtype) if relu else None      # the mask is the layer's own output
     dX_ref, dW_ref = OB.update_gemm_backward(X64, W64, dZ32.astype(np.float64), Z.cpu().double().numpy() if relu else None)
+    tX, tW = OB.update_gemm_backward_terms(X64, W64, dZ32.astype(np.float64), Z.cpu().double().numpy() if relu else None)
     dZ = torch.from_numpy(dZ32).cuda()
     dX, dW = B.ftc_update_gemm_backward(Xd, Wd, dZ, Z=Z)
-    ex, ew = row_err(dX, dX_ref), arr_err(dW, dW_ref)
+    ex, ew = term_err(dX, dX_ref, tX), term_err(dW, dW_ref, tW)
     say(f"  dX err {ex:.3e} dW err {ew:.3e}")
     assert ex < 1e-5 and ew < 1e-5
     dX16, dW2 = B.ftc_update_gemm_backward(Xd, Wd, dZ, Z=Z, dx_dtype=F16)
@@ -291,12 +290,13 @@ def test_gcn_layer_backward(oracle, graphs, name, dtype, d_in, d_out, relu, fact
     else:
         dgT, winT, valsT_d = dg, win, vals_d
     dY = torch.from_numpy(dY32).cuda()
+    tX, tW, _ = OB.gcn_layer_backward_terms(g.row_ptr, g.col_idx, vals_ref, X64, W64, dY32.astype(np.float64), Y64)
     dX, dW = B.ftc_gcn_layer_backward(dgT, winT, valsT_d, Xd, Wd, dY, Y=Y, dinv=dinv_d)
-    ex, ew = row_err(dX, dX_ref), arr_err(dW, dW_ref)
+    ex, ew = term_err(dX, dX_ref, tX), term_err(dW, dW_ref, tW)
     say(f"  dX err {ex:.3e} dW err {ew:.3e}")
     assert ex < GTOL[dtype] and ew < GTOL[dtype]
     dX2, dW2 = B.ftc_gcn_layer_backward(dgT, None, valsT_d, Xd, Wd, dY, Y=Y, dinv=dinv_d)   # row kernels
-    assert row_err(dX2, dX_ref) < GTOL[dtype] and arr_err(dW2, dW_ref) < GTOL[dtype]
+    assert term_err(dX2, dX_ref, tX) < GTOL[dtype] and term_err(dW2, dW_ref, tW) < GTOL[dtype]
     none, dW3 = B.ftc_gcn_layer_backward(dgT, winT, valsT_d, Xd, Wd, dY, Y=Y, dinv=dinv_d, want_dX=False)
     assert none is None and torch.equal(dW3, dW)
 
@@ -313,6 +313,7 @@ def test_agnn_layer_backward(graphs, name, dtype, D, beta):
     Hd, H64 = quantise(synth.normal_features(g.n, D, seed=11), dtype)
     dYd, dY64 = quantise(synth.normal_features(g.n, D, seed=14), dtype)
     dH_ref, dbeta_ref = OB.agnn_layer_backward(g.row_ptr, g.col_idx, H64, beta, dY64)
+    tH, tb = OB.agnn_layer_backward_terms(g.row_ptr, g.col_idx, H64, beta, dY64)
     dg = dev_graph(g)
     win = B.ftc_build_windows(dg)
     T, flag = B.ftc_transpose_index(dg, win)
@@ -320,14 +321,14 @@ def test_agnn_layer_backward(graphs, name, dtype, D, beta):
     p = torch.empty(g.nnz, dtype=F32, device="cuda")
     B.ftc_agnn_layer(dg, win, Hd, beta=beta, edge_p=p)       # forward pass keeps its probabilities
     dH, dbeta = B.ftc_agnn_layer_backward(dg, win, T, Hd, p, dYd, beta=beta)
-    eh = row_err(dH, dH_ref)
-    # dbeta sums nnz signed terms ds_e c_e: compare against the size of a typical partial sum
-    db = abs(float(dbeta.item()) - dbeta_ref)
-    say(f"  dH err {eh:.3e} dbeta {float(dbeta.item()):.6g} ref {dbeta_ref:.6g} diff {db:.2e}")
+    eh = term_err(dH, dH_ref, tH)
+    db = abs(float(dbeta.item()) - dbeta_ref) / tb
+    say(f"  dH err {eh:.3e} dbeta {float(dbeta.item()):.6g} ref {dbeta_ref:.6g} err {db:.2e}")
     assert eh < GTOL[dtype]
-    assert db < 1e-4 * max(abs(dbeta_ref), np.sqrt(g.n) * 1e-2)     # a sum of nnz signed fp32 terms
+    assert db < 1e-5
     dH2, dbeta2 = B.ftc_agnn_layer_backward(dg, None, T, Hd, p, dYd, beta=beta)      # row kernels
-    assert row_err(dH2, dH_ref) < GTOL[dtype]
+    assert term_err(dH2, dH_ref, tH) < GTOL[dtype]
+    assert abs(float(dbeta2.item()) - dbeta_ref) / tb < 1e-5
     dH3, dbeta3 = B.ftc_agnn_layer_backward(dg, win, T, Hd, p, dYd, beta=beta)
     assert torch.equal(dH, dH3) and torch.equal(dbeta, dbeta3)
 
@@ -351,15 +352,16 @@ def test_agnn_forward_row_z_and_fused_backward(oracle, graphs, name, dtype, D, b
     z_ref = OB.agnn_row_z(g.row_ptr, g.col_idx, H64, beta)
     ez = float(np.max(np.abs(row_z.cpu().double().numpy() - z_ref) / np.maximum(z_ref, 1e-300)))
     say(f"  row_z err {ez:.3e}")
-    assert ez < (1e-5 if dtype == F32 else 1e-4)
+    assert ez < 1e-5
     assert torch.equal(Y, B.ftc_agnn_layer(dg, win, Hd, beta=beta))    # the extra output changes nothing
     dH_ref, dbeta_ref = OB.agnn_layer_backward(g.row_ptr, g.col_idx, H64, beta, dY64)
+    tH, tb = OB.agnn_layer_backward_terms(g.row_ptr, g.col_idx, H64, beta, dY64)
     dH, dbeta = B.ftc_agnn_layer_backward_fused(dg, win, Hd, row_z, Y, dYd, beta=beta)
-    eh = row_err(dH, dH_ref)
-    db = abs(float(dbeta.item()) - dbeta_ref)
-    say(f"  dH err {eh:.3e} dbeta {float(dbeta.item()):.6g} ref {dbeta_ref:.6g} diff {db:.2e}")
+    eh = term_err(dH, dH_ref, tH)
+    db = abs(float(dbeta.item()) - dbeta_ref) / tb
+    say(f"  dH err {eh:.3e} dbeta {float(dbeta.item()):.6g} ref {dbeta_ref:.6g} err {db:.2e}")
     assert eh < GTOL[dtype]                                             # fp32 Y: the full-precision bar
-    assert db < 1e-4 * max(abs(dbeta_ref), np.sqrt(g.n) * 1e-2)
+    assert db < 1e-5
     dH2, dbeta2 = B.ftc_agnn_layer_backward_fused(dg, win, Hd, row_z, Y, dYd, beta=beta)
     assert torch.equal(dH, dH2) and torch.equal(dbeta, dbeta2)
     if dtype != F32:
@@ -399,10 +401,11 @@ def test_agnn_fused_backward_matches_the_unfused_route_on_hub_rows():
     Y = B.ftc_agnn_layer(dg, win, Hd, beta=2.0, row_z=row_z)
     dH_f, db_f = B.ftc_agnn_layer_backward_fused(dg, win, Hd, row_z, Y, dYd, beta=2.0)
     dH_ref, db_ref = OB.agnn_layer_backward(g.row_ptr, g.col_idx, H64, 2.0, dY64)
-    eu, ef = row_err(dH_u, dH_ref), row_err(dH_f, dH_ref)
+    tH, tb = OB.agnn_layer_backward_terms(g.row_ptr, g.col_idx, H64, 2.0, dY64)
+    eu, ef = term_err(dH_u, dH_ref, tH), term_err(dH_f, dH_ref, tH)
     say(f"hub rows: unfused err {eu:.3e} fused err {ef:.3e} dbeta {float(db_u.item()):.6g} {float(db_f.item()):.6g} ref {db_ref:.6g}")
     assert eu < 1e-5 and ef < 1e-5
-    assert abs(float(db_f.item()) - db_ref) < 1e-4 * max(abs(db_ref), 1.0)
+    assert abs(float(db_f.item()) - db_ref) / tb < 1e-5 and abs(float(db_u.item()) - db_ref) / tb < 1e-5
     empty = torch.from_numpy(np.diff(g.row_ptr) == 0).cuda()
     assert torch.all(dH_f[empty] == 0) and torch.all(row_z[empty] == 0)
 
@@ -459,21 +462,21 @@ def test_agnn_layer_backward_zero_rows_and_isolated_nodes():
     p = torch.empty(g.nnz, dtype=F32, device="cuda")
     B.ftc_agnn_layer(dg, win, Hd, beta=1.5, edge_p=p)
     dH, dbeta = B.ftc_agnn_layer_backward(dg, win, T, Hd, p, dYd, beta=1.5)
-    keep = np.ones(g.n, dtype=bool)
-    keep[17] = False                       # d/dh of h/max(|h|, eps) at h = 0 is 1/eps: compared on its own scale
-    assert row_err(dH[torch.from_numpy(keep).cuda()], dH_ref[keep]) < 1e-4
-    assert np.all(np.isfinite(dH.cpu().numpy()))
-    assert abs(float(dbeta.item()) - dbeta_ref) < 1e-4 * max(abs(dbeta_ref), 1.0)
-    # the clamped row is the plain scaling by 1e12 that the forward pass applies: no projection term
+    tH, tb = OB.agnn_layer_backward_terms(g.row_ptr, g.col_idx, H64, 1.5, dY64)
+    # d/dh of h / max(|h|, eps) at h = 0 is 1 / eps: the clamped row is the plain scaling by 1e12 that the
+    # forward pass applies (no projection term); its gradient is huge and held to the same relative bar
     assert np.abs(dH_ref[17]).max() > 1e9
-    assert np.max(np.abs(dH[17].cpu().double().numpy() - dH_ref[17])) < 1e-4 * np.abs(dH_ref[17]).max()
+    e1 = term_err(dH, dH_ref, tH)
+    assert e1 < 1e-5
+    assert abs(float(dbeta.item()) - dbeta_ref) / tb < 1e-5
     # the same through the single-pass route
     row_z = torch.empty(g.n, dtype=F32, device="cuda")
     Y = B.ftc_agnn_layer(dg, win, Hd, beta=1.5, row_z=row_z)
     dH2, dbeta2 = B.ftc_agnn_layer_backward_fused(dg, win, Hd, row_z, Y, dYd, beta=1.5)
-    assert row_err(dH2[torch.from_numpy(keep).cuda()], dH_ref[keep]) < 1e-4
-    assert np.max(np.abs(dH2[17].cpu().double().numpy() - dH_ref[17])) < 1e-4 * np.abs(dH_ref[17]).max()
-    assert abs(float(dbeta2.item()) - dbeta_ref) < 1e-4 * max(abs(dbeta_ref), 1.0)
+    e2 = term_err(dH2, dH_ref, tH)
+    say(f"zero row and isolated nodes: edge-array route {e1:.3e}, single pass {e2:.3e}")
+    assert e2 < 1e-5
+    assert abs(float(dbeta2.item()) - dbeta_ref) / tb < 1e-5
 
 
 def test_agnn_layer_backward_16bit_gradient_output(graphs):
@@ -522,9 +525,11 @@ def test_train_path_stacks_against_chained_oracle(oracle, fused, sizes):
     H1 = tp.gcn_h.cpu().double().numpy()
     dH1_ref, dW2_ref, _ = OB.gcn_layer_backward(g.row_ptr, g.col_idx, vals, H1, W264, dOut64)
     _, dW1_ref, _ = OB.gcn_layer_backward(g.row_ptr, g.col_idx, vals, X64, W164, dH1_ref, Y=H1)
-    e1, e2 = arr_err(dW1, dW1_ref), arr_err(dW2, dW2_ref)
+    tH1, tW2, _ = OB.gcn_layer_backward_terms(g.row_ptr, g.col_idx, vals, H1, W264, dOut64)
+    _, tW1, _ = OB.gcn_layer_backward_terms(g.row_ptr, g.col_idx, vals, X64, W164, dH1_ref, Y=H1, dY_terms=tH1)
+    e1, e2 = term_err(dW1, dW1_ref, tW1), term_err(dW2, dW2_ref, tW2)
     say(f"gcn stack dW1 err {e1:.3e} dW2 err {e2:.3e}")
-    assert e1 < 1e-4 and e2 < 1e-4
+    assert e1 < 1e-5 and e2 < 1e-5
     # AGNN
     betas = [1.0, -0.7, 2.0]
     H0d, H064 = quantise(synth.normal_features(n, dh, seed=35), F32)
@@ -534,13 +539,14 @@ def test_train_path_stacks_against_chained_oracle(oracle, fused, sizes):
     Hs = [H064]
     for l in range(3):
         Hs.append(oracle.agnn_layer(g.row_ptr, g.col_idx, Hs[l], betas[l])[0])
-    d, db_ref = dY64, [0.0] * 3
+    d, t, db_ref, tb = dY64, None, [0.0] * 3, [0.0] * 3
     for l in reversed(range(3)):
+        t, tb[l] = OB.agnn_layer_backward_terms(g.row_ptr, g.col_idx, Hs[l], betas[l], d, dY_terms=t)
         d, db_ref[l] = OB.agnn_layer_backward(g.row_ptr, g.col_idx, Hs[l], betas[l], d)
-    eh = row_err(dH0, d)
-    say(f"agnn stack dH0 err {eh:.3e} dbeta {dbeta.cpu().numpy()} ref {db_ref}")
-    assert eh < 1e-4
-    assert np.allclose(dbeta.cpu().double().numpy(), db_ref, rtol=1e-3, atol=1e-3 * np.sqrt(n) * 1e-2)
+    eh = term_err(dH0, d, t)
+    eb = [abs(float(dbeta[l].item()) - db_ref[l]) / tb[l] for l in range(3)]
+    say(f"agnn stack dH0 err {eh:.3e} dbeta {dbeta.cpu().numpy()} ref {db_ref} err {eb}")
+    assert eh < 1e-5 and all(e < 1e-5 for e in eb)
 
 
 @pytest.mark.parametrize("act", [F32, F16])
@@ -564,16 +570,22 @@ def test_train_path_whole_agnn_model_against_chained_oracle(oracle, act):
     dW_in, dW_out, dbeta = tp.agnn_model_backward(Xd, Wid, Wod, betas, dOutd)
     Hs = [tp.agnn_h0.cpu().double().numpy()] + [tp.agnn_h[l].cpu().double().numpy() for l in (1, 2, 3)]
     d, dWo_ref = OB.update_gemm_backward(Hs[3], Wo64, dOut64)
-    db_ref = [0.0] * 3
+    t, tWo = OB.update_gemm_backward_terms(Hs[3], Wo64, dOut64)
+    db_ref, tb = [0.0] * 3, [0.0] * 3
     for l in reversed(range(3)):
         d_in = torch.from_numpy(d).to(act).double().numpy()      # the chain hands gradients on in the activation type
+        t, tb[l] = OB.agnn_layer_backward_terms(g.row_ptr, g.col_idx, Hs[l], betas[l], d_in, dY_terms=t)
         d, db_ref[l] = OB.agnn_layer_backward(g.row_ptr, g.col_idx, Hs[l], betas[l], d_in)
     _, dWi_ref = OB.update_gemm_backward(X64, Wi64, d, Hs[0])
-    ei, eo = arr_err(dW_in, dWi_ref), arr_err(dW_out, dWo_ref)
-    say(f"agnn model ({act}): dW_in err {ei:.3e} dW_out err {eo:.3e} dbeta {dbeta.cpu().numpy()} ref {db_ref}")
+    _, tWi = OB.update_gemm_backward_terms(X64, Wi64, d, Hs[0], dZ_terms=t)
+    ei, eo = term_err(dW_in, dWi_ref, tWi), term_err(dW_out, dWo_ref, tWo)
+    eb = [abs(float(dbeta[l].item()) - db_ref[l]) / tb[l] for l in range(3)]
+    say(f"agnn model ({act}): dW_in err {ei:.3e} dW_out err {eo:.3e} dbeta {dbeta.cpu().numpy()} ref {db_ref} err {eb}")
+    # fp16 activations: the gradients handed from layer to layer are rounded to fp16 on both sides, and a value
+    # that sits on a rounding boundary may fall either way: the 16-bit bar
     tol = 1e-5 if act == F32 else 2e-3
     assert ei < tol and eo < 1e-5
-    assert np.allclose(dbeta.cpu().double().numpy(), db_ref, rtol=10 * tol, atol=10 * tol)
+    assert all(e < tol for e in eb)
 
 
 def test_train_path_rejects_a_non_symmetric_pattern():
@@ -641,24 +653,16 @@ def test_agnn_backward_random_shapes(case):
     p = torch.empty(g.nnz, dtype=F32, device="cuda")
     B.ftc_agnn_layer(dg, win, Hd, beta=beta, edge_p=p)
     dH, dbeta = B.ftc_agnn_layer_backward(dg, win, T, Hd, p, dYd, beta=beta)
-    # the part of dH_i that arrives through the aggregated rows is the signed sum of p_ji dY_j over the
-    # rows j that hold i: its terms cancel (visibly so with one-element rows)
-    from oracle import ftc_oracle
-    Y_ref, _, p_ref = ftc_oracle.agnn_layer(g.row_ptr, g.col_idx, H64, beta)
-    P = sp.csr_matrix((p_ref, g.col_idx, g.row_ptr), shape=(n, n))
-    agg_abs = np.asarray(P.T @ np.abs(dY64)).max(axis=1) if g.nnz else np.zeros(n)
-    assert row_err(dH, dH_ref, agg_abs) < 1e-5
-    assert abs(float(dbeta.item()) - dbeta_ref) < 1e-4 * max(abs(dbeta_ref), 1.0)
+    tH, tb = OB.agnn_layer_backward_terms(g.row_ptr, g.col_idx, H64, beta, dY64)
+    tb = tb if tb > 0 else 1.0
+    eh, eb = term_err(dH, dH_ref, tH), abs(float(dbeta.item()) - dbeta_ref) / tb
+    say(f"  edge-array route: dH err {eh:.3e} dbeta err {eb:.3e}")
+    assert eh < 1e-5 and eb < 1e-5
     fused_ok = B.lib().ftc_agnn_layer_backward_fused_workspace_bytes(n, g.nnz, D) > 0 and (D * Hd.element_size()) % 16 == 0
     if fused_ok:
         row_z = torch.empty(n, dtype=F32, device="cuda")
         Y = B.ftc_agnn_layer(dg, win, Hd, beta=beta, row_z=row_z)
         dH2, dbeta2 = B.ftc_agnn_layer_backward_fused(dg, win, Hd, row_z, Y, dYd, beta=beta)
-        # The single pass takes t_i = <dY_i, y_i> from the stored output instead of summing p dp, so
-        # p (dp - t_i) keeps a rounding of the two terms where they cancel (a row whose attention sits on
-        # one neighbour); it reaches dH_i as |beta| |dY_i| |y_i| / |h_i|.
-        nrm = lambda a: np.sqrt((a * a).sum(axis=1))
-        cancelled = abs(beta) * nrm(dY64) * nrm(Y_ref) / np.maximum(nrm(H64), 1e-12)
-        assert row_err(dH2, dH_ref, agg_abs + cancelled) < 1e-5
-        assert abs(float(dbeta2.item()) - dbeta_ref) < 1e-4 * max(abs(dbeta_ref), 1.0)
-        say("  single-pass route checked too")
+        eh2, eb2 = term_err(dH2, dH_ref, tH), abs(float(dbeta2.item()) - dbeta_ref) / tb
+        say(f"  single-pass route: dH err {eh2:.3e} dbeta err {eb2:.3e}")
+        assert eh2 < 1e-5 and eb2 < 1e-5
