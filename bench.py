@@ -214,51 +214,6 @@ def density_sweep(n=1 << 18, k=32, dims=(32, 64, 128, 256), iters=20):
             print(json.dumps(rec), flush=True)
 
 
-def gather_probe(iters=10):
-    """How fast can the GPU deliver the rows the aggregation kernels ask for, with nothing else going on?
-    The bare gather pattern (ftc_gather_probe) on uniformly random rows, on an L2-resident row set and
-    on the column indices of the two largest benchmark graphs.  One JSON line per case."""
-    import numpy as np
-    import torch
-    import synth
-    from paper_2412_12218_amd import binding as B
-    dev = torch.device("cuda:0")
-    sink = torch.zeros(1, dtype=torch.float32, device=dev)
-
-    def run(tag, idx, n_rows, row_bytes):
-        X = torch.zeros(n_rows * row_bytes, dtype=torch.uint8, device=dev)
-        for _ in range(3):
-            B.ftc_gather_probe(idx, X, row_bytes, row_bytes, sink)
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record()
-        for _ in range(iters):
-            B.ftc_gather_probe(idx, X, row_bytes, row_bytes, sink)
-        b.record()
-        b.synchronize()
-        ms = a.elapsed_time(b) / iters
-        n = idx.numel() // 512 * 512
-        print(json.dumps({"indices": tag, "row_bytes": row_bytes, "rows": n, "ms": ms,
-                          "G_rows_per_s": n / ms / 1e6, "useful_TBs": n * row_bytes / ms / 1e9}), flush=True)
-
-    rng = np.random.default_rng(0)
-    n = 1 << 20
-    uni = torch.from_numpy(rng.integers(0, n, size=32 << 20, dtype=np.int32)).to(dev)
-    hot = torch.from_numpy(rng.integers(0, 1 << 14, size=32 << 20, dtype=np.int32)).to(dev)
-    for rb in (16, 32, 64, 128):
-        run("uniform over 2^20 rows", uni, n, rb)
-    for rb in (16, 32, 64, 128):
-        run("uniform over 2^14 rows (L2 resident)", hot, n, rb)
-    del uni, hot
-    g5 = synth.config_graph(5)
-    c5 = torch.from_numpy(g5.col_idx).to(dev)
-    for rb in (16, 32, 64):
-        run("cfg5 R-MAT col_idx", c5, g5.n, rb)
-    del c5
-    g4 = synth.config_graph(4)
-    c4 = torch.from_numpy(g4.col_idx).to(dev)
-    run("cfg4 SBM col_idx", c4, g4.n, 128)
-
-
 def reorder_suite(iters=10):
     """What the locality reordering costs and what it buys: per benchmark graph and ordering, the time
     of ftc_degree_order + ftc_permute_graph, the share of distinct window columns (sum_uniq / nnz) and
@@ -389,8 +344,6 @@ def main():
     ap.add_argument("--cpu-scale", type=int, default=20, help="R-MAT scale of the oracle's sample; 0 = skip")
     ap.add_argument("--no-kernels", action="store_true", help="skip the stand-alone SpMM/SDDMM section")
     ap.add_argument("--no-reordered", action="store_true", help="skip the step on the relabelled graph")
-    ap.add_argument("--probe", action="store_true",
-                    help="instead of the benchmark: the bare gather rate of the GPU on the benchmark graphs' indices")
     ap.add_argument("--reorder", action="store_true",
                     help="instead of the benchmark: cost and effect of the locality reordering on the benchmark graphs")
     ap.add_argument("--train", action="store_true",
@@ -412,9 +365,6 @@ def main():
     B.lib()
     if args.sweep:
         density_sweep()
-        return
-    if args.probe:
-        gather_probe()
         return
     if args.train:
         train_suite(args.scale)

@@ -10,11 +10,9 @@
  *    never prints: a call validates its arguments on the host and enqueues kernels on
  *    `stream` (a hipStream_t passed as void*, NULL = the default stream).  Scratch
  *    memory comes from a caller-provided workspace whose size is returned by the
- *    matching *_workspace_bytes query (a pure host function).  The only state the library
- *    keeps is a set of three side streams and four events, created at the first
- *    ftc_build_windows of a process (default priority, never destroyed): independent kernels of
- *    the graph transformation run on them, forked from and joined back into `stream` with
- *    events, so that for the caller everything still happens in stream order.
+ *    matching *_workspace_bytes query (a pure host function).  The library keeps no state
+ *    between calls apart from the thread-local error text (and the built-in scratch buffer of
+ *    ftc_spmm_noalloc); a call may be recorded into a HIP graph, the first one included.
  *  - Return value: FTC_OK or a negative ftc_status; ftc_last_error() returns a
  *    thread-local description of the last failure.
  *  - The graph is a CSR adjacency with int32 indices (`nodePointer` / `edgeList` in the
@@ -114,6 +112,25 @@ int32_t ftc_validate_csr(const ftc_csr *g, int32_t *flag, void *stream);
 size_t ftc_build_windows_workspace_bytes(int32_t n, int32_t nnz, int32_t blk_h, int32_t blk_w);
 int32_t ftc_build_windows(const ftc_csr *g, ftc_windows *out, void *ws, size_t ws_bytes,
                           void *stream);
+
+/*
+ * The same transformation with its independent kernels side by side.  Windows of different sizes
+ * are condensed by different kernels (Section V.A: the windows do not depend on each other), each of
+ * which fills only part of the GPU; given three more streams they overlap (0.39 instead of 0.54 ms
+ * on the R-MAT benchmark graph).  `side` holds three hipStream_t and four hipEvent_t (timing may be
+ * disabled) created by the caller on the device of `stream`, all at the default priority: `stream`
+ * forks into the side streams through `fork` after the classification and waits for `join[i]` of
+ * each before the final scan, so for the caller everything still happens in stream order and nothing
+ * waits on the host.  The handles are used only during the call; two calls that overlap in time need
+ * two sets.  side == NULL is ftc_build_windows.
+ */
+typedef struct {
+    void *stream[3]; /* hipStream_t */
+    void *fork;      /* hipEvent_t  */
+    void *join[3];   /* hipEvent_t  */
+} ftc_side_streams;
+int32_t ftc_build_windows_concurrent(const ftc_csr *g, ftc_windows *out, void *ws, size_t ws_bytes,
+                                     const ftc_side_streams *side, void *stream);
 
 /*
  * Symmetric GCN normalisation for a pattern that already contains the self-loops
@@ -339,16 +356,19 @@ int32_t ftc_agnn_layer_backward(const ftc_csr *g, const ftc_windows *w, const in
  * H and dY share dtype and leading dimension, rows 16-byte aligned; the window index is required;
  * (dtype, D) must be a width the single-pass forward covers, with at most 128 elements once
  * padded to its lane layout (ftc_plan_graph reports it), and |beta| < 43.  FTC_EUNSUPPORTED otherwise: use
- * ftc_agnn_layer_backward.  The pattern is taken to be symmetric (ftc_transpose_index, flag 0,
- * checks it); on another pattern the result is the gradient of nothing.
+ * ftc_agnn_layer_backward.  The formulas hold on a symmetric pattern only.  pattern_flag (device
+ * int32, may be NULL) is the flag ftc_transpose_index wrote for this graph: when it is not zero
+ * (some entry has no transposed partner) every element of dH and *dbeta is set to NaN instead of a
+ * gradient of nothing.  NULL: the caller vouches for the symmetry.
  */
 size_t ftc_agnn_layer_backward_fused_workspace_bytes(int32_t n, int32_t nnz, int32_t D);
 int32_t ftc_agnn_layer_backward_fused(const ftc_csr *g, const ftc_windows *w, const void *H,
                                       int32_t ld, int32_t dtype, int32_t D, float beta,
                                       const float *row_z, const void *Y, int32_t ldy,
                                       int32_t y_dtype, const void *dY, int32_t lddy, void *dH,
-                                      int32_t lddh, int32_t dh_dtype, float *dbeta, void *ws,
-                                      size_t ws_bytes, void *stream);
+                                      int32_t lddh, int32_t dh_dtype, float *dbeta,
+                                      const int32_t *pattern_flag, void *ws, size_t ws_bytes,
+                                      void *stream);
 
 /*
  * ---- Locality reordering (preprocessing) ------------------------------------------------------
@@ -447,18 +467,6 @@ typedef struct {
 /* Host-only, pure.  sum_deg_sq from ftc_degree_stats, sum_uniq = summary[0] of ftc_build_windows. */
 int32_t ftc_plan_graph(int32_t n, int32_t nnz, int64_t sum_deg_sq, int64_t sum_uniq, int32_t D,
                        int32_t dtype, ftc_plan *plan);
-
-/*
- * Measurement aid (no part of the method): enqueues the bare gather pattern of the aggregation
- * kernels -- for every index i of idx[0 .. n_idx) (device, int32; a trailing group of fewer than
- * 512 indices is ignored) the row_bytes (16, 32, 64 or 128) bytes at X + idx[i] * stride_bytes are
- * loaded, 16 bytes per lane, and discarded.  Every idx[i] * stride_bytes + row_bytes must lie
- * inside X (not checked).  *sink (device) is written only if the loaded data are not all zero.
- * bench.py --probe times it on the column indices of the benchmark graphs: the rate at which the
- * GPU delivers those rows at all.
- */
-int32_t ftc_gather_probe(const int32_t *idx, int64_t n_idx, const void *X, int32_t row_bytes,
-                         int32_t stride_bytes, float *sink, void *stream);
 
 #ifdef __cplusplus
 }

@@ -30,6 +30,7 @@ _SIGNATURES = {
     "ftc_validate_csr": (_I, [_P, _P, _P]),
     "ftc_build_windows_workspace_bytes": (_Z, [_I, _I, _I, _I]),
     "ftc_build_windows": (_I, [_P, _P, _P, _Z, _P]),
+    "ftc_build_windows_concurrent": (_I, [_P, _P, _P, _Z, _P, _P]),
     "ftc_gcn_norm": (_I, [_P, _P, _P, _P, _P]),
     "ftc_spmm_workspace_bytes": (_Z, [_I, _I, _I]),
     "ftc_spmm": (_I, [_P, _P, _P, _P, _I, _I, _I, _P, _I, _I, _P, _I, _I, _P, _Z, _P]),
@@ -56,7 +57,7 @@ _SIGNATURES = {
     "ftc_agnn_layer_backward_workspace_bytes": (_Z, [_I, _I, _I]),
     "ftc_agnn_layer_backward": (_I, [_P, _P, _P, _P, _I, _I, _I, _F, _P, _P, _I, _P, _I, _I, _P, _I, _P, _Z, _P]),
     "ftc_agnn_layer_backward_fused_workspace_bytes": (_Z, [_I, _I, _I]),
-    "ftc_agnn_layer_backward_fused": (_I, [_P, _P, _P, _I, _I, _I, _F, _P, _P, _I, _I, _P, _I, _P, _I, _I, _P, _P, _Z, _P]),
+    "ftc_agnn_layer_backward_fused": (_I, [_P, _P, _P, _I, _I, _I, _F, _P, _P, _I, _I, _P, _I, _P, _I, _I, _P, _P, _P, _Z, _P]),
     "ftc_reorder_workspace_bytes": (_Z, [_I, _I]),
     "ftc_degree_order": (_I, [_P, _I, _P, _P, _P, _Z, _P]),
     "ftc_order_by_key": (_I, [_I, _P, _P, _P, _P, _P, _Z, _P]),
@@ -65,7 +66,6 @@ _SIGNATURES = {
     "ftc_permute_rows": (_I, [_I, _P, _I, _I, _I, _P, _P, _I, _P]),
     "ftc_degree_stats": (_I, [_P, _P, _P]),
     "ftc_plan_graph": (_I, [_I, _I, C.c_int64, C.c_int64, _I, _I, _P]),
-    "ftc_gather_probe": (_I, [_P, C.c_int64, _P, _I, _I, _P, _P]),
 }
 EXPORTS = list(_SIGNATURES)
 
@@ -179,11 +179,41 @@ def ftc_validate_csr(g):
     return flag
 
 
-def ftc_build_windows(g, blk_h=16, blk_w=8):
-    w = Windows(g, blk_h, blk_w)
-    nbytes = lib().ftc_build_windows_workspace_bytes(g.n, g.nnz, blk_h, blk_w)
-    ws = _workspace(nbytes, g.row_ptr.device)
+class ftc_side_streams(C.Structure):
+    _fields_ = [("stream", C.c_void_p * 3), ("fork", C.c_void_p), ("join", C.c_void_p * 3)]
+
+
+class SideStreams:
+    """Three streams and four events for ftc_build_windows_concurrent, created through torch (device plumbing
+    only) on the current device at the default priority; keeps them alive as long as the object lives."""
+
+    def __init__(self):
+        self.streams = [torch.cuda.Stream() for _ in range(3)]
+        self.events = [torch.cuda.Event(enable_timing=False) for _ in range(4)]
+        for ev, st in zip(self.events, [torch.cuda.current_stream()] + self.streams):
+            ev.record(st)              # torch creates the event handle at its first record
+        self.c = ftc_side_streams()
+        for i in range(3):
+            self.c.stream[i] = self.streams[i].cuda_stream
+            self.c.join[i] = self.events[1 + i].cuda_event
+        self.c.fork = self.events[0].cuda_event
+
+
+def ftc_build_windows(g, blk_h=16, blk_w=8, out=None, ws=None):
+    w = out if out is not None else Windows(g, blk_h, blk_w)
+    if ws is None:
+        ws = _workspace(lib().ftc_build_windows_workspace_bytes(g.n, g.nnz, w.c.blk_h, w.c.blk_w), g.row_ptr.device)
     _check(lib().ftc_build_windows(C.byref(g.c), C.byref(w.c), _ptr(ws), C.c_size_t(ws.numel()), _stream()))
+    return w
+
+
+def ftc_build_windows_concurrent(g, side, blk_h=16, blk_w=8, out=None, ws=None):
+    """side: a SideStreams (or None: the same as ftc_build_windows)."""
+    w = out if out is not None else Windows(g, blk_h, blk_w)
+    if ws is None:
+        ws = _workspace(lib().ftc_build_windows_workspace_bytes(g.n, g.nnz, w.c.blk_h, w.c.blk_w), g.row_ptr.device)
+    _check(lib().ftc_build_windows_concurrent(C.byref(g.c), C.byref(w.c), _ptr(ws), C.c_size_t(ws.numel()),
+                                              C.byref(side.c) if side is not None else None, _stream()))
     return w
 
 
@@ -297,11 +327,6 @@ def ftc_agnn_layer(g, w, H, beta=1.0, out=None, out_dtype=torch.float32, edge_p=
     return out
 
 
-def ftc_gather_probe(idx, X, row_bytes, stride_bytes, sink):
-    _check(lib().ftc_gather_probe(_ptr(idx), C.c_int64(idx.numel()), _ptr(X), C.c_int32(row_bytes),
-                                  C.c_int32(stride_bytes), _ptr(sink), _stream()))
-
-
 # ---- backward pass (gradients are fp32 tensors) ----------------------------------------------------
 def ftc_transpose_index(g, w=None):
     T = torch.empty(g.nnz, dtype=torch.int32, device=g.row_ptr.device)
@@ -384,7 +409,8 @@ def ftc_agnn_layer_backward(g, w, T, H, p, dY, beta=1.0, dH=None, dh_dtype=torch
     return dH, dbeta
 
 
-def ftc_agnn_layer_backward_fused(g, w, H, row_z, Y, dY, beta=1.0, dH=None, dh_dtype=torch.float32, dbeta=None, ws=None):
+def ftc_agnn_layer_backward_fused(g, w, H, row_z, Y, dY, beta=1.0, dH=None, dh_dtype=torch.float32, dbeta=None, ws=None,
+                                  pattern_flag=None):
     n, D = H.shape
     assert dY.dtype == H.dtype and dY.shape == H.shape and dY.stride(0) == H.stride(0) and Y.shape == H.shape
     if dH is None:
@@ -396,7 +422,8 @@ def ftc_agnn_layer_backward_fused(g, w, H, row_z, Y, dY, beta=1.0, dH=None, dh_d
     _check(lib().ftc_agnn_layer_backward_fused(
         C.byref(g.c), _wref(w), _ptr(H), C.c_int32(H.stride(0)), C.c_int32(_dt(H)), C.c_int32(D), C.c_float(beta),
         _ptr(row_z), _ptr(Y), C.c_int32(Y.stride(0)), C.c_int32(_dt(Y)), _ptr(dY), C.c_int32(dY.stride(0)), _ptr(dH),
-        C.c_int32(dH.stride(0)), C.c_int32(_dt(dH)), _ptr(dbeta), _ptr(ws), C.c_size_t(ws.numel()), _stream()))
+        C.c_int32(dH.stride(0)), C.c_int32(_dt(dH)), _ptr(dbeta), _ptr(pattern_flag), _ptr(ws), C.c_size_t(ws.numel()),
+        _stream()))
     return dH, dbeta
 
 

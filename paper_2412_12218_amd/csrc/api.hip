@@ -115,7 +115,8 @@ size_t ftc_build_windows_workspace_bytes(int32_t n, int32_t nnz, int32_t blk_h, 
     return build_windows_ws(n, nnz, blk_h, blk_w);
 }
 
-int32_t ftc_build_windows(const ftc_csr *g, ftc_windows *out, void *ws, size_t ws_bytes, void *stream)
+int32_t ftc_build_windows_concurrent(const ftc_csr *g, ftc_windows *out, void *ws, size_t ws_bytes,
+                                     const ftc_side_streams *side, void *stream)
 {
     FTC_TRY(check_csr(g, "ftc_build_windows"));
     FTC_TRY(check_windows(g, out, "ftc_build_windows", true));
@@ -125,7 +126,23 @@ int32_t ftc_build_windows(const ftc_csr *g, ftc_windows *out, void *ws, size_t w
                     ws ? ws_bytes : static_cast<size_t>(0));
     if (reinterpret_cast<uintptr_t>(ws) % 256 != 0)
         return fail(FTC_EALIGN, "ftc_build_windows: workspace must be 256-byte aligned");
-    return launch_build_windows(*g, *out, ws, ws_bytes, static_cast<hipStream_t>(stream));
+    if (side) {
+        bool ok = side->fork != nullptr;
+        for (int i = 0; i < 3; ++i) {
+            ok = ok && side->stream[i] && side->join[i] && side->stream[i] != stream;
+            for (int j = 0; j < i; ++j) ok = ok && side->stream[i] != side->stream[j] && side->join[i] != side->join[j];
+            ok = ok && side->join[i] != side->fork;
+        }
+        if (!ok)
+            return fail(FTC_EINVAL, "ftc_build_windows_concurrent: side needs three distinct streams other than `stream` and "
+                                    "four distinct events");
+    }
+    return launch_build_windows(*g, *out, ws, ws_bytes, side, static_cast<hipStream_t>(stream));
+}
+
+int32_t ftc_build_windows(const ftc_csr *g, ftc_windows *out, void *ws, size_t ws_bytes, void *stream)
+{
+    return ftc_build_windows_concurrent(g, out, ws, ws_bytes, nullptr, stream);
 }
 
 int32_t ftc_gcn_norm(const ftc_csr *g, const ftc_windows *w, float *vals, float *dinv, void *stream)
@@ -685,7 +702,8 @@ size_t ftc_agnn_layer_backward_fused_workspace_bytes(int32_t n, int32_t nnz, int
 int32_t ftc_agnn_layer_backward_fused(const ftc_csr *g, const ftc_windows *w, const void *H, int32_t ld, int32_t dtype,
                                       int32_t D, float beta, const float *row_z, const void *Y, int32_t ldy,
                                       int32_t y_dtype, const void *dY, int32_t lddy, void *dH, int32_t lddh,
-                                      int32_t dh_dtype, float *dbeta, void *ws, size_t ws_bytes, void *stream)
+                                      int32_t dh_dtype, float *dbeta, const int32_t *pattern_flag, void *ws,
+                                      size_t ws_bytes, void *stream)
 {
     FTC_TRY(check_csr(g, "ftc_agnn_layer_backward_fused"));
     if (g->n == 0) return FTC_OK;
@@ -710,8 +728,11 @@ int32_t ftc_agnn_layer_backward_fused(const ftc_csr *g, const ftc_windows *w, co
         return fail(FTC_EWORKSPACE, "ftc_agnn_layer_backward_fused: workspace of %zu bytes needed", need);
     if (reinterpret_cast<uintptr_t>(ws) % 256 != 0)
         return fail(FTC_EALIGN, "ftc_agnn_layer_backward_fused: workspace must be 256-byte aligned");
-    return launch_agnn_backward_fused(*g, *w, H, dY, ld, dtype, D, beta, row_z, Y, ldy, y_dtype, dH, lddh, dh_dtype,
-                                      dbeta, ws, static_cast<hipStream_t>(stream));
+    FTC_TRY(launch_agnn_backward_fused(*g, *w, H, dY, ld, dtype, D, beta, row_z, Y, ldy, y_dtype, dH, lddh, dh_dtype,
+                                       dbeta, ws, static_cast<hipStream_t>(stream)));
+    if (pattern_flag)  // not a symmetric pattern: NaN instead of a gradient of nothing
+        return launch_poison_if_flag(pattern_flag, g->n, D, dH, lddh, dh_dtype, dbeta, static_cast<hipStream_t>(stream));
+    return FTC_OK;
 }
 
 // ---- locality reordering (preprocessing) ---------------------------------------------------------

@@ -490,6 +490,27 @@ int32_t launch_edge_dot(int nnz, const float *a, const float *b, float *out, voi
     return launch_status("edge_dot");
 }
 
+// ---- guard of the single-pass AGNN backward: a pattern that is not symmetric gets NaN, not numbers ------
+// *flag != 0 (the flag of ftc_transpose_index): every element of the n x D matrix M and *scalar become NaN.
+// With *flag == 0 every thread returns after one load.
+__global__ __launch_bounds__(256) void poison_if_flag_kernel(const int32_t *__restrict__ flag, int n, int D,
+                                                             void *__restrict__ M, int ld, int dt,
+                                                             float *__restrict__ scalar)
+{
+    if (*flag == 0) return;
+    const float nan = __int_as_float(0x7fc00000);
+    const int64_t total = static_cast<int64_t>(n) * D;
+    for (int64_t t = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x; t < total; t += static_cast<int64_t>(gridDim.x) * 256)
+        store_elem(M, (t / D) * ld + t % D, dt, nan);
+    if (blockIdx.x == 0 && threadIdx.x == 0) *scalar = nan;
+}
+
+int32_t launch_poison_if_flag(const int32_t *flag, int n, int D, void *M, int ld, int dt, float *scalar, hipStream_t s)
+{
+    hipLaunchKernelGGL(poison_if_flag_kernel, dim3(256), dim3(256), 0, s, flag, n, D, M, ld, dt, scalar);
+    return launch_status("poison_if_flag");
+}
+
 // ---- dH = base + rinv * (q - hn <hn, q>), hn = rinv * h --------------------------------------------
 // q is the gradient with respect to the normalised rows, base the part of dH that reaches h through
 // the aggregated rows; eight lanes per row.  A row whose norm was clamped (|h| <= 1e-12) is a plain

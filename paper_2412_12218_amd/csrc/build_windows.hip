@@ -21,7 +21,6 @@
 // win_col_ptr / block_partition / summary and a last kernel packs the lists into win_cols.
 #include "ftc_common.hpp"
 
-#include <mutex>
 
 namespace ftc {
 
@@ -32,7 +31,6 @@ constexpr int HUB_SLOTS_MAX = 1024; // hub windows handled at once (one thread e
 constexpr int HUB_CHUNK = 4096;     // edges per work item of the edge-parallel hub kernels
 constexpr int HUB_GROUP = 8;        // bitmap words per stored prefix (one 32-byte load)
 constexpr int HUB_GRID = 2048;      // workgroups of the edge-parallel hub kernels (grid-stride over chunks)
-constexpr int N_CU = 256;           // compute units: the persistent grids are multiples of it
 
 enum { C_MID = 0, C_LARGE = 1, C_HUB = 2, C_CHUNKS = 3, C_MID_NEXT = 4, C_LARGE_NEXT = 5, C_WORDS = 8 };
 
@@ -899,51 +897,12 @@ __global__ __launch_bounds__(256) void win_pack_kernel(int n_windows, const int 
         if (src[j] >= 0) win_cols[o_first + j * 64 + lane] = val[j];
 }
 
-// Side streams for the kernels that do not depend on each other (created once per process and
-// device, default priority, never destroyed).  The classes of windows are condensed by different
-// kernels, each of which fills only part of the GPU; after the classification they run side by
-// side: the caller's stream forks into the side streams with an event and joins them again before
-// the scan.  Nothing here waits on the host.
-namespace {
-struct SideStreams {
-    int device = -1;
-    hipStream_t stream[3] = {nullptr, nullptr, nullptr};
-    hipEvent_t fork = nullptr;
-    hipEvent_t join[3] = {nullptr, nullptr, nullptr};
-    bool ok = false;
-};
-SideStreams g_side;
-std::mutex g_side_mutex;
-
-// Returns nullptr when streams or events cannot be created: the caller then runs everything on its
-// own stream.
-SideStreams *side_streams()
-{
-    std::lock_guard<std::mutex> lock(g_side_mutex);
-    int dev = -1;
-    if (hipGetDevice(&dev) != hipSuccess) {
-        (void)hipGetLastError();
-        return nullptr;
-    }
-    if (g_side.ok && g_side.device == dev) return &g_side;
-    if (g_side.ok) return nullptr;  // another device than the one the streams live on: no side streams
-    SideStreams t;
-    t.device = dev;
-    bool good = hipEventCreateWithFlags(&t.fork, hipEventDisableTiming) == hipSuccess;
-    for (int i = 0; i < 3 && good; ++i)
-        good = hipStreamCreateWithFlags(&t.stream[i], hipStreamNonBlocking) == hipSuccess &&
-               hipEventCreateWithFlags(&t.join[i], hipEventDisableTiming) == hipSuccess;
-    if (!good) {
-        (void)hipGetLastError();
-        return nullptr;
-    }
-    t.ok = true;
-    g_side = t;
-    return &g_side;
-}
-}  // namespace
-
-int32_t launch_build_windows(const ftc_csr &g, ftc_windows &w, void *ws, size_t ws_bytes, hipStream_t s)
+// The classes of windows are condensed by different kernels, none of which depends on another and each of
+// which fills only part of the GPU.  With three side streams and four events from the caller they run side
+// by side after the classification: the caller's stream forks into the side streams with an event and
+// joins them again before the scan.  Nothing here waits on the host and the library keeps no state.
+int32_t launch_build_windows(const ftc_csr &g, ftc_windows &w, void *ws, size_t ws_bytes, const ftc_side_streams *side_in,
+                             hipStream_t s)
 {
     (void)ws_bytes;
     const WinWorkspace k = carve(ws, g.n, g.nnz, w.n_windows);
@@ -956,7 +915,14 @@ int32_t launch_build_windows(const ftc_csr &g, ftc_windows &w, void *ws, size_t 
     const bool queued = g.nnz > WAVE_CAP;  // otherwise no window can be queued
     int32_t st = FTC_OK;
     hipStream_t s_mid = s, s_large = s, s_hub = s;
-    SideStreams *side = nullptr;
+    const ftc_side_streams *side = nullptr;
+    // compute units of the current device: the persistent grids are multiples of it
+    int n_cu = 256, dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+        n_cu < 1) {
+        (void)hipGetLastError();
+        n_cu = 256;
+    }
     if (queued) {
         hipLaunchKernelGGL(win_clear_kernel, dim3(1), dim3(64), 0, s, k.counters);
         hipLaunchKernelGGL(win_classify_kernel, dim3((w.n_windows + 1023) / 1024), dim3(1024), 0, s, g.n,
@@ -964,25 +930,22 @@ int32_t launch_build_windows(const ftc_csr &g, ftc_windows &w, void *ws, size_t 
                            k.counters);
         st = launch_status("build_windows classify");
         if (st != FTC_OK) return st;
-        side = side_streams();
+        side = side_in;
         if (side) {
-            if (hipEventRecord(side->fork, s) != hipSuccess) {
+            hipEvent_t fork = static_cast<hipEvent_t>(side->fork);
+            bool good = hipEventRecord(fork, s) == hipSuccess;
+            for (int i = 0; i < 3 && good; ++i)
+                good = hipStreamWaitEvent(static_cast<hipStream_t>(side->stream[i]), fork, 0) == hipSuccess;
+            if (!good) {
+                // a side stream that did not take the dependency must not be used; the ones that did only
+                // wait for work that is already queued on s
                 (void)hipGetLastError();
-                side = nullptr;
-            } else {
-                bool good = true;
-                for (int i = 0; i < 3; ++i) good = good && hipStreamWaitEvent(side->stream[i], side->fork, 0) == hipSuccess;
-                if (!good) {
-                    // a side stream that did not take the dependency must not be used; the ones that
-                    // did only wait for work that is already queued on s
-                    (void)hipGetLastError();
-                    side = nullptr;
-                } else {
-                    s_mid = side->stream[0];
-                    s_large = side->stream[1];
-                    s_hub = side->stream[2];
-                }
+                set_error("build_windows: cannot fork into the side streams");
+                return FTC_EHIP;
             }
+            s_mid = static_cast<hipStream_t>(side->stream[0]);
+            s_large = static_cast<hipStream_t>(side->stream[1]);
+            s_hub = static_cast<hipStream_t>(side->stream[2]);
         }
     }
     hipLaunchKernelGGL(win_wave_kernel, dim3(w.n_windows), dim3(64), 0, s, g.n, g.row_ptr, g.col_idx, w.blk_h,
@@ -993,7 +956,7 @@ int32_t launch_build_windows(const ftc_csr &g, ftc_windows &w, void *ws, size_t 
         // 1024-thread workgroup per CU), never more than the queue can hold
 #define FTC_RANGE(NT, SLOTS, RANK, PER_CU, CAP, LIST, COUNTER, NEXT, STREAM)                                  \
     hipLaunchKernelGGL((win_compact_kernel<NT, SLOTS, RANK, PER_CU>),                                         \
-                       dim3(CAP < PER_CU * N_CU ? CAP : PER_CU * N_CU), dim3(NT), 0, STREAM, g.n, g.row_ptr,  \
+                       dim3(CAP < PER_CU * n_cu ? CAP : PER_CU * n_cu), dim3(NT), 0, STREAM, g.n, g.row_ptr,  \
                        g.col_idx, w.blk_h, w.edge_to_row, w.edge_to_col, k.uniq_count, k.tmp_cols, LIST,      \
                        k.counters + COUNTER, k.counters + NEXT)
         if (st == FTC_OK) {
@@ -1022,8 +985,9 @@ int32_t launch_build_windows(const ftc_csr &g, ftc_windows &w, void *ws, size_t 
         if (side) {
             // join: also after a failed launch, so that no side stream is left ahead of the caller's
             for (int i = 0; i < 3; ++i) {
-                if (hipEventRecord(side->join[i], side->stream[i]) != hipSuccess ||
-                    hipStreamWaitEvent(s, side->join[i], 0) != hipSuccess) {
+                if (hipEventRecord(static_cast<hipEvent_t>(side->join[i]), static_cast<hipStream_t>(side->stream[i])) !=
+                        hipSuccess ||
+                    hipStreamWaitEvent(s, static_cast<hipEvent_t>(side->join[i]), 0) != hipSuccess) {
                     (void)hipGetLastError();
                     if (st == FTC_OK) {
                         set_error("build_windows: cannot join the side streams");

@@ -82,6 +82,7 @@ int32_t launch_sddmm_mfma(const ftc_csr &g, const ftc_windows &w, const void *X,
 int32_t launch_spmm_mfma(const ftc_csr &g, const ftc_windows &w, const float *vals, const void *X, int ldx, int dt,
                          int D, void *out, int ldo, int odt, Epi epi, const uint8_t *flags, hipStream_t s);
 // backward.hip
+int32_t launch_poison_if_flag(const int32_t *flag, int n, int D, void *M, int ld, int dt, float *scalar, hipStream_t s);
 int32_t launch_transpose_index(const ftc_csr &g, const int *edge_to_row, int *T, int *flag, hipStream_t s);
 int32_t launch_softmax_backward(const ftc_csr &g, const float *p, const float *dp, float *ds, hipStream_t s);
 int32_t launch_softmax_backward_seg(const ftc_csr &g, const ftc_windows &w, const float *p, const float *dp, float *ds,
@@ -115,7 +116,8 @@ int32_t launch_permute_graph(const ftc_csr &g, const int *perm, const int *inv, 
 int32_t launch_permute_rows(int n, const void *X, int ldx, int dt, int D, const int *map, void *out, int ldo,
                             hipStream_t s);
 size_t build_windows_ws(int n, int nnz, int blk_h, int blk_w);
-int32_t launch_build_windows(const ftc_csr &g, ftc_windows &w, void *ws, size_t ws_bytes, hipStream_t s);
+int32_t launch_build_windows(const ftc_csr &g, ftc_windows &w, void *ws, size_t ws_bytes, const ftc_side_streams *side,
+                             hipStream_t s);
 
 // ---- device side -----------------------------------------------------------------------------
 #if defined(__HIPCC__)

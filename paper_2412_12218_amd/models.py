@@ -1,6 +1,7 @@
 """Layer chaining of the two benchmark models (Section VI: 2-layer GCN with hidden size 16,
 4-layer AGNN with hidden size 32): HotPath is the forward pass the benchmark times, TrainPath
-the forward + backward pass of the same two models.
+the forward + backward pass of the same two models, PlannedGraph the per-graph adaptation that the
+paper's outlook (Section VII) names: statistics of the graph decide how it is prepared.
 
 Every step is a call into libftc through `binding`; this module only owns the device
 buffers between the calls (allocated once in __init__, so a forward pass allocates nothing).
@@ -10,15 +11,66 @@ import torch
 from . import binding as B
 
 
+class PlannedGraph:
+    """Per-graph adaptive preparation (Section VII: fit the use of the hardware to the input graph).
+
+    One pass over the graph's statistics (ftc_degree_stats, the window build's summary) goes to the host,
+    ftc_plan_graph turns it into choices, and this class carries them out: relabel the nodes by degree
+    class, or try the community ordering (label propagation) and keep it only if the windows then share
+    more columns (sum_uniq drops), or leave the graph as it is.  `g` and `win` are the graph and window
+    index to run the layers on; features enter with enter(X) and results leave with leave(Y), so the
+    caller keeps the original numbering (permutation in, permutation out).  All device work is libftc's;
+    the host only compares the few numbers the plan is made of."""
+
+    def __init__(self, g, D, dtype, lp_rounds=10, side=None):
+        self.g_given = g
+        self.g, self.perm, self.inv, self.applied = g, None, None, "none"
+        ws = B._workspace(B.lib().ftc_reorder_workspace_bytes(g.n, g.nnz), g.row_ptr.device)
+        self.win = B.ftc_build_windows_concurrent(g, side)
+        stats = B.ftc_degree_stats(g)
+        self.sum_uniq_given = int(self.win.summary[0].item())          # the one host read the plan needs
+        self.plan = B.ftc_plan_graph(g.n, g.nnz, int(stats[0].item()), self.sum_uniq_given, D, dtype)
+        self.sum_uniq = self.sum_uniq_given
+        order = self.plan["reorder"]
+        if order == B.FTC_ORDER_DEGREE_CLASSES:
+            perm, inv = B.ftc_degree_order(g, B.FTC_ORDER_DEGREE_CLASSES, ws=ws)
+            self._relabel(perm, inv, ws, side, "degree classes", keep_if_fewer_columns=False)
+        elif order == B.FTC_ORDER_COMMUNITIES:
+            labels = B.ftc_label_propagation(g, lp_rounds, ws=ws)
+            perm, inv, _ = B.ftc_order_by_key(labels, ws=ws)
+            self._relabel(perm, inv, ws, side, "communities", keep_if_fewer_columns=True)
+
+    def _relabel(self, perm, inv, ws, side, name, keep_if_fewer_columns):
+        g2, flag = B.ftc_permute_graph(self.g_given, perm, inv, ws=ws)
+        win2 = B.ftc_build_windows_concurrent(g2, side)
+        su2 = int(win2.summary[0].item())
+        assert int(flag.item()) == 0
+        # a trial ordering is kept only if it makes the rows of a window share at least 2 % more columns
+        if keep_if_fewer_columns and su2 > 0.98 * self.sum_uniq_given:
+            self.trial = {"ordering": name, "sum_uniq": su2, "kept": False}
+            return
+        self.g, self.win, self.perm, self.inv, self.applied, self.sum_uniq = g2, win2, perm, inv, name, su2
+
+    def enter(self, X, out=None):
+        """Rows of X (original numbering) in the numbering of self.g."""
+        return X if self.perm is None else B.ftc_permute_rows(X, self.perm, out=out)
+
+    def leave(self, Y, out=None):
+        """Rows of Y (numbering of self.g) back in the original numbering."""
+        return Y if self.inv is None else B.ftc_permute_rows(Y, self.inv, out=out)
+
+
 class HotPath:
     """window build + GCN normalisation + 2-layer GCN + 4-layer AGNN on one graph."""
 
     def __init__(self, g, d_feat=128, gcn_hidden=16, agnn_hidden=32, n_out=8, agnn_layers=4,
-                 act_dtype=torch.float16, path=B.FTC_PATH_AUTO):
+                 act_dtype=torch.float16, path=B.FTC_PATH_AUTO, concurrent_build=True):
         dev = g.row_ptr.device
         L = B.lib()
         self.g, self.path, self.agnn_layers = g, path, agnn_layers
         self.win = B.Windows(g)
+        # the independent kernels of the window build overlap on three side streams owned here
+        self.side = B.SideStreams() if concurrent_build else None
         n, nnz = g.n, g.nnz
         f32 = dict(dtype=torch.float32, device=dev)
         act = dict(dtype=act_dtype, device=dev)
@@ -35,8 +87,7 @@ class HotPath:
 
     def build(self):
         g, w = self.g, self.win
-        B._check(B.lib().ftc_build_windows(B.C.byref(g.c), B.C.byref(w.c), B._ptr(self.ws_win),
-                                           B.C.c_size_t(self.ws_win.numel()), B._stream()))
+        B.ftc_build_windows_concurrent(g, self.side, out=w, ws=self.ws_win)
         B._check(B.lib().ftc_gcn_norm(B.C.byref(g.c), B.C.byref(w.c), None, B._ptr(self.dinv),
                                       B._stream()))
 
@@ -65,8 +116,7 @@ class HotPath:
         """The step as a HIP graph: every call of the library only enqueues kernels (and the window build's
         fork / join events) on the stream it is given and allocates nothing, so the whole step can be
         captured once and replayed with one launch; the results land in the same buffers as step()'s.
-        The step runs once eagerly first (creates the library's side streams outside the capture)."""
-        self.step(X, W1, W2, W_in, W_out, betas)
+        The library keeps no state, so nothing has to run eagerly first."""
         torch.cuda.synchronize()
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
@@ -87,6 +137,7 @@ class TrainPath:
         self.g, self.win, self.dinv, self.path, self.agnn_layers = g, win, dinv, path, agnn_layers
         n, nnz = g.n, g.nnz
         self.T, flag = B.ftc_transpose_index(g, win)
+        self.pattern_flag = flag           # handed to the single-pass backward, which refuses a non-symmetric pattern
         if int(flag.item()) != 0:
             raise ValueError("TrainPath needs a symmetric sparsity pattern with ascending, duplicate-free rows")
         f32 = dict(dtype=torch.float32, device=dev)
@@ -161,7 +212,8 @@ class TrainPath:
             if self.fused:
                 y = self.agnn_y32[l][:, :self.agnn_h[l].shape[1]] if self.keep_f32 else self.agnn_h[l + 1]
                 B.ftc_agnn_layer_backward_fused(self.g, self.win, self.agnn_h[l], self.agnn_z[l], y, d,
-                                                beta=betas[l], dH=nxt, dbeta=self.dbeta[l:l + 1], ws=self.ws)
+                                                beta=betas[l], dH=nxt, dbeta=self.dbeta[l:l + 1], ws=self.ws,
+                                                pattern_flag=self.pattern_flag)
             else:
                 B.ftc_agnn_layer_backward(self.g, self.win, self.T, self.agnn_h[l], self.agnn_p[l], d, beta=betas[l],
                                           dH=nxt, dbeta=self.dbeta[l:l + 1], path=self.path, ws=self.ws)

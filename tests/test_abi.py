@@ -114,11 +114,11 @@ def test_backward_and_reordering_validate_on_the_host():
                                      I(16), I(0), fake, I(0), fake, big, None) == B.FTC_EINVAL
     # the single-pass route needs the window index
     assert L.ftc_agnn_layer_backward_fused(C.byref(g), None, fake, I(16), I(1), I(16), F(1.0), fake, other, I(16), I(0),
-                                           other, I(16), C.c_void_p(0x5000), I(16), I(0), fake, fake, big, None) == B.FTC_EINVAL
+                                           other, I(16), C.c_void_p(0x5000), I(16), I(0), fake, None, fake, big, None) == B.FTC_EINVAL
     assert b"window index" in L.ftc_last_error()
     # ... and a width it covers
     assert L.ftc_agnn_layer_backward_fused(C.byref(g), C.byref(w), fake, I(256), I(1), I(256), F(1.0), fake, other, I(256),
-                                           I(0), other, I(256), C.c_void_p(0x5000), I(256), I(0), fake, fake, big, None) \
+                                           I(0), other, I(256), C.c_void_p(0x5000), I(256), I(0), fake, fake, fake, big, None) \
         == B.FTC_EUNSUPPORTED
     assert L.ftc_degree_order(C.byref(g), I(7), fake, fake, fake, big, None) == B.FTC_EINVAL          # unknown ordering
     assert L.ftc_degree_order(C.byref(g), I(0), fake, fake, fake, C.c_size_t(16), None) == B.FTC_EWORKSPACE
@@ -131,6 +131,27 @@ def test_backward_and_reordering_validate_on_the_host():
     assert L.ftc_reorder_workspace_bytes(1000, 5000) > 5000 * 4 * 4
     assert L.ftc_agnn_layer_backward_fused_workspace_bytes(1000, 5000, 32) > 1000 * 64 * 4
     assert L.ftc_agnn_layer_backward_fused_workspace_bytes(1000, 5000, 512) == 0
+
+
+def test_side_streams_are_checked_on_the_host():
+    """ftc_build_windows_concurrent: the caller's three streams and four events must be there and distinct; the
+    library keeps none of its own (the fake handles are never used: validation fails first)."""
+    L = B.lib()
+    g = B.ftc_csr(4, 10, 0x1000, 0x2000)
+    w = B.ftc_windows(16, 8, 1, 0x10, 0x20, 0x30, 0x40, 0x50, 0x60)
+    fake, big = C.c_void_p(0x1000), C.c_size_t(1 << 30)
+    side = B.ftc_side_streams()
+    assert L.ftc_build_windows_concurrent(C.byref(g), C.byref(w), fake, big, C.byref(side), None) == B.FTC_EINVAL
+    assert b"three distinct streams" in L.ftc_last_error()
+    for i in range(3):
+        side.stream[i], side.join[i] = 0x100 * (i + 1), 0x1000 * (i + 1)
+    side.fork = 0x1000                                                   # the same event twice
+    assert L.ftc_build_windows_concurrent(C.byref(g), C.byref(w), fake, big, C.byref(side), None) == B.FTC_EINVAL
+    side.fork = 0x9000
+    assert L.ftc_build_windows_concurrent(C.byref(g), C.byref(w), fake, big, C.byref(side), C.c_void_p(0x200)) \
+        == B.FTC_EINVAL                                                  # a side stream that is the caller's stream
+    assert L.ftc_build_windows_concurrent(C.byref(g), C.byref(w), None, C.c_size_t(0), C.byref(side), None) \
+        == B.FTC_EWORKSPACE
 
 
 def test_wrong_argument_count_is_rejected_by_the_binding():

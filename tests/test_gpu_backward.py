@@ -410,6 +410,29 @@ def test_agnn_fused_backward_matches_the_unfused_route_on_hub_rows():
     assert torch.all(dH_f[empty] == 0) and torch.all(row_z[empty] == 0)
 
 
+def test_single_pass_backward_reports_a_pattern_that_is_not_symmetric(graphs):
+    """The single-pass route holds on a symmetric pattern only.  Given the flag of ftc_transpose_index it turns
+    the gradients of a non-symmetric graph into NaN; on a symmetric graph the flag changes nothing."""
+    for name in ("directed", "cfg1"):
+        g = graphs[name]
+        dg = dev_graph(g)
+        win = B.ftc_build_windows(dg)
+        _, flag = B.ftc_transpose_index(dg, win)
+        Hd, _ = quantise(synth.normal_features(g.n, 32, seed=1), F16)
+        dYd, _ = quantise(synth.normal_features(g.n, 32, seed=2), F16)
+        row_z = torch.empty(g.n, dtype=F32, device="cuda")
+        Y = B.ftc_agnn_layer(dg, win, Hd, beta=1.0, row_z=row_z)
+        dH, dbeta = B.ftc_agnn_layer_backward_fused(dg, win, Hd, row_z, Y, dYd, pattern_flag=flag)
+        dH16, _ = B.ftc_agnn_layer_backward_fused(dg, win, Hd, row_z, Y, dYd, pattern_flag=flag, dh_dtype=F16)
+        if name == "directed":
+            assert int(flag.item()) == 1
+            assert bool(torch.isnan(dH).all()) and bool(torch.isnan(dbeta).all()) and bool(torch.isnan(dH16).all())
+        else:
+            assert int(flag.item()) == 0
+            dH0, dbeta0 = B.ftc_agnn_layer_backward_fused(dg, win, Hd, row_z, Y, dYd)
+            assert torch.equal(dH, dH0) and torch.equal(dbeta, dbeta0) and bool(torch.isfinite(dH).all())
+
+
 def test_backward_on_a_graph_without_entries():
     g = synth.Graph(70, np.zeros(71, dtype=np.int32), np.zeros(0, dtype=np.int32), "no_edges")
     dg = dev_graph(g)

@@ -171,6 +171,59 @@ def test_degree_stats_and_plan_from_device_numbers(graphs, name):
         assert plan["reuse"] >= 1.0 and plan["skew"] >= 1.0 - 1e-9
 
 
+# ------------------------------------------------------------------ the plan carried out
+@pytest.mark.parametrize("which", ["rmat", "sbm", "small"])
+def test_planned_graph_applies_the_plan_and_keeps_the_original_numbering(oracle, which):
+    """PlannedGraph: statistics -> plan -> relabelled graph.  The skewed R-MAT graph is relabelled by degree
+    class, the permuted block model gets the community trial and keeps it (its windows then share columns),
+    a graph whose features fit one L2 is left alone; in every case a GCN layer and an AGNN layer run through
+    enter() / leave() equal the oracle on the graph as given."""
+    from paper_2412_12218_amd.models import PlannedGraph
+    if which == "rmat":
+        g, dtype, D, expect = synth.config_graph(5, 1 / 16), F16, 64, "degree classes"
+    elif which == "sbm":
+        g, dtype, D, expect = synth.config_graph(4, 0.05), BF16, 64, "communities"
+    else:
+        g, dtype, D, expect = synth.config_graph(1), F16, 32, "none"
+    dg = dev_graph(g)
+    pl = PlannedGraph(dg, D, dtype)
+    say(f"planned {which}: n={g.n} nnz={g.nnz} plan={pl.plan} applied={pl.applied} sum_uniq {pl.sum_uniq_given} -> {pl.sum_uniq}")
+    assert pl.applied == expect
+    if which == "sbm":
+        assert pl.sum_uniq < 0.98 * pl.sum_uniq_given
+    _, dinv = B.ftc_gcn_norm(pl.g, pl.win, want_vals=False)
+    Xd, X64 = quantise(synth.uniform_features(g.n, D, seed=9), dtype)
+    Wd, W64 = quantise(synth.glorot_uniform(D, 16, seed=10), dtype)
+    out = pl.leave(B.ftc_gcn_layer(pl.g, pl.win, None, pl.enter(Xd), Wd, relu=True, dinv=dinv))
+    _, dinv64 = oracle.gcn_norm(g.row_ptr, g.col_idx)
+    d32 = dinv64.astype(np.float32).astype(np.float64)
+    rows = np.repeat(np.arange(g.n), np.diff(g.row_ptr))
+    ref, ab = oracle.gcn_layer(g.row_ptr, g.col_idx, d32[rows] * d32[g.col_idx], X64, W64, relu=True)
+    err = norm_err(out, ref, ab)
+    say(f"  gcn layer on the planned graph: err {err:.3e}")
+    assert err < TOL[dtype]
+    Hd, H64 = quantise(synth.normal_features(g.n, D, seed=11), dtype)
+    ref, ab, _ = oracle.agnn_layer(g.row_ptr, g.col_idx, H64, 1.0)
+    out = pl.leave(B.ftc_agnn_layer(pl.g, pl.win, pl.enter(Hd)))
+    err = norm_err(out, ref, ab)
+    say(f"  agnn layer on the planned graph: err {err:.3e}")
+    assert err < TOL[dtype]
+
+
+def test_planned_graph_drops_a_community_trial_that_does_not_help():
+    """The block model once more, this time already in community order (the graph the first plan produced):
+    the plan proposes the trial again (the statistics cannot see the order), the relabelled windows share no
+    more columns than before, and the graph stays as it is."""
+    from paper_2412_12218_amd.models import PlannedGraph
+    g = synth.config_graph(4, 0.05)
+    first = PlannedGraph(dev_graph(g), 64, BF16)
+    assert first.applied == "communities"
+    pl = PlannedGraph(first.g, 64, BF16)
+    say(f"planned twice: plan={pl.plan} applied={pl.applied} trial={getattr(pl, 'trial', None)}")
+    assert pl.plan["reorder"] == B.FTC_ORDER_COMMUNITIES
+    assert pl.applied == "none" and pl.trial["kept"] is False and pl.perm is None and pl.g is first.g
+
+
 # ------------------------------------------------------------------ community ordering
 def sbm_small():
     return synth.sbm(12, 200, 14 * 12 * 200, 2 * 12 * 200, seed=5)
