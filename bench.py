@@ -87,10 +87,22 @@ def cpu_baseline(scale, seed, g=None):
                       f"same recipe as the workload, {dt:.1f} s"}
 
 
-def kernel_suite(tag, g, feat32, dtype, D, iters=20, oracle=False):
+def fabric_bytes(key):
+    """Counter-measured L2 <-> fabric bytes per launch (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a copy of
+    known size) from the committed summary; None where no profile covers the kernel."""
+    path = os.path.join(ROOT, "profiles", "fabric_traffic.json")
+    if not os.path.exists(path):
+        return None
+    with open(path) as f:
+        return json.load(f).get(key)
+
+
+def kernel_suite(tag, g, feat32, dtype, D, iters=20, oracle=False, ops=("spmm", "sddmm", "softmax")):
     """Stand-alone SpMM / SDDMM / edge-softmax timings on one graph (events on the launch stream), warm (back to
-    back) and cold (a 1 GiB buffer is overwritten between launches so that neither L2 nor the
-    memory-side cache holds X).  Returns a dict of ms and algorithmic GB/s."""
+    back) and cold (a 1 GiB buffer is overwritten between launches).  Per operation three byte counts: `alg`
+    (what the method moves: one gathered row per distinct window column, every index / value / output once),
+    `compulsory` (every array once: the lower bound no access order can beat) and `fabric` (what the counters
+    saw between L2 and the fabric; reads served by the memory-side cache count there as well as reads from HBM)."""
     import numpy as np
     import torch
     from paper_2412_12218_amd import binding as B
@@ -110,6 +122,9 @@ def kernel_suite(tag, g, feat32, dtype, D, iters=20, oracle=False):
     nbytes = {"spmm": sum_uniq * D * e + g.nnz * 8 + g.n * D * 4 + rp,
               "sddmm": sum_uniq * D * e + g.n * D * e + g.nnz * 8 + rp,
               "softmax": g.nnz * 8 + rp}
+    compulsory = {"spmm": g.n * D * e + g.nnz * 8 + g.n * D * 4 + rp,     # X, column ids + values, output, row starts
+                  "sddmm": g.n * D * e + g.nnz * 8 + rp,                  # X (= Y), column ids + scores, row starts
+                  "softmax": g.nnz * 8 + rp}
     ws_sm = B._workspace(B.lib().ftc_edge_softmax_workspace_bytes(g.n, g.nnz), dev)
     p_out = torch.empty(g.nnz, dtype=torch.float32, device=dev)
     fns = {"spmm": lambda: B.ftc_spmm(dg, win, vals, X, out=out, ws=ws),
@@ -117,8 +132,11 @@ def kernel_suite(tag, g, feat32, dtype, D, iters=20, oracle=False):
            "sddmm": lambda: B.ftc_sddmm(dg, win, X, X, None, None, 1.0, out=s_out, ws=ws, cosine=True),
            # edge softmax over the scores the SDDMM has just written
            "softmax": lambda: B.ftc_edge_softmax(dg, win, s_out, out=p_out, ws=ws_sm)}
-    res = {"graph": tag, "n": g.n, "nnz": g.nnz, "sum_uniq": sum_uniq, "D": D, "dtype": str(dtype)[6:]}
+    res = {"graph": tag, "n": g.n, "nnz": g.nnz, "sum_uniq": sum_uniq, "D": D, "dtype": str(dtype)[6:],
+           "feature_matrix_MB": g.n * D * e / 1e6}
     for op, fn in fns.items():
+        if op not in ops:
+            continue
         for _ in range(5):
             fn()
         for mode in ("warm", "cold"):
@@ -138,6 +156,8 @@ def kernel_suite(tag, g, feat32, dtype, D, iters=20, oracle=False):
             res[f"{op}_{mode}_GBs"] = nbytes[op] / (ms * 1e-3) / 1e9
             res[f"{op}_{mode}_frac"] = nbytes[op] / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS
         res[f"{op}_alg_bytes"] = nbytes[op]
+        res[f"{op}_compulsory_bytes"] = compulsory[op]
+        res[f"{op}_fabric_bytes"] = fabric_bytes(f"{tag.split()[0]}_D{D}_{op}")
     if oracle:
         del X, out, s_out, p_out, flush, ws, ws_sm
         res["oracle"] = oracle_kernel_times(g, feat32, dtype, nbytes)
@@ -412,8 +432,7 @@ def main():
             b.record()
             calls.append((name, a, b, bracket_all))
 
-        timed("build_windows", lambda: B._check(L.ftc_build_windows(
-            C.byref(dg.c), C.byref(hp.win.c), B._ptr(hp.ws_win), C.c_size_t(hp.ws_win.numel()), B._stream())))
+        timed("build_windows", lambda: B.ftc_build_windows_concurrent(dg, hp.side, out=hp.win, ws=hp.ws_win))
         timed("gcn_norm", lambda: B._check(L.ftc_gcn_norm(
             C.byref(dg.c), C.byref(hp.win.c), None, B._ptr(hp.dinv), B._stream())))
         timed("gcn_layer1", lambda: B.ftc_gcn_layer(dg, hp.win, None, X, W1, relu=True, out=hp.gcn_h, ws=hp.ws,
@@ -462,6 +481,8 @@ def main():
                                "fp16 features Nx128, GCN 128-16-8, AGNN 128-32x4-8, fp32 accumulate"},
         "roofline": {"bound": "hbm", "kernel": "agnn_fused_kernel + agnn_fused_fixup_kernel (call ftc_agnn_layer)", "achieved": dom_gbs,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": dom_gbs / HBM_PEAK_GBS, "traffic": None,
+                     "traffic_kind": "bytes between L2 and the fabric per launch (FETCH_SIZE x 2 + WRITE_SIZE); the 64 MB "
+                                     "feature matrix fits the memory-side cache, so most of these reads never reach HBM",
                      "alg_bytes_per_launch": dom_bytes, "avg_ms": avg_ms[dom]},
         "gcn_2layer_ms": avg_ms["gcn_layer1"] + avg_ms["gcn_layer2"],
         "agnn_layer_ms": avg_ms["agnn_layer"],
@@ -478,11 +499,10 @@ def main():
     calib_dst.copy_(calib_src)
     torch.cuda.synchronize()
     del calib_src, calib_dst
-    # HBM traffic of the dominant kernel from the committed counter summary (separate profiler runs)
-    traffic_file = os.path.join(ROOT, "profiles", "hbm_traffic.json")
-    if os.path.exists(traffic_file):
-        with open(traffic_file) as f:
-            out["roofline"]["traffic"] = json.load(f).get("agnn_fused_kernel_bytes_per_launch")
+    # L2 <-> fabric traffic of the dominant kernel from the committed counter summary (separate profiler runs)
+    out["roofline"]["traffic"] = fabric_bytes("cfg5_agnn_fused_kernel")
+    if out["roofline"]["traffic"]:
+        out["roofline"]["achieved_by_traffic"] = out["roofline"]["traffic"] / (avg_ms[dom] * 1e-3) / 1e9
     # the same step captured once as a HIP graph and replayed (one launch per step instead of ~45)
     graph = hp.capture(X, W1, W2, Win, Wout, betas)
     for _ in range(args.warmup):
@@ -495,18 +515,16 @@ def main():
     out["graph_replay_ms_per_step"] = (time.perf_counter() - t0) / args.steps * 1e3
     del graph
     if not args.no_reordered:
-        # the same step on the graph relabelled by degree class (one-time preprocessing, timed separately):
-        # reported beside the benchmark value, which stays the graph as given
-        ws_ro = B._workspace(L.ftc_reorder_workspace_bytes(g.n, g.nnz), dev)
-        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-        ev[0].record()
-        perm, inv = B.ftc_degree_order(dg, B.FTC_ORDER_DEGREE_CLASSES, ws=ws_ro)
-        pg, flag = B.ftc_permute_graph(dg, perm, inv, ws=ws_ro)
-        Xp = B.ftc_permute_rows(X, perm)
-        ev[1].record()
-        ev[1].synchronize()
-        assert int(flag.item()) == 0
-        hp2 = HotPath(pg)
+        # the same step on the graph as the per-graph plan prepares it (statistics -> ftc_plan_graph -> relabelling;
+        # one-time preprocessing, timed separately): reported beside the benchmark value, which stays the graph as given
+        from paper_2412_12218_amd.models import PlannedGraph
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        pl = PlannedGraph(dg, 32, torch.float16, side=hp.side)
+        Xp = pl.enter(X)
+        torch.cuda.synchronize()
+        prep_ms = (time.perf_counter() - t0) * 1e3
+        hp2 = HotPath(pl.g)
         for _ in range(args.warmup):
             hp2.step(Xp, W1, W2, Win, Wout, betas)
         torch.cuda.synchronize()
@@ -515,11 +533,11 @@ def main():
             hp2.step(Xp, W1, W2, Win, Wout, betas)
         torch.cuda.synchronize()
         ms2 = (time.perf_counter() - t0) / args.steps * 1e3
-        su2 = int(hp2.win.summary[0].item())
-        out["reordered"] = {"ordering": "degree classes (ftc_degree_order + ftc_permute_graph + ftc_permute_rows)",
-                            "preprocessing_ms": ev[0].elapsed_time(ev[1]), "ms_per_step": ms2, "sum_uniq": su2,
-                            "speedup_vs_as_given": ms_per_step / ms2}
-        del hp2, pg, Xp, ws_ro
+        out["reordered"] = {"plan": pl.plan, "applied": pl.applied,
+                            "preprocessing_ms": prep_ms, "ms_per_step": ms2, "sum_uniq": pl.sum_uniq,
+                            "speedup_vs_as_given": ms_per_step / ms2,
+                            "break_even_steps": prep_ms / (ms_per_step - ms2) if ms2 < ms_per_step else None}
+        del hp2, pl, Xp
     if not args.no_kernels:
         # the two largest graphs: stand-alone aggregation and edge-score kernels, fp32 output
         k5 = kernel_suite("cfg5 R-MAT", g, synth.normal_features(g.n, 32, seed + 20), torch.float16, 32,
@@ -527,7 +545,11 @@ def main():
         g4 = synth.config_graph(4) if args.scale == 20 else synth.config_graph(4, 2.0 ** (args.scale - 20))
         k4 = kernel_suite("cfg4 SBM", g4, synth.uniform_features(g4.n, 64, 3 + 20), torch.bfloat16, 64,
                           oracle=args.cpu_scale > 0)
-        out["kernels"] = [k4, k5]
+        # the same graph with a feature matrix of 512 MB, twice the memory-side cache: what the gather kernels do
+        # when the rows have to come from HBM
+        k4big = kernel_suite("cfg4 SBM", g4, synth.uniform_features(g4.n, 256, 3 + 21), torch.bfloat16, 256,
+                             ops=("spmm", "sddmm"))
+        out["kernels"] = [k4, k5, k4big]
     if args.cpu_scale > 0:
         out["cpu_baseline"] = cpu_baseline(args.cpu_scale, seed, g if args.cpu_scale == args.scale else None)
     print(json.dumps(out))
