@@ -3,14 +3,15 @@
 // Every row window is independent (the paper parallelises the same step over CPU threads).  How
 // a window is condensed depends on its edge count, because power-law graphs have windows of a
 // few edges next to windows of 10^5:
-//   1. up to WAVE_CAP edges (almost every window): one wave sorts the column ids in registers
-//      with a bitonic network (lane shuffles, no barriers), de-duplicates with a flag scan and
-//      finds every edge's rank by binary search in the unique list parked in LDS;
-//   2. up to the hub threshold: one workgroup per window walks the column space in ranges of
-//      2^RL ids with a bitmap of one range in LDS: set bits, prefix sums of the words'
-//      popcounts, rank = word prefix + popcount below the column's bit.  The bitmap is small
-//      (16 KiB for 2^17 ids) so that several workgroups share a CU and hide each other's
-//      latencies; the window's column ids stay in registers between the passes when they fit;
+//   1. up to WAVE_CAP edges: one wave sorts the column ids in registers with a bitonic network
+//      (lane shuffles, no barriers), de-duplicates with a flag scan and finds every edge's rank by
+//      binary search in the unique list parked in LDS;
+//   2. up to MID_CAP edges: one wave per window with a two-level bitmap in LDS (a coarse bitmap
+//      names the 32-column words the window touches, the fine bitmap holds one word per touched
+//      word): set bits, prefix sums of the popcounts, rank = prefix of the word + bits below the
+//      column's own.  The wave keeps its column ids in registers and never meets a workgroup
+//      barrier; a CU works on as many windows at once as their bitmaps fit into its LDS;
+//   2b. up to the hub threshold: the same two-level bitmap, one workgroup of 1024 threads per window;
 //   3. hub windows (more edges than the threshold, at most HUB_SLOTS_MAX of them by the choice
 //      of the threshold): edge-parallel over the whole GPU with one bitmap of n bits per hub in
 //      global memory: set bits (atomics), one workgroup per hub turns popcounts into prefixes
@@ -24,15 +25,18 @@
 
 namespace ftc {
 
-constexpr int WAVE_CAP = 1024;      // edges per window sorted by a single wave in registers
-constexpr int MID_CAP = 4096;       // edges per window condensed by a 256-thread workgroup
+constexpr int WAVE_CAP = 256;       // edges per window sorted by a single wave in registers
+constexpr int B1_CAP = 1024;        // edges per window of the three size classes of the wave-level bitmap kernel
+constexpr int B2_CAP = 2048;
+constexpr int MID_CAP = 4096;
+constexpr int B4_CAP = 16384;       // ... and of the same kernel with four waves per window
 constexpr int HUB_MIN_EDGES = 16384;
 constexpr int HUB_SLOTS_MAX = 1024; // hub windows handled at once (one thread each in the planning kernel)
 constexpr int HUB_CHUNK = 4096;     // edges per work item of the edge-parallel hub kernels
 constexpr int HUB_GROUP = 8;        // bitmap words per stored prefix (one 32-byte load)
 constexpr int HUB_GRID = 2048;      // workgroups of the edge-parallel hub kernels (grid-stride over chunks)
 
-enum { C_MID = 0, C_LARGE = 1, C_HUB = 2, C_CHUNKS = 3, C_MID_NEXT = 4, C_LARGE_NEXT = 5, C_WORDS = 8 };
+enum { C_B1 = 0, C_B2 = 1, C_B3 = 2, C_B4 = 3, C_LARGE = 4, C_HUB = 5, C_CHUNKS = 6, C_LARGE_NEXT = 7, C_WORDS = 16 };
 
 // A window is a hub when it has more edges than this.  The three terms keep (a) small windows in
 // LDS, (b) a hub's bitmap (n / 8 bytes) below four bytes per edge of the hub, (c) the number of
@@ -55,8 +59,9 @@ constexpr int PACK_PER_WAVE = 1024;  // entries of win_cols that one wave of the
 
 struct WinWorkspace {
     int *uniq_count;      // [n_windows]
-    int *list_mid;        // [cap_mid]    windows of WAVE_CAP+1 .. MID_CAP edges
-    int *list_large;      // [cap_large]  windows of MID_CAP+1 .. threshold edges
+    int4 *list_b[4];      // [cap_b[i]]   windows of WAVE_CAP+1 .. B1_CAP, .. B2_CAP, .. MID_CAP, .. B4_CAP edges:
+                          //              {window, first edge, edges, -}
+    int *list_large;      // [cap_large]  windows of B4_CAP+1 .. threshold edges
     int *list_hub;        // [slots]
     int *counters;        // [C_WORDS]
     int *hub_chunk_ptr;   // [slots + 1]  first work item of every hub
@@ -65,7 +70,7 @@ struct WinWorkspace {
     int *hub_grp;         // [slots * words_per_slot / HUB_GROUP]
     int *tmp_cols;        // [nnz]
     int *pack_win;        // [nnz / PACK_PER_WAVE + 2]  window of every PACK_PER_WAVE-th entry of win_cols
-    int cap_mid, cap_large, slots, wps;
+    int cap_b[4], cap_large, slots, wps;
     size_t total;
 };
 
@@ -79,12 +84,13 @@ static WinWorkspace carve(void *ws, int n, int nnz, int n_windows)
         off += align_up(bytes, 256);
         return q;
     };
-    w.cap_mid = nnz / (WAVE_CAP + 1) + 1 < n_windows ? nnz / (WAVE_CAP + 1) + 1 : n_windows;
-    w.cap_large = nnz / (MID_CAP + 1) + 1 < n_windows ? nnz / (MID_CAP + 1) + 1 : n_windows;
+    const int lower[4] = {WAVE_CAP, B1_CAP, B2_CAP, MID_CAP};
+    for (int i = 0; i < 4; ++i) w.cap_b[i] = nnz / (lower[i] + 1) + 1 < n_windows ? nnz / (lower[i] + 1) + 1 : n_windows;
+    w.cap_large = nnz / (B4_CAP + 1) + 1 < n_windows ? nnz / (B4_CAP + 1) + 1 : n_windows;
     w.slots = hub_slots(n, nnz);
     w.wps = hub_words_per_slot(n);
     w.uniq_count = reinterpret_cast<int *>(take(sizeof(int) * static_cast<size_t>(n_windows)));
-    w.list_mid = reinterpret_cast<int *>(take(sizeof(int) * static_cast<size_t>(w.cap_mid)));
+    for (int i = 0; i < 4; ++i) w.list_b[i] = reinterpret_cast<int4 *>(take(sizeof(int4) * static_cast<size_t>(w.cap_b[i])));
     w.list_large = reinterpret_cast<int *>(take(sizeof(int) * static_cast<size_t>(w.cap_large)));
     w.list_hub = reinterpret_cast<int *>(take(sizeof(int) * static_cast<size_t>(w.slots)));
     w.counters = reinterpret_cast<int *>(take(sizeof(int) * C_WORDS));
@@ -175,28 +181,35 @@ __device__ __forceinline__ int row_of_edge(const int *rp, int rows, int e)
 // entries of a workgroup are numbered in LDS first): thousands of atomics on one address would
 // serialise.
 __global__ __launch_bounds__(1024) void win_classify_kernel(int n, int n_windows, const int *__restrict__ row_ptr,
-                                                            int blk_h, int hub_thr, int *__restrict__ list_mid,
-                                                            int *__restrict__ list_large,
+                                                            int blk_h, int hub_thr, int4 *__restrict__ list_b1,
+                                                            int4 *__restrict__ list_b2, int4 *__restrict__ list_b3,
+                                                            int4 *__restrict__ list_b4, int *__restrict__ list_large,
                                                             int *__restrict__ list_hub, int *counters)
 {
-    __shared__ int cnt_s[3], base_s[3];
-    if (threadIdx.x < 3) cnt_s[threadIdx.x] = 0;
+    __shared__ int cnt_s[6], base_s[6];
+    if (threadIdx.x < 6) cnt_s[threadIdx.x] = 0;
     __syncthreads();
     const int w = blockIdx.x * 1024 + threadIdx.x;
-    int cls = -1, pos = 0;
+    int cls = -1, pos = 0, e0 = 0, cnt = 0;
     if (w < n_windows) {
         const int r0 = w * blk_h;
-        const int cnt = row_ptr[min(n, r0 + blk_h)] - row_ptr[r0];
-        if (cnt > WAVE_CAP) cls = cnt <= MID_CAP ? 0 : (cnt <= hub_thr ? 1 : 2);
+        e0 = row_ptr[r0];
+        cnt = row_ptr[min(n, r0 + blk_h)] - e0;
+        if (cnt > WAVE_CAP)
+            cls = cnt <= B1_CAP ? 0 : (cnt <= B2_CAP ? 1 : (cnt <= MID_CAP ? 2 : (cnt <= hub_thr ? (cnt <= B4_CAP ? 3 : 4) : 5)));
     }
     if (cls >= 0) pos = atomicAdd(&cnt_s[cls], 1);
     __syncthreads();
-    if (threadIdx.x < 3 && cnt_s[threadIdx.x] > 0)
-        base_s[threadIdx.x] = atomicAdd(&counters[threadIdx.x], cnt_s[threadIdx.x]);  // C_MID, C_LARGE, C_HUB
+    if (threadIdx.x < 6 && cnt_s[threadIdx.x] > 0)
+        base_s[threadIdx.x] = atomicAdd(&counters[threadIdx.x], cnt_s[threadIdx.x]);  // C_B1 .. C_HUB
     __syncthreads();
-    if (cls == 0) list_mid[base_s[0] + pos] = w;
-    else if (cls == 1) list_large[base_s[1] + pos] = w;
-    else if (cls == 2) list_hub[base_s[2] + pos] = w;
+    // the bitmap kernels get the window's first edge and edge count with its id: one dependent load less per window
+    if (cls == 0) list_b1[base_s[0] + pos] = make_int4(w, e0, cnt, 0);
+    else if (cls == 1) list_b2[base_s[1] + pos] = make_int4(w, e0, cnt, 0);
+    else if (cls == 2) list_b3[base_s[2] + pos] = make_int4(w, e0, cnt, 0);
+    else if (cls == 3) list_b4[base_s[3] + pos] = make_int4(w, e0, cnt, 0);
+    else if (cls == 4) list_large[base_s[4] + pos] = w;
+    else if (cls == 5) list_hub[base_s[5] + pos] = w;
 }
 
 // ---- windows of at most WAVE_CAP edges: one wave, keys in registers --------------------------------
@@ -310,7 +323,7 @@ __global__ __launch_bounds__(64) void win_wave_kernel(int n, const int *__restri
     for (int t = threadIdx.x; t <= rows; t += 64) rp[t] = row_ptr[r0 + t];
     __syncthreads();
     const int cnt = rp[rows] - rp[0];
-    if (cnt > WAVE_CAP) return;  // queued by the classification kernel for the workgroup kernels
+    if (cnt > WAVE_CAP) return;  // queued by the classification kernel for the bitmap kernels
     if (cnt == 0) {
         if (threadIdx.x == 0) uniq_count[w] = 0;
         return;
@@ -318,12 +331,249 @@ __global__ __launch_bounds__(64) void win_wave_kernel(int n, const int *__restri
 #define FTC_WAVE(E) condense_window_wave<E>(w, r0, rows, rp, cnt, col_idx, edge_to_row, edge_to_col, uniq_count, tmp_cols, uniq_lds)
     if (cnt <= 64) FTC_WAVE(1);
     else if (cnt <= 128) FTC_WAVE(2);
-    else if (cnt <= 256) FTC_WAVE(4);
-    else if (cnt <= 512) FTC_WAVE(8);
-    else FTC_WAVE(16);
+    else FTC_WAVE(4);
 #undef FTC_WAVE
 }
 
+
+// ---- windows of WAVE_CAP + 1 .. MID_CAP edges: one wave, two-level bitmap in LDS -------------------
+// LDS operations of one wave execute in order; the fences keep the compiler from moving LDS reads
+// above the writes of other lanes they depend on.
+__device__ __forceinline__ void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+constexpr int WB_RANGE_LOG2 = 20;                     // column ids per pass over the coarse bitmap
+constexpr int WB_CW = (1 << WB_RANGE_LOG2) / 1024;    // its words: one bit per 32-column word of the range
+
+// One wave condenses one window of at most F edges; the window's column ids (F / 64 per lane) and the
+// slots they fall into stay in registers.  Per range of 2^20 column ids:
+//   A. coarse bitmap: which 32-column words does the window touch (at most one per edge, so at most F);
+//   B. prefix sums of its popcounts number the touched words in ascending order (their "slots");
+//   C. fine bitmap, one word per slot: set bits, prefix sums of the popcounts, rank of an edge =
+//      prefix of its slot + bits below its own; every edge also stores its column id at its rank in
+//      the unique list (edges with the same column store the same value to the same place).
+// Lanes own 16-byte pieces of the bitmaps, piece p = lane + 64 q: the LDS accesses of a step touch 64
+// consecutive pieces (no bank conflicts) and a step's prefix is one scan over the lanes.
+// A persistent grid of single-wave workgroups that walks the queue with a stride of the grid size: a
+// ticket counter (one atomic per window on a single address) would serialise tens of thousands of
+// waves, 12 ns each, and the windows of a queue differ in size by at most a factor of four.
+template <int F, int NW>
+__global__ __launch_bounds__(64 * NW) void win_bitmap_wave_kernel(int n, int nnz, const int *__restrict__ row_ptr,
+                                                                  const int *__restrict__ col_idx, int blk_h,
+                                                                  int *__restrict__ edge_to_row,
+                                                                  int *__restrict__ edge_to_col,
+                                                                  int *__restrict__ uniq_count,
+                                                                  int *__restrict__ tmp_cols,
+                                                                  const int4 *__restrict__ list,
+                                                                  const int *__restrict__ count)
+{
+    constexpr int NT = 64 * NW;
+    constexpr int EPL = F / NT;              // edges per lane
+    constexpr int NWC = NW < 4 ? NW : 4;     // waves that scan the coarse bitmap (it has 256 pieces)
+    constexpr int CPW = WB_CW / 4 / NWC;     // its pieces per scanning wave ...
+    constexpr int CP = CPW / 64;             // ... and per lane
+    constexpr int FPW = F / 4 / NW;          // pieces of the fine bitmap per wave ...
+    constexpr int FP = FPW / 64;             // ... and per lane
+    static_assert(CP >= 1 && FP >= 1, "every lane owns at least one piece of each bitmap");
+    constexpr bool AHEAD = EPL <= 32;        // registers for the next window's column ids as well
+    __shared__ __attribute__((aligned(16))) uint32_t coarse[WB_CW];
+    __shared__ __attribute__((aligned(16))) uint16_t cpre[WB_CW];   // slots before each coarse word, inside its wave's share
+    __shared__ __attribute__((aligned(16))) uint32_t fine[F];
+    __shared__ __attribute__((aligned(16))) uint16_t fpre[F];       // unique columns before each slot, inside its wave's share
+    __shared__ int rp[65];
+    __shared__ int wtot_c[2][NWC], wtot_f[2][NW];                   // per-wave totals of the two scans (double-buffered)
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n_items = *count;
+    const int stride = static_cast<int>(gridDim.x);
+    // With one wave LDS operations execute in order and only the compiler has to be held back; with several
+    // waves the phases are separated by workgroup barriers.
+    auto sync = [&]() {
+        if constexpr (NW == 1) wave_lds_sync();
+        else __syncthreads();
+    };
+    if (wave < NWC) {
+#pragma unroll
+        for (int q = 0; q < CP; ++q)
+            *reinterpret_cast<uint4 *>(&coarse[(wave * CPW + lane + 64 * q) * 4]) = make_uint4(0u, 0u, 0u, 0u);
+    }
+#pragma unroll
+    for (int q = 0; q < FP; ++q)
+        *reinterpret_cast<uint4 *>(&fine[(wave * FPW + lane + 64 * q) * 4]) = make_uint4(0u, 0u, 0u, 0u);
+    const int n_ranges = static_cast<int>((static_cast<int64_t>(n) + (1 << WB_RANGE_LOG2) - 1) >> WB_RANGE_LOG2);
+    // Every load that names the next windows is issued a window (the queue entry: two windows) ahead, so
+    // that a window's own work starts with its column ids already in registers.
+    int item = static_cast<int>(blockIdx.x);
+    if (item >= n_items) return;
+    int4 ent = list[item];
+    int4 ent1 = list[min(item + stride, n_items - 1)];  // beyond the queue: the last entry once more, never used
+    // Unconditional loads from clamped addresses, so that they are issued back to back (a branch around each
+    // load makes the compiler wait for the previous one); which of them belong to the window is decided at use.
+    auto load_cols = [&](const int4 &en, int (&c)[EPL]) {
+#pragma unroll
+        for (int k = 0; k < EPL; ++k) c[k] = col_idx[min(en.y + k * NT + tid, nnz - 1)];
+    };
+    // row starts of a window (for edge_to_row): thread r holds the start of row r, thread 0 also the 65th value
+    // of a window of 64 rows; loaded a window ahead like the column ids
+    auto load_starts = [&](const int4 &en, int &a, int &b) {
+        const int r0 = en.x * blk_h;
+        const int rows = min(n, r0 + blk_h) - r0;
+        a = row_ptr[min(r0 + (tid & 63), n)];  // beyond the window's rows: never used
+        b = row_ptr[min(r0 + 64, n)];
+    };
+    int col[EPL], col_ahead[AHEAD ? EPL : 1];
+    int st_a = 0, st_b = 0, st_a_ahead = 0, st_b_ahead = 0;
+    load_cols(ent, col);
+    load_starts(ent, st_a, st_b);
+    int parity = 0;
+    for (; item < n_items; item += stride) {  // uniform
+        const int w = ent.x, e0 = ent.y, cnt = min(ent.z, F);
+        const int r0 = w * blk_h;
+        const int rows = min(n, r0 + blk_h) - r0;
+        sync();  // the previous window is done with rp; the clearing of the bitmaps is complete
+        if (tid < 64) rp[tid] = st_a;
+        if (tid == 0) rp[64] = st_b;
+        __builtin_amdgcn_sched_barrier(0);  // the loads for the windows ahead are issued after this, not waited for here
+        const int4 ent2 = list[min(item + 2 * stride, n_items - 1)];
+        if (item + stride < n_items) {  // uniform
+            if constexpr (AHEAD) load_cols(ent1, col_ahead);
+            load_starts(ent1, st_a_ahead, st_b_ahead);
+        }
+        int base = 0;  // unique columns found so far
+        for (int range = 0; range < n_ranges; ++range) {
+            const int lo = range << WB_RANGE_LOG2;
+            if (NW > 1 && range > 0) __syncthreads();  // the clearing after the previous range is complete
+            // A. coarse bits
+            bool any = false;
+#pragma unroll
+            for (int k = 0; k < EPL; ++k) {
+                int ck = k * NT + tid < cnt ? col[k] : -1;
+                asm volatile("" : "+v"(ck));  // what is derived from a column id is recomputed in every phase, not kept in registers
+                const unsigned c = static_cast<unsigned>(ck - lo);
+                if (ck >= 0 && c < (1u << WB_RANGE_LOG2)) {
+                    atomicOr(&coarse[c >> 10], 1u << ((c >> 5) & 31));
+                    any = true;
+                }
+                if ((k & 7) == 7) __builtin_amdgcn_sched_barrier(0);  // eight edges at a time: bounds the registers in flight
+            }
+            bool some;
+            if constexpr (NW == 1) {
+                wave_lds_sync();
+                some = __builtin_amdgcn_ballot_w64(any) != 0ull;
+            } else {
+                some = __syncthreads_or(any ? 1 : 0) != 0;
+            }
+            if (!some) continue;  // none of the window's columns lies in this range (uniform)
+            // B. number the touched words: every wave scans its share, the shares are joined through the wave totals
+            int carry = 0;
+            if (wave < NWC) {  // uniform over the wave
+#pragma unroll
+                for (int q = 0; q < CP; ++q) {
+                    const int p = wave * CPW + lane + 64 * q;
+                    const uint4 v = *reinterpret_cast<const uint4 *>(&coarse[p * 4]);
+                    const int c0 = __popc(v.x), c1 = c0 + __popc(v.y), c2 = c1 + __popc(v.z), mine = c2 + __popc(v.w);
+                    const int incl = wave_inclusive_scan(mine);
+                    const unsigned run = static_cast<unsigned>(carry + incl - mine);
+                    *reinterpret_cast<uint2 *>(&cpre[p * 4]) = make_uint2(run | ((run + c0) << 16), (run + c1) | ((run + c2) << 16));
+                    carry += __shfl(incl, 63, 64);
+                }
+                if (lane == 0) wtot_c[parity][wave] = carry;
+            }
+            sync();
+            int coff[NWC], n_slots = 0;  // slots before each scanning wave's share; at most one slot per edge in all
+#pragma unroll
+            for (int k = 0; k < NWC; ++k) {  // the same numbers in every lane: kept in scalar registers
+                coff[k] = n_slots;
+                n_slots += __builtin_amdgcn_readfirstlane(wtot_c[parity][k]);
+            }
+            // C. fine bits
+            auto slot_of = [&](unsigned c) {
+                const int cw = c >> 10;
+                int off = 0;
+#pragma unroll
+                for (int k = 1; k < NWC; ++k) off = (cw >> 2) >= k * CPW ? coff[k] : off;
+                return off + static_cast<int>(cpre[cw]) + __popc(coarse[cw] & ((1u << ((c >> 5) & 31)) - 1u));
+            };
+#pragma unroll
+            for (int k = 0; k < EPL; ++k) {
+                int ck = k * NT + tid < cnt ? col[k] : -1;
+                asm volatile("" : "+v"(ck));
+                const unsigned c = static_cast<unsigned>(ck - lo);
+                if (ck >= 0 && c < (1u << WB_RANGE_LOG2)) atomicOr(&fine[slot_of(c)], 1u << (c & 31));
+                if ((k & 7) == 7) __builtin_amdgcn_sched_barrier(0);
+            }
+            sync();
+            carry = 0;
+#pragma unroll
+            for (int q = 0; q < FP; ++q) {
+                if ((wave * FPW + 64 * q) * 4 < n_slots) {  // uniform over the wave
+                    const int p = wave * FPW + lane + 64 * q;
+                    const uint4 v = *reinterpret_cast<const uint4 *>(&fine[p * 4]);
+                    const int c0 = __popc(v.x), c1 = c0 + __popc(v.y), c2 = c1 + __popc(v.z), mine = c2 + __popc(v.w);
+                    const int incl = wave_inclusive_scan(mine);
+                    const unsigned run = static_cast<unsigned>(carry + incl - mine);
+                    *reinterpret_cast<uint2 *>(&fpre[p * 4]) = make_uint2(run | ((run + c0) << 16), (run + c1) | ((run + c2) << 16));
+                    carry += __shfl(incl, 63, 64);
+                }
+            }
+            if (lane == 0) wtot_f[parity][wave] = carry;
+            sync();
+            int foff[NW], range_total = 0;
+#pragma unroll
+            for (int k = 0; k < NW; ++k) {
+                foff[k] = range_total;
+                range_total += __builtin_amdgcn_readfirstlane(wtot_f[parity][k]);
+            }
+            parity ^= 1;
+#pragma unroll
+            for (int k = 0; k < EPL; ++k) {
+                int ck = k * NT + tid < cnt ? col[k] : -1;
+                asm volatile("" : "+v"(ck));
+                const unsigned c = static_cast<unsigned>(ck - lo);
+                if (ck >= 0 && c < (1u << WB_RANGE_LOG2)) {
+                    const int sl = slot_of(c);
+                    int off = 0;
+#pragma unroll
+                    for (int j = 1; j < NW; ++j) off = (sl >> 2) >= j * FPW ? foff[j] : off;
+                    const int rank = base + off + static_cast<int>(fpre[sl]) + __popc(fine[sl] & ((1u << (c & 31)) - 1u));
+                    edge_to_col[e0 + k * NT + tid] = rank;
+                    tmp_cols[e0 + rank] = ck;
+                }
+                if ((k & 7) == 7) __builtin_amdgcn_sched_barrier(0);
+            }
+            base += range_total;
+            sync();  // every lane is done reading the bitmaps
+#pragma unroll
+            for (int q = 0; q < FP; ++q)
+                if ((wave * FPW + 64 * q) * 4 < n_slots)
+                    *reinterpret_cast<uint4 *>(&fine[(wave * FPW + lane + 64 * q) * 4]) = make_uint4(0u, 0u, 0u, 0u);
+            if (wave < NWC) {
+#pragma unroll
+                for (int q = 0; q < CP; ++q)
+                    *reinterpret_cast<uint4 *>(&coarse[(wave * CPW + lane + 64 * q) * 4]) = make_uint4(0u, 0u, 0u, 0u);
+            }
+        }
+        if (tid == 0) uniq_count[w] = base;
+        sync();
+        for (int r = wave; r < rows; r += NW) {
+            const int b = min(rp[r + 1], e0 + cnt);
+            for (int e = max(rp[r], e0) + lane; e < b; e += 64) edge_to_row[e] = r0 + r;
+        }
+        ent = ent1;
+        ent1 = ent2;
+        st_a = st_a_ahead;
+        st_b = st_b_ahead;
+        if constexpr (AHEAD) {
+#pragma unroll
+            for (int k = 0; k < EPL; ++k) col[k] = col_ahead[k];
+        } else {
+            if (item + stride < n_items) load_cols(ent, col);
+        }
+    }
+}
 
 // ---- queued windows below the hub threshold: two-level bitmap in LDS ------------------------------
 // A window of c edges touches at most c of the n / 32 bitmap words of the column space, so the
@@ -926,8 +1176,8 @@ int32_t launch_build_windows(const ftc_csr &g, ftc_windows &w, void *ws, size_t 
     if (queued) {
         hipLaunchKernelGGL(win_clear_kernel, dim3(1), dim3(64), 0, s, k.counters);
         hipLaunchKernelGGL(win_classify_kernel, dim3((w.n_windows + 1023) / 1024), dim3(1024), 0, s, g.n,
-                           w.n_windows, g.row_ptr, w.blk_h, hub_thr, k.list_mid, k.list_large, k.list_hub,
-                           k.counters);
+                           w.n_windows, g.row_ptr, w.blk_h, hub_thr, k.list_b[0], k.list_b[1], k.list_b[2], k.list_b[3],
+                           k.list_large, k.list_hub, k.counters);
         st = launch_status("build_windows classify");
         if (st != FTC_OK) return st;
         side = side_in;
@@ -959,11 +1209,29 @@ int32_t launch_build_windows(const ftc_csr &g, ftc_windows &w, void *ws, size_t 
                        dim3(CAP < PER_CU * n_cu ? CAP : PER_CU * n_cu), dim3(NT), 0, STREAM, g.n, g.row_ptr,  \
                        g.col_idx, w.blk_h, w.edge_to_row, w.edge_to_col, k.uniq_count, k.tmp_cols, LIST,      \
                        k.counters + COUNTER, k.counters + NEXT)
-        if (st == FTC_OK) {
-            FTC_RANGE(256, 2048, uint16_t, 5, k.cap_mid, k.list_mid, C_MID, C_MID_NEXT, s_mid);
-            st = launch_status("build_windows compact (mid)");
-        }
+        // bitmap kernels, largest windows first; as many workgroups per CU as their LDS allows
+#define FTC_WB(F, NW, PER_CU, I, COUNTER, STREAM)                                                                    \
+    hipLaunchKernelGGL((win_bitmap_wave_kernel<F, NW>), dim3(k.cap_b[I] < PER_CU * n_cu ? k.cap_b[I] : PER_CU * n_cu), \
+                       dim3(64 * NW), 0, STREAM, g.n, g.nnz, g.row_ptr, g.col_idx, w.blk_h, w.edge_to_row, w.edge_to_col, \
+                       k.uniq_count, k.tmp_cols, k.list_b[I], k.counters + COUNTER)
         if (st == FTC_OK && g.nnz > MID_CAP) {
+            FTC_WB(16384, 16, 1, 3, C_B4, s_large);
+            st = launch_status("build_windows bitmap (4097 .. 16384 edges)");
+        }
+        if (st == FTC_OK && g.nnz > B2_CAP) {
+            FTC_WB(4096, 4, 5, 2, C_B3, s_mid);
+            st = launch_status("build_windows bitmap (2049 .. 4096 edges)");
+        }
+        if (st == FTC_OK && g.nnz > B1_CAP) {
+            FTC_WB(2048, 2, 8, 1, C_B2, s_mid);
+            st = launch_status("build_windows bitmap (1025 .. 2048 edges)");
+        }
+        if (st == FTC_OK) {
+            FTC_WB(1024, 1, 13, 0, C_B1, s_mid);
+            st = launch_status("build_windows bitmap (257 .. 1024 edges)");
+        }
+#undef FTC_WB
+        if (st == FTC_OK && g.nnz > B4_CAP && hub_thr > B4_CAP) {
             FTC_RANGE(1024, 8192, uint32_t, 1, k.cap_large, k.list_large, C_LARGE, C_LARGE_NEXT, s_large);
             st = launch_status("build_windows compact (large)");
         }
