@@ -29,14 +29,17 @@ constexpr int WAVE_CAP = 256;       // edges per window sorted by a single wave 
 constexpr int B1_CAP = 1024;        // edges per window of the three size classes of the wave-level bitmap kernel
 constexpr int B2_CAP = 2048;
 constexpr int MID_CAP = 4096;
-constexpr int B4_CAP = 16384;       // ... and of the same kernel with four waves per window
+constexpr int B4_CAP = 16384;       // ... and of the same kernel with sixteen waves per window
+constexpr int DIRECT_MAX_RANGES = 4; // graphs of up to this many 2^20-column ranges: every window above MID_CAP edges takes
+                                     // the direct-bitmap kernel (a workgroup per window, one bit per column of a range)
 constexpr int HUB_MIN_EDGES = 16384;
 constexpr int HUB_SLOTS_MAX = 1024; // hub windows handled at once (one thread each in the planning kernel)
 constexpr int HUB_CHUNK = 4096;     // edges per work item of the edge-parallel hub kernels
 constexpr int HUB_GROUP = 8;        // bitmap words per stored prefix (one 32-byte load)
 constexpr int HUB_GRID = 2048;      // workgroups of the edge-parallel hub kernels (grid-stride over chunks)
 
-enum { C_B1 = 0, C_B2 = 1, C_B3 = 2, C_B4 = 3, C_LARGE = 4, C_HUB = 5, C_CHUNKS = 6, C_LARGE_NEXT = 7, C_WORDS = 16 };
+enum { C_B1 = 0, C_B2 = 1, C_B3 = 2, C_B4 = 3, C_LARGE = 4, C_HUB = 5, C_DIRECT = 6, C_CHUNKS = 7, C_LARGE_NEXT = 8,
+       C_DIRECT_NEXT = 9, C_WORDS = 16 };
 
 // A window is a hub when it has more edges than this.  The three terms keep (a) small windows in
 // LDS, (b) a hub's bitmap (n / 8 bytes) below four bytes per edge of the hub, (c) the number of
@@ -61,6 +64,8 @@ struct WinWorkspace {
     int *uniq_count;      // [n_windows]
     int4 *list_b[4];      // [cap_b[i]]   windows of WAVE_CAP+1 .. B1_CAP, .. B2_CAP, .. MID_CAP, .. B4_CAP edges:
                           //              {window, first edge, edges, -}
+    int4 *list_direct;    // [cap_b[3]]   windows above MID_CAP edges on graphs of few column ranges (then list_b[3],
+                          //              list_large and list_hub stay empty)
     int *list_large;      // [cap_large]  windows of B4_CAP+1 .. threshold edges
     int *list_hub;        // [slots]
     int *counters;        // [C_WORDS]
@@ -91,6 +96,7 @@ static WinWorkspace carve(void *ws, int n, int nnz, int n_windows)
     w.wps = hub_words_per_slot(n);
     w.uniq_count = reinterpret_cast<int *>(take(sizeof(int) * static_cast<size_t>(n_windows)));
     for (int i = 0; i < 4; ++i) w.list_b[i] = reinterpret_cast<int4 *>(take(sizeof(int4) * static_cast<size_t>(w.cap_b[i])));
+    w.list_direct = reinterpret_cast<int4 *>(take(sizeof(int4) * static_cast<size_t>(w.cap_b[3])));
     w.list_large = reinterpret_cast<int *>(take(sizeof(int) * static_cast<size_t>(w.cap_large)));
     w.list_hub = reinterpret_cast<int *>(take(sizeof(int) * static_cast<size_t>(w.slots)));
     w.counters = reinterpret_cast<int *>(take(sizeof(int) * C_WORDS));
@@ -184,10 +190,11 @@ __global__ __launch_bounds__(1024) void win_classify_kernel(int n, int n_windows
                                                             int blk_h, int hub_thr, int4 *__restrict__ list_b1,
                                                             int4 *__restrict__ list_b2, int4 *__restrict__ list_b3,
                                                             int4 *__restrict__ list_b4, int *__restrict__ list_large,
-                                                            int *__restrict__ list_hub, int *counters)
+                                                            int *__restrict__ list_hub, int4 *__restrict__ list_direct,
+                                                            int direct, int *counters)
 {
-    __shared__ int cnt_s[6], base_s[6];
-    if (threadIdx.x < 6) cnt_s[threadIdx.x] = 0;
+    __shared__ int cnt_s[7], base_s[7];
+    if (threadIdx.x < 7) cnt_s[threadIdx.x] = 0;
     __syncthreads();
     const int w = blockIdx.x * 1024 + threadIdx.x;
     int cls = -1, pos = 0, e0 = 0, cnt = 0;
@@ -196,12 +203,13 @@ __global__ __launch_bounds__(1024) void win_classify_kernel(int n, int n_windows
         e0 = row_ptr[r0];
         cnt = row_ptr[min(n, r0 + blk_h)] - e0;
         if (cnt > WAVE_CAP)
-            cls = cnt <= B1_CAP ? 0 : (cnt <= B2_CAP ? 1 : (cnt <= MID_CAP ? 2 : (cnt <= hub_thr ? (cnt <= B4_CAP ? 3 : 4) : 5)));
+            cls = cnt <= B1_CAP ? 0
+                                : (cnt <= B2_CAP ? 1 : (cnt <= MID_CAP ? 2 : (direct ? 6 : (cnt <= hub_thr ? (cnt <= B4_CAP ? 3 : 4) : 5))));
     }
     if (cls >= 0) pos = atomicAdd(&cnt_s[cls], 1);
     __syncthreads();
-    if (threadIdx.x < 6 && cnt_s[threadIdx.x] > 0)
-        base_s[threadIdx.x] = atomicAdd(&counters[threadIdx.x], cnt_s[threadIdx.x]);  // C_B1 .. C_HUB
+    if (threadIdx.x < 7 && cnt_s[threadIdx.x] > 0)
+        base_s[threadIdx.x] = atomicAdd(&counters[threadIdx.x], cnt_s[threadIdx.x]);  // C_B1 .. C_DIRECT
     __syncthreads();
     // the bitmap kernels get the window's first edge and edge count with its id: one dependent load less per window
     if (cls == 0) list_b1[base_s[0] + pos] = make_int4(w, e0, cnt, 0);
@@ -210,6 +218,7 @@ __global__ __launch_bounds__(1024) void win_classify_kernel(int n, int n_windows
     else if (cls == 3) list_b4[base_s[3] + pos] = make_int4(w, e0, cnt, 0);
     else if (cls == 4) list_large[base_s[4] + pos] = w;
     else if (cls == 5) list_hub[base_s[5] + pos] = w;
+    else if (cls == 6) list_direct[base_s[6] + pos] = make_int4(w, e0, cnt, 0);
 }
 
 // ---- windows of at most WAVE_CAP edges: one wave, keys in registers --------------------------------
@@ -572,6 +581,128 @@ __global__ __launch_bounds__(64 * NW) void win_bitmap_wave_kernel(int n, int nnz
         } else {
             if (item + stride < n_items) load_cols(ent, col);
         }
+    }
+}
+
+// ---- windows above MID_CAP edges: one workgroup, one bit per column of a 2^20-column range in LDS -----------
+// With this many edges the window touches a good part of the 32768 bitmap words of a range anyway, so the bitmap
+// is kept whole (128 KiB of the CU's 160) and the coarse level drops out: set bits, prefix sums of the popcounts
+// per 16-byte piece (each of the 16 waves scans a sixteenth, joined through the wave totals), rank of an edge =
+// prefix of its piece + bits below its own, unique list written by the edges at their rank.  A window can have
+// any number of edges (its column ids are read again in the second phase, from L2), so this one kernel takes
+// what the two-level workgroup kernel and the edge-parallel hub kernels take on graphs of many column ranges,
+// where a pass over all edges per range would cost too much.  Windows come from a ticket counter (a few hundred
+// to a few thousand queue entries, very different in size).
+constexpr int DB_WORDS = (1 << WB_RANGE_LOG2) / 32;  // bitmap words per range
+constexpr int DB_PIECES = DB_WORDS / 4;
+__global__ __launch_bounds__(1024) void win_direct_kernel(int n, const int *__restrict__ row_ptr,
+                                                          const int *__restrict__ col_idx, int blk_h,
+                                                          int *__restrict__ edge_to_row, int *__restrict__ edge_to_col,
+                                                          int *__restrict__ uniq_count, int *__restrict__ tmp_cols,
+                                                          const int4 *__restrict__ list, const int *__restrict__ count,
+                                                          int *next_ticket)
+{
+    constexpr int NT = 1024, NW = 16;
+    constexpr int PW = DB_PIECES / NW;  // pieces per wave: 512
+    constexpr int PL = PW / 64;         // ... and per lane: 8
+    constexpr int EB = 8;               // edges per thread and batch
+    __shared__ __attribute__((aligned(16))) uint32_t bits[DB_WORDS];
+    __shared__ uint16_t pre[DB_PIECES];  // unique columns before each piece, inside its wave's share (below 65536)
+    __shared__ int wtot[NW], woff[NW + 1];  // unique columns of every wave's share, and before it
+    __shared__ int rp[65];
+    __shared__ int next_s;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n_items = *count;
+#pragma unroll
+    for (int q = 0; q < PL; ++q) *reinterpret_cast<uint4 *>(&bits[(wave * PW + lane + 64 * q) * 4]) = make_uint4(0u, 0u, 0u, 0u);
+    const int n_ranges = static_cast<int>((static_cast<int64_t>(n) + (1 << WB_RANGE_LOG2) - 1) >> WB_RANGE_LOG2);
+    for (int item = blockIdx.x; item < n_items;) {  // uniform
+        int ticket = 0;
+        if (tid == 0) ticket = atomicAdd(next_ticket, 1) + static_cast<int>(gridDim.x);
+        const int4 ent = list[item];
+        const int w = ent.x, e0 = ent.y, cnt = ent.z;
+        const int r0 = w * blk_h;
+        const int rows = min(n, r0 + blk_h) - r0;
+        __syncthreads();  // the previous window is done with rp; the clearing of the bitmap is complete
+        if (tid <= rows) rp[tid] = row_ptr[r0 + tid];
+        // f(column, index of the edge inside the window) for every edge, EB loads in flight per thread
+        auto for_edges = [&](auto f) {
+            for (int ib = tid; ib < cnt; ib += NT * EB) {
+                int c8[EB];
+#pragma unroll
+                for (int j = 0; j < EB; ++j) {
+                    const int i = ib + j * NT;
+                    c8[j] = i < cnt ? col_idx[e0 + i] : -1;
+                }
+#pragma unroll
+                for (int j = 0; j < EB; ++j) f(c8[j], ib + j * NT);
+            }
+        };
+        int base = 0;
+        for (int range = 0; range < n_ranges; ++range) {
+            const int lo = range << WB_RANGE_LOG2;
+            if (range > 0) __syncthreads();  // the clearing after the previous range is complete
+            bool any = false;
+            for_edges([&](int col, int) {
+                const unsigned c = static_cast<unsigned>(col - lo);
+                if (col >= 0 && c < (1u << WB_RANGE_LOG2)) {
+                    // the popular columns of a large window are hit thousands of times and atomics on one address
+                    // serialise: the word is read first and the atomic skipped when the bit is there (bits are only set)
+                    uint32_t *p = &bits[c >> 5];
+                    const uint32_t m = 1u << (c & 31);
+                    if ((__hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) & m) == 0u) atomicOr(p, m);
+                    any = true;
+                }
+            });
+            if (!__syncthreads_or(any ? 1 : 0)) continue;  // none of the window's columns lies in this range
+            int carry = 0;
+#pragma unroll
+            for (int q = 0; q < PL; ++q) {
+                const int p = wave * PW + lane + 64 * q;
+                const uint4 v = *reinterpret_cast<const uint4 *>(&bits[p * 4]);
+                const int mine = __popc(v.x) + __popc(v.y) + __popc(v.z) + __popc(v.w);
+                const int incl = wave_inclusive_scan(mine);
+                pre[p] = static_cast<uint16_t>(carry + incl - mine);
+                carry += __shfl(incl, 63, 64);
+            }
+            if (lane == 0) wtot[wave] = carry;
+            __syncthreads();
+            if (wave == 0) {
+                const int t = lane < NW ? wtot[lane] : 0;
+                const int incl = wave_inclusive_scan(t);
+                if (lane < NW) woff[lane] = incl - t;
+                if (lane == NW - 1) woff[NW] = incl;
+            }
+            __syncthreads();
+            const int range_total = woff[NW];
+            for_edges([&](int col, int i) {
+                const unsigned c = static_cast<unsigned>(col - lo);
+                if (col >= 0 && c < (1u << WB_RANGE_LOG2)) {
+                    const int piece = c >> 7, j = (c >> 5) & 3;
+                    const uint4 v = *reinterpret_cast<const uint4 *>(&bits[piece * 4]);
+                    const uint32_t own = j == 0 ? v.x : (j == 1 ? v.y : (j == 2 ? v.z : v.w));
+                    const int rank = base + woff[piece / PW] + static_cast<int>(pre[piece]) + __popc(own & ((1u << (c & 31)) - 1u)) +
+                                     (j > 0 ? __popc(v.x) : 0) + (j > 1 ? __popc(v.y) : 0) + (j > 2 ? __popc(v.z) : 0);
+                    edge_to_col[e0 + i] = rank;
+                    tmp_cols[e0 + rank] = col;
+                }
+            });
+            base += range_total;
+            __syncthreads();  // every thread is done reading the bitmap
+#pragma unroll
+            for (int q = 0; q < PL; ++q)
+                *reinterpret_cast<uint4 *>(&bits[(wave * PW + lane + 64 * q) * 4]) = make_uint4(0u, 0u, 0u, 0u);
+        }
+        if (tid == 0) {
+            uniq_count[w] = base;
+            next_s = ticket;
+        }
+        __syncthreads();  // rp (written before the first barrier of the window) and next_s
+        for (int r = wave; r < rows; r += NW) {
+            const int b = min(rp[r + 1], e0 + cnt);
+            for (int e = max(rp[r], e0) + lane; e < b; e += 64) edge_to_row[e] = r0 + r;
+        }
+        item = next_s;
     }
 }
 
@@ -1162,6 +1293,7 @@ int32_t launch_build_windows(const ftc_csr &g, ftc_windows &w, void *ws, size_t 
         return launch_status("build_windows scan");
     }
     const int hub_thr = hub_threshold(g.n, g.nnz);
+    const bool direct = (static_cast<int64_t>(g.n) + (1 << WB_RANGE_LOG2) - 1) >> WB_RANGE_LOG2 <= DIRECT_MAX_RANGES;
     const bool queued = g.nnz > WAVE_CAP;  // otherwise no window can be queued
     int32_t st = FTC_OK;
     hipStream_t s_mid = s, s_large = s, s_hub = s;
@@ -1177,7 +1309,7 @@ int32_t launch_build_windows(const ftc_csr &g, ftc_windows &w, void *ws, size_t 
         hipLaunchKernelGGL(win_clear_kernel, dim3(1), dim3(64), 0, s, k.counters);
         hipLaunchKernelGGL(win_classify_kernel, dim3((w.n_windows + 1023) / 1024), dim3(1024), 0, s, g.n,
                            w.n_windows, g.row_ptr, w.blk_h, hub_thr, k.list_b[0], k.list_b[1], k.list_b[2], k.list_b[3],
-                           k.list_large, k.list_hub, k.counters);
+                           k.list_large, k.list_hub, k.list_direct, direct ? 1 : 0, k.counters);
         st = launch_status("build_windows classify");
         if (st != FTC_OK) return st;
         side = side_in;
@@ -1214,7 +1346,13 @@ int32_t launch_build_windows(const ftc_csr &g, ftc_windows &w, void *ws, size_t 
     hipLaunchKernelGGL((win_bitmap_wave_kernel<F, NW>), dim3(k.cap_b[I] < PER_CU * n_cu ? k.cap_b[I] : PER_CU * n_cu), \
                        dim3(64 * NW), 0, STREAM, g.n, g.nnz, g.row_ptr, g.col_idx, w.blk_h, w.edge_to_row, w.edge_to_col, \
                        k.uniq_count, k.tmp_cols, k.list_b[I], k.counters + COUNTER)
-        if (st == FTC_OK && g.nnz > MID_CAP) {
+        if (st == FTC_OK && g.nnz > MID_CAP && direct) {
+            hipLaunchKernelGGL(win_direct_kernel, dim3(k.cap_b[3] < n_cu ? k.cap_b[3] : n_cu), dim3(1024), 0, s_large, g.n,
+                               g.row_ptr, g.col_idx, w.blk_h, w.edge_to_row, w.edge_to_col, k.uniq_count, k.tmp_cols,
+                               k.list_direct, k.counters + C_DIRECT, k.counters + C_DIRECT_NEXT);
+            st = launch_status("build_windows direct bitmap (above 4096 edges)");
+        }
+        if (st == FTC_OK && g.nnz > MID_CAP && !direct) {
             FTC_WB(16384, 16, 1, 3, C_B4, s_large);
             st = launch_status("build_windows bitmap (4097 .. 16384 edges)");
         }
@@ -1231,12 +1369,12 @@ int32_t launch_build_windows(const ftc_csr &g, ftc_windows &w, void *ws, size_t 
             st = launch_status("build_windows bitmap (257 .. 1024 edges)");
         }
 #undef FTC_WB
-        if (st == FTC_OK && g.nnz > B4_CAP && hub_thr > B4_CAP) {
+        if (st == FTC_OK && g.nnz > B4_CAP && hub_thr > B4_CAP && !direct) {
             FTC_RANGE(1024, 8192, uint32_t, 1, k.cap_large, k.list_large, C_LARGE, C_LARGE_NEXT, s_large);
             st = launch_status("build_windows compact (large)");
         }
 #undef FTC_RANGE
-        if (st == FTC_OK && g.nnz > hub_thr) {
+        if (st == FTC_OK && g.nnz > hub_thr && !direct) {
             hipLaunchKernelGGL(hub_plan_kernel, dim3(1), dim3(1024), 0, s_hub, g.n, g.row_ptr, w.blk_h, k.list_hub,
                                k.counters, k.hub_chunk_ptr, k.chunk_table);
             hipLaunchKernelGGL(hub_clear_kernel, dim3(512), dim3(256), 0, s_hub, k.counters, k.hub_bits, k.wps);
