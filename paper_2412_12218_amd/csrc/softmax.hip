@@ -103,8 +103,8 @@ int32_t launch_softmax(const ftc_csr &g, const float *in, float *out, hipStream_
 //      a table in LDS and its probabilities are written at once from the registers: such edges
 //      cross HBM twice in all (score in, probability out).  The piece entering from the left and
 //      the piece leaving to the right go to a carry buffer together with their extents.
-//   2. fix-up kernel: pieces of a row cut by range boundaries are combined in edge order.
-//   3. cut-row kernel: the probabilities of the cut pieces, by the wave that owns the range.
+//   2. cut-row kernel: the wave that owns a range combines the pieces of the (at most two) rows cut by its
+//      boundaries, in an order fixed by the row's extent, and writes the probabilities of its own pieces.
 constexpr int SMS_R = 1024;
 constexpr int SMS_C = SMS_R / 64;  // 64-edge chunks per wave
 
@@ -183,7 +183,9 @@ struct SoftmaxFwd {
     __device__ static MZ identity() { return MZ{-INFINITY, 0.f}; }
     __device__ static void push(MZ &a, float s, float) { mz_push(a, s); }
     __device__ static MZ combine(MZ a, MZ b) { return mz_combine(a, b); }
-    __device__ static float result(float s, float, float2 t) { return __expf(s - t.x) / t.y; }
+    // a row's pair as its entries use it: (maximum, 1 / sum), the division done once per row piece
+    __device__ static float2 final_pair(float2 t) { return make_float2(t.x, 1.f / t.y); }
+    __device__ static float result(float s, float, float2 t) { return __expf(s - t.x) * t.y; }
 };
 
 struct SoftmaxBwd {
@@ -191,6 +193,7 @@ struct SoftmaxBwd {
     __device__ static MZ identity() { return MZ{0.f, 0.f}; }
     __device__ static void push(MZ &a, float p, float dp) { a.z = fmaf(p, dp, a.z); }
     __device__ static MZ combine(MZ a, MZ b) { return MZ{0.f, a.z + b.z}; }
+    __device__ static float2 final_pair(float2 t) { return t; }
     __device__ static float result(float p, float dp, float2 t) { return p * (dp - t.y); }
 };
 
@@ -202,72 +205,146 @@ struct SoftmaxBwd {
 // the others count the row beginnings; the number indexes the table of final pairs in LDS.
 //
 // Per range: carry[2v] = pair of the piece entering from the left, carry[2v+1] = pair of the piece
-// leaving to the right; meta[v] = {edges of the entering piece, first edge of the leaving piece
-// (n_valid when none), row of the leaving piece or -1, unused}.
+// leaving to the right; meta[2v] = {edges of the entering piece, first edge of the leaving piece
+// (n_valid when none), 1 if there is a leaving piece else -1, first range of the entering piece's row},
+// meta[2v+1] = {last range of the entering piece's row, last range of the leaving piece's row, -, -}: the
+// second kernel finds the pieces of its cut rows without reading a row start.
 constexpr int SMS_L = SMS_R / 64;
 
+// Rows that may begin inside a range before the per-entry row ids are read instead of the row starts.
+constexpr int SMS_Q = 4;  // row starts per lane
+
 template <class Op, bool VEC>
-__global__ __launch_bounds__(256) void softmax_local_kernel(int nnz, int n_ranges,
+__global__ __launch_bounds__(256) void softmax_local_kernel(int nnz, int n_ranges, const int *__restrict__ row_ptr,
                                                             const int *__restrict__ edge_to_row,
                                                             const float *in, const float *in2, float *out,
                                                             float2 *__restrict__ carry,
                                                             int4 *__restrict__ meta)
 {
     __shared__ float2 table_all[4][SMS_R + 1];
+    __shared__ __attribute__((aligned(16))) uint8_t marks_all[4][SMS_R];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int v = blockIdx.x * 4 + wave;
     if (v >= n_ranges) return;  // no workgroup barrier below
     float2 *table = table_all[wave];
+    uint8_t *marks = marks_all[wave];
     const int base = v * SMS_R;
     const int n_valid = min(SMS_R, nnz - base);
     const int prev_row = base > 0 ? edge_to_row[base - 1] : -1;
     const int next_row = base + n_valid < nnz ? edge_to_row[base + n_valid] : -1;
+    const int r_first = edge_to_row[base], r_last = edge_to_row[base + n_valid - 1];
+    // extents of the two rows the range's boundaries may cut (lanes 0, 1, 2; used at the very end)
+    const int ext = row_ptr[lane == 0 ? r_first : (lane == 1 ? r_first + 1 : r_last + 1)];
     const int e0 = lane * SMS_L;  // first edge of the lane inside the range
     float sc[SMS_L], sc2[Op::TWO_INPUTS ? SMS_L : 1];
-    int rw[SMS_L];
-    if (VEC && n_valid == SMS_R) {
+    unsigned begins = 0;  // bit k: a row begins at the lane's k-th edge
+    const int n_starts = r_last - r_first;  // rows r_first + 1 .. r_last begin inside the range
+    if (VEC && n_valid == SMS_R && n_starts <= 64 * SMS_Q) {
+        // The scores are the only per-entry stream: where the rows begin comes from the row starts (a few per
+        // lane), marked in a byte per entry in LDS; every lane then reads the marks of its own entries.  (Rows
+        // without entries share their start with the next row: the same mark.)
+        int st[SMS_Q];
+#pragma unroll
+        for (int q = 0; q < SMS_Q; ++q) {
+            const int t = q * 64 + lane;
+            st[q] = t < n_starts ? row_ptr[r_first + 1 + t] - base : -1;
+        }
 #pragma unroll
         for (int q = 0; q < SMS_L / 4; ++q) {
-            const int4 r4 = *reinterpret_cast<const int4 *>(edge_to_row + base + e0 + 4 * q);
             const float4 s4 = *reinterpret_cast<const float4 *>(in + base + e0 + 4 * q);
-            rw[4 * q] = r4.x; rw[4 * q + 1] = r4.y; rw[4 * q + 2] = r4.z; rw[4 * q + 3] = r4.w;
             sc[4 * q] = s4.x; sc[4 * q + 1] = s4.y; sc[4 * q + 2] = s4.z; sc[4 * q + 3] = s4.w;
             if constexpr (Op::TWO_INPUTS) {
                 const float4 t4 = *reinterpret_cast<const float4 *>(in2 + base + e0 + 4 * q);
                 sc2[4 * q] = t4.x; sc2[4 * q + 1] = t4.y; sc2[4 * q + 2] = t4.z; sc2[4 * q + 3] = t4.w;
             }
         }
+        *reinterpret_cast<uint4 *>(marks + e0) = make_uint4(0u, 0u, 0u, 0u);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int q = 0; q < SMS_Q; ++q)
+            if (st[q] >= 0 && st[q] < SMS_R) marks[st[q]] = 1;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const uint4 mk = *reinterpret_cast<const uint4 *>(marks + e0);
+        const uint32_t mw[4] = {mk.x, mk.y, mk.z, mk.w};
+#pragma unroll
+        for (int k = 0; k < SMS_L; ++k) begins |= ((mw[k / 4] >> (8 * (k % 4))) & 1u) << k;
+        if (lane == 0 && prev_row != r_first) begins |= 1u;  // the range's first entry begins a row
     } else {
+        int rw[SMS_L];
+        if (VEC && n_valid == SMS_R) {
 #pragma unroll
-        for (int k = 0; k < SMS_L; ++k) {
-            const bool ok = e0 + k < n_valid;
-            rw[k] = ok ? edge_to_row[base + e0 + k] : -2 - (e0 + k);  // padding: rows of their own
-            sc[k] = ok ? in[base + e0 + k] : 0.f;
-            if constexpr (Op::TWO_INPUTS) sc2[k] = ok ? in2[base + e0 + k] : 0.f;
+            for (int q = 0; q < SMS_L / 4; ++q) {
+                const int4 r4 = *reinterpret_cast<const int4 *>(edge_to_row + base + e0 + 4 * q);
+                const float4 s4 = *reinterpret_cast<const float4 *>(in + base + e0 + 4 * q);
+                rw[4 * q] = r4.x; rw[4 * q + 1] = r4.y; rw[4 * q + 2] = r4.z; rw[4 * q + 3] = r4.w;
+                sc[4 * q] = s4.x; sc[4 * q + 1] = s4.y; sc[4 * q + 2] = s4.z; sc[4 * q + 3] = s4.w;
+                if constexpr (Op::TWO_INPUTS) {
+                    const float4 t4 = *reinterpret_cast<const float4 *>(in2 + base + e0 + 4 * q);
+                    sc2[4 * q] = t4.x; sc2[4 * q + 1] = t4.y; sc2[4 * q + 2] = t4.z; sc2[4 * q + 3] = t4.w;
+                }
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < SMS_L; ++k) {
+                const bool ok = e0 + k < n_valid;
+                rw[k] = ok ? edge_to_row[base + e0 + k] : -2 - (e0 + k);  // padding: rows of their own
+                sc[k] = ok ? in[base + e0 + k] : 0.f;
+                if constexpr (Op::TWO_INPUTS) sc2[k] = ok ? in2[base + e0 + k] : 0.f;
+            }
         }
-    }
-    // row beginnings inside the lane; `left` is the row of the edge before the lane's first
-    int left = __builtin_amdgcn_update_dpp(0, rw[SMS_L - 1], 0x138, 0xf, 0xf, false);  // wave_shr:1
-    if (lane == 0) left = prev_row;
-    unsigned begins = 0;
+        // row beginnings inside the lane; `left` is the row of the edge before the lane's first
+        int left = __builtin_amdgcn_update_dpp(0, rw[SMS_L - 1], 0x138, 0xf, 0xf, false);  // wave_shr:1
+        if (lane == 0) left = prev_row;
 #pragma unroll
-    for (int k = 0; k < SMS_L; ++k) begins |= (rw[k] != (k == 0 ? left : rw[k - 1]) ? 1u : 0u) << k;
+        for (int k = 0; k < SMS_L; ++k) begins |= (rw[k] != (k == 0 ? left : rw[k - 1]) ? 1u : 0u) << k;
+    }
     const int nb = __popc(begins);
     const int first_num = wave_inclusive_scan(nb) - nb;  // number of the row that is open at the lane's start
     // first walk: pairs of the pieces
     MZ cur = Op::identity(), first_piece = Op::identity();
-    int seen = 0;
+    float seg_max[Op::TWO_INPUTS ? 1 : SMS_L];  // forward: maximum of the piece every entry lies in
+    if constexpr (!Op::TWO_INPUTS) {
+        // Branch-free: running maxima forwards (restarting where a row begins), the piece's maximum carried
+        // backwards to all its entries, ONE exponential per entry relative to that maximum, running sums.  What
+        // an entry still lacks afterwards is a factor of its piece alone: exp(piece maximum - row maximum) / row sum.
+        float run[SMS_L];
 #pragma unroll
-    for (int k = 0; k < SMS_L; ++k) {
-        if (begins >> k & 1u) {
-            if (seen == 0) first_piece = cur;                                  // joined with the lanes on the left below
-            else table[first_num + seen] = make_float2(cur.m, cur.z);           // a row inside the lane: final
-            ++seen;
-            cur = Op::identity();
+        for (int k = 0; k < SMS_L; ++k) run[k] = (k == 0 || (begins >> k & 1u)) ? sc[k] : fmaxf(run[k - 1], sc[k]);
+        seg_max[SMS_L - 1] = run[SMS_L - 1];
+#pragma unroll
+        for (int k = SMS_L - 2; k >= 0; --k) seg_max[k] = (begins >> (k + 1) & 1u) ? run[k] : seg_max[k + 1];
+#pragma unroll
+        for (int k = 0; k < SMS_L; ++k) {
+            sc[k] = __expf(sc[k] - seg_max[k]);                                   // sc now holds the exponentials
+            run[k] = (k == 0 || (begins >> k & 1u)) ? sc[k] : run[k - 1] + sc[k];  // ... and run their sums inside the piece
         }
-        Op::push(cur, sc[k], sc2[Op::TWO_INPUTS ? k : 0]);
+#pragma unroll
+        for (int k = 0; k < SMS_L - 1; ++k) {
+            if (begins >> (k + 1) & 1u) {  // a piece ends at entry k
+                const int before = __popc(begins & ((2u << k) - 1u));  // row beginnings up to entry k
+                if (before == 0) first_piece = MZ{seg_max[k], run[k]};  // joined with the lanes on the left below
+                else table[first_num + before] = make_float2(seg_max[k], run[k]);  // a row inside the lane: final
+            }
+        }
+        cur = MZ{seg_max[SMS_L - 1], run[SMS_L - 1]};
+        if (nb == 0) first_piece = cur;
+    } else {
+        int seen = 0;
+#pragma unroll
+        for (int k = 0; k < SMS_L; ++k) {
+            if (begins >> k & 1u) {
+                if (seen == 0) first_piece = cur;                                  // joined with the lanes on the left below
+                else table[first_num + seen] = make_float2(cur.m, cur.z);           // a row inside the lane: final
+                ++seen;
+                cur = Op::identity();
+            }
+            Op::push(cur, sc[k], sc2[Op::TWO_INPUTS ? k : 0]);
+        }
+        if (nb == 0) first_piece = cur;
     }
-    if (nb == 0) first_piece = cur;
     // one segmented scan over the lanes: what flows into a lane from the left
     const MZ incl = wave_segmented_scan<Op>(cur, nb > 0 ? 1 : 0, lane);  // `cur` is the lane's last (or only) piece
     MZ from_left;
@@ -280,8 +357,7 @@ __global__ __launch_bounds__(256) void softmax_local_kernel(int nnz, int n_range
         else table[first_num] = make_float2(t.m, t.z);
     }
     const int last_num = __shfl(first_num + nb, 63, 64);  // number of the range's last row
-    const int last_row = __shfl(rw[SMS_L - 1], 63, 64);
-    const bool right_open = n_valid == SMS_R && next_row == last_row;
+    const bool right_open = n_valid == SMS_R && next_row == r_last;
     if (lane == 63) {
         if (last_num == 0) carry[2 * static_cast<size_t>(v)] = make_float2(incl.m, incl.z);  // one row, open on the left
         else if (right_open) carry[2 * static_cast<size_t>(v) + 1] = make_float2(incl.m, incl.z);
@@ -308,8 +384,17 @@ __global__ __launch_bounds__(256) void softmax_local_kernel(int nnz, int n_range
         tail_cnt += in_tail ? 1 : 0;
         pr[k] = 0.f;
         if (ok && !in_head && !in_tail) {
-            if (!have) { t = table[num]; have = true; }
-            pr[k] = Op::result(sc[k], sc2[Op::TWO_INPUTS ? k : 0], t);
+            if constexpr (!Op::TWO_INPUTS) {
+                if (!have) {  // the factor of this piece of the row
+                    t = Op::final_pair(table[num]);
+                    t.y *= __expf(seg_max[k] - t.x);
+                    have = true;
+                }
+                pr[k] = sc[k] * t.y;
+            } else {
+                if (!have) { t = Op::final_pair(table[num]); have = true; }
+                pr[k] = Op::result(sc[k], sc2[Op::TWO_INPUTS ? k : 0], t);
+            }
             done |= 1u << k;
         }
     }
@@ -325,35 +410,45 @@ __global__ __launch_bounds__(256) void softmax_local_kernel(int nnz, int n_range
     }
     head_cnt = wave_sum_int(head_cnt);
     tail_cnt = wave_sum_int(tail_cnt);
-    if (lane == 0) meta[v] = make_int4(head_cnt, n_valid - tail_cnt, tail_num >= 0 ? last_row : -1, 0);
-}
-
-template <class Op>
-__global__ __launch_bounds__(256) void softmax_fixup_kernel(int n_ranges, const int *__restrict__ row_ptr,
-                                                            const float2 *__restrict__ carry,
-                                                            const int4 *__restrict__ meta,
-                                                            float2 *__restrict__ stats)
-{
-    const int v = blockIdx.x * 256 + threadIdx.x;
-    if (v >= n_ranges) return;
-    const int r = meta[v].z;
-    if (r < 0) return;
-    const int last = (row_ptr[r + 1] - 1) / SMS_R;
-    float2 t = carry[2 * static_cast<size_t>(v) + 1];
-    MZ acc = {t.x, t.y};
-    for (int u = v + 1; u <= last; ++u) {
-        t = carry[2 * static_cast<size_t>(u)];
-        acc = Op::combine(acc, MZ{t.x, t.y});
+    const int head_begin = __shfl(ext, 0, 64), head_end = __shfl(ext, 1, 64), tail_end = __shfl(ext, 2, 64);
+    if (lane == 0) {
+        meta[2 * static_cast<size_t>(v)] = make_int4(head_cnt, n_valid - tail_cnt, tail_num >= 0 ? 1 : -1, head_begin / SMS_R);
+        meta[2 * static_cast<size_t>(v) + 1] = make_int4((head_end - 1) / SMS_R, (tail_end - 1) / SMS_R, 0, 0);
     }
-    stats[r] = make_float2(acc.m, acc.z);
 }
 
-// Probabilities of the pieces of cut rows: the entering piece (edges [0, head_len) of the range,
-// row = row of the edge before the range) and the leaving piece (edges [tail_start, n_valid)).
+// The pair of a row cut by range boundaries: its leaving piece in range u_first, the whole ranges in between
+// and its entering piece in range u_last, combined in an order that depends on (u_first, u_last) alone.  Every
+// wave that holds a piece of the row computes the pair itself and gets the same bits (a row of K ranges is read
+// K times by K waves: K is 2 for nearly every cut row and a few dozen for the longest rows of a power-law graph).
 template <class Op>
-__global__ __launch_bounds__(256) void softmax_cut_kernel(int nnz, int n_ranges,
-                                                          const int *__restrict__ edge_to_row,
-                                                          const float2 *__restrict__ stats,
+__device__ __forceinline__ MZ cut_row_pair(const float2 *__restrict__ carry, int u_first, int u_last, int lane)
+{
+    MZ acc = Op::identity();
+    bool have = false;
+    for (int u = u_first + lane; u <= u_last; u += 64) {
+        const float2 t = carry[2 * static_cast<size_t>(u) + (u == u_first ? 1 : 0)];
+        acc = have ? Op::combine(acc, MZ{t.x, t.y}) : MZ{t.x, t.y};
+        have = true;
+    }
+    const int n_lanes = min(64, u_last - u_first + 1);  // lanes that hold something
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        MZ o;
+        o.m = __shfl_down(acc.m, off, 64);
+        o.z = __shfl_down(acc.z, off, 64);
+        if (lane + off < n_lanes && lane < off) acc = Op::combine(acc, o);
+    }
+    MZ r;
+    r.m = __shfl(acc.m, 0, 64);
+    r.z = __shfl(acc.z, 0, 64);
+    return r;
+}
+
+// Results of the pieces of cut rows: the entering piece (edges [0, head_len) of the range, row = row of the
+// edge before the range) and the leaving piece (edges [tail_start, n_valid)), by the wave that owns the range.
+template <class Op>
+__global__ __launch_bounds__(256) void softmax_cut_kernel(int nnz, int n_ranges, const float2 *__restrict__ carry,
                                                           const int4 *__restrict__ meta, const float *in,
                                                           const float *in2, float *out)
 {
@@ -362,14 +457,16 @@ __global__ __launch_bounds__(256) void softmax_cut_kernel(int nnz, int n_ranges,
     if (v >= n_ranges) return;
     const int base = v * SMS_R;
     const int n_valid = min(SMS_R, nnz - base);
-    const int4 mt = meta[v];
+    const int4 mt = meta[2 * static_cast<size_t>(v)], mx = meta[2 * static_cast<size_t>(v) + 1];
     if (mt.x > 0) {
-        const float2 st = stats[edge_to_row[base - 1]];  // head_len > 0 implies base > 0
+        const MZ pr = cut_row_pair<Op>(carry, mt.w, mx.x, lane);
+        const float2 st = Op::final_pair(make_float2(pr.m, pr.z));
         for (int i = lane; i < mt.x; i += 64)
             out[base + i] = Op::result(in[base + i], Op::TWO_INPUTS ? in2[base + i] : 0.f, st);
     }
     if (mt.z >= 0) {
-        const float2 st = stats[mt.z];
+        const MZ pr = cut_row_pair<Op>(carry, v, mx.y, lane);  // the row of the leaving piece begins in this range
+        const float2 st = Op::final_pair(make_float2(pr.m, pr.z));
         for (int i = mt.y + lane; i < n_valid; i += 64)
             out[base + i] = Op::result(in[base + i], Op::TWO_INPUTS ? in2[base + i] : 0.f, st);
     }
@@ -377,9 +474,9 @@ __global__ __launch_bounds__(256) void softmax_cut_kernel(int nnz, int n_ranges,
 
 size_t softmax_seg_ws(int n, int nnz)
 {
+    (void)n;
     const size_t n_ranges = (static_cast<size_t>(nnz) + SMS_R - 1) / SMS_R;
-    return align_up(static_cast<size_t>(n) * sizeof(float2), 256) + align_up(n_ranges * 2 * sizeof(float2), 256) +
-           align_up(n_ranges * sizeof(int4), 256);
+    return align_up(n_ranges * 2 * sizeof(float2), 256) + align_up(n_ranges * 2 * sizeof(int4), 256);
 }
 
 template <class Op>
@@ -389,8 +486,6 @@ static int32_t launch_ranges(const ftc_csr &g, const ftc_windows &w, const float
     if (g.n == 0 || g.nnz == 0) return FTC_OK;
     const int n_ranges = ceil_div(g.nnz, SMS_R);
     char *p = static_cast<char *>(ws);
-    float2 *stats = reinterpret_cast<float2 *>(p);
-    p += align_up(static_cast<size_t>(g.n) * sizeof(float2), 256);
     float2 *carry = reinterpret_cast<float2 *>(p);
     p += align_up(static_cast<size_t>(n_ranges) * 2 * sizeof(float2), 256);
     int4 *meta = reinterpret_cast<int4 *>(p);
@@ -398,18 +493,14 @@ static int32_t launch_ranges(const ftc_csr &g, const ftc_windows &w, const float
     const bool vec = aligned16(in) && aligned16(out) && aligned16(w.edge_to_row) && (!in2 || aligned16(in2));
     if (vec)
         hipLaunchKernelGGL((softmax_local_kernel<Op, true>), dim3((n_ranges + 3) / 4), dim3(256), 0, s, g.nnz,
-                           n_ranges, w.edge_to_row, in, in2, out, carry, meta);
+                           n_ranges, g.row_ptr, w.edge_to_row, in, in2, out, carry, meta);
     else
         hipLaunchKernelGGL((softmax_local_kernel<Op, false>), dim3((n_ranges + 3) / 4), dim3(256), 0, s, g.nnz,
-                           n_ranges, w.edge_to_row, in, in2, out, carry, meta);
+                           n_ranges, g.row_ptr, w.edge_to_row, in, in2, out, carry, meta);
     int32_t st = launch_status("edge_softmax local");
     if (st != FTC_OK) return st;
-    hipLaunchKernelGGL(softmax_fixup_kernel<Op>, dim3((n_ranges + 255) / 256), dim3(256), 0, s, n_ranges, g.row_ptr,
-                       carry, meta, stats);
-    st = launch_status("edge_softmax fixup");
-    if (st != FTC_OK) return st;
-    hipLaunchKernelGGL(softmax_cut_kernel<Op>, dim3((n_ranges + 3) / 4), dim3(256), 0, s, g.nnz, n_ranges,
-                       w.edge_to_row, stats, meta, in, in2, out);
+    hipLaunchKernelGGL(softmax_cut_kernel<Op>, dim3((n_ranges + 3) / 4), dim3(256), 0, s, g.nnz, n_ranges, carry, meta,
+                       in, in2, out);
     return launch_status("edge_softmax cut rows");
 }
 
