@@ -278,6 +278,9 @@ __global__ __launch_bounds__(256) void agnn_fused_kernel(int nnz, int n_ranges, 
     }
 }
 
+// G lanes (four features each) finish one cut row, 64 / G rows per wave: the kernel is a chain of two dependent
+// loads per row (the range's record, then the two pieces), so it is the number of rows in flight that counts.
+template <int G>
 __global__ __launch_bounds__(256) void agnn_fused_fixup_kernel(int n, int n_ranges, const int *__restrict__ row_ptr,
                                                                const float *__restrict__ carry,
                                                                const int *__restrict__ carry_tail_row, int DP,
@@ -285,36 +288,44 @@ __global__ __launch_bounds__(256) void agnn_fused_fixup_kernel(int n, int n_rang
                                                                float *__restrict__ row_z, float *__restrict__ out32,
                                                                int ld32)
 {
+    constexpr int R = 64 / G;  // ranges per wave
     const int DPZ = DP + 4;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int v = blockIdx.x * 4 + wave;
-    if (v < n_ranges) {
-        // Nearly every open row ends in the next range: numerator and denominator are the head
-        // piece of range v + 1 plus the tail piece of range v.  Their addresses depend on v alone,
-        // so they are loaded together with the range's record instead of after it.
-        const int2 rec = reinterpret_cast<const int2 *>(carry_tail_row)[v];
-        float spec[4], spec_z = 1.f;
-        {
-            const float *hv = carry + (static_cast<size_t>(v + 1) * 2) * DPZ;
-            const float *tv = carry + (static_cast<size_t>(v) * 2 + 1) * DPZ;
-            const bool ok = v + 1 < n_ranges;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int d = i * 64 + lane;
-                spec[i] = (ok && d < D) ? hv[d] + tv[d] : 0.f;
-            }
-            if (ok) spec_z = hv[DP] + tv[DP];
+    const int sub = lane % G;
+    const int v_mine = (blockIdx.x * 4 + wave) * R + lane / G;
+    int2 rec = make_int2(-1, 0);
+    if (v_mine < n_ranges) rec = reinterpret_cast<const int2 *>(carry_tail_row)[v_mine];
+    // Nearly every open row ends in the next range: numerator and denominator are the head piece of range
+    // v + 1 plus the tail piece of range v.  Their addresses depend on v alone, so they are loaded together
+    // with the range's record instead of after it.
+    {
+        const bool ok = v_mine + 1 < n_ranges && sub * 4 < DP;
+        const size_t vv = ok ? static_cast<size_t>(v_mine) : 0;
+        const float *hv = carry + (vv + 1) * 2 * DPZ;
+        const float *tv = carry + (vv * 2 + 1) * DPZ;
+        float4 h4 = make_float4(0.f, 0.f, 0.f, 0.f), t4 = h4;
+        float spec_z = 1.f;
+        if (ok) {
+            h4 = *reinterpret_cast<const float4 *>(hv + sub * 4);
+            t4 = *reinterpret_cast<const float4 *>(tv + sub * 4);
+            spec_z = hv[DP] + tv[DP];
         }
         const int r = rec.x;
-        if (r >= 0 && rec.y) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int d = i * 64 + lane;
-                if (d < D) store_elem(out, static_cast<int64_t>(r) * ldo + d, odt, spec[i] / spec_z);
-                if (out32 && d < D) out32[static_cast<int64_t>(r) * ld32 + d] = spec[i] / spec_z;
-            }
-            if (row_z && lane == 0) row_z[r] = spec_z;
-        } else if (r >= 0) {
+        if (ok && r >= 0 && rec.y && sub * 4 < D) {
+            const float o[4] = {(h4.x + t4.x) / spec_z, (h4.y + t4.y) / spec_z, (h4.z + t4.z) / spec_z,
+                                (h4.w + t4.w) / spec_z};
+            store_vec<4>(out, static_cast<int64_t>(r) * ldo + sub * 4, odt, o);
+            if (out32) store_vec<4>(out32, static_cast<int64_t>(r) * ld32 + sub * 4, FTC_F32, o);
+        }
+        if (ok && r >= 0 && rec.y && row_z && sub == 0) row_z[r] = spec_z;
+    }
+    // rows that go on beyond the next range (long rows of a power-law graph): one at a time, by the whole wave
+    unsigned long long longs = __builtin_amdgcn_ballot_w64(rec.x >= 0 && !rec.y && sub == 0);
+    while (longs) {
+        const int src = __ffsll(static_cast<long long>(longs)) - 1;
+        longs &= longs - 1;
+        const int v = __shfl(v_mine, src, 64), r = __shfl(rec.x, src, 64);
+        {
             const int last = (row_ptr[r + 1] - 1) / AG_R;
             // teams of `dl` lanes (one lane per feature) share the ranges of a long row round-robin,
             // four loads in flight each; team sums are added in team order (fixed by the shape)
@@ -425,11 +436,22 @@ int32_t launch_agnn_fused(const ftc_csr &g, const ftc_windows &w, const void *H,
         const int32_t st = launch_status("agnn_fused");
         if (st != FTC_OK) return st;
     }
+    // lanes per cut row in the fix-up kernel: four features per lane
+    int grp = 1;
+    while (grp * 4 < dp) grp <<= 1;
     const int64_t blocks_rows = (static_cast<int64_t>(g.n) + 255) / 256;
-    const int64_t blocks_ranges = (n_ranges + 3) / 4;
+    const int64_t per_block = 4 * (64 / grp);
+    const int64_t blocks_ranges = (n_ranges + per_block - 1) / per_block;
     const unsigned grid2 = static_cast<unsigned>(blocks_rows > blocks_ranges ? blocks_rows : blocks_ranges);
-    hipLaunchKernelGGL(agnn_fused_fixup_kernel, dim3(grid2), dim3(256), 0, s, g.n, n_ranges, g.row_ptr, carry,
-                       tail_row, dp, D, out, ldo, odt, row_z, out32, ld32);
+#define FTC_FX(G)                                                                                                    \
+    case G:                                                                                                          \
+        hipLaunchKernelGGL(agnn_fused_fixup_kernel<G>, dim3(grid2), dim3(256), 0, s, g.n, n_ranges, g.row_ptr, carry, \
+                           tail_row, dp, D, out, ldo, odt, row_z, out32, ld32);                                      \
+        break;
+    switch (grp) {
+        FTC_FX(1) FTC_FX(2) FTC_FX(4) FTC_FX(8) FTC_FX(16) FTC_FX(32) FTC_FX(64)
+    }
+#undef FTC_FX
     return launch_status("agnn_fused fixup");
 }
 
