@@ -453,14 +453,11 @@ int32_t launch_agnn_backward_fused(const ftc_csr &g, const ftc_windows &w, const
         if (st != FTC_OK) return st;
     }
     // rows cut by wave boundaries and rows without entries: the SpMM fix-up on the 2 * DP wide rows
-    const int64_t blocks_rows = (static_cast<int64_t>(n) + 255) / 256;
-    const int64_t blocks_ranges = (n_ranges + 3) / 4;
-    const unsigned grid2 = static_cast<unsigned>(blocks_rows > blocks_ranges ? blocks_rows : blocks_ranges);
-    hipLaunchKernelGGL(spmm_seg_fixup_kernel, dim3(grid2), dim3(256), 0, s, n, n_ranges, g.row_ptr, carry, tail_row, dp2,
-                       dp2, static_cast<void *>(QA), dp2, static_cast<int>(FTC_F32), Epi{0, nullptr},
-                       static_cast<const uint8_t *>(nullptr), SEG_R);
+    int32_t st = launch_seg_fixup(n, n_ranges, g.row_ptr, carry, tail_row, dp2, dp2, QA, dp2, FTC_F32, Epi{0, nullptr},
+                                  nullptr, SEG_R, s, "agnn_backward_fused fixup");
+    if (st != FTC_OK) return st;
     hipLaunchKernelGGL(dbeta_sum_kernel, dim3(1), dim3(1024), 0, s, n_ranges, dbeta_part, dbeta);
-    int32_t st = launch_status("agnn_backward_fused fixup");
+    st = launch_status("agnn_backward_fused dbeta");
     if (st != FTC_OK) return st;
     // dH = agg + (q - hn <hn, q>) / |h|, rounded once to the requested type
     float *rinv = reinterpret_cast<float *>(stats);  // the pairs are dead: their array takes the inverse norms

@@ -340,11 +340,11 @@ __device__ __forceinline__ float group_sum_dpp(float v)
 }
 
 // Second pass of the edge-balanced kernels (spmm_seg.hip): finishes the rows cut by a wave boundary
-// from the carry buffer and zero-fills the rows without entries.
-__global__ void spmm_seg_fixup_kernel(int n, int n_ranges, const int *__restrict__ row_ptr,
-                                      const float *__restrict__ carry, const int *__restrict__ carry_tail_row, int DP,
-                                      int D, void *__restrict__ out, int ldo, int odt, Epi epi,
-                                      const uint8_t *__restrict__ dense, int seg_r);
+// from the carry buffer (rows of dp floats, dp a multiple of 4, 16-byte aligned) and zero-fills the rows
+// without entries.
+int32_t launch_seg_fixup(int n, int n_ranges, const int *row_ptr, const float *carry, const int *tail_row, int dp,
+                         int D, void *out, int ldo, int odt, Epi epi, const uint8_t *dense, int seg_r, hipStream_t s,
+                         const char *what);
 
 // Workgroups are handed to the eight XCDs round-robin by their index, and every XCD has an L2 of its
 // own.  The edge-balanced kernels walk the edges in order, so neighbouring workgroups gather

@@ -312,12 +312,8 @@ int32_t launch_spmm_lane(const ftc_csr &g, const ftc_windows &w, const float *va
         const int32_t st = launch_status("spmm_lane");
         if (st != FTC_OK) return st;
     }
-    const int64_t blocks_rows = (static_cast<int64_t>(g.n) + 255) / 256;
-    const int64_t blocks_ranges = (n_ranges + 3) / 4;
-    const unsigned grid2 = static_cast<unsigned>(blocks_rows > blocks_ranges ? blocks_rows : blocks_ranges);
-    hipLaunchKernelGGL(spmm_seg_fixup_kernel, dim3(grid2), dim3(256), 0, s, g.n, n_ranges, g.row_ptr, carry, tail_row, dp,
-                       D, out, ldo, odt, epi, static_cast<const uint8_t *>(nullptr), range);
-    return launch_status("spmm_lane fixup");
+    return launch_seg_fixup(g.n, n_ranges, g.row_ptr, carry, tail_row, dp, D, out, ldo, odt, epi, nullptr, range, s,
+                            "spmm_lane fixup");
 }
 
 }  // namespace ftc

@@ -248,71 +248,107 @@ __global__ __launch_bounds__(256) void spmm_seg_kernel(int nnz, int n_ranges, co
     }
 }
 
-// Second pass: rows cut by a wave boundary, and rows without any stored entry.
+// Second pass: rows cut by a wave boundary, and rows without any stored entry.  G lanes (four features
+// each) finish one cut row, 64 / G rows per wave: the kernel is a chain of two dependent loads per row (the
+// range's record, then the two pieces), so it is the number of rows in flight that counts.  DP is a
+// multiple of 4 and the carry buffer 16-byte aligned (both by construction of the first pass).
+template <int G>
 __global__ __launch_bounds__(256) void spmm_seg_fixup_kernel(int n, int n_ranges, const int *__restrict__ row_ptr,
                                                              const float *__restrict__ carry,
                                                              const int *__restrict__ carry_tail_row, int DP,
                                                              int D, void *__restrict__ out, int ldo, int odt,
                                                              Epi epi, const uint8_t *__restrict__ dense, int seg_r)
 {
+    constexpr int R = 64 / G;  // ranges per wave
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int v = blockIdx.x * 4 + wave;
-    if (v < n_ranges) {
-        // Nearly every open row ends in the next range: out = head piece of range v + 1 + tail piece
-        // of range v.  Their addresses depend on v alone, so they are loaded together with the
-        // range's record instead of after it (the kernel is a chain of dependent loads otherwise).
-        const int2 rec = reinterpret_cast<const int2 *>(carry_tail_row)[v];
-        float spec[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int d = i * 64 + lane;
-            spec[i] = 0.f;
-            if (d < D && v + 1 < n_ranges)
-                spec[i] = carry[(static_cast<size_t>(v + 1) * 2) * DP + d] + carry[(static_cast<size_t>(v) * 2 + 1) * DP + d];
+    const int sub = lane % G;
+    const int v_mine = (blockIdx.x * 4 + wave) * R + lane / G;
+    int2 rec = make_int2(-1, 0);
+    if (v_mine < n_ranges) rec = reinterpret_cast<const int2 *>(carry_tail_row)[v_mine];
+    // Nearly every open row ends in the next range: out = head piece of range v + 1 + tail piece of
+    // range v.  Their addresses depend on v alone, so they are loaded together with the range's record
+    // instead of after it.
+    for (int f0 = 0; f0 < DP; f0 += 4 * G) {
+        const int f = f0 + sub * 4;
+        const bool ok = v_mine + 1 < n_ranges && f < DP;
+        const size_t vv = ok ? static_cast<size_t>(v_mine) : 0;
+        float4 h4 = make_float4(0.f, 0.f, 0.f, 0.f), t4 = h4;
+        if (ok) {
+            h4 = *reinterpret_cast<const float4 *>(carry + (vv + 1) * 2 * DP + f);
+            t4 = *reinterpret_cast<const float4 *>(carry + (vv * 2 + 1) * DP + f);
         }
-        const int r = rec.x;
-        if (r >= 0 && !(dense && dense[r >> 4]) && rec.y) {
+        int r = rec.x;
+        if (r >= 0 && dense && dense[r >> 4]) r = -1;
+        if (f0 == 0) rec.x = r;
+        if (ok && r >= 0 && rec.y) {
+            const float fac = epi.factor(r);
+            const float o[4] = {h4.x + t4.x, h4.y + t4.y, h4.z + t4.z, h4.w + t4.w};
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int d = i * 64 + lane;
-                if (d < D) store_elem(out, static_cast<int64_t>(r) * ldo + d, odt, epi.apply(epi.factor(r), spec[i]));
+            for (int i = 0; i < 4; ++i)
+                if (f + i < D) store_elem(out, static_cast<int64_t>(r) * ldo + f + i, odt, epi.apply(fac, o[i]));
+        }
+    }
+    // rows that go on beyond the next range (long rows of a power-law graph): one at a time, by the whole wave
+    unsigned long long longs = __builtin_amdgcn_ballot_w64(rec.x >= 0 && !rec.y && sub == 0);
+    while (longs) {
+        const int src = __ffsll(static_cast<long long>(longs)) - 1;
+        longs &= longs - 1;
+        const int v = __shfl(v_mine, src, 64), r = __shfl(rec.x, src, 64);
+        const int last = (row_ptr[r + 1] - 1) / seg_r;  // wave range holding the row's final edge
+        // A hub row can span hundreds of ranges.  The 64 lanes are split into `parts` teams of
+        // `dl` lanes (one lane per feature); team p adds the head pieces of ranges v+1+p,
+        // v+1+p+parts, ... four at a time, then the teams' sums are added in team order.  The
+        // order is fixed by the shape alone, so the result is reproducible.
+        int dl = 1;
+        while (dl < D && dl < 64) dl <<= 1;
+        const int parts = 64 / dl;
+        const int part = lane / dl;
+        for (int d0 = 0; d0 < D; d0 += 64) {
+            const int d = d0 + lane % dl;
+            const bool dok = d < D;
+            const float *base = carry + (dok ? d : 0);
+            float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+            int u = v + 1 + part;
+            for (; u + 3 * parts <= last; u += 4 * parts) {
+                const float a0 = base[(static_cast<size_t>(u) * 2) * DP];
+                const float a1 = base[(static_cast<size_t>(u + parts) * 2) * DP];
+                const float a2 = base[(static_cast<size_t>(u + 2 * parts) * 2) * DP];
+                const float a3 = base[(static_cast<size_t>(u + 3 * parts) * 2) * DP];
+                s0 += a0; s1 += a1; s2 += a2; s3 += a3;
             }
-        } else if (r >= 0 && !(dense && dense[r >> 4])) {
-            const int last = (row_ptr[r + 1] - 1) / seg_r;  // wave range holding the row's final edge
-            // A hub row can span hundreds of ranges.  The 64 lanes are split into `parts` teams of
-            // `dl` lanes (one lane per feature); team p adds the head pieces of ranges v+1+p,
-            // v+1+p+parts, ... four at a time, then the teams' sums are added in team order.  The
-            // order is fixed by the shape alone, so the result is reproducible.
-            int dl = 1;
-            while (dl < D && dl < 64) dl <<= 1;
-            const int parts = 64 / dl;
-            const int part = lane / dl;
-            for (int d0 = 0; d0 < D; d0 += 64) {
-                const int d = d0 + lane % dl;
-                const bool dok = d < D;
-                const float *base = carry + (dok ? d : 0);
-                float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
-                int u = v + 1 + part;
-                for (; u + 3 * parts <= last; u += 4 * parts) {
-                    const float a0 = base[(static_cast<size_t>(u) * 2) * DP];
-                    const float a1 = base[(static_cast<size_t>(u + parts) * 2) * DP];
-                    const float a2 = base[(static_cast<size_t>(u + 2 * parts) * 2) * DP];
-                    const float a3 = base[(static_cast<size_t>(u + 3 * parts) * 2) * DP];
-                    s0 += a0; s1 += a1; s2 += a2; s3 += a3;
-                }
-                for (; u <= last; u += parts) s0 += base[(static_cast<size_t>(u) * 2) * DP];
-                float sum = (s0 + s1) + (s2 + s3);
-                for (int off = 32; off >= dl; off >>= 1) sum += __shfl_down(sum, off, 64);
-                if (lane < dl && dok) {
-                    sum += carry[(static_cast<size_t>(v) * 2 + 1) * DP + d];
-                    store_elem(out, static_cast<int64_t>(r) * ldo + d, odt, epi.apply(epi.factor(r), sum));
-                }
+            for (; u <= last; u += parts) s0 += base[(static_cast<size_t>(u) * 2) * DP];
+            float sum = (s0 + s1) + (s2 + s3);
+            for (int off = 32; off >= dl; off >>= 1) sum += __shfl_down(sum, off, 64);
+            if (lane < dl && dok) {
+                sum += carry[(static_cast<size_t>(v) * 2 + 1) * DP + d];
+                store_elem(out, static_cast<int64_t>(r) * ldo + d, odt, epi.apply(epi.factor(r), sum));
             }
         }
     }
     const int64_t row = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
     if (row < n && row_ptr[row] == row_ptr[row + 1] && !(dense && dense[row >> 4]))
         for (int d = 0; d < D; ++d) store_elem(out, row * ldo + d, odt, 0.f);
+}
+
+int32_t launch_seg_fixup(int n, int n_ranges, const int *row_ptr, const float *carry, const int *tail_row, int dp,
+                         int D, void *out, int ldo, int odt, Epi epi, const uint8_t *dense, int seg_r, hipStream_t s,
+                         const char *what)
+{
+    int grp = 1;
+    while (grp * 4 < dp && grp < 16) grp <<= 1;  // at most 16 lanes a row: wider rows take several rounds
+    const int64_t blocks_rows = (static_cast<int64_t>(n) + 255) / 256;
+    const int64_t blocks_ranges = ceil_div(n_ranges, 4 * (64 / grp));
+    const unsigned grid2 = static_cast<unsigned>(blocks_rows > blocks_ranges ? blocks_rows : blocks_ranges);
+#define FTC_FX(G)                                                                                                  \
+    case G:                                                                                                        \
+        hipLaunchKernelGGL(spmm_seg_fixup_kernel<G>, dim3(grid2), dim3(256), 0, s, n, n_ranges, row_ptr, carry,    \
+                           tail_row, dp, D, out, ldo, odt, epi, dense, seg_r);                                     \
+        break;
+    switch (grp) {
+        FTC_FX(1) FTC_FX(2) FTC_FX(4) FTC_FX(8) FTC_FX(16)
+    }
+#undef FTC_FX
+    return launch_status(what);
 }
 
 template <class T>
@@ -375,12 +411,8 @@ int32_t launch_spmm_seg(const ftc_csr &g, const ftc_windows &w, const float *val
         const int32_t st = launch_status("spmm_seg");
         if (st != FTC_OK) return st;
     }
-    const int64_t blocks_rows = (static_cast<int64_t>(g.n) + 255) / 256;
-    const int64_t blocks_ranges = (n_ranges + 3) / 4;
-    const unsigned grid2 = static_cast<unsigned>(blocks_rows > blocks_ranges ? blocks_rows : blocks_ranges);
-    hipLaunchKernelGGL(spmm_seg_fixup_kernel, dim3(grid2), dim3(256), 0, s, g.n, n_ranges, g.row_ptr, carry,
-                       tail_row, dp, D, out, ldo, odt, epi, dense, SEG_R);
-    return launch_status("spmm_seg fixup");
+    return launch_seg_fixup(g.n, n_ranges, g.row_ptr, carry, tail_row, dp, D, out, ldo, odt, epi, dense, SEG_R, s,
+                            "spmm_seg fixup");
 }
 
 }  // namespace ftc
