@@ -38,6 +38,20 @@ constexpr int HUB_CHUNK = 4096;     // edges per work item of the edge-parallel 
 constexpr int HUB_GROUP = 8;        // bitmap words per stored prefix (one 32-byte load)
 constexpr int HUB_GRID = 2048;      // workgroups of the edge-parallel hub kernels (grid-stride over chunks)
 
+// Parts a window of `cnt` edges is queued in for the direct kernel: every part builds the window's whole bitmap
+// and ranks DIRECT_PART_EDGES of its edges or fewer, so that the few windows of 10^5 edges of a power-law graph do not
+// keep one workgroup busy long after every other one has finished (one workgroup took 0.31 ms for the R-MAT
+// benchmark graph's largest window, 256 000 edges; building the bitmap is the cheaper half of the work, 0.18 ns per
+// edge against 0.40 ns for ranking and writing).  cnt / DIRECT_PART_EDGES + 1 <= cnt / (MID_CAP + 1) above
+// DIRECT_SPLIT_MIN: the queue's capacity of nnz / (MID_CAP + 1) + 1 entries holds.
+constexpr int DIRECT_SPLIT_MIN = 32768, DIRECT_PART_EDGES = 16384, DIRECT_PARTS_MAX = 16;
+__host__ __device__ inline int direct_parts(int cnt)
+{
+    if (cnt <= DIRECT_SPLIT_MIN) return 1;
+    const int p = (cnt + DIRECT_PART_EDGES - 1) / DIRECT_PART_EDGES;
+    return p < DIRECT_PARTS_MAX ? p : DIRECT_PARTS_MAX;
+}
+
 enum { C_B1 = 0, C_B2 = 1, C_B3 = 2, C_B4 = 3, C_LARGE = 4, C_HUB = 5, C_DIRECT = 6, C_CHUNKS = 7, C_LARGE_NEXT = 8,
        C_DIRECT_NEXT = 9, C_WORDS = 16 };
 
@@ -64,8 +78,8 @@ struct WinWorkspace {
     int *uniq_count;      // [n_windows]
     int4 *list_b[4];      // [cap_b[i]]   windows of WAVE_CAP+1 .. B1_CAP, .. B2_CAP, .. MID_CAP, .. B4_CAP edges:
                           //              {window, first edge, edges, -}
-    int4 *list_direct;    // [cap_b[3]]   windows above MID_CAP edges on graphs of few column ranges (then list_b[3],
-                          //              list_large and list_hub stay empty)
+    int4 *list_direct;    // [cap_direct] windows above MID_CAP edges on graphs of few column ranges (then list_b[3],
+                          //              list_large and list_hub stay empty): {window, first edge, edges, part | parts << 8}
     int *list_large;      // [cap_large]  windows of B4_CAP+1 .. threshold edges
     int *list_hub;        // [slots]
     int *counters;        // [C_WORDS]
@@ -75,7 +89,7 @@ struct WinWorkspace {
     int *hub_grp;         // [slots * words_per_slot / HUB_GROUP]
     int *tmp_cols;        // [nnz]
     int *pack_win;        // [nnz / PACK_PER_WAVE + 2]  window of every PACK_PER_WAVE-th entry of win_cols
-    int cap_b[4], cap_large, slots, wps;
+    int cap_b[4], cap_direct, cap_large, slots, wps;
     size_t total;
 };
 
@@ -91,12 +105,16 @@ static WinWorkspace carve(void *ws, int n, int nnz, int n_windows)
     };
     const int lower[4] = {WAVE_CAP, B1_CAP, B2_CAP, MID_CAP};
     for (int i = 0; i < 4; ++i) w.cap_b[i] = nnz / (lower[i] + 1) + 1 < n_windows ? nnz / (lower[i] + 1) + 1 : n_windows;
+    {
+        const int64_t by_parts = static_cast<int64_t>(n_windows) * DIRECT_PARTS_MAX;
+        w.cap_direct = nnz / (MID_CAP + 1) + 1 < by_parts ? nnz / (MID_CAP + 1) + 1 : static_cast<int>(by_parts);
+    }
     w.cap_large = nnz / (B4_CAP + 1) + 1 < n_windows ? nnz / (B4_CAP + 1) + 1 : n_windows;
     w.slots = hub_slots(n, nnz);
     w.wps = hub_words_per_slot(n);
     w.uniq_count = reinterpret_cast<int *>(take(sizeof(int) * static_cast<size_t>(n_windows)));
     for (int i = 0; i < 4; ++i) w.list_b[i] = reinterpret_cast<int4 *>(take(sizeof(int4) * static_cast<size_t>(w.cap_b[i])));
-    w.list_direct = reinterpret_cast<int4 *>(take(sizeof(int4) * static_cast<size_t>(w.cap_b[3])));
+    w.list_direct = reinterpret_cast<int4 *>(take(sizeof(int4) * static_cast<size_t>(w.cap_direct)));
     w.list_large = reinterpret_cast<int *>(take(sizeof(int) * static_cast<size_t>(w.cap_large)));
     w.list_hub = reinterpret_cast<int *>(take(sizeof(int) * static_cast<size_t>(w.slots)));
     w.counters = reinterpret_cast<int *>(take(sizeof(int) * C_WORDS));
@@ -206,7 +224,9 @@ __global__ __launch_bounds__(1024) void win_classify_kernel(int n, int n_windows
             cls = cnt <= B1_CAP ? 0
                                 : (cnt <= B2_CAP ? 1 : (cnt <= MID_CAP ? 2 : (direct ? 6 : (cnt <= hub_thr ? (cnt <= B4_CAP ? 3 : 4) : 5))));
     }
-    if (cls >= 0) pos = atomicAdd(&cnt_s[cls], 1);
+    // a window above DIRECT_SPLIT_MIN edges is queued once per part (see win_direct_kernel)
+    const int parts = cls == 6 ? direct_parts(cnt) : 1;
+    if (cls >= 0) pos = atomicAdd(&cnt_s[cls], parts);
     __syncthreads();
     if (threadIdx.x < 7 && cnt_s[threadIdx.x] > 0)
         base_s[threadIdx.x] = atomicAdd(&counters[threadIdx.x], cnt_s[threadIdx.x]);  // C_B1 .. C_DIRECT
@@ -218,7 +238,8 @@ __global__ __launch_bounds__(1024) void win_classify_kernel(int n, int n_windows
     else if (cls == 3) list_b4[base_s[3] + pos] = make_int4(w, e0, cnt, 0);
     else if (cls == 4) list_large[base_s[4] + pos] = w;
     else if (cls == 5) list_hub[base_s[5] + pos] = w;
-    else if (cls == 6) list_direct[base_s[6] + pos] = make_int4(w, e0, cnt, 0);
+    else if (cls == 6)
+        for (int part = 0; part < parts; ++part) list_direct[base_s[6] + pos + part] = make_int4(w, e0, cnt, part | (parts << 8));
 }
 
 // ---- windows of at most WAVE_CAP edges: one wave, keys in registers --------------------------------
@@ -591,8 +612,10 @@ __global__ __launch_bounds__(64 * NW) void win_bitmap_wave_kernel(int n, int nnz
 // prefix of its piece + bits below its own, unique list written by the edges at their rank.  A window can have
 // any number of edges (its column ids are read again in the second phase, from L2), so this one kernel takes
 // what the two-level workgroup kernel and the edge-parallel hub kernels take on graphs of many column ranges,
-// where a pass over all edges per range would cost too much.  Windows come from a ticket counter (a few hundred
-// to a few thousand queue entries, very different in size).
+// where a pass over all edges per range would cost too much.  Queue entries come from a ticket counter (a few
+// hundred to a few thousand, very different in size); a window above DIRECT_SPLIT_MIN edges has several entries,
+// one per part of its edges (see direct_parts): every part builds the whole bitmap and ranks its own edges, the
+// unique list is the same whichever part writes an entry of it.
 constexpr int DB_WORDS = (1 << WB_RANGE_LOG2) / 32;  // bitmap words per range
 constexpr int DB_PIECES = DB_WORDS / 4;
 __global__ __launch_bounds__(1024) void win_direct_kernel(int n, const int *__restrict__ row_ptr,
@@ -621,21 +644,24 @@ __global__ __launch_bounds__(1024) void win_direct_kernel(int n, const int *__re
         if (tid == 0) ticket = atomicAdd(next_ticket, 1) + static_cast<int>(gridDim.x);
         const int4 ent = list[item];
         const int w = ent.x, e0 = ent.y, cnt = ent.z;
+        // the part of the window's edges this workgroup ranks (whole multiples of the workgroup, so that the parts'
+        // loads stay aligned); the bitmap is built from all of the window's edges by every part
+        const int parts = max(1, ent.w >> 8), part = ent.w & 255;
+        const int per_part = ((cnt + parts - 1) / parts + NT - 1) / NT * NT;
+        const int i_lo = min(cnt, part * per_part), i_hi = min(cnt, i_lo + per_part);
         const int r0 = w * blk_h;
         const int rows = min(n, r0 + blk_h) - r0;
         __syncthreads();  // the previous window is done with rp; the clearing of the bitmap is complete
         if (tid <= rows) rp[tid] = row_ptr[r0 + tid];
-        // f(column, index of the edge inside the window) for every edge, EB loads in flight per thread
-        auto for_edges = [&](auto f) {
-            for (int ib = tid; ib < cnt; ib += NT * EB) {
+        // f(column or -1, index of the edge inside the window) for the edges lo .. hi - 1, EB loads in flight per thread
+        // (the loads are unconditional, from an index clamped into the window: a load inside a branch is waited for at once)
+        auto for_edges = [&](int lo, int hi, auto f) {
+            for (int ib = lo + tid; ib < hi; ib += NT * EB) {
                 int c8[EB];
 #pragma unroll
-                for (int j = 0; j < EB; ++j) {
-                    const int i = ib + j * NT;
-                    c8[j] = i < cnt ? col_idx[e0 + i] : -1;
-                }
+                for (int j = 0; j < EB; ++j) c8[j] = col_idx[e0 + min(ib + j * NT, cnt - 1)];
 #pragma unroll
-                for (int j = 0; j < EB; ++j) f(c8[j], ib + j * NT);
+                for (int j = 0; j < EB; ++j) f(ib + j * NT < hi ? c8[j] : -1, ib + j * NT);
             }
         };
         int base = 0;
@@ -643,7 +669,7 @@ __global__ __launch_bounds__(1024) void win_direct_kernel(int n, const int *__re
             const int lo = range << WB_RANGE_LOG2;
             if (range > 0) __syncthreads();  // the clearing after the previous range is complete
             bool any = false;
-            for_edges([&](int col, int) {
+            for_edges(0, cnt, [&](int col, int) {
                 const unsigned c = static_cast<unsigned>(col - lo);
                 if (col >= 0 && c < (1u << WB_RANGE_LOG2)) {
                     // the popular columns of a large window are hit thousands of times and atomics on one address
@@ -675,7 +701,7 @@ __global__ __launch_bounds__(1024) void win_direct_kernel(int n, const int *__re
             }
             __syncthreads();
             const int range_total = woff[NW];
-            for_edges([&](int col, int i) {
+            for_edges(i_lo, i_hi, [&](int col, int i) {
                 const unsigned c = static_cast<unsigned>(col - lo);
                 if (col >= 0 && c < (1u << WB_RANGE_LOG2)) {
                     const int piece = c >> 7, j = (c >> 5) & 3;
@@ -694,13 +720,13 @@ __global__ __launch_bounds__(1024) void win_direct_kernel(int n, const int *__re
                 *reinterpret_cast<uint4 *>(&bits[(wave * PW + lane + 64 * q) * 4]) = make_uint4(0u, 0u, 0u, 0u);
         }
         if (tid == 0) {
-            uniq_count[w] = base;
+            if (part == 0) uniq_count[w] = base;
             next_s = ticket;
         }
         __syncthreads();  // rp (written before the first barrier of the window) and next_s
         for (int r = wave; r < rows; r += NW) {
-            const int b = min(rp[r + 1], e0 + cnt);
-            for (int e = max(rp[r], e0) + lane; e < b; e += 64) edge_to_row[e] = r0 + r;
+            const int b = min(rp[r + 1], e0 + i_hi);
+            for (int e = max(rp[r], e0 + i_lo) + lane; e < b; e += 64) edge_to_row[e] = r0 + r;
         }
         item = next_s;
     }
@@ -1347,7 +1373,7 @@ int32_t launch_build_windows(const ftc_csr &g, ftc_windows &w, void *ws, size_t 
                        dim3(64 * NW), 0, STREAM, g.n, g.nnz, g.row_ptr, g.col_idx, w.blk_h, w.edge_to_row, w.edge_to_col, \
                        k.uniq_count, k.tmp_cols, k.list_b[I], k.counters + COUNTER)
         if (st == FTC_OK && g.nnz > MID_CAP && direct) {
-            hipLaunchKernelGGL(win_direct_kernel, dim3(k.cap_b[3] < n_cu ? k.cap_b[3] : n_cu), dim3(1024), 0, s_large, g.n,
+            hipLaunchKernelGGL(win_direct_kernel, dim3(k.cap_direct < n_cu ? k.cap_direct : n_cu), dim3(1024), 0, s_large, g.n,
                                g.row_ptr, g.col_idx, w.blk_h, w.edge_to_row, w.edge_to_col, k.uniq_count, k.tmp_cols,
                                k.list_direct, k.counters + C_DIRECT, k.counters + C_DIRECT_NEXT);
             st = launch_status("build_windows direct bitmap (above 4096 edges)");
