@@ -1387,7 +1387,7 @@ int32_t launch_build_windows(const ftc_csr &g, ftc_windows &w, void *ws, size_t 
             st = launch_status("build_windows bitmap (2049 .. 4096 edges)");
         }
         if (st == FTC_OK && g.nnz > B1_CAP) {
-            FTC_WB(2048, 2, 8, 1, C_B2, s_mid);
+            FTC_WB(2048, 2, 8, 1, C_B2, direct ? s_hub : s_mid);  // the hub stream is free when the direct kernel takes the hubs
             st = launch_status("build_windows bitmap (1025 .. 2048 edges)");
         }
         if (st == FTC_OK) {
