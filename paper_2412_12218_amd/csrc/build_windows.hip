@@ -73,6 +73,8 @@ static int hub_slots(int n, int nnz)
 static int hub_words_per_slot(int n) { return ((n + 31) / 32 + HUB_GROUP - 1) / HUB_GROUP * HUB_GROUP; }
 
 constexpr int PACK_PER_WAVE = 1024;  // entries of win_cols that one wave of the pack kernel copies
+constexpr int SCAN_CHUNK = 1024;     // windows per workgroup of the two-level scan
+constexpr int SCAN_CHUNKS_MAX = 4096;  // beyond that many chunks the single-workgroup scan runs
 
 struct WinWorkspace {
     int *uniq_count;      // [n_windows]
@@ -89,6 +91,8 @@ struct WinWorkspace {
     int *hub_grp;         // [slots * words_per_slot / HUB_GROUP]
     int *tmp_cols;        // [nnz]
     int *pack_win;        // [nnz / PACK_PER_WAVE + 2]  window of every PACK_PER_WAVE-th entry of win_cols
+    int *chunk_uniq;      // [ceil(n_windows / SCAN_CHUNK)]  unique columns of every chunk of windows
+    long long *chunk_blocks;  // the same for the tile counts
     int cap_b[4], cap_direct, cap_large, slots, wps;
     size_t total;
 };
@@ -124,6 +128,11 @@ static WinWorkspace carve(void *ws, int n, int nnz, int n_windows)
     w.hub_grp = reinterpret_cast<int *>(take(sizeof(int) * static_cast<size_t>(w.slots) * (w.wps / HUB_GROUP)));
     w.tmp_cols = reinterpret_cast<int *>(take(sizeof(int) * static_cast<size_t>(nnz)));
     w.pack_win = reinterpret_cast<int *>(take(sizeof(int) * (static_cast<size_t>(nnz) / PACK_PER_WAVE + 2)));
+    {
+        const size_t chunks = (static_cast<size_t>(n_windows) + SCAN_CHUNK - 1) / SCAN_CHUNK;
+        w.chunk_uniq = reinterpret_cast<int *>(take(sizeof(int) * chunks));
+        w.chunk_blocks = reinterpret_cast<long long *>(take(sizeof(long long) * chunks));
+    }
     w.total = off;
     return w;
 }
@@ -1201,6 +1210,121 @@ __global__ __launch_bounds__(1024) void win_scan_kernel(int n_windows, int blk_w
     }
 }
 
+// ---- the same scan on many workgroups ------------------------------------------------------------------
+// A single workgroup needs 23 us for 65536 windows, all of it latency.  Two small kernels instead: every
+// workgroup adds up the unique counts (and tile counts) of its SCAN_CHUNK windows; then every workgroup adds
+// the sums of the chunks before its own (at most SCAN_CHUNKS_MAX of them), scans its own windows and writes
+// win_col_ptr, block_partition and, for every run of PACK_PER_WAVE entries of win_cols that begins inside
+// one of its lists, the window that holds the run's first entry (what win_pack_plan_kernel writes after
+// the single-workgroup scan).  Integer sums: the result does not depend on the order.
+__device__ __forceinline__ int tiles_of(int u, int blk_w, int shift)
+{
+    return shift >= 0 ? (u + blk_w - 1) >> shift : (u + blk_w - 1) / blk_w;
+}
+
+__device__ __forceinline__ void load_counts4(const int *__restrict__ uniq_count, int first, int n_windows, int (&u)[4])
+{
+    if (first + 3 < n_windows) {  // uniq_count lives in the workspace: 256-byte aligned
+        const int4 v = *reinterpret_cast<const int4 *>(uniq_count + first);
+        u[0] = v.x; u[1] = v.y; u[2] = v.z; u[3] = v.w;
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) u[j] = first + j < n_windows ? uniq_count[first + j] : 0;
+    }
+}
+
+__global__ __launch_bounds__(256) void win_chunk_sums_kernel(int n_windows, int blk_w, const int *__restrict__ uniq_count,
+                                                             int *__restrict__ chunk_uniq,
+                                                             long long *__restrict__ chunk_blocks)
+{
+    __shared__ int su[4];
+    __shared__ long long sb[4];
+    const int tid = threadIdx.x;
+    const int shift = (blk_w & (blk_w - 1)) == 0 ? __ffs(blk_w) - 1 : -1;
+    int u[4];
+    load_counts4(uniq_count, blockIdx.x * SCAN_CHUNK + tid * 4, n_windows, u);
+    int a = u[0] + u[1] + u[2] + u[3];
+    long long b = static_cast<long long>(tiles_of(u[0], blk_w, shift)) + tiles_of(u[1], blk_w, shift) +
+                  tiles_of(u[2], blk_w, shift) + tiles_of(u[3], blk_w, shift);
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) {
+        a += __shfl_xor(a, m, 64);
+        b += __shfl_xor(b, m, 64);
+    }
+    if ((tid & 63) == 0) { su[tid >> 6] = a; sb[tid >> 6] = b; }
+    __syncthreads();
+    if (tid == 0) {
+        chunk_uniq[blockIdx.x] = su[0] + su[1] + su[2] + su[3];
+        chunk_blocks[blockIdx.x] = sb[0] + sb[1] + sb[2] + sb[3];
+    }
+}
+
+__global__ __launch_bounds__(256) void win_chunk_scan_kernel(int n_windows, int blk_w, const int *__restrict__ uniq_count,
+                                                             const int *__restrict__ chunk_uniq,
+                                                             const long long *__restrict__ chunk_blocks,
+                                                             int *__restrict__ win_col_ptr,
+                                                             int *__restrict__ block_partition,
+                                                             int64_t *__restrict__ summary, int *__restrict__ pack_win)
+{
+    __shared__ int su[4];
+    __shared__ long long sb[4];
+    __shared__ int wave_tot[4];
+    const int tid = threadIdx.x;
+    const int shift = (blk_w & (blk_w - 1)) == 0 ? __ffs(blk_w) - 1 : -1;
+    const bool vec_ok = ((reinterpret_cast<uintptr_t>(win_col_ptr) | reinterpret_cast<uintptr_t>(block_partition)) & 15u) == 0;
+    const int first = blockIdx.x * SCAN_CHUNK + tid * 4;
+    int u[4];
+    load_counts4(uniq_count, first, n_windows, u);
+    // sums of the chunks before this one (and, in the last workgroup, of all chunks: the summary)
+    const bool last = blockIdx.x == gridDim.x - 1;
+    int a = 0;
+    long long b = 0;
+    for (int c = tid; c < static_cast<int>(blockIdx.x); c += 256) {
+        a += chunk_uniq[c];
+        if (last) b += chunk_blocks[c];
+    }
+    if (last && tid == 0) b += chunk_blocks[blockIdx.x];
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) {
+        a += __shfl_xor(a, m, 64);
+        b += __shfl_xor(b, m, 64);
+    }
+    if ((tid & 63) == 0) { su[tid >> 6] = a; sb[tid >> 6] = b; }
+    __syncthreads();
+    const int carry = su[0] + su[1] + su[2] + su[3];
+    int chunk_total;
+    const int run = carry + block_scan_one_barrier<256>(u[0] + u[1] + u[2] + u[3], wave_tot, &chunk_total);
+    const int p[5] = {run, run + u[0], run + u[0] + u[1], run + u[0] + u[1] + u[2], run + u[0] + u[1] + u[2] + u[3]};
+    if (vec_ok && first + 3 < n_windows) {
+        *reinterpret_cast<int4 *>(win_col_ptr + first) = make_int4(p[0], p[1], p[2], p[3]);
+        *reinterpret_cast<int4 *>(block_partition + first) =
+            make_int4(tiles_of(u[0], blk_w, shift), tiles_of(u[1], blk_w, shift), tiles_of(u[2], blk_w, shift),
+                      tiles_of(u[3], blk_w, shift));
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (first + j < n_windows) {
+                win_col_ptr[first + j] = p[j];
+                block_partition[first + j] = tiles_of(u[j], blk_w, shift);
+            }
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        if (first + j < n_windows) {
+            // runs of the pack kernel that begin inside this window's list
+            for (long long c = (p[j] + static_cast<long long>(PACK_PER_WAVE) - 1) / PACK_PER_WAVE; c * PACK_PER_WAVE < p[j + 1]; ++c)
+                pack_win[c] = first + j;
+            if (first + j == n_windows - 1) {
+                pack_win[(p[j + 1] + static_cast<long long>(PACK_PER_WAVE) - 1) / PACK_PER_WAVE] = first + j;
+                win_col_ptr[n_windows] = p[j + 1];
+                summary[0] = p[j + 1];
+            }
+        }
+    }
+    if (last && tid == 0) summary[1] = sb[0] + sb[1] + sb[2] + sb[3];
+}
+
 // The pack kernel's work units are runs of PACK_PER_WAVE entries of win_cols.  Every window names
 // itself to the runs that begin inside its list (none for most windows; at most n / PACK_PER_WAVE + 1
 // for one window, since a list has at most n entries); the entry after the last run holds the last
@@ -1430,13 +1554,23 @@ int32_t launch_build_windows(const ftc_csr &g, ftc_windows &w, void *ws, size_t 
         }
     }
     if (st != FTC_OK) return st;
-    hipLaunchKernelGGL(win_scan_kernel, dim3(1), dim3(1024), 0, s, w.n_windows, w.blk_w, k.uniq_count,
-                       w.win_col_ptr, w.block_partition, w.summary);
-    st = launch_status("build_windows scan");
-    if (st != FTC_OK) return st;
-    if (g.nnz == 0) return FTC_OK;
-    hipLaunchKernelGGL(win_pack_plan_kernel, dim3((w.n_windows + 255) / 256), dim3(256), 0, s, w.n_windows, w.win_col_ptr,
-                       k.pack_win);
+    const int chunks = ceil_div(w.n_windows, SCAN_CHUNK);
+    if (chunks > 1 && chunks <= SCAN_CHUNKS_MAX && g.nnz > 0) {
+        hipLaunchKernelGGL(win_chunk_sums_kernel, dim3(chunks), dim3(256), 0, s, w.n_windows, w.blk_w, k.uniq_count,
+                           k.chunk_uniq, k.chunk_blocks);
+        hipLaunchKernelGGL(win_chunk_scan_kernel, dim3(chunks), dim3(256), 0, s, w.n_windows, w.blk_w, k.uniq_count,
+                           k.chunk_uniq, k.chunk_blocks, w.win_col_ptr, w.block_partition, w.summary, k.pack_win);
+        st = launch_status("build_windows scan (chunks)");
+        if (st != FTC_OK) return st;
+    } else {
+        hipLaunchKernelGGL(win_scan_kernel, dim3(1), dim3(1024), 0, s, w.n_windows, w.blk_w, k.uniq_count,
+                           w.win_col_ptr, w.block_partition, w.summary);
+        st = launch_status("build_windows scan");
+        if (st != FTC_OK) return st;
+        if (g.nnz == 0) return FTC_OK;
+        hipLaunchKernelGGL(win_pack_plan_kernel, dim3((w.n_windows + 255) / 256), dim3(256), 0, s, w.n_windows, w.win_col_ptr,
+                           k.pack_win);
+    }
     hipLaunchKernelGGL(win_pack_kernel, dim3(ceil_div(g.nnz, 4 * PACK_PER_WAVE)), dim3(256), 0, s,
                        w.n_windows, g.row_ptr, w.blk_h, w.win_col_ptr, k.pack_win, k.tmp_cols, w.win_cols);
     return launch_status("build_windows pack");
