@@ -1480,9 +1480,24 @@ int32_t launch_build_windows(const ftc_csr &g, ftc_windows &w, void *ws, size_t 
             s_hub = static_cast<hipStream_t>(side->stream[2]);
         }
     }
-    hipLaunchKernelGGL(win_wave_kernel, dim3(w.n_windows), dim3(64), 0, s, g.n, g.row_ptr, g.col_idx, w.blk_h,
-                       w.edge_to_row, w.edge_to_col, k.uniq_count, k.tmp_cols);
-    st = launch_status("build_windows wave");
+    // The one-workgroup bitmap kernel is the longest chain of the build.  With side streams it stays on the caller's
+    // stream and is launched first (a dependency between streams costs about 20 us before the dependent kernel
+    // starts, and again at the join if the side stream is the last to finish); the wave kernel takes its place on the
+    // side stream.
+    hipStream_t s_wave = s;
+    if (queued && g.nnz > MID_CAP && direct) {
+        hipLaunchKernelGGL(win_direct_kernel, dim3(k.cap_direct < n_cu ? k.cap_direct : n_cu), dim3(1024), 0, s, g.n,
+                           g.row_ptr, g.col_idx, w.blk_h, w.edge_to_row, w.edge_to_col, k.uniq_count, k.tmp_cols,
+                           k.list_direct, k.counters + C_DIRECT, k.counters + C_DIRECT_NEXT);
+        st = launch_status("build_windows direct bitmap (above 4096 edges)");
+        if (st != FTC_OK && !side) return st;
+        s_wave = s_large;
+    }
+    if (st == FTC_OK) {
+        hipLaunchKernelGGL(win_wave_kernel, dim3(w.n_windows), dim3(64), 0, s_wave, g.n, g.row_ptr, g.col_idx, w.blk_h,
+                           w.edge_to_row, w.edge_to_col, k.uniq_count, k.tmp_cols);
+        st = launch_status("build_windows wave");
+    }
     if (queued) {
         // persistent grids: as many workgroups as fit on the chip at once (five 256-thread or one
         // 1024-thread workgroup per CU), never more than the queue can hold
@@ -1496,12 +1511,6 @@ int32_t launch_build_windows(const ftc_csr &g, ftc_windows &w, void *ws, size_t 
     hipLaunchKernelGGL((win_bitmap_wave_kernel<F, NW>), dim3(k.cap_b[I] < PER_CU * n_cu ? k.cap_b[I] : PER_CU * n_cu), \
                        dim3(64 * NW), 0, STREAM, g.n, g.nnz, g.row_ptr, g.col_idx, w.blk_h, w.edge_to_row, w.edge_to_col, \
                        k.uniq_count, k.tmp_cols, k.list_b[I], k.counters + COUNTER)
-        if (st == FTC_OK && g.nnz > MID_CAP && direct) {
-            hipLaunchKernelGGL(win_direct_kernel, dim3(k.cap_direct < n_cu ? k.cap_direct : n_cu), dim3(1024), 0, s_large, g.n,
-                               g.row_ptr, g.col_idx, w.blk_h, w.edge_to_row, w.edge_to_col, k.uniq_count, k.tmp_cols,
-                               k.list_direct, k.counters + C_DIRECT, k.counters + C_DIRECT_NEXT);
-            st = launch_status("build_windows direct bitmap (above 4096 edges)");
-        }
         if (st == FTC_OK && g.nnz > MID_CAP && !direct) {
             FTC_WB(16384, 16, 1, 3, C_B4, s_large);
             st = launch_status("build_windows bitmap (4097 .. 16384 edges)");
@@ -1515,7 +1524,9 @@ int32_t launch_build_windows(const ftc_csr &g, ftc_windows &w, void *ws, size_t 
             st = launch_status("build_windows bitmap (1025 .. 2048 edges)");
         }
         if (st == FTC_OK) {
-            FTC_WB(1024, 1, 13, 0, C_B1, s_mid);
+            // last on the caller's stream when that stream also runs the one-workgroup kernel: the stream that
+            // finishes last should be the caller's, whose wait for the side streams then costs nothing
+            FTC_WB(1024, 1, 13, 0, C_B1, (direct && g.nnz > MID_CAP) ? s : s_mid);
             st = launch_status("build_windows bitmap (257 .. 1024 edges)");
         }
 #undef FTC_WB
