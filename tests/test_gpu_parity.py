@@ -143,10 +143,12 @@ def size_class_graph(n, seed):
 
 
 @pytest.mark.parametrize("n,blk", [(40_003, (16, 8)), (40_003, (64, 8)), (40_003, (5, 3)),
-                                   ((1 << 21) + 4099, (16, 8))])
+                                   ((1 << 21) + 4099, (16, 8)), ((1 << 22) + 4099, (16, 8))])
 def test_build_windows_size_classes(oracle, n, blk):
-    """Every size class of the window build, also on a graph with more than 2^21 nodes (wider bitmap
-    ranges in LDS, hub bitmaps of more than 2^16 words)."""
+    """Every size class of the window build, also on a graph with more than 2^21 nodes (three column
+    ranges per large window, windows queued in parts) and on one with more than 2^22 nodes (more than four
+    ranges: the two-level workgroup kernels and the edge-parallel hub kernels with bitmaps of more than 2^16
+    words take the large windows there)."""
     g = size_class_graph(n, seed=n % 1000)
     say(f"build_windows classes n={g.n} nnz={g.nnz} blk={blk}")
     ref = oracle.build_windows(g.row_ptr, g.col_idx, *blk)
@@ -168,12 +170,14 @@ def test_build_windows_degenerate(oracle):
     check_windows(B.ftc_build_windows(dev_graph(g)), oracle.build_windows(g.row_ptr, g.col_idx))
 
 
-@pytest.mark.parametrize("which", ["classes", "cfg5s", "cfg1", "no_edges"])
+@pytest.mark.parametrize("which", ["classes", "classes_many_ranges", "cfg5s", "cfg1", "no_edges"])
 def test_build_windows_concurrent_on_the_callers_side_streams(oracle, graphs, which):
     """The same index with the independent kernels on three side streams of the caller's: bit-exact against
     the oracle, twice with the same set of streams, and equal to the call that runs in stream order."""
     if which == "classes":
         g = size_class_graph(40_003, seed=3)
+    elif which == "classes_many_ranges":   # more than four 2^20-column ranges: the other set of large-window kernels
+        g = size_class_graph((1 << 22) + 77, seed=4)
     elif which == "no_edges":
         g = synth.Graph(33, np.zeros(34, dtype=np.int32), np.zeros(0, dtype=np.int32))
     else:
