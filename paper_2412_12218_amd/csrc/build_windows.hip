@@ -6,20 +6,25 @@
 //   1. up to WAVE_CAP edges: one wave sorts the column ids in registers with a bitonic network
 //      (lane shuffles, no barriers), de-duplicates with a flag scan and finds every edge's rank by
 //      binary search in the unique list parked in LDS;
-//   2. up to MID_CAP edges: one wave per window with a two-level bitmap in LDS (a coarse bitmap
-//      names the 32-column words the window touches, the fine bitmap holds one word per touched
-//      word): set bits, prefix sums of the popcounts, rank = prefix of the word + bits below the
-//      column's own.  The wave keeps its column ids in registers and never meets a workgroup
-//      barrier; a CU works on as many windows at once as their bitmaps fit into its LDS;
-//   2b. up to the hub threshold: the same two-level bitmap, one workgroup of 1024 threads per window;
-//   3. hub windows (more edges than the threshold, at most HUB_SLOTS_MAX of them by the choice
-//      of the threshold): edge-parallel over the whole GPU with one bitmap of n bits per hub in
-//      global memory: set bits (atomics), one workgroup per hub turns popcounts into prefixes
-//      and emits the unique list, then every edge reads its rank.
+//   2. up to MID_CAP edges, in three size classes: one, two or four waves per window with a two-level
+//      bitmap in LDS (a coarse bitmap names the 32-column words the window touches, the fine bitmap
+//      holds one word per touched word): set bits, prefix sums of the popcounts, rank = prefix of the
+//      word + bits below the column's own.  The waves keep their column ids in registers; a CU works
+//      on as many windows at once as their bitmaps fit into its LDS;
+//   3. above MID_CAP edges on graphs of up to DIRECT_MAX_RANGES ranges of 2^20 columns: one workgroup
+//      of 1024 threads with the whole bitmap of a range in LDS (no coarse level); windows of 10^5
+//      edges are queued in parts, each of which builds the bitmap and ranks its share of the edges;
+//   3b. on larger graphs instead: the two-level bitmap with sixteen waves up to B4_CAP edges, a
+//      workgroup of 1024 threads up to the hub threshold, and hub windows (more edges than the
+//      threshold, at most HUB_SLOTS_MAX of them by the choice of the threshold) edge-parallel over
+//      the whole GPU with one bitmap of n bits per hub in global memory: set bits (atomics), one
+//      workgroup per hub turns popcounts into prefixes, then every edge reads its rank.
 // All of them also write edge_to_row for their window's edges.
 // The unique lists are first written at the window's edge offset of a temporary array (a
-// window never has more distinct columns than edges), then a scan over the windows gives
-// win_col_ptr / block_partition / summary and a last kernel packs the lists into win_cols.
+// window never has more distinct columns than edges), then a scan over the windows (chunk sums, then
+// chunk scans) gives win_col_ptr / block_partition / summary and a last kernel packs the lists into
+// win_cols.  The kernels of the size classes are independent: with side streams from the caller they
+// run side by side.
 #include "ftc_common.hpp"
 
 
