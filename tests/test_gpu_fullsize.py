@@ -9,7 +9,7 @@ import torch
 import synth
 from parity import TOL, check_windows, dev_graph, norm_err, quantise
 from paper_2412_12218_amd import binding as B
-from paper_2412_12218_amd.models import HotPath
+from paper_2412_12218_amd.models import HotPath, PlannedGraph
 
 pytestmark = pytest.mark.gpu
 F32, F16, BF16 = torch.float32, torch.float16, torch.bfloat16
@@ -109,6 +109,71 @@ def test_cfg4_spmm_sddmm_full(oracle, threads):
     serr = norm_err(s, sref, sab)
     say(f"  sddmm (cosine) err {serr:.3e}")
     assert serr < 2e-3
+
+
+def test_cfg4_wide_features_sampled_rows(oracle, threads):
+    """The benchmark's out-of-cache point: cfg4 with a 512 MB feature matrix (bf16, D = 256).  The kernels run on the
+    whole graph; the oracle computes 40 000 sampled rows (a sub-matrix of those rows with all columns kept) and every
+    one of their elements and entries is compared."""
+    g = synth.config_graph(4)
+    D = 256
+    say(f"cfg4 D={D} n={g.n} nnz={g.nnz}")
+    dg = dev_graph(g)
+    win = B.ftc_build_windows(dg)
+    vals64, _ = oracle.gcn_norm(g.row_ptr, g.col_idx)
+    vals32 = vals64.astype(np.float32)
+    Xd, X64 = quantise(synth.uniform_features(g.n, D, seed=4), BF16)
+    out = B.ftc_spmm(dg, win, torch.from_numpy(vals32).cuda(), Xd)
+    s = B.ftc_sddmm(dg, win, Xd, Xd, cosine=True)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(44)
+    rows = np.sort(rng.choice(g.n, size=40_000, replace=False))
+    rows[:3] = [0, 1, 2]
+    rows[-1] = g.n - 1
+    rows = np.unique(rows)
+    rp = g.row_ptr.astype(np.int64)
+    deg = (rp[rows + 1] - rp[rows])
+    sub_ptr = np.zeros(rows.size + 1, dtype=np.int64)
+    sub_ptr[1:] = np.cumsum(deg)
+    entries = np.concatenate([np.arange(rp[r], rp[r + 1]) for r in rows])
+    sub_col = g.col_idx[entries]
+    # SpMM of the sampled rows: a matrix with those rows and all n columns
+    ref, ab = oracle.spmm(sub_ptr.astype(np.int32), sub_col, vals32[entries].astype(np.float64), X64)
+    err = norm_err(out[torch.from_numpy(rows).cuda()], ref, ab)
+    say(f"  spmm err on {rows.size} rows {err:.3e}")
+    assert err < 2e-3
+    # cosine scores of their entries: x_i is row rows[k] of X
+    rinv64 = oracle.row_rnorm(X64)
+    Xrows = X64[rows]
+    dots = np.empty(entries.size)
+    dabs = np.empty(entries.size)
+    pos = 0
+    for k in range(rows.size):
+        c = sub_col[sub_ptr[k]:sub_ptr[k + 1]]
+        prod = X64[c] * Xrows[k]
+        dots[pos:pos + c.size] = prod.sum(axis=1) * rinv64[rows[k]] * rinv64[c]
+        dabs[pos:pos + c.size] = np.abs(prod).sum(axis=1) * rinv64[rows[k]] * rinv64[c]
+        pos += c.size
+    serr = norm_err(s[torch.from_numpy(entries).cuda()], dots, dabs)
+    say(f"  sddmm (cosine) err on {entries.size} entries {serr:.3e}")
+    assert serr < 2e-3
+
+
+def test_cfg5_planned_graph_agnn_layer_full(oracle, threads):
+    """The benchmark's relabelled leg at full size: the per-graph plan (degree classes on the R-MAT workload), one
+    AGNN layer on the relabelled graph, features in and results out through the permutations, every element against
+    the oracle on the graph as given."""
+    g = synth.config_graph(5)
+    dg = dev_graph(g)
+    pg = PlannedGraph(dg, 32, F16)
+    say(f"cfg5 plan applied: {pg.applied}, sum_uniq {pg.sum_uniq} (given {pg.sum_uniq_given})")
+    assert pg.applied == "degree classes" and pg.sum_uniq < pg.sum_uniq_given
+    Hd, H64 = quantise(synth.normal_features(g.n, 32, seed=55), F16)
+    ref, ab, _ = oracle.agnn_layer(g.row_ptr, g.col_idx, H64, 1.0)
+    out = pg.leave(B.ftc_agnn_layer(pg.g, pg.win, pg.enter(Hd), beta=1.0))
+    err = norm_err(out, ref, ab)
+    say(f"  agnn_layer through the plan err {err:.3e}")
+    assert err < 2e-3
 
 
 def test_cfg5_models_layer_by_layer(oracle, threads):
