@@ -127,8 +127,8 @@ __global__ __launch_bounds__(256) void agnn_backward_fused_kernel(
         const int i = j * 64 + lane;
         if (i < n_valid) {
             const int p = i + i / RUN;
-            s_col[p] = col_idx[base + i];
-            s_row[p] = edge_to_row[base + i];
+            s_col[p] = __builtin_nontemporal_load(col_idx + base + i);  // streamed once: no need to keep them in L2
+            s_row[p] = __builtin_nontemporal_load(edge_to_row + base + i);
         }
     }
     const int prev_row = (active && base > 0) ? edge_to_row[base - 1] : -1;

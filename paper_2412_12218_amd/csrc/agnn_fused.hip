@@ -74,7 +74,7 @@ __global__ __launch_bounds__(256) void agnn_fused_kernel(int nnz, int n_ranges, 
         for (int j = 0; j < AG_R / 64; ++j) {
             const int i = j * 64 + lane;
             const int p = i + i / RUN;
-            s_col[p] = col_idx[base + i];
+            s_col[p] = __builtin_nontemporal_load(col_idx + base + i);  // streamed once: no need to keep it in L2
             s_row[p] = rows[j];
         }
     } else {
@@ -83,8 +83,8 @@ __global__ __launch_bounds__(256) void agnn_fused_kernel(int nnz, int n_ranges, 
             const int i = j * 64 + lane;
             if (i < n_valid) {
                 const int p = i + i / RUN;
-                s_col[p] = col_idx[base + i];
-                s_row[p] = edge_to_row[base + i];
+                s_col[p] = __builtin_nontemporal_load(col_idx + base + i);  // streamed once: no need to keep it in L2
+                s_row[p] = __builtin_nontemporal_load(edge_to_row + base + i);
             }
         }
     }
@@ -116,7 +116,7 @@ __global__ __launch_bounds__(256) void agnn_fused_kernel(int nnz, int n_ranges, 
             float o[VEC];
 #pragma unroll
             for (int j = 0; j < VEC; ++j) o[j] = acc[j] * inv;
-            store_vec<VEC>(out, static_cast<int64_t>(row) * ldo + sub * VEC, odt, o);
+            store_vec_nt<VEC>(out, static_cast<int64_t>(row) * ldo + sub * VEC, odt, o);
             if constexpr (KEEP)
                 if (out32) store_vec<VEC>(out32, static_cast<int64_t>(row) * ld32 + sub * VEC, FTC_F32, o);  // unrounded copy
         }

@@ -320,6 +320,49 @@ __device__ __forceinline__ void store_vec(void *base, int64_t idx, int dtype, co
     }
 }
 
+// The same store with the non-temporal hint: rows that are written once and not read again by this kernel
+// should not push gathered rows out of L2.
+typedef uint32_t ftc_u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t ftc_u32x2 __attribute__((ext_vector_type(2)));
+typedef float ftc_f32x4 __attribute__((ext_vector_type(4)));
+template <int NV>
+__device__ __forceinline__ void store_vec_nt(void *base, int64_t idx, int dtype, const float (&f)[NV])
+{
+    if (dtype == FTC_F32) {
+        float *p = static_cast<float *>(base) + idx;
+        if constexpr (NV >= 4) {
+#pragma unroll
+            for (int k = 0; k < NV / 4; ++k) {
+                ftc_f32x4 v = {f[4 * k], f[4 * k + 1], f[4 * k + 2], f[4 * k + 3]};
+                __builtin_nontemporal_store(v, reinterpret_cast<ftc_f32x4 *>(p) + k);
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < NV; ++k) __builtin_nontemporal_store(f[k], p + k);
+        }
+    } else {
+        uint16_t *q = static_cast<uint16_t *>(base) + idx;
+        if constexpr (NV == 8 || NV == 4) {
+            uint32_t w[NV / 2];
+#pragma unroll
+            for (int k = 0; k < NV / 2; ++k) {
+                const uint32_t lo = dtype == FTC_F16 ? f32_to_f16_bits(f[2 * k]) : f32_to_bf16_bits(f[2 * k]);
+                const uint32_t hi = dtype == FTC_F16 ? f32_to_f16_bits(f[2 * k + 1]) : f32_to_bf16_bits(f[2 * k + 1]);
+                w[k] = lo | (hi << 16);
+            }
+            if constexpr (NV == 8) {
+                ftc_u32x4 v = {w[0], w[1], w[2], w[3]};
+                __builtin_nontemporal_store(v, reinterpret_cast<ftc_u32x4 *>(q));
+            } else {
+                ftc_u32x2 v = {w[0], w[1]};
+                __builtin_nontemporal_store(v, reinterpret_cast<ftc_u32x2 *>(q));
+            }
+        } else {
+            store_vec<NV>(base, idx, dtype, f);
+        }
+    }
+}
+
 template <int CTRL>
 __device__ __forceinline__ float dpp_add(float v)
 {

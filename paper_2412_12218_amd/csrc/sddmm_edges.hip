@@ -56,7 +56,7 @@ __global__ __launch_bounds__(256) void sddmm_edges_kernel(int nnz, int n_ranges,
             const int p = i + i / RUN;
             const int er = from_starts ? rows[j] : edge_to_row[base + i];
             const bool skip = dense && dense[er >> 4];  // that window goes to the matrix cores
-            s_col[p] = skip ? -1 : col_idx[base + i];
+            s_col[p] = skip ? -1 : __builtin_nontemporal_load(col_idx + base + i);  // streamed once
             s_row[p] = skip ? -1 : er;
         }
     }
@@ -115,7 +115,7 @@ __global__ __launch_bounds__(256) void sddmm_edges_kernel(int nnz, int n_ranges,
         if (i < n_valid && s_col[pp] >= 0) {
             const int p = pp;
             const float scale = alpha * (rs ? rs[s_row[p]] : 1.f) * (cs ? cs[s_col[p]] : 1.f);
-            out[base + i] = scale * s_dot[p];
+            __builtin_nontemporal_store(scale * s_dot[p], out + base + i);  // written once, not read here
         }
     }
 }

@@ -98,9 +98,9 @@ __global__ __launch_bounds__(256) void spmm_seg_kernel(int nnz, int n_ranges, co
             const int p = i + i / RUN;
             const int er = from_starts ? rows[j] : edge_to_row[base + i];
             // edges of windows that go to the matrix cores are skipped here (column -1)
-            s_col[p] = (dense && dense[er >> 4]) ? -1 : col_idx[base + i];
+            s_col[p] = (dense && dense[er >> 4]) ? -1 : __builtin_nontemporal_load(col_idx + base + i);  // streamed once
             s_row[p] = er;
-            if constexpr (VALS) s_val[p] = vals[base + i];
+            if constexpr (VALS) s_val[p] = __builtin_nontemporal_load(vals + base + i);
         }
     }
     const int prev_row = (active && base > 0) ? edge_to_row[base - 1] : -1;
@@ -125,7 +125,7 @@ __global__ __launch_bounds__(256) void spmm_seg_kernel(int nnz, int n_ranges, co
             const float f = epi.factor(row);
 #pragma unroll
             for (int j = 0; j < VEC; ++j) o[j] = epi.apply(f, acc[j]);
-            store_vec<VEC>(out, static_cast<int64_t>(row) * ldo + sub * VEC, odt, o);
+            store_vec_nt<VEC>(out, static_cast<int64_t>(row) * ldo + sub * VEC, odt, o);
         }
     };
 
