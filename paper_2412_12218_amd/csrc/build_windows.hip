@@ -341,13 +341,15 @@ __device__ __forceinline__ void condense_window_wave(int w, int r0, int rows, co
                 const int mid = (lo + hi) >> 1;
                 if (uniq_lds[mid] < orig[k]) lo = mid + 1; else hi = mid;
             }
-            edge_to_col[e0 + i] = lo;
+            // the per-edge arrays are written once and read by no kernel of the build: the non-temporal hint keeps
+            // them from pushing the unique lists (which the pack kernel reads back) out of the caches
+            __builtin_nontemporal_store(lo, edge_to_col + e0 + i);
             int a = 0, b = rows;  // last row index with rp[a] <= edge
             while (b - a > 1) {
                 const int mid = (a + b) >> 1;
                 if (rp[mid] <= e0 + i) a = mid; else b = mid;
             }
-            edge_to_row[e0 + i] = r0 + a;
+            __builtin_nontemporal_store(r0 + a, edge_to_row + e0 + i);
         }
     }
     if (lane == 0) uniq_count[w] = n_uniq;
@@ -583,7 +585,7 @@ __global__ __launch_bounds__(64 * NW) void win_bitmap_wave_kernel(int n, int nnz
 #pragma unroll
                     for (int j = 1; j < NW; ++j) off = (sl >> 2) >= j * FPW ? foff[j] : off;
                     const int rank = base + off + static_cast<int>(fpre[sl]) + __popc(fine[sl] & ((1u << (c & 31)) - 1u));
-                    edge_to_col[e0 + k * NT + tid] = rank;
+                    __builtin_nontemporal_store(rank, edge_to_col + e0 + k * NT + tid);
                     tmp_cols[e0 + rank] = ck;
                 }
                 if ((k & 7) == 7) __builtin_amdgcn_sched_barrier(0);
@@ -604,7 +606,7 @@ __global__ __launch_bounds__(64 * NW) void win_bitmap_wave_kernel(int n, int nnz
         sync();
         for (int r = wave; r < rows; r += NW) {
             const int b = min(rp[r + 1], e0 + cnt);
-            for (int e = max(rp[r], e0) + lane; e < b; e += 64) edge_to_row[e] = r0 + r;
+            for (int e = max(rp[r], e0) + lane; e < b; e += 64) __builtin_nontemporal_store(r0 + r, edge_to_row + e);
         }
         ent = ent1;
         ent1 = ent2;
@@ -723,7 +725,7 @@ __global__ __launch_bounds__(1024) void win_direct_kernel(int n, const int *__re
                     const uint32_t own = j == 0 ? v.x : (j == 1 ? v.y : (j == 2 ? v.z : v.w));
                     const int rank = base + woff[piece / PW] + static_cast<int>(pre[piece]) + __popc(own & ((1u << (c & 31)) - 1u)) +
                                      (j > 0 ? __popc(v.x) : 0) + (j > 1 ? __popc(v.y) : 0) + (j > 2 ? __popc(v.z) : 0);
-                    edge_to_col[e0 + i] = rank;
+                    __builtin_nontemporal_store(rank, edge_to_col + e0 + i);
                     tmp_cols[e0 + rank] = col;
                 }
             });
@@ -740,7 +742,7 @@ __global__ __launch_bounds__(1024) void win_direct_kernel(int n, const int *__re
         __syncthreads();  // rp (written before the first barrier of the window) and next_s
         for (int r = wave; r < rows; r += NW) {
             const int b = min(rp[r + 1], e0 + i_hi);
-            for (int e = max(rp[r], e0 + i_lo) + lane; e < b; e += 64) edge_to_row[e] = r0 + r;
+            for (int e = max(rp[r], e0 + i_lo) + lane; e < b; e += 64) __builtin_nontemporal_store(r0 + r, edge_to_row + e);
         }
         item = next_s;
     }
@@ -811,7 +813,7 @@ __global__ __launch_bounds__(NT, MIN_WG_PER_CU) void win_compact_kernel(
         if (tid <= rows) rp[tid] = row_ptr[r0 + tid];
         __syncthreads();
         const int e0 = rp[0], e1 = rp[rows];
-        for (int e = e0 + tid; e < e1; e += NT) edge_to_row[e] = r0 + row_of_edge(rp, rows, e);
+        for (int e = e0 + tid; e < e1; e += NT) __builtin_nontemporal_store(r0 + row_of_edge(rp, rows, e), edge_to_row + e);
         // f(column, edge) for every edge of the window.  The column ids are read again in every
         // phase (they come from L2 after the first time): keeping them in registers between the
         // phases was measured slower, because it halves the number of workgroups a CU can hold.
@@ -1054,7 +1056,7 @@ __global__ __launch_bounds__(256) void hub_edges_kernel(int n, const int *__rest
 #pragma unroll
             for (int q = 0; q < PER; ++q) {
                 const int e = e0 + tid + q * 256;
-                if (col[q] >= 0) edge_to_row[e] = r0 + row_of_edge(rp, rows, e);
+                if (col[q] >= 0) __builtin_nontemporal_store(r0 + row_of_edge(rp, rows, e), edge_to_row + e);
                 // Consecutive lanes hold consecutive edges, and inside a (sorted) row consecutive
                 // edges of a hub often fall into the same bitmap word: their bits are OR-ed along
                 // the lanes (a scan over runs of equal words) and only the last lane of a run goes
@@ -1089,7 +1091,7 @@ __global__ __launch_bounds__(256) void hub_edges_kernel(int n, const int *__rest
                     int r = gp[g];
 #pragma unroll
                     for (int k = 0; k < HUB_GROUP; ++k) r += __popc(wv[k] & (k < j ? 0xffffffffu : (k == j ? below : 0u)));
-                    edge_to_col[e0 + tid + q * 256] = r;
+                    __builtin_nontemporal_store(r, edge_to_col + e0 + tid + q * 256);
                 }
             }
         }
@@ -1427,10 +1429,10 @@ __global__ __launch_bounds__(256) void win_pack_kernel(int n_windows, const int 
     }
     int val[STEPS];
 #pragma unroll
-    for (int j = 0; j < STEPS; ++j) val[j] = src[j] >= 0 ? tmp_cols[src[j]] : 0;
+    for (int j = 0; j < STEPS; ++j) val[j] = src[j] >= 0 ? __builtin_nontemporal_load(tmp_cols + src[j]) : 0;  // read once
 #pragma unroll
     for (int j = 0; j < STEPS; ++j)
-        if (src[j] >= 0) win_cols[o_first + j * 64 + lane] = val[j];
+        if (src[j] >= 0) __builtin_nontemporal_store(val[j], win_cols + o_first + j * 64 + lane);
 }
 
 // The classes of windows are condensed by different kernels, none of which depends on another and each of
