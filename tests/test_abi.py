@@ -177,3 +177,17 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(B, "LIB_PATH", "/nonexistent/libftc.so")
     with pytest.raises(FileNotFoundError):
         B.lib()
+
+
+def test_header_is_plain_c(tmp_path):
+    """The boundary is a C ABI: the header compiles as C99 on its own (no C++ types, no torch, no HIP headers)."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "ftc.h"\n'
+                   'int main(void) { ftc_csr g; ftc_windows w; ftc_side_streams s; (void)g; (void)w; (void)s;\n'
+                   '    return (int)sizeof(ftc_plan) > 0 && FTC_NOALLOC_SCRATCH_MIB > 0 ? 0 : 1; }\n')
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only",
+                    "-I", os.path.join(ROOT, "include"), str(src)], check=True)
